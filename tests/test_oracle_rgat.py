@@ -1,0 +1,142 @@
+"""Pins of the RGAT oracle: a hand-computed example, invariants, special cases
+that reduce to sparse-matrix routines, an independent compact + reordered
+formulation, and finite differences."""
+import os
+
+import numpy as np
+import scipy.sparse as sp
+
+from oracle import layers as O
+from paper_2412_04747_amd import synth
+from fd import central_fd, assert_close
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "rgat_two_edges.txt")
+
+
+def _gold():
+    vals = {}
+    for line in open(GOLD):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, *v = line.split()
+        vals[k] = np.array([float(x) for x in v])
+    return vals
+
+
+def _rand(seed, N=12, R=3, E=40, d_in=5, d_out=4):
+    rng, src, dst, rel, _ = synth.tiny(seed, N, R, E)
+    p = {k: v.astype(np.float64) for k, v in synth.rgat_params(rng, N, R, d_in, d_out).items()}
+    return src, dst, rel, p
+
+
+def test_hand_computed_example():
+    ln2, ln3 = np.log(2.0), np.log(3.0)
+    X = np.array([[1, 0], [0, 1], [1, 1]], float)
+    W = np.array([[[1, 2], [3, 4]], [[0, 1], [-1, 0]]], float)
+    w_s = np.array([[ln3 + 1, 0], [3 * ln2, 0]])
+    w_t = np.array([[-0.25, 0], [ln2, -ln2]])
+    src = np.array([0, 1], np.int32); dst = np.array([2, 2], np.int32); rel = np.array([0, 1], np.int32)
+    g = _gold()
+    out, alpha, z = O.rgat_fwd(3, src, dst, rel, X, W, w_s, w_t, 0.2, want_alpha=True)
+    assert_close(alpha, g["alpha"], 1e-14, "alpha")
+    assert_close(z, [ln3, -5 * ln2], 1e-14, "z")
+    assert_close(out[2], g["out2"], 1e-14, "out")
+    assert np.all(out[:2] == 0)
+    dOut = np.array([[0, 0], [0, 0], [1, 0]], float)
+    b = O.rgat_bwd(3, src, dst, rel, X, W, w_s, w_t, dOut, 0.2)
+    assert_close(b["dw_s"], np.stack([g["dw_s0"], g["dw_s1"]]), 1e-13, "dw_s")
+    assert_close(b["dw_t"], np.stack([g["dw_t0"], g["dw_t1"]]), 1e-13, "dw_t")
+    # dX[2] = sum_e dz_e w_t[r] W_r^T (node 2 is only a destination)
+    dz = g["dz"]
+    assert_close(b["dX"][2], dz[0] * w_t[0] @ W[0].T + dz[1] * w_t[1] @ W[1].T, 1e-13, "dX[2]")
+
+
+def test_softmax_sums_to_one_and_single_in_edge():
+    src, dst, rel, p = _rand(7, N=30, R=4, E=60)
+    N = 30
+    out, alpha, _ = O.rgat_fwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], want_alpha=True)
+    deg = np.bincount(dst, minlength=N)
+    s = np.bincount(dst, weights=alpha, minlength=N)
+    assert np.abs(s[deg > 0] - 1).max() < 1e-12
+    assert np.all(out[deg == 0] == 0)
+    ones = np.flatnonzero(deg == 1)
+    assert len(ones) > 0
+    for v in ones:
+        e = int(np.flatnonzero(dst == v)[0])
+        assert_close(out[v], p["X"][src[e]] @ p["W"][rel[e]], 1e-12, "single in-edge")
+
+
+def test_zero_attention_vectors_give_mean_aggregation():
+    # w_s = w_t = 0 => alpha = 1/indeg(v): RGCN-style sum with c_v = total in-degree
+    src, dst, rel, p = _rand(8, N=14, R=3, E=50)
+    N = 14
+    z0 = np.zeros_like(p["w_s"])
+    got = O.rgat_fwd(N, src, dst, rel, p["X"], p["W"], z0, z0)
+    deg = np.bincount(dst, minlength=N).astype(float)
+    want = np.zeros_like(got)
+    for r in range(3):
+        m = rel == r
+        A = sp.coo_matrix((np.ones(m.sum()), (dst[m], src[m])), shape=(N, N)).tocsr()
+        want += (A @ p["X"]) @ p["W"][r]
+    want /= np.maximum(deg, 1)[:, None]
+    assert_close(got, want, 1e-12)
+
+
+def _compact_reordered(N, src, dst, rel, X, W, w_s, w_t, slope):
+    """Independent formulation: messages stored once per unique (src, rel) pair
+    (compact materialization) and logits via x (W w) (linear operator
+    reordering).  Both are exact rewrites, so the result must equal the
+    vanilla per-edge oracle."""
+    pairs = sorted(set(zip(rel.tolist(), src.tolist())))
+    pid = {k: i for i, k in enumerate(pairs)}
+    Hs = np.stack([X[u] @ W[r] for r, u in pairs])
+    Ws = np.einsum("rij,rj->ri", W, w_s)
+    Wt = np.einsum("rij,rj->ri", W, w_t)
+    z = np.array([X[u] @ Ws[r] + X[v] @ Wt[r] for u, v, r in zip(src, dst, rel)])
+    l = np.where(z > 0, z, slope * z)
+    out = np.zeros((N, W.shape[2]))
+    for v in range(N):
+        es = np.flatnonzero(dst == v)
+        if len(es) == 0:
+            continue
+        a = np.exp(l[es]); a /= a.sum()                 # the listing's un-shifted softmax
+        for k, e in enumerate(es):
+            out[v] += a[k] * Hs[pid[(int(rel[e]), int(src[e]))]]
+    return out, len(pairs)
+
+
+def test_compact_and_reordered_equal_vanilla():
+    src, dst, rel, p = _rand(9, N=10, R=2, E=60)          # many repeated (src, rel) pairs
+    got = O.rgat_fwd(10, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], 0.2)
+    want, P = _compact_reordered(10, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], 0.2)
+    assert P < len(src)
+    assert_close(got, want, 1e-12)
+
+
+def test_edge_order_invariance():
+    src, dst, rel, p = _rand(10)
+    perm = np.random.default_rng(1).permutation(len(src))
+    a = O.rgat_fwd(12, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"])
+    b = O.rgat_fwd(12, src[perm], dst[perm], rel[perm], p["X"], p["W"], p["w_s"], p["w_t"])
+    assert_close(a, b, 1e-12)
+    ga = O.rgat_bwd(12, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
+    gb = O.rgat_bwd(12, src[perm], dst[perm], rel[perm], p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
+    for k in ga:
+        assert_close(ga[k], gb[k], 1e-12, k)
+
+
+def test_backward_matches_finite_differences():
+    for seed in (11, 12):
+        src, dst, rel, p = _rand(seed, N=8, R=3, E=25, d_in=4, d_out=3)
+        N = 8
+        # self-loop edge and duplicate edge are ordinary edges
+        src = np.append(src, [3, src[0]]).astype(np.int32)
+        dst = np.append(dst, [3, dst[0]]).astype(np.int32)
+        rel = np.append(rel, [1, rel[0]]).astype(np.int32)
+        _, _, z = O.rgat_fwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], want_alpha=True)
+        assert np.abs(z).min() > 1e-3, "sample too close to the leaky-ReLU kink"
+        G = p["dOut"]
+        loss = lambda q: float((O.rgat_fwd(N, src, dst, rel, q["X"], q["W"], q["w_s"], q["w_t"]) * G).sum())
+        g = O.rgat_bwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], G)
+        for name, key in (("X", "dX"), ("W", "dW"), ("w_s", "dw_s"), ("w_t", "dw_t")):
+            assert_close(g[key], central_fd(loss, p, name), 2e-6, key)
