@@ -1,0 +1,218 @@
+/*
+ * rgnn.h - C ABI of the MI355X (gfx950) relational-GNN layer library.
+ *
+ * One layer of RGCN, RGAT or HGT, forward and backward, over a heterogeneous
+ * graph with typed nodes and typed edges (thesis Ch.3, "RGNN Formulation and
+ * Operators").  The library is built from three pieces: a relation-segmented
+ * typed-linear kernel on the matrix cores (Ch.3 "Inefficiency in Existing
+ * Computation Stack": segment MM, Y[i] = X[i] W[T[i]] without replicating W),
+ * destination-major edge-traversal kernels (edge softmax and weighted
+ * aggregation, Ch.3 listing "attention calculation in a single-headed RGAT
+ * model"), and compact materialization (Ch.3 "Compact Tensor Materialization
+ * and Data Layout": edge data that depends only on (source node, edge type)
+ * is stored once per unique pair).
+ *
+ * Conventions
+ *   - Every function returns rgnn_status_t; nothing throws or aborts.
+ *     rgnn_last_error() gives the message of the calling thread's last failure.
+ *   - All tensor arguments of the layer calls are DEVICE pointers, row-major,
+ *     contiguous, 16-byte aligned, owned by the caller.  The library owns only
+ *     the opaque graph object.
+ *   - Layer calls allocate nothing and do not synchronise; they enqueue kernels
+ *     on `stream` (a hipStream_t cast to void*, NULL = default stream).
+ *     `workspace` and `saved` are caller-provided device buffers of at least the
+ *     sizes rgnn_workspace_bytes reports; `saved` must be kept unchanged between
+ *     a forward call and its backward call, `workspace` is scratch.
+ *   - Weights are stored [type][d_in][d_out] so that y = x W (row vector times
+ *     matrix), as in Eq. (rgcn).
+ *   - Gradients are overwritten, not accumulated.
+ *   - Index arrays are int32; graphs with 2^31 or more edges are rejected.
+ */
+#ifndef RGNN_H
+#define RGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RGNN_OK = 0,
+    RGNN_EINVAL = 1,        /* NULL pointer, bad size, id out of range */
+    RGNN_EUNSUPPORTED = 2,  /* valid request the kernels do not cover (dimension, dtype, heads) */
+    RGNN_ENOMEM = 3,        /* host or device allocation failed (graph_create only) */
+    RGNN_EHIP = 4,          /* a HIP runtime call failed; see rgnn_last_error() */
+    RGNN_EWORKSPACE = 5     /* workspace / saved pointer NULL while its size is non-zero */
+} rgnn_status_t;
+
+typedef enum { RGNN_F32 = 0, RGNN_BF16 = 1 } rgnn_dtype_t;
+enum { RGNN_LAYER_RGCN = 0, RGNN_LAYER_RGAT = 1, RGNN_LAYER_HGT = 2 };
+enum { RGNN_NORM_NONE = 0, RGNN_NORM_IN_DEGREE_PER_REL = 1 };
+enum { RGNN_ACT_NONE = 0, RGNN_ACT_RELU = 1 };
+enum { RGNN_MEM_HOST = 0, RGNN_MEM_DEVICE = 1 };
+enum { RGNN_COO = 0, RGNN_CSR_DST = 1 };
+
+typedef struct rgnn_graph rgnn_graph_t;
+
+typedef struct {
+    int64_t num_nodes;           /* N */
+    int64_t num_edges;           /* E */
+    int64_t num_pairs;           /* P: unique (source node, relation) pairs; P/E is the thesis's entity compaction ratio */
+    int64_t num_runs;            /* Q: unique (destination node, relation) pairs */
+    int64_t max_in_degree;
+    int64_t max_pair_out_degree; /* most edges sharing one (source, relation) pair */
+    int64_t index_bytes;         /* device memory held by the graph */
+    int32_t num_rels;            /* R */
+    int32_t num_ntypes;          /* T */
+} rgnn_graph_info_t;
+
+/* Parameters of one layer call.  Fields a layer does not use are ignored.
+ *   dtype      storage type of the tensor arguments (RGNN_F32; RGNN_BF16 = bfloat16
+ *              inputs, fp32 accumulation, fp32 outputs and gradients).
+ *   d_in,d_out feature widths.  Supported: d_in == d_out in {32, 64, 128}.
+ *   heads      HGT: number of heads H (d_out % H == 0, d_out/H in {16, 32, 64}); RGAT: must be 1.
+ *   slope      RGAT leaky-ReLU negative slope (the derivative at 0 is `slope`).
+ *   norm       RGCN: RGNN_NORM_IN_DEGREE_PER_REL divides each message by c_{v,r},
+ *              the number of incoming edges of v with relation r (Eq. (rgcn)).
+ *   activation RGCN: sigma of Eq. (rgcn), RGNN_ACT_NONE or RGNN_ACT_RELU. */
+typedef struct {
+    int32_t dtype;
+    int32_t d_in;
+    int32_t d_out;
+    int32_t heads;
+    float slope;
+    int32_t norm;
+    int32_t activation;
+    uint32_t flags;              /* reserved, must be 0 */
+} rgnn_layer_desc_t;
+
+/* Message of the last failing call made by this thread ("" if none). */
+const char* rgnn_last_error(void);
+
+/*
+ * Build the graph index (dataset preprocessing in the thesis: "transposition,
+ * converting COO to CSR", Ch.3 "Code Generation"; the compact-materialization
+ * mapping is "precompute[d] ... in a CSR-like format").
+ *
+ *   format RGNN_COO:     a = src[E], b = dst[E]
+ *   format RGNN_CSR_DST: a = col (source ids)[E], b = rowptr[N+1] over destinations
+ *   rel[E]               relation (edge type) id in [0, num_rels)
+ *   ntype[N]             node type id in [0, num_ntypes); may be NULL iff num_ntypes == 1
+ *   rel_src_ntype[R], rel_dst_ntype[R]  optional (both or neither): when given, every
+ *                        edge is checked to connect the node types its relation is tied to
+ *   mem                  RGNN_MEM_HOST or RGNN_MEM_DEVICE: where ALL the input arrays live
+ *
+ * Edges may be in any order, with duplicates and self-loops.  The index is
+ * canonical: destination-major CSR sorted by (dst, rel, src, input edge id);
+ * pair ids are ranks in ascending (rel, src) order.  Synchronises the device.
+ * Errors: EINVAL for NULLs / negative sizes / ids out of range / type mismatch,
+ * EUNSUPPORTED for E >= 2^31 or N*N*R >= 2^63, ENOMEM, EHIP.  *g is NULL on failure.
+ */
+rgnn_status_t rgnn_graph_create(rgnn_graph_t** g, int64_t num_nodes, int32_t num_ntypes, int32_t num_rels,
+                                int64_t num_edges, int32_t format, const int32_t* a, const int32_t* b,
+                                const int32_t* rel, const int32_t* ntype, const int32_t* rel_src_ntype,
+                                const int32_t* rel_dst_ntype, int32_t mem);
+
+/* Free the graph and its device arrays.  NULL is accepted. */
+rgnn_status_t rgnn_graph_destroy(rgnn_graph_t* g);
+
+rgnn_status_t rgnn_graph_info(const rgnn_graph_t* g, rgnn_graph_info_t* out);
+
+/* Index arrays that can be copied out (all int32) for bit-exact checks. */
+enum {
+    RGNN_IDX_IN_PTR = 0,      /* [N+1] CSR offsets by destination */
+    RGNN_IDX_IN_SRC = 1,      /* [E] source of the CSR edge */
+    RGNN_IDX_IN_REL = 2,      /* [E] relation of the CSR edge */
+    RGNN_IDX_IN_EID = 3,      /* [E] input position of the CSR edge */
+    RGNN_IDX_IN_PAIR = 4,     /* [E] pair id of the CSR edge */
+    RGNN_IDX_IN_RUN = 5,      /* [E] run id ((dst, rel) group) of the CSR edge */
+    RGNN_IDX_IN_CNT = 6,      /* [E] length of that run = c_{v,r} */
+    RGNN_IDX_PAIR_PTR = 7,    /* [R+1] pairs of each relation (thesis: unique_etype_ptr) */
+    RGNN_IDX_PAIR_SRC = 8,    /* [P] source node of the pair (thesis: unique_row_idx) */
+    RGNN_IDX_PAIR_REL = 9,    /* [P] relation of the pair */
+    RGNN_IDX_RUN_PTR = 10,    /* [Q+1] CSR edge range of each run */
+    RGNN_IDX_RUN_DST = 11,    /* [Q] */
+    RGNN_IDX_RUN_REL = 12,    /* [Q] */
+    RGNN_IDX_DST_RUN_PTR = 13,/* [N+1] runs of each destination */
+    RGNN_IDX_RELRUN_PTR = 14, /* [R+1] */
+    RGNN_IDX_RELRUN_IDX = 15, /* [Q] run ids sorted by (rel, dst) */
+    RGNN_IDX_OUT_PTR = 16,    /* [P+1] pair-major transpose offsets */
+    RGNN_IDX_OUT_EPOS = 17,   /* [E] CSR position, sorted by (pair, CSR position) */
+    RGNN_IDX_OUT_DST = 18,    /* [E] destination of that edge */
+    RGNN_IDX_SRCPAIR_PTR = 19,/* [N+1] pairs of each source node */
+    RGNN_IDX_SRCPAIR_IDX = 20,/* [P] pair ids sorted by (src, rel) */
+    RGNN_IDX_NTYPE_PTR = 21,  /* [T+1] */
+    RGNN_IDX_NTYPE_PERM = 22, /* [N] node ids sorted by (type, id) */
+    RGNN_IDX_COUNT = 23
+};
+
+/* Copy index array `which` to host memory.  `bytes` must equal 4 * its length,
+ * else EINVAL.  Synchronises the device. */
+rgnn_status_t rgnn_graph_export(const rgnn_graph_t* g, int32_t which, void* host_dst, size_t bytes);
+
+/* Sizes (bytes) of the buffers the layer calls need: forward scratch, backward
+ * scratch, and the `saved` buffer the forward fills for the backward.  Any out
+ * pointer may be NULL. */
+rgnn_status_t rgnn_workspace_bytes(const rgnn_graph_t* g, int32_t layer, const rgnn_layer_desc_t* desc,
+                                   size_t* fwd_workspace, size_t* bwd_workspace, size_t* saved);
+
+/*
+ * RGCN (Eq. (rgcn)):  out[v] = act( X[v] W0 + sum_{e=(u->v,r)} (1/c_{v,r}) X[u] W[r] ).
+ *   X [N, d_in]; W [R, d_in, d_out]; W0 [d_in, d_out] or NULL (no self-loop term);
+ *   out [N, d_out].  Nodes without incoming edges get act(X[v] W0) (0 without W0).
+ * Backward: given dOut [N, d_out] (gradient w.r.t. out) writes dX [N, d_in],
+ *   dW [R, d_in, d_out], dW0 [d_in, d_out] (ignored when W0 is NULL).  `out` is the
+ *   forward result (read only when activation != NONE).
+ */
+rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* W,
+                            const void* W0, void* out, void* saved, void* workspace, void* stream);
+rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* W,
+                            const void* W0, const void* out, const void* saved, const void* dOut, void* dX,
+                            void* dW, void* dW0, void* workspace, void* stream);
+
+/*
+ * Single-head RGAT (Ch.3 listing "attention calculation in a single-headed RGAT
+ * model"; the message of an edge is hs):
+ *   hs = X[u] W[r];  ht = X[v] W[r];  z_e = hs.w_s[r] + ht.w_t[r];
+ *   att_e = softmax over ALL incoming edges of v of leakyrelu(z_e);
+ *   out[v] = sum_{e in in(v)} att_e hs.
+ *   X [N, d_in]; W [R, d_in, d_out]; w_s, w_t [R, d_out]; out [N, d_out].
+ * Nodes without incoming edges get 0.
+ * Backward writes dX [N, d_in], dW [R, d_in, d_out], dw_s, dw_t [R, d_out].
+ * Layout of `saved` after the forward (exposed for tests): Hs [P, d_out] fp32,
+ * the compact messages, then att [E] fp32 in CSR order holding att_e with the
+ * sign bit set when z_e <= 0.
+ */
+rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* W,
+                            const void* w_s, const void* w_t, void* out, void* saved, void* workspace,
+                            void* stream);
+rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* W,
+                            const void* w_s, const void* w_t, const void* out, const void* saved,
+                            const void* dOut, void* dX, void* dW, void* dw_s, void* dw_t, void* workspace,
+                            void* stream);
+
+/*
+ * HGT (caption of the figure "HGT and RGAT layer"): per node type tau(n) the
+ * linears Wk, Wq, Wv, Wo [T, d, d]; per relation and head the attention and
+ * message matrices Watt, Wmsg [R, H, dh, dh] (dh = d/H); optional prior mu [R, H]
+ * (NULL = 1):
+ *   k = X[u] Wk[tau(u)], q = X[v] Wq[tau(v)], val = X[u] Wv[tau(u)];
+ *   logit_e^h = mu[r,h] ((k^h Watt[r,h]) . q^h) / sqrt(dh); att^h = edge softmax per head;
+ *   out[v] = ( ||_h sum_e att_e^h (val^h Wmsg[r,h]) ) Wo[tau(v)].
+ * Backward writes dX and the gradient of every weight (dmu ignored when mu is NULL).
+ */
+rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* Wk,
+                           const void* Wq, const void* Wv, const void* Wo, const void* Watt, const void* Wmsg,
+                           const void* mu, void* out, void* saved, void* workspace, void* stream);
+rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* Wk,
+                           const void* Wq, const void* Wv, const void* Wo, const void* Watt, const void* Wmsg,
+                           const void* mu, const void* out, const void* saved, const void* dOut, void* dX,
+                           void* dWk, void* dWq, void* dWv, void* dWo, void* dWatt, void* dWmsg, void* dmu,
+                           void* workspace, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RGNN_H */

@@ -1,0 +1,285 @@
+// Layer entry points of the C ABI: argument checks, carving of the caller's workspace, and
+// the sequence of kernel launches that makes up each layer.  No allocation, no
+// synchronisation; everything is enqueued on the caller's stream.
+#include "rgnn_internal.h"
+#include "traversal.h"
+
+using namespace rgnn;
+
+namespace {
+
+// Bump allocator over a caller-provided buffer; with base == nullptr it only measures.
+struct Carver {
+    char* base;
+    size_t off = 0;
+    explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+    template <typename Tv>
+    Tv* take(size_t n) {
+        Tv* p = base ? reinterpret_cast<Tv*>(base + off) : nullptr;
+        off += align_up(std::max<size_t>(n, 1) * sizeof(Tv));
+        return p;
+    }
+};
+
+rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int layer) {
+    if (!g || !d) RGNN_FAIL(RGNN_EINVAL, "graph or desc is NULL");
+    if (d->flags != 0) RGNN_FAIL(RGNN_EINVAL, "desc.flags must be 0");
+    if (d->dtype != RGNN_F32) RGNN_FAIL(RGNN_EUNSUPPORTED, "only RGNN_F32 is implemented");
+    if (d->d_in != d->d_out || (d->d_in != 32 && d->d_in != 64 && d->d_in != 128))
+        RGNN_FAIL(RGNN_EUNSUPPORTED, "need d_in == d_out in {32, 64, 128}, got %d -> %d", d->d_in, d->d_out);
+    if (layer == RGNN_LAYER_RGAT && d->heads != 1) RGNN_FAIL(RGNN_EUNSUPPORTED, "RGAT supports heads == 1 only");
+    if (layer == RGNN_LAYER_RGAT && !(d->slope >= 0.f && d->slope <= 1.f))
+        RGNN_FAIL(RGNN_EINVAL, "leaky-ReLU slope must be in [0, 1]");
+    if (layer == RGNN_LAYER_RGCN) {
+        if (d->norm != RGNN_NORM_NONE && d->norm != RGNN_NORM_IN_DEGREE_PER_REL) RGNN_FAIL(RGNN_EINVAL, "unknown norm %d", d->norm);
+        if (d->activation != RGNN_ACT_NONE && d->activation != RGNN_ACT_RELU) RGNN_FAIL(RGNN_EINVAL, "unknown activation %d", d->activation);
+    }
+    if (layer == RGNN_LAYER_HGT) RGNN_FAIL(RGNN_EUNSUPPORTED, "HGT is not implemented yet");
+    return RGNN_OK;
+}
+
+// ---- RGAT buffers -----------------------------------------------------------------------
+struct RgatSaved { float* Hs; float* att; };
+struct RgatFwdWs { float* wtp; float* s_src; float* s_dst; float* part_m; float* part_s; float* partial; };
+struct RgatBwdWs {
+    float* wtp; float* adz; float* ds_dst; float* ds_src; float* G; float* dXp; float* A; float* U;
+    float* tl_part; float* partial;
+};
+
+size_t carve_rgat_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatSaved* s) {
+    Carver c(base);
+    s->Hs = c.take<float>((size_t)g->P * d->d_out);
+    s->att = c.take<float>((size_t)g->E);
+    return c.off;
+}
+size_t carve_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatFwdWs* w) {
+    Carver c(base);
+    w->wtp = c.take<float>((size_t)g->R * d->d_in);
+    w->s_src = c.take<float>((size_t)g->P);
+    w->s_dst = c.take<float>((size_t)g->Q);
+    w->part_m = c.take<float>((size_t)g->dst_items.num_partials);
+    w->part_s = c.take<float>((size_t)g->dst_items.num_partials);
+    w->partial = c.take<float>((size_t)g->dst_items.num_partials * d->d_out);
+    return c.off;
+}
+size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatBwdWs* w) {
+    Carver c(base);
+    w->wtp = c.take<float>((size_t)g->R * d->d_in);
+    w->adz = c.take<float>((size_t)g->E * 2);
+    w->ds_dst = c.take<float>((size_t)g->Q);
+    w->ds_src = c.take<float>((size_t)g->P);
+    w->G = c.take<float>((size_t)g->P * d->d_out);
+    w->dXp = c.take<float>((size_t)g->P * d->d_in);
+    w->A = c.take<float>((size_t)g->R * d->d_in);
+    w->U = c.take<float>((size_t)g->R * d->d_in);
+    w->tl_part = c.take<float>(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles));
+    w->partial = c.take<float>(std::max((size_t)g->pair_items.num_partials * d->d_out,
+                                        (size_t)g->relrun_items.num_partials * d->d_in));
+    return c.off;
+}
+
+// ---- RGCN buffers -----------------------------------------------------------------------
+struct RgcnFwdWs { float* Hs; float* partial; };
+struct RgcnBwdWs { float* dPre; float* G; float* dXp; float* dX0; float* tl_part; float* partial; };
+
+size_t carve_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgcnFwdWs* w) {
+    Carver c(base);
+    w->Hs = c.take<float>((size_t)g->P * d->d_out);
+    w->partial = c.take<float>((size_t)g->dst_items.num_partials * d->d_out);
+    return c.off;
+}
+size_t carve_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgcnBwdWs* w) {
+    Carver c(base);
+    w->dPre = c.take<float>(d->activation == RGNN_ACT_RELU ? (size_t)g->N * d->d_out : 0);
+    w->G = c.take<float>((size_t)g->P * d->d_out);
+    w->dXp = c.take<float>((size_t)g->P * d->d_in);
+    w->dX0 = c.take<float>((size_t)g->N * d->d_in);
+    w->tl_part = c.take<float>(std::max(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles),
+                                        typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->all_tiles)));
+    w->partial = c.take<float>((size_t)g->pair_items.num_partials * d->d_out);
+    return c.off;
+}
+
+}  // namespace
+
+extern "C" rgnn_status_t rgnn_workspace_bytes(const rgnn_graph_t* g, int32_t layer, const rgnn_layer_desc_t* desc,
+                                              size_t* fwd_workspace, size_t* bwd_workspace, size_t* saved) {
+    if (layer != RGNN_LAYER_RGCN && layer != RGNN_LAYER_RGAT && layer != RGNN_LAYER_HGT)
+        RGNN_FAIL(RGNN_EINVAL, "unknown layer %d", layer);
+    RGNN_TRY(check_desc(g, desc, layer));
+    size_t f = 0, b = 0, s = 0;
+    if (layer == RGNN_LAYER_RGAT) {
+        RgatFwdWs fw; RgatBwdWs bw; RgatSaved sv;
+        f = carve_rgat_fwd(g, desc, nullptr, &fw);
+        b = carve_rgat_bwd(g, desc, nullptr, &bw);
+        s = carve_rgat_saved(g, desc, nullptr, &sv);
+    } else if (layer == RGNN_LAYER_RGCN) {
+        RgcnFwdWs fw; RgcnBwdWs bw;
+        f = carve_rgcn_fwd(g, desc, nullptr, &fw);
+        b = carve_rgcn_bwd(g, desc, nullptr, &bw);
+        s = 0;
+    }
+    if (fwd_workspace) *fwd_workspace = f;
+    if (bwd_workspace) *bwd_workspace = b;
+    if (saved) *saved = s;
+    return RGNN_OK;
+}
+
+// =========================================================================== RGCN
+
+extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
+                                       const void* W, const void* W0, void* out, void* saved, void* workspace,
+                                       void* stream) {
+    (void)saved;
+    RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGCN));
+    if (!X || !W || !out) RGNN_FAIL(RGNN_EINVAL, "X, W or out is NULL");
+    if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int D = desc->d_out;
+    RgcnFwdWs w;
+    carve_rgcn_fwd(g, desc, workspace, &w);
+    // 1. compact messages: Hs[p] = X[pair_src[p]] W[rel(p)]
+    TypedLinearArgs a{};
+    a.tiles = &g->pair_tiles; a.X = static_cast<const float*>(X); a.gather = g->idx[RGNN_IDX_PAIR_SRC];
+    a.W = static_cast<const float*>(W); a.Y = w.Hs;
+    RGNN_TRY(typed_linear_fwd(desc->d_in, D, a, st));
+    // 2. out[v] = sum_e (1/c) Hs[pair_e]
+    const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
+    RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, coef, 1, 0, w.Hs,
+                        static_cast<float*>(out), w.partial, st));
+    // 3. self-loop: out += X W0
+    if (W0) {
+        TypedLinearArgs s{};
+        s.tiles = &g->all_tiles; s.X = static_cast<const float*>(X); s.W = static_cast<const float*>(W0);
+        s.Y = static_cast<float*>(out); s.accumulate = 1;
+        RGNN_TRY(typed_linear_fwd(desc->d_in, D, s, st));
+    }
+    if (desc->activation == RGNN_ACT_RELU) RGNN_TRY(relu_inplace((size_t)g->N * D, static_cast<float*>(out), st));
+    return RGNN_OK;
+}
+
+extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
+                                       const void* W, const void* W0, const void* out, const void* saved,
+                                       const void* dOut, void* dX, void* dW, void* dW0, void* workspace,
+                                       void* stream) {
+    (void)saved;
+    RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGCN));
+    if (!X || !W || !dOut || !dX || !dW) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
+    if (W0 && !dW0) RGNN_FAIL(RGNN_EINVAL, "dW0 is NULL but W0 is given");
+    if (desc->activation != RGNN_ACT_NONE && !out) RGNN_FAIL(RGNN_EINVAL, "out is needed for the activation's gradient");
+    if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int D = desc->d_out, K = desc->d_in;
+    RgcnBwdWs w;
+    carve_rgcn_bwd(g, desc, workspace, &w);
+    const float* dPre = static_cast<const float*>(dOut);
+    if (desc->activation == RGNN_ACT_RELU) {
+        RGNN_TRY(relu_grad((size_t)g->N * D, static_cast<const float*>(out), dPre, w.dPre, st));
+        dPre = w.dPre;
+    }
+    // 1. dHs[p] = sum_{e in out(p)} (1/c_e) dPre[dst_e]
+    const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
+    RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, coef, 1, 0, dPre, w.G,
+                        w.partial, st));
+    // 2. per pair dXp = dHs W^T; dW[r] = sum X^T dHs
+    TypedLinearBwdArgs b{};
+    b.tiles = &g->pair_tiles; b.X = static_cast<const float*>(X); b.gather = g->idx[RGNN_IDX_PAIR_SRC];
+    b.W = static_cast<const float*>(W); b.dY = w.G; b.dXrow = w.dXp; b.dW = static_cast<float*>(dW); b.part = w.tl_part;
+    RGNN_TRY(typed_linear_bwd(K, D, b, st));
+    // 3. self-loop: dX0 = dPre W0^T, dW0 = X^T dPre
+    if (W0) {
+        TypedLinearBwdArgs s{};
+        s.tiles = &g->all_tiles; s.X = static_cast<const float*>(X); s.W = static_cast<const float*>(W0); s.dY = dPre;
+        s.dXrow = w.dX0; s.dW = static_cast<float*>(dW0); s.part = w.tl_part;
+        RGNN_TRY(typed_linear_bwd(K, D, s, st));
+    }
+    // 4. dX[u] = sum over u's pairs of dXp (+ dX0[u])
+    RGNN_TRY(node_grad_sum(g, K, w.dXp, nullptr, nullptr, W0 ? w.dX0 : nullptr, static_cast<float*>(dX), st));
+    return RGNN_OK;
+}
+
+// =========================================================================== RGAT
+
+extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
+                                       const void* W, const void* w_s, const void* w_t, void* out, void* saved,
+                                       void* workspace, void* stream) {
+    RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGAT));
+    if (!X || !W || !w_s || !w_t || !out) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
+    if (!workspace || !saved) RGNN_FAIL(RGNN_EWORKSPACE, "workspace or saved is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int D = desc->d_out, K = desc->d_in;
+    RgatFwdWs w; RgatSaved sv;
+    carve_rgat_fwd(g, desc, workspace, &w);
+    carve_rgat_saved(g, desc, saved, &sv);
+    // 1. compact messages and the source half of the logit:
+    //    Hs[p] = X[pair_src[p]] W[r];  s_src[p] = Hs[p] . w_s[r]
+    TypedLinearArgs a{};
+    a.tiles = &g->pair_tiles; a.X = static_cast<const float*>(X); a.gather = g->idx[RGNN_IDX_PAIR_SRC];
+    a.W = static_cast<const float*>(W); a.Y = sv.Hs; a.vec = static_cast<const float*>(w_s); a.s_out = w.s_src;
+    RGNN_TRY(typed_linear_fwd(K, D, a, st));
+    // 2. destination half, once per (dst, rel) run, reordered: s_dst[q] = X[dst] . (W[r] w_t[r])
+    RGNN_TRY(fold_weight(g->R, K, D, static_cast<const float*>(W), static_cast<const float*>(w_t), w.wtp, st));
+    RGNN_TRY(run_logit(g, K, static_cast<const float*>(X), w.wtp, w.s_dst, st));
+    // 3. edge softmax over each destination's incoming edges
+    RGNN_TRY(edge_softmax(g, w.s_src, w.s_dst, desc->slope, sv.att, w.part_m, w.part_s, st));
+    // 4. out[v] = sum_e att_e Hs[pair_e]
+    RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, 1, 1, sv.Hs,
+                        static_cast<float*>(out), w.partial, st));
+    return RGNN_OK;
+}
+
+extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
+                                       const void* W, const void* w_s, const void* w_t, const void* out,
+                                       const void* saved, const void* dOut, void* dX, void* dW, void* dw_s,
+                                       void* dw_t, void* workspace, void* stream) {
+    RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGAT));
+    if (!X || !W || !w_s || !w_t || !out || !dOut || !dX || !dW || !dw_s || !dw_t)
+        RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
+    if (!workspace || !saved) RGNN_FAIL(RGNN_EWORKSPACE, "workspace or saved is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int D = desc->d_out, K = desc->d_in;
+    RgatBwdWs w; RgatSaved sv;
+    carve_rgat_bwd(g, desc, workspace, &w);
+    carve_rgat_saved(g, desc, const_cast<void*>(saved), &sv);
+    const float* Xf = static_cast<const float*>(X);
+    const float* Wf = static_cast<const float*>(W);
+    const float* dO = static_cast<const float*>(dOut);
+    // 1. per CSR edge: (att_e, dz_e)
+    RGNN_TRY(edge_dot_bwd(g, D, sv.att, sv.Hs, dO, static_cast<const float*>(out), desc->slope, w.adz, st));
+    // 2. ds_dst[q] = sum over the run's edges of dz;  ds_src[p] = sum over the pair's edges of dz
+    RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], nullptr, w.adz, 2, 1, w.ds_dst, st));
+    RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2, 1, w.ds_src, st));
+    // 3. G[p] = sum_{e in out(p)} att_e dOut[dst_e]
+    RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.adz, 2, 0, dO, w.G,
+                        w.partial, st));
+    // 4. dHs[p] = G[p] + ds_src[p] w_s[r];  dXp[p] = dHs[p] W[r]^T;  dW[r] = sum X^T dHs;  A[r] = sum ds_src X
+    TypedLinearBwdArgs b{};
+    b.tiles = &g->pair_tiles; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
+    b.rowscale = w.ds_src; b.vec = static_cast<const float*>(w_s); b.dW = static_cast<float*>(dW); b.Avec = w.A;
+    b.part = w.tl_part;
+    RGNN_TRY(typed_linear_bwd(K, D, b, st));
+    // 5. U[r] = sum over r's runs of ds_dst[q] X[run_dst[q]]
+    RGNN_TRY(gather_sum(g->relrun_items, K, g->idx[RGNN_IDX_RELRUN_IDX], g->idx[RGNN_IDX_RUN_DST], 1, w.ds_dst, 1, 0, Xf,
+                        w.U, w.partial, st));
+    // 6. dw_s = A W, dw_t = U W, dW += U^T (x) w_t
+    RGNN_TRY(rgat_param_finish(g->R, K, D, Wf, static_cast<const float*>(w_t), w.A, w.U, static_cast<float*>(dW),
+                               static_cast<float*>(dw_s), static_cast<float*>(dw_t), st));
+    // 7. dX[u] = sum over u's pairs of dXp + sum over u's runs of ds_dst[q] (W[r] w_t[r])
+    RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_t), w.wtp, st));
+    RGNN_TRY(node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, nullptr, static_cast<float*>(dX), st));
+    return RGNN_OK;
+}
+
+// =========================================================================== HGT (not built yet)
+
+extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void*, const void*,
+                                      const void*, const void*, const void*, const void*, const void*, const void*,
+                                      void*, void*, void*, void*) {
+    return check_desc(g, desc, RGNN_LAYER_HGT);
+}
+extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void*, const void*,
+                                      const void*, const void*, const void*, const void*, const void*, const void*,
+                                      const void*, const void*, const void*, void*, void*, void*, void*, void*, void*,
+                                      void*, void*, void*, void*) {
+    return check_desc(g, desc, RGNN_LAYER_HGT);
+}

@@ -1,0 +1,130 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string>
+#include <vector>
+#include "../../include/rgnn.h"
+
+namespace rgnn {
+
+// ---- error plumbing ------------------------------------------------------
+void set_error(const char* fmt, ...);
+#define RGNN_HIP(call)                                                                  \
+    do {                                                                                \
+        hipError_t e_ = (call);                                                         \
+        if (e_ != hipSuccess) {                                                         \
+            rgnn::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return RGNN_EHIP;                                                           \
+        }                                                                               \
+    } while (0)
+#define RGNN_FAIL(code, ...)          \
+    do {                              \
+        rgnn::set_error(__VA_ARGS__); \
+        return (code);                \
+    } while (0)
+#define RGNN_TRY(expr)                      \
+    do {                                    \
+        rgnn_status_t s_ = (expr);          \
+        if (s_ != RGNN_OK) return s_;       \
+    } while (0)
+
+// ---- work lists ----------------------------------------------------------
+// Row tiles of a segmented row range (rows grouped by relation or node type),
+// cut into `num_chunks` contiguous chunks, one per persistent workgroup.  A
+// chunk owns one partial-gradient slot per distinct segment it touches; slots
+// are numbered in (chunk, segment) order, which is also segment order, so the
+// slots of one segment are contiguous (seg_slot_ptr).
+struct TileList {
+    int32_t tile_rows = 0;       // rows per tile
+    int32_t num_tiles = 0;
+    int32_t num_chunks = 0;
+    int32_t num_slots = 0;
+    int32_t num_segs = 0;
+    int32_t* tile_seg = nullptr;     // [num_tiles]  device
+    int32_t* tile_row0 = nullptr;    // [num_tiles]  first row of the tile
+    int32_t* tile_row1 = nullptr;    // [num_tiles]  end row (exclusive; <= row0 + tile_rows)
+    int32_t* chunk_tile = nullptr;   // [num_chunks+1]
+    int32_t* chunk_slot = nullptr;   // [num_chunks]  first slot of the chunk
+    int32_t* seg_slot_ptr = nullptr; // [num_segs+1]
+};
+
+// Segments of a CSR-like list cut into items of at most `max_len` entries.  An
+// item is either a whole segment (slot < 0: the result goes to row `row`) or a
+// piece of a split segment (slot >= 0: the result goes to partial row `slot`;
+// split_* lists say which partial rows sum to which output row).
+struct ItemList {
+    int32_t num_items = 0;
+    int32_t num_partials = 0;
+    int32_t num_split = 0;
+    int32_t* beg = nullptr;        // [num_items]
+    int32_t* end = nullptr;        // [num_items]
+    int32_t* row = nullptr;        // [num_items] segment id
+    int32_t* slot = nullptr;       // [num_items] partial row or -1
+    int32_t* split_row = nullptr;  // [num_split]
+    int32_t* split_ptr = nullptr;  // [num_split+1] range of partial rows
+    int32_t* part_item = nullptr;  // [num_partials] item that writes the partial row
+    int32_t* part_split = nullptr; // [num_partials] index into split_* of its segment
+};
+
+}  // namespace rgnn
+
+struct rgnn_graph {
+    int64_t N = 0, E = 0, P = 0, Q = 0;
+    int32_t R = 0, T = 0;
+    int64_t max_in_degree = 0, max_pair_out_degree = 0;
+    size_t index_bytes = 0;
+    int32_t* idx[RGNN_IDX_COUNT] = {};     // device arrays, see RGNN_IDX_*
+    int64_t idx_len[RGNN_IDX_COUNT] = {};
+    float* in_invc = nullptr;              // [E] 1 / c_{v,r} per CSR edge
+    rgnn::TileList pair_tiles;             // pairs segmented by relation
+    rgnn::TileList node_tiles;             // nodes (in ntype_perm order) segmented by type
+    rgnn::TileList all_tiles;              // all nodes as one segment (RGCN self-loop)
+    rgnn::ItemList dst_items;              // CSR edges by destination
+    rgnn::ItemList pair_items;             // transposed edges by pair
+    rgnn::ItemList relrun_items;           // runs by relation
+    std::vector<void*> allocs;             // every device allocation, for destroy
+};
+
+namespace rgnn {
+
+constexpr int kTileRows = 64;       // rows per typed-linear tile
+constexpr int kMaxChunks = 1024;    // persistent workgroups of the typed-linear kernels
+constexpr int kItemMax = 256;       // longest traversal item (entries)
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// ---- kernel launchers (typed_linear.hip) --------------------------------
+struct TypedLinearArgs {
+    const TileList* tiles;
+    const float* X;          // input rows
+    const int32_t* gather;   // row i reads X[gather[i]] (nullptr: X[i])
+    const float* W;          // [segs][KD][ND]
+    float* Y;                // output rows
+    int scatter_out;         // 1: row i writes Y[gather[i]], 0: Y[i]
+    int accumulate;          // 1: Y += result
+    const float* vec;        // optional [segs][ND]: s_out[i] = Y_row . vec[seg]
+    float* s_out;
+};
+rgnn_status_t typed_linear_fwd(int d_in, int d_out, const TypedLinearArgs& a, hipStream_t st);
+
+struct TypedLinearBwdArgs {
+    const TileList* tiles;
+    const float* X;          // forward input rows
+    const int32_t* gather;   // forward gather (nullptr: identity)
+    const float* W;          // [segs][KD][ND]
+    const float* dY;         // gradient of the forward output
+    int dy_gathered;         // 1: row i reads dY[gather[i]], 0: dY[i]
+    float* dXrow;            // [rows][KD] per-row input gradient dY_i W^T (row i, or gather[i] if scatter_dx)
+    int scatter_dx;
+    const float* rowscale;   // optional [rows]: A[seg] = sum_i rowscale[i] X_row_i
+    const float* vec;        // optional [segs][ND] (with rowscale): dY_eff[i] = dY[i] + rowscale[i] * vec[seg]
+    float* dW;               // [segs][KD][ND]
+    float* Avec;             // [segs][KD] (with rowscale)
+    float* part;             // scratch [num_slots][KD*ND + KD]
+};
+size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t);
+rgnn_status_t typed_linear_bwd(int d_in, int d_out, const TypedLinearBwdArgs& a, hipStream_t st);
+
+}  // namespace rgnn

@@ -1,0 +1,506 @@
+// Edge-traversal kernels: per-destination edge softmax, weighted gather-sum aggregation
+// (forward over destination-major CSR, backward over the pair-major transpose), the
+// backward per-edge dot product, and the small segment sums around them.
+//
+// These replace the thesis's traversal template (Ch.3 "The GEMM Template and the Traversal
+// Template": one block per edge or node, partial sums per thread and warp, then atomicAdd)
+// by segment walks: every output row has exactly one owner, so nothing is accumulated with
+// atomics and results do not depend on scheduling.  All of them are HBM-bound: a feature
+// row of D floats is read by D/4 lanes as one 16-byte load each, so a 64-lane wavefront
+// has four 256-byte rows (D = 64) in flight per load instruction, and the edge loop is
+// unrolled four times to keep sixteen row reads in flight per wavefront.
+//
+// Segments longer than kItemMax entries (hub nodes) are cut into items by the graph index;
+// an item of a cut segment writes a partial row and a combine kernel sums the partial rows
+// of each cut segment in order.
+#include "rgnn_internal.h"
+#include "traversal.h"
+
+namespace rgnn {
+
+struct Items {
+    int n;
+    const int32_t* beg;
+    const int32_t* end;
+    const int32_t* row;
+    const int32_t* slot;
+};
+static Items dev_items(const ItemList& L) { return Items{L.num_items, L.beg, L.end, L.row, L.slot}; }
+
+template <int W>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+    for (int o = W / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float dot4(const float4& a, const float4& b) {
+    return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+}
+__device__ __forceinline__ void fma4(float4& acc, float c, const float4& v) {
+    acc.x += c * v.x; acc.y += c * v.y; acc.z += c * v.z; acc.w += c * v.w;
+}
+
+// ------------------------------------------------------------------ small dense helpers
+
+// wv[r][k] = sum_n W[r][k][n] * w[r][n]      (linear operator reordering, Ch.3: x (W w) instead of (x W) w)
+__global__ void fold_weight_kernel(const float* __restrict__ W, const float* __restrict__ w, int kd, int nd,
+                                   int total, float* __restrict__ wv) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;  // (r, k)
+    if (i >= total) return;
+    const int r = i / kd;
+    const float* Wr = W + (size_t)i * nd;
+    const float* wr = w + (size_t)r * nd;
+    float s = 0.f;
+    for (int n = 0; n < nd; ++n) s += Wr[n] * wr[n];
+    wv[i] = s;
+}
+
+// s_dst[q] = X[run_dst[q]] . wtp[run_rel[q]]
+template <int D>
+__global__ void run_logit_kernel(int Q, const int32_t* __restrict__ run_dst, const int32_t* __restrict__ run_rel,
+                                 const float* __restrict__ X, const float* __restrict__ wtp, float* __restrict__ s_dst) {
+    constexpr int LPR = D / 4;
+    const int q = (blockIdx.x * blockDim.x + threadIdx.x) / LPR, c4 = threadIdx.x % LPR;
+    float s = 0.f;
+    if (q < Q) {
+        const float4 x = *reinterpret_cast<const float4*>(X + (size_t)run_dst[q] * D + c4 * 4);
+        const float4 w = *reinterpret_cast<const float4*>(wtp + (size_t)run_rel[q] * D + c4 * 4);
+        s = dot4(x, w);
+    }
+    s = group_sum<LPR>(s);
+    if (q < Q && c4 == 0) s_dst[q] = s;
+}
+
+// out[i] = sum_{j in [ptr[i], ptr[i+1])} val[(via ? via[j] : j) * stride + off].
+// One lane per segment; segments longer than 32 are then summed by the whole wavefront.
+__global__ void segment_scalar_sum_kernel(int n, const int32_t* __restrict__ ptr, const int32_t* __restrict__ via,
+                                          const float* __restrict__ val, int stride, int off, float* __restrict__ out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    int b = 0, e = 0;
+    if (i < n) { b = ptr[i]; e = ptr[i + 1]; }
+    const bool coop = (e - b) > 32;
+    float s = 0.f;
+    if (!coop)
+        for (int j = b; j < e; ++j) s += val[(size_t)(via ? via[j] : j) * stride + off];
+    unsigned long long mask = __ballot(coop);
+    while (mask) {
+        const int L = __ffsll((long long)mask) - 1;
+        mask &= mask - 1;
+        const int bb = __shfl(b, L), ee = __shfl(e, L);
+        float t = 0.f;
+        for (int j = bb + lane; j < ee; j += 64) t += val[(size_t)(via ? via[j] : j) * stride + off];
+        t = group_sum<64>(t);
+        if (lane == L) s = t;
+    }
+    if (i < n) out[i] = s;
+}
+
+// ------------------------------------------------------------------ edge softmax (RGAT)
+
+// Per item of the destination-major list: l_e = leakyrelu(s_src[pair] + s_dst[run]) is
+// written to att, then max and sum of exp; a whole-node item normalises at once
+// (att_e = +-exp(l - m)/sum, sign bit set when z_e <= 0), a piece of a cut node stores
+// (m, sum) for the combine step.
+struct SoftmaxArgs {
+    Items it;
+    const int32_t* in_pair;
+    const int32_t* in_run;
+    const float* s_src;
+    const float* s_dst;
+    float slope;
+    float* att;
+    float* part_m;
+    float* part_s;
+};
+
+__device__ __forceinline__ float signed_att(float l, float m, float inv) {
+    const float a = expf(l - m) * inv;
+    return l > 0.f ? a : -a;
+}
+
+__global__ void edge_softmax_kernel(SoftmaxArgs a) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    int b = 0, e = 0, slot = -1;
+    if (i < a.it.n) { b = a.it.beg[i]; e = a.it.end[i]; slot = a.it.slot[i]; }
+    const bool coop = (e - b) > 16;
+    if (!coop && e > b) {
+        float m = -INFINITY, s = 0.f;
+        for (int j = b; j < e; ++j) {
+            const float z = a.s_src[a.in_pair[j]] + a.s_dst[a.in_run[j]];
+            const float l = z > 0.f ? z : a.slope * z;
+            a.att[j] = l;
+            m = fmaxf(m, l);
+        }
+        for (int j = b; j < e; ++j) s += expf(a.att[j] - m);
+        if (slot < 0) {
+            const float inv = 1.f / s;
+            for (int j = b; j < e; ++j) a.att[j] = signed_att(a.att[j], m, inv);
+        } else {
+            a.part_m[slot] = m;
+            a.part_s[slot] = s;
+        }
+    }
+    unsigned long long mask = __ballot(coop);
+    while (mask) {
+        const int L = __ffsll((long long)mask) - 1;
+        mask &= mask - 1;
+        const int bb = __shfl(b, L), ee = __shfl(e, L), sl = __shfl(slot, L);
+        float m = -INFINITY, s = 0.f;
+        for (int j = bb + lane; j < ee; j += 64) {
+            const float z = a.s_src[a.in_pair[j]] + a.s_dst[a.in_run[j]];
+            const float l = z > 0.f ? z : a.slope * z;
+            a.att[j] = l;
+            m = fmaxf(m, l);
+        }
+        m = wave_max(m);
+        for (int j = bb + lane; j < ee; j += 64) s += expf(a.att[j] - m);
+        s = group_sum<64>(s);
+        if (sl < 0) {
+            const float inv = 1.f / s;
+            for (int j = bb + lane; j < ee; j += 64) a.att[j] = signed_att(a.att[j], m, inv);
+        } else if (lane == 0) {
+            a.part_m[sl] = m;
+            a.part_s[sl] = s;
+        }
+    }
+}
+
+// Cut nodes: combine the pieces' (m, sum) in order, then normalise every piece.
+// One wavefront per piece; each recomputes its node's totals (a node has few pieces).
+__global__ void edge_softmax_finish_kernel(int num_partials, const int32_t* __restrict__ part_item,
+                                           const int32_t* __restrict__ part_split,
+                                           const int32_t* __restrict__ split_ptr, Items it,
+                                           const float* __restrict__ part_m, const float* __restrict__ part_s,
+                                           float* __restrict__ att) {
+    const int t = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    if (t >= num_partials) return;
+    const int sp = part_split[t];
+    const int p0 = split_ptr[sp], p1 = split_ptr[sp + 1];
+    float m = -INFINITY;
+    for (int p = p0 + lane; p < p1; p += 64) m = fmaxf(m, part_m[p]);
+    m = wave_max(m);
+    float s = 0.f;
+    for (int p = p0 + lane; p < p1; p += 64) s += part_s[p] * expf(part_m[p] - m);
+    s = group_sum<64>(s);
+    const float inv = 1.f / s;
+    const int item = part_item[t];
+    for (int j = it.beg[item] + lane; j < it.end[item]; j += 64) att[j] = signed_att(att[j], m, inv);
+}
+
+// ------------------------------------------------------------------ weighted gather-sum
+
+// For item i with entries j in [beg, end):
+//   k   = via ? via[j] : j
+//   row = row_by_k ? rowidx[k] : rowidx[j]
+//   c   = coef ? coef[k * cstride] : 1            (absolute value if cabs)
+//   acc += c * src[row]
+// and acc goes to out[row_i] (whole segment) or partial[slot] (piece of a cut segment).
+struct GatherArgs {
+    Items it;
+    const int32_t* via;
+    const int32_t* rowidx;
+    int row_by_k;
+    const float* coef;
+    int cstride;
+    int cabs;
+    const float* src;
+    float* out;
+    float* partial;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
+    constexpr int LPR = D / 4, IPB = 256 / LPR;
+    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+    if (i >= a.it.n) return;
+    const int b = a.it.beg[i], e = a.it.end[i];
+    float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
+    for (int j = b; j < e; j += 4) {
+        int row[4];
+        float c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            row[u] = -1;
+            c[u] = 0.f;
+            if (j + u < e) {
+                const int k = a.via ? a.via[j + u] : j + u;
+                row[u] = a.row_by_k ? a.rowidx[k] : a.rowidx[j + u];
+                c[u] = a.coef ? a.coef[(size_t)k * a.cstride] : 1.f;
+                if (a.cabs) c[u] = fabsf(c[u]);
+            }
+        }
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            v[u] = row[u] >= 0 ? *reinterpret_cast<const float4*>(a.src + (size_t)row[u] * D + c4 * 4)
+                               : make_float4(0.f, 0.f, 0.f, 0.f);
+        fma4(acc0, c[0], v[0]);
+        fma4(acc1, c[1], v[1]);
+        fma4(acc0, c[2], v[2]);
+        fma4(acc1, c[3], v[3]);
+    }
+    acc0.x += acc1.x; acc0.y += acc1.y; acc0.z += acc1.z; acc0.w += acc1.w;
+    const int slot = a.it.slot[i];
+    float* o = slot < 0 ? a.out + (size_t)a.it.row[i] * D : a.partial + (size_t)slot * D;
+    *reinterpret_cast<float4*>(o + c4 * 4) = acc0;
+}
+
+// out[split_row[s]] = sum of partial rows [split_ptr[s], split_ptr[s+1]) in order.
+template <int D>
+__global__ void combine_partials_kernel(int num_split, const int32_t* __restrict__ split_row,
+                                        const int32_t* __restrict__ split_ptr, const float* __restrict__ partial,
+                                        float* __restrict__ out) {
+    constexpr int LPR = D / 4;
+    const int s = (blockIdx.x * blockDim.x + threadIdx.x) / LPR, c4 = threadIdx.x % LPR;
+    if (s >= num_split) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int p = split_ptr[s]; p < split_ptr[s + 1]; ++p)
+        fma4(acc, 1.f, *reinterpret_cast<const float4*>(partial + (size_t)p * D + c4 * 4));
+    *reinterpret_cast<float4*>(out + (size_t)split_row[s] * D + c4 * 4) = acc;
+}
+
+// ------------------------------------------------------------------ backward per-edge dot (RGAT)
+
+// For every CSR edge e of destination v:  g_e = dOut[v] . Hs[pair_e];
+// with gbar_v = sum_e att_e g_e = dOut[v] . out[v] (because out[v] = sum_e att_e Hs[pair_e]):
+//   dl_e = att_e (g_e - gbar_v);  dz_e = dl_e * (z_e > 0 ? 1 : slope);   adz[e] = (att_e, dz_e).
+// No reduction over the segment is needed, so pieces of cut nodes are independent.
+struct EdgeDotArgs {
+    Items it;
+    const int32_t* in_pair;
+    const float* att;
+    const float* Hs;
+    const float* dOut;
+    const float* out;
+    float slope;
+    float2* adz;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
+    constexpr int LPR = D / 4, IPB = 256 / LPR;
+    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+    if (i >= a.it.n) return;
+    const int b = a.it.beg[i], e = a.it.end[i];
+    if (e == b) return;
+    const size_t v = (size_t)a.it.row[i];
+    const float4 go = *reinterpret_cast<const float4*>(a.dOut + v * D + c4 * 4);
+    const float4 ov = *reinterpret_cast<const float4*>(a.out + v * D + c4 * 4);
+    const float gbar = group_sum<LPR>(dot4(go, ov));
+    for (int j = b; j < e; j += 4) {
+        float at[4];
+        float4 h[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            at[u] = 0.f;
+            h[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (j + u < e) {
+                at[u] = a.att[j + u];
+                h[u] = *reinterpret_cast<const float4*>(a.Hs + (size_t)a.in_pair[j + u] * D + c4 * 4);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float g = group_sum<LPR>(dot4(go, h[u]));
+            const float al = fabsf(at[u]);
+            const float dl = al * (g - gbar);
+            const float dz = dl * (signbit(at[u]) ? a.slope : 1.f);
+            if (c4 == 0 && j + u < e) a.adz[j + u] = make_float2(al, dz);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ dX assembly
+
+// dX[u] = sum_{p in srcpair(u)} dXp[p]  +  sum_{q in runs(u)} ds_dst[q] * wtp[run_rel[q]]  +  extra[u]
+// (second and third terms optional).
+struct NodeSumArgs {
+    int N;
+    const int32_t* srcpair_ptr;
+    const int32_t* srcpair_idx;
+    const float* dXp;
+    const int32_t* dst_run_ptr;
+    const int32_t* run_rel;
+    const float* ds_dst;
+    const float* wtp;
+    const float* extra;
+    float* dX;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
+    constexpr int LPR = D / 4, IPB = 256 / LPR;
+    const int u = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+    if (u >= a.N) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (a.extra) acc = *reinterpret_cast<const float4*>(a.extra + (size_t)u * D + c4 * 4);
+    const int b = a.srcpair_ptr[u], e = a.srcpair_ptr[u + 1];
+    for (int j = b; j < e; j += 2) {
+        const float4 v0 = *reinterpret_cast<const float4*>(a.dXp + (size_t)a.srcpair_idx[j] * D + c4 * 4);
+        float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (j + 1 < e) v1 = *reinterpret_cast<const float4*>(a.dXp + (size_t)a.srcpair_idx[j + 1] * D + c4 * 4);
+        fma4(acc, 1.f, v0);
+        fma4(acc, 1.f, v1);
+    }
+    if (a.ds_dst) {
+        for (int q = a.dst_run_ptr[u]; q < a.dst_run_ptr[u + 1]; ++q)
+            fma4(acc, a.ds_dst[q], *reinterpret_cast<const float4*>(a.wtp + (size_t)a.run_rel[q] * D + c4 * 4));
+    }
+    *reinterpret_cast<float4*>(a.dX + (size_t)u * D + c4 * 4) = acc;
+}
+
+// ------------------------------------------------------------------ RGAT parameter-gradient epilogue
+
+// Per relation r:  dw_s[r] = A[r] W[r];  dw_t[r] = U[r] W[r];  dW[r] += U[r]^T (x) w_t[r]
+// where A[r] = sum_p ds_src[p] X[src_p] and U[r] = sum_q ds_dst[q] X[dst_q].
+__global__ void rgat_param_finish_kernel(int kd, int nd, const float* __restrict__ W, const float* __restrict__ w_t,
+                                         const float* __restrict__ A, const float* __restrict__ U,
+                                         float* __restrict__ dW, float* __restrict__ dw_s, float* __restrict__ dw_t) {
+    const int r = blockIdx.x;
+    const float* Wr = W + (size_t)r * kd * nd;
+    const float* Ar = A + (size_t)r * kd;
+    const float* Ur = U + (size_t)r * kd;
+    for (int n = threadIdx.x; n < nd; n += blockDim.x) {
+        float s = 0.f, t = 0.f;
+        for (int k = 0; k < kd; ++k) {
+            s += Ar[k] * Wr[k * nd + n];
+            t += Ur[k] * Wr[k * nd + n];
+        }
+        dw_s[(size_t)r * nd + n] = s;
+        dw_t[(size_t)r * nd + n] = t;
+    }
+    for (int i = threadIdx.x; i < kd * nd; i += blockDim.x)
+        dW[(size_t)r * kd * nd + i] += Ur[i / nd] * w_t[(size_t)r * nd + i % nd];
+}
+
+// ------------------------------------------------------------------ elementwise
+
+__global__ void relu_kernel(size_t n, float* __restrict__ x) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) x[i] = x[i] > 0.f ? x[i] : 0.f;
+}
+// y = (ref > 0) ? g : 0
+__global__ void relu_grad_kernel(size_t n, const float* __restrict__ ref, const float* __restrict__ g,
+                                 float* __restrict__ y) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) y[i] = ref[i] > 0.f ? g[i] : 0.f;
+}
+
+// ==================================================================== host launchers
+
+#define CHECK_LAUNCH() RGNN_HIP(hipGetLastError())
+static inline unsigned blocks_for(size_t n, unsigned per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+
+#define DISPATCH_D(D_, CALL)                                                           \
+    do {                                                                               \
+        if ((D_) == 64) { constexpr int DD = 64; CALL; }                               \
+        else if ((D_) == 32) { constexpr int DD = 32; CALL; }                          \
+        else if ((D_) == 128) { constexpr int DD = 128; CALL; }                        \
+        else RGNN_FAIL(RGNN_EUNSUPPORTED, "feature width %d not supported (32/64/128)", (int)(D_)); \
+    } while (0)
+
+rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st) {
+    const int total = R * kd;
+    hipLaunchKernelGGL(fold_weight_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, st, W, w, kd, nd, total, wv);
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st) {
+    if (g->Q == 0) return RGNN_OK;
+    DISPATCH_D(D, hipLaunchKernelGGL(run_logit_kernel<DD>, dim3(blocks_for((size_t)g->Q * (DD / 4), 256)), dim3(256), 0,
+                                     st, (int)g->Q, g->idx[RGNN_IDX_RUN_DST], g->idx[RGNN_IDX_RUN_REL], X, wtp, s_dst));
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const int32_t* via, const float* val, int stride, int off,
+                                 float* out, hipStream_t st) {
+    if (n == 0) return RGNN_OK;
+    hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ptr, via, val, stride,
+                       off, out);
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
+                           float* part_m, float* part_s, hipStream_t st) {
+    const ItemList& L = g->dst_items;
+    if (L.num_items == 0) return RGNN_OK;
+    SoftmaxArgs a{dev_items(L), g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN], s_src, s_dst, slope, att, part_m, part_s};
+    hipLaunchKernelGGL(edge_softmax_kernel, dim3(blocks_for(L.num_items, 256)), dim3(256), 0, st, a);
+    CHECK_LAUNCH();
+    if (L.num_partials > 0) {
+        hipLaunchKernelGGL(edge_softmax_finish_kernel, dim3(blocks_for((size_t)L.num_partials * 64, 256)), dim3(256), 0,
+                           st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), part_m, part_s, att);
+        CHECK_LAUNCH();
+    }
+    return RGNN_OK;
+}
+
+rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
+                         const float* coef, int cstride, int cabs, const float* src, float* out, float* partial,
+                         hipStream_t st) {
+    if (L.num_items == 0) return RGNN_OK;
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, src, out, partial};
+    DISPATCH_D(D, hipLaunchKernelGGL(gather_sum_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256), 0,
+                                     st, a));
+    CHECK_LAUNCH();
+    if (L.num_split > 0) {
+        DISPATCH_D(D, hipLaunchKernelGGL(combine_partials_kernel<DD>, dim3(blocks_for((size_t)L.num_split * (DD / 4), 256)),
+                                         dim3(256), 0, st, L.num_split, L.split_row, L.split_ptr, partial, out));
+        CHECK_LAUNCH();
+    }
+    return RGNN_OK;
+}
+
+rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
+                           const float* out, float slope, float* adz, hipStream_t st) {
+    const ItemList& L = g->dst_items;
+    if (L.num_items == 0 || g->E == 0) return RGNN_OK;
+    EdgeDotArgs a{dev_items(L), g->idx[RGNN_IDX_IN_PAIR], att, Hs, dOut, out, slope, reinterpret_cast<float2*>(adz)};
+    DISPATCH_D(D, hipLaunchKernelGGL(edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
+                                     0, st, a));
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const float* dXp, const float* ds_dst, const float* wtp,
+                            const float* extra, float* dX, hipStream_t st) {
+    if (g->N == 0) return RGNN_OK;
+    NodeSumArgs a{(int)g->N, g->idx[RGNN_IDX_SRCPAIR_PTR], g->idx[RGNN_IDX_SRCPAIR_IDX], dXp,
+                  g->idx[RGNN_IDX_DST_RUN_PTR], g->idx[RGNN_IDX_RUN_REL], ds_dst, wtp, extra, dX};
+    DISPATCH_D(D, hipLaunchKernelGGL(node_grad_sum_kernel<DD>, dim3(blocks_for((size_t)g->N, 256 / (DD / 4))), dim3(256),
+                                     0, st, a));
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const float* w_t, const float* A,
+                                const float* U, float* dW, float* dw_s, float* dw_t, hipStream_t st) {
+    hipLaunchKernelGGL(rgat_param_finish_kernel, dim3(R), dim3(256), 0, st, kd, nd, W, w_t, A, U, dW, dw_s, dw_t);
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t relu_inplace(size_t n, float* x, hipStream_t st) {
+    if (n == 0) return RGNN_OK;
+    hipLaunchKernelGGL(relu_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, x);
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+rgnn_status_t relu_grad(size_t n, const float* ref, const float* gin, float* y, hipStream_t st) {
+    if (n == 0) return RGNN_OK;
+    hipLaunchKernelGGL(relu_grad_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ref, gin, y);
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+}  // namespace rgnn

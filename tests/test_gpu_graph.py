@@ -1,0 +1,59 @@
+"""Graph index built by the library vs the numpy oracle: bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import graph_index
+from paper_2412_04747_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _compare(N, R, T, src, dst, rel, ntype):
+    from paper_2412_04747_amd.harness import Graph
+    from paper_2412_04747_amd import binding as B
+    g = Graph(N, R, src, dst, rel, ntype if T > 1 else None, T)
+    want = graph_index.build(N, R, src, dst, rel, ntype, T)
+    assert (g.P, g.Q, int(g.info.max_in_degree)) == (want["P"], want["Q"], want["max_in_degree"])
+    for name in B.INDEX_NAMES:
+        got = g.export(name)
+        assert np.array_equal(got, want[name]), name
+    g.close()
+
+
+def test_tiny_and_degenerate():
+    print("graph: tiny cases", flush=True)
+    for seed, (N, R, E, T) in enumerate([(6, 2, 20, 1), (9, 4, 35, 3), (5, 3, 0, 2), (1, 1, 3, 1), (300, 7, 5000, 4)]):
+        _, src, dst, rel, ntype = synth.tiny(seed, N, R, E, T)
+        _compare(N, R, T, src, dst, rel, ntype)
+
+
+def test_skewed_with_hub_and_empty_relations():
+    print("graph: config 2 + hub", flush=True)
+    g = synth.config(2)
+    N, R = g["N"], g["R"] + 3                          # three relations without edges
+    src, dst, rel = g["src"].copy(), g["dst"].copy(), g["rel"].copy()
+    dst[:5000] = 7                                     # a hub far above the item length
+    _compare(N, R, 1, src, dst, rel, np.zeros(N, np.int32))
+
+
+def test_edge_order_does_not_change_the_index():
+    from paper_2412_04747_amd.harness import Graph
+    _, src, dst, rel, _ = synth.tiny(5, 50, 4, 400)
+    perm = np.random.default_rng(0).permutation(len(src))
+    a = Graph(50, 4, src, dst, rel)
+    b = Graph(50, 4, src[perm], dst[perm], rel[perm])
+    for name in ("in_ptr", "in_src", "in_rel", "in_pair", "out_epos", "pair_src", "relrun_idx"):
+        assert np.array_equal(a.export(name), b.export(name)), name
+
+
+def test_bad_ids_are_rejected():
+    from paper_2412_04747_amd.harness import Graph
+    from paper_2412_04747_amd.binding import RgnnError
+    src = np.array([0, 1], np.int32); dst = np.array([1, 5], np.int32); rel = np.array([0, 0], np.int32)
+    with pytest.raises(RgnnError) as e:
+        Graph(3, 1, src, dst, rel)
+    assert e.value.status == 1
+    with pytest.raises(RgnnError):
+        Graph(3, 2, np.array([0], np.int32), np.array([1], np.int32), np.array([0], np.int32),
+              ntype=np.array([0, 1, 1], np.int32), T=2, rel_src_ntype=np.array([1, 0], np.int32),
+              rel_dst_ntype=np.array([1, 0], np.int32))

@@ -1,0 +1,60 @@
+"""RGCN layer on the GPU vs the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+from oracle import layers as O
+from paper_2412_04747_amd import synth
+from parity import check, TOL_F32
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(N, R, src, dst, rel, p, d, norm, act, self_loop, bwd=True, tag=""):
+    import torch
+    from paper_2412_04747_amd.harness import Graph, RgcnLayer
+    print(f"rgcn case {tag}: N={N} R={R} E={len(src)} d={d} norm={norm} act={act} W0={self_loop}", flush=True)
+    g = Graph(N, R, src, dst, rel)
+    L = RgcnLayer(g, d, norm, act, self_loop)
+    W0 = p["W0"] if self_loop else None
+    L.load(p["X"], p["W"], W0, p["dOut"])
+    L.fwd()
+    torch.cuda.synchronize()
+    want = O.rgcn_fwd(N, src, dst, rel, p["X"], p["W"], W0, norm, act)
+    check(L.out, want, TOL_F32, "out")
+    if bwd:
+        L.bwd()
+        torch.cuda.synchronize()
+        wg = O.rgcn_bwd(N, src, dst, rel, p["X"], p["W"], W0, p["dOut"], norm, act, out=want)
+        for k, v in L.grads().items():
+            check(v, wg[k], TOL_F32, k)
+    g.close()
+
+
+def test_config1_forward():
+    c = synth.config(1)
+    _run(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 32, "in_degree_per_rel", "none", False, bwd=False, tag="C1")
+
+
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_forward_backward_all_options(d):
+    rng, src, dst, rel, _ = synth.tiny(40 + d, N=700, R=5, E=6000)
+    p = synth.rgcn_params(rng, 700, 5, d, d, self_loop=True)
+    _run(700, 5, src, dst, rel, p, d, "in_degree_per_rel", "none", True, tag=f"d{d}")
+    _run(700, 5, src, dst, rel, p, d, "none", "relu", True, tag=f"d{d}-relu")
+    _run(700, 5, src, dst, rel, p, d, "none", "none", False, tag=f"d{d}-plain")
+
+
+def test_hub_and_isolated_nodes():
+    rng, src, dst, rel, _ = synth.tiny(50, N=400, R=3, E=3000)
+    dst[:1500] = 3          # hub far above the item length, many nodes left without in-edges
+    src[:900] = 5           # one (src, rel) pair feeding many edges
+    rel[:900] = 1
+    p = synth.rgcn_params(rng, 400, 3, 64, 64, self_loop=True)
+    _run(400, 3, src, dst, rel, p, 64, "in_degree_per_rel", "none", True, tag="hub")
+
+
+def test_empty_graph():
+    rng = np.random.default_rng(0)
+    p = synth.rgcn_params(rng, 10, 2, 32, 32, self_loop=True)
+    e = np.zeros(0, np.int32)
+    _run(10, 2, e, e, e, p, 32, "in_degree_per_rel", "none", True, tag="empty")
