@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark: RGAT layer forward+backward on one MI355X, edges/s.
+
+One step = one pass of the whole hot path (rgnn_rgat_fwd + rgnn_rgat_bwd) over the
+synthetic 1M-node / 200-relation / 10M-edge graph, inputs resident in HBM, graph index
+built beforehand (the thesis also times the layer only, with preprocessing done before).
+Prints ONE JSON line with the throughput, the roofline of the dominant kernel (timed live
+with HIP events on the launch stream, through the library's profiling hooks) and the CPU
+oracle timed on the host cores on the same inputs.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def algorithmic_work(name, E, N, P, Q, R, d):
+    """(bound, bytes, flops) one launch of kernel `name` must move / compute (fp32, b = 4).
+    Gathered rows are counted once per reference (no cache reuse assumed); index and scalar
+    traffic as listed; see DESIGN.md "Kernels and their rooflines"."""
+    b = 4
+    row = d * b
+    table = {
+        # per pair: gathered X row + stored Hs row + pair_src + s_src; weights once
+        "typed_linear_fwd": ("mfma", P * (2 * row + 8) + R * d * d * b, 2.0 * P * d * d),
+        # per pair: G row + gathered X row + stored dXp row + pair_src + ds_src; weights once, dW slots ignored
+        "typed_linear_bwd": ("mfma", P * (3 * row + 8) + R * d * d * b, 4.0 * P * d * d),
+        # per edge: Hs row + in_pair + att; per node: out row + item (beg, end)
+        "aggregate_fwd": ("hbm", E * (row + 8) + N * (row + 8), 2.0 * E * d),
+        # per edge: Hs row + in_pair + att + (att, dz) store; per node: dOut row + out row + item
+        "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8), 2.0 * E * d),
+        # per edge: dOut row + out_epos + out_dst + (att, dz); per pair: G row + item
+        "aggregate_bwd_pair": ("hbm", E * (row + 16) + P * (row + 8), 2.0 * E * d),
+        # per run: X row + relrun_idx + run_dst + ds_dst
+        "dst_side_wgrad": ("hbm", Q * (row + 12), 2.0 * Q * d),
+        # per pair: dXp row + srcpair_idx; per run: ds_dst + run_rel; per node: dX row + 2 ptrs
+        "node_grad_sum": ("hbm", P * (row + 4) + Q * 8 + N * (row + 8), 1.0 * P * d),
+        # per edge: in_pair, in_run, s_src, s_dst, att write (reads of its own writes not counted)
+        "edge_softmax": ("hbm", E * 20 + N * 8, 10.0 * E),
+        "run_logit": ("hbm", Q * (row + 12), 2.0 * Q * d),
+    }
+    return table.get(name)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="synthetic workload id (3 = headline RGAT graph)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
+    ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle leg (no cpu_baseline, no parity)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); the multi-GPU sharding is a design note "
+                 "in DESIGN.md, not code.")
+
+    import numpy as np
+    import torch
+    from paper_2412_04747_amd import synth, binding as B
+    from paper_2412_04747_amd.harness import Graph, RgatLayer
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    t0 = time.time()
+    c = synth.config(args.config, args.scale)
+    assert c["layer"] == "rgat", "bench.py times the RGAT workloads (configs 2 and 3)"
+    N, R, E, d = c["N"], c["R"], c["E"], c["d_out"]
+    print(f"[bench] generated config {args.config}: N={N} R={R} E={E} d={d} in {time.time() - t0:.1f}s",
+          file=sys.stderr, flush=True)
+
+    cpu = None
+    want = None
+    if not args.no_oracle:
+        from oracle import layers as O
+        t0 = time.time()
+        want_out = O.rgat_fwd(N, c["src"], c["dst"], c["rel"], c["X"], c["W"], c["w_s"], c["w_t"], c["slope"])
+        t_f = time.time() - t0
+        t0 = time.time()
+        want = O.rgat_bwd(N, c["src"], c["dst"], c["rel"], c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"], c["slope"])
+        t_b = time.time() - t0
+        want["out"] = want_out
+        cpu = {"value": E / (t_f + t_b), "unit": "edges/s", "cores": O.num_threads(), "kind": "oracle",
+               "sample": f"full workload, 1 repetition (fwd {t_f:.2f}s + bwd {t_b:.2f}s)"}
+        print(f"[bench] oracle fwd {t_f:.2f}s bwd {t_b:.2f}s on {O.num_threads()} threads", file=sys.stderr, flush=True)
+
+    t0 = time.time()
+    g = Graph(N, R, c["src"], c["dst"], c["rel"])
+    P, Q = g.P, g.Q
+    print(f"[bench] graph index built in {time.time() - t0:.1f}s: P/E={P / E:.3f} Q/E={Q / E:.3f} "
+          f"max in-degree {g.info.max_in_degree} index {g.info.index_bytes / 2**20:.0f} MiB", file=sys.stderr, flush=True)
+    L = RgatLayer(g, d, c["slope"])
+    L.load(c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"])
+
+    for _ in range(args.warmup):
+        L.fwd(); L.bwd()
+    torch.cuda.synchronize()
+    # untimed clean pass, to show what the profiling events cost
+    tc = time.perf_counter()
+    for _ in range(args.steps):
+        L.fwd(); L.bwd()
+    torch.cuda.synchronize()
+    clean_ms = (time.perf_counter() - tc) * 1e3 / args.steps
+
+    B.rgnn_profile_start()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        L.fwd(); L.bwd()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    rep = B.rgnn_profile_stop()
+    ms_per_step = dt * 1e3 / args.steps
+
+    parity = None
+    if want is not None:
+        parity = {}
+        got = dict(out=L.out, **L.grads())
+        for k, v in got.items():
+            a = v.cpu().numpy().astype(np.float64)
+            parity[k] = float(np.abs(a - want[k]).max() / max(np.abs(want[k]).max(), 1e-30))
+        print(f"[bench] max relative error vs oracle: {parity}", file=sys.stderr, flush=True)
+
+    kernels = []
+    for name, (n, ms) in rep.items():
+        avg_ms = ms / n
+        w = algorithmic_work(name, E, N, P, Q, R, d)
+        row = {"name": name, "launches_per_step": n / args.steps, "avg_ms": avg_ms, "ms_per_step": ms / args.steps}
+        if w:
+            row["GBps"] = w[1] / avg_ms / 1e6
+            row["TFLOPs"] = w[2] / avg_ms / 1e9
+            row["bound"] = w[0]
+        kernels.append(row)
+    kernels.sort(key=lambda r: -r["ms_per_step"])
+    for r in kernels:
+        print("[bench] {name:28s} {ms_per_step:8.3f} ms/step  avg {avg_ms:8.3f} ms  {gb:>9s} GB/s {tf:>8s} TF/s".format(
+            gb=f"{r['GBps']:.0f}" if "GBps" in r else "-", tf=f"{r['TFLOPs']:.1f}" if "TFLOPs" in r else "-", **r),
+            file=sys.stderr, flush=True)
+    dom = kernels[0]
+    w = algorithmic_work(dom["name"], E, N, P, Q, R, d)
+    if w and w[0] == "mfma":
+        roof = {"kernel": dom["name"], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": FP32_MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": dom["TFLOPs"] / FP32_MFMA_PEAK_TFLOPS, "traffic": None}
+    else:
+        gb = dom.get("GBps", 0.0)
+        roof = {"kernel": dom["name"], "bound": "hbm", "achieved": gb, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": gb / HBM_PEAK_GBS, "traffic": None}
+    roof["avg_ms"] = dom["avg_ms"]
+    roof["algorithmic_bytes"] = w[1] if w else None
+
+    line = {
+        "metric": "edges/sec for RGAT layer fwd+bwd", "value": E * args.steps / dt, "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}]: RGAT single-head fwd+bwd fp32, N={N}, R={R}, E={E}, d={d}"
+                               + ("" if args.scale == 1.0 else f" (scale {args.scale})"),
+                   "P_over_E": P / E, "Q_over_E": Q / E, "max_in_degree": int(g.info.max_in_degree)},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "ms_per_step_without_profiling_events": clean_ms,
+        "parity_max_rel_err": parity,
+        "kernels": kernels,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -212,6 +212,17 @@ rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc,
                            void* dWk, void* dWq, void* dWv, void* dWo, void* dWatt, void* dWmsg, void* dmu,
                            void* workspace, void* stream);
 
+/*
+ * Per-kernel timing for benchmarks (not part of the layer definition).  Between
+ * rgnn_profile_start() and rgnn_profile_stop() every kernel the layer calls launch is
+ * bracketed by HIP events on the caller's stream.  rgnn_profile_stop() synchronises the
+ * device and writes one text line per kernel name, "name launches total_ms\n", in first
+ * launch order, into `report` (NUL-terminated, truncated at whole lines to fit
+ * report_bytes).  Events are created on demand while profiling is on.
+ */
+rgnn_status_t rgnn_profile_start(void);
+rgnn_status_t rgnn_profile_stop(char* report, size_t report_bytes);
+
 #ifdef __cplusplus
 }
 #endif

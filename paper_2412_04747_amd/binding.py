@@ -28,7 +28,7 @@ INDEX_NAMES = ["in_ptr", "in_src", "in_rel", "in_eid", "in_pair", "in_run", "in_
 
 EXPORTS = ["rgnn_last_error", "rgnn_graph_create", "rgnn_graph_destroy", "rgnn_graph_info", "rgnn_graph_export",
            "rgnn_workspace_bytes", "rgnn_rgcn_fwd", "rgnn_rgcn_bwd", "rgnn_rgat_fwd", "rgnn_rgat_bwd",
-           "rgnn_hgt_fwd", "rgnn_hgt_bwd"]
+           "rgnn_hgt_fwd", "rgnn_hgt_bwd", "rgnn_profile_start", "rgnn_profile_stop"]
 
 
 class RgnnError(RuntimeError):
@@ -148,3 +148,18 @@ def rgnn_hgt_bwd(g, desc, X, Wk, Wq, Wv, Wo, Watt, Wmsg, mu, out, saved, dOut, d
                               _ptr(Wmsg), _ptr(mu), _ptr(out), _ptr(saved), _ptr(dOut), _ptr(dX), _ptr(dWk),
                               _ptr(dWq), _ptr(dWv), _ptr(dWo), _ptr(dWatt), _ptr(dWmsg), _ptr(dmu),
                               _ptr(workspace), _ptr(stream)))
+
+
+def rgnn_profile_start():
+    _check(lib().rgnn_profile_start())
+
+
+def rgnn_profile_stop():
+    """-> {kernel name: (launches, total milliseconds)} in first-launch order."""
+    buf = C.create_string_buffer(1 << 16)
+    _check(lib().rgnn_profile_stop(buf, C.c_size_t(len(buf))))
+    rep = {}
+    for line in buf.value.decode().splitlines():
+        name, n, ms = line.split()
+        rep[name] = (int(n), float(ms))
+    return rep

@@ -146,12 +146,12 @@ extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     // 2. out[v] = sum_e (1/c) Hs[pair_e]
     const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, coef, 1, 0, w.Hs,
-                        static_cast<float*>(out), w.partial, st));
+                        static_cast<float*>(out), w.partial, st, "aggregate_fwd", "aggregate_fwd.combine"));
     // 3. self-loop: out += X W0
     if (W0) {
         TypedLinearArgs s{};
         s.tiles = &g->all_tiles; s.X = static_cast<const float*>(X); s.W = static_cast<const float*>(W0);
-        s.Y = static_cast<float*>(out); s.accumulate = 1;
+        s.Y = static_cast<float*>(out); s.accumulate = 1; s.label = "self_loop_fwd";
         RGNN_TRY(typed_linear_fwd(desc->d_in, D, s, st));
     }
     if (desc->activation == RGNN_ACT_RELU) RGNN_TRY(relu_inplace((size_t)g->N * D, static_cast<float*>(out), st));
@@ -180,7 +180,7 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     // 1. dHs[p] = sum_{e in out(p)} (1/c_e) dPre[dst_e]
     const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
     RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, coef, 1, 0, dPre, w.G,
-                        w.partial, st));
+                        w.partial, st, "aggregate_bwd_pair", "aggregate_bwd_pair.combine"));
     // 2. per pair dXp = dHs W^T; dW[r] = sum X^T dHs
     TypedLinearBwdArgs b{};
     b.tiles = &g->pair_tiles; b.X = static_cast<const float*>(X); b.gather = g->idx[RGNN_IDX_PAIR_SRC];
@@ -190,7 +190,7 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     if (W0) {
         TypedLinearBwdArgs s{};
         s.tiles = &g->all_tiles; s.X = static_cast<const float*>(X); s.W = static_cast<const float*>(W0); s.dY = dPre;
-        s.dXrow = w.dX0; s.dW = static_cast<float*>(dW0); s.part = w.tl_part;
+        s.dXrow = w.dX0; s.dW = static_cast<float*>(dW0); s.part = w.tl_part; s.label = "self_loop_bwd";
         RGNN_TRY(typed_linear_bwd(K, D, s, st));
     }
     // 4. dX[u] = sum over u's pairs of dXp (+ dX0[u])
@@ -224,7 +224,7 @@ extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     RGNN_TRY(edge_softmax(g, w.s_src, w.s_dst, desc->slope, sv.att, w.part_m, w.part_s, st));
     // 4. out[v] = sum_e att_e Hs[pair_e]
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, 1, 1, sv.Hs,
-                        static_cast<float*>(out), w.partial, st));
+                        static_cast<float*>(out), w.partial, st, "aggregate_fwd", "aggregate_fwd.combine"));
     return RGNN_OK;
 }
 
@@ -247,11 +247,11 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     // 1. per CSR edge: (att_e, dz_e)
     RGNN_TRY(edge_dot_bwd(g, D, sv.att, sv.Hs, dO, static_cast<const float*>(out), desc->slope, w.adz, st));
     // 2. ds_dst[q] = sum over the run's edges of dz;  ds_src[p] = sum over the pair's edges of dz
-    RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], nullptr, w.adz, 2, 1, w.ds_dst, st));
-    RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2, 1, w.ds_src, st));
+    RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], nullptr, w.adz, 2, 1, w.ds_dst, st, "ds_dst_sum"));
+    RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2, 1, w.ds_src, st, "ds_src_sum"));
     // 3. G[p] = sum_{e in out(p)} att_e dOut[dst_e]
     RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.adz, 2, 0, dO, w.G,
-                        w.partial, st));
+                        w.partial, st, "aggregate_bwd_pair", "aggregate_bwd_pair.combine"));
     // 4. dHs[p] = G[p] + ds_src[p] w_s[r];  dXp[p] = dHs[p] W[r]^T;  dW[r] = sum X^T dHs;  A[r] = sum ds_src X
     TypedLinearBwdArgs b{};
     b.tiles = &g->pair_tiles; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
@@ -260,7 +260,7 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     RGNN_TRY(typed_linear_bwd(K, D, b, st));
     // 5. U[r] = sum over r's runs of ds_dst[q] X[run_dst[q]]
     RGNN_TRY(gather_sum(g->relrun_items, K, g->idx[RGNN_IDX_RELRUN_IDX], g->idx[RGNN_IDX_RUN_DST], 1, w.ds_dst, 1, 0, Xf,
-                        w.U, w.partial, st));
+                        w.U, w.partial, st, "dst_side_wgrad", "dst_side_wgrad.combine"));
     // 6. dw_s = A W, dw_t = U W, dW += U^T (x) w_t
     RGNN_TRY(rgat_param_finish(g->R, K, D, Wf, static_cast<const float*>(w_t), w.A, w.U, static_cast<float*>(dW),
                                static_cast<float*>(dw_s), static_cast<float*>(dw_t), st));

@@ -1,0 +1,70 @@
+// Optional per-kernel timing with HIP events on the caller's stream, for benchmarks.
+// Off by default; while on, every kernel launch of the layer calls is bracketed by two
+// events (created on demand, so the no-allocation guarantee of the layer calls does not
+// hold while profiling).
+#include "rgnn_internal.h"
+
+#include <stdio.h>
+#include <string.h>
+#include <map>
+#include <mutex>
+
+namespace rgnn {
+
+struct Record { const char* name; hipEvent_t a, b; };
+static bool g_on = false;
+static std::vector<Record> g_rec;
+static std::mutex g_mu;
+
+KernelTimer::KernelTimer(hipStream_t st, const char* name) : st_(st), idx_(-1) {
+    if (!g_on) return;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Record r{name, nullptr, nullptr};
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    (void)hipEventRecord(r.a, st_);
+    idx_ = (int)g_rec.size();
+    g_rec.push_back(r);
+}
+KernelTimer::~KernelTimer() {
+    if (idx_ < 0) return;
+    std::lock_guard<std::mutex> lk(g_mu);
+    (void)hipEventRecord(g_rec[idx_].b, st_);
+}
+
+}  // namespace rgnn
+
+using namespace rgnn;
+
+extern "C" rgnn_status_t rgnn_profile_start(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (auto& r : g_rec) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    g_rec.clear();
+    g_on = true;
+    return RGNN_OK;
+}
+
+extern "C" rgnn_status_t rgnn_profile_stop(char* report, size_t report_bytes) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_on = false;
+    RGNN_HIP(hipDeviceSynchronize());
+    std::vector<const char*> order;
+    std::map<std::string, std::pair<int, double>> agg;
+    for (auto& r : g_rec) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) ms = 0.f;
+        auto it = agg.find(r.name);
+        if (it == agg.end()) { order.push_back(r.name); agg[r.name] = {1, (double)ms}; }
+        else { it->second.first++; it->second.second += ms; }
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_rec.clear();
+    size_t off = 0;
+    if (report && report_bytes) report[0] = 0;
+    for (const char* n : order) {
+        char line[160];
+        const int len = snprintf(line, sizeof(line), "%s %d %.6f\n", n, agg[n].first, agg[n].second);
+        if (report && off + (size_t)len + 1 <= report_bytes) { memcpy(report + off, line, (size_t)len + 1); off += (size_t)len; }
+    }
+    return RGNN_OK;
+}

@@ -30,6 +30,16 @@ void set_error(const char* fmt, ...);
         if (s_ != RGNN_OK) return s_;       \
     } while (0)
 
+// ---- optional kernel timing (profile.hip) ----------------------------------
+class KernelTimer {
+  public:
+    KernelTimer(hipStream_t st, const char* name);
+    ~KernelTimer();
+  private:
+    hipStream_t st_;
+    int idx_;
+};
+
 // ---- work lists ----------------------------------------------------------
 // Row tiles of a segmented row range (rows grouped by relation or node type),
 // cut into `num_chunks` contiguous chunks, one per persistent workgroup.  A
@@ -106,6 +116,7 @@ struct TypedLinearArgs {
     int accumulate;          // 1: Y += result
     const float* vec;        // optional [segs][ND]: s_out[i] = Y_row . vec[seg]
     float* s_out;
+    const char* label;       // name in the timing report (nullptr: default)
 };
 rgnn_status_t typed_linear_fwd(int d_in, int d_out, const TypedLinearArgs& a, hipStream_t st);
 
@@ -123,6 +134,7 @@ struct TypedLinearBwdArgs {
     float* dW;               // [segs][KD][ND]
     float* Avec;             // [segs][KD] (with rowscale)
     float* part;             // scratch [num_slots][KD*ND + KD]
+    const char* label;
 };
 size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t);
 rgnn_status_t typed_linear_bwd(int d_in, int d_out, const TypedLinearBwdArgs& a, hipStream_t st);

@@ -7,12 +7,12 @@ namespace rgnn {
 rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st);
 rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st);
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const int32_t* via, const float* val, int stride, int off,
-                                 float* out, hipStream_t st);
+                                 float* out, hipStream_t st, const char* label);
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
                            float* part_m, float* part_s, hipStream_t st);
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
                          const float* coef, int cstride, int cabs, const float* src, float* out, float* partial,
-                         hipStream_t st);
+                         hipStream_t st, const char* label, const char* combine_label);
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
                            const float* out, float slope, float* adz, hipStream_t st);
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const float* dXp, const float* ds_dst, const float* wtp,

@@ -408,6 +408,7 @@ static inline unsigned blocks_for(size_t n, unsigned per_block) { return (unsign
 
 rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st) {
     const int total = R * kd;
+    KernelTimer kt(st, "fold_weight");
     hipLaunchKernelGGL(fold_weight_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, st, W, w, kd, nd, total, wv);
     CHECK_LAUNCH();
     return RGNN_OK;
@@ -415,6 +416,7 @@ rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w,
 
 rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st) {
     if (g->Q == 0) return RGNN_OK;
+    KernelTimer kt(st, "run_logit");
     DISPATCH_D(D, hipLaunchKernelGGL(run_logit_kernel<DD>, dim3(blocks_for((size_t)g->Q * (DD / 4), 256)), dim3(256), 0,
                                      st, (int)g->Q, g->idx[RGNN_IDX_RUN_DST], g->idx[RGNN_IDX_RUN_REL], X, wtp, s_dst));
     CHECK_LAUNCH();
@@ -422,8 +424,9 @@ rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float*
 }
 
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const int32_t* via, const float* val, int stride, int off,
-                                 float* out, hipStream_t st) {
+                                 float* out, hipStream_t st, const char* label) {
     if (n == 0) return RGNN_OK;
+    KernelTimer kt(st, label);
     hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ptr, via, val, stride,
                        off, out);
     CHECK_LAUNCH();
@@ -435,9 +438,13 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
     const ItemList& L = g->dst_items;
     if (L.num_items == 0) return RGNN_OK;
     SoftmaxArgs a{dev_items(L), g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN], s_src, s_dst, slope, att, part_m, part_s};
-    hipLaunchKernelGGL(edge_softmax_kernel, dim3(blocks_for(L.num_items, 256)), dim3(256), 0, st, a);
-    CHECK_LAUNCH();
+    {
+        KernelTimer kt(st, "edge_softmax");
+        hipLaunchKernelGGL(edge_softmax_kernel, dim3(blocks_for(L.num_items, 256)), dim3(256), 0, st, a);
+        CHECK_LAUNCH();
+    }
     if (L.num_partials > 0) {
+        KernelTimer kt(st, "edge_softmax.finish");
         hipLaunchKernelGGL(edge_softmax_finish_kernel, dim3(blocks_for((size_t)L.num_partials * 64, 256)), dim3(256), 0,
                            st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), part_m, part_s, att);
         CHECK_LAUNCH();
@@ -447,13 +454,17 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
 
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
                          const float* coef, int cstride, int cabs, const float* src, float* out, float* partial,
-                         hipStream_t st) {
+                         hipStream_t st, const char* label, const char* combine_label) {
     if (L.num_items == 0) return RGNN_OK;
     GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, src, out, partial};
-    DISPATCH_D(D, hipLaunchKernelGGL(gather_sum_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256), 0,
-                                     st, a));
-    CHECK_LAUNCH();
+    {
+        KernelTimer kt(st, label);
+        DISPATCH_D(D, hipLaunchKernelGGL(gather_sum_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
+                                         0, st, a));
+        CHECK_LAUNCH();
+    }
     if (L.num_split > 0) {
+        KernelTimer kt(st, combine_label);
         DISPATCH_D(D, hipLaunchKernelGGL(combine_partials_kernel<DD>, dim3(blocks_for((size_t)L.num_split * (DD / 4), 256)),
                                          dim3(256), 0, st, L.num_split, L.split_row, L.split_ptr, partial, out));
         CHECK_LAUNCH();
@@ -466,6 +477,7 @@ rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const f
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
     EdgeDotArgs a{dev_items(L), g->idx[RGNN_IDX_IN_PAIR], att, Hs, dOut, out, slope, reinterpret_cast<float2*>(adz)};
+    KernelTimer kt(st, "edge_dot_bwd");
     DISPATCH_D(D, hipLaunchKernelGGL(edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
                                      0, st, a));
     CHECK_LAUNCH();
@@ -477,6 +489,7 @@ rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const float* dXp, const 
     if (g->N == 0) return RGNN_OK;
     NodeSumArgs a{(int)g->N, g->idx[RGNN_IDX_SRCPAIR_PTR], g->idx[RGNN_IDX_SRCPAIR_IDX], dXp,
                   g->idx[RGNN_IDX_DST_RUN_PTR], g->idx[RGNN_IDX_RUN_REL], ds_dst, wtp, extra, dX};
+    KernelTimer kt(st, "node_grad_sum");
     DISPATCH_D(D, hipLaunchKernelGGL(node_grad_sum_kernel<DD>, dim3(blocks_for((size_t)g->N, 256 / (DD / 4))), dim3(256),
                                      0, st, a));
     CHECK_LAUNCH();
@@ -485,6 +498,7 @@ rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const float* dXp, const 
 
 rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const float* w_t, const float* A,
                                 const float* U, float* dW, float* dw_s, float* dw_t, hipStream_t st) {
+    KernelTimer kt(st, "rgat_param_finish");
     hipLaunchKernelGGL(rgat_param_finish_kernel, dim3(R), dim3(256), 0, st, kd, nd, W, w_t, A, U, dW, dw_s, dw_t);
     CHECK_LAUNCH();
     return RGNN_OK;
@@ -492,12 +506,14 @@ rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const flo
 
 rgnn_status_t relu_inplace(size_t n, float* x, hipStream_t st) {
     if (n == 0) return RGNN_OK;
+    KernelTimer kt(st, "relu");
     hipLaunchKernelGGL(relu_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, x);
     CHECK_LAUNCH();
     return RGNN_OK;
 }
 rgnn_status_t relu_grad(size_t n, const float* ref, const float* gin, float* y, hipStream_t st) {
     if (n == 0) return RGNN_OK;
+    KernelTimer kt(st, "relu_grad");
     hipLaunchKernelGGL(relu_grad_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ref, gin, y);
     CHECK_LAUNCH();
     return RGNN_OK;

@@ -328,6 +328,7 @@ static rgnn_status_t launch_fwd(const TypedLinearArgs& a, hipStream_t st) {
     const size_t lds = sizeof(float) * (KD * ND + TM * STG);
     auto kern = typed_linear_fwd_kernel<KD, ND>;
     RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
                        a.Y, a.scatter_out, a.accumulate, a.vec, a.s_out);
     RGNN_HIP(hipGetLastError());
@@ -353,11 +354,13 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
     auto kern = typed_linear_bwd_kernel<KD, ND>;
     if (a.tiles->num_tiles > 0) {
         RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
         hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
                            a.dY, a.dy_gathered, a.dXrow, a.scatter_dx, a.rowscale, a.vec, a.part);
         RGNN_HIP(hipGetLastError());
     }
     const int kn = KD * ND;
+    KernelTimer kt(st, "typed_linear_bwd.reduce");
     hipLaunchKernelGGL(slot_reduce_kernel, dim3((kn + KD + 255) / 256, a.tiles->num_segs), dim3(256), 0, st, a.part,
                        a.tiles->seg_slot_ptr, kn, KD, a.dW, a.Avec);
     RGNN_HIP(hipGetLastError());
