@@ -137,12 +137,42 @@ static void build_items(Uploader& U, ItemList& L, const std::vector<int32_t>& pt
             sptr.push_back(partials);
         }
     }
+    // Order the items by length, longest first (stable): the lanes of a wavefront and the
+    // wavefronts of a workgroup then walk items of equal length and finish together, and the
+    // long items are scheduled before the short ones fill the tail.
+    {
+        const int n = (int)beg.size();
+        std::vector<int32_t> cnt(max_len + 2, 0), perm(n), inv(n);
+        for (int i = 0; i < n; ++i) cnt[max_len - (end[i] - beg[i]) + 1]++;
+        for (int l = 0; l <= max_len; ++l) cnt[l + 1] += cnt[l];
+        for (int i = 0; i < n; ++i) { const int p = cnt[max_len - (end[i] - beg[i])]++; perm[p] = i; inv[i] = p; }
+        auto apply = [&](std::vector<int32_t>& v) {
+            std::vector<int32_t> t(n);
+            for (int p = 0; p < n; ++p) t[p] = v[perm[p]];
+            v.swap(t);
+        };
+        apply(beg); apply(end); apply(row); apply(slot);
+        for (auto& it : pitem) it = inv[it];
+    }
     L.num_items = (int)beg.size();
     L.num_partials = partials;
     L.num_split = (int)srow.size();
     L.beg = U.up(beg); L.end = U.up(end); L.row = U.up(row); L.slot = U.up(slot);
     L.split_row = U.up(srow); L.split_ptr = U.up(sptr);
     L.part_item = U.up(pitem); L.part_split = U.up(psplit);
+    std::vector<int32_t> lng;
+    for (int i = 0; i < L.num_items; ++i)
+        if (end[i] - beg[i] > kSerialMax || slot[i] >= 0) lng.push_back(i);
+    L.num_long = (int)lng.size();
+    L.long_item = U.up(lng);
+}
+
+static void build_long(Uploader& U, LongList& L, const std::vector<int32_t>& ptr) {
+    std::vector<int32_t> ids;
+    for (size_t i = 0; i + 1 < ptr.size(); ++i)
+        if (ptr[i + 1] - ptr[i] > kSerialMax) ids.push_back((int32_t)i);
+    L.n = (int)ids.size();
+    L.ids = U.up(ids);
 }
 
 template <typename Tv>
@@ -301,6 +331,8 @@ static rgnn_status_t build(rgnn_graph* g, int format, const int32_t* a, const in
     build_items(U, g->dst_items, in_ptr, kItemMax);
     build_items(U, g->pair_items, out_ptr, kItemMax);
     build_items(U, g->relrun_items, relrun_ptr, kItemMax);
+    build_long(U, g->long_runs, run_ptr);
+    build_long(U, g->long_pairs, out_ptr);
     return U.st;
 }
 

@@ -75,9 +75,19 @@ struct ItemList {
     int32_t* split_row = nullptr;  // [num_split]
     int32_t* split_ptr = nullptr;  // [num_split+1] range of partial rows
     int32_t* part_item = nullptr;  // [num_partials] item that writes the partial row
+    int32_t num_long = 0;
+    int32_t* long_item = nullptr;  // [num_long] items with more than kSerialMax entries, and every piece of a cut segment
     int32_t* part_split = nullptr; // [num_partials] index into split_* of its segment
 };
 
+}  // namespace rgnn
+
+namespace rgnn {
+// Ids of the segments of a CSR-like list that are longer than kSerialMax entries.
+struct LongList {
+    int32_t n = 0;
+    int32_t* ids = nullptr;
+};
 }  // namespace rgnn
 
 struct rgnn_graph {
@@ -94,14 +104,18 @@ struct rgnn_graph {
     rgnn::ItemList dst_items;              // CSR edges by destination
     rgnn::ItemList pair_items;             // transposed edges by pair
     rgnn::ItemList relrun_items;           // runs by relation
+    rgnn::LongList long_runs;              // runs (run_ptr) too long for one lane
+    rgnn::LongList long_pairs;             // pairs (out_ptr) too long for one lane
     std::vector<void*> allocs;             // every device allocation, for destroy
 };
 
 namespace rgnn {
 
 constexpr int kTileRows = 64;       // rows per typed-linear tile
-constexpr int kMaxChunks = 1024;    // persistent workgroups of the typed-linear kernels
+constexpr int kMaxChunks = 4096;    // tile chunks (workgroups) of the typed-linear kernels: several per resident
+                                    // workgroup slot, so the hardware dispatcher evens out the tail
 constexpr int kItemMax = 256;       // longest traversal item (entries)
+constexpr int kSerialMax = 32;      // longest segment a single lane walks; longer ones get a wavefront
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 

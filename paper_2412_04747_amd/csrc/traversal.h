@@ -6,8 +6,8 @@ namespace rgnn {
 
 rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st);
 rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st);
-rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const int32_t* via, const float* val, int stride, int off,
-                                 float* out, hipStream_t st, const char* label);
+rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
+                                 int stride, int off, float* out, hipStream_t st, const char* label);
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
                            float* part_m, float* part_s, hipStream_t st);
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,

@@ -77,28 +77,29 @@ __global__ void run_logit_kernel(int Q, const int32_t* __restrict__ run_dst, con
 }
 
 // out[i] = sum_{j in [ptr[i], ptr[i+1])} val[(via ? via[j] : j) * stride + off].
-// One lane per segment; segments longer than 32 are then summed by the whole wavefront.
+// One lane per segment of at most kSerialMax entries; the longer ones (listed by the graph
+// index) get one wavefront each in a second kernel.
 __global__ void segment_scalar_sum_kernel(int n, const int32_t* __restrict__ ptr, const int32_t* __restrict__ via,
                                           const float* __restrict__ val, int stride, int off, float* __restrict__ out) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    const int lane = threadIdx.x & 63;
-    int b = 0, e = 0;
-    if (i < n) { b = ptr[i]; e = ptr[i + 1]; }
-    const bool coop = (e - b) > 32;
+    if (i >= n) return;
+    const int b = ptr[i], e = ptr[i + 1];
+    if (e - b > kSerialMax) return;
     float s = 0.f;
-    if (!coop)
-        for (int j = b; j < e; ++j) s += val[(size_t)(via ? via[j] : j) * stride + off];
-    unsigned long long mask = __ballot(coop);
-    while (mask) {
-        const int L = __ffsll((long long)mask) - 1;
-        mask &= mask - 1;
-        const int bb = __shfl(b, L), ee = __shfl(e, L);
-        float t = 0.f;
-        for (int j = bb + lane; j < ee; j += 64) t += val[(size_t)(via ? via[j] : j) * stride + off];
-        t = group_sum<64>(t);
-        if (lane == L) s = t;
-    }
-    if (i < n) out[i] = s;
+    for (int j = b; j < e; ++j) s += val[(size_t)(via ? via[j] : j) * stride + off];
+    out[i] = s;
+}
+__global__ void segment_scalar_sum_long_kernel(int n_long, const int32_t* __restrict__ long_ids,
+                                               const int32_t* __restrict__ ptr, const int32_t* __restrict__ via,
+                                               const float* __restrict__ val, int stride, int off,
+                                               float* __restrict__ out) {
+    const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    if (w >= n_long) return;
+    const int i = long_ids[w];
+    float t = 0.f;
+    for (int j = ptr[i] + lane; j < ptr[i + 1]; j += 64) t += val[(size_t)(via ? via[j] : j) * stride + off];
+    t = group_sum<64>(t);
+    if (lane == 0) out[i] = t;
 }
 
 // ------------------------------------------------------------------ edge softmax (RGAT)
@@ -124,51 +125,48 @@ __device__ __forceinline__ float signed_att(float l, float m, float inv) {
     return l > 0.f ? a : -a;
 }
 
-__global__ void edge_softmax_kernel(SoftmaxArgs a) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    const int lane = threadIdx.x & 63;
-    int b = 0, e = 0, slot = -1;
-    if (i < a.it.n) { b = a.it.beg[i]; e = a.it.end[i]; slot = a.it.slot[i]; }
-    const bool coop = (e - b) > 16;
-    if (!coop && e > b) {
-        float m = -INFINITY, s = 0.f;
-        for (int j = b; j < e; ++j) {
-            const float z = a.s_src[a.in_pair[j]] + a.s_dst[a.in_run[j]];
-            const float l = z > 0.f ? z : a.slope * z;
-            a.att[j] = l;
-            m = fmaxf(m, l);
-        }
-        for (int j = b; j < e; ++j) s += expf(a.att[j] - m);
-        if (slot < 0) {
-            const float inv = 1.f / s;
-            for (int j = b; j < e; ++j) a.att[j] = signed_att(a.att[j], m, inv);
-        } else {
-            a.part_m[slot] = m;
-            a.part_s[slot] = s;
-        }
+// Destinations with at most kSerialMax incoming edges: one lane per node, in node order, so
+// that neighbouring lanes walk neighbouring CSR ranges.  Everything else (longer nodes and
+// the pieces of cut nodes) goes through edge_softmax_long_kernel.
+__global__ void edge_softmax_kernel(SoftmaxArgs a, int N, const int32_t* __restrict__ in_ptr) {
+    const int v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= N) return;
+    const int b = in_ptr[v], e = in_ptr[v + 1];
+    if (e == b || e - b > kSerialMax) return;
+    float m = -INFINITY, s = 0.f;
+    for (int j = b; j < e; ++j) {
+        const float z = a.s_src[a.in_pair[j]] + a.s_dst[a.in_run[j]];
+        const float l = z > 0.f ? z : a.slope * z;
+        a.att[j] = l;
+        m = fmaxf(m, l);
     }
-    unsigned long long mask = __ballot(coop);
-    while (mask) {
-        const int L = __ffsll((long long)mask) - 1;
-        mask &= mask - 1;
-        const int bb = __shfl(b, L), ee = __shfl(e, L), sl = __shfl(slot, L);
-        float m = -INFINITY, s = 0.f;
-        for (int j = bb + lane; j < ee; j += 64) {
-            const float z = a.s_src[a.in_pair[j]] + a.s_dst[a.in_run[j]];
-            const float l = z > 0.f ? z : a.slope * z;
-            a.att[j] = l;
-            m = fmaxf(m, l);
-        }
-        m = wave_max(m);
-        for (int j = bb + lane; j < ee; j += 64) s += expf(a.att[j] - m);
-        s = group_sum<64>(s);
-        if (sl < 0) {
-            const float inv = 1.f / s;
-            for (int j = bb + lane; j < ee; j += 64) a.att[j] = signed_att(a.att[j], m, inv);
-        } else if (lane == 0) {
-            a.part_m[sl] = m;
-            a.part_s[sl] = s;
-        }
+    for (int j = b; j < e; ++j) s += expf(a.att[j] - m);
+    const float inv = 1.f / s;
+    for (int j = b; j < e; ++j) a.att[j] = signed_att(a.att[j], m, inv);
+}
+
+// One wavefront per item that is longer than kSerialMax or is a piece of a cut node.
+__global__ void edge_softmax_long_kernel(SoftmaxArgs a, int n_long, const int32_t* __restrict__ long_item) {
+    const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    if (w >= n_long) return;
+    const int i = long_item[w];
+    const int bb = a.it.beg[i], ee = a.it.end[i], sl = a.it.slot[i];
+    float m = -INFINITY, s = 0.f;
+    for (int j = bb + lane; j < ee; j += 64) {
+        const float z = a.s_src[a.in_pair[j]] + a.s_dst[a.in_run[j]];
+        const float l = z > 0.f ? z : a.slope * z;
+        a.att[j] = l;
+        m = fmaxf(m, l);
+    }
+    m = wave_max(m);
+    for (int j = bb + lane; j < ee; j += 64) s += expf(a.att[j] - m);
+    s = group_sum<64>(s);
+    if (sl < 0) {
+        const float inv = 1.f / s;
+        for (int j = bb + lane; j < ee; j += 64) a.att[j] = signed_att(a.att[j], m, inv);
+    } else if (lane == 0) {
+        a.part_m[sl] = m;
+        a.part_s[sl] = s;
     }
 }
 
@@ -252,18 +250,31 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
     *reinterpret_cast<float4*>(o + c4 * 4) = acc0;
 }
 
-// out[split_row[s]] = sum of partial rows [split_ptr[s], split_ptr[s+1]) in order.
+// out[split_row[s]] = sum of partial rows [split_ptr[s], split_ptr[s+1]).  One workgroup per
+// cut segment: group g of D/4 lanes sums partial rows g, g + G, g + 2G, ... (two at a time),
+// then the G group sums are added in group order through LDS, so the summation order is fixed.
 template <int D>
-__global__ void combine_partials_kernel(int num_split, const int32_t* __restrict__ split_row,
-                                        const int32_t* __restrict__ split_ptr, const float* __restrict__ partial,
-                                        float* __restrict__ out) {
-    constexpr int LPR = D / 4;
-    const int s = (blockIdx.x * blockDim.x + threadIdx.x) / LPR, c4 = threadIdx.x % LPR;
-    if (s >= num_split) return;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int p = split_ptr[s]; p < split_ptr[s + 1]; ++p)
-        fma4(acc, 1.f, *reinterpret_cast<const float4*>(partial + (size_t)p * D + c4 * 4));
-    *reinterpret_cast<float4*>(out + (size_t)split_row[s] * D + c4 * 4) = acc;
+__global__ __launch_bounds__(1024) void combine_partials_kernel(const int32_t* __restrict__ split_row,
+                                                                const int32_t* __restrict__ split_ptr,
+                                                                const float* __restrict__ partial,
+                                                                float* __restrict__ out) {
+    constexpr int LPR = D / 4, G = 1024 / LPR;
+    __shared__ float4 red[1024];
+    const int s = blockIdx.x, g = threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+    const int p0 = split_ptr[s], p1 = split_ptr[s + 1];
+    float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
+    for (int p = p0 + g; p < p1; p += 2 * G) {
+        fma4(acc0, 1.f, *reinterpret_cast<const float4*>(partial + (size_t)p * D + c4 * 4));
+        if (p + G < p1) fma4(acc1, 1.f, *reinterpret_cast<const float4*>(partial + (size_t)(p + G) * D + c4 * 4));
+    }
+    fma4(acc0, 1.f, acc1);
+    red[threadIdx.x] = acc0;
+    __syncthreads();
+    if (g == 0) {
+        float4 t = red[c4];
+        for (int k = 1; k < G; ++k) fma4(t, 1.f, red[k * LPR + c4]);
+        *reinterpret_cast<float4*>(out + (size_t)split_row[s] * D + c4 * 4) = t;
+    }
 }
 
 // ------------------------------------------------------------------ backward per-edge dot (RGAT)
@@ -423,13 +434,18 @@ rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float*
     return RGNN_OK;
 }
 
-rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const int32_t* via, const float* val, int stride, int off,
-                                 float* out, hipStream_t st, const char* label) {
+rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
+                                 int stride, int off, float* out, hipStream_t st, const char* label) {
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, label);
     hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ptr, via, val, stride,
                        off, out);
     CHECK_LAUNCH();
+    if (lng.n > 0) {
+        hipLaunchKernelGGL(segment_scalar_sum_long_kernel, dim3(blocks_for((size_t)lng.n * 64, 256)), dim3(256), 0, st,
+                           lng.n, lng.ids, ptr, via, val, stride, off, out);
+        CHECK_LAUNCH();
+    }
     return RGNN_OK;
 }
 
@@ -440,8 +456,14 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
     SoftmaxArgs a{dev_items(L), g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN], s_src, s_dst, slope, att, part_m, part_s};
     {
         KernelTimer kt(st, "edge_softmax");
-        hipLaunchKernelGGL(edge_softmax_kernel, dim3(blocks_for(L.num_items, 256)), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(edge_softmax_kernel, dim3(blocks_for((size_t)g->N, 256)), dim3(256), 0, st, a, (int)g->N,
+                           g->idx[RGNN_IDX_IN_PTR]);
         CHECK_LAUNCH();
+        if (L.num_long > 0) {
+            hipLaunchKernelGGL(edge_softmax_long_kernel, dim3(blocks_for((size_t)L.num_long * 64, 256)), dim3(256), 0, st,
+                               a, L.num_long, L.long_item);
+            CHECK_LAUNCH();
+        }
     }
     if (L.num_partials > 0) {
         KernelTimer kt(st, "edge_softmax.finish");
@@ -465,8 +487,8 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
     }
     if (L.num_split > 0) {
         KernelTimer kt(st, combine_label);
-        DISPATCH_D(D, hipLaunchKernelGGL(combine_partials_kernel<DD>, dim3(blocks_for((size_t)L.num_split * (DD / 4), 256)),
-                                         dim3(256), 0, st, L.num_split, L.split_row, L.split_ptr, partial, out));
+        DISPATCH_D(D, hipLaunchKernelGGL(combine_partials_kernel<DD>, dim3(L.num_split), dim3(1024), 0, st, L.split_row,
+                                         L.split_ptr, partial, out));
         CHECK_LAUNCH();
     }
     return RGNN_OK;

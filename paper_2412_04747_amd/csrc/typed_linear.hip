@@ -36,6 +36,11 @@ struct TileArgs {
 constexpr int TM = kTileRows;
 
 // ---------------------------------------------------------------------------------------
+// Forward.  Software pipeline per workgroup: the rows of tile t+1 are fetched from HBM
+// into registers while tile t is multiplied out of LDS, so the gather latency (index, then
+// row) hides behind the MFMAs and the epilogue.  Two barriers per tile: one after the
+// input tile is written to LDS, one after the accumulators are staged for the coalesced
+// 16-byte row stores.
 template <int KD, int ND>
 __global__ __launch_bounds__(256) void typed_linear_fwd_kernel(TileArgs t, const float* __restrict__ X,
                                                                const int32_t* __restrict__ gather,
@@ -44,33 +49,43 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_kernel(TileArgs t, const
                                                                const float* __restrict__ vec, float* __restrict__ s_out) {
     constexpr int XS = KD + 4, YS = ND + 4;
     constexpr int CB = ND / 32, NBLK = 2 * CB, NBW = (NBLK + 3) / 4;
+    constexpr int LPRI = KD / 4, RPPI = 256 / LPRI, NX = TM / RPPI;   // input rows: lanes per row, rows per pass, passes
+    constexpr int LPRO = ND / 4, RPPO = 256 / LPRO;
     extern __shared__ __align__(16) float smem[];
-    float* Ws = smem;            // [KD][ND]
-    float* Xs = smem + KD * ND;  // [TM][max(XS, YS)], reused to stage the output tile
+    float* Ws = smem;                 // [KD][ND]
+    float* Xs = Ws + KD * ND;         // [TM][XS]
+    float* Ys = Xs + TM * XS;         // [TM][YS]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 31, kh = lane >> 5, rb = wave & 1;
+    const int ci = tid % LPRI, ri = tid / LPRI;
+    const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
+    float4 xr[NX];
+    auto fetch = [&](int ti) {
+        const int row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
+#pragma unroll
+        for (int it = 0; it < NX; ++it) {
+            const int row = row0 + ri + it * RPPI;
+            xr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < row1) {
+                const size_t s = gather ? (size_t)gather[row] : (size_t)row;
+                xr[it] = *reinterpret_cast<const float4*>(X + s * KD + ci * 4);
+            }
+        }
+    };
+    if (t0 < t1) fetch(t0);
     int cur_seg = -1;
-    for (int ti = t.chunk_tile[blockIdx.x]; ti < t.chunk_tile[blockIdx.x + 1]; ++ti) {
+    for (int ti = t0; ti < t1; ++ti) {
         const int seg = t.tile_seg[ti], row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
         if (seg != cur_seg) {
             const float4* Wg = reinterpret_cast<const float4*>(W + (size_t)seg * KD * ND);
             for (int i = tid; i < KD * ND / 4; i += 256) reinterpret_cast<float4*>(Ws)[i] = Wg[i];
             cur_seg = seg;
         }
-        {
-            constexpr int LPR = KD / 4, RPP = 256 / LPR;
-            const int c4 = tid % LPR;
-            for (int r = tid / LPR; r < TM; r += RPP) {
-                const int row = row0 + r;
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (row < row1) {
-                    const size_t s = gather ? (size_t)gather[row] : (size_t)row;
-                    v = *reinterpret_cast<const float4*>(X + s * KD + c4 * 4);
-                }
-                *reinterpret_cast<float4*>(Xs + r * XS + c4 * 4) = v;
-            }
-        }
+#pragma unroll
+        for (int it = 0; it < NX; ++it)
+            *reinterpret_cast<float4*>(Xs + (ri + it * RPPI) * XS + ci * 4) = xr[it];
         __syncthreads();
+        if (ti + 1 < t1) fetch(ti + 1);
         v16f acc[NBW];
 #pragma unroll
         for (int b = 0; b < NBW; ++b)
@@ -90,26 +105,22 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_kernel(TileArgs t, const
                         acc[b] = mfma32(av[i], Ws[(k0 + i) * ND + cb * 32 + m], acc[b]);
                     }
             }
-        }
-        __syncthreads();  // every wave is done reading Xs before it is reused as the output stage
-        if (wave < NBLK) {
 #pragma unroll
             for (int b = 0; b < NBW; ++b) {
                 const int cb = (wave >> 1) + 2 * b;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) Xs[(rb * 32 + acc_row(v, kh)) * YS + cb * 32 + m] = acc[b][v];
+                for (int v = 0; v < 16; ++v) Ys[(rb * 32 + acc_row(v, kh)) * YS + cb * 32 + m] = acc[b][v];
             }
         }
         __syncthreads();
         {
-            constexpr int LPR = ND / 4, RPP = 256 / LPR;
-            const int c4 = tid % LPR;
+            const int c4 = tid % LPRO;
             float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
             if (vec) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + c4 * 4);
-            for (int r = tid / LPR; r < TM; r += RPP) {
+            for (int r = tid / LPRO; r < TM; r += RPPO) {
                 const int row = row0 + r;
                 const bool ok = row < row1;
-                float4 y = *reinterpret_cast<const float4*>(Xs + r * YS + c4 * 4);
+                float4 y = *reinterpret_cast<const float4*>(Ys + r * YS + c4 * 4);
                 if (ok) {
                     const size_t d = (scatter_out && gather) ? (size_t)gather[row] : (size_t)row;
                     float4* yp = reinterpret_cast<float4*>(Y + d * ND + c4 * 4);
@@ -122,12 +133,13 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_kernel(TileArgs t, const
                 if (vec) {
                     float s = y.x * wv.x + y.y * wv.y + y.z * wv.z + y.w * wv.w;
 #pragma unroll
-                    for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o);
+                    for (int o = LPRO / 2; o > 0; o >>= 1) s += __shfl_xor(s, o);
                     if (ok && c4 == 0) s_out[row] = s;
                 }
             }
         }
-        __syncthreads();  // the stage is read out before the next tile overwrites it
+        // no barrier here: the next iteration's writes go to Xs (all MFMA reads of it are
+        // behind the barrier above) and Ys is rewritten only after the next barrier.
     }
 }
 
@@ -304,6 +316,178 @@ __global__ __launch_bounds__(256) void typed_linear_bwd_kernel(TileArgs t, const
     }
 }
 
+// Pipelined variant of the backward tile kernel for feature widths up to 64: the X and dY
+// rows of tile t+1 are fetched into registers while tile t is processed, and dXrow is staged
+// in its own LDS buffer so that two barriers per tile suffice.
+template <int KD, int ND>
+__global__ __launch_bounds__(256) void typed_linear_bwd_pipe_kernel(TileArgs t, const float* __restrict__ X,
+                                                                    const int32_t* __restrict__ gather,
+                                                                    const float* __restrict__ W,
+                                                                    const float* __restrict__ dY, int dy_gathered,
+                                                                    float* __restrict__ dXrow, int scatter_dx,
+                                                                    const float* __restrict__ rowscale,
+                                                                    const float* __restrict__ vec,
+                                                                    float* __restrict__ part) {
+    constexpr int XS = KD + 4, YS = ND + 4, WS = ND + 1;
+    constexpr int KB = KD / 32, NB = ND / 32;
+    constexpr int DBLK = 2 * KB, DBW = (DBLK + 3) / 4;
+    constexpr int WBLK = KB * NB, WBW = (WBLK + 3) / 4;
+    constexpr int AG = 256 / KD;
+    constexpr int SLOT = KD * ND + KD;
+    constexpr int LPRX = KD / 4, RPPX = 256 / LPRX, NXR = TM / RPPX;
+    constexpr int LPRY = ND / 4, RPPY = 256 / LPRY, NYR = TM / RPPY;
+    extern __shared__ __align__(16) float smem[];
+    float* Ws = smem;                 // [KD][WS]
+    float* dYs = Ws + KD * WS;        // [TM][YS]
+    float* Xs = dYs + TM * YS;        // [TM][XS]
+    float* DXs = Xs + TM * XS;        // [TM][XS]  dXrow stage
+    float* dss = DXs + TM * XS;       // [TM]
+    float* red = dss + TM;            // [256]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 31, kh = lane >> 5, rb = wave & 1;
+    const int cx = tid % LPRX, rx = tid / LPRX, cy = tid % LPRY, ry = tid / LPRY;
+    v16f accw[WBW];
+#pragma unroll
+    for (int b = 0; b < WBW; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accw[b][v] = 0.f;
+    float acca = 0.f;
+    const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
+    float4 xr[NXR], yr[NYR];
+    float sr[NYR];
+    float dsr = 0.f;
+    auto fetch = [&](int ti) {
+        const int row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
+#pragma unroll
+        for (int it = 0; it < NXR; ++it) {
+            const int row = row0 + rx + it * RPPX;
+            xr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < row1) {
+                const size_t s = gather ? (size_t)gather[row] : (size_t)row;
+                xr[it] = *reinterpret_cast<const float4*>(X + s * KD + cx * 4);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < NYR; ++it) {
+            const int row = row0 + ry + it * RPPY;
+            yr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            sr[it] = 0.f;
+            if (row < row1) {
+                const size_t s = (dy_gathered && gather) ? (size_t)gather[row] : (size_t)row;
+                yr[it] = *reinterpret_cast<const float4*>(dY + s * ND + cy * 4);
+                if (rowscale) sr[it] = rowscale[row];
+            }
+        }
+        dsr = (rowscale && tid < TM && row0 + tid < row1) ? rowscale[row0 + tid] : 0.f;
+    };
+    if (t0 < t1) fetch(t0);
+    int cur_seg = -1;
+    int slot = t.chunk_slot[blockIdx.x] - 1;
+    for (int ti = t0; ti <= t1; ++ti) {
+        const int seg = (ti < t1) ? t.tile_seg[ti] : -2;
+        if (seg != cur_seg) {
+            if (cur_seg >= 0) {  // flush the finished segment's partial sums
+                float* ps = part + (size_t)slot * SLOT;
+                if (wave < WBLK) {
+#pragma unroll
+                    for (int b = 0; b < WBW; ++b) {
+                        const int blk = wave + 4 * b, kb = blk % KB, nb = blk / KB;
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            ps[(kb * 32 + acc_row(v, kh)) * ND + nb * 32 + m] = accw[b][v];
+                            accw[b][v] = 0.f;
+                        }
+                    }
+                }
+                __syncthreads();   // earlier readers of red are done
+                red[tid] = acca;
+                acca = 0.f;
+                __syncthreads();
+                if (tid < KD) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int g2 = 0; g2 < AG; ++g2) s += red[g2 * KD + tid];
+                    ps[KD * ND + tid] = s;
+                }
+            }
+            if (ti == t1) break;
+            ++slot;
+            // every wave is past the previous tile's second barrier, so Ws is free
+            const float* Wg = W + (size_t)seg * KD * ND;
+            for (int i = tid; i < KD * ND; i += 256) Ws[(i / ND) * WS + (i % ND)] = Wg[i];
+            cur_seg = seg;
+        }
+        const int row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
+        {
+            float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (vec && rowscale) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + cy * 4);
+#pragma unroll
+            for (int it = 0; it < NXR; ++it)
+                *reinterpret_cast<float4*>(Xs + (rx + it * RPPX) * XS + cx * 4) = xr[it];
+#pragma unroll
+            for (int it = 0; it < NYR; ++it) {
+                float4 v = yr[it];
+                v.x += sr[it] * wv.x; v.y += sr[it] * wv.y; v.z += sr[it] * wv.z; v.w += sr[it] * wv.w;
+                *reinterpret_cast<float4*>(dYs + (ry + it * RPPY) * YS + cy * 4) = v;
+            }
+            if (tid < TM) dss[tid] = dsr;
+        }
+        __syncthreads();
+        if (ti + 1 < t1) fetch(ti + 1);
+        v16f accx[DBW];
+#pragma unroll
+        for (int b = 0; b < DBW; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) accx[b][v] = 0.f;
+        if (wave < DBLK) {
+#pragma unroll 2
+            for (int tt = 0; tt < ND / 8; ++tt) {
+                const int n0 = kh * (ND / 2) + 4 * tt;
+                const float4 a4 = *reinterpret_cast<const float4*>(dYs + (rb * 32 + m) * YS + n0);
+                const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int b = 0; b < DBW; ++b) {
+                        const int cb = (wave >> 1) + 2 * b;
+                        accx[b] = mfma32(av[i], Ws[(cb * 32 + m) * WS + n0 + i], accx[b]);
+                    }
+            }
+#pragma unroll
+            for (int b = 0; b < DBW; ++b) {
+                const int cb = (wave >> 1) + 2 * b;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) DXs[(rb * 32 + acc_row(v, kh)) * XS + cb * 32 + m] = accx[b][v];
+            }
+        }
+        if (wave < WBLK) {
+#pragma unroll 4
+            for (int s = 0; s < TM / 2; ++s) {
+                const int r = 2 * s + kh;
+#pragma unroll
+                for (int b = 0; b < WBW; ++b) {
+                    const int blk = wave + 4 * b, kb = blk % KB, nb = blk / KB;
+                    accw[b] = mfma32(Xs[r * XS + kb * 32 + m], dYs[r * YS + nb * 32 + m], accw[b]);
+                }
+            }
+        }
+        if (rowscale) {
+            const int k = tid % KD;
+            for (int r = tid / KD; r < TM; r += AG) acca += dss[r] * Xs[r * XS + k];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < NXR; ++it) {
+            const int r = rx + it * RPPX, row = row0 + r;
+            if (row < row1) {
+                const size_t d = (scatter_dx && gather) ? (size_t)gather[row] : (size_t)row;
+                *reinterpret_cast<float4*>(dXrow + d * KD + cx * 4) =
+                    *reinterpret_cast<const float4*>(DXs + r * XS + cx * 4);
+            }
+        }
+    }
+}
+
 // dW[s] (and Avec[s]) = sum of the partial slots of segment s, in slot order.
 __global__ void slot_reduce_kernel(const float* __restrict__ part, const int32_t* __restrict__ seg_slot_ptr,
                                    int kn, int kd, float* __restrict__ dW, float* __restrict__ Avec) {
@@ -324,8 +508,7 @@ static TileArgs tile_args(const TileList& t) {
 
 template <int KD, int ND>
 static rgnn_status_t launch_fwd(const TypedLinearArgs& a, hipStream_t st) {
-    constexpr int STG = (KD > ND ? KD : ND) + 4;
-    const size_t lds = sizeof(float) * (KD * ND + TM * STG);
+    const size_t lds = sizeof(float) * (KD * ND + TM * (KD + 4) + TM * (ND + 4));
     auto kern = typed_linear_fwd_kernel<KD, ND>;
     RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
@@ -350,8 +533,10 @@ size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t) {
 template <int KD, int ND>
 static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
     constexpr int STG = (KD > ND ? KD : ND) + 4;
-    const size_t lds = sizeof(float) * (KD * (ND + 1) + TM * STG + TM * (KD + 4) + TM + 256);
-    auto kern = typed_linear_bwd_kernel<KD, ND>;
+    constexpr bool PIPE = (KD <= 64 && ND <= 64);
+    const size_t lds = PIPE ? sizeof(float) * (KD * (ND + 1) + TM * (ND + 4) + 2 * TM * (KD + 4) + TM + 256)
+                            : sizeof(float) * (KD * (ND + 1) + TM * STG + TM * (KD + 4) + TM + 256);
+    auto kern = PIPE ? typed_linear_bwd_pipe_kernel<KD, ND> : typed_linear_bwd_kernel<KD, ND>;
     if (a.tiles->num_tiles > 0) {
         RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
