@@ -42,7 +42,7 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
 struct RgatSaved { float* Hs; float* att; };
 struct RgatFwdWs { float* wtp; float* s_src; float* s_dst; float* part_m; float* part_s; float* partial; };
 struct RgatBwdWs {
-    float* wtp; float* adz; float* ds_dst; float* ds_src; float* G; float* dXp; float* A; float* U;
+    float* wtp; float* wsp; float* adz; float* ds_dst; float* ds_src; float* G; float* dXp; float* A; float* U;
     float* tl_part; float* partial;
 };
 
@@ -65,6 +65,7 @@ size_t carve_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
 size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatBwdWs* w) {
     Carver c(base);
     w->wtp = c.take<float>((size_t)g->R * d->d_in);
+    w->wsp = c.take<float>((size_t)g->R * d->d_in);
     w->adz = c.take<float>((size_t)g->E * 2);
     w->ds_dst = c.take<float>((size_t)g->Q);
     w->ds_src = c.take<float>((size_t)g->P);
@@ -146,7 +147,7 @@ extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     // 2. out[v] = sum_e (1/c) Hs[pair_e]
     const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, coef, 1, 0, w.Hs,
-                        static_cast<float*>(out), w.partial, st, "aggregate_fwd", "aggregate_fwd.combine"));
+                        static_cast<float*>(out), w.partial, st, 0, "aggregate_fwd", "aggregate_fwd.combine"));
     // 3. self-loop: out += X W0
     if (W0) {
         TypedLinearArgs s{};
@@ -180,7 +181,7 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     // 1. dHs[p] = sum_{e in out(p)} (1/c_e) dPre[dst_e]
     const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
     RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, coef, 1, 0, dPre, w.G,
-                        w.partial, st, "aggregate_bwd_pair", "aggregate_bwd_pair.combine"));
+                        w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine"));
     // 2. per pair dXp = dHs W^T; dW[r] = sum X^T dHs
     TypedLinearBwdArgs b{};
     b.tiles = &g->pair_tiles; b.X = static_cast<const float*>(X); b.gather = g->idx[RGNN_IDX_PAIR_SRC];
@@ -224,7 +225,7 @@ extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     RGNN_TRY(edge_softmax(g, w.s_src, w.s_dst, desc->slope, sv.att, w.part_m, w.part_s, st));
     // 4. out[v] = sum_e att_e Hs[pair_e]
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, 1, 1, sv.Hs,
-                        static_cast<float*>(out), w.partial, st, "aggregate_fwd", "aggregate_fwd.combine"));
+                        static_cast<float*>(out), w.partial, st, 0, "aggregate_fwd", "aggregate_fwd.combine"));
     return RGNN_OK;
 }
 
@@ -251,19 +252,22 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2, 1, w.ds_src, st, "ds_src_sum"));
     // 3. G[p] = sum_{e in out(p)} att_e dOut[dst_e]
     RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.adz, 2, 0, dO, w.G,
-                        w.partial, st, "aggregate_bwd_pair", "aggregate_bwd_pair.combine"));
-    // 4. dHs[p] = G[p] + ds_src[p] w_s[r];  dXp[p] = dHs[p] W[r]^T;  dW[r] = sum X^T dHs;  A[r] = sum ds_src X
+                        w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine"));
+    // 4. with dHs[p] = G[p] + ds_src[p] w_s[r]:
+    //    dXp[p] = dHs[p] W[r]^T = G[p] W[r]^T + ds_src[p] (W[r] w_s[r]);  dW[r] = sum X^T G (+ A^T (x) w_s in step 6);
+    //    A[r] = sum ds_src X
+    RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_s), w.wsp, st));
     TypedLinearBwdArgs b{};
     b.tiles = &g->pair_tiles; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
-    b.rowscale = w.ds_src; b.vec = static_cast<const float*>(w_s); b.dW = static_cast<float*>(dW); b.Avec = w.A;
+    b.rowscale = w.ds_src; b.vec = w.wsp; b.dW = static_cast<float*>(dW); b.Avec = w.A;
     b.part = w.tl_part;
     RGNN_TRY(typed_linear_bwd(K, D, b, st));
     // 5. U[r] = sum over r's runs of ds_dst[q] X[run_dst[q]]
     RGNN_TRY(gather_sum(g->relrun_items, K, g->idx[RGNN_IDX_RELRUN_IDX], g->idx[RGNN_IDX_RUN_DST], 1, w.ds_dst, 1, 0, Xf,
-                        w.U, w.partial, st, "dst_side_wgrad", "dst_side_wgrad.combine"));
-    // 6. dw_s = A W, dw_t = U W, dW += U^T (x) w_t
-    RGNN_TRY(rgat_param_finish(g->R, K, D, Wf, static_cast<const float*>(w_t), w.A, w.U, static_cast<float*>(dW),
-                               static_cast<float*>(dw_s), static_cast<float*>(dw_t), st));
+                        w.U, w.partial, st, 2, "dst_side_wgrad", "dst_side_wgrad.combine"));
+    // 6. dw_s = A W, dw_t = U W, dW += A^T (x) w_s + U^T (x) w_t
+    RGNN_TRY(rgat_param_finish(g->R, K, D, Wf, static_cast<const float*>(w_s), static_cast<const float*>(w_t), w.A, w.U,
+                               static_cast<float*>(dW), static_cast<float*>(dw_s), static_cast<float*>(dw_t), st));
     // 7. dX[u] = sum over u's pairs of dXp + sum over u's runs of ds_dst[q] (W[r] w_t[r])
     RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_t), w.wtp, st));
     RGNN_TRY(node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, nullptr, static_cast<float*>(dX), st));

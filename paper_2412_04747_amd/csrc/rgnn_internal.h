@@ -144,7 +144,7 @@ struct TypedLinearBwdArgs {
     float* dXrow;            // [rows][KD] per-row input gradient dY_i W^T (row i, or gather[i] if scatter_dx)
     int scatter_dx;
     const float* rowscale;   // optional [rows]: A[seg] = sum_i rowscale[i] X_row_i
-    const float* vec;        // optional [segs][ND] (with rowscale): dY_eff[i] = dY[i] + rowscale[i] * vec[seg]
+    const float* vec;        // optional [segs][KD] (with rowscale): dXrow[i] += rowscale[i] * vec[seg]
     float* dW;               // [segs][KD][ND]
     float* Avec;             // [segs][KD] (with rowscale)
     float* part;             // scratch [num_slots][KD*ND + KD]

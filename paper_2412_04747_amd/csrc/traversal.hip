@@ -213,7 +213,9 @@ struct GatherArgs {
     float* partial;
 };
 
-template <int D>
+// ROLE only gives each use its own kernel name in profiler output (0 forward aggregation over
+// destinations, 1 backward aggregation over pairs, 2 destination-side weight gradient).
+template <int D, int ROLE>
 __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
     constexpr int LPR = D / 4, IPB = 256 / LPR;
     const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
@@ -369,11 +371,12 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
 
 // ------------------------------------------------------------------ RGAT parameter-gradient epilogue
 
-// Per relation r:  dw_s[r] = A[r] W[r];  dw_t[r] = U[r] W[r];  dW[r] += U[r]^T (x) w_t[r]
+// Per relation r:  dw_s[r] = A[r] W[r];  dw_t[r] = U[r] W[r];  dW[r] += A[r]^T (x) w_s[r] + U[r]^T (x) w_t[r]
 // where A[r] = sum_p ds_src[p] X[src_p] and U[r] = sum_q ds_dst[q] X[dst_q].
-__global__ void rgat_param_finish_kernel(int kd, int nd, const float* __restrict__ W, const float* __restrict__ w_t,
-                                         const float* __restrict__ A, const float* __restrict__ U,
-                                         float* __restrict__ dW, float* __restrict__ dw_s, float* __restrict__ dw_t) {
+__global__ void rgat_param_finish_kernel(int kd, int nd, const float* __restrict__ W, const float* __restrict__ w_s,
+                                         const float* __restrict__ w_t, const float* __restrict__ A,
+                                         const float* __restrict__ U, float* __restrict__ dW,
+                                         float* __restrict__ dw_s, float* __restrict__ dw_t) {
     const int r = blockIdx.x;
     const float* Wr = W + (size_t)r * kd * nd;
     const float* Ar = A + (size_t)r * kd;
@@ -388,7 +391,8 @@ __global__ void rgat_param_finish_kernel(int kd, int nd, const float* __restrict
         dw_t[(size_t)r * nd + n] = t;
     }
     for (int i = threadIdx.x; i < kd * nd; i += blockDim.x)
-        dW[(size_t)r * kd * nd + i] += Ur[i / nd] * w_t[(size_t)r * nd + i % nd];
+        dW[(size_t)r * kd * nd + i] +=
+            Ar[i / nd] * w_s[(size_t)r * nd + i % nd] + Ur[i / nd] * w_t[(size_t)r * nd + i % nd];
 }
 
 // ------------------------------------------------------------------ elementwise
@@ -476,13 +480,15 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
 
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
                          const float* coef, int cstride, int cabs, const float* src, float* out, float* partial,
-                         hipStream_t st, const char* label, const char* combine_label) {
+                         hipStream_t st, int role, const char* label, const char* combine_label) {
     if (L.num_items == 0) return RGNN_OK;
     GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, src, out, partial};
     {
         KernelTimer kt(st, label);
-        DISPATCH_D(D, hipLaunchKernelGGL(gather_sum_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
-                                         0, st, a));
+        const dim3 grid(blocks_for(L.num_items, 256 / (D / 4)));
+        if (role == 0) DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 0>), grid, dim3(256), 0, st, a));
+        else if (role == 1) DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 1>), grid, dim3(256), 0, st, a));
+        else DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 2>), grid, dim3(256), 0, st, a));
         CHECK_LAUNCH();
     }
     if (L.num_split > 0) {
@@ -518,10 +524,10 @@ rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const float* dXp, const 
     return RGNN_OK;
 }
 
-rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const float* w_t, const float* A,
-                                const float* U, float* dW, float* dw_s, float* dw_t, hipStream_t st) {
+rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const float* w_s, const float* w_t,
+                                const float* A, const float* U, float* dW, float* dw_s, float* dw_t, hipStream_t st) {
     KernelTimer kt(st, "rgat_param_finish");
-    hipLaunchKernelGGL(rgat_param_finish_kernel, dim3(R), dim3(256), 0, st, kd, nd, W, w_t, A, U, dW, dw_s, dw_t);
+    hipLaunchKernelGGL(rgat_param_finish_kernel, dim3(R), dim3(256), 0, st, kd, nd, W, w_s, w_t, A, U, dW, dw_s, dw_t);
     CHECK_LAUNCH();
     return RGNN_OK;
 }

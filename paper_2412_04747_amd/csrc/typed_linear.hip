@@ -60,19 +60,24 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_kernel(TileArgs t, const
     const int ci = tid % LPRI, ri = tid / LPRI;
     const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
     float4 xr[NX];
-    auto fetch = [&](int ti) {
+    int gi[NX];   // source rows of the tile after the one held in xr (-1: past the segment end)
+    auto fetch_idx = [&](int ti) {
         const int row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
 #pragma unroll
         for (int it = 0; it < NX; ++it) {
             const int row = row0 + ri + it * RPPI;
-            xr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < row1) {
-                const size_t s = gather ? (size_t)gather[row] : (size_t)row;
-                xr[it] = *reinterpret_cast<const float4*>(X + s * KD + ci * 4);
-            }
+            gi[it] = row < row1 ? (gather ? gather[row] : row) : -1;
         }
     };
-    if (t0 < t1) fetch(t0);
+    auto fetch_rows = [&]() {
+#pragma unroll
+        for (int it = 0; it < NX; ++it) {
+            xr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gi[it] >= 0) xr[it] = *reinterpret_cast<const float4*>(X + (size_t)gi[it] * KD + ci * 4);
+        }
+    };
+    if (t0 < t1) { fetch_idx(t0); fetch_rows(); }
+    if (t0 + 1 < t1) fetch_idx(t0 + 1);
     int cur_seg = -1;
     for (int ti = t0; ti < t1; ++ti) {
         const int seg = t.tile_seg[ti], row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
@@ -85,7 +90,8 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_kernel(TileArgs t, const
         for (int it = 0; it < NX; ++it)
             *reinterpret_cast<float4*>(Xs + (ri + it * RPPI) * XS + ci * 4) = xr[it];
         __syncthreads();
-        if (ti + 1 < t1) fetch(ti + 1);
+        if (ti + 1 < t1) fetch_rows();      // rows of tile ti+1; their indices were requested a tile earlier
+        if (ti + 2 < t1) fetch_idx(ti + 2);
         v16f acc[NBW];
 #pragma unroll
         for (int b = 0; b < NBW; ++b)
@@ -144,11 +150,13 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_kernel(TileArgs t, const
 }
 
 // ---------------------------------------------------------------------------------------
-// Backward tile: dY_eff[i] = dY[i] + rowscale[i] * vec[seg]   (the rank-1 term lets the caller
-// fold d(row . vec)/d row into the same pass), then
-//   dXrow[i]  = dY_eff[i] W^T                      (MFMA, contraction over the output features)
-//   dW[seg]  += X_tile^T dY_eff                    (MFMA, contraction over the tile's rows)
-//   Avec[seg]+= sum_i rowscale[i] X_tile[i]        (vector ALU)
+// Backward tile:
+//   dXrow[i]  = dY[i] W^T + rowscale[i] * xvec[seg]   (MFMA, contraction over the output features;
+//                                                     the rank-1 term is added when the row is stored)
+//   dW[seg]  += X_tile^T dY                           (MFMA, contraction over the tile's rows)
+//   Avec[seg]+= sum_i rowscale[i] X_tile[i]           (vector ALU)
+// With dY_eff = dY + rowscale (x) v, xvec = W v gives dXrow = dY_eff W^T exactly, and the caller
+// completes dW = X^T dY_eff by adding Avec^T (x) v.
 // dW and Avec stay in registers while consecutive tiles share a segment and are flushed to
 // the chunk's partial slot when the segment changes; a second kernel sums the slots of each
 // segment in slot order, so the result does not depend on scheduling.
@@ -236,18 +244,12 @@ __global__ __launch_bounds__(256) void typed_linear_bwd_kernel(TileArgs t, const
         {
             constexpr int LPR = ND / 4, RPP = 256 / LPR;
             const int c4 = tid % LPR;
-            float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (vec) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + c4 * 4);
             for (int r = tid / LPR; r < TM; r += RPP) {
                 const int row = row0 + r;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (row < row1) {
                     const size_t s = (dy_gathered && gather) ? (size_t)gather[row] : (size_t)row;
                     v = *reinterpret_cast<const float4*>(dY + s * ND + c4 * 4);
-                    if (rowscale && vec) {
-                        const float sc = rowscale[row];
-                        v.x += sc * wv.x; v.y += sc * wv.y; v.z += sc * wv.z; v.w += sc * wv.w;
-                    }
                 }
                 *reinterpret_cast<float4*>(dYs + r * STG + c4 * 4) = v;
             }
@@ -303,12 +305,16 @@ __global__ __launch_bounds__(256) void typed_linear_bwd_kernel(TileArgs t, const
         {
             constexpr int LPR = KD / 4, RPP = 256 / LPR;
             const int c4 = tid % LPR;
+            float4 xv = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (rowscale && vec) xv = *reinterpret_cast<const float4*>(vec + (size_t)seg * KD + c4 * 4);
             for (int r = tid / LPR; r < TM; r += RPP) {
                 const int row = row0 + r;
                 if (row < row1) {
                     const size_t d = (scatter_dx && gather) ? (size_t)gather[row] : (size_t)row;
-                    *reinterpret_cast<float4*>(dXrow + d * KD + c4 * 4) =
-                        *reinterpret_cast<const float4*>(dYs + r * STG + c4 * 4);
+                    float4 o = *reinterpret_cast<const float4*>(dYs + r * STG + c4 * 4);
+                    const float sc = dss[r];
+                    o.x += sc * xv.x; o.y += sc * xv.y; o.z += sc * xv.z; o.w += sc * xv.w;
+                    *reinterpret_cast<float4*>(dXrow + d * KD + c4 * 4) = o;
                 }
             }
         }
@@ -316,11 +322,148 @@ __global__ __launch_bounds__(256) void typed_linear_bwd_kernel(TileArgs t, const
     }
 }
 
-// Pipelined variant of the backward tile kernel for feature widths up to 64: the X and dY
-// rows of tile t+1 are fetched into registers while tile t is processed, and dXrow is staged
-// in its own LDS buffer so that two barriers per tile suffice.
+// ---------------------------------------------------------------------------------------
+// Wave-independent kernels (feature widths up to 64).
+//
+// Within a run of tiles that share a segment, the wavefronts of a workgroup do not
+// synchronise with each other: wavefront w owns the 32-row units w, w + NW, ... of the run,
+// stages them in its private LDS region and keeps the rows of its next unit in flight in
+// registers (the gather indices one unit further ahead).  Workgroup barriers are needed only
+// when the segment changes (reload of the shared weight tile, flush of the weight-gradient
+// partial sums).  This keeps 8 KB (forward) / 16 KB (backward) of HBM reads in flight per
+// wavefront at all times, which is what the random row gather needs.
+//
+// LDS accesses of one wavefront are executed in issue order, so inside a wavefront a store
+// followed by a load of another lane's data needs no barrier; wave_lds_fence() only stops
+// the compiler from moving LDS accesses across it and waits for outstanding LDS operations.
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// First tile index >= ti whose segment differs from tile ti's (or t1).
+__device__ __forceinline__ int run_end(const int32_t* __restrict__ tile_seg, int ti, int t1) {
+    const int seg = tile_seg[ti];
+    int e = ti + 1;
+    while (e < t1 && tile_seg[e] == seg) ++e;
+    return e;
+}
+
 template <int KD, int ND>
-__global__ __launch_bounds__(256) void typed_linear_bwd_pipe_kernel(TileArgs t, const float* __restrict__ X,
+__global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, const float* __restrict__ X,
+                                                                    const int32_t* __restrict__ gather,
+                                                                    const float* __restrict__ W, float* __restrict__ Y,
+                                                                    int scatter_out, int accumulate,
+                                                                    const float* __restrict__ vec,
+                                                                    float* __restrict__ s_out) {
+    constexpr int NW = 4;                                   // wavefronts per workgroup
+    constexpr int XS = (KD > ND ? KD : ND) + 4;             // row stride of the per-wave stage
+    constexpr int CB = ND / 32;
+    constexpr int LPRI = KD / 4, RPI = 64 / LPRI, NX = 32 / RPI;   // input: lanes per row, rows per load, loads per unit
+    constexpr int LPRO = ND / 4, RPO = 64 / LPRO, NO = 32 / RPO;
+    extern __shared__ __align__(16) float smem[];
+    float* Ws = smem;                                       // [KD][ND]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float* Xw = smem + KD * ND + wave * 32 * XS;            // [32][XS] private to this wavefront
+    const int m = lane & 31, kh = lane >> 5;
+    const int ci = lane % LPRI, ri = lane / LPRI, co = lane % LPRO, ro = lane / LPRO;
+    const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
+    for (int ta = t0; ta < t1;) {
+        const int tb = run_end(t.tile_seg, ta, t1);
+        const int seg = t.tile_seg[ta];
+        const int ra = t.tile_row0[ta], rbnd = t.tile_row1[tb - 1];   // rows [ra, rbnd) of this segment
+        const int nu = (rbnd - ra + 31) / 32;
+        __syncthreads();                                    // every wavefront is done with the previous weight
+        {
+            const float4* Wg = reinterpret_cast<const float4*>(W + (size_t)seg * KD * ND);
+            for (int i = tid; i < KD * ND / 4; i += 64 * NW) reinterpret_cast<float4*>(Ws)[i] = Wg[i];
+        }
+        __syncthreads();
+        float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (vec) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + co * 4);
+        float4 xr[NX];
+        int gi[NX];
+        auto fetch_idx = [&](int u) {
+#pragma unroll
+            for (int it = 0; it < NX; ++it) {
+                const int row = ra + u * 32 + ri + it * RPI;
+                gi[it] = (u < nu && row < rbnd) ? (gather ? gather[row] : row) : -1;
+            }
+        };
+        auto fetch_rows = [&]() {
+#pragma unroll
+            for (int it = 0; it < NX; ++it) {
+                xr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (gi[it] >= 0) xr[it] = *reinterpret_cast<const float4*>(X + (size_t)gi[it] * KD + ci * 4);
+            }
+        };
+        fetch_idx(wave);
+        fetch_rows();
+        fetch_idx(wave + NW);
+        for (int u = wave; u < nu; u += NW) {
+#pragma unroll
+            for (int it = 0; it < NX; ++it)
+                *reinterpret_cast<float4*>(Xw + (ri + it * RPI) * XS + ci * 4) = xr[it];
+            wave_lds_fence();
+            fetch_rows();                 // unit u + NW (all-zero past the end)
+            fetch_idx(u + 2 * NW);
+            v16f acc[CB];
+#pragma unroll
+            for (int b = 0; b < CB; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+#pragma unroll 2
+            for (int tt = 0; tt < KD / 8; ++tt) {
+                const int k0 = kh * (KD / 2) + 4 * tt;
+                const float4 a4 = *reinterpret_cast<const float4*>(Xw + m * XS + k0);
+                const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int b = 0; b < CB; ++b) acc[b] = mfma32(av[i], Ws[(k0 + i) * ND + b * 32 + m], acc[b]);
+            }
+            wave_lds_fence();             // all reads of the input rows are done before the stage is overwritten
+#pragma unroll
+            for (int b = 0; b < CB; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) Xw[acc_row(v, kh) * XS + b * 32 + m] = acc[b][v];
+            wave_lds_fence();
+#pragma unroll
+            for (int it = 0; it < NO; ++it) {
+                const int r = ro + it * RPO, row = ra + u * 32 + r;
+                const bool ok = row < rbnd;
+                float4 y = *reinterpret_cast<const float4*>(Xw + r * XS + co * 4);
+                if (ok) {
+                    const size_t d = (scatter_out && gather) ? (size_t)gather[row] : (size_t)row;
+                    float4* yp = reinterpret_cast<float4*>(Y + d * ND + co * 4);
+                    if (accumulate) {
+                        const float4 o = *yp;
+                        y.x += o.x; y.y += o.y; y.z += o.z; y.w += o.w;
+                    }
+                    *yp = y;
+                }
+                if (vec) {
+                    float sdot = y.x * wv.x + y.y * wv.y + y.z * wv.z + y.w * wv.w;
+#pragma unroll
+                    for (int o = LPRO / 2; o > 0; o >>= 1) sdot += __shfl_xor(sdot, o);
+                    if (ok && co == 0) s_out[row] = sdot;
+                }
+            }
+            wave_lds_fence();             // the stage is read out before the next unit's rows overwrite it
+        }
+        ta = tb;
+    }
+}
+
+// Backward, wave-independent: eight wavefronts per workgroup, each owning 32-row units of
+// the run.  Per unit a wavefront forms dXrow = dY_eff W^T (two 32x32 blocks) and adds its
+// rows' contribution to the full KD x ND weight gradient (KB*NB blocks, kept in registers
+// for the whole run) and to Avec.  At the end of a run the eight wavefronts' partial weight
+// gradients are summed in wavefront order through LDS and written to the chunk's slot.
+template <int KD, int ND>
+__global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, const float* __restrict__ X,
                                                                     const int32_t* __restrict__ gather,
                                                                     const float* __restrict__ W,
                                                                     const float* __restrict__ dY, int dy_gathered,
@@ -328,163 +471,162 @@ __global__ __launch_bounds__(256) void typed_linear_bwd_pipe_kernel(TileArgs t, 
                                                                     const float* __restrict__ rowscale,
                                                                     const float* __restrict__ vec,
                                                                     float* __restrict__ part) {
-    constexpr int XS = KD + 4, YS = ND + 4, WS = ND + 1;
-    constexpr int KB = KD / 32, NB = ND / 32;
-    constexpr int DBLK = 2 * KB, DBW = (DBLK + 3) / 4;
-    constexpr int WBLK = KB * NB, WBW = (WBLK + 3) / 4;
-    constexpr int AG = 256 / KD;
+    constexpr int NW = 8;
+    constexpr int XS = KD + 4, YS = (ND > KD ? ND : KD) + 4, WS = ND + 1;
+    constexpr int KB = KD / 32, NB = ND / 32, WB = KB * NB;
     constexpr int SLOT = KD * ND + KD;
-    constexpr int LPRX = KD / 4, RPPX = 256 / LPRX, NXR = TM / RPPX;
-    constexpr int LPRY = ND / 4, RPPY = 256 / LPRY, NYR = TM / RPPY;
+    constexpr int LPRX = KD / 4, RPX = 64 / LPRX, NXR = 32 / RPX;
+    constexpr int LPRY = ND / 4, RPY = 64 / LPRY, NYR = 32 / RPY;
+    constexpr int WREG = 32 * XS + 32 * YS + 32;            // floats of LDS per wavefront
     extern __shared__ __align__(16) float smem[];
-    float* Ws = smem;                 // [KD][WS]
-    float* dYs = Ws + KD * WS;        // [TM][YS]
-    float* Xs = dYs + TM * YS;        // [TM][XS]
-    float* DXs = Xs + TM * XS;        // [TM][XS]  dXrow stage
-    float* dss = DXs + TM * XS;       // [TM]
-    float* red = dss + TM;            // [256]
+    float* Ws = smem;                                       // [KD][WS]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m = lane & 31, kh = lane >> 5, rb = wave & 1;
-    const int cx = tid % LPRX, rx = tid / LPRX, cy = tid % LPRY, ry = tid / LPRY;
-    v16f accw[WBW];
-#pragma unroll
-    for (int b = 0; b < WBW; ++b)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) accw[b][v] = 0.f;
-    float acca = 0.f;
+    float* Xw = smem + KD * WS + wave * WREG;               // [32][XS]  gathered input rows
+    float* Yw = Xw + 32 * XS;                               // [32][YS]  dY_eff rows, then the dXrow stage
+    float* dsw = Yw + 32 * YS;                              // [32]      rowscale of the unit's rows
+    const int m = lane & 31, kh = lane >> 5;
+    const int cx = lane % LPRX, rx = lane / LPRX, cy = lane % LPRY, ry = lane / LPRY;
     const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
-    float4 xr[NXR], yr[NYR];
-    float sr[NYR];
-    float dsr = 0.f;
-    auto fetch = [&](int ti) {
-        const int row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
-#pragma unroll
-        for (int it = 0; it < NXR; ++it) {
-            const int row = row0 + rx + it * RPPX;
-            xr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < row1) {
-                const size_t s = gather ? (size_t)gather[row] : (size_t)row;
-                xr[it] = *reinterpret_cast<const float4*>(X + s * KD + cx * 4);
-            }
-        }
-#pragma unroll
-        for (int it = 0; it < NYR; ++it) {
-            const int row = row0 + ry + it * RPPY;
-            yr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            sr[it] = 0.f;
-            if (row < row1) {
-                const size_t s = (dy_gathered && gather) ? (size_t)gather[row] : (size_t)row;
-                yr[it] = *reinterpret_cast<const float4*>(dY + s * ND + cy * 4);
-                if (rowscale) sr[it] = rowscale[row];
-            }
-        }
-        dsr = (rowscale && tid < TM && row0 + tid < row1) ? rowscale[row0 + tid] : 0.f;
-    };
-    if (t0 < t1) fetch(t0);
-    int cur_seg = -1;
-    int slot = t.chunk_slot[blockIdx.x] - 1;
-    for (int ti = t0; ti <= t1; ++ti) {
-        const int seg = (ti < t1) ? t.tile_seg[ti] : -2;
-        if (seg != cur_seg) {
-            if (cur_seg >= 0) {  // flush the finished segment's partial sums
-                float* ps = part + (size_t)slot * SLOT;
-                if (wave < WBLK) {
-#pragma unroll
-                    for (int b = 0; b < WBW; ++b) {
-                        const int blk = wave + 4 * b, kb = blk % KB, nb = blk / KB;
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            ps[(kb * 32 + acc_row(v, kh)) * ND + nb * 32 + m] = accw[b][v];
-                            accw[b][v] = 0.f;
-                        }
-                    }
-                }
-                __syncthreads();   // earlier readers of red are done
-                red[tid] = acca;
-                acca = 0.f;
-                __syncthreads();
-                if (tid < KD) {
-                    float s = 0.f;
-#pragma unroll
-                    for (int g2 = 0; g2 < AG; ++g2) s += red[g2 * KD + tid];
-                    ps[KD * ND + tid] = s;
-                }
-            }
-            if (ti == t1) break;
-            ++slot;
-            // every wave is past the previous tile's second barrier, so Ws is free
-            const float* Wg = W + (size_t)seg * KD * ND;
-            for (int i = tid; i < KD * ND; i += 256) Ws[(i / ND) * WS + (i % ND)] = Wg[i];
-            cur_seg = seg;
-        }
-        const int row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
+    int slot = t.chunk_slot[blockIdx.x];
+    for (int ta = t0; ta < t1; ++slot) {
+        const int tb = run_end(t.tile_seg, ta, t1);
+        const int seg = t.tile_seg[ta];
+        const int ra = t.tile_row0[ta], rbnd = t.tile_row1[tb - 1];
+        const int nu = (rbnd - ra + 31) / 32;
+        __syncthreads();                                    // previous run's flush has read the LDS regions
         {
-            float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (vec && rowscale) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + cy * 4);
-#pragma unroll
-            for (int it = 0; it < NXR; ++it)
-                *reinterpret_cast<float4*>(Xs + (rx + it * RPPX) * XS + cx * 4) = xr[it];
-#pragma unroll
-            for (int it = 0; it < NYR; ++it) {
-                float4 v = yr[it];
-                v.x += sr[it] * wv.x; v.y += sr[it] * wv.y; v.z += sr[it] * wv.z; v.w += sr[it] * wv.w;
-                *reinterpret_cast<float4*>(dYs + (ry + it * RPPY) * YS + cy * 4) = v;
-            }
-            if (tid < TM) dss[tid] = dsr;
+            const float* Wg = W + (size_t)seg * KD * ND;
+            for (int i = tid; i < KD * ND; i += 64 * NW) Ws[(i / ND) * WS + (i % ND)] = Wg[i];
         }
         __syncthreads();
-        if (ti + 1 < t1) fetch(ti + 1);
-        v16f accx[DBW];
+        float4 xv = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (vec && rowscale) xv = *reinterpret_cast<const float4*>(vec + (size_t)seg * KD + cx * 4);
+        v16f accw[WB];
 #pragma unroll
-        for (int b = 0; b < DBW; ++b)
+        for (int b = 0; b < WB; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) accx[b][v] = 0.f;
-        if (wave < DBLK) {
+            for (int v = 0; v < 16; ++v) accw[b][v] = 0.f;
+        float acca = 0.f;                                   // Avec[k = lane] (lanes < KD)
+        float4 xr[NXR], yr[NYR];
+        float dsr = 0.f;
+        int gi[NXR];
+        auto fetch_idx = [&](int u) {
+#pragma unroll
+            for (int it = 0; it < NXR; ++it) {
+                const int row = ra + u * 32 + rx + it * RPX;
+                gi[it] = (u < nu && row < rbnd) ? (gather ? gather[row] : row) : -1;
+            }
+        };
+        auto fetch = [&](int u) {
+#pragma unroll
+            for (int it = 0; it < NXR; ++it) {
+                xr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (gi[it] >= 0) xr[it] = *reinterpret_cast<const float4*>(X + (size_t)gi[it] * KD + cx * 4);
+            }
+#pragma unroll
+            for (int it = 0; it < NYR; ++it) {
+                const int row = ra + u * 32 + ry + it * RPY;
+                yr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (u < nu && row < rbnd) {
+                    const size_t s2 = (dy_gathered && gather) ? (size_t)gather[row] : (size_t)row;
+                    yr[it] = *reinterpret_cast<const float4*>(dY + s2 * ND + cy * 4);
+                }
+            }
+            const int row = ra + u * 32 + lane;
+            dsr = (rowscale && lane < 32 && u < nu && row < rbnd) ? rowscale[row] : 0.f;
+        };
+        fetch_idx(wave);
+        fetch(wave);
+        fetch_idx(wave + NW);
+        for (int u = wave; u < nu; u += NW) {
+#pragma unroll
+            for (int it = 0; it < NXR; ++it)
+                *reinterpret_cast<float4*>(Xw + (rx + it * RPX) * XS + cx * 4) = xr[it];
+#pragma unroll
+            for (int it = 0; it < NYR; ++it)
+                *reinterpret_cast<float4*>(Yw + (ry + it * RPY) * YS + cy * 4) = yr[it];
+            if (lane < 32) dsw[lane] = dsr;
+            wave_lds_fence();
+            fetch(u + NW);
+            fetch_idx(u + 2 * NW);
+            // dXrow unit: 32 x KD, contraction over the output features
+            v16f accx[KB];
+#pragma unroll
+            for (int b = 0; b < KB; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) accx[b][v] = 0.f;
 #pragma unroll 2
             for (int tt = 0; tt < ND / 8; ++tt) {
                 const int n0 = kh * (ND / 2) + 4 * tt;
-                const float4 a4 = *reinterpret_cast<const float4*>(dYs + (rb * 32 + m) * YS + n0);
+                const float4 a4 = *reinterpret_cast<const float4*>(Yw + m * YS + n0);
                 const float av[4] = {a4.x, a4.y, a4.z, a4.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
-                    for (int b = 0; b < DBW; ++b) {
-                        const int cb = (wave >> 1) + 2 * b;
-                        accx[b] = mfma32(av[i], Ws[(cb * 32 + m) * WS + n0 + i], accx[b]);
-                    }
+                    for (int b = 0; b < KB; ++b) accx[b] = mfma32(av[i], Ws[(b * 32 + m) * WS + n0 + i], accx[b]);
             }
-#pragma unroll
-            for (int b = 0; b < DBW; ++b) {
-                const int cb = (wave >> 1) + 2 * b;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) DXs[(rb * 32 + acc_row(v, kh)) * XS + cb * 32 + m] = accx[b][v];
-            }
-        }
-        if (wave < WBLK) {
+            // weight gradient: KD x ND, contraction over the unit's 32 rows (two rows per MFMA)
 #pragma unroll 4
-            for (int s = 0; s < TM / 2; ++s) {
-                const int r = 2 * s + kh;
+            for (int s2 = 0; s2 < 16; ++s2) {
+                const int r = 2 * s2 + kh;
+                float av[KB], bv[NB];
 #pragma unroll
-                for (int b = 0; b < WBW; ++b) {
-                    const int blk = wave + 4 * b, kb = blk % KB, nb = blk / KB;
-                    accw[b] = mfma32(Xs[r * XS + kb * 32 + m], dYs[r * YS + nb * 32 + m], accw[b]);
+                for (int kb = 0; kb < KB; ++kb) av[kb] = Xw[r * XS + kb * 32 + m];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) bv[nb] = Yw[r * YS + nb * 32 + m];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb) accw[nb * KB + kb] = mfma32(av[kb], bv[nb], accw[nb * KB + kb]);
+            }
+            if (rowscale && lane < KD) {
+#pragma unroll 8
+                for (int r = 0; r < 32; ++r) acca += dsw[r] * Xw[r * XS + lane];
+            }
+            wave_lds_fence();             // all reads of Yw are done before it becomes the dXrow stage
+#pragma unroll
+            for (int b = 0; b < KB; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) Yw[acc_row(v, kh) * YS + b * 32 + m] = accx[b][v];
+            wave_lds_fence();
+#pragma unroll
+            for (int it = 0; it < NXR; ++it) {
+                const int r = rx + it * RPX, row = ra + u * 32 + r;
+                if (row < rbnd) {
+                    const size_t d = (scatter_dx && gather) ? (size_t)gather[row] : (size_t)row;
+                    float4 o = *reinterpret_cast<const float4*>(Yw + r * YS + cx * 4);
+                    const float sc = dsw[r];
+                    o.x += sc * xv.x; o.y += sc * xv.y; o.z += sc * xv.z; o.w += sc * xv.w;
+                    *reinterpret_cast<float4*>(dXrow + d * KD + cx * 4) = o;
                 }
             }
+            wave_lds_fence();
         }
-        if (rowscale) {
-            const int k = tid % KD;
-            for (int r = tid / KD; r < TM; r += AG) acca += dss[r] * Xs[r * XS + k];
+        // flush: every wavefront parks its partial weight gradient in its own LDS region, then
+        // all threads add the eight copies in wavefront order.
+        __syncthreads();
+        {
+            float* mine = smem + KD * WS + wave * WREG;      // >= KD*ND + KD floats per region (checked on the host)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        mine[(kb * 32 + acc_row(v, kh)) * ND + nb * 32 + m] = accw[nb * KB + kb][v];
+            if (lane < KD) mine[KD * ND + lane] = acca;
         }
         __syncthreads();
+        {
+            float* ps = part + (size_t)slot * SLOT;
+            for (int i = tid; i < SLOT; i += 64 * NW) {
+                float sum = 0.f;
 #pragma unroll
-        for (int it = 0; it < NXR; ++it) {
-            const int r = rx + it * RPPX, row = row0 + r;
-            if (row < row1) {
-                const size_t d = (scatter_dx && gather) ? (size_t)gather[row] : (size_t)row;
-                *reinterpret_cast<float4*>(dXrow + d * KD + cx * 4) =
-                    *reinterpret_cast<const float4*>(DXs + r * XS + cx * 4);
+                for (int w2 = 0; w2 < NW; ++w2) sum += smem[KD * WS + w2 * WREG + i];
+                ps[i] = sum;
             }
         }
+        ta = tb;
     }
 }
 
@@ -508,8 +650,12 @@ static TileArgs tile_args(const TileList& t) {
 
 template <int KD, int ND>
 static rgnn_status_t launch_fwd(const TypedLinearArgs& a, hipStream_t st) {
-    const size_t lds = sizeof(float) * (KD * ND + TM * (KD + 4) + TM * (ND + 4));
-    auto kern = typed_linear_fwd_kernel<KD, ND>;
+    constexpr bool WAVE = (KD <= 64 && ND <= 64);
+    const size_t lds = WAVE ? sizeof(float) * (KD * ND + 4 * 32 * ((KD > ND ? KD : ND) + 4))
+                            : sizeof(float) * (KD * ND + TM * (KD + 4) + TM * (ND + 4));
+    void (*kern)(TileArgs, const float*, const int32_t*, const float*, float*, int, int, const float*, float*);
+    if constexpr (WAVE) kern = typed_linear_fwd_wave_kernel<KD, ND>;
+    else kern = typed_linear_fwd_kernel<KD, ND>;
     RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
@@ -533,14 +679,20 @@ size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t) {
 template <int KD, int ND>
 static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
     constexpr int STG = (KD > ND ? KD : ND) + 4;
-    constexpr bool PIPE = (KD <= 64 && ND <= 64);
-    const size_t lds = PIPE ? sizeof(float) * (KD * (ND + 1) + TM * (ND + 4) + 2 * TM * (KD + 4) + TM + 256)
+    constexpr bool WAVE = (KD <= 64 && ND <= 64);
+    constexpr int WREG = 32 * (KD + 4) + 32 * ((ND > KD ? ND : KD) + 4) + 32;
+    static_assert(!WAVE || WREG >= KD * ND + KD, "per-wavefront LDS region must hold a weight-gradient copy");
+    const size_t lds = WAVE ? sizeof(float) * (KD * (ND + 1) + 8 * WREG)
                             : sizeof(float) * (KD * (ND + 1) + TM * STG + TM * (KD + 4) + TM + 256);
-    auto kern = PIPE ? typed_linear_bwd_pipe_kernel<KD, ND> : typed_linear_bwd_kernel<KD, ND>;
+    void (*kern)(TileArgs, const float*, const int32_t*, const float*, const float*, int, float*, int, const float*,
+                 const float*, float*);
+    if constexpr (WAVE) kern = typed_linear_bwd_wave_kernel<KD, ND>;
+    else kern = typed_linear_bwd_kernel<KD, ND>;
+    const int threads = WAVE ? 512 : 256;
     if (a.tiles->num_tiles > 0) {
         RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
-        hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
+        hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(threads), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
                            a.dY, a.dy_gathered, a.dXrow, a.scatter_dx, a.rowscale, a.vec, a.part);
         RGNN_HIP(hipGetLastError());
     }
