@@ -16,6 +16,9 @@
 namespace rgnn {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+// Native 4-float vector for the register prefetch buffers: unlike HIP's float4 struct it is
+// copied with plain vector loads and stores, so arrays of it stay in registers.
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ v16f mfma32(float a, float b, v16f c) {
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
@@ -351,11 +354,17 @@ __device__ __forceinline__ int run_end(const int32_t* __restrict__ tile_seg, int
     return e;
 }
 
-template <int KD, int ND>
+// Compile-time switches of the wave kernels.  They are template parameters rather than
+// run-time flags so that the unit loop holds no conditional global load: with one, the
+// compiler has to wait for every outstanding memory operation (the prefetched rows and the
+// previous unit's stores) at each use.
+//   GATHER   rows are read through the gather list        SCATTER  outputs are written through it as well
+//   ACCUM    forward: Y += result                         VEC      forward: s_out = Y_row . vec[seg]
+//   DYG      backward: dY rows are read through the list  RS       backward: rowscale / Avec / xvec in use
+template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC>
 __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, const float* __restrict__ X,
                                                                     const int32_t* __restrict__ gather,
                                                                     const float* __restrict__ W, float* __restrict__ Y,
-                                                                    int scatter_out, int accumulate,
                                                                     const float* __restrict__ vec,
                                                                     float* __restrict__ s_out) {
     constexpr int NW = 4;                                   // wavefronts per workgroup
@@ -363,6 +372,7 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
     constexpr int CB = ND / 32;
     constexpr int LPRI = KD / 4, RPI = 64 / LPRI, NX = 32 / RPI;   // input: lanes per row, rows per load, loads per unit
     constexpr int LPRO = ND / 4, RPO = 64 / LPRO, NO = 32 / RPO;
+    static_assert(!SCATTER || KD == ND, "scattered output reuses the input rows' lane mapping");
     extern __shared__ __align__(16) float smem[];
     float* Ws = smem;                                       // [KD][ND]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -382,33 +392,34 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
         }
         __syncthreads();
         float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (vec) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + co * 4);
-        float4 xr[NX];
-        int gi[NX];
-        auto fetch_idx = [&](int u) {
-#pragma unroll
-            for (int it = 0; it < NX; ++it) {
-                const int row = ra + u * 32 + ri + it * RPI;
-                gi[it] = (u < nu && row < rbnd) ? (gather ? gather[row] : row) : -1;
-            }
-        };
-        auto fetch_rows = [&]() {
-#pragma unroll
-            for (int it = 0; it < NX; ++it) {
-                xr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (gi[it] >= 0) xr[it] = *reinterpret_cast<const float4*>(X + (size_t)gi[it] * KD + ci * 4);
-            }
-        };
-        fetch_idx(wave);
-        fetch_rows();
-        fetch_idx(wave + NW);
+        if (VEC) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + co * 4);
+        // Rows past the end of the run are clamped to its last row, so every load below is
+        // unconditional; what they bring in is never stored.
+        v4f xr[NX];
+        int gi[NX], gcur[NX];
+#define RGNN_FETCH_IDX(U)                                                           \
+    _Pragma("unroll") for (int it = 0; it < NX; ++it) {                             \
+        const int row_ = min(ra + (U) * 32 + ri + it * RPI, rbnd - 1);              \
+        gi[it] = GATHER ? gather[row_] : row_;                                      \
+    }
+#define RGNN_FETCH_ROWS()                                                           \
+    _Pragma("unroll") for (int it = 0; it < NX; ++it) {                             \
+        xr[it] = *reinterpret_cast<const v4f*>(X + (size_t)gi[it] * KD + ci * 4); \
+        gcur[it] = gi[it];                                                          \
+    }
+        RGNN_FETCH_IDX(wave)
+        RGNN_FETCH_ROWS()
+        RGNN_FETCH_IDX(wave + NW)
         for (int u = wave; u < nu; u += NW) {
+            int gout[NX];
 #pragma unroll
-            for (int it = 0; it < NX; ++it)
-                *reinterpret_cast<float4*>(Xw + (ri + it * RPI) * XS + ci * 4) = xr[it];
+            for (int it = 0; it < NX; ++it) {
+                *reinterpret_cast<v4f*>(Xw + (ri + it * RPI) * XS + ci * 4) = xr[it];
+                gout[it] = gcur[it];
+            }
             wave_lds_fence();
-            fetch_rows();                 // unit u + NW (all-zero past the end)
-            fetch_idx(u + 2 * NW);
+            RGNN_FETCH_ROWS()             // unit u + NW
+            RGNN_FETCH_IDX(u + 2 * NW)
             v16f acc[CB];
 #pragma unroll
             for (int b = 0; b < CB; ++b)
@@ -435,16 +446,14 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
                 const int r = ro + it * RPO, row = ra + u * 32 + r;
                 const bool ok = row < rbnd;
                 float4 y = *reinterpret_cast<const float4*>(Xw + r * XS + co * 4);
-                if (ok) {
-                    const size_t d = (scatter_out && gather) ? (size_t)gather[row] : (size_t)row;
-                    float4* yp = reinterpret_cast<float4*>(Y + d * ND + co * 4);
-                    if (accumulate) {
-                        const float4 o = *yp;
-                        y.x += o.x; y.y += o.y; y.z += o.z; y.w += o.w;
-                    }
-                    *yp = y;
+                const size_t d = SCATTER ? (size_t)gout[it] : (size_t)min(row, rbnd - 1);
+                float4* yp = reinterpret_cast<float4*>(Y + d * ND + co * 4);
+                if (ACCUM) {
+                    const float4 o = *yp;
+                    y.x += o.x; y.y += o.y; y.z += o.z; y.w += o.w;
                 }
-                if (vec) {
+                if (ok) *yp = y;
+                if (VEC) {
                     float sdot = y.x * wv.x + y.y * wv.y + y.z * wv.z + y.w * wv.w;
 #pragma unroll
                     for (int o = LPRO / 2; o > 0; o >>= 1) sdot += __shfl_xor(sdot, o);
@@ -453,21 +462,23 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
             }
             wave_lds_fence();             // the stage is read out before the next unit's rows overwrite it
         }
+#undef RGNN_FETCH_IDX
+#undef RGNN_FETCH_ROWS
         ta = tb;
     }
 }
 
 // Backward, wave-independent: eight wavefronts per workgroup, each owning 32-row units of
-// the run.  Per unit a wavefront forms dXrow = dY_eff W^T (two 32x32 blocks) and adds its
+// the run.  Per unit a wavefront forms dXrow = dY W^T (+ rowscale (x) xvec) and adds its
 // rows' contribution to the full KD x ND weight gradient (KB*NB blocks, kept in registers
 // for the whole run) and to Avec.  At the end of a run the eight wavefronts' partial weight
 // gradients are summed in wavefront order through LDS and written to the chunk's slot.
-template <int KD, int ND>
+template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS>
 __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, const float* __restrict__ X,
                                                                     const int32_t* __restrict__ gather,
                                                                     const float* __restrict__ W,
-                                                                    const float* __restrict__ dY, int dy_gathered,
-                                                                    float* __restrict__ dXrow, int scatter_dx,
+                                                                    const float* __restrict__ dY,
+                                                                    float* __restrict__ dXrow,
                                                                     const float* __restrict__ rowscale,
                                                                     const float* __restrict__ vec,
                                                                     float* __restrict__ part) {
@@ -478,11 +489,12 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
     constexpr int LPRX = KD / 4, RPX = 64 / LPRX, NXR = 32 / RPX;
     constexpr int LPRY = ND / 4, RPY = 64 / LPRY, NYR = 32 / RPY;
     constexpr int WREG = 32 * XS + 32 * YS + 32;            // floats of LDS per wavefront
+    static_assert(!(DYG || SCATTER) || KD == ND, "gathered dY / scattered dXrow reuse the X rows' lane mapping");
     extern __shared__ __align__(16) float smem[];
     float* Ws = smem;                                       // [KD][WS]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float* Xw = smem + KD * WS + wave * WREG;               // [32][XS]  gathered input rows
-    float* Yw = Xw + 32 * XS;                               // [32][YS]  dY_eff rows, then the dXrow stage
+    float* Yw = Xw + 32 * XS;                               // [32][YS]  dY rows, then the dXrow stage
     float* dsw = Yw + 32 * YS;                              // [32]      rowscale of the unit's rows
     const int m = lane & 31, kh = lane >> 5;
     const int cx = lane % LPRX, rx = lane / LPRX, cy = lane % LPRY, ry = lane / LPRY;
@@ -500,52 +512,60 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
         }
         __syncthreads();
         float4 xv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (vec && rowscale) xv = *reinterpret_cast<const float4*>(vec + (size_t)seg * KD + cx * 4);
+        if (RS && vec) xv = *reinterpret_cast<const float4*>(vec + (size_t)seg * KD + cx * 4);
         v16f accw[WB];
 #pragma unroll
         for (int b = 0; b < WB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) accw[b][v] = 0.f;
         float acca = 0.f;                                   // Avec[k = lane] (lanes < KD)
-        float4 xr[NXR], yr[NYR];
+        // Rows past the end of the run are clamped to its last row (loads stay unconditional)
+        // and zeroed when they are written to LDS, so they add nothing to the weight gradient.
+        v4f xr[NXR], yr[NYR];
         float dsr = 0.f;
-        int gi[NXR];
+        int gi[NXR], gcur[NXR];
         auto fetch_idx = [&](int u) {
 #pragma unroll
             for (int it = 0; it < NXR; ++it) {
-                const int row = ra + u * 32 + rx + it * RPX;
-                gi[it] = (u < nu && row < rbnd) ? (gather ? gather[row] : row) : -1;
+                const int row = min(ra + u * 32 + rx + it * RPX, rbnd - 1);
+                gi[it] = GATHER ? gather[row] : row;
             }
         };
         auto fetch = [&](int u) {
 #pragma unroll
             for (int it = 0; it < NXR; ++it) {
-                xr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (gi[it] >= 0) xr[it] = *reinterpret_cast<const float4*>(X + (size_t)gi[it] * KD + cx * 4);
+                xr[it] = *reinterpret_cast<const v4f*>(X + (size_t)gi[it] * KD + cx * 4);
+                gcur[it] = gi[it];
             }
 #pragma unroll
             for (int it = 0; it < NYR; ++it) {
-                const int row = ra + u * 32 + ry + it * RPY;
-                yr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (u < nu && row < rbnd) {
-                    const size_t s2 = (dy_gathered && gather) ? (size_t)gather[row] : (size_t)row;
-                    yr[it] = *reinterpret_cast<const float4*>(dY + s2 * ND + cy * 4);
-                }
+                const size_t s2 = DYG ? (size_t)gi[it] : (size_t)min(ra + u * 32 + ry + it * RPY, rbnd - 1);
+                yr[it] = *reinterpret_cast<const v4f*>(dY + s2 * ND + cy * 4);
             }
-            const int row = ra + u * 32 + lane;
-            dsr = (rowscale && lane < 32 && u < nu && row < rbnd) ? rowscale[row] : 0.f;
+            if (RS) dsr = rowscale[min(ra + u * 32 + (lane & 31), rbnd - 1)];
         };
         fetch_idx(wave);
         fetch(wave);
         fetch_idx(wave + NW);
         for (int u = wave; u < nu; u += NW) {
+            const int rows_left = rbnd - (ra + u * 32);      // rows of this unit that exist (may exceed 32)
+            int gout[NXR];
 #pragma unroll
-            for (int it = 0; it < NXR; ++it)
-                *reinterpret_cast<float4*>(Xw + (rx + it * RPX) * XS + cx * 4) = xr[it];
+            for (int it = 0; it < NXR; ++it) {
+                const bool ok = rx + it * RPX < rows_left;
+                v4f v = xr[it];
+                if (!ok) v = v4f{0.f, 0.f, 0.f, 0.f};
+                *reinterpret_cast<v4f*>(Xw + (rx + it * RPX) * XS + cx * 4) = v;
+                gout[it] = gcur[it];
+            }
 #pragma unroll
-            for (int it = 0; it < NYR; ++it)
-                *reinterpret_cast<float4*>(Yw + (ry + it * RPY) * YS + cy * 4) = yr[it];
-            if (lane < 32) dsw[lane] = dsr;
+            for (int it = 0; it < NYR; ++it) {
+                const bool ok = ry + it * RPY < rows_left;
+                v4f v = yr[it];
+                if (!ok) v = v4f{0.f, 0.f, 0.f, 0.f};
+                *reinterpret_cast<v4f*>(Yw + (ry + it * RPY) * YS + cy * 4) = v;
+            }
+            if (RS && lane < 32) dsw[lane] = lane < rows_left ? dsr : 0.f;
             wave_lds_fence();
             fetch(u + NW);
             fetch_idx(u + 2 * NW);
@@ -579,7 +599,7 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
 #pragma unroll
                     for (int kb = 0; kb < KB; ++kb) accw[nb * KB + kb] = mfma32(av[kb], bv[nb], accw[nb * KB + kb]);
             }
-            if (rowscale && lane < KD) {
+            if (RS && lane < KD) {
 #pragma unroll 8
                 for (int r = 0; r < 32; ++r) acca += dsw[r] * Xw[r * XS + lane];
             }
@@ -591,14 +611,14 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
             wave_lds_fence();
 #pragma unroll
             for (int it = 0; it < NXR; ++it) {
-                const int r = rx + it * RPX, row = ra + u * 32 + r;
-                if (row < rbnd) {
-                    const size_t d = (scatter_dx && gather) ? (size_t)gather[row] : (size_t)row;
-                    float4 o = *reinterpret_cast<const float4*>(Yw + r * YS + cx * 4);
+                const int r = rx + it * RPX;
+                float4 o = *reinterpret_cast<const float4*>(Yw + r * YS + cx * 4);
+                if (RS) {
                     const float sc = dsw[r];
                     o.x += sc * xv.x; o.y += sc * xv.y; o.z += sc * xv.z; o.w += sc * xv.w;
-                    *reinterpret_cast<float4*>(dXrow + d * KD + cx * 4) = o;
                 }
+                const size_t d = SCATTER ? (size_t)gout[it] : (size_t)(ra + u * 32 + r);
+                if (r < rows_left) *reinterpret_cast<float4*>(dXrow + d * KD + cx * 4) = o;
             }
             wave_lds_fence();
         }
@@ -606,7 +626,7 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
         // all threads add the eight copies in wavefront order.
         __syncthreads();
         {
-            float* mine = smem + KD * WS + wave * WREG;      // >= KD*ND + KD floats per region (checked on the host)
+            float* mine = smem + KD * WS + wave * WREG;      // holds KD*ND + KD floats (checked on the host)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -648,14 +668,31 @@ static TileArgs tile_args(const TileList& t) {
     return TileArgs{t.tile_seg, t.tile_row0, t.tile_row1, t.chunk_tile, t.chunk_slot};
 }
 
+template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC>
+static rgnn_status_t launch_fwd_wave(const TypedLinearArgs& a, hipStream_t st) {
+    const size_t lds = sizeof(float) * (KD * ND + 4 * 32 * ((KD > ND ? KD : ND) + 4));
+    auto kern = typed_linear_fwd_wave_kernel<KD, ND, GATHER, SCATTER, ACCUM, VEC>;
+    RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
+    hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W, a.Y,
+                       a.vec, a.s_out);
+    RGNN_HIP(hipGetLastError());
+    return RGNN_OK;
+}
+
 template <int KD, int ND>
 static rgnn_status_t launch_fwd(const TypedLinearArgs& a, hipStream_t st) {
-    constexpr bool WAVE = (KD <= 64 && ND <= 64);
-    const size_t lds = WAVE ? sizeof(float) * (KD * ND + 4 * 32 * ((KD > ND ? KD : ND) + 4))
-                            : sizeof(float) * (KD * ND + TM * (KD + 4) + TM * (ND + 4));
-    void (*kern)(TileArgs, const float*, const int32_t*, const float*, float*, int, int, const float*, float*);
-    if constexpr (WAVE) kern = typed_linear_fwd_wave_kernel<KD, ND>;
-    else kern = typed_linear_fwd_kernel<KD, ND>;
+    if constexpr (KD <= 64 && ND <= 64) {
+        // the combinations the layers use
+        const bool g = a.gather != nullptr, sc = g && a.scatter_out, ac = a.accumulate != 0, v = a.vec != nullptr;
+        if (g && !sc && !ac && v) return launch_fwd_wave<KD, ND, true, false, false, true>(a, st);
+        if (g && !sc && !ac && !v) return launch_fwd_wave<KD, ND, true, false, false, false>(a, st);
+        if (g && sc && !ac && !v) return launch_fwd_wave<KD, ND, true, true, false, false>(a, st);
+        if (!g && !ac && !v) return launch_fwd_wave<KD, ND, false, false, false, false>(a, st);
+        if (!g && ac && !v) return launch_fwd_wave<KD, ND, false, false, true, false>(a, st);
+    }
+    const size_t lds = sizeof(float) * (KD * ND + TM * (KD + 4) + TM * (ND + 4));
+    auto kern = typed_linear_fwd_kernel<KD, ND>;
     RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
@@ -676,32 +713,54 @@ size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t) {
     return (size_t)std::max(t.num_slots, 1) * ((size_t)d_in * d_out + d_in);
 }
 
-template <int KD, int ND>
-static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
-    constexpr int STG = (KD > ND ? KD : ND) + 4;
-    constexpr bool WAVE = (KD <= 64 && ND <= 64);
-    constexpr int WREG = 32 * (KD + 4) + 32 * ((ND > KD ? ND : KD) + 4) + 32;
-    static_assert(!WAVE || WREG >= KD * ND + KD, "per-wavefront LDS region must hold a weight-gradient copy");
-    const size_t lds = WAVE ? sizeof(float) * (KD * (ND + 1) + 8 * WREG)
-                            : sizeof(float) * (KD * (ND + 1) + TM * STG + TM * (KD + 4) + TM + 256);
-    void (*kern)(TileArgs, const float*, const int32_t*, const float*, const float*, int, float*, int, const float*,
-                 const float*, float*);
-    if constexpr (WAVE) kern = typed_linear_bwd_wave_kernel<KD, ND>;
-    else kern = typed_linear_bwd_kernel<KD, ND>;
-    const int threads = WAVE ? 512 : 256;
-    if (a.tiles->num_tiles > 0) {
-        RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
-        hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(threads), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
-                           a.dY, a.dy_gathered, a.dXrow, a.scatter_dx, a.rowscale, a.vec, a.part);
-        RGNN_HIP(hipGetLastError());
-    }
-    const int kn = KD * ND;
+static rgnn_status_t launch_slot_reduce(int kd, int nd, const TypedLinearBwdArgs& a, hipStream_t st) {
+    const int kn = kd * nd;
     KernelTimer kt(st, "typed_linear_bwd.reduce");
-    hipLaunchKernelGGL(slot_reduce_kernel, dim3((kn + KD + 255) / 256, a.tiles->num_segs), dim3(256), 0, st, a.part,
-                       a.tiles->seg_slot_ptr, kn, KD, a.dW, a.Avec);
+    hipLaunchKernelGGL(slot_reduce_kernel, dim3((kn + kd + 255) / 256, a.tiles->num_segs), dim3(256), 0, st, a.part,
+                       a.tiles->seg_slot_ptr, kn, kd, a.dW, a.Avec);
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
+}
+
+template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS>
+static rgnn_status_t launch_bwd_wave(const TypedLinearBwdArgs& a, hipStream_t st) {
+    constexpr int WREG = 32 * (KD + 4) + 32 * ((ND > KD ? ND : KD) + 4) + 32;
+    static_assert(WREG >= KD * ND + KD, "per-wavefront LDS region must hold a weight-gradient copy");
+    const size_t lds = sizeof(float) * (KD * (ND + 1) + 8 * WREG);
+    auto kern = typed_linear_bwd_wave_kernel<KD, ND, GATHER, DYG, SCATTER, RS>;
+    RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
+    hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(512), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
+                       a.dY, a.dXrow, a.rowscale, a.vec, a.part);
+    RGNN_HIP(hipGetLastError());
+    return RGNN_OK;
+}
+
+template <int KD, int ND>
+static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
+    if (a.tiles->num_tiles > 0) {
+        bool done = false;
+        if constexpr (KD <= 64 && ND <= 64) {
+            const bool g = a.gather != nullptr, dg = g && a.dy_gathered, sc = g && a.scatter_dx, rs = a.rowscale != nullptr;
+            done = true;
+            if (g && !dg && !sc && rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true>(a, st)));
+            else if (g && !dg && !sc && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, false>(a, st)));
+            else if (g && dg && sc && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, true, true, false>(a, st)));
+            else if (!g && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, false, false, false, false>(a, st)));
+            else done = false;
+        }
+        if (!done) {
+            constexpr int STG = (KD > ND ? KD : ND) + 4;
+            const size_t lds = sizeof(float) * (KD * (ND + 1) + TM * STG + TM * (KD + 4) + TM + 256);
+            auto kern = typed_linear_bwd_kernel<KD, ND>;
+            RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
+            hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather,
+                               a.W, a.dY, a.dy_gathered, a.dXrow, a.scatter_dx, a.rowscale, a.vec, a.part);
+            RGNN_HIP(hipGetLastError());
+        }
+    }
+    return launch_slot_reduce(KD, ND, a, st);
 }
 
 rgnn_status_t typed_linear_bwd(int d_in, int d_out, const TypedLinearBwdArgs& a, hipStream_t st) {
