@@ -159,6 +159,14 @@ def main():
         gb = dom.get("GBps", 0.0)
         roof = {"kernel": dom["name"], "bound": "hbm", "achieved": gb, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": gb / HBM_PEAK_GBS, "traffic": None}
+    # HBM bytes per launch from rocprofv3 counters (two --pmc runs of this same command, calibrated
+    # against the 1 GiB copy above); only valid for the full-size default workload.
+    tsv = os.path.join(ROOT, "profiles", "rgat_c3_hbm_traffic.tsv")
+    if args.config == 3 and args.scale == 1.0 and os.path.exists(tsv):
+        for ln in open(tsv):
+            f = ln.rstrip("\n").split("\t")
+            if not ln.startswith("#") and f[0] == dom["name"]:
+                roof["traffic"] = float(f[1]) + float(f[2])
     roof["avg_ms"] = dom["avg_ms"]
     roof["algorithmic_bytes"] = w[1] if w else None
 

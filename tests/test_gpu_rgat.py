@@ -61,6 +61,14 @@ def test_config2():
     _run(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 64, "C2")
 
 
+@pytest.mark.timeout(900)
+def test_config3_full_size():
+    """The benchmark's workload (10M edges, 200 relations, hubs of in-degree 50k), every output
+    element against the oracle."""
+    c = synth.config(3)
+    _run(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 64, "C3", check_saved=False)
+
+
 def test_hub_empty_relation_isolated_nodes():
     rng, src, dst, rel, _ = synth.tiny(70, N=300, R=5, E=4000)
     rel[rel == 4] = 0       # relation 4 has no edge
