@@ -1,0 +1,298 @@
+// HGT-specific kernels: block-diagonal expansion of the per-(relation, head) matrices, the
+// per-head edge logits, the per-head edge softmax and the per-head backward edge dot.
+// (Caption of the thesis figure "HGT and RGAT layer": attention of HGT is an edgewise dot
+// product between the relation-transformed key of the source and the query of the
+// destination; the message depends only on (source node, edge type), so both are stored
+// once per pair.)
+//
+// The d_head x d_head matrices W[r][h] are expanded to one block-diagonal d x d matrix per
+// relation so that the relation-segmented typed-linear kernel serves them unchanged; with
+// bf16 or fp32 inputs that kernel is bound by HBM traffic at these widths, so the extra
+// zero blocks cost no time.
+#include "rgnn_internal.h"
+#include "traversal.h"
+
+namespace rgnn {
+
+struct Items {
+    int n;
+    const int32_t* beg;
+    const int32_t* end;
+    const int32_t* row;
+    const int32_t* slot;
+};
+static Items dev_items(const ItemList& L) { return Items{L.num_items, L.beg, L.end, L.row, L.slot}; }
+
+template <int W>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+    for (int o = W / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ float group_sum_dyn(float v, int w) {
+    for (int o = w / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float dot4(const float4& a, const float4& b) {
+    return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+}
+
+// Wbd[r][i][j] = c(r, h) * W[r][h][i % dh][j % dh] if i and j lie in the same head h, else 0.
+// c = (mu ? mu[r][h] : 1) / sqrt(dh) when `scaled` (attention), 1 otherwise (message).
+__global__ void hgt_expand_kernel(int R, int d, int H, const float* __restrict__ W, const float* __restrict__ mu,
+                                  int scaled, float* __restrict__ Wbd) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)R * d * d;
+    if (i >= total) return;
+    const int dh = d / H;
+    const int r = (int)(i / ((size_t)d * d)), a = (int)(i / d % d), b = (int)(i % d);
+    const int ha = a / dh, hb = b / dh;
+    float v = 0.f;
+    if (ha == hb) {
+        float c = 1.f;
+        if (scaled) c = (mu ? mu[r * H + ha] : 1.f) * rsqrtf((float)dh);
+        v = c * W[(((size_t)r * H + ha) * dh + a % dh) * dh + b % dh];
+    }
+    Wbd[i] = v;
+}
+
+// One workgroup per (relation, head): dW[r][h] = c * block(dWbd[r], h); for the attention
+// matrices also dmu[r][h] = sum(block .* W[r][h]) / sqrt(dh).
+__global__ void hgt_extract_kernel(int d, int H, const float* __restrict__ dWbd, const float* __restrict__ W,
+                                   const float* __restrict__ mu, int scaled, float* __restrict__ dW,
+                                   float* __restrict__ dmu) {
+    __shared__ float red[256];
+    const int r = blockIdx.x / H, h = blockIdx.x % H, dh = d / H;
+    const float inv = rsqrtf((float)dh);
+    const float c = scaled ? (mu ? mu[r * H + h] : 1.f) * inv : 1.f;
+    float s = 0.f;
+    for (int i = threadIdx.x; i < dh * dh; i += blockDim.x) {
+        const int a = i / dh, b = i % dh;
+        const float g = dWbd[((size_t)r * d + h * dh + a) * d + h * dh + b];
+        const size_t wi = ((size_t)r * H + h) * dh * dh + i;
+        dW[wi] = c * g;
+        s += g * W[wi];
+    }
+    if (!(scaled && dmu)) return;
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = blockDim.x / 2; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) dmu[r * H + h] = red[0] * inv;
+}
+
+// logit[e][h] = Ka[pair_e][h] . Q[v][h]   (Ka already carries mu / sqrt(dh))
+template <int D>
+__global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, const int32_t* __restrict__ in_pair,
+                                                             const float* __restrict__ Ka,
+                                                             const float* __restrict__ Q, float* __restrict__ logit) {
+    constexpr int LPR = D / 4, IPB = 256 / LPR;
+    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+    if (i >= it.n) return;
+    const int b = it.beg[i], e = it.end[i];
+    if (e == b) return;
+    const int lph = LPR / H, head = c4 / lph;
+    const float4 q = *reinterpret_cast<const float4*>(Q + (size_t)it.row[i] * D + c4 * 4);
+    for (int j = b; j < e; j += 4) {
+        float4 k[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            k[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (j + u < e) k[u] = *reinterpret_cast<const float4*>(Ka + (size_t)in_pair[j + u] * D + c4 * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float s = group_sum_dyn(dot4(q, k[u]), lph);
+            if (c4 % lph == 0 && j + u < e) logit[(size_t)(j + u) * H + head] = s;
+        }
+    }
+}
+
+// Per-head softmax of att[e][h] (holding logits on entry) over each destination's edges.
+// Short nodes: one lane per (node, head).  Long items and pieces of cut nodes: one wavefront
+// per item, heads in turn; pieces store (max, sum) per head for the finish kernel.
+__global__ void hgt_softmax_kernel(int N, int H, const int32_t* __restrict__ in_ptr, float* __restrict__ att) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= N * H) return;
+    const int v = t / H, h = t % H;
+    const int b = in_ptr[v], e = in_ptr[v + 1];
+    if (e == b || e - b > kSerialMax) return;
+    float m = -INFINITY, s = 0.f;
+    for (int j = b; j < e; ++j) m = fmaxf(m, att[(size_t)j * H + h]);
+    for (int j = b; j < e; ++j) s += expf(att[(size_t)j * H + h] - m);
+    const float inv = 1.f / s;
+    for (int j = b; j < e; ++j) att[(size_t)j * H + h] = expf(att[(size_t)j * H + h] - m) * inv;
+}
+__global__ void hgt_softmax_long_kernel(Items it, int n_long, const int32_t* __restrict__ long_item, int H,
+                                        float* __restrict__ att, float* __restrict__ part_m,
+                                        float* __restrict__ part_s) {
+    const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    if (w >= n_long) return;
+    const int i = long_item[w];
+    const int bb = it.beg[i], ee = it.end[i], sl = it.slot[i];
+    for (int h = 0; h < H; ++h) {
+        float m = -INFINITY, s = 0.f;
+        for (int j = bb + lane; j < ee; j += 64) m = fmaxf(m, att[(size_t)j * H + h]);
+        m = wave_max(m);
+        for (int j = bb + lane; j < ee; j += 64) s += expf(att[(size_t)j * H + h] - m);
+        s = group_sum<64>(s);
+        if (sl < 0) {
+            const float inv = 1.f / s;
+            for (int j = bb + lane; j < ee; j += 64) att[(size_t)j * H + h] = expf(att[(size_t)j * H + h] - m) * inv;
+        } else if (lane == 0) {
+            part_m[(size_t)sl * H + h] = m;
+            part_s[(size_t)sl * H + h] = s;
+        }
+    }
+}
+__global__ void hgt_softmax_finish_kernel(int num_partials, const int32_t* __restrict__ part_item,
+                                          const int32_t* __restrict__ part_split,
+                                          const int32_t* __restrict__ split_ptr, Items it, int H,
+                                          const float* __restrict__ part_m, const float* __restrict__ part_s,
+                                          float* __restrict__ att) {
+    const int t = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    if (t >= num_partials) return;
+    const int sp = part_split[t];
+    const int p0 = split_ptr[sp], p1 = split_ptr[sp + 1];
+    const int item = part_item[t];
+    for (int h = 0; h < H; ++h) {
+        float m = -INFINITY;
+        for (int p = p0 + lane; p < p1; p += 64) m = fmaxf(m, part_m[(size_t)p * H + h]);
+        m = wave_max(m);
+        float s = 0.f;
+        for (int p = p0 + lane; p < p1; p += 64) s += part_s[(size_t)p * H + h] * expf(part_m[(size_t)p * H + h] - m);
+        s = group_sum<64>(s);
+        const float inv = 1.f / s;
+        for (int j = it.beg[item] + lane; j < it.end[item]; j += 64)
+            att[(size_t)j * H + h] = expf(att[(size_t)j * H + h] - m) * inv;
+    }
+}
+
+// dl[e][h] = att[e][h] * (dZ[v][h] . M[pair_e][h] - dZ[v][h] . Z[v][h])
+// (the second term is sum_e att_e g_e because Z[v][h] = sum_e att_e M[pair_e][h]).
+template <int D>
+__global__ __launch_bounds__(256) void hgt_edge_dot_bwd_kernel(Items it, int H, const int32_t* __restrict__ in_pair,
+                                                               const float* __restrict__ att,
+                                                               const float* __restrict__ M,
+                                                               const float* __restrict__ dZ,
+                                                               const float* __restrict__ Z, float* __restrict__ dl) {
+    constexpr int LPR = D / 4, IPB = 256 / LPR;
+    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+    if (i >= it.n) return;
+    const int b = it.beg[i], e = it.end[i];
+    if (e == b) return;
+    const int lph = LPR / H, head = c4 / lph;
+    const size_t v = (size_t)it.row[i];
+    const float4 gz = *reinterpret_cast<const float4*>(dZ + v * D + c4 * 4);
+    const float4 zz = *reinterpret_cast<const float4*>(Z + v * D + c4 * 4);
+    const float gbar = group_sum_dyn(dot4(gz, zz), lph);
+    for (int j = b; j < e; j += 4) {
+        float4 mm[4];
+        float a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            mm[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            a[u] = 0.f;
+            if (j + u < e) {
+                mm[u] = *reinterpret_cast<const float4*>(M + (size_t)in_pair[j + u] * D + c4 * 4);
+                a[u] = att[(size_t)(j + u) * H + head];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float g = group_sum_dyn(dot4(gz, mm[u]), lph);
+            if (c4 % lph == 0 && j + u < e) dl[(size_t)(j + u) * H + head] = a[u] * (g - gbar);
+        }
+    }
+}
+
+__global__ void add3_kernel(size_t n, const float* __restrict__ a, const float* __restrict__ b,
+                            const float* __restrict__ c, float* __restrict__ out) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = a[i] + b[i] + c[i];
+}
+
+// ---------------------------------------------------------------------------------------- launchers
+#define CHECK_LAUNCH() RGNN_HIP(hipGetLastError())
+static inline unsigned blocks_for(size_t n, unsigned per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+#define DISPATCH_D(D_, CALL)                                                           \
+    do {                                                                               \
+        if ((D_) == 64) { constexpr int DD = 64; CALL; }                               \
+        else if ((D_) == 32) { constexpr int DD = 32; CALL; }                          \
+        else if ((D_) == 128) { constexpr int DD = 128; CALL; }                        \
+        else RGNN_FAIL(RGNN_EUNSUPPORTED, "feature width %d not supported (32/64/128)", (int)(D_)); \
+    } while (0)
+
+rgnn_status_t hgt_expand(int R, int d, int H, const float* W, const float* mu, int scaled, float* Wbd, hipStream_t st) {
+    KernelTimer kt(st, "hgt_expand");
+    hipLaunchKernelGGL(hgt_expand_kernel, dim3(blocks_for((size_t)R * d * d, 256)), dim3(256), 0, st, R, d, H, W, mu,
+                       scaled, Wbd);
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+rgnn_status_t hgt_extract(int R, int d, int H, const float* dWbd, const float* W, const float* mu, int scaled, float* dW,
+                          float* dmu, hipStream_t st) {
+    KernelTimer kt(st, "hgt_extract");
+    hipLaunchKernelGGL(hgt_extract_kernel, dim3(R * H), dim3(256), 0, st, d, H, dWbd, W, mu, scaled, dW, dmu);
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const float* Ka, const float* Q, float* logit,
+                             hipStream_t st) {
+    const ItemList& L = g->dst_items;
+    if (L.num_items == 0 || g->E == 0) return RGNN_OK;
+    KernelTimer kt(st, "hgt_edge_logit");
+    DISPATCH_D(D, hipLaunchKernelGGL(hgt_edge_logit_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
+                                     0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], Ka, Q, logit));
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st) {
+    const ItemList& L = g->dst_items;
+    if (g->E == 0) return RGNN_OK;
+    {
+        KernelTimer kt(st, "hgt_softmax");
+        hipLaunchKernelGGL(hgt_softmax_kernel, dim3(blocks_for((size_t)g->N * H, 256)), dim3(256), 0, st, (int)g->N, H,
+                           g->idx[RGNN_IDX_IN_PTR], att);
+        CHECK_LAUNCH();
+        if (L.num_long > 0) {
+            hipLaunchKernelGGL(hgt_softmax_long_kernel, dim3(blocks_for((size_t)L.num_long * 64, 256)), dim3(256), 0, st,
+                               dev_items(L), L.num_long, L.long_item, H, att, part_m, part_s);
+            CHECK_LAUNCH();
+        }
+    }
+    if (L.num_partials > 0) {
+        KernelTimer kt(st, "hgt_softmax.finish");
+        hipLaunchKernelGGL(hgt_softmax_finish_kernel, dim3(blocks_for((size_t)L.num_partials * 64, 256)), dim3(256), 0,
+                           st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), H, part_m, part_s,
+                           att);
+        CHECK_LAUNCH();
+    }
+    return RGNN_OK;
+}
+rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* att, const float* M, const float* dZ,
+                               const float* Z, float* dl, hipStream_t st) {
+    const ItemList& L = g->dst_items;
+    if (L.num_items == 0 || g->E == 0) return RGNN_OK;
+    KernelTimer kt(st, "hgt_edge_dot_bwd");
+    DISPATCH_D(D, hipLaunchKernelGGL(hgt_edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))),
+                                     dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], att, M, dZ, Z, dl));
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+rgnn_status_t add3(size_t n, const float* a, const float* b, const float* c, float* out, hipStream_t st) {
+    if (n == 0) return RGNN_OK;
+    KernelTimer kt(st, "add3");
+    hipLaunchKernelGGL(add3_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, a, b, c, out);
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+}  // namespace rgnn

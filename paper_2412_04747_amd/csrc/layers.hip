@@ -34,7 +34,11 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
         if (d->norm != RGNN_NORM_NONE && d->norm != RGNN_NORM_IN_DEGREE_PER_REL) RGNN_FAIL(RGNN_EINVAL, "unknown norm %d", d->norm);
         if (d->activation != RGNN_ACT_NONE && d->activation != RGNN_ACT_RELU) RGNN_FAIL(RGNN_EINVAL, "unknown activation %d", d->activation);
     }
-    if (layer == RGNN_LAYER_HGT) RGNN_FAIL(RGNN_EUNSUPPORTED, "HGT is not implemented yet");
+    if (layer == RGNN_LAYER_HGT) {
+        if (d->heads < 1 || d->d_out % d->heads != 0) RGNN_FAIL(RGNN_EINVAL, "heads must divide d_out");
+        const int dh = d->d_out / d->heads;
+        if (dh != 16 && dh != 32 && dh != 64) RGNN_FAIL(RGNN_EUNSUPPORTED, "HGT needs d_out / heads in {16, 32, 64}, got %d", dh);
+    }
     return RGNN_OK;
 }
 
@@ -101,6 +105,48 @@ size_t carve_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
     return c.off;
 }
 
+// ---- HGT buffers ------------------------------------------------------------------------
+struct HgtSaved { float* K; float* Q; float* V; float* Z; float* Ka; float* M; float* att; };
+struct HgtFwdWs { float* Wbd_att; float* Wbd_msg; float* part_m; float* part_s; float* partial; };
+struct HgtBwdWs {
+    float* Wbd_att; float* Wbd_msg; float* dWbd_att; float* dWbd_msg; float* dZ; float* dl; float* dM; float* dKa;
+    float* dQ; float* dKp; float* dVp; float* dK; float* dV; float* dXk; float* dXq; float* dXv; float* tl_part;
+    float* partial;
+};
+
+size_t carve_hgt_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtSaved* s) {
+    Carver c(base);
+    const size_t nd = (size_t)g->N * d->d_out, pd = (size_t)g->P * d->d_out;
+    s->K = c.take<float>(nd); s->Q = c.take<float>(nd); s->V = c.take<float>(nd); s->Z = c.take<float>(nd);
+    s->Ka = c.take<float>(pd); s->M = c.take<float>(pd);
+    s->att = c.take<float>((size_t)g->E * d->heads);
+    return c.off;
+}
+size_t carve_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtFwdWs* w) {
+    Carver c(base);
+    const size_t rdd = (size_t)g->R * d->d_out * d->d_out;
+    w->Wbd_att = c.take<float>(rdd); w->Wbd_msg = c.take<float>(rdd);
+    w->part_m = c.take<float>((size_t)g->dst_items.num_partials * d->heads);
+    w->part_s = c.take<float>((size_t)g->dst_items.num_partials * d->heads);
+    w->partial = c.take<float>((size_t)g->dst_items.num_partials * d->d_out);
+    return c.off;
+}
+size_t carve_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtBwdWs* w) {
+    Carver c(base);
+    const size_t D = d->d_out, rdd = (size_t)g->R * D * D, nd = (size_t)g->N * D, pd = (size_t)g->P * D;
+    w->Wbd_att = c.take<float>(rdd); w->Wbd_msg = c.take<float>(rdd);
+    w->dWbd_att = c.take<float>(rdd); w->dWbd_msg = c.take<float>(rdd);
+    w->dZ = c.take<float>(nd); w->dl = c.take<float>((size_t)g->E * d->heads);
+    w->dM = c.take<float>(pd); w->dKa = c.take<float>(pd); w->dQ = c.take<float>(nd);
+    w->dKp = c.take<float>(pd); w->dVp = c.take<float>(pd);
+    w->dK = c.take<float>(nd); w->dV = c.take<float>(nd);
+    w->dXk = c.take<float>(nd); w->dXq = c.take<float>(nd); w->dXv = c.take<float>(nd);
+    w->tl_part = c.take<float>(std::max(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles),
+                                        typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->node_tiles)));
+    w->partial = c.take<float>((size_t)std::max(g->pair_items.num_partials, g->dst_items.num_partials) * D);
+    return c.off;
+}
+
 }  // namespace
 
 extern "C" rgnn_status_t rgnn_workspace_bytes(const rgnn_graph_t* g, int32_t layer, const rgnn_layer_desc_t* desc,
@@ -119,6 +165,11 @@ extern "C" rgnn_status_t rgnn_workspace_bytes(const rgnn_graph_t* g, int32_t lay
         f = carve_rgcn_fwd(g, desc, nullptr, &fw);
         b = carve_rgcn_bwd(g, desc, nullptr, &bw);
         s = 0;
+    } else {
+        HgtFwdWs fw; HgtBwdWs bw; HgtSaved sv;
+        f = carve_hgt_fwd(g, desc, nullptr, &fw);
+        b = carve_hgt_bwd(g, desc, nullptr, &bw);
+        s = carve_hgt_saved(g, desc, nullptr, &sv);
     }
     if (fwd_workspace) *fwd_workspace = f;
     if (bwd_workspace) *bwd_workspace = b;
@@ -274,16 +325,123 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     return RGNN_OK;
 }
 
-// =========================================================================== HGT (not built yet)
+// =========================================================================== HGT
 
-extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void*, const void*,
-                                      const void*, const void*, const void*, const void*, const void*, const void*,
-                                      void*, void*, void*, void*) {
-    return check_desc(g, desc, RGNN_LAYER_HGT);
+namespace {
+// Y[perm[i]] = X[perm[i]] W[type(i)] over the node-type segments.
+rgnn_status_t node_typed_linear(const rgnn_graph_t* g, int d, const float* X, const float* W, float* Y, const char* label,
+                                hipStream_t st) {
+    TypedLinearArgs a{};
+    a.tiles = &g->node_tiles; a.X = X; a.gather = g->idx[RGNN_IDX_NTYPE_PERM]; a.W = W; a.Y = Y; a.scatter_out = 1;
+    a.label = label;
+    return typed_linear_fwd(d, d, a, st);
 }
-extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void*, const void*,
-                                      const void*, const void*, const void*, const void*, const void*, const void*,
-                                      const void*, const void*, const void*, void*, void*, void*, void*, void*, void*,
-                                      void*, void*, void*, void*) {
-    return check_desc(g, desc, RGNN_LAYER_HGT);
+rgnn_status_t node_typed_linear_bwd(const rgnn_graph_t* g, int d, const float* X, const float* W, const float* dY,
+                                    float* dXrow, float* dW, float* part, const char* label, hipStream_t st) {
+    TypedLinearBwdArgs b{};
+    b.tiles = &g->node_tiles; b.X = X; b.gather = g->idx[RGNN_IDX_NTYPE_PERM]; b.W = W; b.dY = dY; b.dy_gathered = 1;
+    b.dXrow = dXrow; b.scatter_dx = 1; b.dW = dW; b.part = part; b.label = label;
+    return typed_linear_bwd(d, d, b, st);
+}
+rgnn_status_t pair_typed_linear(const rgnn_graph_t* g, int d, const float* X, const float* W, float* Y, const char* label,
+                                hipStream_t st) {
+    TypedLinearArgs a{};
+    a.tiles = &g->pair_tiles; a.X = X; a.gather = g->idx[RGNN_IDX_PAIR_SRC]; a.W = W; a.Y = Y; a.label = label;
+    return typed_linear_fwd(d, d, a, st);
+}
+rgnn_status_t pair_typed_linear_bwd(const rgnn_graph_t* g, int d, const float* X, const float* W, const float* dY,
+                                    float* dXrow, float* dW, float* part, const char* label, hipStream_t st) {
+    TypedLinearBwdArgs b{};
+    b.tiles = &g->pair_tiles; b.X = X; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = W; b.dY = dY; b.dXrow = dXrow;
+    b.dW = dW; b.part = part; b.label = label;
+    return typed_linear_bwd(d, d, b, st);
+}
+}  // namespace
+
+extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
+                                      const void* Wk, const void* Wq, const void* Wv, const void* Wo, const void* Watt,
+                                      const void* Wmsg, const void* mu, void* out, void* saved, void* workspace,
+                                      void* stream) {
+    RGNN_TRY(check_desc(g, desc, RGNN_LAYER_HGT));
+    if (!X || !Wk || !Wq || !Wv || !Wo || !Watt || !Wmsg || !out) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
+    if (!workspace || !saved) RGNN_FAIL(RGNN_EWORKSPACE, "workspace or saved is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int D = desc->d_out, H = desc->heads;
+    HgtFwdWs w; HgtSaved sv;
+    carve_hgt_fwd(g, desc, workspace, &w);
+    carve_hgt_saved(g, desc, saved, &sv);
+    const float* Xf = static_cast<const float*>(X);
+    // 1. per node type: K, Q, V
+    RGNN_TRY(node_typed_linear(g, D, Xf, static_cast<const float*>(Wk), sv.K, "node_linear_k", st));
+    RGNN_TRY(node_typed_linear(g, D, Xf, static_cast<const float*>(Wq), sv.Q, "node_linear_q", st));
+    RGNN_TRY(node_typed_linear(g, D, Xf, static_cast<const float*>(Wv), sv.V, "node_linear_v", st));
+    // 2. per (relation, head) matrices as block-diagonal d x d weights; mu / sqrt(dh) folded into the attention one
+    RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Watt), static_cast<const float*>(mu), 1, w.Wbd_att, st));
+    RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Wmsg), nullptr, 0, w.Wbd_msg, st));
+    // 3. compact per pair: Ka[p] = K[src_p] Watt[r], M[p] = V[src_p] Wmsg[r]
+    RGNN_TRY(pair_typed_linear(g, D, sv.K, w.Wbd_att, sv.Ka, "pair_linear_att", st));
+    RGNN_TRY(pair_typed_linear(g, D, sv.V, w.Wbd_msg, sv.M, "pair_linear_msg", st));
+    // 4. per edge and head: logit, softmax over the destination's edges
+    RGNN_TRY(hgt_edge_logit(g, D, H, sv.Ka, sv.Q, sv.att, st));
+    RGNN_TRY(hgt_softmax(g, H, sv.att, w.part_m, w.part_s, st));
+    // 5. Z[v][h] = sum_e att[e][h] M[pair_e][h]
+    RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, H, 0, sv.M, sv.Z, w.partial, st, 0,
+                        "aggregate_fwd", "aggregate_fwd.combine", H));
+    // 6. out = Z Wo[type]
+    RGNN_TRY(node_typed_linear(g, D, sv.Z, static_cast<const float*>(Wo), static_cast<float*>(out), "node_linear_out", st));
+    return RGNN_OK;
+}
+
+extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
+                                      const void* Wk, const void* Wq, const void* Wv, const void* Wo, const void* Watt,
+                                      const void* Wmsg, const void* mu, const void* out, const void* saved,
+                                      const void* dOut, void* dX, void* dWk, void* dWq, void* dWv, void* dWo,
+                                      void* dWatt, void* dWmsg, void* dmu, void* workspace, void* stream) {
+    (void)out;
+    RGNN_TRY(check_desc(g, desc, RGNN_LAYER_HGT));
+    if (!X || !Wk || !Wq || !Wv || !Wo || !Watt || !Wmsg || !dOut || !dX || !dWk || !dWq || !dWv || !dWo || !dWatt || !dWmsg)
+        RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
+    if (mu && !dmu) RGNN_FAIL(RGNN_EINVAL, "dmu is NULL but mu is given");
+    if (!workspace || !saved) RGNN_FAIL(RGNN_EWORKSPACE, "workspace or saved is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int D = desc->d_out, H = desc->heads;
+    HgtBwdWs w; HgtSaved sv;
+    carve_hgt_bwd(g, desc, workspace, &w);
+    carve_hgt_saved(g, desc, const_cast<void*>(saved), &sv);
+    const float* Xf = static_cast<const float*>(X);
+    const float* dO = static_cast<const float*>(dOut);
+    // 1. output linear: dZ = dOut Wo^T, dWo = Z^T dOut
+    RGNN_TRY(node_typed_linear_bwd(g, D, sv.Z, static_cast<const float*>(Wo), dO, w.dZ, static_cast<float*>(dWo), w.tl_part,
+                                   "node_linear_out_bwd", st));
+    // 2. per edge and head: d logit
+    RGNN_TRY(hgt_edge_dot_bwd(g, D, H, sv.att, sv.M, w.dZ, sv.Z, w.dl, st));
+    // 3. pair-major: dM[p][h] = sum att dZ[dst][h];  dKa[p][h] = sum dl Q[dst][h]
+    RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, sv.att, H, 0, w.dZ, w.dM,
+                        w.partial, st, 1, "aggregate_bwd_msg", "aggregate_bwd_msg.combine", H));
+    RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.dl, H, 0, sv.Q, w.dKa,
+                        w.partial, st, 1, "aggregate_bwd_key", "aggregate_bwd_key.combine", H));
+    // 4. destination-major: dQ[v][h] = sum dl Ka[pair][h]
+    RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, w.dl, H, 0, sv.Ka, w.dQ, w.partial, st, 0,
+                        "aggregate_bwd_query", "aggregate_bwd_query.combine", H));
+    // 5. per-pair linears backward
+    RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Watt), static_cast<const float*>(mu), 1, w.Wbd_att, st));
+    RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Wmsg), nullptr, 0, w.Wbd_msg, st));
+    RGNN_TRY(pair_typed_linear_bwd(g, D, sv.K, w.Wbd_att, w.dKa, w.dKp, w.dWbd_att, w.tl_part, "pair_linear_att_bwd", st));
+    RGNN_TRY(pair_typed_linear_bwd(g, D, sv.V, w.Wbd_msg, w.dM, w.dVp, w.dWbd_msg, w.tl_part, "pair_linear_msg_bwd", st));
+    RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_att, static_cast<const float*>(Watt), static_cast<const float*>(mu), 1,
+                         static_cast<float*>(dWatt), static_cast<float*>(dmu), st));
+    RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_msg, static_cast<const float*>(Wmsg), nullptr, 0, static_cast<float*>(dWmsg),
+                         nullptr, st));
+    // 6. dK[u], dV[u] = sums over u's pairs
+    RGNN_TRY(node_grad_sum(g, D, w.dKp, nullptr, nullptr, nullptr, w.dK, st));
+    RGNN_TRY(node_grad_sum(g, D, w.dVp, nullptr, nullptr, nullptr, w.dV, st));
+    // 7. node linears backward and dX
+    RGNN_TRY(node_typed_linear_bwd(g, D, Xf, static_cast<const float*>(Wk), w.dK, w.dXk, static_cast<float*>(dWk), w.tl_part,
+                                   "node_linear_k_bwd", st));
+    RGNN_TRY(node_typed_linear_bwd(g, D, Xf, static_cast<const float*>(Wq), w.dQ, w.dXq, static_cast<float*>(dWq), w.tl_part,
+                                   "node_linear_q_bwd", st));
+    RGNN_TRY(node_typed_linear_bwd(g, D, Xf, static_cast<const float*>(Wv), w.dV, w.dXv, static_cast<float*>(dWv), w.tl_part,
+                                   "node_linear_v_bwd", st));
+    RGNN_TRY(add3((size_t)g->N * D, w.dXk, w.dXq, w.dXv, static_cast<float*>(dX), st));
+    return RGNN_OK;
 }

@@ -197,7 +197,8 @@ __global__ void edge_softmax_finish_kernel(int num_partials, const int32_t* __re
 // For item i with entries j in [beg, end):
 //   k   = via ? via[j] : j
 //   row = row_by_k ? rowidx[k] : rowidx[j]
-//   c   = coef ? coef[k * cstride] : 1            (absolute value if cabs)
+//   c   = coef ? coef[k * cstride + head] : 1     (absolute value if cabs; head = which of the
+//                                                  `heads` equal column groups the lane's columns lie in)
 //   acc += c * src[row]
 // and acc goes to out[row_i] (whole segment) or partial[slot] (piece of a cut segment).
 struct GatherArgs {
@@ -208,6 +209,7 @@ struct GatherArgs {
     const float* coef;
     int cstride;
     int cabs;
+    int lanes_per_head;   // D/4 / heads
     const float* src;
     float* out;
     float* partial;
@@ -221,6 +223,7 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
     const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
     if (i >= a.it.n) return;
     const int b = a.it.beg[i], e = a.it.end[i];
+    const int head = c4 / a.lanes_per_head;
     float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
     for (int j = b; j < e; j += 4) {
         int row[4];
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
             if (j + u < e) {
                 const int k = a.via ? a.via[j + u] : j + u;
                 row[u] = a.row_by_k ? a.rowidx[k] : a.rowidx[j + u];
-                c[u] = a.coef ? a.coef[(size_t)k * a.cstride] : 1.f;
+                c[u] = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;
                 if (a.cabs) c[u] = fabsf(c[u]);
             }
         }
@@ -480,9 +483,9 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
 
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
                          const float* coef, int cstride, int cabs, const float* src, float* out, float* partial,
-                         hipStream_t st, int role, const char* label, const char* combine_label) {
+                         hipStream_t st, int role, const char* label, const char* combine_label, int heads) {
     if (L.num_items == 0) return RGNN_OK;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, src, out, partial};
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, (D / 4) / heads, src, out, partial};
     {
         KernelTimer kt(st, label);
         const dim3 grid(blocks_for(L.num_items, 256 / (D / 4)));

@@ -123,3 +123,38 @@ class RgcnLayer:
         if self.self_loop:
             g["dW0"] = self.dW0
         return g
+
+
+class HgtLayer:
+    def __init__(self, graph, d, heads, with_mu=True):
+        self.g, self.d, self.H = graph, d, heads
+        self.desc = B.make_desc(B.RGNN_F32, d, d, heads)
+        f, b, s = B.rgnn_workspace_bytes(graph.handle, B.RGNN_LAYER_HGT, self.desc)
+        self.ws = _buf(max(f, b))
+        self.saved = _buf(s)
+        N, R, T, dh = graph.N, graph.R, graph.T, d // heads
+        e = lambda *shape: torch.empty(*shape, device="cuda")
+        self.out, self.dX = e(N, d), e(N, d)
+        self.dWk, self.dWq, self.dWv, self.dWo = e(T, d, d), e(T, d, d), e(T, d, d), e(T, d, d)
+        self.dWatt, self.dWmsg = e(R, heads, dh, dh), e(R, heads, dh, dh)
+        self.dmu = e(R, heads) if with_mu else None
+
+    def load(self, X, Wk, Wq, Wv, Wo, Watt, Wmsg, mu=None, dOut=None):
+        (self.X, self.Wk, self.Wq, self.Wv, self.Wo, self.Watt, self.Wmsg, self.mu, self.dOut) = map(
+            _dev, (X, Wk, Wq, Wv, Wo, Watt, Wmsg, mu, dOut))
+
+    def fwd(self):
+        B.rgnn_hgt_fwd(self.g.handle, self.desc, self.X, self.Wk, self.Wq, self.Wv, self.Wo, self.Watt, self.Wmsg,
+                       self.mu, self.out, self.saved, self.ws, _stream())
+
+    def bwd(self):
+        B.rgnn_hgt_bwd(self.g.handle, self.desc, self.X, self.Wk, self.Wq, self.Wv, self.Wo, self.Watt, self.Wmsg,
+                       self.mu, self.out, self.saved, self.dOut, self.dX, self.dWk, self.dWq, self.dWv, self.dWo,
+                       self.dWatt, self.dWmsg, self.dmu, self.ws, _stream())
+
+    def grads(self):
+        g = dict(dX=self.dX, dWk=self.dWk, dWq=self.dWq, dWv=self.dWv, dWo=self.dWo, dWatt=self.dWatt,
+                 dWmsg=self.dWmsg)
+        if self.dmu is not None:
+            g["dmu"] = self.dmu
+        return g

@@ -1,0 +1,61 @@
+"""HGT layer (forward + backward) on the GPU vs the CPU oracle."""
+import numpy as np
+import pytest
+
+from oracle import layers as O
+from paper_2412_04747_amd import synth
+from parity import check, TOL_F32
+
+pytestmark = pytest.mark.gpu
+
+NAMES = ("X", "Wk", "Wq", "Wv", "Wo", "Watt", "Wmsg", "mu")
+
+
+def _run(N, T, R, src, dst, rel, ntype, p, d, H, tag):
+    import torch
+    from paper_2412_04747_amd.harness import Graph, HgtLayer
+    print(f"hgt case {tag}: N={N} T={T} R={R} E={len(src)} d={d} H={H} mu={'yes' if p['mu'] is not None else 'no'}",
+          flush=True)
+    g = Graph(N, R, src, dst, rel, ntype if T > 1 else None, T)
+    L = HgtLayer(g, d, H, with_mu=p["mu"] is not None)
+    L.load(*[p[k] for k in NAMES], dOut=p["dOut"])
+    L.fwd()
+    torch.cuda.synchronize()
+    nt = ntype if T > 1 else None
+    want = O.hgt_fwd(N, src, dst, rel, nt, *[p[k] for k in NAMES])
+    check(L.out, want, TOL_F32, "out")
+    L.bwd()
+    torch.cuda.synchronize()
+    wg = O.hgt_bwd(N, src, dst, rel, nt, *[p[k] for k in NAMES], p["dOut"])
+    errs = {k: check(v, wg[k], TOL_F32, k) for k, v in L.grads().items()}
+    print("   max rel errors:", {k: f"{v:.1e}" for k, v in errs.items()}, flush=True)
+    out1 = L.out.clone()
+    first = {k: v.clone() for k, v in L.grads().items()}
+    L.fwd(); L.bwd()
+    torch.cuda.synchronize()
+    assert torch.equal(out1, L.out)
+    for k, v in L.grads().items():
+        assert torch.equal(first[k], v), k
+    g.close()
+
+
+@pytest.mark.parametrize("d,H,mu", [(64, 2, True), (64, 4, False), (128, 4, True), (32, 1, True)])
+def test_small_typed(d, H, mu):
+    rng, src, dst, rel, ntype = synth.tiny(90 + d + H, N=600, R=5, E=5000, T=3)
+    p = synth.hgt_params(rng, 600, 3, 5, d, H, with_mu=mu)
+    _run(600, 3, 5, src, dst, rel, ntype, p, d, H, f"small-d{d}-H{H}")
+
+
+def test_hub_isolated_and_single_type():
+    rng, src, dst, rel, ntype = synth.tiny(95, N=300, R=4, E=4000, T=1)
+    dst[:2500] = 9
+    src[:700] = 4
+    rel[:700] = 2
+    p = synth.hgt_params(rng, 300, 1, 4, 64, 2, with_mu=True)
+    _run(300, 1, 4, src, dst, rel, ntype, p, 64, 2, "hub")
+
+
+def test_scaled_config4():
+    c = synth.config(4, scale=0.01)          # 20k nodes, 200k edges, 8 node types, 30 relations, d=128, H=4
+    c["mu"] = None
+    _run(c["N"], c["T"], c["R"], c["src"], c["dst"], c["rel"], c["ntype"], c, 128, 4, "C4/100")
