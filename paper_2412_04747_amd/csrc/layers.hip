@@ -21,10 +21,30 @@ struct Carver {
     }
 };
 
+// bfloat16 inputs: every bf16 tensor argument is widened to fp32 in a staging area that
+// follows the regular carve-out of the workspace, and the fp32 kernels run on the copies
+// (bf16 storage at the boundary, fp32 arithmetic and fp32 results).
+struct Bf16Stage {
+    Carver c;
+    bool on;
+    hipStream_t st;
+    rgnn_status_t status = RGNN_OK;
+    Bf16Stage(void* ws, size_t carved, bool bf16, hipStream_t s)
+        : c(ws ? static_cast<char*>(ws) + carved : nullptr), on(bf16), st(s) {}
+    // returns the fp32 view of `p` (n elements): p itself for fp32 input, the widened copy for bf16
+    const float* in(const void* p, size_t n) {
+        if (!on || !p) return static_cast<const float*>(p);
+        float* d = c.take<float>(n);
+        if (c.base && status == RGNN_OK) status = widen_bf16(n, static_cast<const uint16_t*>(p), d, st);
+        return d;
+    }
+    void reserve(size_t n) { if (on) (void)c.take<float>(n); }
+};
+
 rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int layer) {
     if (!g || !d) RGNN_FAIL(RGNN_EINVAL, "graph or desc is NULL");
     if (d->flags != 0) RGNN_FAIL(RGNN_EINVAL, "desc.flags must be 0");
-    if (d->dtype != RGNN_F32) RGNN_FAIL(RGNN_EUNSUPPORTED, "only RGNN_F32 is implemented");
+    if (d->dtype != RGNN_F32 && d->dtype != RGNN_BF16) RGNN_FAIL(RGNN_EINVAL, "unknown dtype %d", d->dtype);
     if (d->d_in != d->d_out || (d->d_in != 32 && d->d_in != 64 && d->d_in != 128))
         RGNN_FAIL(RGNN_EUNSUPPORTED, "need d_in == d_out in {32, 64, 128}, got %d -> %d", d->d_in, d->d_out);
     if (layer == RGNN_LAYER_RGAT && d->heads != 1) RGNN_FAIL(RGNN_EUNSUPPORTED, "RGAT supports heads == 1 only");
@@ -147,6 +167,22 @@ size_t carve_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* ba
     return c.off;
 }
 
+// Staging sizes, in the order the entry points widen their arguments.
+size_t stage_bytes(const rgnn_graph_t* g, int layer, const rgnn_layer_desc_t* d, bool bwd) {
+    Bf16Stage s(nullptr, 0, d->dtype == RGNN_BF16, nullptr);
+    const size_t N = g->N, R = g->R, T = g->T, di = d->d_in, dz = d->d_out;
+    s.reserve(N * di);                                   // X
+    if (layer == RGNN_LAYER_RGCN) { s.reserve(R * di * dz); s.reserve(di * dz); }
+    if (layer == RGNN_LAYER_RGAT) { s.reserve(R * di * dz); s.reserve(R * dz); s.reserve(R * dz); }
+    if (layer == RGNN_LAYER_HGT) {
+        const size_t dh = dz / d->heads;
+        for (int i = 0; i < 4; ++i) s.reserve(T * dz * dz);
+        s.reserve(R * d->heads * dh * dh); s.reserve(R * d->heads * dh * dh); s.reserve(R * d->heads);
+    }
+    if (bwd) s.reserve(N * dz);                          // dOut
+    return s.c.off;
+}
+
 }  // namespace
 
 extern "C" rgnn_status_t rgnn_workspace_bytes(const rgnn_graph_t* g, int32_t layer, const rgnn_layer_desc_t* desc,
@@ -171,6 +207,8 @@ extern "C" rgnn_status_t rgnn_workspace_bytes(const rgnn_graph_t* g, int32_t lay
         b = carve_hgt_bwd(g, desc, nullptr, &bw);
         s = carve_hgt_saved(g, desc, nullptr, &sv);
     }
+    f += stage_bytes(g, layer, desc, false);
+    b += stage_bytes(g, layer, desc, true);
     if (fwd_workspace) *fwd_workspace = f;
     if (bwd_workspace) *bwd_workspace = b;
     if (saved) *saved = s;
@@ -189,7 +227,11 @@ extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out;
     RgcnFwdWs w;
-    carve_rgcn_fwd(g, desc, workspace, &w);
+    Bf16Stage stg(workspace, carve_rgcn_fwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    X = stg.in(X, (size_t)g->N * desc->d_in);
+    W = stg.in(W, (size_t)g->R * desc->d_in * D);
+    W0 = stg.in(W0, (size_t)desc->d_in * D);
+    RGNN_TRY(stg.status);
     // 1. compact messages: Hs[p] = X[pair_src[p]] W[rel(p)]
     TypedLinearArgs a{};
     a.tiles = &g->pair_tiles; a.X = static_cast<const float*>(X); a.gather = g->idx[RGNN_IDX_PAIR_SRC];
@@ -223,7 +265,12 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, K = desc->d_in;
     RgcnBwdWs w;
-    carve_rgcn_bwd(g, desc, workspace, &w);
+    Bf16Stage stg(workspace, carve_rgcn_bwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    X = stg.in(X, (size_t)g->N * K);
+    W = stg.in(W, (size_t)g->R * K * D);
+    if (W0) W0 = stg.in(W0, (size_t)K * D); else stg.reserve((size_t)K * D);
+    dOut = stg.in(dOut, (size_t)g->N * D);
+    RGNN_TRY(stg.status);
     const float* dPre = static_cast<const float*>(dOut);
     if (desc->activation == RGNN_ACT_RELU) {
         RGNN_TRY(relu_grad((size_t)g->N * D, static_cast<const float*>(out), dPre, w.dPre, st));
@@ -261,7 +308,12 @@ extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, K = desc->d_in;
     RgatFwdWs w; RgatSaved sv;
-    carve_rgat_fwd(g, desc, workspace, &w);
+    Bf16Stage stg(workspace, carve_rgat_fwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    X = stg.in(X, (size_t)g->N * K);
+    W = stg.in(W, (size_t)g->R * K * D);
+    w_s = stg.in(w_s, (size_t)g->R * D);
+    w_t = stg.in(w_t, (size_t)g->R * D);
+    RGNN_TRY(stg.status);
     carve_rgat_saved(g, desc, saved, &sv);
     // 1. compact messages and the source half of the logit:
     //    Hs[p] = X[pair_src[p]] W[r];  s_src[p] = Hs[p] . w_s[r]
@@ -291,7 +343,13 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, K = desc->d_in;
     RgatBwdWs w; RgatSaved sv;
-    carve_rgat_bwd(g, desc, workspace, &w);
+    Bf16Stage stg(workspace, carve_rgat_bwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    X = stg.in(X, (size_t)g->N * K);
+    W = stg.in(W, (size_t)g->R * K * D);
+    w_s = stg.in(w_s, (size_t)g->R * D);
+    w_t = stg.in(w_t, (size_t)g->R * D);
+    dOut = stg.in(dOut, (size_t)g->N * D);
+    RGNN_TRY(stg.status);
     carve_rgat_saved(g, desc, const_cast<void*>(saved), &sv);
     const float* Xf = static_cast<const float*>(X);
     const float* Wf = static_cast<const float*>(W);
@@ -368,7 +426,15 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, H = desc->heads;
     HgtFwdWs w; HgtSaved sv;
-    carve_hgt_fwd(g, desc, workspace, &w);
+    Bf16Stage stg(workspace, carve_hgt_fwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    {
+        const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
+        X = stg.in(X, (size_t)g->N * D);
+        Wk = stg.in(Wk, tdd); Wq = stg.in(Wq, tdd); Wv = stg.in(Wv, tdd); Wo = stg.in(Wo, tdd);
+        Watt = stg.in(Watt, rh * dh * dh); Wmsg = stg.in(Wmsg, rh * dh * dh);
+        if (mu) mu = stg.in(mu, rh); else stg.reserve(rh);
+        RGNN_TRY(stg.status);
+    }
     carve_hgt_saved(g, desc, saved, &sv);
     const float* Xf = static_cast<const float*>(X);
     // 1. per node type: K, Q, V
@@ -406,7 +472,16 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, H = desc->heads;
     HgtBwdWs w; HgtSaved sv;
-    carve_hgt_bwd(g, desc, workspace, &w);
+    Bf16Stage stg(workspace, carve_hgt_bwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    {
+        const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
+        X = stg.in(X, (size_t)g->N * D);
+        Wk = stg.in(Wk, tdd); Wq = stg.in(Wq, tdd); Wv = stg.in(Wv, tdd); Wo = stg.in(Wo, tdd);
+        Watt = stg.in(Watt, rh * dh * dh); Wmsg = stg.in(Wmsg, rh * dh * dh);
+        if (mu) mu = stg.in(mu, rh); else stg.reserve(rh);
+        dOut = stg.in(dOut, (size_t)g->N * D);
+        RGNN_TRY(stg.status);
+    }
     carve_hgt_saved(g, desc, const_cast<void*>(saved), &sv);
     const float* Xf = static_cast<const float*>(X);
     const float* dO = static_cast<const float*>(dOut);

@@ -30,6 +30,7 @@ rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* a
                                const float* Z, float* dl, hipStream_t st);
 rgnn_status_t add3(size_t n, const float* a, const float* b, const float* c, float* out, hipStream_t st);
 
+rgnn_status_t widen_bf16(size_t n, const uint16_t* src, float* dst, hipStream_t st);
 rgnn_status_t relu_inplace(size_t n, float* x, hipStream_t st);
 rgnn_status_t relu_grad(size_t n, const float* ref, const float* gin, float* y, hipStream_t st);
 

@@ -411,6 +411,12 @@ __global__ void relu_grad_kernel(size_t n, const float* __restrict__ ref, const 
     if (i < n) y[i] = ref[i] > 0.f ? g[i] : 0.f;
 }
 
+// bfloat16 -> fp32 (exact: the bf16 bits are the upper half of the fp32 word)
+__global__ void widen_bf16_kernel(size_t n, const uint16_t* __restrict__ src, float* __restrict__ dst) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = __uint_as_float((uint32_t)src[i] << 16);
+}
+
 // ==================================================================== host launchers
 
 #define CHECK_LAUNCH() RGNN_HIP(hipGetLastError())
@@ -535,6 +541,13 @@ rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const flo
     return RGNN_OK;
 }
 
+rgnn_status_t widen_bf16(size_t n, const uint16_t* src, float* dst, hipStream_t st) {
+    if (n == 0) return RGNN_OK;
+    KernelTimer kt(st, "widen_bf16");
+    hipLaunchKernelGGL(widen_bf16_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, src, dst);
+    CHECK_LAUNCH();
+    return RGNN_OK;
+}
 rgnn_status_t relu_inplace(size_t n, float* x, hipStream_t st) {
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, "relu");

@@ -15,6 +15,12 @@ def _dev(a, dtype=torch.float32):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda", dtype=dtype)
 
 
+def _tdtype(name):
+    """Storage type of the tensor arguments: "f32", or "bf16" (values must already be
+    bf16-representable, e.g. from synth.round_to_bf16, so the conversion is exact)."""
+    return (B.RGNN_BF16, torch.bfloat16) if name == "bf16" else (B.RGNN_F32, torch.float32)
+
+
 def _buf(nbytes):
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
 
@@ -56,9 +62,10 @@ class Graph:
 class RgatLayer:
     """Device buffers for one RGAT layer call pair on a graph."""
 
-    def __init__(self, graph, d, slope=0.2):
+    def __init__(self, graph, d, slope=0.2, dtype="f32"):
         self.g, self.d = graph, d
-        self.desc = B.make_desc(B.RGNN_F32, d, d, 1, slope)
+        code, self.tdt = _tdtype(dtype)
+        self.desc = B.make_desc(code, d, d, 1, slope)
         f, b, s = B.rgnn_workspace_bytes(graph.handle, B.RGNN_LAYER_RGAT, self.desc)
         self.ws = _buf(max(f, b))
         self.saved = _buf(s)
@@ -70,7 +77,8 @@ class RgatLayer:
         self.dw_t = torch.empty(R, d, device="cuda")
 
     def load(self, X, W, w_s, w_t, dOut=None):
-        self.X, self.W, self.w_s, self.w_t, self.dOut = _dev(X), _dev(W), _dev(w_s), _dev(w_t), _dev(dOut)
+        t = self.tdt
+        self.X, self.W, self.w_s, self.w_t, self.dOut = _dev(X, t), _dev(W, t), _dev(w_s, t), _dev(w_t, t), _dev(dOut, t)
 
     def fwd(self):
         B.rgnn_rgat_fwd(self.g.handle, self.desc, self.X, self.W, self.w_s, self.w_t, self.out, self.saved, self.ws,
@@ -94,9 +102,10 @@ class RgatLayer:
 
 
 class RgcnLayer:
-    def __init__(self, graph, d, norm="in_degree_per_rel", act="none", self_loop=False):
+    def __init__(self, graph, d, norm="in_degree_per_rel", act="none", self_loop=False, dtype="f32"):
         self.g, self.d, self.self_loop = graph, d, self_loop
-        self.desc = B.make_desc(B.RGNN_F32, d, d, 1, 0.0,
+        code, self.tdt = _tdtype(dtype)
+        self.desc = B.make_desc(code, d, d, 1, 0.0,
                                 B.RGNN_NORM_IN_DEGREE_PER_REL if norm == "in_degree_per_rel" else B.RGNN_NORM_NONE,
                                 B.RGNN_ACT_RELU if act == "relu" else B.RGNN_ACT_NONE)
         f, b, s = B.rgnn_workspace_bytes(graph.handle, B.RGNN_LAYER_RGCN, self.desc)
@@ -109,7 +118,8 @@ class RgcnLayer:
         self.dW0 = torch.empty(d, d, device="cuda") if self_loop else None
 
     def load(self, X, W, W0=None, dOut=None):
-        self.X, self.W, self.W0, self.dOut = _dev(X), _dev(W), _dev(W0), _dev(dOut)
+        t = self.tdt
+        self.X, self.W, self.W0, self.dOut = _dev(X, t), _dev(W, t), _dev(W0, t), _dev(dOut, t)
 
     def fwd(self):
         B.rgnn_rgcn_fwd(self.g.handle, self.desc, self.X, self.W, self.W0, self.out, self.saved, self.ws, _stream())
@@ -126,9 +136,10 @@ class RgcnLayer:
 
 
 class HgtLayer:
-    def __init__(self, graph, d, heads, with_mu=True):
+    def __init__(self, graph, d, heads, with_mu=True, dtype="f32"):
         self.g, self.d, self.H = graph, d, heads
-        self.desc = B.make_desc(B.RGNN_F32, d, d, heads)
+        code, self.tdt = _tdtype(dtype)
+        self.desc = B.make_desc(code, d, d, heads)
         f, b, s = B.rgnn_workspace_bytes(graph.handle, B.RGNN_LAYER_HGT, self.desc)
         self.ws = _buf(max(f, b))
         self.saved = _buf(s)
@@ -140,8 +151,8 @@ class HgtLayer:
         self.dmu = e(R, heads) if with_mu else None
 
     def load(self, X, Wk, Wq, Wv, Wo, Watt, Wmsg, mu=None, dOut=None):
-        (self.X, self.Wk, self.Wq, self.Wv, self.Wo, self.Watt, self.Wmsg, self.mu, self.dOut) = map(
-            _dev, (X, Wk, Wq, Wv, Wo, Watt, Wmsg, mu, dOut))
+        (self.X, self.Wk, self.Wq, self.Wv, self.Wo, self.Watt, self.Wmsg, self.mu, self.dOut) = (
+            _dev(a, self.tdt) for a in (X, Wk, Wq, Wv, Wo, Watt, Wmsg, mu, dOut))
 
     def fwd(self):
         B.rgnn_hgt_fwd(self.g.handle, self.desc, self.X, self.Wk, self.Wq, self.Wv, self.Wo, self.Watt, self.Wmsg,

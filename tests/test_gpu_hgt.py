@@ -4,31 +4,35 @@ import pytest
 
 from oracle import layers as O
 from paper_2412_04747_amd import synth
-from parity import check, TOL_F32
+from parity import check, TOL_F32, TOL_BF16
 
 pytestmark = pytest.mark.gpu
 
 NAMES = ("X", "Wk", "Wq", "Wv", "Wo", "Watt", "Wmsg", "mu")
 
 
-def _run(N, T, R, src, dst, rel, ntype, p, d, H, tag):
+def _run(N, T, R, src, dst, rel, ntype, p, d, H, tag, dtype="f32", repeat=True):
     import torch
     from paper_2412_04747_amd.harness import Graph, HgtLayer
     print(f"hgt case {tag}: N={N} T={T} R={R} E={len(src)} d={d} H={H} mu={'yes' if p['mu'] is not None else 'no'}",
           flush=True)
     g = Graph(N, R, src, dst, rel, ntype if T > 1 else None, T)
-    L = HgtLayer(g, d, H, with_mu=p["mu"] is not None)
+    L = HgtLayer(g, d, H, with_mu=p["mu"] is not None, dtype=dtype)
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
     L.load(*[p[k] for k in NAMES], dOut=p["dOut"])
     L.fwd()
     torch.cuda.synchronize()
     nt = ntype if T > 1 else None
     want = O.hgt_fwd(N, src, dst, rel, nt, *[p[k] for k in NAMES])
-    check(L.out, want, TOL_F32, "out")
+    check(L.out, want, tol, "out")
     L.bwd()
     torch.cuda.synchronize()
     wg = O.hgt_bwd(N, src, dst, rel, nt, *[p[k] for k in NAMES], p["dOut"])
-    errs = {k: check(v, wg[k], TOL_F32, k) for k, v in L.grads().items()}
+    errs = {k: check(v, wg[k], tol, k) for k, v in L.grads().items()}
     print("   max rel errors:", {k: f"{v:.1e}" for k, v in errs.items()}, flush=True)
+    if not repeat:
+        g.close()
+        return
     out1 = L.out.clone()
     first = {k: v.clone() for k, v in L.grads().items()}
     L.fwd(); L.bwd()
@@ -55,7 +59,15 @@ def test_hub_isolated_and_single_type():
     _run(300, 1, 4, src, dst, rel, ntype, p, 64, 2, "hub")
 
 
-def test_scaled_config4():
+def test_scaled_config4_bf16():
     c = synth.config(4, scale=0.01)          # 20k nodes, 200k edges, 8 node types, 30 relations, d=128, H=4
     c["mu"] = None
-    _run(c["N"], c["T"], c["R"], c["src"], c["dst"], c["rel"], c["ntype"], c, 128, 4, "C4/100")
+    _run(c["N"], c["T"], c["R"], c["src"], c["dst"], c["rel"], c["ntype"], c, 128, 4, "C4/100", dtype="bf16")
+
+
+@pytest.mark.timeout(1100)
+def test_config4_full_size_bf16():
+    """2M nodes of 8 types, 30 relations, 20M edges, hidden 128 in 4 heads, bf16 inputs."""
+    c = synth.config(4)
+    c["mu"] = None
+    _run(c["N"], c["T"], c["R"], c["src"], c["dst"], c["rel"], c["ntype"], c, 128, 4, "C4", dtype="bf16", repeat=False)

@@ -4,29 +4,30 @@ import pytest
 
 from oracle import layers as O
 from paper_2412_04747_amd import synth
-from parity import check, TOL_F32
+from parity import check, TOL_F32, TOL_BF16
 
 pytestmark = pytest.mark.gpu
 
 
-def _run(N, R, src, dst, rel, p, d, norm, act, self_loop, bwd=True, tag=""):
+def _run(N, R, src, dst, rel, p, d, norm, act, self_loop, bwd=True, tag="", dtype="f32"):
     import torch
     from paper_2412_04747_amd.harness import Graph, RgcnLayer
     print(f"rgcn case {tag}: N={N} R={R} E={len(src)} d={d} norm={norm} act={act} W0={self_loop}", flush=True)
     g = Graph(N, R, src, dst, rel)
-    L = RgcnLayer(g, d, norm, act, self_loop)
+    L = RgcnLayer(g, d, norm, act, self_loop, dtype=dtype)
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
     W0 = p["W0"] if self_loop else None
     L.load(p["X"], p["W"], W0, p["dOut"])
     L.fwd()
     torch.cuda.synchronize()
     want = O.rgcn_fwd(N, src, dst, rel, p["X"], p["W"], W0, norm, act)
-    check(L.out, want, TOL_F32, "out")
+    check(L.out, want, tol, "out")
     if bwd:
         L.bwd()
         torch.cuda.synchronize()
         wg = O.rgcn_bwd(N, src, dst, rel, p["X"], p["W"], W0, p["dOut"], norm, act, out=want)
         for k, v in L.grads().items():
-            check(v, wg[k], TOL_F32, k)
+            check(v, wg[k], tol, k)
     g.close()
 
 
@@ -58,3 +59,17 @@ def test_empty_graph():
     p = synth.rgcn_params(rng, 10, 2, 32, 32, self_loop=True)
     e = np.zeros(0, np.int32)
     _run(10, 2, e, e, e, p, 32, "in_degree_per_rel", "none", True, tag="empty")
+
+
+def test_scaled_config5_bf16():
+    c = synth.config(5, scale=0.01)          # knowledge-graph shaped: 500 relations, many with a handful of edges
+    _run(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 128, "in_degree_per_rel", "none", False, tag="C5/100",
+         dtype="bf16")
+
+
+@pytest.mark.timeout(1100)
+def test_config5_full_size_bf16():
+    """2.5M nodes, 500 relations (100 of them with fewer than 100 edges), 16M edges, d=128, bf16 inputs."""
+    c = synth.config(5)
+    _run(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 128, "in_degree_per_rel", "none", False, tag="C5",
+         dtype="bf16")
