@@ -21,22 +21,29 @@ HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
-def algorithmic_work(name, E, N, P, Q, R, d):
-    """(bound, bytes, flops) one launch of kernel `name` must move / compute (fp32, b = 4).
-    Gathered rows are counted once per reference (no cache reuse assumed); index and scalar
-    traffic as listed; see DESIGN.md "Kernels and their rooflines"."""
+def algorithmic_work(name, E, N, P, Q, R, T, d, H):
+    """(bound, bytes, flops) one launch of kernel `name` must move / compute (fp32 arithmetic,
+    4-byte elements).  Gathered rows are counted once per reference (no cache reuse assumed);
+    index and scalar traffic as listed; see DESIGN.md "Kernels and their rooflines"."""
     b = 4
     row = d * b
+    w2 = d * d * b
+    pair_fwd = ("mfma", P * (2 * row + 4) + R * w2, 2.0 * P * d * d)        # gathered row + stored row + pair_src
+    pair_bwd = ("mfma", P * (3 * row + 4) + R * w2, 4.0 * P * d * d)        # dY row + gathered row + stored row
+    node_fwd = ("mfma", N * (2 * row + 4) + T * w2, 2.0 * N * d * d)
+    node_bwd = ("mfma", N * (3 * row + 4) + T * w2, 4.0 * N * d * d)
+    agg_dst = ("hbm", E * (row + 4 + 4 * H) + N * (row + 8), 2.0 * E * d)    # row + in_pair + coefficient(s); out row + item
+    agg_pair = ("hbm", E * (row + 8 + 4 * H) + P * (row + 8), 2.0 * E * d)   # row + out_epos + out_dst + coefficient(s)
     table = {
-        # per pair: gathered X row + stored Hs row + pair_src + s_src; weights once
-        "typed_linear_fwd": ("mfma", P * (2 * row + 8) + R * d * d * b, 2.0 * P * d * d),
-        # per pair: G row + gathered X row + stored dXp row + pair_src + ds_src; weights once, dW slots ignored
-        "typed_linear_bwd": ("mfma", P * (3 * row + 8) + R * d * d * b, 4.0 * P * d * d),
-        # per edge: Hs row + in_pair + att; per node: out row + item (beg, end)
-        "aggregate_fwd": ("hbm", E * (row + 8) + N * (row + 8), 2.0 * E * d),
+        # RGAT: + s_src per pair; backward also reads ds_src
+        "typed_linear_fwd": ("mfma", pair_fwd[1] + P * 4, pair_fwd[2]),
+        "typed_linear_bwd": ("mfma", pair_bwd[1] + P * 4, pair_bwd[2]),
+        "self_loop_fwd": ("mfma", N * 3 * row + w2, 2.0 * N * d * d),         # X row + out row read and written
+        "self_loop_bwd": ("mfma", N * 3 * row + w2, 4.0 * N * d * d),
+        "aggregate_fwd": agg_dst,
         # per edge: Hs row + in_pair + att + (att, dz) store; per node: dOut row + out row + item
         "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8), 2.0 * E * d),
-        # per edge: dOut row + out_epos + out_dst + (att, dz); per pair: G row + item
+        # RGAT: the coefficient is the (att, dz) pair
         "aggregate_bwd_pair": ("hbm", E * (row + 16) + P * (row + 8), 2.0 * E * d),
         # per run: X row + relrun_idx + run_dst + ds_dst
         "dst_side_wgrad": ("hbm", Q * (row + 12), 2.0 * Q * d),
@@ -45,8 +52,59 @@ def algorithmic_work(name, E, N, P, Q, R, d):
         # per edge: in_pair, in_run, s_src, s_dst, att write (reads of its own writes not counted)
         "edge_softmax": ("hbm", E * 20 + N * 8, 10.0 * E),
         "run_logit": ("hbm", Q * (row + 12), 2.0 * Q * d),
+        # HGT
+        "node_linear_k": node_fwd, "node_linear_q": node_fwd, "node_linear_v": node_fwd, "node_linear_out": node_fwd,
+        "node_linear_k_bwd": node_bwd, "node_linear_q_bwd": node_bwd, "node_linear_v_bwd": node_bwd,
+        "node_linear_out_bwd": node_bwd,
+        "pair_linear_att": pair_fwd, "pair_linear_msg": pair_fwd,
+        "pair_linear_att_bwd": pair_bwd, "pair_linear_msg_bwd": pair_bwd,
+        "hgt_edge_logit": ("hbm", E * (row + 4 + 4 * H) + N * (row + 8), 2.0 * E * d),
+        "hgt_edge_dot_bwd": ("hbm", E * (row + 4 + 8 * H) + N * (2 * row + 8), 2.0 * E * d),
+        "hgt_softmax": ("hbm", E * H * 8 + N * 8, 10.0 * E * H),
+        "aggregate_bwd_msg": agg_pair, "aggregate_bwd_key": agg_pair, "aggregate_bwd_query": agg_dst,
     }
     return table.get(name)
+
+
+def make_layer(c, g):
+    """-> (layer object, forward-only?) for workload dict c on graph g."""
+    from paper_2412_04747_amd.harness import RgatLayer, RgcnLayer, HgtLayer
+    d, dt = c["d_out"], c["dtype"]
+    if c["layer"] == "rgat":
+        L = RgatLayer(g, d, c["slope"], dtype=dt)
+        L.load(c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"])
+    elif c["layer"] == "rgcn":
+        L = RgcnLayer(g, d, c["norm"], "none", False, dtype=dt)
+        L.load(c["X"], c["W"], None, c["dOut"])
+    else:
+        L = HgtLayer(g, d, c["H"], with_mu=False, dtype=dt)
+        L.load(c["X"], c["Wk"], c["Wq"], c["Wv"], c["Wo"], c["Watt"], c["Wmsg"], None, c["dOut"])
+    return L
+
+
+def run_oracle(c):
+    """-> (dict of expected outputs, seconds forward, seconds backward)."""
+    from oracle import layers as O
+    N, s, t, r = c["N"], c["src"], c["dst"], c["rel"]
+    t0 = time.time()
+    if c["layer"] == "rgat":
+        out = O.rgat_fwd(N, s, t, r, c["X"], c["W"], c["w_s"], c["w_t"], c["slope"])
+        tf = time.time() - t0; t0 = time.time()
+        want = O.rgat_bwd(N, s, t, r, c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"], c["slope"])
+    elif c["layer"] == "rgcn":
+        out = O.rgcn_fwd(N, s, t, r, c["X"], c["W"], None, c["norm"], "none")
+        tf = time.time() - t0; t0 = time.time()
+        want = {} if c["cid"] == 1 else O.rgcn_bwd(N, s, t, r, c["X"], c["W"], None, c["dOut"], c["norm"], "none", out=out)
+        want.pop("dW0", None)
+    else:
+        names = ("X", "Wk", "Wq", "Wv", "Wo", "Watt", "Wmsg")
+        out = O.hgt_fwd(N, s, t, r, c["ntype"], *[c[k] for k in names], None)
+        tf = time.time() - t0; t0 = time.time()
+        want = O.hgt_bwd(N, s, t, r, c["ntype"], *[c[k] for k in names], None, c["dOut"])
+        want.pop("dmu", None)
+    tb = time.time() - t0
+    want["out"] = out
+    return want, tf, tb
 
 
 def main():
@@ -54,7 +112,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=3, help="synthetic workload id (3 = headline RGAT graph)")
+    ap.add_argument("--config", type=int, default=3,
+                    help="synthetic workload id 1..5 (default 3 = the headline RGAT graph the metric is quoted on)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle leg (no cpu_baseline, no parity)")
     args = ap.parse_args()
@@ -65,38 +124,39 @@ def main():
     import numpy as np
     import torch
     from paper_2412_04747_amd import synth, binding as B
-    from paper_2412_04747_amd.harness import Graph, RgatLayer
+    from paper_2412_04747_amd.harness import Graph
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     t0 = time.time()
     c = synth.config(args.config, args.scale)
-    assert c["layer"] == "rgat", "bench.py times the RGAT workloads (configs 2 and 3)"
-    N, R, E, d = c["N"], c["R"], c["E"], c["d_out"]
-    print(f"[bench] generated config {args.config}: N={N} R={R} E={E} d={d} in {time.time() - t0:.1f}s",
-          file=sys.stderr, flush=True)
+    N, R, E, d, T, H = c["N"], c["R"], c["E"], c["d_out"], c["T"], c["H"]
+    fwd_only = c["cid"] == 1
+    print(f"[bench] generated config {args.config} ({c['layer']}, {c['dtype']}): N={N} T={T} R={R} E={E} d={d} H={H} "
+          f"in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
     cpu = None
     want = None
     if not args.no_oracle:
         from oracle import layers as O
-        t0 = time.time()
-        want_out = O.rgat_fwd(N, c["src"], c["dst"], c["rel"], c["X"], c["W"], c["w_s"], c["w_t"], c["slope"])
-        t_f = time.time() - t0
-        t0 = time.time()
-        want = O.rgat_bwd(N, c["src"], c["dst"], c["rel"], c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"], c["slope"])
-        t_b = time.time() - t0
-        want["out"] = want_out
+        want, t_f, t_b = run_oracle(c)
+        if fwd_only:
+            t_b = 0.0
         cpu = {"value": E / (t_f + t_b), "unit": "edges/s", "cores": O.num_threads(), "kind": "oracle",
                "sample": f"full workload, 1 repetition (fwd {t_f:.2f}s + bwd {t_b:.2f}s)"}
         print(f"[bench] oracle fwd {t_f:.2f}s bwd {t_b:.2f}s on {O.num_threads()} threads", file=sys.stderr, flush=True)
 
     t0 = time.time()
-    g = Graph(N, R, c["src"], c["dst"], c["rel"])
+    g = Graph(N, R, c["src"], c["dst"], c["rel"], c.get("ntype") if T > 1 else None, T,
+              c.get("rel_src_ntype"), c.get("rel_dst_ntype"))
     P, Q = g.P, g.Q
     print(f"[bench] graph index built in {time.time() - t0:.1f}s: P/E={P / E:.3f} Q/E={Q / E:.3f} "
           f"max in-degree {g.info.max_in_degree} index {g.info.index_bytes / 2**20:.0f} MiB", file=sys.stderr, flush=True)
-    L = RgatLayer(g, d, c["slope"])
-    L.load(c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"])
+    L = make_layer(c, g)
+
+    def step():
+        L.fwd()
+        if not fwd_only:
+            L.bwd()
 
     # One plain 1 GiB device-to-device copy before the timed region: a kernel of known size
     # against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are calibrated.
@@ -107,12 +167,12 @@ def main():
     del cal
 
     for _ in range(args.warmup):
-        L.fwd(); L.bwd()
+        step()
     torch.cuda.synchronize()
     # untimed clean pass, to show what the profiling events cost
     tc = time.perf_counter()
     for _ in range(args.steps):
-        L.fwd(); L.bwd()
+        step()
     torch.cuda.synchronize()
     clean_ms = (time.perf_counter() - tc) * 1e3 / args.steps
 
@@ -120,7 +180,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        L.fwd(); L.bwd()
+        step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     rep = B.rgnn_profile_stop()
@@ -129,8 +189,10 @@ def main():
     parity = None
     if want is not None:
         parity = {}
-        got = dict(out=L.out, **L.grads())
+        got = dict(out=L.out, **({} if fwd_only else L.grads()))
         for k, v in got.items():
+            if k not in want:
+                continue
             a = v.cpu().numpy().astype(np.float64)
             parity[k] = float(np.abs(a - want[k]).max() / max(np.abs(want[k]).max(), 1e-30))
         print(f"[bench] max relative error vs oracle: {parity}", file=sys.stderr, flush=True)
@@ -138,7 +200,7 @@ def main():
     kernels = []
     for name, (n, ms) in rep.items():
         avg_ms = ms / n
-        w = algorithmic_work(name, E, N, P, Q, R, d)
+        w = algorithmic_work(name, E, N, P, Q, R, T, d, H)
         row = {"name": name, "launches_per_step": n / args.steps, "avg_ms": avg_ms, "ms_per_step": ms / args.steps}
         if w:
             row["GBps"] = w[1] / avg_ms / 1e6
@@ -151,7 +213,7 @@ def main():
             gb=f"{r['GBps']:.0f}" if "GBps" in r else "-", tf=f"{r['TFLOPs']:.1f}" if "TFLOPs" in r else "-", **r),
             file=sys.stderr, flush=True)
     dom = kernels[0]
-    w = algorithmic_work(dom["name"], E, N, P, Q, R, d)
+    w = algorithmic_work(dom["name"], E, N, P, Q, R, T, d, H)
     if w and w[0] == "mfma":
         roof = {"kernel": dom["name"], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": FP32_MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": dom["TFLOPs"] / FP32_MFMA_PEAK_TFLOPS, "traffic": None}
@@ -171,10 +233,12 @@ def main():
     roof["algorithmic_bytes"] = w[1] if w else None
 
     line = {
-        "metric": "edges/sec for RGAT layer fwd+bwd", "value": E * args.steps / dt, "unit": "edges/s",
+        "metric": f"edges/sec for {c['layer'].upper()} layer {'fwd' if fwd_only else 'fwd+bwd'}",
+        "value": E * args.steps / dt, "unit": "edges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"configs[{args.config - 1}]: RGAT single-head fwd+bwd fp32, N={N}, R={R}, E={E}, d={d}"
+        "config": {"workload": f"configs[{args.config - 1}]: {c['layer'].upper()} {'fwd' if fwd_only else 'fwd+bwd'}, "
+                               f"{c['dtype']} inputs, N={N}, T={T}, R={R}, E={E}, d={d}, H={H}"
                                + ("" if args.scale == 1.0 else f" (scale {args.scale})"),
                    "P_over_E": P / E, "Q_over_E": Q / E, "max_in_degree": int(g.info.max_in_degree)},
         "roofline": roof,

@@ -69,8 +69,10 @@ typedef struct {
 } rgnn_graph_info_t;
 
 /* Parameters of one layer call.  Fields a layer does not use are ignored.
- *   dtype      storage type of the tensor arguments (RGNN_F32; RGNN_BF16 = bfloat16
- *              inputs, fp32 accumulation, fp32 outputs and gradients).
+ *   dtype      storage type of the INPUT tensor arguments (X, every weight, dOut):
+ *              RGNN_F32, or RGNN_BF16 = bfloat16 inputs.  Arithmetic is fp32 and every
+ *              output (out, all gradients) and the `out` argument of the backward calls
+ *              are fp32 in both cases.
  *   d_in,d_out feature widths.  Supported: d_in == d_out in {32, 64, 128}.
  *   heads      HGT: number of heads H (d_out % H == 0, d_out/H in {16, 32, 64}); RGAT: must be 1.
  *   slope      RGAT leaky-ReLU negative slope (the derivative at 0 is `slope`).

@@ -57,3 +57,55 @@ def test_bad_ids_are_rejected():
         Graph(3, 2, np.array([0], np.int32), np.array([1], np.int32), np.array([0], np.int32),
               ntype=np.array([0, 1, 1], np.int32), T=2, rel_src_ntype=np.array([1, 0], np.int32),
               rel_dst_ntype=np.array([1, 0], np.int32))
+
+
+def test_csr_input_and_device_input_match_coo():
+    """RGNN_CSR_DST input and device-resident input arrays give the same index as host COO."""
+    import torch
+    from paper_2412_04747_amd import binding as B
+    _, src, dst, rel, _ = synth.tiny(6, 80, 5, 900)
+    N, R, E = 80, 5, len(src)
+    want = graph_index.build(N, R, src, dst, rel)
+    # CSR by destination: any edge order inside a row
+    order = np.argsort(dst, kind="stable")
+    rowptr = np.concatenate([[0], np.cumsum(np.bincount(dst, minlength=N))]).astype(np.int32)
+    col, r2 = np.ascontiguousarray(src[order]), np.ascontiguousarray(rel[order])
+    g = B.rgnn_graph_create(N, 1, R, E, B.RGNN_CSR_DST, col, rowptr, r2, mem=B.RGNN_MEM_HOST)
+    for name in ("in_ptr", "in_src", "in_rel", "in_pair", "out_epos", "relrun_idx"):
+        got = B.rgnn_graph_export(g, B.INDEX_NAMES.index(name), len(want[name]))
+        assert np.array_equal(got, want[name]), name
+    B.rgnn_graph_destroy(g)
+    # device-resident COO
+    dev = [torch.from_numpy(a).cuda() for a in (src, dst, rel)]
+    g = B.rgnn_graph_create(N, 1, R, E, B.RGNN_COO, dev[0], dev[1], dev[2], mem=B.RGNN_MEM_DEVICE)
+    for name in B.INDEX_NAMES[:19]:
+        got = B.rgnn_graph_export(g, B.INDEX_NAMES.index(name), len(want[name]))
+        assert np.array_equal(got, want[name]), name
+    B.rgnn_graph_destroy(g)
+    # a row pointer that does not end at E is rejected
+    bad = rowptr.copy(); bad[-1] -= 1
+    with pytest.raises(B.RgnnError):
+        B.rgnn_graph_create(N, 1, R, E, B.RGNN_CSR_DST, col, bad, r2)
+
+
+def test_layer_argument_errors():
+    import torch
+    from paper_2412_04747_amd import binding as B
+    from paper_2412_04747_amd.harness import Graph
+    _, src, dst, rel, _ = synth.tiny(7, 20, 2, 50)
+    g = Graph(20, 2, src, dst, rel)
+    x = torch.zeros(20, 64, device="cuda")
+    for bad, status in ((B.make_desc(d_in=48, d_out=48), 2), (B.make_desc(d_in=64, d_out=32), 2),
+                        (B.make_desc(heads=2), 2), (B.make_desc(flags=1), 1), (B.make_desc(dtype=7), 1)):
+        with pytest.raises(B.RgnnError) as e:
+            B.rgnn_rgat_fwd(g.handle, bad, x, x, x, x, x, x, x)
+        assert e.value.status == status
+    with pytest.raises(B.RgnnError) as e:
+        B.rgnn_rgat_fwd(g.handle, B.make_desc(), x, x, x, x, x, None, x)     # saved missing
+    assert e.value.status == 5
+    with pytest.raises(B.RgnnError) as e:
+        B.rgnn_rgat_fwd(g.handle, B.make_desc(), None, x, x, x, x, x, x)     # X missing
+    assert e.value.status == 1
+    with pytest.raises(B.RgnnError) as e:
+        B.rgnn_hgt_fwd(g.handle, B.make_desc(heads=8), x, x, x, x, x, x, x, None, x, x, x)   # d/H = 8 unsupported
+    assert e.value.status == 2
