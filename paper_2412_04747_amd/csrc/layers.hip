@@ -183,6 +183,42 @@ size_t stage_bytes(const rgnn_graph_t* g, int layer, const rgnn_layer_desc_t* d,
     return s.c.off;
 }
 
+// Forward typed linear  Y[g(i)] / Y[i] = A[g(i)] W[seg].  In bf16 mode it runs on the bf16 matrix
+// cores: an operand whose bf16 original exists (A16 / W16) is used as is, an fp32-only one is split.
+rgnn_status_t tl_fwd(bool bf16, const rgnn::TileList* tiles, int d, const float* A32, const void* A16,
+                     const int32_t* gather, int scatter, const float* W32, const void* W16, float* Y,
+                     const char* label, hipStream_t st) {
+    if (bf16) {
+        TypedLinearBf16Args a{};
+        a.tiles = tiles; a.A = A16 ? A16 : A32; a.a_bf16 = A16 != nullptr; a.gather = gather; a.scatter_out = scatter;
+        a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.Y = Y; a.label = label;
+        return typed_linear_bf16(d, a, st);
+    }
+    TypedLinearArgs a{};
+    a.tiles = tiles; a.X = A32; a.gather = gather; a.W = W32; a.Y = Y; a.scatter_out = scatter; a.label = label;
+    return typed_linear_fwd(d, d, a, st);
+}
+
+// Backward typed linear: dXrow = dY W^T (rows through `gather` on both sides when `both_gathered`),
+// dW = sum X^T dY.  fp32: one fused kernel.  bf16 mode at width 128: dXrow on the bf16 matrix cores
+// (dY split into two bf16 planes), dW by the fp32 tile kernel in weight-gradient-only mode.
+rgnn_status_t tl_bwd(bool bf16, const rgnn::TileList* tiles, int d, const float* X32, const int32_t* gather,
+                     int both_gathered, const float* W32, const void* W16, const float* dY, float* dXrow, float* dW,
+                     float* part, const char* label, hipStream_t st) {
+    TypedLinearBwdArgs b{};
+    b.tiles = tiles; b.X = X32; b.gather = gather; b.W = W32; b.dY = dY; b.dy_gathered = both_gathered;
+    b.dXrow = dXrow; b.scatter_dx = both_gathered; b.dW = dW; b.part = part; b.label = label;
+    if (bf16 && d == 128) {
+        TypedLinearBf16Args a{};
+        a.tiles = tiles; a.A = dY; a.a_bf16 = 0; a.gather = both_gathered ? gather : nullptr; a.scatter_out = both_gathered;
+        a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.transpose_w = 1; a.Y = dXrow; a.label = label;
+        RGNN_TRY(typed_linear_bf16(d, a, st));
+        b.wgrad_only = 1;
+        b.label = "typed_linear_wgrad";
+    }
+    return typed_linear_bwd(d, d, b, st);
+}
+
 }  // namespace
 
 extern "C" rgnn_status_t rgnn_workspace_bytes(const rgnn_graph_t* g, int32_t layer, const rgnn_layer_desc_t* desc,
@@ -227,16 +263,17 @@ extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out;
     RgcnFwdWs w;
-    Bf16Stage stg(workspace, carve_rgcn_fwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    const bool bf16 = desc->dtype == RGNN_BF16;
+    const void* X16 = bf16 ? X : nullptr;
+    const void* W16 = bf16 ? W : nullptr;
+    Bf16Stage stg(workspace, carve_rgcn_fwd(g, desc, workspace, &w), bf16, st);
     X = stg.in(X, (size_t)g->N * desc->d_in);
     W = stg.in(W, (size_t)g->R * desc->d_in * D);
     W0 = stg.in(W0, (size_t)desc->d_in * D);
     RGNN_TRY(stg.status);
     // 1. compact messages: Hs[p] = X[pair_src[p]] W[rel(p)]
-    TypedLinearArgs a{};
-    a.tiles = &g->pair_tiles; a.X = static_cast<const float*>(X); a.gather = g->idx[RGNN_IDX_PAIR_SRC];
-    a.W = static_cast<const float*>(W); a.Y = w.Hs;
-    RGNN_TRY(typed_linear_fwd(desc->d_in, D, a, st));
+    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, static_cast<const float*>(X), X16, g->idx[RGNN_IDX_PAIR_SRC], 0,
+                    static_cast<const float*>(W), W16, w.Hs, "typed_linear_fwd", st));
     // 2. out[v] = sum_e (1/c) Hs[pair_e]
     const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, coef, 1, 0, w.Hs,
@@ -265,7 +302,9 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, K = desc->d_in;
     RgcnBwdWs w;
-    Bf16Stage stg(workspace, carve_rgcn_bwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    const bool bf16 = desc->dtype == RGNN_BF16;
+    const void* W16 = bf16 ? W : nullptr;
+    Bf16Stage stg(workspace, carve_rgcn_bwd(g, desc, workspace, &w), bf16, st);
     X = stg.in(X, (size_t)g->N * K);
     W = stg.in(W, (size_t)g->R * K * D);
     if (W0) W0 = stg.in(W0, (size_t)K * D); else stg.reserve((size_t)K * D);
@@ -281,10 +320,8 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, coef, 1, 0, dPre, w.G,
                         w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine"));
     // 2. per pair dXp = dHs W^T; dW[r] = sum X^T dHs
-    TypedLinearBwdArgs b{};
-    b.tiles = &g->pair_tiles; b.X = static_cast<const float*>(X); b.gather = g->idx[RGNN_IDX_PAIR_SRC];
-    b.W = static_cast<const float*>(W); b.dY = w.G; b.dXrow = w.dXp; b.dW = static_cast<float*>(dW); b.part = w.tl_part;
-    RGNN_TRY(typed_linear_bwd(K, D, b, st));
+    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, static_cast<const float*>(X), g->idx[RGNN_IDX_PAIR_SRC], 0,
+                    static_cast<const float*>(W), W16, w.G, w.dXp, static_cast<float*>(dW), w.tl_part, "typed_linear_bwd", st));
     // 3. self-loop: dX0 = dPre W0^T, dW0 = X^T dPre
     if (W0) {
         TypedLinearBwdArgs s{};
@@ -385,37 +422,6 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
 
 // =========================================================================== HGT
 
-namespace {
-// Y[perm[i]] = X[perm[i]] W[type(i)] over the node-type segments.
-rgnn_status_t node_typed_linear(const rgnn_graph_t* g, int d, const float* X, const float* W, float* Y, const char* label,
-                                hipStream_t st) {
-    TypedLinearArgs a{};
-    a.tiles = &g->node_tiles; a.X = X; a.gather = g->idx[RGNN_IDX_NTYPE_PERM]; a.W = W; a.Y = Y; a.scatter_out = 1;
-    a.label = label;
-    return typed_linear_fwd(d, d, a, st);
-}
-rgnn_status_t node_typed_linear_bwd(const rgnn_graph_t* g, int d, const float* X, const float* W, const float* dY,
-                                    float* dXrow, float* dW, float* part, const char* label, hipStream_t st) {
-    TypedLinearBwdArgs b{};
-    b.tiles = &g->node_tiles; b.X = X; b.gather = g->idx[RGNN_IDX_NTYPE_PERM]; b.W = W; b.dY = dY; b.dy_gathered = 1;
-    b.dXrow = dXrow; b.scatter_dx = 1; b.dW = dW; b.part = part; b.label = label;
-    return typed_linear_bwd(d, d, b, st);
-}
-rgnn_status_t pair_typed_linear(const rgnn_graph_t* g, int d, const float* X, const float* W, float* Y, const char* label,
-                                hipStream_t st) {
-    TypedLinearArgs a{};
-    a.tiles = &g->pair_tiles; a.X = X; a.gather = g->idx[RGNN_IDX_PAIR_SRC]; a.W = W; a.Y = Y; a.label = label;
-    return typed_linear_fwd(d, d, a, st);
-}
-rgnn_status_t pair_typed_linear_bwd(const rgnn_graph_t* g, int d, const float* X, const float* W, const float* dY,
-                                    float* dXrow, float* dW, float* part, const char* label, hipStream_t st) {
-    TypedLinearBwdArgs b{};
-    b.tiles = &g->pair_tiles; b.X = X; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = W; b.dY = dY; b.dXrow = dXrow;
-    b.dW = dW; b.part = part; b.label = label;
-    return typed_linear_bwd(d, d, b, st);
-}
-}  // namespace
-
 extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
                                       const void* Wk, const void* Wq, const void* Wv, const void* Wo, const void* Watt,
                                       const void* Wmsg, const void* mu, void* out, void* saved, void* workspace,
@@ -426,7 +432,10 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, H = desc->heads;
     HgtFwdWs w; HgtSaved sv;
-    Bf16Stage stg(workspace, carve_hgt_fwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    const bool bf16 = desc->dtype == RGNN_BF16;
+    const void *X16 = bf16 ? X : nullptr, *Wk16 = bf16 ? Wk : nullptr, *Wq16 = bf16 ? Wq : nullptr,
+               *Wv16 = bf16 ? Wv : nullptr, *Wo16 = bf16 ? Wo : nullptr;
+    Bf16Stage stg(workspace, carve_hgt_fwd(g, desc, workspace, &w), bf16, st);
     {
         const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
         X = stg.in(X, (size_t)g->N * D);
@@ -437,16 +446,19 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     }
     carve_hgt_saved(g, desc, saved, &sv);
     const float* Xf = static_cast<const float*>(X);
+    const int32_t* perm = g->idx[RGNN_IDX_NTYPE_PERM];
+    const int32_t* psrc = g->idx[RGNN_IDX_PAIR_SRC];
+    auto F = [](const void* p) { return static_cast<const float*>(p); };
     // 1. per node type: K, Q, V
-    RGNN_TRY(node_typed_linear(g, D, Xf, static_cast<const float*>(Wk), sv.K, "node_linear_k", st));
-    RGNN_TRY(node_typed_linear(g, D, Xf, static_cast<const float*>(Wq), sv.Q, "node_linear_q", st));
-    RGNN_TRY(node_typed_linear(g, D, Xf, static_cast<const float*>(Wv), sv.V, "node_linear_v", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wk), Wk16, sv.K, "node_linear_k", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wq), Wq16, sv.Q, "node_linear_q", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wv), Wv16, sv.V, "node_linear_v", st));
     // 2. per (relation, head) matrices as block-diagonal d x d weights; mu / sqrt(dh) folded into the attention one
-    RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Watt), static_cast<const float*>(mu), 1, w.Wbd_att, st));
-    RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Wmsg), nullptr, 0, w.Wbd_msg, st));
+    RGNN_TRY(hgt_expand(g->R, D, H, F(Watt), F(mu), 1, w.Wbd_att, st));
+    RGNN_TRY(hgt_expand(g->R, D, H, F(Wmsg), nullptr, 0, w.Wbd_msg, st));
     // 3. compact per pair: Ka[p] = K[src_p] Watt[r], M[p] = V[src_p] Wmsg[r]
-    RGNN_TRY(pair_typed_linear(g, D, sv.K, w.Wbd_att, sv.Ka, "pair_linear_att", st));
-    RGNN_TRY(pair_typed_linear(g, D, sv.V, w.Wbd_msg, sv.M, "pair_linear_msg", st));
+    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, sv.K, nullptr, psrc, 0, w.Wbd_att, nullptr, sv.Ka, "pair_linear_att", st));
+    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, sv.V, nullptr, psrc, 0, w.Wbd_msg, nullptr, sv.M, "pair_linear_msg", st));
     // 4. per edge and head: logit, softmax over the destination's edges
     RGNN_TRY(hgt_edge_logit(g, D, H, sv.Ka, sv.Q, sv.att, st));
     RGNN_TRY(hgt_softmax(g, H, sv.att, w.part_m, w.part_s, st));
@@ -454,7 +466,8 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, H, 0, sv.M, sv.Z, w.partial, st, 0,
                         "aggregate_fwd", "aggregate_fwd.combine", H));
     // 6. out = Z Wo[type]
-    RGNN_TRY(node_typed_linear(g, D, sv.Z, static_cast<const float*>(Wo), static_cast<float*>(out), "node_linear_out", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, sv.Z, nullptr, perm, 1, F(Wo), Wo16, static_cast<float*>(out),
+                    "node_linear_out", st));
     return RGNN_OK;
 }
 
@@ -472,7 +485,10 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, H = desc->heads;
     HgtBwdWs w; HgtSaved sv;
-    Bf16Stage stg(workspace, carve_hgt_bwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    const bool bf16 = desc->dtype == RGNN_BF16;
+    const void *Wk16 = bf16 ? Wk : nullptr, *Wq16 = bf16 ? Wq : nullptr, *Wv16 = bf16 ? Wv : nullptr,
+               *Wo16 = bf16 ? Wo : nullptr;
+    Bf16Stage stg(workspace, carve_hgt_bwd(g, desc, workspace, &w), bf16, st);
     {
         const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
         X = stg.in(X, (size_t)g->N * D);
@@ -485,9 +501,12 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     carve_hgt_saved(g, desc, const_cast<void*>(saved), &sv);
     const float* Xf = static_cast<const float*>(X);
     const float* dO = static_cast<const float*>(dOut);
+    const int32_t* perm = g->idx[RGNN_IDX_NTYPE_PERM];
+    const int32_t* psrc = g->idx[RGNN_IDX_PAIR_SRC];
+    auto F = [](const void* p) { return static_cast<const float*>(p); };
     // 1. output linear: dZ = dOut Wo^T, dWo = Z^T dOut
-    RGNN_TRY(node_typed_linear_bwd(g, D, sv.Z, static_cast<const float*>(Wo), dO, w.dZ, static_cast<float*>(dWo), w.tl_part,
-                                   "node_linear_out_bwd", st));
+    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, sv.Z, perm, 1, F(Wo), Wo16, dO, w.dZ, static_cast<float*>(dWo), w.tl_part,
+                    "node_linear_out_bwd", st));
     // 2. per edge and head: d logit
     RGNN_TRY(hgt_edge_dot_bwd(g, D, H, sv.att, sv.M, w.dZ, sv.Z, w.dl, st));
     // 3. pair-major: dM[p][h] = sum att dZ[dst][h];  dKa[p][h] = sum dl Q[dst][h]
@@ -501,8 +520,10 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     // 5. per-pair linears backward
     RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Watt), static_cast<const float*>(mu), 1, w.Wbd_att, st));
     RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Wmsg), nullptr, 0, w.Wbd_msg, st));
-    RGNN_TRY(pair_typed_linear_bwd(g, D, sv.K, w.Wbd_att, w.dKa, w.dKp, w.dWbd_att, w.tl_part, "pair_linear_att_bwd", st));
-    RGNN_TRY(pair_typed_linear_bwd(g, D, sv.V, w.Wbd_msg, w.dM, w.dVp, w.dWbd_msg, w.tl_part, "pair_linear_msg_bwd", st));
+    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, sv.K, psrc, 0, w.Wbd_att, nullptr, w.dKa, w.dKp, w.dWbd_att, w.tl_part,
+                    "pair_linear_att_bwd", st));
+    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, sv.V, psrc, 0, w.Wbd_msg, nullptr, w.dM, w.dVp, w.dWbd_msg, w.tl_part,
+                    "pair_linear_msg_bwd", st));
     RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_att, static_cast<const float*>(Watt), static_cast<const float*>(mu), 1,
                          static_cast<float*>(dWatt), static_cast<float*>(dmu), st));
     RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_msg, static_cast<const float*>(Wmsg), nullptr, 0, static_cast<float*>(dWmsg),
@@ -511,12 +532,12 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     RGNN_TRY(node_grad_sum(g, D, w.dKp, nullptr, nullptr, nullptr, w.dK, st));
     RGNN_TRY(node_grad_sum(g, D, w.dVp, nullptr, nullptr, nullptr, w.dV, st));
     // 7. node linears backward and dX
-    RGNN_TRY(node_typed_linear_bwd(g, D, Xf, static_cast<const float*>(Wk), w.dK, w.dXk, static_cast<float*>(dWk), w.tl_part,
-                                   "node_linear_k_bwd", st));
-    RGNN_TRY(node_typed_linear_bwd(g, D, Xf, static_cast<const float*>(Wq), w.dQ, w.dXq, static_cast<float*>(dWq), w.tl_part,
-                                   "node_linear_q_bwd", st));
-    RGNN_TRY(node_typed_linear_bwd(g, D, Xf, static_cast<const float*>(Wv), w.dV, w.dXv, static_cast<float*>(dWv), w.tl_part,
-                                   "node_linear_v_bwd", st));
+    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, perm, 1, F(Wk), Wk16, w.dK, w.dXk, static_cast<float*>(dWk), w.tl_part,
+                    "node_linear_k_bwd", st));
+    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, perm, 1, F(Wq), Wq16, w.dQ, w.dXq, static_cast<float*>(dWq), w.tl_part,
+                    "node_linear_q_bwd", st));
+    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, perm, 1, F(Wv), Wv16, w.dV, w.dXv, static_cast<float*>(dWv), w.tl_part,
+                    "node_linear_v_bwd", st));
     RGNN_TRY(add3((size_t)g->N * D, w.dXk, w.dXq, w.dXv, static_cast<float*>(dX), st));
     return RGNN_OK;
 }

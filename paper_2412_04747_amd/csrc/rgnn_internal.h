@@ -149,7 +149,23 @@ struct TypedLinearBwdArgs {
     float* Avec;             // [segs][KD] (with rowscale)
     float* part;             // scratch [num_slots][KD*ND + KD]
     const char* label;
+    int wgrad_only;          // 1: skip dXrow (the caller forms it elsewhere)
 };
+// bf16 matrix-core variant (typed_linear_bf16.hip): Y[i] = A[g(i)] W[seg]  (or W[seg]^T)
+struct TypedLinearBf16Args {
+    const TileList* tiles;
+    const void* A;           // rows: bf16 (a_bf16) or fp32
+    int a_bf16;
+    const int32_t* gather;   // row i reads A[gather[i]] (nullptr: A[i])
+    int scatter_out;         // 1: row i writes Y[gather[i]]
+    const void* W;           // [segs][d][d]: bf16 (w_bf16) or fp32
+    int w_bf16;
+    int transpose_w;         // 1: multiply by W[seg]^T
+    float* Y;                // fp32 output rows
+    const char* label;
+};
+rgnn_status_t typed_linear_bf16(int d, const TypedLinearBf16Args& a, hipStream_t st);
+
 size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t);
 rgnn_status_t typed_linear_bwd(int d_in, int d_out, const TypedLinearBwdArgs& a, hipStream_t st);
 

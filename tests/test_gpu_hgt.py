@@ -50,6 +50,15 @@ def test_small_typed(d, H, mu):
     _run(600, 3, 5, src, dst, rel, ntype, p, d, H, f"small-d{d}-H{H}")
 
 
+@pytest.mark.parametrize("d,H", [(64, 2), (32, 2), (128, 4)])
+def test_small_typed_bf16(d, H):
+    rng, src, dst, rel, ntype = synth.tiny(190 + d, N=700, R=6, E=6000, T=3)
+    dst[:900] = 5                                   # a hub cut into pieces
+    p = synth.hgt_params(rng, 700, 3, 6, d, H, with_mu=True)
+    p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}
+    _run(700, 3, 6, src, dst, rel, ntype, p, d, H, f"bf16-d{d}-H{H}", dtype="bf16")
+
+
 def test_hub_isolated_and_single_type():
     rng, src, dst, rel, ntype = synth.tiny(95, N=300, R=4, E=4000, T=1)
     dst[:2500] = 9

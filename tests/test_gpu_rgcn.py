@@ -61,6 +61,16 @@ def test_empty_graph():
     _run(10, 2, e, e, e, p, 32, "in_degree_per_rel", "none", True, tag="empty")
 
 
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_small_bf16_all_options(d):
+    rng, src, dst, rel, _ = synth.tiny(140 + d, N=700, R=5, E=6000)
+    dst[:800] = 3
+    p = synth.rgcn_params(rng, 700, 5, d, d, self_loop=True)
+    p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}
+    _run(700, 5, src, dst, rel, p, d, "in_degree_per_rel", "none", True, tag=f"bf16-d{d}", dtype="bf16")
+    _run(700, 5, src, dst, rel, p, d, "none", "relu", False, tag=f"bf16-d{d}-relu", dtype="bf16")
+
+
 def test_scaled_config5_bf16():
     c = synth.config(5, scale=0.01)          # knowledge-graph shaped: 500 relations, many with a handful of edges
     _run(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 128, "in_degree_per_rel", "none", False, tag="C5/100",
