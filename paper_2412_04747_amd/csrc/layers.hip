@@ -200,22 +200,25 @@ rgnn_status_t tl_fwd(bool bf16, const rgnn::TileList* tiles, int d, const float*
 }
 
 // Backward typed linear: dXrow = dY W^T (rows through `gather` on both sides when `both_gathered`),
-// dW = sum X^T dY.  fp32: one fused kernel.  bf16 mode at width 128: dXrow on the bf16 matrix cores
-// (dY split into two bf16 planes), dW by the fp32 tile kernel in weight-gradient-only mode.
-rgnn_status_t tl_bwd(bool bf16, const rgnn::TileList* tiles, int d, const float* X32, const int32_t* gather,
-                     int both_gathered, const float* W32, const void* W16, const float* dY, float* dXrow, float* dW,
-                     float* part, const char* label, hipStream_t st) {
-    TypedLinearBwdArgs b{};
-    b.tiles = tiles; b.X = X32; b.gather = gather; b.W = W32; b.dY = dY; b.dy_gathered = both_gathered;
-    b.dXrow = dXrow; b.scatter_dx = both_gathered; b.dW = dW; b.part = part; b.label = label;
+// dW = sum X^T dY.  fp32: one fused kernel.  bf16 mode at width 128: two kernels on the bf16 matrix
+// cores (dY split into two bf16 planes; X as is when its bf16 original exists).
+rgnn_status_t tl_bwd(bool bf16, const rgnn::TileList* tiles, int d, const float* X32, const void* X16,
+                     const int32_t* gather, int both_gathered, const float* W32, const void* W16, const float* dY,
+                     float* dXrow, float* dW, float* part, const char* label, hipStream_t st) {
     if (bf16 && d == 128) {
         TypedLinearBf16Args a{};
         a.tiles = tiles; a.A = dY; a.a_bf16 = 0; a.gather = both_gathered ? gather : nullptr; a.scatter_out = both_gathered;
         a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.transpose_w = 1; a.Y = dXrow; a.label = label;
         RGNN_TRY(typed_linear_bf16(d, a, st));
-        b.wgrad_only = 1;
-        b.label = "typed_linear_wgrad";
+        TypedLinearWgradBf16Args w{};
+        w.tiles = tiles; w.X = X16 ? X16 : X32; w.x_bf16 = X16 != nullptr; w.gather = gather; w.dy_gathered = both_gathered;
+        w.dY = dY; w.part = part; w.label = "typed_linear_wgrad";
+        RGNN_TRY(typed_linear_wgrad_bf16(d, w, st));
+        return typed_linear_slot_reduce(d, d, *tiles, part, dW, nullptr, st);
     }
+    TypedLinearBwdArgs b{};
+    b.tiles = tiles; b.X = X32; b.gather = gather; b.W = W32; b.dY = dY; b.dy_gathered = both_gathered;
+    b.dXrow = dXrow; b.scatter_dx = both_gathered; b.dW = dW; b.part = part; b.label = label;
     return typed_linear_bwd(d, d, b, st);
 }
 
@@ -304,6 +307,7 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     RgcnBwdWs w;
     const bool bf16 = desc->dtype == RGNN_BF16;
     const void* W16 = bf16 ? W : nullptr;
+    const void* X16 = bf16 ? X : nullptr;
     Bf16Stage stg(workspace, carve_rgcn_bwd(g, desc, workspace, &w), bf16, st);
     X = stg.in(X, (size_t)g->N * K);
     W = stg.in(W, (size_t)g->R * K * D);
@@ -320,7 +324,7 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, coef, 1, 0, dPre, w.G,
                         w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine"));
     // 2. per pair dXp = dHs W^T; dW[r] = sum X^T dHs
-    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, static_cast<const float*>(X), g->idx[RGNN_IDX_PAIR_SRC], 0,
+    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, static_cast<const float*>(X), X16, g->idx[RGNN_IDX_PAIR_SRC], 0,
                     static_cast<const float*>(W), W16, w.G, w.dXp, static_cast<float*>(dW), w.tl_part, "typed_linear_bwd", st));
     // 3. self-loop: dX0 = dPre W0^T, dW0 = X^T dPre
     if (W0) {
@@ -487,7 +491,7 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     HgtBwdWs w; HgtSaved sv;
     const bool bf16 = desc->dtype == RGNN_BF16;
     const void *Wk16 = bf16 ? Wk : nullptr, *Wq16 = bf16 ? Wq : nullptr, *Wv16 = bf16 ? Wv : nullptr,
-               *Wo16 = bf16 ? Wo : nullptr;
+               *Wo16 = bf16 ? Wo : nullptr, *X16 = bf16 ? X : nullptr;
     Bf16Stage stg(workspace, carve_hgt_bwd(g, desc, workspace, &w), bf16, st);
     {
         const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
@@ -505,7 +509,7 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     const int32_t* psrc = g->idx[RGNN_IDX_PAIR_SRC];
     auto F = [](const void* p) { return static_cast<const float*>(p); };
     // 1. output linear: dZ = dOut Wo^T, dWo = Z^T dOut
-    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, sv.Z, perm, 1, F(Wo), Wo16, dO, w.dZ, static_cast<float*>(dWo), w.tl_part,
+    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, sv.Z, nullptr, perm, 1, F(Wo), Wo16, dO, w.dZ, static_cast<float*>(dWo), w.tl_part,
                     "node_linear_out_bwd", st));
     // 2. per edge and head: d logit
     RGNN_TRY(hgt_edge_dot_bwd(g, D, H, sv.att, sv.M, w.dZ, sv.Z, w.dl, st));
@@ -520,9 +524,9 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     // 5. per-pair linears backward
     RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Watt), static_cast<const float*>(mu), 1, w.Wbd_att, st));
     RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Wmsg), nullptr, 0, w.Wbd_msg, st));
-    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, sv.K, psrc, 0, w.Wbd_att, nullptr, w.dKa, w.dKp, w.dWbd_att, w.tl_part,
+    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, sv.K, nullptr, psrc, 0, w.Wbd_att, nullptr, w.dKa, w.dKp, w.dWbd_att, w.tl_part,
                     "pair_linear_att_bwd", st));
-    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, sv.V, psrc, 0, w.Wbd_msg, nullptr, w.dM, w.dVp, w.dWbd_msg, w.tl_part,
+    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, sv.V, nullptr, psrc, 0, w.Wbd_msg, nullptr, w.dM, w.dVp, w.dWbd_msg, w.tl_part,
                     "pair_linear_msg_bwd", st));
     RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_att, static_cast<const float*>(Watt), static_cast<const float*>(mu), 1,
                          static_cast<float*>(dWatt), static_cast<float*>(dmu), st));
@@ -532,11 +536,11 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     RGNN_TRY(node_grad_sum(g, D, w.dKp, nullptr, nullptr, nullptr, w.dK, st));
     RGNN_TRY(node_grad_sum(g, D, w.dVp, nullptr, nullptr, nullptr, w.dV, st));
     // 7. node linears backward and dX
-    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, perm, 1, F(Wk), Wk16, w.dK, w.dXk, static_cast<float*>(dWk), w.tl_part,
+    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wk), Wk16, w.dK, w.dXk, static_cast<float*>(dWk), w.tl_part,
                     "node_linear_k_bwd", st));
-    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, perm, 1, F(Wq), Wq16, w.dQ, w.dXq, static_cast<float*>(dWq), w.tl_part,
+    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wq), Wq16, w.dQ, w.dXq, static_cast<float*>(dWq), w.tl_part,
                     "node_linear_q_bwd", st));
-    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, perm, 1, F(Wv), Wv16, w.dV, w.dXv, static_cast<float*>(dWv), w.tl_part,
+    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wv), Wv16, w.dV, w.dXv, static_cast<float*>(dWv), w.tl_part,
                     "node_linear_v_bwd", st));
     RGNN_TRY(add3((size_t)g->N * D, w.dXk, w.dXq, w.dXv, static_cast<float*>(dX), st));
     return RGNN_OK;

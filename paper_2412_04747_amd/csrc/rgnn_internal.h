@@ -166,6 +166,22 @@ struct TypedLinearBf16Args {
 };
 rgnn_status_t typed_linear_bf16(int d, const TypedLinearBf16Args& a, hipStream_t st);
 
+// bf16 matrix-core weight gradient: part[slot] = sum over the chunk's rows of X[g(i)]^T dY[i];
+// typed_linear_slot_reduce then adds a segment's slots into dW.
+struct TypedLinearWgradBf16Args {
+    const TileList* tiles;
+    const void* X;           // rows: bf16 (x_bf16) or fp32
+    int x_bf16;
+    const int32_t* gather;
+    int dy_gathered;         // 1: dY rows are read through the gather list as well
+    const float* dY;
+    float* part;
+    const char* label;
+};
+rgnn_status_t typed_linear_wgrad_bf16(int d, const TypedLinearWgradBf16Args& a, hipStream_t st);
+rgnn_status_t typed_linear_slot_reduce(int d_in, int d_out, const TileList& tiles, const float* part, float* dW,
+                                       float* Avec, hipStream_t st);
+
 size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t);
 rgnn_status_t typed_linear_bwd(int d_in, int d_out, const TypedLinearBwdArgs& a, hipStream_t st);
 

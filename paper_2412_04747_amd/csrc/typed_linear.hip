@@ -764,6 +764,16 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
     return launch_slot_reduce(KD, ND, a, st);
 }
 
+rgnn_status_t typed_linear_slot_reduce(int d_in, int d_out, const TileList& tiles, const float* part, float* dW,
+                                       float* Avec, hipStream_t st) {
+    const int kn = d_in * d_out;
+    KernelTimer kt(st, "typed_linear_bwd.reduce");
+    hipLaunchKernelGGL(slot_reduce_kernel, dim3((kn + d_in + 255) / 256, tiles.num_segs), dim3(256), 0, st, part,
+                       tiles.seg_slot_ptr, kn, d_in, dW, Avec);
+    RGNN_HIP(hipGetLastError());
+    return RGNN_OK;
+}
+
 rgnn_status_t typed_linear_bwd(int d_in, int d_out, const TypedLinearBwdArgs& a, hipStream_t st) {
     if (d_in == 64 && d_out == 64) return launch_bwd<64, 64>(a, st);
     if (d_in == 32 && d_out == 32) return launch_bwd<32, 32>(a, st);

@@ -178,6 +178,180 @@ __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, con
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Weight gradient on the bf16 matrix cores:  dW[seg] = sum_{i in seg} X[g(i)]^T dY[i],  D x D.
+// The contraction runs over rows, so the MFMA operands are "eight consecutive rows of one
+// feature": the 64-row tile is stored feature-major in LDS (T[f][row]), transposed while it is
+// written.  Feature row f keeps its eight 16-byte row groups at positions g ^ ((f ^ (f >> 3)) & 7):
+// the 16-byte operand reads of 8 neighbouring features then fall on 8 different bank groups, and
+// the 2-byte transposing writes of the 16 (or 32) lanes sharing a row spread over 8 banks as well.
+// X is used as is when its bf16 original exists, otherwise it and dY are split into hi + lo planes.
+// Each of the four wavefronts owns one 32-feature band of X and all four 32-column blocks of dY
+// (64 accumulator registers), kept across the tiles of a segment and flushed to the chunk's slot.
+__device__ __forceinline__ int tswz(int f, int row) {
+    return f * 64 + ((((row >> 3) ^ (f ^ (f >> 3))) & 7) << 3) + (row & 7);
+}
+
+template <int D, bool X_BF16, bool GATHER, bool DYG>
+__global__ __launch_bounds__(256) void typed_linear_wgrad_bf16_kernel(TileArgsB t, const int32_t* __restrict__ chunk_slot,
+                                                                      const void* __restrict__ Xv,
+                                                                      const int32_t* __restrict__ gather,
+                                                                      const float* __restrict__ dY,
+                                                                      float* __restrict__ part) {
+    static_assert(D == 128, "four wavefronts x four 32-column blocks");
+    constexpr int TMW = 64;
+    constexpr int XPL = X_BF16 ? 1 : 2;
+    constexpr int LPX = X_BF16 ? D / 8 : D / 4, RPX = 256 / LPX, NXL = TMW / RPX;   // X: lanes/row, rows/pass, passes
+    constexpr int LPY = D / 4, RPY = 256 / LPY, NYL = TMW / RPY;
+    constexpr int SLOT = D * D + D;
+    extern __shared__ __align__(16) unsigned short lds[];
+    unsigned short* Xt = lds;                         // [XPL][D][64]
+    unsigned short* Yt = lds + XPL * D * 64;          // [2][D][64]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 31, kh = lane >> 5;
+    const int cx = tid % LPX, rx = tid / LPX, cy = tid % LPY, ry = tid / LPY;
+    v16f acc[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+    const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
+    v4u xr[NXL], yr[NYL];
+    int gi[NXL];
+#define RGNN_W_FETCH_IDX(TI)                                                        \
+    {                                                                               \
+        const int row0_ = t.tile_row0[TI], row1_ = t.tile_row1[TI];                 \
+        _Pragma("unroll") for (int it = 0; it < NXL; ++it) {                        \
+            const int row_ = min(row0_ + rx + it * RPX, row1_ - 1);                 \
+            gi[it] = GATHER ? gather[row_] : row_;                                  \
+        }                                                                           \
+    }
+#define RGNN_W_FETCH(TI)                                                            \
+    {                                                                               \
+        const int row0_ = t.tile_row0[TI], row1_ = t.tile_row1[TI];                 \
+        _Pragma("unroll") for (int it = 0; it < NXL; ++it)                          \
+            xr[it] = *reinterpret_cast<const v4u*>(static_cast<const char*>(Xv) +   \
+                                                   (size_t)gi[it] * D * (X_BF16 ? 2 : 4) + cx * 16); \
+        _Pragma("unroll") for (int it = 0; it < NYL; ++it) {                        \
+            const int row_ = min(row0_ + ry + it * RPY, row1_ - 1);                 \
+            const size_t s_ = (DYG && GATHER) ? (size_t)gather[row_] : (size_t)row_; \
+            yr[it] = *reinterpret_cast<const v4u*>(dY + s_ * D + cy * 4);           \
+        }                                                                           \
+    }
+    if (t0 < t1) {
+        RGNN_W_FETCH_IDX(t0)
+        RGNN_W_FETCH(t0)
+    }
+    if (t0 + 1 < t1) RGNN_W_FETCH_IDX(t0 + 1)
+    int cur_seg = -1;
+    int slot = chunk_slot[blockIdx.x] - 1;
+    for (int ti = t0; ti <= t1; ++ti) {
+        const int seg = (ti < t1) ? t.tile_seg[ti] : -2;
+        if (seg != cur_seg) {
+            if (cur_seg >= 0) {   // flush: band `wave` of the gradient, four column blocks
+                float* ps = part + (size_t)slot * SLOT;
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        ps[(wave * 32 + acc_row16(v, kh)) * D + b * 32 + m] = acc[b][v];
+                        acc[b][v] = 0.f;
+                    }
+            }
+            if (ti == t1) break;
+            ++slot;
+            cur_seg = seg;
+        }
+        const int rows = t.tile_row1[ti] - t.tile_row0[ti];
+        // transpose the prefetched rows into LDS (rows past the end of the tile as zeros)
+#pragma unroll
+        for (int it = 0; it < NXL; ++it) {
+            const int r = rx + it * RPX;
+            const bool ok = r < rows;
+            if (X_BF16) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned w = xr[it][e >> 1];
+                    const unsigned short v = ok ? (unsigned short)((e & 1) ? (w >> 16) : (w & 0xFFFFu)) : (unsigned short)0;
+                    Xt[tswz(cx * 8 + e, r)] = v;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    unsigned h, l;
+                    bf16_split(ok ? __uint_as_float(xr[it][e]) : 0.f, h, l);
+                    Xt[tswz(cx * 4 + e, r)] = (unsigned short)h;
+                    Xt[D * 64 + tswz(cx * 4 + e, r)] = (unsigned short)l;
+                }
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < NYL; ++it) {
+            const int r = ry + it * RPY;
+            const bool ok = r < rows;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                unsigned h, l;
+                bf16_split(ok ? __uint_as_float(yr[it][e]) : 0.f, h, l);
+                Yt[tswz(cy * 4 + e, r)] = (unsigned short)h;
+                Yt[D * 64 + tswz(cy * 4 + e, r)] = (unsigned short)l;
+            }
+        }
+        __syncthreads();
+        if (ti + 1 < t1) RGNN_W_FETCH(ti + 1)
+        if (ti + 2 < t1) RGNN_W_FETCH_IDX(ti + 2)
+#pragma unroll
+        for (int s = 0; s < TMW / 16; ++s) {
+            const int r0 = 16 * s + 8 * kh;
+            const int fa = wave * 32 + m;
+            const bf16x8 ah = *reinterpret_cast<const bf16x8*>(Xt + tswz(fa, r0));
+            bf16x8 al;
+            if (!X_BF16) al = *reinterpret_cast<const bf16x8*>(Xt + D * 64 + tswz(fa, r0));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int fb = b * 32 + m;
+                const bf16x8 bh = *reinterpret_cast<const bf16x8*>(Yt + tswz(fb, r0));
+                const bf16x8 bl = *reinterpret_cast<const bf16x8*>(Yt + D * 64 + tswz(fb, r0));
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc[b], 0, 0, 0);
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc[b], 0, 0, 0);
+                if (!X_BF16) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc[b], 0, 0, 0);
+            }
+        }
+        __syncthreads();   // operand reads are done before the next tile is transposed in
+    }
+#undef RGNN_W_FETCH_IDX
+#undef RGNN_W_FETCH
+}
+
+template <bool X_BF16, bool GATHER, bool DYG>
+static rgnn_status_t launch_wgrad(const TypedLinearWgradBf16Args& a, hipStream_t st) {
+    constexpr int D = 128;
+    const size_t lds = sizeof(unsigned short) * ((X_BF16 ? 1 : 2) + 2) * D * 64;
+    auto kern = typed_linear_wgrad_bf16_kernel<D, X_BF16, GATHER, DYG>;
+    RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KernelTimer kt(st, a.label ? a.label : "typed_linear_wgrad");
+    TileArgsB t{a.tiles->tile_seg, a.tiles->tile_row0, a.tiles->tile_row1, a.tiles->chunk_tile};
+    hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.tiles->chunk_slot, a.X, a.gather, a.dY,
+                       a.part);
+    RGNN_HIP(hipGetLastError());
+    return RGNN_OK;
+}
+
+// Fills the partial slots only; the caller sums them with the slot reduction of typed_linear.hip.
+rgnn_status_t typed_linear_wgrad_bf16(int d, const TypedLinearWgradBf16Args& a, hipStream_t st) {
+    if (d != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_wgrad_bf16: width %d not supported (128)", d);
+    if (a.tiles->num_tiles == 0) return RGNN_OK;
+    const bool g = a.gather != nullptr, dg = g && a.dy_gathered;
+    if (a.x_bf16) {
+        if (g && dg) return launch_wgrad<true, true, true>(a, st);
+        if (g) return launch_wgrad<true, true, false>(a, st);
+        return launch_wgrad<true, false, false>(a, st);
+    }
+    if (g && dg) return launch_wgrad<false, true, true>(a, st);
+    if (g) return launch_wgrad<false, true, false>(a, st);
+    return launch_wgrad<false, false, false>(a, st);
+}
+
 template <int CD, int OD, bool A_BF16, bool W_BF16, bool WT, bool GATHER, bool SCATTER>
 static rgnn_status_t launch(const TypedLinearBf16Args& a, hipStream_t st) {
     constexpr int LS = CD + 8, APL = A_BF16 ? 1 : 2, WPL = W_BF16 ? 1 : 2;
