@@ -117,13 +117,15 @@ static void build_tiles(Uploader& U, TileList& t, const std::vector<int32_t>& se
 }
 
 // Items of at most max_len entries over segments ptr[0..S].
-static void build_items(Uploader& U, ItemList& L, const std::vector<int32_t>& ptr, int max_len) {
+// Segments shorter than `min_len` are left out (their owner handles them elsewhere).
+static void build_items(Uploader& U, ItemList& L, const std::vector<int32_t>& ptr, int max_len, int min_len = 0) {
     const int S = (int)ptr.size() - 1;
     std::vector<int32_t> beg, end, row, slot, srow, sptr, pitem, psplit;
     sptr.push_back(0);
     int partials = 0;
     for (int s = 0; s < S; ++s) {
         const int32_t a = ptr[s], b = ptr[s + 1];
+        if (b - a < min_len) continue;
         if (b - a <= max_len) {
             beg.push_back(a); end.push_back(b); row.push_back(s); slot.push_back(-1);
         } else {
@@ -142,10 +144,12 @@ static void build_items(Uploader& U, ItemList& L, const std::vector<int32_t>& pt
     // long items are scheduled before the short ones fill the tail.
     {
         const int n = (int)beg.size();
-        std::vector<int32_t> cnt(max_len + 2, 0), perm(n), inv(n);
-        for (int i = 0; i < n; ++i) cnt[max_len - (end[i] - beg[i]) + 1]++;
-        for (int l = 0; l <= max_len; ++l) cnt[l + 1] += cnt[l];
-        for (int i = 0; i < n; ++i) { const int p = cnt[max_len - (end[i] - beg[i])]++; perm[p] = i; inv[i] = p; }
+        int longest = 0;
+        for (int i = 0; i < n; ++i) longest = std::max(longest, end[i] - beg[i]);
+        std::vector<int32_t> cnt(longest + 2, 0), perm(n), inv(n);
+        for (int i = 0; i < n; ++i) cnt[longest - (end[i] - beg[i]) + 1]++;
+        for (int l = 0; l <= longest; ++l) cnt[l + 1] += cnt[l];
+        for (int i = 0; i < n; ++i) { const int p = cnt[longest - (end[i] - beg[i])]++; perm[p] = i; inv[i] = p; }
         auto apply = [&](std::vector<int32_t>& v) {
             std::vector<int32_t> t(n);
             for (int p = 0; p < n; ++p) t[p] = v[perm[p]];
@@ -331,6 +335,16 @@ static rgnn_status_t build(rgnn_graph* g, int format, const int32_t* a, const in
     build_items(U, g->dst_items, in_ptr, kItemMax);
     build_items(U, g->pair_items, out_ptr, kItemMax);
     build_items(U, g->relrun_items, relrun_ptr, kItemMax);
+    build_items(U, g->pair_items_multi, out_ptr, kItemMax, 2);
+    build_items(U, g->srcpair_items, srcpair_ptr, 1 << 30);
+    {   // CSR edge -> pair id, with the top bit set when the pair has this edge only
+        std::vector<int32_t> tag((size_t)E);
+        for (int64_t i = 0; i < E; ++i) {
+            const int32_t p = in_pair[i];
+            tag[i] = (out_ptr[p + 1] - out_ptr[p] == 1) ? (int32_t)((uint32_t)p | 0x80000000u) : p;
+        }
+        g->in_pair_tag = U.up(tag);
+    }
     build_long(U, g->long_runs, run_ptr);
     build_long(U, g->long_pairs, out_ptr);
     return U.st;

@@ -103,6 +103,9 @@ struct rgnn_graph {
     rgnn::TileList all_tiles;              // all nodes as one segment (RGCN self-loop)
     rgnn::ItemList dst_items;              // CSR edges by destination
     rgnn::ItemList pair_items;             // transposed edges by pair
+    rgnn::ItemList pair_items_multi;       // the same, pairs with two or more edges only
+    rgnn::ItemList srcpair_items;          // pairs by source node (never cut)
+    int32_t* in_pair_tag = nullptr;        // [E] in_pair with the top bit set when the pair has a single edge
     rgnn::ItemList relrun_items;           // runs by relation
     rgnn::LongList long_runs;              // runs (run_ptr) too long for one lane
     rgnn::LongList long_pairs;             // pairs (out_ptr) too long for one lane

@@ -7,14 +7,14 @@ namespace rgnn {
 rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st);
 rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st);
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
-                                 int stride, int off, float* out, hipStream_t st, const char* label);
+                                 int stride, int off, float* out, hipStream_t st, const char* label, int min_len = 0);
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
                            float* part_m, float* part_s, hipStream_t st);
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
                          const float* coef, int cstride, int cabs, const float* src, float* out, float* partial,
                          hipStream_t st, int role, const char* label, const char* combine_label, int heads = 1);
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
-                           const float* out, float slope, float* adz, hipStream_t st);
+                           const float* out, float slope, float* adz, float* G, float* ds_src, hipStream_t st);
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const float* dXp, const float* ds_dst, const float* wtp,
                             const float* extra, float* dX, hipStream_t st);
 rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const float* w_s, const float* w_t,

@@ -80,11 +80,12 @@ __global__ void run_logit_kernel(int Q, const int32_t* __restrict__ run_dst, con
 // One lane per segment of at most kSerialMax entries; the longer ones (listed by the graph
 // index) get one wavefront each in a second kernel.
 __global__ void segment_scalar_sum_kernel(int n, const int32_t* __restrict__ ptr, const int32_t* __restrict__ via,
-                                          const float* __restrict__ val, int stride, int off, float* __restrict__ out) {
+                                          const float* __restrict__ val, int stride, int off, int min_len,
+                                          float* __restrict__ out) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int b = ptr[i], e = ptr[i + 1];
-    if (e - b > kSerialMax) return;
+    if (e - b > kSerialMax || e - b < min_len) return;
     float s = 0.f;
     for (int j = b; j < e; ++j) s += val[(size_t)(via ? via[j] : j) * stride + off];
     out[i] = s;
@@ -288,6 +289,10 @@ __global__ __launch_bounds__(1024) void combine_partials_kernel(const int32_t* _
 // with gbar_v = sum_e att_e g_e = dOut[v] . out[v] (because out[v] = sum_e att_e Hs[pair_e]):
 //   dl_e = att_e (g_e - gbar_v);  dz_e = dl_e * (z_e > 0 ? 1 : slope);   adz[e] = (att_e, dz_e).
 // No reduction over the segment is needed, so pieces of cut nodes are independent.
+// An edge that is the only edge of its (source, relation) pair also owns that pair's rows of the
+// backward aggregation, G[p] = att_e dOut[v] and ds_src[p] = dz_e, and writes them here (the
+// destination's dOut row is already in registers); the pair-major walk then only visits pairs
+// with several edges.  in_pair carries the "single edge" flag in its top bit.
 struct EdgeDotArgs {
     Items it;
     const int32_t* in_pair;
@@ -297,6 +302,8 @@ struct EdgeDotArgs {
     const float* out;
     float slope;
     float2* adz;
+    float* G;
+    float* ds_src;
 };
 
 template <int D>
@@ -313,13 +320,16 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
     for (int j = b; j < e; j += 4) {
         float at[4];
         float4 h[4];
+        int pr[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             at[u] = 0.f;
+            pr[u] = 0;
             h[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (j + u < e) {
                 at[u] = a.att[j + u];
-                h[u] = *reinterpret_cast<const float4*>(a.Hs + (size_t)a.in_pair[j + u] * D + c4 * 4);
+                pr[u] = a.in_pair[j + u];
+                h[u] = *reinterpret_cast<const float4*>(a.Hs + (size_t)(pr[u] & 0x7FFFFFFF) * D + c4 * 4);
             }
         }
 #pragma unroll
@@ -329,6 +339,11 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
             const float dl = al * (g - gbar);
             const float dz = dl * (signbit(at[u]) ? a.slope : 1.f);
             if (c4 == 0 && j + u < e) a.adz[j + u] = make_float2(al, dz);
+            if (pr[u] < 0) {   // single-edge pair (implies j + u < e)
+                const size_t p = (size_t)(pr[u] & 0x7FFFFFFF);
+                *reinterpret_cast<float4*>(a.G + p * D + c4 * 4) = make_float4(al * go.x, al * go.y, al * go.z, al * go.w);
+                if (c4 == 0) a.ds_src[p] = dz;
+            }
         }
     }
 }
@@ -338,7 +353,7 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
 // dX[u] = sum_{p in srcpair(u)} dXp[p]  +  sum_{q in runs(u)} ds_dst[q] * wtp[run_rel[q]]  +  extra[u]
 // (second and third terms optional).
 struct NodeSumArgs {
-    int N;
+    Items it;             // pairs by source node, ordered by length, never cut
     const int32_t* srcpair_ptr;
     const int32_t* srcpair_idx;
     const float* dXp;
@@ -353,11 +368,12 @@ struct NodeSumArgs {
 template <int D>
 __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
     constexpr int LPR = D / 4, IPB = 256 / LPR;
-    const int u = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
-    if (u >= a.N) return;
+    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+    if (i >= a.it.n) return;
+    const int u = a.it.row[i];
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     if (a.extra) acc = *reinterpret_cast<const float4*>(a.extra + (size_t)u * D + c4 * 4);
-    const int b = a.srcpair_ptr[u], e = a.srcpair_ptr[u + 1];
+    const int b = a.it.beg[i], e = a.it.end[i];
     for (int j = b; j < e; j += 2) {
         const float4 v0 = *reinterpret_cast<const float4*>(a.dXp + (size_t)a.srcpair_idx[j] * D + c4 * 4);
         float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -448,11 +464,11 @@ rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float*
 }
 
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
-                                 int stride, int off, float* out, hipStream_t st, const char* label) {
+                                 int stride, int off, float* out, hipStream_t st, const char* label, int min_len) {
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, label);
     hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ptr, via, val, stride,
-                       off, out);
+                       off, min_len, out);
     CHECK_LAUNCH();
     if (lng.n > 0) {
         hipLaunchKernelGGL(segment_scalar_sum_long_kernel, dim3(blocks_for((size_t)lng.n * 64, 256)), dim3(256), 0, st,
@@ -510,10 +526,10 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
 }
 
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
-                           const float* out, float slope, float* adz, hipStream_t st) {
+                           const float* out, float slope, float* adz, float* G, float* ds_src, hipStream_t st) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
-    EdgeDotArgs a{dev_items(L), g->idx[RGNN_IDX_IN_PAIR], att, Hs, dOut, out, slope, reinterpret_cast<float2*>(adz)};
+    EdgeDotArgs a{dev_items(L), g->in_pair_tag, att, Hs, dOut, out, slope, reinterpret_cast<float2*>(adz), G, ds_src};
     KernelTimer kt(st, "edge_dot_bwd");
     DISPATCH_D(D, hipLaunchKernelGGL(edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
                                      0, st, a));
@@ -524,7 +540,7 @@ rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const f
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const float* dXp, const float* ds_dst, const float* wtp,
                             const float* extra, float* dX, hipStream_t st) {
     if (g->N == 0) return RGNN_OK;
-    NodeSumArgs a{(int)g->N, g->idx[RGNN_IDX_SRCPAIR_PTR], g->idx[RGNN_IDX_SRCPAIR_IDX], dXp,
+    NodeSumArgs a{dev_items(g->srcpair_items), g->idx[RGNN_IDX_SRCPAIR_PTR], g->idx[RGNN_IDX_SRCPAIR_IDX], dXp,
                   g->idx[RGNN_IDX_DST_RUN_PTR], g->idx[RGNN_IDX_RUN_REL], ds_dst, wtp, extra, dX};
     KernelTimer kt(st, "node_grad_sum");
     DISPATCH_D(D, hipLaunchKernelGGL(node_grad_sum_kernel<DD>, dim3(blocks_for((size_t)g->N, 256 / (DD / 4))), dim3(256),

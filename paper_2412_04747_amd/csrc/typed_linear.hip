@@ -658,8 +658,18 @@ __global__ void slot_reduce_kernel(const float* __restrict__ part, const int32_t
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     const int slot_sz = kn + kd;
     if (i >= slot_sz) return;
-    float s = 0.f;
-    for (int sl = seg_slot_ptr[seg]; sl < seg_slot_ptr[seg + 1]; ++sl) s += part[(size_t)sl * slot_sz + i];
+    // four partial sums keep four loads in flight; they are combined in a fixed order
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    const int b = seg_slot_ptr[seg], e = seg_slot_ptr[seg + 1];
+    int sl = b;
+    for (; sl + 3 < e; sl += 4) {
+        s0 += part[(size_t)sl * slot_sz + i];
+        s1 += part[(size_t)(sl + 1) * slot_sz + i];
+        s2 += part[(size_t)(sl + 2) * slot_sz + i];
+        s3 += part[(size_t)(sl + 3) * slot_sz + i];
+    }
+    for (; sl < e; ++sl) s0 += part[(size_t)sl * slot_sz + i];
+    const float s = (s0 + s1) + (s2 + s3);
     if (i < kn) dW[(size_t)seg * kn + i] = s;
     else if (Avec) Avec[(size_t)seg * kd + (i - kn)] = s;
 }
