@@ -21,7 +21,7 @@ HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
-def algorithmic_work(name, E, N, P, Q, R, T, d, H):
+def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0):
     """(bound, bytes, flops) one launch of kernel `name` must move / compute (fp32 arithmetic,
     4-byte elements).  Gathered rows are counted once per reference (no cache reuse assumed);
     index and scalar traffic as listed; see DESIGN.md "Kernels and their rooflines"."""
@@ -41,10 +41,11 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H):
         "self_loop_fwd": ("mfma", N * 3 * row + w2, 2.0 * N * d * d),         # X row + out row read and written
         "self_loop_bwd": ("mfma", N * 3 * row + w2, 4.0 * N * d * d),
         "aggregate_fwd": agg_dst,
-        # per edge: Hs row + in_pair + att + (att, dz) store; per node: dOut row + out row + item
-        "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8), 2.0 * E * d),
-        # RGAT: the coefficient is the (att, dz) pair
-        "aggregate_bwd_pair": ("hbm", E * (row + 16) + P * (row + 8), 2.0 * E * d),
+        # per edge: Hs row + in_pair + att + (att, dz) store; per node: dOut row + out row + item;
+        # per single-edge pair (P1 of them): its G row and ds_src
+        "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8) + P1 * (row + 4), 2.0 * E * d),
+        # RGAT: only the E - P1 edges of the P - P1 pairs with several edges; coefficient = the (att, dz) pair
+        "aggregate_bwd_pair": ("hbm", (E - P1) * (row + 16) + (P - P1) * (row + 8), 2.0 * (E - P1) * d),
         # per run: X row + relrun_idx + run_dst + ds_dst
         "dst_side_wgrad": ("hbm", Q * (row + 12), 2.0 * Q * d),
         # per pair: dXp row + srcpair_idx; per run: ds_dst + run_rel; per node: dX row + 2 ptrs
@@ -149,6 +150,7 @@ def main():
     g = Graph(N, R, c["src"], c["dst"], c["rel"], c.get("ntype") if T > 1 else None, T,
               c.get("rel_src_ntype"), c.get("rel_dst_ntype"))
     P, Q = g.P, g.Q
+    P1 = int(g.info.num_single_pairs) if c["layer"] == "rgat" else 0
     print(f"[bench] graph index built in {time.time() - t0:.1f}s: P/E={P / E:.3f} Q/E={Q / E:.3f} "
           f"max in-degree {g.info.max_in_degree} index {g.info.index_bytes / 2**20:.0f} MiB", file=sys.stderr, flush=True)
     L = make_layer(c, g)
@@ -200,7 +202,7 @@ def main():
     kernels = []
     for name, (n, ms) in rep.items():
         avg_ms = ms / n
-        w = algorithmic_work(name, E, N, P, Q, R, T, d, H)
+        w = algorithmic_work(name, E, N, P, Q, R, T, d, H, P1)
         row = {"name": name, "launches_per_step": n / args.steps, "avg_ms": avg_ms, "ms_per_step": ms / args.steps}
         if w:
             row["GBps"] = w[1] / avg_ms / 1e6
@@ -213,7 +215,7 @@ def main():
             gb=f"{r['GBps']:.0f}" if "GBps" in r else "-", tf=f"{r['TFLOPs']:.1f}" if "TFLOPs" in r else "-", **r),
             file=sys.stderr, flush=True)
     dom = kernels[0]
-    w = algorithmic_work(dom["name"], E, N, P, Q, R, T, d, H)
+    w = algorithmic_work(dom["name"], E, N, P, Q, R, T, d, H, P1)
     if w and w[0] == "mfma":
         roof = {"kernel": dom["name"], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": FP32_MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": dom["TFLOPs"] / FP32_MFMA_PEAK_TFLOPS, "traffic": None}

@@ -66,6 +66,7 @@ typedef struct {
     int64_t index_bytes;         /* device memory held by the graph */
     int32_t num_rels;            /* R */
     int32_t num_ntypes;          /* T */
+    int64_t num_single_pairs;    /* pairs with exactly one edge */
 } rgnn_graph_info_t;
 
 /* Parameters of one layer call.  Fields a layer does not use are ignored.

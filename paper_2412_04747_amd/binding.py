@@ -40,7 +40,8 @@ class RgnnError(RuntimeError):
 class GraphInfo(C.Structure):
     _fields_ = [("num_nodes", C.c_int64), ("num_edges", C.c_int64), ("num_pairs", C.c_int64),
                 ("num_runs", C.c_int64), ("max_in_degree", C.c_int64), ("max_pair_out_degree", C.c_int64),
-                ("index_bytes", C.c_int64), ("num_rels", C.c_int32), ("num_ntypes", C.c_int32)]
+                ("index_bytes", C.c_int64), ("num_rels", C.c_int32), ("num_ntypes", C.c_int32),
+                ("num_single_pairs", C.c_int64)]
 
 
 class LayerDesc(C.Structure):

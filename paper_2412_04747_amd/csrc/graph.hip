@@ -3,7 +3,8 @@
 // Integer bookkeeping only.  Built once per graph (dataset preprocessing in the thesis,
 // Ch.3 "Code Generation": transposition, COO -> CSR; Ch.3 "Compact Tensor Materialization
 // and Data Layout": the (source node, edge type) -> row mapping, precomputed, CSR-like).
-// The sorts run on the host with an LSD radix sort; the arrays then live on the device.
+// The index arrays are produced on the device (graph_build.hip); this file derives the small
+// work lists from their offset arrays on the host and holds the graph entry points of the ABI.
 #include "rgnn_internal.h"
 
 #include <stdarg.h>
@@ -20,29 +21,6 @@ void set_error(const char* fmt, ...) {
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
-}
-
-// Stable LSD radix sort of (key, value) pairs by key, 8 bits per pass, over the
-// significant bits only.
-static void radix_sort_pairs(std::vector<uint64_t>& key, std::vector<uint32_t>& val, uint64_t max_key) {
-    const size_t n = key.size();
-    if (n < 2) return;
-    int bits = 0;
-    while (bits < 64 && (max_key >> bits) != 0) ++bits;
-    std::vector<uint64_t> k2(n);
-    std::vector<uint32_t> v2(n);
-    for (int shift = 0; shift < bits; shift += 8) {
-        size_t cnt[257] = {0};
-        for (size_t i = 0; i < n; ++i) cnt[((key[i] >> shift) & 0xFF) + 1]++;
-        for (int b = 0; b < 256; ++b) cnt[b + 1] += cnt[b];
-        for (size_t i = 0; i < n; ++i) {
-            const size_t p = cnt[(key[i] >> shift) & 0xFF]++;
-            k2[p] = key[i];
-            v2[p] = val[i];
-        }
-        key.swap(k2);
-        val.swap(v2);
-    }
 }
 
 struct Uploader {
@@ -179,172 +157,41 @@ static void build_long(Uploader& U, LongList& L, const std::vector<int32_t>& ptr
     L.ids = U.up(ids);
 }
 
-template <typename Tv>
-static rgnn_status_t fetch(std::vector<Tv>& h, const Tv* p, size_t n, int mem) {
+static rgnn_status_t download(std::vector<int32_t>& h, const int32_t* d, size_t n) {
     h.resize(n);
-    if (n == 0) return RGNN_OK;
-    if (mem == RGNN_MEM_DEVICE) RGNN_HIP(hipMemcpy(h.data(), p, n * sizeof(Tv), hipMemcpyDeviceToHost));
-    else memcpy(h.data(), p, n * sizeof(Tv));
+    if (n) RGNN_HIP(hipMemcpy(h.data(), d, n * sizeof(int32_t), hipMemcpyDeviceToHost));
     return RGNN_OK;
 }
 
+rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, const int32_t* b, const int32_t* relp,
+                                 const int32_t* ntypep, const int32_t* rstp, const int32_t* rdtp, int mem);
+
 static rgnn_status_t build(rgnn_graph* g, int format, const int32_t* a, const int32_t* b, const int32_t* relp,
                            const int32_t* ntypep, const int32_t* rstp, const int32_t* rdtp, int mem) {
-    const int64_t N = g->N, E = g->E;
-    const int32_t R = g->R, T = g->T;
-    std::vector<int32_t> src, dst, rel, ntype, rst, rdt;
-    RGNN_TRY(fetch(src, a, (size_t)E, mem));
-    RGNN_TRY(fetch(rel, relp, (size_t)E, mem));
-    if (format == RGNN_COO) {
-        RGNN_TRY(fetch(dst, b, (size_t)E, mem));
-    } else {
-        std::vector<int32_t> rp;
-        RGNN_TRY(fetch(rp, b, (size_t)N + 1, mem));
-        if (rp[0] != 0 || rp[N] != E) RGNN_FAIL(RGNN_EINVAL, "CSR rowptr must start at 0 and end at num_edges");
-        dst.resize((size_t)E);
-        for (int64_t v = 0; v < N; ++v) {
-            if (rp[v + 1] < rp[v]) RGNN_FAIL(RGNN_EINVAL, "CSR rowptr is not monotone at row %lld", (long long)v);
-            for (int32_t e = rp[v]; e < rp[v + 1]; ++e) dst[e] = (int32_t)v;
-        }
-    }
-    if (ntypep) RGNN_TRY(fetch(ntype, ntypep, (size_t)N, mem));
-    else ntype.assign((size_t)N, 0);
-    for (int64_t n = 0; n < N; ++n)
-        if (ntype[n] < 0 || ntype[n] >= T) RGNN_FAIL(RGNN_EINVAL, "ntype[%lld] = %d out of range [0, %d)", (long long)n, ntype[n], T);
-    if (rstp) {
-        RGNN_TRY(fetch(rst, rstp, (size_t)R, mem));
-        RGNN_TRY(fetch(rdt, rdtp, (size_t)R, mem));
-    }
-    for (int64_t e = 0; e < E; ++e) {
-        if (src[e] < 0 || src[e] >= N || dst[e] < 0 || dst[e] >= N || rel[e] < 0 || rel[e] >= R)
-            RGNN_FAIL(RGNN_EINVAL, "edge %lld = (%d -> %d, rel %d) out of range (N = %lld, R = %d)", (long long)e,
-                      src[e], dst[e], rel[e], (long long)N, R);
-        if (rstp && (ntype[src[e]] != rst[rel[e]] || ntype[dst[e]] != rdt[rel[e]]))
-            RGNN_FAIL(RGNN_EINVAL, "edge %lld: node types (%d -> %d) do not match relation %d's (%d -> %d)",
-                      (long long)e, ntype[src[e]], ntype[dst[e]], rel[e], rst[rel[e]], rdt[rel[e]]);
-    }
-
-    Uploader U{g};
-    const uint64_t uN = (uint64_t)std::max<int64_t>(N, 1), uR = (uint64_t)std::max<int32_t>(R, 1);
-
-    // 1. CSR order: (dst, rel, src, input id)
-    std::vector<uint64_t> key((size_t)E);
-    std::vector<uint32_t> val((size_t)E);
-    for (int64_t e = 0; e < E; ++e) {
-        key[e] = ((uint64_t)dst[e] * uR + (uint64_t)rel[e]) * uN + (uint64_t)src[e];
-        val[e] = (uint32_t)e;
-    }
-    radix_sort_pairs(key, val, uN * uR * uN);
-    std::vector<int32_t> in_ptr((size_t)N + 1, 0), in_src((size_t)E), in_rel((size_t)E), in_dst((size_t)E), in_eid((size_t)E);
-    for (int64_t i = 0; i < E; ++i) {
-        const int32_t e = (int32_t)val[i];
-        in_eid[i] = e; in_src[i] = src[e]; in_rel[i] = rel[e]; in_dst[i] = dst[e];
-        in_ptr[dst[e] + 1]++;
-    }
-    for (int64_t v = 0; v < N; ++v) in_ptr[v + 1] += in_ptr[v];
-    for (int64_t v = 0; v < N; ++v) g->max_in_degree = std::max<int64_t>(g->max_in_degree, in_ptr[v + 1] - in_ptr[v]);
-
-    // 2. pairs: CSR positions sorted by ((rel, src), position); the sorted order is the
-    //    pair-major transpose, the distinct keys in order are the pairs.
-    for (int64_t i = 0; i < E; ++i) {
-        key[i] = (uint64_t)in_rel[i] * uN + (uint64_t)in_src[i];
-        val[i] = (uint32_t)i;
-    }
-    radix_sort_pairs(key, val, uR * uN);
-    std::vector<int32_t> in_pair((size_t)E), out_epos((size_t)E), out_dst((size_t)E), pair_src, pair_rel, out_ptr;
-    std::vector<int32_t> pair_ptr((size_t)R + 1, 0);
-    for (int64_t i = 0; i < E; ++i) {
-        if (i == 0 || key[i] != key[i - 1]) {
-            pair_src.push_back((int32_t)(key[i] % uN));
-            pair_rel.push_back((int32_t)(key[i] / uN));
-            pair_ptr[pair_rel.back() + 1]++;
-            out_ptr.push_back((int32_t)i);
-        }
-        in_pair[val[i]] = (int32_t)pair_src.size() - 1;
-        out_epos[i] = (int32_t)val[i];
-        out_dst[i] = in_dst[val[i]];
-    }
-    out_ptr.push_back((int32_t)E);
-    const int64_t P = (int64_t)pair_src.size();
-    g->P = P;
-    for (int32_t r = 0; r < R; ++r) pair_ptr[r + 1] += pair_ptr[r];
-    for (int64_t p = 0; p < P; ++p)
+    RGNN_TRY(build_index_device(g, format, a, b, relp, ntypep, rstp, rdtp, mem));
+    // offsets back to the host: statistics and the work lists are cheap linear passes over them
+    std::vector<int32_t> in_ptr, out_ptr, pair_ptr, relrun_ptr, srcpair_ptr, ntype_ptr, run_ptr;
+    RGNN_TRY(download(in_ptr, g->idx[RGNN_IDX_IN_PTR], (size_t)g->N + 1));
+    RGNN_TRY(download(out_ptr, g->idx[RGNN_IDX_OUT_PTR], (size_t)g->P + 1));
+    RGNN_TRY(download(pair_ptr, g->idx[RGNN_IDX_PAIR_PTR], (size_t)g->R + 1));
+    RGNN_TRY(download(relrun_ptr, g->idx[RGNN_IDX_RELRUN_PTR], (size_t)g->R + 1));
+    RGNN_TRY(download(srcpair_ptr, g->idx[RGNN_IDX_SRCPAIR_PTR], (size_t)g->N + 1));
+    RGNN_TRY(download(ntype_ptr, g->idx[RGNN_IDX_NTYPE_PTR], (size_t)g->T + 1));
+    RGNN_TRY(download(run_ptr, g->idx[RGNN_IDX_RUN_PTR], (size_t)g->Q + 1));
+    for (int64_t v = 0; v < g->N; ++v) g->max_in_degree = std::max<int64_t>(g->max_in_degree, in_ptr[v + 1] - in_ptr[v]);
+    for (int64_t p = 0; p < g->P; ++p) {
         g->max_pair_out_degree = std::max<int64_t>(g->max_pair_out_degree, out_ptr[p + 1] - out_ptr[p]);
-
-    // 3. runs of equal (dst, rel) in CSR order
-    std::vector<int32_t> in_run((size_t)E), in_cnt((size_t)E), run_ptr, run_dst, run_rel, dst_run_ptr((size_t)N + 1, 0);
-    for (int64_t i = 0; i < E; ++i) {
-        if (i == 0 || in_dst[i] != in_dst[i - 1] || in_rel[i] != in_rel[i - 1]) {
-            run_ptr.push_back((int32_t)i);
-            run_dst.push_back(in_dst[i]);
-            run_rel.push_back(in_rel[i]);
-            dst_run_ptr[in_dst[i] + 1]++;
-        }
-        in_run[i] = (int32_t)run_dst.size() - 1;
+        g->num_single_pairs += (out_ptr[p + 1] - out_ptr[p] == 1);
     }
-    run_ptr.push_back((int32_t)E);
-    const int64_t Q = (int64_t)run_dst.size();
-    g->Q = Q;
-    for (int64_t v = 0; v < N; ++v) dst_run_ptr[v + 1] += dst_run_ptr[v];
-    std::vector<float> in_invc((size_t)E);
-    for (int64_t i = 0; i < E; ++i) {
-        in_cnt[i] = run_ptr[in_run[i] + 1] - run_ptr[in_run[i]];
-        in_invc[i] = 1.0f / (float)in_cnt[i];
-    }
-
-    // 4. runs sorted by (rel, dst)
-    key.resize((size_t)Q); val.resize((size_t)Q);
-    for (int64_t q = 0; q < Q; ++q) { key[q] = (uint64_t)run_rel[q] * uN + (uint64_t)run_dst[q]; val[q] = (uint32_t)q; }
-    radix_sort_pairs(key, val, uR * uN);
-    std::vector<int32_t> relrun_idx((size_t)Q), relrun_ptr((size_t)R + 1, 0);
-    for (int64_t i = 0; i < Q; ++i) { relrun_idx[i] = (int32_t)val[i]; relrun_ptr[run_rel[val[i]] + 1]++; }
-    for (int32_t r = 0; r < R; ++r) relrun_ptr[r + 1] += relrun_ptr[r];
-
-    // 5. pairs sorted by (src, rel)
-    key.resize((size_t)P); val.resize((size_t)P);
-    for (int64_t p = 0; p < P; ++p) { key[p] = (uint64_t)pair_src[p] * uR + (uint64_t)pair_rel[p]; val[p] = (uint32_t)p; }
-    radix_sort_pairs(key, val, uN * uR);
-    std::vector<int32_t> srcpair_idx((size_t)P), srcpair_ptr((size_t)N + 1, 0);
-    for (int64_t i = 0; i < P; ++i) { srcpair_idx[i] = (int32_t)val[i]; srcpair_ptr[pair_src[val[i]] + 1]++; }
-    for (int64_t v = 0; v < N; ++v) srcpair_ptr[v + 1] += srcpair_ptr[v];
-
-    // 6. nodes sorted by (type, id): counting sort
-    std::vector<int32_t> ntype_ptr((size_t)T + 1, 0), ntype_perm((size_t)N);
-    for (int64_t n = 0; n < N; ++n) ntype_ptr[ntype[n] + 1]++;
-    for (int32_t t = 0; t < T; ++t) ntype_ptr[t + 1] += ntype_ptr[t];
-    {
-        std::vector<int32_t> fill(ntype_ptr.begin(), ntype_ptr.end() - 1);
-        for (int64_t n = 0; n < N; ++n) ntype_perm[fill[ntype[n]]++] = (int32_t)n;
-    }
-
-    U.idx(RGNN_IDX_IN_PTR, in_ptr);       U.idx(RGNN_IDX_IN_SRC, in_src);     U.idx(RGNN_IDX_IN_REL, in_rel);
-    U.idx(RGNN_IDX_IN_EID, in_eid);       U.idx(RGNN_IDX_IN_PAIR, in_pair);   U.idx(RGNN_IDX_IN_RUN, in_run);
-    U.idx(RGNN_IDX_IN_CNT, in_cnt);       U.idx(RGNN_IDX_PAIR_PTR, pair_ptr); U.idx(RGNN_IDX_PAIR_SRC, pair_src);
-    U.idx(RGNN_IDX_PAIR_REL, pair_rel);   U.idx(RGNN_IDX_RUN_PTR, run_ptr);   U.idx(RGNN_IDX_RUN_DST, run_dst);
-    U.idx(RGNN_IDX_RUN_REL, run_rel);     U.idx(RGNN_IDX_DST_RUN_PTR, dst_run_ptr);
-    U.idx(RGNN_IDX_RELRUN_PTR, relrun_ptr); U.idx(RGNN_IDX_RELRUN_IDX, relrun_idx);
-    U.idx(RGNN_IDX_OUT_PTR, out_ptr);     U.idx(RGNN_IDX_OUT_EPOS, out_epos); U.idx(RGNN_IDX_OUT_DST, out_dst);
-    U.idx(RGNN_IDX_SRCPAIR_PTR, srcpair_ptr); U.idx(RGNN_IDX_SRCPAIR_IDX, srcpair_idx);
-    U.idx(RGNN_IDX_NTYPE_PTR, ntype_ptr); U.idx(RGNN_IDX_NTYPE_PERM, ntype_perm);
-    g->in_invc = U.up(in_invc);
-
-    // 7. work lists
+    Uploader U{g};
     build_tiles(U, g->pair_tiles, pair_ptr, kTileRows);
     build_tiles(U, g->node_tiles, ntype_ptr, kTileRows);
-    build_tiles(U, g->all_tiles, std::vector<int32_t>{0, (int32_t)N}, kTileRows);
+    build_tiles(U, g->all_tiles, std::vector<int32_t>{0, (int32_t)g->N}, kTileRows);
     build_items(U, g->dst_items, in_ptr, kItemMax);
     build_items(U, g->pair_items, out_ptr, kItemMax);
     build_items(U, g->relrun_items, relrun_ptr, kItemMax);
     build_items(U, g->pair_items_multi, out_ptr, kItemMax, 2);
     build_items(U, g->srcpair_items, srcpair_ptr, 1 << 30);
-    {   // CSR edge -> pair id, with the top bit set when the pair has this edge only
-        std::vector<int32_t> tag((size_t)E);
-        for (int64_t i = 0; i < E; ++i) {
-            const int32_t p = in_pair[i];
-            tag[i] = (out_ptr[p + 1] - out_ptr[p] == 1) ? (int32_t)((uint32_t)p | 0x80000000u) : p;
-        }
-        g->in_pair_tag = U.up(tag);
-    }
     build_long(U, g->long_runs, run_ptr);
     build_long(U, g->long_pairs, out_ptr);
     return U.st;
@@ -382,7 +229,7 @@ extern "C" rgnn_status_t rgnn_graph_create(rgnn_graph_t** gout, int64_t num_node
     g->N = num_nodes; g->E = num_edges; g->R = num_rels; g->T = num_ntypes;
     rgnn_status_t st;
     try {
-        st = build(g, format, a, b, rel, ntype, rel_src_ntype, rel_dst_ntype, mem);
+        st = build(g, format, a, b, rel, ntype, ntype ? rel_src_ntype : nullptr, ntype ? rel_dst_ntype : nullptr, mem);
     } catch (const std::bad_alloc&) {
         set_error("out of host memory while building the graph index");
         st = RGNN_ENOMEM;
@@ -405,6 +252,7 @@ extern "C" rgnn_status_t rgnn_graph_info(const rgnn_graph_t* g, rgnn_graph_info_
     out->num_nodes = g->N; out->num_edges = g->E; out->num_pairs = g->P; out->num_runs = g->Q;
     out->max_in_degree = g->max_in_degree; out->max_pair_out_degree = g->max_pair_out_degree;
     out->index_bytes = (int64_t)g->index_bytes; out->num_rels = g->R; out->num_ntypes = g->T;
+    out->num_single_pairs = g->num_single_pairs;
     return RGNN_OK;
 }
 

@@ -60,20 +60,25 @@ __global__ void fold_weight_kernel(const float* __restrict__ W, const float* __r
     wv[i] = s;
 }
 
-// s_dst[q] = X[run_dst[q]] . wtp[run_rel[q]]
+// s_dst[q] = X[run_dst[q]] . wtp[run_rel[q]]; each lane group takes four consecutive runs so
+// that four row reads are in flight per lane.
 template <int D>
 __global__ void run_logit_kernel(int Q, const int32_t* __restrict__ run_dst, const int32_t* __restrict__ run_rel,
                                  const float* __restrict__ X, const float* __restrict__ wtp, float* __restrict__ s_dst) {
     constexpr int LPR = D / 4;
-    const int q = (blockIdx.x * blockDim.x + threadIdx.x) / LPR, c4 = threadIdx.x % LPR;
-    float s = 0.f;
-    if (q < Q) {
-        const float4 x = *reinterpret_cast<const float4*>(X + (size_t)run_dst[q] * D + c4 * 4);
-        const float4 w = *reinterpret_cast<const float4*>(wtp + (size_t)run_rel[q] * D + c4 * 4);
-        s = dot4(x, w);
+    const int q0 = ((blockIdx.x * blockDim.x + threadIdx.x) / LPR) * 4, c4 = threadIdx.x % LPR;
+    float4 x[4], w[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int q = min(q0 + u, Q - 1);
+        x[u] = *reinterpret_cast<const float4*>(X + (size_t)run_dst[q] * D + c4 * 4);
+        w[u] = *reinterpret_cast<const float4*>(wtp + (size_t)run_rel[q] * D + c4 * 4);
     }
-    s = group_sum<LPR>(s);
-    if (q < Q && c4 == 0) s_dst[q] = s;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const float s = group_sum<LPR>(dot4(x[u], w[u]));
+        if (q0 + u < Q && c4 == 0) s_dst[q0 + u] = s;
+    }
 }
 
 // out[i] = sum_{j in [ptr[i], ptr[i+1])} val[(via ? via[j] : j) * stride + off].
@@ -374,17 +379,39 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     if (a.extra) acc = *reinterpret_cast<const float4*>(a.extra + (size_t)u * D + c4 * 4);
     const int b = a.it.beg[i], e = a.it.end[i];
-    for (int j = b; j < e; j += 2) {
-        const float4 v0 = *reinterpret_cast<const float4*>(a.dXp + (size_t)a.srcpair_idx[j] * D + c4 * 4);
-        float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (j + 1 < e) v1 = *reinterpret_cast<const float4*>(a.dXp + (size_t)a.srcpair_idx[j + 1] * D + c4 * 4);
-        fma4(acc, 1.f, v0);
-        fma4(acc, 1.f, v1);
+    float4 acc1 = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = b; j < e; j += 4) {
+        float4 v[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            v[t] = j + t < e ? *reinterpret_cast<const float4*>(a.dXp + (size_t)a.srcpair_idx[j + t] * D + c4 * 4)
+                             : make_float4(0.f, 0.f, 0.f, 0.f);
+        fma4(acc, 1.f, v[0]);
+        fma4(acc1, 1.f, v[1]);
+        fma4(acc, 1.f, v[2]);
+        fma4(acc1, 1.f, v[3]);
     }
     if (a.ds_dst) {
-        for (int q = a.dst_run_ptr[u]; q < a.dst_run_ptr[u + 1]; ++q)
-            fma4(acc, a.ds_dst[q], *reinterpret_cast<const float4*>(a.wtp + (size_t)a.run_rel[q] * D + c4 * 4));
+        const int qb = a.dst_run_ptr[u], qe = a.dst_run_ptr[u + 1];
+        for (int q = qb; q < qe; q += 4) {
+            float c[4];
+            float4 v[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                c[t] = 0.f;
+                v[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (q + t < qe) {
+                    c[t] = a.ds_dst[q + t];
+                    v[t] = *reinterpret_cast<const float4*>(a.wtp + (size_t)a.run_rel[q + t] * D + c4 * 4);
+                }
+            }
+            fma4(acc, c[0], v[0]);
+            fma4(acc1, c[1], v[1]);
+            fma4(acc, c[2], v[2]);
+            fma4(acc1, c[3], v[3]);
+        }
     }
+    fma4(acc, 1.f, acc1);
     *reinterpret_cast<float4*>(a.dX + (size_t)u * D + c4 * 4) = acc;
 }
 
@@ -457,7 +484,7 @@ rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w,
 rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st) {
     if (g->Q == 0) return RGNN_OK;
     KernelTimer kt(st, "run_logit");
-    DISPATCH_D(D, hipLaunchKernelGGL(run_logit_kernel<DD>, dim3(blocks_for((size_t)g->Q * (DD / 4), 256)), dim3(256), 0,
+    DISPATCH_D(D, hipLaunchKernelGGL(run_logit_kernel<DD>, dim3(blocks_for((size_t)((g->Q + 3) / 4) * (DD / 4), 256)), dim3(256), 0,
                                      st, (int)g->Q, g->idx[RGNN_IDX_RUN_DST], g->idx[RGNN_IDX_RUN_REL], X, wtp, s_dst));
     CHECK_LAUNCH();
     return RGNN_OK;
