@@ -21,7 +21,7 @@ HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
-def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0):
+def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False):
     """(bound, bytes, flops) one launch of kernel `name` must move / compute (fp32 arithmetic,
     4-byte elements).  Gathered rows are counted once per reference (no cache reuse assumed);
     index and scalar traffic as listed; see DESIGN.md "Kernels and their rooflines"."""
@@ -64,6 +64,20 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0):
         "hgt_softmax": ("hbm", E * H * 8 + N * 8, 10.0 * E * H),
         "aggregate_bwd_msg": agg_pair, "aggregate_bwd_key": agg_pair, "aggregate_bwd_query": agg_dst,
     }
+    if bf16 and d == 128:
+        # bfloat16 workloads at width 128: the backward typed linear is two kernels.  "<label>" forms
+        # dXrow = dY W^T (dY row in, dXrow row out), "<label>.wgrad" the weight gradient (X row, 2-byte
+        # elements when X is a bf16 input, + dY row); forward typed linears read 2-byte rows of bf16 inputs.
+        rows = {"typed_linear": P, "pair_linear": P, "node_linear": N}
+        key = name.split(".")[0]
+        n_rows = next((v for k, v in rows.items() if key.startswith(k)), None)
+        x_in = key.startswith("node_linear") and not key.startswith("node_linear_out") or key.startswith("typed_linear")
+        if n_rows is not None and key.endswith("_bwd"):
+            if name.endswith(".wgrad"):
+                return ("hbm", n_rows * ((row // 2 if x_in else row) + row + 4), 2.0 * n_rows * d * d)
+            return ("hbm", n_rows * (2 * row + 4), 2.0 * n_rows * d * d)
+        if n_rows is not None and key in table:
+            return ("hbm", n_rows * ((row // 2 if x_in else row) + row + 4), 2.0 * n_rows * d * d)
     return table.get(name)
 
 
@@ -202,7 +216,7 @@ def main():
     kernels = []
     for name, (n, ms) in rep.items():
         avg_ms = ms / n
-        w = algorithmic_work(name, E, N, P, Q, R, T, d, H, P1)
+        w = algorithmic_work(name, E, N, P, Q, R, T, d, H, P1, c["dtype"] == "bf16")
         row = {"name": name, "launches_per_step": n / args.steps, "avg_ms": avg_ms, "ms_per_step": ms / args.steps}
         if w:
             row["GBps"] = w[1] / avg_ms / 1e6
@@ -215,7 +229,7 @@ def main():
             gb=f"{r['GBps']:.0f}" if "GBps" in r else "-", tf=f"{r['TFLOPs']:.1f}" if "TFLOPs" in r else "-", **r),
             file=sys.stderr, flush=True)
     dom = kernels[0]
-    w = algorithmic_work(dom["name"], E, N, P, Q, R, T, d, H, P1)
+    w = algorithmic_work(dom["name"], E, N, P, Q, R, T, d, H, P1, c["dtype"] == "bf16")
     if w and w[0] == "mfma":
         roof = {"kernel": dom["name"], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": FP32_MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": dom["TFLOPs"] / FP32_MFMA_PEAK_TFLOPS, "traffic": None}

@@ -4,6 +4,9 @@
 #include "rgnn_internal.h"
 #include "traversal.h"
 
+#include <map>
+#include <mutex>
+
 using namespace rgnn;
 
 namespace {
@@ -202,6 +205,16 @@ rgnn_status_t tl_fwd(bool bf16, const rgnn::TileList* tiles, int d, const float*
 // Backward typed linear: dXrow = dY W^T (rows through `gather` on both sides when `both_gathered`),
 // dW = sum X^T dY.  fp32: one fused kernel.  bf16 mode at width 128: two kernels on the bf16 matrix
 // cores (dY split into two bf16 planes; X as is when its bf16 original exists).
+// "<label>.wgrad", with static storage (kernel-timer names must outlive the call)
+const char* wgrad_label(const char* label) {
+    static std::mutex mu;
+    static std::map<std::string, std::string> names;
+    std::lock_guard<std::mutex> lk(mu);
+    auto it = names.find(label);
+    if (it == names.end()) it = names.emplace(label, std::string(label) + ".wgrad").first;
+    return it->second.c_str();
+}
+
 rgnn_status_t tl_bwd(bool bf16, const rgnn::TileList* tiles, int d, const float* X32, const void* X16,
                      const int32_t* gather, int both_gathered, const float* W32, const void* W16, const float* dY,
                      float* dXrow, float* dW, float* part, const char* label, hipStream_t st) {
@@ -212,7 +225,7 @@ rgnn_status_t tl_bwd(bool bf16, const rgnn::TileList* tiles, int d, const float*
         RGNN_TRY(typed_linear_bf16(d, a, st));
         TypedLinearWgradBf16Args w{};
         w.tiles = tiles; w.X = X16 ? X16 : X32; w.x_bf16 = X16 != nullptr; w.gather = gather; w.dy_gathered = both_gathered;
-        w.dY = dY; w.part = part; w.label = "typed_linear_wgrad";
+        w.dY = dY; w.part = part; w.label = wgrad_label(label);
         RGNN_TRY(typed_linear_wgrad_bf16(d, w, st));
         return typed_linear_slot_reduce(d, d, *tiles, part, dW, nullptr, st);
     }
