@@ -149,6 +149,15 @@ static void build_items(Uploader& U, ItemList& L, const std::vector<int32_t>& pt
     L.long_item = U.up(lng);
 }
 
+// Longest item for a list of `total` entries: kItemMax on large lists; shorter on small ones, where
+// a few long serial walks would otherwise be the whole run time (never below kSerialMax, so that
+// every item a single lane walks stays short).
+static int item_cut(int64_t total) {
+    int cut = kSerialMax;
+    while (cut < kItemMax && (int64_t)cut * kItemTarget < total) cut *= 2;
+    return cut;
+}
+
 static void build_long(Uploader& U, LongList& L, const std::vector<int32_t>& ptr) {
     std::vector<int32_t> ids;
     for (size_t i = 0; i + 1 < ptr.size(); ++i)
@@ -187,10 +196,10 @@ static rgnn_status_t build(rgnn_graph* g, int format, const int32_t* a, const in
     build_tiles(U, g->pair_tiles, pair_ptr, kTileRows);
     build_tiles(U, g->node_tiles, ntype_ptr, kTileRows);
     build_tiles(U, g->all_tiles, std::vector<int32_t>{0, (int32_t)g->N}, kTileRows);
-    build_items(U, g->dst_items, in_ptr, kItemMax);
-    build_items(U, g->pair_items, out_ptr, kItemMax);
-    build_items(U, g->relrun_items, relrun_ptr, kItemMax);
-    build_items(U, g->pair_items_multi, out_ptr, kItemMax, 2);
+    build_items(U, g->dst_items, in_ptr, item_cut(g->E));
+    build_items(U, g->pair_items, out_ptr, item_cut(g->E));
+    build_items(U, g->relrun_items, relrun_ptr, item_cut(g->Q));
+    build_items(U, g->pair_items_multi, out_ptr, item_cut(g->E), 2);
     build_items(U, g->srcpair_items, srcpair_ptr, 1 << 30);
     build_long(U, g->long_runs, run_ptr);
     build_long(U, g->long_pairs, out_ptr);

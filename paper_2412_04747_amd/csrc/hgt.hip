@@ -11,36 +11,9 @@
 // zero blocks cost no time.
 #include "rgnn_internal.h"
 #include "traversal.h"
+#include "device_utils.h"
 
 namespace rgnn {
-
-struct Items {
-    int n;
-    const int32_t* beg;
-    const int32_t* end;
-    const int32_t* row;
-    const int32_t* slot;
-};
-static Items dev_items(const ItemList& L) { return Items{L.num_items, L.beg, L.end, L.row, L.slot}; }
-
-template <int W>
-__device__ __forceinline__ float group_sum(float v) {
-#pragma unroll
-    for (int o = W / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-__device__ __forceinline__ float group_sum_dyn(float v, int w) {
-    for (int o = w / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
-}
-__device__ __forceinline__ float dot4(const float4& a, const float4& b) {
-    return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
-}
 
 // Wbd[r][i][j] = c(r, h) * W[r][h][i % dh][j % dh] if i and j lie in the same head h, else 0.
 // c = (mu ? mu[r][h] : 1) / sqrt(dh) when `scaled` (attention), 1 otherwise (message).
@@ -220,28 +193,19 @@ __global__ void add3_kernel(size_t n, const float* __restrict__ a, const float* 
 }
 
 // ---------------------------------------------------------------------------------------- launchers
-#define CHECK_LAUNCH() RGNN_HIP(hipGetLastError())
-static inline unsigned blocks_for(size_t n, unsigned per_block) { return (unsigned)((n + per_block - 1) / per_block); }
-#define DISPATCH_D(D_, CALL)                                                           \
-    do {                                                                               \
-        if ((D_) == 64) { constexpr int DD = 64; CALL; }                               \
-        else if ((D_) == 32) { constexpr int DD = 32; CALL; }                          \
-        else if ((D_) == 128) { constexpr int DD = 128; CALL; }                        \
-        else RGNN_FAIL(RGNN_EUNSUPPORTED, "feature width %d not supported (32/64/128)", (int)(D_)); \
-    } while (0)
 
 rgnn_status_t hgt_expand(int R, int d, int H, const float* W, const float* mu, int scaled, float* Wbd, hipStream_t st) {
     KernelTimer kt(st, "hgt_expand");
     hipLaunchKernelGGL(hgt_expand_kernel, dim3(blocks_for((size_t)R * d * d, 256)), dim3(256), 0, st, R, d, H, W, mu,
                        scaled, Wbd);
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 rgnn_status_t hgt_extract(int R, int d, int H, const float* dWbd, const float* W, const float* mu, int scaled, float* dW,
                           float* dmu, hipStream_t st) {
     KernelTimer kt(st, "hgt_extract");
     hipLaunchKernelGGL(hgt_extract_kernel, dim3(R * H), dim3(256), 0, st, d, H, dWbd, W, mu, scaled, dW, dmu);
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const float* Ka, const float* Q, float* logit,
@@ -249,9 +213,9 @@ rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const float* Ka,
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
     KernelTimer kt(st, "hgt_edge_logit");
-    DISPATCH_D(D, hipLaunchKernelGGL(hgt_edge_logit_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
+    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(hgt_edge_logit_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
                                      0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], Ka, Q, logit));
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st) {
@@ -261,11 +225,11 @@ rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m,
         KernelTimer kt(st, "hgt_softmax");
         hipLaunchKernelGGL(hgt_softmax_kernel, dim3(blocks_for((size_t)g->N * H, 256)), dim3(256), 0, st, (int)g->N, H,
                            g->idx[RGNN_IDX_IN_PTR], att);
-        CHECK_LAUNCH();
+        RGNN_CHECK_LAUNCH();
         if (L.num_long > 0) {
             hipLaunchKernelGGL(hgt_softmax_long_kernel, dim3(blocks_for((size_t)L.num_long * 64, 256)), dim3(256), 0, st,
                                dev_items(L), L.num_long, L.long_item, H, att, part_m, part_s);
-            CHECK_LAUNCH();
+            RGNN_CHECK_LAUNCH();
         }
     }
     if (L.num_partials > 0) {
@@ -273,7 +237,7 @@ rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m,
         hipLaunchKernelGGL(hgt_softmax_finish_kernel, dim3(blocks_for((size_t)L.num_partials * 64, 256)), dim3(256), 0,
                            st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), H, part_m, part_s,
                            att);
-        CHECK_LAUNCH();
+        RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;
 }
@@ -282,16 +246,16 @@ rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* a
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
     KernelTimer kt(st, "hgt_edge_dot_bwd");
-    DISPATCH_D(D, hipLaunchKernelGGL(hgt_edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))),
+    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(hgt_edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))),
                                      dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], att, M, dZ, Z, dl));
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 rgnn_status_t add3(size_t n, const float* a, const float* b, const float* c, float* out, hipStream_t st) {
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, "add3");
     hipLaunchKernelGGL(add3_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, a, b, c, out);
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 

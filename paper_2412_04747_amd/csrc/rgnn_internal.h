@@ -119,6 +119,7 @@ constexpr int kTileRows = 64;       // rows per typed-linear tile
 constexpr int kMaxChunks = 4096;    // tile chunks (workgroups) of the typed-linear kernels: several per resident
                                     // workgroup slot, so the hardware dispatcher evens out the tail
 constexpr int kItemMax = 256;       // longest traversal item (entries)
+constexpr int kItemTarget = 65536;  // lists are cut finer while they yield fewer items than this
 constexpr int kSerialMax = 32;      // longest segment a single lane walks; longer ones get a wavefront
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -153,7 +154,6 @@ struct TypedLinearBwdArgs {
     float* Avec;             // [segs][KD] (with rowscale)
     float* part;             // scratch [num_slots][KD*ND + KD]
     const char* label;
-    int wgrad_only;          // 1: skip dXrow (the caller forms it elsewhere)
 };
 // bf16 matrix-core variant (typed_linear_bf16.hip): Y[i] = A[g(i)] W[seg]  (or W[seg]^T)
 struct TypedLinearBf16Args {

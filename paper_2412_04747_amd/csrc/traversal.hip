@@ -15,35 +15,9 @@
 // of each cut segment in order.
 #include "rgnn_internal.h"
 #include "traversal.h"
+#include "device_utils.h"
 
 namespace rgnn {
-
-struct Items {
-    int n;
-    const int32_t* beg;
-    const int32_t* end;
-    const int32_t* row;
-    const int32_t* slot;
-};
-static Items dev_items(const ItemList& L) { return Items{L.num_items, L.beg, L.end, L.row, L.slot}; }
-
-template <int W>
-__device__ __forceinline__ float group_sum(float v) {
-#pragma unroll
-    for (int o = W / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
-}
-__device__ __forceinline__ float dot4(const float4& a, const float4& b) {
-    return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
-}
-__device__ __forceinline__ void fma4(float4& acc, float c, const float4& v) {
-    acc.x += c * v.x; acc.y += c * v.y; acc.z += c * v.z; acc.w += c * v.w;
-}
 
 // ------------------------------------------------------------------ small dense helpers
 
@@ -462,31 +436,21 @@ __global__ void widen_bf16_kernel(size_t n, const uint16_t* __restrict__ src, fl
 
 // ==================================================================== host launchers
 
-#define CHECK_LAUNCH() RGNN_HIP(hipGetLastError())
-static inline unsigned blocks_for(size_t n, unsigned per_block) { return (unsigned)((n + per_block - 1) / per_block); }
-
-#define DISPATCH_D(D_, CALL)                                                           \
-    do {                                                                               \
-        if ((D_) == 64) { constexpr int DD = 64; CALL; }                               \
-        else if ((D_) == 32) { constexpr int DD = 32; CALL; }                          \
-        else if ((D_) == 128) { constexpr int DD = 128; CALL; }                        \
-        else RGNN_FAIL(RGNN_EUNSUPPORTED, "feature width %d not supported (32/64/128)", (int)(D_)); \
-    } while (0)
 
 rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st) {
     const int total = R * kd;
     KernelTimer kt(st, "fold_weight");
     hipLaunchKernelGGL(fold_weight_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, st, W, w, kd, nd, total, wv);
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 
 rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st) {
     if (g->Q == 0) return RGNN_OK;
     KernelTimer kt(st, "run_logit");
-    DISPATCH_D(D, hipLaunchKernelGGL(run_logit_kernel<DD>, dim3(blocks_for((size_t)((g->Q + 3) / 4) * (DD / 4), 256)), dim3(256), 0,
+    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(run_logit_kernel<DD>, dim3(blocks_for((size_t)((g->Q + 3) / 4) * (DD / 4), 256)), dim3(256), 0,
                                      st, (int)g->Q, g->idx[RGNN_IDX_RUN_DST], g->idx[RGNN_IDX_RUN_REL], X, wtp, s_dst));
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 
@@ -496,11 +460,11 @@ rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng,
     KernelTimer kt(st, label);
     hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ptr, via, val, stride,
                        off, min_len, out);
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     if (lng.n > 0) {
         hipLaunchKernelGGL(segment_scalar_sum_long_kernel, dim3(blocks_for((size_t)lng.n * 64, 256)), dim3(256), 0, st,
                            lng.n, lng.ids, ptr, via, val, stride, off, out);
-        CHECK_LAUNCH();
+        RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;
 }
@@ -514,18 +478,18 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
         KernelTimer kt(st, "edge_softmax");
         hipLaunchKernelGGL(edge_softmax_kernel, dim3(blocks_for((size_t)g->N, 256)), dim3(256), 0, st, a, (int)g->N,
                            g->idx[RGNN_IDX_IN_PTR]);
-        CHECK_LAUNCH();
+        RGNN_CHECK_LAUNCH();
         if (L.num_long > 0) {
             hipLaunchKernelGGL(edge_softmax_long_kernel, dim3(blocks_for((size_t)L.num_long * 64, 256)), dim3(256), 0, st,
                                a, L.num_long, L.long_item);
-            CHECK_LAUNCH();
+            RGNN_CHECK_LAUNCH();
         }
     }
     if (L.num_partials > 0) {
         KernelTimer kt(st, "edge_softmax.finish");
         hipLaunchKernelGGL(edge_softmax_finish_kernel, dim3(blocks_for((size_t)L.num_partials * 64, 256)), dim3(256), 0,
                            st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), part_m, part_s, att);
-        CHECK_LAUNCH();
+        RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;
 }
@@ -538,16 +502,16 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
     {
         KernelTimer kt(st, label);
         const dim3 grid(blocks_for(L.num_items, 256 / (D / 4)));
-        if (role == 0) DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 0>), grid, dim3(256), 0, st, a));
-        else if (role == 1) DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 1>), grid, dim3(256), 0, st, a));
-        else DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 2>), grid, dim3(256), 0, st, a));
-        CHECK_LAUNCH();
+        if (role == 0) RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 0>), grid, dim3(256), 0, st, a));
+        else if (role == 1) RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 1>), grid, dim3(256), 0, st, a));
+        else RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 2>), grid, dim3(256), 0, st, a));
+        RGNN_CHECK_LAUNCH();
     }
     if (L.num_split > 0) {
         KernelTimer kt(st, combine_label);
-        DISPATCH_D(D, hipLaunchKernelGGL(combine_partials_kernel<DD>, dim3(L.num_split), dim3(1024), 0, st, L.split_row,
+        RGNN_DISPATCH_D(D, hipLaunchKernelGGL(combine_partials_kernel<DD>, dim3(L.num_split), dim3(1024), 0, st, L.split_row,
                                          L.split_ptr, partial, out));
-        CHECK_LAUNCH();
+        RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;
 }
@@ -558,9 +522,9 @@ rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const f
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
     EdgeDotArgs a{dev_items(L), g->in_pair_tag, att, Hs, dOut, out, slope, reinterpret_cast<float2*>(adz), G, ds_src};
     KernelTimer kt(st, "edge_dot_bwd");
-    DISPATCH_D(D, hipLaunchKernelGGL(edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
+    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
                                      0, st, a));
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 
@@ -570,9 +534,9 @@ rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const float* dXp, const 
     NodeSumArgs a{dev_items(g->srcpair_items), g->idx[RGNN_IDX_SRCPAIR_PTR], g->idx[RGNN_IDX_SRCPAIR_IDX], dXp,
                   g->idx[RGNN_IDX_DST_RUN_PTR], g->idx[RGNN_IDX_RUN_REL], ds_dst, wtp, extra, dX};
     KernelTimer kt(st, "node_grad_sum");
-    DISPATCH_D(D, hipLaunchKernelGGL(node_grad_sum_kernel<DD>, dim3(blocks_for((size_t)g->N, 256 / (DD / 4))), dim3(256),
+    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(node_grad_sum_kernel<DD>, dim3(blocks_for((size_t)g->N, 256 / (DD / 4))), dim3(256),
                                      0, st, a));
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 
@@ -580,7 +544,7 @@ rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const flo
                                 const float* A, const float* U, float* dW, float* dw_s, float* dw_t, hipStream_t st) {
     KernelTimer kt(st, "rgat_param_finish");
     hipLaunchKernelGGL(rgat_param_finish_kernel, dim3(R), dim3(256), 0, st, kd, nd, W, w_s, w_t, A, U, dW, dw_s, dw_t);
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 
@@ -588,21 +552,21 @@ rgnn_status_t widen_bf16(size_t n, const uint16_t* src, float* dst, hipStream_t 
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, "widen_bf16");
     hipLaunchKernelGGL(widen_bf16_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, src, dst);
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 rgnn_status_t relu_inplace(size_t n, float* x, hipStream_t st) {
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, "relu");
     hipLaunchKernelGGL(relu_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, x);
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 rgnn_status_t relu_grad(size_t n, const float* ref, const float* gin, float* y, hipStream_t st) {
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, "relu_grad");
     hipLaunchKernelGGL(relu_grad_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ref, gin, y);
-    CHECK_LAUNCH();
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_kernel(TileArgs t, const
 // dW and Avec stay in registers while consecutive tiles share a segment and are flushed to
 // the chunk's partial slot when the segment changes; a second kernel sums the slots of each
 // segment in slot order, so the result does not depend on scheduling.
-template <int KD, int ND, bool WGRAD_ONLY>
+template <int KD, int ND>
 __global__ __launch_bounds__(256) void typed_linear_bwd_kernel(TileArgs t, const float* __restrict__ X,
                                                                const int32_t* __restrict__ gather,
                                                                const float* __restrict__ W,
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(256) void typed_linear_bwd_kernel(TileArgs t, const
         for (int b = 0; b < DBW; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) accx[b][v] = 0.f;
-        if (!WGRAD_ONLY && wave < DBLK) {
+        if (wave < DBLK) {
 #pragma unroll 2
             for (int tt = 0; tt < ND / 8; ++tt) {
                 const int n0 = kh * (ND / 2) + 4 * tt;
@@ -296,7 +296,6 @@ __global__ __launch_bounds__(256) void typed_linear_bwd_kernel(TileArgs t, const
             for (int r = tid / KD; r < TM; r += AG) acca += dss[r] * Xs[r * XS + k];
         }
         __syncthreads();  // all reads of dYs done; reuse it to stage dXrow
-        if (WGRAD_ONLY) continue;
         if (wave < DBLK) {
 #pragma unroll
             for (int b = 0; b < DBW; ++b) {
@@ -751,7 +750,7 @@ template <int KD, int ND>
 static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
     if (a.tiles->num_tiles > 0) {
         bool done = false;
-        if constexpr (KD <= 64 && ND <= 64) if (!a.wgrad_only) {
+        if constexpr (KD <= 64 && ND <= 64) {
             const bool g = a.gather != nullptr, dg = g && a.dy_gathered, sc = g && a.scatter_dx, rs = a.rowscale != nullptr;
             done = true;
             if (g && !dg && !sc && rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true>(a, st)));
@@ -763,7 +762,7 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
         if (!done) {
             constexpr int STG = (KD > ND ? KD : ND) + 4;
             const size_t lds = sizeof(float) * (KD * (ND + 1) + TM * STG + TM * (KD + 4) + TM + 256);
-            auto kern = a.wgrad_only ? typed_linear_bwd_kernel<KD, ND, true> : typed_linear_bwd_kernel<KD, ND, false>;
+            auto kern = typed_linear_bwd_kernel<KD, ND>;
             RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
             hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather,
