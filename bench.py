@@ -21,35 +21,55 @@ HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
-def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False):
-    """(bound, bytes, flops) one launch of kernel `name` must move / compute (fp32 arithmetic,
-    4-byte elements).  Gathered rows are counted once per reference (no cache reuse assumed);
-    index and scalar traffic as listed; see DESIGN.md "Kernels and their rooflines"."""
-    b = 4
-    row = d * b
-    w2 = d * d * b
+def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat"):
+    """(bound, bytes, flops) one launch of kernel `name` must move / compute.  Gathered rows are
+    counted once per reference (no cache reuse assumed); index and scalar traffic as listed; see
+    DESIGN.md "Kernels and their rooflines".  Row tensors are 4-byte elements, except in the
+    bfloat16 workloads at width 128, where inputs and intermediate rows are 2-byte elements
+    (results handed back to the caller stay fp32)."""
+    half = bf16 and d == 128
+    r32 = d * 4                       # an fp32 row
+    row = d * 2 if half else r32      # an input / intermediate row
+    wb = 2 if half else 4             # element size of a given weight
+    if half:
+        rows = {"typed_linear": P, "pair_linear": P, "node_linear": N}
+        key = name.split(".")[0]
+        n = next((v for k, v in rows.items() if key.startswith(k)), None)
+        if n is not None:
+            # one row in, one row out (or two rows in for the weight gradient), + the gather index
+            segs = T if key.startswith("node_linear") else R
+            w2 = d * d * (4 if key.startswith("pair_linear") else wb)       # block-diagonal weights are fp32
+            if name.endswith(".wgrad"):
+                return ("hbm", n * (2 * row + 4) + segs * d * d * 4, 2.0 * n * d * d)
+            out_row = r32 if key in ("node_linear_out", "node_linear_k_bwd", "node_linear_q_bwd", "node_linear_v_bwd") else row
+            extra = r32 if key in ("node_linear_q_bwd", "node_linear_v_bwd") else 0   # accumulate into dX
+            return ("hbm", n * (row + out_row + extra + 4) + segs * w2, 2.0 * n * d * d)
+    w2 = d * d * 4
     pair_fwd = ("mfma", P * (2 * row + 4) + R * w2, 2.0 * P * d * d)        # gathered row + stored row + pair_src
     pair_bwd = ("mfma", P * (3 * row + 4) + R * w2, 4.0 * P * d * d)        # dY row + gathered row + stored row
     node_fwd = ("mfma", N * (2 * row + 4) + T * w2, 2.0 * N * d * d)
     node_bwd = ("mfma", N * (3 * row + 4) + T * w2, 4.0 * N * d * d)
-    agg_dst = ("hbm", E * (row + 4 + 4 * H) + N * (row + 8), 2.0 * E * d)    # row + in_pair + coefficient(s); out row + item
-    agg_pair = ("hbm", E * (row + 8 + 4 * H) + P * (row + 8), 2.0 * E * d)   # row + out_epos + out_dst + coefficient(s)
+    out_dst = row if layer == "hgt" else r32                                  # HGT's Z / dQ are intermediates
+    agg_dst = ("hbm", E * (row + 4 + 4 * H) + N * (out_dst + 8), 2.0 * E * d)  # row + in_pair + coefficient(s); out row + item
+    agg_pair = ("hbm", E * (row + 8 + 4 * H) + P * (row + 8), 2.0 * E * d)    # row + out_epos + out_dst + coefficient(s)
     table = {
         # RGAT: + s_src per pair; backward also reads ds_src
-        "typed_linear_fwd": ("mfma", pair_fwd[1] + P * 4, pair_fwd[2]),
-        "typed_linear_bwd": ("mfma", pair_bwd[1] + P * 4, pair_bwd[2]),
-        "self_loop_fwd": ("mfma", N * 3 * row + w2, 2.0 * N * d * d),         # X row + out row read and written
-        "self_loop_bwd": ("mfma", N * 3 * row + w2, 4.0 * N * d * d),
+        "typed_linear_fwd": ("mfma", pair_fwd[1] + (P * 4 if layer == "rgat" else 0), pair_fwd[2]),
+        "typed_linear_bwd": ("mfma", pair_bwd[1] + (P * 4 if layer == "rgat" else 0), pair_bwd[2]),
+        "self_loop_fwd": ("mfma", N * 3 * r32 + w2, 2.0 * N * d * d),         # X row + out row read and written
+        "self_loop_bwd": ("mfma", N * 3 * r32 + w2, 4.0 * N * d * d),
         "aggregate_fwd": agg_dst,
         # per edge: Hs row + in_pair + att + (att, dz) store; per node: dOut row + out row + item;
         # per single-edge pair (P1 of them): its G row and ds_src
         "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8) + P1 * (row + 4), 2.0 * E * d),
-        # RGAT: only the E - P1 edges of the P - P1 pairs with several edges; coefficient = the (att, dz) pair
-        "aggregate_bwd_pair": ("hbm", (E - P1) * (row + 16) + (P - P1) * (row + 8), 2.0 * (E - P1) * d),
+        # RGAT: only the E - P1 edges of the P - P1 pairs with several edges; coefficient = the (att, dz) pair.
+        # RGCN: every edge; row + out_dst + coefficient
+        "aggregate_bwd_pair": ("hbm", (E - P1) * (row + 16) + (P - P1) * (row + 8), 2.0 * (E - P1) * d) if layer == "rgat"
+                              else ("hbm", E * (row + 8) + P * (row + 8), 2.0 * E * d),
         # per run: X row + relrun_idx + run_dst + ds_dst
         "dst_side_wgrad": ("hbm", Q * (row + 12), 2.0 * Q * d),
-        # per pair: dXp row + srcpair_idx; per run: ds_dst + run_rel; per node: dX row + 2 ptrs
-        "node_grad_sum": ("hbm", P * (row + 4) + Q * 8 + N * (row + 8), 1.0 * P * d),
+        # per pair: dXp row + srcpair_idx; per run (RGAT): ds_dst + run_rel; per node: result row + 2 ptrs
+        "node_grad_sum": ("hbm", P * (row + 4) + (Q * 8 if layer == "rgat" else 0) + N * (out_dst + 8), 1.0 * P * d),
         # per edge: in_pair, in_run, s_src, s_dst, att write (reads of its own writes not counted)
         "edge_softmax": ("hbm", E * 20 + N * 8, 10.0 * E),
         "run_logit": ("hbm", Q * (row + 12), 2.0 * Q * d),
@@ -64,20 +84,6 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False):
         "hgt_softmax": ("hbm", E * H * 8 + N * 8, 10.0 * E * H),
         "aggregate_bwd_msg": agg_pair, "aggregate_bwd_key": agg_pair, "aggregate_bwd_query": agg_dst,
     }
-    if bf16 and d == 128:
-        # bfloat16 workloads at width 128: the backward typed linear is two kernels.  "<label>" forms
-        # dXrow = dY W^T (dY row in, dXrow row out), "<label>.wgrad" the weight gradient (X row, 2-byte
-        # elements when X is a bf16 input, + dY row); forward typed linears read 2-byte rows of bf16 inputs.
-        rows = {"typed_linear": P, "pair_linear": P, "node_linear": N}
-        key = name.split(".")[0]
-        n_rows = next((v for k, v in rows.items() if key.startswith(k)), None)
-        x_in = key.startswith("node_linear") and not key.startswith("node_linear_out") or key.startswith("typed_linear")
-        if n_rows is not None and key.endswith("_bwd"):
-            if name.endswith(".wgrad"):
-                return ("hbm", n_rows * ((row // 2 if x_in else row) + row + 4), 2.0 * n_rows * d * d)
-            return ("hbm", n_rows * (2 * row + 4), 2.0 * n_rows * d * d)
-        if n_rows is not None and key in table:
-            return ("hbm", n_rows * ((row // 2 if x_in else row) + row + 4), 2.0 * n_rows * d * d)
     return table.get(name)
 
 
@@ -216,7 +222,7 @@ def main():
     kernels = []
     for name, (n, ms) in rep.items():
         avg_ms = ms / n
-        w = algorithmic_work(name, E, N, P, Q, R, T, d, H, P1, c["dtype"] == "bf16")
+        w = algorithmic_work(name, E, N, P, Q, R, T, d, H, P1, c["dtype"] == "bf16", c["layer"])
         row = {"name": name, "launches_per_step": n / args.steps, "avg_ms": avg_ms, "ms_per_step": ms / args.steps}
         if w:
             row["GBps"] = w[1] / avg_ms / 1e6
@@ -229,7 +235,7 @@ def main():
             gb=f"{r['GBps']:.0f}" if "GBps" in r else "-", tf=f"{r['TFLOPs']:.1f}" if "TFLOPs" in r else "-", **r),
             file=sys.stderr, flush=True)
     dom = kernels[0]
-    w = algorithmic_work(dom["name"], E, N, P, Q, R, T, d, H, P1, c["dtype"] == "bf16")
+    w = algorithmic_work(dom["name"], E, N, P, Q, R, T, d, H, P1, c["dtype"] == "bf16", c["layer"])
     if w and w[0] == "mfma":
         roof = {"kernel": dom["name"], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": FP32_MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": dom["TFLOPs"] / FP32_MFMA_PEAK_TFLOPS, "traffic": None}

@@ -71,9 +71,13 @@ typedef struct {
 
 /* Parameters of one layer call.  Fields a layer does not use are ignored.
  *   dtype      storage type of the INPUT tensor arguments (X, every weight, dOut):
- *              RGNN_F32, or RGNN_BF16 = bfloat16 inputs.  Arithmetic is fp32 and every
- *              output (out, all gradients) and the `out` argument of the backward calls
- *              are fp32 in both cases.
+ *              RGNN_F32, or RGNN_BF16 = bfloat16 inputs.  Sums and products are fp32 and
+ *              every output (out, all gradients) and the `out` argument of the backward
+ *              calls are fp32 in both cases.  With RGNN_BF16 at width 128 the RGCN and HGT
+ *              layers also keep their intermediate row tensors (projected messages, keys,
+ *              queries, values and their gradients, in the workspace and in `saved`) in
+ *              bfloat16, rounded to nearest even from the fp32 accumulators; results then
+ *              agree with an fp64 evaluation to a few 1e-3 relative to the largest entry.
  *   d_in,d_out feature widths.  Supported: d_in == d_out in {32, 64, 128}.
  *   heads      HGT: number of heads H (d_out % H == 0, d_out/H in {16, 32, 64}); RGAT: must be 1.
  *   slope      RGAT leaky-ReLU negative slope (the derivative at 0 is `slope`).

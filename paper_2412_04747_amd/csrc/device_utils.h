@@ -38,14 +38,90 @@ __device__ __forceinline__ void fma4(float4& acc, float c, const float4& v) {
     acc.x += c * v.x; acc.y += c * v.y; acc.z += c * v.z; acc.w += c * v.w;
 }
 
+// ---- feature rows in fp32 or bf16 storage --------------------------------------------------------
+// A lane owns the columns one 16-byte load brings in: 4 of an fp32 row, 8 of a bf16 row.  All
+// arithmetic is fp32; bf16 is a storage format only (widening is exact, narrowing rounds to
+// nearest even).
+typedef unsigned short bf16_t;   // bit pattern of a bfloat16
+
+template <typename T> struct RowT;
+template <> struct RowT<float> { static constexpr int V = 4; };
+template <> struct RowT<bf16_t> { static constexpr int V = 8; };
+
+// two fp32 -> packed bf16 pair (lo in bits 0..15), round to nearest even, one v_cvt_pk_bf16_f32
+typedef float rgnn_v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 rgnn_bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned bf16_pack2(float lo, float hi) {
+    const rgnn_v2f v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, rgnn_bf16x2));
+}
+
+// v[0..V) = p[0..V), p 16-byte aligned for V * sizeof(T) == 16 (8-byte aligned for four bf16)
+template <int V>
+__device__ __forceinline__ void load_cols(const float* __restrict__ p, float (&v)[V]) {
+#pragma unroll
+    for (int q = 0; q < V / 4; ++q) {
+        const float4 t = reinterpret_cast<const float4*>(p)[q];
+        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+    }
+}
+template <int V>
+__device__ __forceinline__ void load_cols(const bf16_t* __restrict__ p, float (&v)[V]) {
+    if constexpr (V == 8) {
+        const uint4 t = *reinterpret_cast<const uint4*>(p);
+        v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+        v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+        v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xFFFF0000u);
+        v[6] = __uint_as_float(t.w << 16); v[7] = __uint_as_float(t.w & 0xFFFF0000u);
+    } else {
+        static_assert(V == 4, "four or eight columns per lane");
+        const uint2 t = *reinterpret_cast<const uint2*>(p);
+        v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+        v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+    }
+}
+template <int V>
+__device__ __forceinline__ void store_cols(float* __restrict__ p, const float (&v)[V]) {
+#pragma unroll
+    for (int q = 0; q < V / 4; ++q)
+        reinterpret_cast<float4*>(p)[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+}
+template <int V>
+__device__ __forceinline__ void store_cols(bf16_t* __restrict__ p, const float (&v)[V]) {
+    if constexpr (V == 8) {
+        *reinterpret_cast<uint4*>(p) = make_uint4(bf16_pack2(v[0], v[1]), bf16_pack2(v[2], v[3]), bf16_pack2(v[4], v[5]),
+                                                  bf16_pack2(v[6], v[7]));
+    } else {
+        static_assert(V == 4, "four or eight columns per lane");
+        *reinterpret_cast<uint2*>(p) = make_uint2(bf16_pack2(v[0], v[1]), bf16_pack2(v[2], v[3]));
+    }
+}
+template <int V>
+__device__ __forceinline__ void zero_cols(float (&v)[V]) {
+#pragma unroll
+    for (int q = 0; q < V; ++q) v[q] = 0.f;
+}
+template <int V>
+__device__ __forceinline__ void fma_cols(float (&acc)[V], float c, const float (&v)[V]) {
+#pragma unroll
+    for (int q = 0; q < V; ++q) acc[q] += c * v[q];
+}
+template <int V>
+__device__ __forceinline__ float dot_cols(const float (&a)[V], const float (&b)[V]) {
+    float s = 0.f;
+#pragma unroll
+    for (int q = 0; q < V; ++q) s += a[q] * b[q];
+    return s;
+}
+
 inline unsigned blocks_for(size_t n, unsigned per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 
 #define RGNN_CHECK_LAUNCH() RGNN_HIP(hipGetLastError())
-#define RGNN_DISPATCH_D(D_, CALL)                                                      \
+#define RGNN_DISPATCH_D(D_, ...)                                                       \
     do {                                                                               \
-        if ((D_) == 64) { constexpr int DD = 64; CALL; }                               \
-        else if ((D_) == 32) { constexpr int DD = 32; CALL; }                          \
-        else if ((D_) == 128) { constexpr int DD = 128; CALL; }                        \
+        if ((D_) == 64) { constexpr int DD = 64; __VA_ARGS__; }                               \
+        else if ((D_) == 32) { constexpr int DD = 32; __VA_ARGS__; }                          \
+        else if ((D_) == 128) { constexpr int DD = 128; __VA_ARGS__; }                        \
         else RGNN_FAIL(RGNN_EUNSUPPORTED, "feature width %d not supported (32/64/128)", (int)(D_)); \
     } while (0)
 

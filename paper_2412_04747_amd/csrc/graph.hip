@@ -56,7 +56,8 @@ struct Uploader {
 };
 
 // Tiles of `tile_rows` rows over segments seg_ptr[0..S], cut into chunks.
-static void build_tiles(Uploader& U, TileList& t, const std::vector<int32_t>& seg_ptr, int tile_rows) {
+static void build_tiles(Uploader& U, TileList& t, const std::vector<int32_t>& seg_ptr, int tile_rows,
+                        int max_chunks = kMaxChunks) {
     const int S = (int)seg_ptr.size() - 1;
     std::vector<int32_t> tseg, r0, r1;
     for (int s = 0; s < S; ++s)
@@ -66,7 +67,9 @@ static void build_tiles(Uploader& U, TileList& t, const std::vector<int32_t>& se
             r1.push_back(std::min<int32_t>(a + tile_rows, seg_ptr[s + 1]));
         }
     const int nt = (int)tseg.size();
-    const int nc = std::min(nt, kMaxChunks);
+    // a chunk pays for one weight-tile load and one weight-gradient flush, so it should span several
+    // tiles; but small inputs still need a few hundred chunks to occupy the compute units
+    const int nc = std::min(max_chunks, std::max(std::min(nt, kMinChunks), nt / kChunkTiles));
     std::vector<int32_t> ctile(nc + 1, 0), cslot(std::max(nc, 1), 0), sslot(S + 1, 0);
     int slots = 0;
     std::vector<int32_t> seg_slots(S, 0);
@@ -119,15 +122,18 @@ static void build_items(Uploader& U, ItemList& L, const std::vector<int32_t>& pt
     }
     // Order the items by length, longest first (stable): the lanes of a wavefront and the
     // wavefronts of a workgroup then walk items of equal length and finish together, and the
-    // long items are scheduled before the short ones fill the tail.
+    // long items are scheduled before the short ones fill the tail.  Among items of equal length
+    // the pieces of cut segments come first, so the whole segments with exactly one entry form
+    // one contiguous range [first_single, first_single + num_single), which has a kernel of its own.
     {
         const int n = (int)beg.size();
         int longest = 0;
         for (int i = 0; i < n; ++i) longest = std::max(longest, end[i] - beg[i]);
-        std::vector<int32_t> cnt(longest + 2, 0), perm(n), inv(n);
-        for (int i = 0; i < n; ++i) cnt[longest - (end[i] - beg[i]) + 1]++;
-        for (int l = 0; l <= longest; ++l) cnt[l + 1] += cnt[l];
-        for (int i = 0; i < n; ++i) { const int p = cnt[longest - (end[i] - beg[i])]++; perm[p] = i; inv[i] = p; }
+        auto key = [&](int i) { return 2 * (longest - (end[i] - beg[i])) + (slot[i] < 0 ? 1 : 0); };
+        std::vector<int32_t> cnt(2 * longest + 3, 0), perm(n), inv(n);
+        for (int i = 0; i < n; ++i) cnt[key(i) + 1]++;
+        for (size_t l = 0; l + 1 < cnt.size(); ++l) cnt[l + 1] += cnt[l];
+        for (int i = 0; i < n; ++i) { const int p = cnt[key(i)]++; perm[p] = i; inv[i] = p; }
         auto apply = [&](std::vector<int32_t>& v) {
             std::vector<int32_t> t(n);
             for (int p = 0; p < n; ++p) t[p] = v[perm[p]];
@@ -135,6 +141,13 @@ static void build_items(Uploader& U, ItemList& L, const std::vector<int32_t>& pt
         };
         apply(beg); apply(end); apply(row); apply(slot);
         for (auto& it : pitem) it = inv[it];
+        L.first_single = n;
+        L.num_single = 0;
+        for (int i = 0; i < n; ++i)
+            if (end[i] - beg[i] == 1 && slot[i] < 0) {
+                if (L.num_single == 0) L.first_single = i;
+                ++L.num_single;
+            }
     }
     L.num_items = (int)beg.size();
     L.num_partials = partials;
@@ -196,9 +209,11 @@ static rgnn_status_t build(rgnn_graph* g, int format, const int32_t* a, const in
     build_tiles(U, g->pair_tiles, pair_ptr, kTileRows);
     build_tiles(U, g->node_tiles, ntype_ptr, kTileRows);
     build_tiles(U, g->all_tiles, std::vector<int32_t>{0, (int32_t)g->N}, kTileRows);
+    build_tiles(U, g->pair_tiles_wide, pair_ptr, kTileRows, kWideChunks);
+    build_tiles(U, g->node_tiles_wide, ntype_ptr, kTileRows, kWideChunks);
     build_items(U, g->dst_items, in_ptr, item_cut(g->E));
     build_items(U, g->pair_items, out_ptr, item_cut(g->E));
-    build_items(U, g->relrun_items, relrun_ptr, item_cut(g->Q));
+    build_items(U, g->relrun_items, relrun_ptr, item_cut(g->E));
     build_items(U, g->pair_items_multi, out_ptr, item_cut(g->E), 2);
     build_items(U, g->srcpair_items, srcpair_ptr, 1 << 30);
     build_long(U, g->long_runs, run_ptr);

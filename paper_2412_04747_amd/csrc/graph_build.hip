@@ -180,6 +180,11 @@ __global__ void k_sorted_major(long long n, long long mul, const u64* key, const
     major[i] = (int32_t)(key[i] / (u64)mul);
     perm[i] = (int32_t)val[i];
 }
+// out_invc[j] = in_invc[out_epos[j]]: the per-edge norm coefficient in pair-major edge order
+__global__ void k_permute_f32(long long n, const int32_t* idx, const float* src, float* dst) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[idx[i]];
+}
 __global__ void k_tag(long long E, const int32_t* in_pair, const int32_t* out_ptr, int32_t* tag) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= E) return;
@@ -235,7 +240,7 @@ rgnn_status_t input(Tmp& hold, const T* p, size_t n, int mem, const T** out) {
 
 }  // namespace
 
-// Fills g->idx[*], g->in_invc, g->in_pair_tag, g->P, g->Q.  Synchronous.
+// Fills g->idx[*], g->in_invc, g->out_invc, g->in_pair_tag, g->P, g->Q.  Synchronous.
 rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, const int32_t* b, const int32_t* relp,
                                  const int32_t* ntypep, const int32_t* rstp, const int32_t* rdtp, int mem) {
     const long long N = g->N, E = g->E;
@@ -364,6 +369,8 @@ rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, co
     // ---- 7. pair ids tagged with "single edge"
     RGNN_TRY(keep<int32_t>(g, (size_t)E, &g->in_pair_tag));
     LAUNCH(k_tag, (size_t)E, E, g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_OUT_PTR], g->in_pair_tag);
+    RGNN_TRY(keep<float>(g, (size_t)E, &g->out_invc));
+    LAUNCH(k_permute_f32, (size_t)E, E, g->idx[RGNN_IDX_OUT_EPOS], g->in_invc, g->out_invc);
     RGNN_HIP(hipDeviceSynchronize());
     return RGNN_OK;
 }

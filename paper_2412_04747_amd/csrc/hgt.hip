@@ -61,29 +61,30 @@ __global__ void hgt_extract_kernel(int d, int H, const float* __restrict__ dWbd,
     if (threadIdx.x == 0) dmu[r * H + h] = red[0] * inv;
 }
 
-// logit[e][h] = Ka[pair_e][h] . Q[v][h]   (Ka already carries mu / sqrt(dh))
-template <int D>
+// logit[e][h] = Ka[pair_e][h] . Q[v][h]   (Ka already carries mu / sqrt(dh)); TI = storage type of the rows
+template <int D, typename TI>
 __global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, const int32_t* __restrict__ in_pair,
-                                                             const float* __restrict__ Ka,
-                                                             const float* __restrict__ Q, float* __restrict__ logit) {
-    constexpr int LPR = D / 4, IPB = 256 / LPR;
-    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+                                                             const TI* __restrict__ Ka, const TI* __restrict__ Q,
+                                                             float* __restrict__ logit) {
+    constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
+    const int i = blockIdx.x * IPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
     if (i >= it.n) return;
     const int b = it.beg[i], e = it.end[i];
     if (e == b) return;
-    const int lph = LPR / H, head = c4 / lph;
-    const float4 q = *reinterpret_cast<const float4*>(Q + (size_t)it.row[i] * D + c4 * 4);
+    const int lph = LPR / H, head = cv / lph;
+    float q[V];
+    load_cols(Q + (size_t)it.row[i] * D + cv * V, q);
     for (int j = b; j < e; j += 4) {
-        float4 k[4];
+        float k[4][V];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            k[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (j + u < e) k[u] = *reinterpret_cast<const float4*>(Ka + (size_t)in_pair[j + u] * D + c4 * 4);
+            if (j + u < e) load_cols(Ka + (size_t)in_pair[j + u] * D + cv * V, k[u]);
+            else zero_cols(k[u]);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float s = group_sum_dyn(dot4(q, k[u]), lph);
-            if (c4 % lph == 0 && j + u < e) logit[(size_t)(j + u) * H + head] = s;
+            const float s = group_sum_dyn(dot_cols(q, k[u]), lph);
+            if (cv % lph == 0 && j + u < e) logit[(size_t)(j + u) * H + head] = s;
         }
     }
 }
@@ -150,38 +151,38 @@ __global__ void hgt_softmax_finish_kernel(int num_partials, const int32_t* __res
 
 // dl[e][h] = att[e][h] * (dZ[v][h] . M[pair_e][h] - dZ[v][h] . Z[v][h])
 // (the second term is sum_e att_e g_e because Z[v][h] = sum_e att_e M[pair_e][h]).
-template <int D>
+template <int D, typename TI>
 __global__ __launch_bounds__(256) void hgt_edge_dot_bwd_kernel(Items it, int H, const int32_t* __restrict__ in_pair,
                                                                const float* __restrict__ att,
-                                                               const float* __restrict__ M,
-                                                               const float* __restrict__ dZ,
-                                                               const float* __restrict__ Z, float* __restrict__ dl) {
-    constexpr int LPR = D / 4, IPB = 256 / LPR;
-    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+                                                               const TI* __restrict__ M, const TI* __restrict__ dZ,
+                                                               const TI* __restrict__ Z, float* __restrict__ dl) {
+    constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
+    const int i = blockIdx.x * IPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
     if (i >= it.n) return;
     const int b = it.beg[i], e = it.end[i];
     if (e == b) return;
-    const int lph = LPR / H, head = c4 / lph;
+    const int lph = LPR / H, head = cv / lph;
     const size_t v = (size_t)it.row[i];
-    const float4 gz = *reinterpret_cast<const float4*>(dZ + v * D + c4 * 4);
-    const float4 zz = *reinterpret_cast<const float4*>(Z + v * D + c4 * 4);
-    const float gbar = group_sum_dyn(dot4(gz, zz), lph);
+    float gz[V], zz[V];
+    load_cols(dZ + v * D + cv * V, gz);
+    load_cols(Z + v * D + cv * V, zz);
+    const float gbar = group_sum_dyn(dot_cols(gz, zz), lph);
     for (int j = b; j < e; j += 4) {
-        float4 mm[4];
+        float mm[4][V];
         float a[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            mm[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            zero_cols(mm[u]);
             a[u] = 0.f;
             if (j + u < e) {
-                mm[u] = *reinterpret_cast<const float4*>(M + (size_t)in_pair[j + u] * D + c4 * 4);
+                load_cols(M + (size_t)in_pair[j + u] * D + cv * V, mm[u]);
                 a[u] = att[(size_t)(j + u) * H + head];
             }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float g = group_sum_dyn(dot4(gz, mm[u]), lph);
-            if (c4 % lph == 0 && j + u < e) dl[(size_t)(j + u) * H + head] = a[u] * (g - gbar);
+            const float g = group_sum_dyn(dot_cols(gz, mm[u]), lph);
+            if (cv % lph == 0 && j + u < e) dl[(size_t)(j + u) * H + head] = a[u] * (g - gbar);
         }
     }
 }
@@ -208,13 +209,21 @@ rgnn_status_t hgt_extract(int R, int d, int H, const float* dWbd, const float* W
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
-rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const float* Ka, const float* Q, float* logit,
-                             hipStream_t st) {
+rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const void* Ka, const void* Q, float* logit,
+                             hipStream_t st, int rows_bf16) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
     KernelTimer kt(st, "hgt_edge_logit");
-    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(hgt_edge_logit_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
-                                     0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], Ka, Q, logit));
+    if (rows_bf16) {
+        if (D != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "bf16 rows need width 128, got %d", D);
+        hipLaunchKernelGGL((hgt_edge_logit_kernel<128, bf16_t>), dim3(blocks_for(L.num_items, 256 / (128 / 8))), dim3(256), 0, st,
+                           dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], static_cast<const bf16_t*>(Ka),
+                           static_cast<const bf16_t*>(Q), logit);
+    } else {
+        RGNN_DISPATCH_D(D, hipLaunchKernelGGL((hgt_edge_logit_kernel<DD, float>), dim3(blocks_for(L.num_items, 256 / (DD / 4))),
+                                              dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR],
+                                              static_cast<const float*>(Ka), static_cast<const float*>(Q), logit));
+    }
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
@@ -241,13 +250,22 @@ rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m,
     }
     return RGNN_OK;
 }
-rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* att, const float* M, const float* dZ,
-                               const float* Z, float* dl, hipStream_t st) {
+rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* att, const void* M, const void* dZ,
+                               const void* Z, float* dl, hipStream_t st, int rows_bf16) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
     KernelTimer kt(st, "hgt_edge_dot_bwd");
-    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(hgt_edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))),
-                                     dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], att, M, dZ, Z, dl));
+    if (rows_bf16) {
+        if (D != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "bf16 rows need width 128, got %d", D);
+        hipLaunchKernelGGL((hgt_edge_dot_bwd_kernel<128, bf16_t>), dim3(blocks_for(L.num_items, 256 / (128 / 8))), dim3(256), 0,
+                           st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], att, static_cast<const bf16_t*>(M),
+                           static_cast<const bf16_t*>(dZ), static_cast<const bf16_t*>(Z), dl);
+    } else {
+        RGNN_DISPATCH_D(D, hipLaunchKernelGGL((hgt_edge_dot_bwd_kernel<DD, float>), dim3(blocks_for(L.num_items, 256 / (DD / 4))),
+                                              dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], att,
+                                              static_cast<const float*>(M), static_cast<const float*>(dZ),
+                                              static_cast<const float*>(Z), dl));
+    }
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

@@ -22,11 +22,18 @@ struct Carver {
         off += align_up(std::max<size_t>(n, 1) * sizeof(Tv));
         return p;
     }
+    // n elements of a row tensor stored as bf16 (half) or fp32
+    void* rows(size_t n, bool half) { return half ? static_cast<void*>(take<uint16_t>(n)) : static_cast<void*>(take<float>(n)); }
 };
 
-// bfloat16 inputs: every bf16 tensor argument is widened to fp32 in a staging area that
-// follows the regular carve-out of the workspace, and the fp32 kernels run on the copies
-// (bf16 storage at the boundary, fp32 arithmetic and fp32 results).
+// bfloat16 workloads at width 128 keep every row tensor (inputs, intermediates, saved tensors,
+// incoming gradients) in bf16 storage and run the typed linears on the bf16 matrix cores; sums
+// and products are fp32, results handed back to the caller are fp32.  At the other widths the
+// bf16 inputs are widened once and the fp32 kernels run on the copies.
+inline bool rows_bf16(const rgnn_layer_desc_t* d) { return d->dtype == RGNN_BF16 && d->d_out == 128; }
+
+// bfloat16 inputs that an fp32 kernel consumes are widened to fp32 in a staging area that
+// follows the regular carve-out of the workspace.
 struct Bf16Stage {
     Carver c;
     bool on;
@@ -107,20 +114,22 @@ size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
 }
 
 // ---- RGCN buffers -----------------------------------------------------------------------
-struct RgcnFwdWs { float* Hs; float* partial; };
-struct RgcnBwdWs { float* dPre; float* G; float* dXp; float* dX0; float* tl_part; float* partial; };
+struct RgcnFwdWs { void* Hs; float* partial; };
+struct RgcnBwdWs { void* dPre; float* dPre32; void* G; void* dXp; float* dX0; float* tl_part; float* partial; };
 
 size_t carve_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgcnFwdWs* w) {
     Carver c(base);
-    w->Hs = c.take<float>((size_t)g->P * d->d_out);
+    w->Hs = c.rows((size_t)g->P * d->d_out, rows_bf16(d));
     w->partial = c.take<float>((size_t)g->dst_items.num_partials * d->d_out);
     return c.off;
 }
 size_t carve_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgcnBwdWs* w) {
     Carver c(base);
-    w->dPre = c.take<float>(d->activation == RGNN_ACT_RELU ? (size_t)g->N * d->d_out : 0);
-    w->G = c.take<float>((size_t)g->P * d->d_out);
-    w->dXp = c.take<float>((size_t)g->P * d->d_in);
+    const bool h = rows_bf16(d), relu = d->activation == RGNN_ACT_RELU;
+    w->dPre = c.rows(relu ? (size_t)g->N * d->d_out : 0, h);
+    w->dPre32 = c.take<float>(relu && h ? (size_t)g->N * d->d_out : 0);   // fp32 copy for the self-loop kernels
+    w->G = c.rows((size_t)g->P * d->d_out, h);
+    w->dXp = c.rows((size_t)g->P * d->d_in, h);
     w->dX0 = c.take<float>((size_t)g->N * d->d_in);
     w->tl_part = c.take<float>(std::max(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles),
                                         typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->all_tiles)));
@@ -129,19 +138,21 @@ size_t carve_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
 }
 
 // ---- HGT buffers ------------------------------------------------------------------------
-struct HgtSaved { float* K; float* Q; float* V; float* Z; float* Ka; float* M; float* att; };
+// Row tensors (void*) are bf16 when rows_bf16(desc), fp32 otherwise.
+struct HgtSaved { void* K; void* Q; void* V; void* Z; void* Ka; void* M; float* att; };
 struct HgtFwdWs { float* Wbd_att; float* Wbd_msg; float* part_m; float* part_s; float* partial; };
 struct HgtBwdWs {
-    float* Wbd_att; float* Wbd_msg; float* dWbd_att; float* dWbd_msg; float* dZ; float* dl; float* dM; float* dKa;
-    float* dQ; float* dKp; float* dVp; float* dK; float* dV; float* dXk; float* dXq; float* dXv; float* tl_part;
+    float* Wbd_att; float* Wbd_msg; float* dWbd_att; float* dWbd_msg; void* dZ; float* dl; void* dM; void* dKa;
+    void* dQ; void* dKp; void* dVp; void* dK; void* dV; float* dXk; float* dXq; float* dXv; float* tl_part;
     float* partial;
 };
 
 size_t carve_hgt_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtSaved* s) {
     Carver c(base);
+    const bool h = rows_bf16(d);
     const size_t nd = (size_t)g->N * d->d_out, pd = (size_t)g->P * d->d_out;
-    s->K = c.take<float>(nd); s->Q = c.take<float>(nd); s->V = c.take<float>(nd); s->Z = c.take<float>(nd);
-    s->Ka = c.take<float>(pd); s->M = c.take<float>(pd);
+    s->K = c.rows(nd, h); s->Q = c.rows(nd, h); s->V = c.rows(nd, h); s->Z = c.rows(nd, h);
+    s->Ka = c.rows(pd, h); s->M = c.rows(pd, h);
     s->att = c.take<float>((size_t)g->E * d->heads);
     return c.off;
 }
@@ -156,21 +167,23 @@ size_t carve_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* ba
 }
 size_t carve_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtBwdWs* w) {
     Carver c(base);
+    const bool h = rows_bf16(d);
     const size_t D = d->d_out, rdd = (size_t)g->R * D * D, nd = (size_t)g->N * D, pd = (size_t)g->P * D;
     w->Wbd_att = c.take<float>(rdd); w->Wbd_msg = c.take<float>(rdd);
     w->dWbd_att = c.take<float>(rdd); w->dWbd_msg = c.take<float>(rdd);
-    w->dZ = c.take<float>(nd); w->dl = c.take<float>((size_t)g->E * d->heads);
-    w->dM = c.take<float>(pd); w->dKa = c.take<float>(pd); w->dQ = c.take<float>(nd);
-    w->dKp = c.take<float>(pd); w->dVp = c.take<float>(pd);
-    w->dK = c.take<float>(nd); w->dV = c.take<float>(nd);
-    w->dXk = c.take<float>(nd); w->dXq = c.take<float>(nd); w->dXv = c.take<float>(nd);
+    w->dZ = c.rows(nd, h); w->dl = c.take<float>((size_t)g->E * d->heads);
+    w->dM = c.rows(pd, h); w->dKa = c.rows(pd, h); w->dQ = c.rows(nd, h);
+    w->dKp = c.rows(pd, h); w->dVp = c.rows(pd, h);
+    w->dK = c.rows(nd, h); w->dV = c.rows(nd, h);
+    w->dXk = c.take<float>(h ? 0 : nd); w->dXq = c.take<float>(h ? 0 : nd); w->dXv = c.take<float>(h ? 0 : nd);
     w->tl_part = c.take<float>(std::max(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles),
                                         typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->node_tiles)));
     w->partial = c.take<float>((size_t)std::max(g->pair_items.num_partials, g->dst_items.num_partials) * D);
     return c.off;
 }
 
-// Staging sizes, in the order the entry points widen their arguments.
+// Staging sizes: room for every tensor argument an entry point may widen (an upper bound at width 128,
+// where most bf16 arguments are consumed as they are).
 size_t stage_bytes(const rgnn_graph_t* g, int layer, const rgnn_layer_desc_t* d, bool bwd) {
     Bf16Stage s(nullptr, 0, d->dtype == RGNN_BF16, nullptr);
     const size_t N = g->N, R = g->R, T = g->T, di = d->d_in, dz = d->d_out;
@@ -187,24 +200,23 @@ size_t stage_bytes(const rgnn_graph_t* g, int layer, const rgnn_layer_desc_t* d,
 }
 
 // Forward typed linear  Y[g(i)] / Y[i] = A[g(i)] W[seg].  In bf16 mode it runs on the bf16 matrix
-// cores: an operand whose bf16 original exists (A16 / W16) is used as is, an fp32-only one is split.
+// cores: an operand whose bf16 form exists (A16 / W16) is used as is, an fp32-only one is split.
+// y16: the output rows are stored as bf16 (width 128 only).
 rgnn_status_t tl_fwd(bool bf16, const rgnn::TileList* tiles, int d, const float* A32, const void* A16,
-                     const int32_t* gather, int scatter, const float* W32, const void* W16, float* Y,
+                     const int32_t* gather, int scatter, const float* W32, const void* W16, void* Y, bool y16,
                      const char* label, hipStream_t st) {
     if (bf16) {
         TypedLinearBf16Args a{};
         a.tiles = tiles; a.A = A16 ? A16 : A32; a.a_bf16 = A16 != nullptr; a.gather = gather; a.scatter_out = scatter;
-        a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.Y = Y; a.label = label;
+        a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.Y = Y; a.y_bf16 = y16; a.label = label;
         return typed_linear_bf16(d, a, st);
     }
     TypedLinearArgs a{};
-    a.tiles = tiles; a.X = A32; a.gather = gather; a.W = W32; a.Y = Y; a.scatter_out = scatter; a.label = label;
+    a.tiles = tiles; a.X = A32; a.gather = gather; a.W = W32; a.Y = static_cast<float*>(Y); a.scatter_out = scatter;
+    a.label = label;
     return typed_linear_fwd(d, d, a, st);
 }
 
-// Backward typed linear: dXrow = dY W^T (rows through `gather` on both sides when `both_gathered`),
-// dW = sum X^T dY.  fp32: one fused kernel.  bf16 mode at width 128: two kernels on the bf16 matrix
-// cores (dY split into two bf16 planes; X as is when its bf16 original exists).
 // "<label>.wgrad", with static storage (kernel-timer names must outlive the call)
 const char* wgrad_label(const char* label) {
     static std::mutex mu;
@@ -215,23 +227,33 @@ const char* wgrad_label(const char* label) {
     return it->second.c_str();
 }
 
-rgnn_status_t tl_bwd(bool bf16, const rgnn::TileList* tiles, int d, const float* X32, const void* X16,
-                     const int32_t* gather, int both_gathered, const float* W32, const void* W16, const float* dY,
-                     float* dXrow, float* dW, float* part, const char* label, hipStream_t st) {
-    if (bf16 && d == 128) {
+// Backward typed linear: dXrow = dY W^T (rows through `gather` on both sides when `both_gathered`),
+// dW = sum X^T dY.
+//   rows16 (bf16 rows, width 128): X and dY are bf16; two kernels on the bf16 matrix cores (dY W^T with
+//     the weight as is when its bf16 form W16 exists, split otherwise; X^T dY into per-chunk slots) and
+//     the slot reduction.  dXrow is stored as bf16 (dx16) or fp32.
+//   otherwise: the fused fp32 kernel on fp32 X, W, dY.
+//   wide: the same tiles in fewer chunks, for the weight-gradient kernel;  dx_acc: dXrow += (fp32 dXrow, rows16)
+rgnn_status_t tl_bwd(bool rows16, const rgnn::TileList* tiles, const rgnn::TileList* wide, int d, const void* X,
+                     const int32_t* gather, int both_gathered, const float* W32, const void* W16, const void* dY,
+                     void* dXrow, bool dx16, float* dW, float* part, const char* label, hipStream_t st,
+                     bool dx_acc = false) {
+    if (rows16) {
         TypedLinearBf16Args a{};
-        a.tiles = tiles; a.A = dY; a.a_bf16 = 0; a.gather = both_gathered ? gather : nullptr; a.scatter_out = both_gathered;
-        a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.transpose_w = 1; a.Y = dXrow; a.label = label;
+        a.tiles = tiles; a.A = dY; a.a_bf16 = 1; a.gather = both_gathered ? gather : nullptr; a.scatter_out = both_gathered;
+        a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.transpose_w = 1; a.Y = dXrow; a.y_bf16 = dx16; a.accumulate = dx_acc; a.label = label;
         RGNN_TRY(typed_linear_bf16(d, a, st));
         TypedLinearWgradBf16Args w{};
-        w.tiles = tiles; w.X = X16 ? X16 : X32; w.x_bf16 = X16 != nullptr; w.gather = gather; w.dy_gathered = both_gathered;
-        w.dY = dY; w.part = part; w.label = wgrad_label(label);
+        w.tiles = wide; w.X = X; w.gather = gather; w.dy_gathered = both_gathered; w.dY = dY; w.part = part;
+        w.label = wgrad_label(label);
         RGNN_TRY(typed_linear_wgrad_bf16(d, w, st));
-        return typed_linear_slot_reduce(d, d, *tiles, part, dW, nullptr, st);
+        return typed_linear_slot_reduce(d, d, *wide, part, dW, nullptr, st);
     }
+    if (dx_acc) RGNN_FAIL(RGNN_EUNSUPPORTED, "accumulating input gradient needs bf16 rows");
     TypedLinearBwdArgs b{};
-    b.tiles = tiles; b.X = X32; b.gather = gather; b.W = W32; b.dY = dY; b.dy_gathered = both_gathered;
-    b.dXrow = dXrow; b.scatter_dx = both_gathered; b.dW = dW; b.part = part; b.label = label;
+    b.tiles = tiles; b.X = static_cast<const float*>(X); b.gather = gather; b.W = W32; b.dY = static_cast<const float*>(dY);
+    b.dy_gathered = both_gathered; b.dXrow = static_cast<float*>(dXrow); b.scatter_dx = both_gathered; b.dW = dW;
+    b.part = part; b.label = label;
     return typed_linear_bwd(d, d, b, st);
 }
 
@@ -279,25 +301,25 @@ extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out;
     RgcnFwdWs w;
-    const bool bf16 = desc->dtype == RGNN_BF16;
+    const bool bf16 = desc->dtype == RGNN_BF16, h = rows_bf16(desc);
     const void* X16 = bf16 ? X : nullptr;
     const void* W16 = bf16 ? W : nullptr;
     Bf16Stage stg(workspace, carve_rgcn_fwd(g, desc, workspace, &w), bf16, st);
-    X = stg.in(X, (size_t)g->N * desc->d_in);
-    W = stg.in(W, (size_t)g->R * desc->d_in * D);
-    W0 = stg.in(W0, (size_t)desc->d_in * D);
+    // fp32 copies for the fp32 kernels: everything below width 128, only the self-loop operands at 128
+    const float* X32 = (!h || W0) ? stg.in(X, (size_t)g->N * desc->d_in) : nullptr;
+    const float* W32 = !h ? stg.in(W, (size_t)g->R * desc->d_in * D) : nullptr;
+    const float* W032 = stg.in(W0, (size_t)desc->d_in * D);
     RGNN_TRY(stg.status);
     // 1. compact messages: Hs[p] = X[pair_src[p]] W[rel(p)]
-    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, static_cast<const float*>(X), X16, g->idx[RGNN_IDX_PAIR_SRC], 0,
-                    static_cast<const float*>(W), W16, w.Hs, "typed_linear_fwd", st));
+    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, X32, X16, g->idx[RGNN_IDX_PAIR_SRC], 0, W32, W16, w.Hs, h, "typed_linear_fwd", st));
     // 2. out[v] = sum_e (1/c) Hs[pair_e]
     const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
-    RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, coef, 1, 0, w.Hs,
-                        static_cast<float*>(out), w.partial, st, 0, "aggregate_fwd", "aggregate_fwd.combine"));
+    RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, coef, 1, 0, w.Hs, out, w.partial, st, 0,
+                        "aggregate_fwd", "aggregate_fwd.combine", 1, h, 0));
     // 3. self-loop: out += X W0
     if (W0) {
         TypedLinearArgs s{};
-        s.tiles = &g->all_tiles; s.X = static_cast<const float*>(X); s.W = static_cast<const float*>(W0);
+        s.tiles = &g->all_tiles; s.X = X32; s.W = W032;
         s.Y = static_cast<float*>(out); s.accumulate = 1; s.label = "self_loop_fwd";
         RGNN_TRY(typed_linear_fwd(desc->d_in, D, s, st));
     }
@@ -318,36 +340,46 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, K = desc->d_in;
     RgcnBwdWs w;
-    const bool bf16 = desc->dtype == RGNN_BF16;
+    const bool bf16 = desc->dtype == RGNN_BF16, h = rows_bf16(desc), relu = desc->activation == RGNN_ACT_RELU;
     const void* W16 = bf16 ? W : nullptr;
-    const void* X16 = bf16 ? X : nullptr;
     Bf16Stage stg(workspace, carve_rgcn_bwd(g, desc, workspace, &w), bf16, st);
-    X = stg.in(X, (size_t)g->N * K);
-    W = stg.in(W, (size_t)g->R * K * D);
-    if (W0) W0 = stg.in(W0, (size_t)K * D); else stg.reserve((size_t)K * D);
-    dOut = stg.in(dOut, (size_t)g->N * D);
+    const float* X32 = (!h || W0) ? stg.in(X, (size_t)g->N * K) : nullptr;
+    const float* W32 = !h ? stg.in(W, (size_t)g->R * K * D) : nullptr;
+    const float* W032 = stg.in(W0, (size_t)K * D);
+    const float* dO32 = (!h || W0) ? stg.in(dOut, (size_t)g->N * D) : nullptr;
     RGNN_TRY(stg.status);
-    const float* dPre = static_cast<const float*>(dOut);
-    if (desc->activation == RGNN_ACT_RELU) {
-        RGNN_TRY(relu_grad((size_t)g->N * D, static_cast<const float*>(out), dPre, w.dPre, st));
+    // gradient before the activation, in the storage the traversal reads (dPre) and, where an fp32
+    // kernel needs it, in fp32 (dPre32)
+    const void* dPre = h ? dOut : dO32;
+    const float* dPre32 = dO32;
+    if (relu) {
+        RGNN_TRY(relu_grad((size_t)g->N * D, static_cast<const float*>(out), dPre, w.dPre, st, h));
         dPre = w.dPre;
+        if (h && W0) {
+            RGNN_TRY(relu_grad((size_t)g->N * D, static_cast<const float*>(out), dO32, w.dPre32, st, 0));
+            dPre32 = w.dPre32;
+        } else if (!h) {
+            dPre32 = static_cast<const float*>(w.dPre);
+        }
     }
     // 1. dHs[p] = sum_{e in out(p)} (1/c_e) dPre[dst_e]
     const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
-    RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, coef, 1, 0, dPre, w.G,
-                        w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine"));
+    //    (coefficients from the pair-major copy, so no per-edge indirection is left)
+    const float* ocoef = coef ? g->out_invc : nullptr;
+    RGNN_TRY(gather_sum(g->pair_items, D, nullptr, g->idx[RGNN_IDX_OUT_DST], 0, ocoef, 1, 0, dPre, w.G,
+                        w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", 1, h, h));
     // 2. per pair dXp = dHs W^T; dW[r] = sum X^T dHs
-    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, static_cast<const float*>(X), X16, g->idx[RGNN_IDX_PAIR_SRC], 0,
-                    static_cast<const float*>(W), W16, w.G, w.dXp, static_cast<float*>(dW), w.tl_part, "typed_linear_bwd", st));
+    RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, h ? X : static_cast<const void*>(X32), g->idx[RGNN_IDX_PAIR_SRC], 0, W32, W16, w.G,
+                    w.dXp, h, static_cast<float*>(dW), w.tl_part, "typed_linear_bwd", st));
     // 3. self-loop: dX0 = dPre W0^T, dW0 = X^T dPre
     if (W0) {
         TypedLinearBwdArgs s{};
-        s.tiles = &g->all_tiles; s.X = static_cast<const float*>(X); s.W = static_cast<const float*>(W0); s.dY = dPre;
+        s.tiles = &g->all_tiles; s.X = X32; s.W = W032; s.dY = dPre32;
         s.dXrow = w.dX0; s.dW = static_cast<float*>(dW0); s.part = w.tl_part; s.label = "self_loop_bwd";
         RGNN_TRY(typed_linear_bwd(K, D, s, st));
     }
     // 4. dX[u] = sum over u's pairs of dXp (+ dX0[u])
-    RGNN_TRY(node_grad_sum(g, K, w.dXp, nullptr, nullptr, W0 ? w.dX0 : nullptr, static_cast<float*>(dX), st));
+    RGNN_TRY(node_grad_sum(g, K, w.dXp, nullptr, nullptr, W0 ? w.dX0 : nullptr, dX, st, h, 0));
     return RGNN_OK;
 }
 
@@ -449,42 +481,45 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, H = desc->heads;
     HgtFwdWs w; HgtSaved sv;
-    const bool bf16 = desc->dtype == RGNN_BF16;
+    const bool bf16 = desc->dtype == RGNN_BF16, h = rows_bf16(desc);
     const void *X16 = bf16 ? X : nullptr, *Wk16 = bf16 ? Wk : nullptr, *Wq16 = bf16 ? Wq : nullptr,
                *Wv16 = bf16 ? Wv : nullptr, *Wo16 = bf16 ? Wo : nullptr;
     Bf16Stage stg(workspace, carve_hgt_fwd(g, desc, workspace, &w), bf16, st);
-    {
-        const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
-        X = stg.in(X, (size_t)g->N * D);
-        Wk = stg.in(Wk, tdd); Wq = stg.in(Wq, tdd); Wv = stg.in(Wv, tdd); Wo = stg.in(Wo, tdd);
-        Watt = stg.in(Watt, rh * dh * dh); Wmsg = stg.in(Wmsg, rh * dh * dh);
-        if (mu) mu = stg.in(mu, rh); else stg.reserve(rh);
-        RGNN_TRY(stg.status);
-    }
+    const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
+    // fp32 copies: at width 128 only of the small per-relation parameters (their expansion is an fp32 kernel)
+    const float* X32 = !h ? stg.in(X, (size_t)g->N * D) : nullptr;
+    const float* Wk32 = !h ? stg.in(Wk, tdd) : nullptr;
+    const float* Wq32 = !h ? stg.in(Wq, tdd) : nullptr;
+    const float* Wv32 = !h ? stg.in(Wv, tdd) : nullptr;
+    const float* Wo32 = !h ? stg.in(Wo, tdd) : nullptr;
+    const float* Watt32 = stg.in(Watt, rh * dh * dh);
+    const float* Wmsg32 = stg.in(Wmsg, rh * dh * dh);
+    const float* mu32 = stg.in(mu, rh);
+    RGNN_TRY(stg.status);
     carve_hgt_saved(g, desc, saved, &sv);
-    const float* Xf = static_cast<const float*>(X);
     const int32_t* perm = g->idx[RGNN_IDX_NTYPE_PERM];
     const int32_t* psrc = g->idx[RGNN_IDX_PAIR_SRC];
-    auto F = [](const void* p) { return static_cast<const float*>(p); };
+    // bf16 form of an intermediate row tensor (nullptr when the rows are fp32) and its fp32 form
+    auto R16 = [h](const void* p) { return h ? p : nullptr; };
+    auto R32 = [h](const void* p) { return h ? nullptr : static_cast<const float*>(p); };
     // 1. per node type: K, Q, V
-    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wk), Wk16, sv.K, "node_linear_k", st));
-    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wq), Wq16, sv.Q, "node_linear_q", st));
-    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wv), Wv16, sv.V, "node_linear_v", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, X32, X16, perm, 1, Wk32, Wk16, sv.K, h, "node_linear_k", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, X32, X16, perm, 1, Wq32, Wq16, sv.Q, h, "node_linear_q", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, X32, X16, perm, 1, Wv32, Wv16, sv.V, h, "node_linear_v", st));
     // 2. per (relation, head) matrices as block-diagonal d x d weights; mu / sqrt(dh) folded into the attention one
-    RGNN_TRY(hgt_expand(g->R, D, H, F(Watt), F(mu), 1, w.Wbd_att, st));
-    RGNN_TRY(hgt_expand(g->R, D, H, F(Wmsg), nullptr, 0, w.Wbd_msg, st));
+    RGNN_TRY(hgt_expand(g->R, D, H, Watt32, mu32, 1, w.Wbd_att, st));
+    RGNN_TRY(hgt_expand(g->R, D, H, Wmsg32, nullptr, 0, w.Wbd_msg, st));
     // 3. compact per pair: Ka[p] = K[src_p] Watt[r], M[p] = V[src_p] Wmsg[r]
-    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, sv.K, nullptr, psrc, 0, w.Wbd_att, nullptr, sv.Ka, "pair_linear_att", st));
-    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, sv.V, nullptr, psrc, 0, w.Wbd_msg, nullptr, sv.M, "pair_linear_msg", st));
+    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, R32(sv.K), R16(sv.K), psrc, 0, w.Wbd_att, nullptr, sv.Ka, h, "pair_linear_att", st));
+    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, R32(sv.V), R16(sv.V), psrc, 0, w.Wbd_msg, nullptr, sv.M, h, "pair_linear_msg", st));
     // 4. per edge and head: logit, softmax over the destination's edges
-    RGNN_TRY(hgt_edge_logit(g, D, H, sv.Ka, sv.Q, sv.att, st));
+    RGNN_TRY(hgt_edge_logit(g, D, H, sv.Ka, sv.Q, sv.att, st, h));
     RGNN_TRY(hgt_softmax(g, H, sv.att, w.part_m, w.part_s, st));
     // 5. Z[v][h] = sum_e att[e][h] M[pair_e][h]
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, H, 0, sv.M, sv.Z, w.partial, st, 0,
-                        "aggregate_fwd", "aggregate_fwd.combine", H));
+                        "aggregate_fwd", "aggregate_fwd.combine", H, h, h));
     // 6. out = Z Wo[type]
-    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, sv.Z, nullptr, perm, 1, F(Wo), Wo16, static_cast<float*>(out),
-                    "node_linear_out", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, R32(sv.Z), R16(sv.Z), perm, 1, Wo32, Wo16, out, false, "node_linear_out", st));
     return RGNN_OK;
 }
 
@@ -502,59 +537,60 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, H = desc->heads;
     HgtBwdWs w; HgtSaved sv;
-    const bool bf16 = desc->dtype == RGNN_BF16;
+    const bool bf16 = desc->dtype == RGNN_BF16, h = rows_bf16(desc);
     const void *Wk16 = bf16 ? Wk : nullptr, *Wq16 = bf16 ? Wq : nullptr, *Wv16 = bf16 ? Wv : nullptr,
-               *Wo16 = bf16 ? Wo : nullptr, *X16 = bf16 ? X : nullptr;
+               *Wo16 = bf16 ? Wo : nullptr;
     Bf16Stage stg(workspace, carve_hgt_bwd(g, desc, workspace, &w), bf16, st);
-    {
-        const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
-        X = stg.in(X, (size_t)g->N * D);
-        Wk = stg.in(Wk, tdd); Wq = stg.in(Wq, tdd); Wv = stg.in(Wv, tdd); Wo = stg.in(Wo, tdd);
-        Watt = stg.in(Watt, rh * dh * dh); Wmsg = stg.in(Wmsg, rh * dh * dh);
-        if (mu) mu = stg.in(mu, rh); else stg.reserve(rh);
-        dOut = stg.in(dOut, (size_t)g->N * D);
-        RGNN_TRY(stg.status);
-    }
+    const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
+    const float* X32 = !h ? stg.in(X, (size_t)g->N * D) : nullptr;
+    const float* Wk32 = !h ? stg.in(Wk, tdd) : nullptr;
+    const float* Wq32 = !h ? stg.in(Wq, tdd) : nullptr;
+    const float* Wv32 = !h ? stg.in(Wv, tdd) : nullptr;
+    const float* Wo32 = !h ? stg.in(Wo, tdd) : nullptr;
+    const float* Watt32 = stg.in(Watt, rh * dh * dh);
+    const float* Wmsg32 = stg.in(Wmsg, rh * dh * dh);
+    const float* mu32 = stg.in(mu, rh);
+    const float* dO32 = !h ? stg.in(dOut, (size_t)g->N * D) : nullptr;
+    RGNN_TRY(stg.status);
     carve_hgt_saved(g, desc, const_cast<void*>(saved), &sv);
-    const float* Xf = static_cast<const float*>(X);
-    const float* dO = static_cast<const float*>(dOut);
+    // row operands in the storage of this mode: the caller's bf16 tensors as they are, or the fp32 copies
+    const void* Xr = h ? X : static_cast<const void*>(X32);
+    const void* dOr = h ? dOut : static_cast<const void*>(dO32);
     const int32_t* perm = g->idx[RGNN_IDX_NTYPE_PERM];
     const int32_t* psrc = g->idx[RGNN_IDX_PAIR_SRC];
-    auto F = [](const void* p) { return static_cast<const float*>(p); };
     // 1. output linear: dZ = dOut Wo^T, dWo = Z^T dOut
-    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, sv.Z, nullptr, perm, 1, F(Wo), Wo16, dO, w.dZ, static_cast<float*>(dWo), w.tl_part,
+    RGNN_TRY(tl_bwd(h, &g->node_tiles, &g->node_tiles_wide, D, sv.Z, perm, 1, Wo32, Wo16, dOr, w.dZ, h, static_cast<float*>(dWo), w.tl_part,
                     "node_linear_out_bwd", st));
     // 2. per edge and head: d logit
-    RGNN_TRY(hgt_edge_dot_bwd(g, D, H, sv.att, sv.M, w.dZ, sv.Z, w.dl, st));
+    RGNN_TRY(hgt_edge_dot_bwd(g, D, H, sv.att, sv.M, w.dZ, sv.Z, w.dl, st, h));
     // 3. pair-major: dM[p][h] = sum att dZ[dst][h];  dKa[p][h] = sum dl Q[dst][h]
     RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, sv.att, H, 0, w.dZ, w.dM,
-                        w.partial, st, 1, "aggregate_bwd_msg", "aggregate_bwd_msg.combine", H));
+                        w.partial, st, 1, "aggregate_bwd_msg", "aggregate_bwd_msg.combine", H, h, h));
     RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.dl, H, 0, sv.Q, w.dKa,
-                        w.partial, st, 1, "aggregate_bwd_key", "aggregate_bwd_key.combine", H));
+                        w.partial, st, 1, "aggregate_bwd_key", "aggregate_bwd_key.combine", H, h, h));
     // 4. destination-major: dQ[v][h] = sum dl Ka[pair][h]
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, w.dl, H, 0, sv.Ka, w.dQ, w.partial, st, 0,
-                        "aggregate_bwd_query", "aggregate_bwd_query.combine", H));
+                        "aggregate_bwd_query", "aggregate_bwd_query.combine", H, h, h));
     // 5. per-pair linears backward
-    RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Watt), static_cast<const float*>(mu), 1, w.Wbd_att, st));
-    RGNN_TRY(hgt_expand(g->R, D, H, static_cast<const float*>(Wmsg), nullptr, 0, w.Wbd_msg, st));
-    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, sv.K, nullptr, psrc, 0, w.Wbd_att, nullptr, w.dKa, w.dKp, w.dWbd_att, w.tl_part,
+    RGNN_TRY(hgt_expand(g->R, D, H, Watt32, mu32, 1, w.Wbd_att, st));
+    RGNN_TRY(hgt_expand(g->R, D, H, Wmsg32, nullptr, 0, w.Wbd_msg, st));
+    RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, sv.K, psrc, 0, w.Wbd_att, nullptr, w.dKa, w.dKp, h, w.dWbd_att, w.tl_part,
                     "pair_linear_att_bwd", st));
-    RGNN_TRY(tl_bwd(bf16, &g->pair_tiles, D, sv.V, nullptr, psrc, 0, w.Wbd_msg, nullptr, w.dM, w.dVp, w.dWbd_msg, w.tl_part,
+    RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, sv.V, psrc, 0, w.Wbd_msg, nullptr, w.dM, w.dVp, h, w.dWbd_msg, w.tl_part,
                     "pair_linear_msg_bwd", st));
-    RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_att, static_cast<const float*>(Watt), static_cast<const float*>(mu), 1,
-                         static_cast<float*>(dWatt), static_cast<float*>(dmu), st));
-    RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_msg, static_cast<const float*>(Wmsg), nullptr, 0, static_cast<float*>(dWmsg),
-                         nullptr, st));
+    RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_att, Watt32, mu32, 1, static_cast<float*>(dWatt), static_cast<float*>(dmu), st));
+    RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_msg, Wmsg32, nullptr, 0, static_cast<float*>(dWmsg), nullptr, st));
     // 6. dK[u], dV[u] = sums over u's pairs
-    RGNN_TRY(node_grad_sum(g, D, w.dKp, nullptr, nullptr, nullptr, w.dK, st));
-    RGNN_TRY(node_grad_sum(g, D, w.dVp, nullptr, nullptr, nullptr, w.dV, st));
+    RGNN_TRY(node_grad_sum(g, D, w.dKp, nullptr, nullptr, nullptr, w.dK, st, h, h));
+    RGNN_TRY(node_grad_sum(g, D, w.dVp, nullptr, nullptr, nullptr, w.dV, st, h, h));
     // 7. node linears backward and dX
-    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wk), Wk16, w.dK, w.dXk, static_cast<float*>(dWk), w.tl_part,
-                    "node_linear_k_bwd", st));
-    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wq), Wq16, w.dQ, w.dXq, static_cast<float*>(dWq), w.tl_part,
-                    "node_linear_q_bwd", st));
-    RGNN_TRY(tl_bwd(bf16, &g->node_tiles, D, Xf, X16, perm, 1, F(Wv), Wv16, w.dV, w.dXv, static_cast<float*>(dWv), w.tl_part,
-                    "node_linear_v_bwd", st));
-    RGNN_TRY(add3((size_t)g->N * D, w.dXk, w.dXq, w.dXv, static_cast<float*>(dX), st));
+    //    (bf16 rows: the three input gradients are accumulated into dX by the kernels themselves)
+    RGNN_TRY(tl_bwd(h, &g->node_tiles, &g->node_tiles_wide, D, Xr, perm, 1, Wk32, Wk16, w.dK, h ? dX : static_cast<void*>(w.dXk),
+                    false, static_cast<float*>(dWk), w.tl_part, "node_linear_k_bwd", st));
+    RGNN_TRY(tl_bwd(h, &g->node_tiles, &g->node_tiles_wide, D, Xr, perm, 1, Wq32, Wq16, w.dQ, h ? dX : static_cast<void*>(w.dXq),
+                    false, static_cast<float*>(dWq), w.tl_part, "node_linear_q_bwd", st, h));
+    RGNN_TRY(tl_bwd(h, &g->node_tiles, &g->node_tiles_wide, D, Xr, perm, 1, Wv32, Wv16, w.dV, h ? dX : static_cast<void*>(w.dXv),
+                    false, static_cast<float*>(dWv), w.tl_part, "node_linear_v_bwd", st, h));
+    if (!h) RGNN_TRY(add3((size_t)g->N * D, w.dXk, w.dXq, w.dXv, static_cast<float*>(dX), st));
     return RGNN_OK;
 }

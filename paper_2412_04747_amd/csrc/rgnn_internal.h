@@ -79,6 +79,8 @@ struct ItemList {
     int32_t num_long = 0;
     int32_t* long_item = nullptr;  // [num_long] items with more than kSerialMax entries, and every piece of a cut segment
     int32_t* part_split = nullptr; // [num_partials] index into split_* of its segment
+    int32_t first_single = 0;      // items [first_single, first_single + num_single) are the whole segments
+    int32_t num_single = 0;        // with exactly one entry
 };
 
 }  // namespace rgnn
@@ -99,9 +101,12 @@ struct rgnn_graph {
     int32_t* idx[RGNN_IDX_COUNT] = {};     // device arrays, see RGNN_IDX_*
     int64_t idx_len[RGNN_IDX_COUNT] = {};
     float* in_invc = nullptr;              // [E] 1 / c_{v,r} per CSR edge
+    float* out_invc = nullptr;             // [E] the same per pair-major edge: in_invc[out_epos[j]]
     rgnn::TileList pair_tiles;             // pairs segmented by relation
     rgnn::TileList node_tiles;             // nodes (in ntype_perm order) segmented by type
     rgnn::TileList all_tiles;              // all nodes as one segment (RGCN self-loop)
+    rgnn::TileList pair_tiles_wide;        // same tiles as pair_tiles / node_tiles in fewer, longer chunks: for the
+    rgnn::TileList node_tiles_wide;        // weight-gradient kernels, whose chunks each flush a d x d partial
     rgnn::ItemList dst_items;              // CSR edges by destination
     rgnn::ItemList pair_items;             // transposed edges by pair
     rgnn::ItemList pair_items_multi;       // the same, pairs with two or more edges only
@@ -118,6 +123,9 @@ namespace rgnn {
 constexpr int kTileRows = 64;       // rows per typed-linear tile
 constexpr int kMaxChunks = 4096;    // tile chunks (workgroups) of the typed-linear kernels: several per resident
                                     // workgroup slot, so the hardware dispatcher evens out the tail
+constexpr int kWideChunks = 1024;   // chunk limit of the weight-gradient lists
+constexpr int kMinChunks = 512;     // fewer chunks than this only when there are fewer tiles
+constexpr int kChunkTiles = 8;      // tiles a chunk spans before the chunk count grows beyond kMinChunks
 constexpr int kItemMax = 256;       // longest traversal item (entries)
 constexpr int kItemTarget = 65536;  // lists are cut finer while they yield fewer items than this
 constexpr int kSerialMax = 32;      // longest segment a single lane walks; longer ones get a wavefront
@@ -165,7 +173,9 @@ struct TypedLinearBf16Args {
     const void* W;           // [segs][d][d]: bf16 (w_bf16) or fp32
     int w_bf16;
     int transpose_w;         // 1: multiply by W[seg]^T
-    float* Y;                // fp32 output rows
+    void* Y;                 // output rows: bf16 (y_bf16) or fp32
+    int y_bf16;
+    int accumulate;          // 1: Y += result (fp32 Y)
     const char* label;
 };
 rgnn_status_t typed_linear_bf16(int d, const TypedLinearBf16Args& a, hipStream_t st);
@@ -174,11 +184,10 @@ rgnn_status_t typed_linear_bf16(int d, const TypedLinearBf16Args& a, hipStream_t
 // typed_linear_slot_reduce then adds a segment's slots into dW.
 struct TypedLinearWgradBf16Args {
     const TileList* tiles;
-    const void* X;           // rows: bf16 (x_bf16) or fp32
-    int x_bf16;
+    const void* X;           // bf16 rows
     const int32_t* gather;
     int dy_gathered;         // 1: dY rows are read through the gather list as well
-    const float* dY;
+    const void* dY;          // bf16 rows
     float* part;
     const char* label;
 };

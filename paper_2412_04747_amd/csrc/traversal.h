@@ -11,27 +11,28 @@ rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng,
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
                            float* part_m, float* part_s, hipStream_t st);
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
-                         const float* coef, int cstride, int cabs, const float* src, float* out, float* partial,
-                         hipStream_t st, int role, const char* label, const char* combine_label, int heads = 1);
+                         const float* coef, int cstride, int cabs, const void* src, void* out, float* partial,
+                         hipStream_t st, int role, const char* label, const char* combine_label, int heads = 1,
+                         int src_bf16 = 0, int out_bf16 = 0);
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
                            const float* out, float slope, float* adz, float* G, float* ds_src, hipStream_t st);
-rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const float* dXp, const float* ds_dst, const float* wtp,
-                            const float* extra, float* dX, hipStream_t st);
+rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const float* ds_dst, const float* wtp,
+                            const float* extra, void* dX, hipStream_t st, int in_bf16 = 0, int out_bf16 = 0);
 rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const float* w_s, const float* w_t,
                                 const float* A, const float* U, float* dW, float* dw_s, float* dw_t, hipStream_t st);
 // hgt.hip
 rgnn_status_t hgt_expand(int R, int d, int H, const float* W, const float* mu, int scaled, float* Wbd, hipStream_t st);
 rgnn_status_t hgt_extract(int R, int d, int H, const float* dWbd, const float* W, const float* mu, int scaled, float* dW,
                           float* dmu, hipStream_t st);
-rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const float* Ka, const float* Q, float* logit,
-                             hipStream_t st);
+rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const void* Ka, const void* Q, float* logit,
+                             hipStream_t st, int rows_bf16 = 0);
 rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st);
-rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* att, const float* M, const float* dZ,
-                               const float* Z, float* dl, hipStream_t st);
+rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* att, const void* M, const void* dZ,
+                               const void* Z, float* dl, hipStream_t st, int rows_bf16 = 0);
 rgnn_status_t add3(size_t n, const float* a, const float* b, const float* c, float* out, hipStream_t st);
 
 rgnn_status_t widen_bf16(size_t n, const uint16_t* src, float* dst, hipStream_t st);
 rgnn_status_t relu_inplace(size_t n, float* x, hipStream_t st);
-rgnn_status_t relu_grad(size_t n, const float* ref, const float* gin, float* y, hipStream_t st);
+rgnn_status_t relu_grad(size_t n, const float* ref, const void* gin, void* y, hipStream_t st, int bf16 = 0);
 
 }  // namespace rgnn

@@ -189,22 +189,30 @@ struct GatherArgs {
     const float* coef;
     int cstride;
     int cabs;
-    int lanes_per_head;   // D/4 / heads
-    const float* src;
-    float* out;
-    float* partial;
+    int lanes_per_head;   // lanes per row / heads
+    const void* src;      // rows of TI
+    void* out;            // rows of TO
+    float* partial;       // fp32 rows
+    int skip_first;       // items [skip_first, skip_first + skip_n) are left to gather_single_kernel
+    int skip_n;
 };
 
 // ROLE only gives each use its own kernel name in profiler output (0 forward aggregation over
 // destinations, 1 backward aggregation over pairs, 2 destination-side weight gradient).
-template <int D, int ROLE>
+// TI / TO: storage type of the gathered rows and of the output rows (float or bf16_t).
+template <int D, int ROLE, typename TI, typename TO>
 __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
-    constexpr int LPR = D / 4, IPB = 256 / LPR;
-    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
-    if (i >= a.it.n) return;
+    constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
+    int i = blockIdx.x * IPB + threadIdx.x / LPR;
+    const int cv = threadIdx.x % LPR;
+    if (i >= a.it.n - a.skip_n) return;
+    if (i >= a.skip_first) i += a.skip_n;      // the single-entry segments have their own kernel
+    const TI* __restrict__ src = static_cast<const TI*>(a.src);
     const int b = a.it.beg[i], e = a.it.end[i];
-    const int head = c4 / a.lanes_per_head;
-    float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
+    const int head = cv / a.lanes_per_head;
+    float acc0[V], acc1[V];
+    zero_cols(acc0);
+    zero_cols(acc1);
     for (int j = b; j < e; j += 4) {
         int row[4];
         float c[4];
@@ -219,30 +227,71 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
                 if (a.cabs) c[u] = fabsf(c[u]);
             }
         }
-        float4 v[4];
+        float v[4][V];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-            v[u] = row[u] >= 0 ? *reinterpret_cast<const float4*>(a.src + (size_t)row[u] * D + c4 * 4)
-                               : make_float4(0.f, 0.f, 0.f, 0.f);
-        fma4(acc0, c[0], v[0]);
-        fma4(acc1, c[1], v[1]);
-        fma4(acc0, c[2], v[2]);
-        fma4(acc1, c[3], v[3]);
+        for (int u = 0; u < 4; ++u) {
+            if (row[u] >= 0) load_cols(src + (size_t)row[u] * D + cv * V, v[u]);
+            else zero_cols(v[u]);
+        }
+        fma_cols(acc0, c[0], v[0]);
+        fma_cols(acc1, c[1], v[1]);
+        fma_cols(acc0, c[2], v[2]);
+        fma_cols(acc1, c[3], v[3]);
     }
-    acc0.x += acc1.x; acc0.y += acc1.y; acc0.z += acc1.z; acc0.w += acc1.w;
+    fma_cols(acc0, 1.f, acc1);
     const int slot = a.it.slot[i];
-    float* o = slot < 0 ? a.out + (size_t)a.it.row[i] * D : a.partial + (size_t)slot * D;
-    *reinterpret_cast<float4*>(o + c4 * 4) = acc0;
+    if (slot < 0) store_cols(static_cast<TO*>(a.out) + (size_t)a.it.row[i] * D + cv * V, acc0);
+    else store_cols(a.partial + (size_t)slot * D + cv * V, acc0);
+}
+
+// The whole segments with exactly one entry, items [first, first + n): out[row_i] = c * src[row].
+// A group of lanes handles four of them at a time, all loads of the four independent, which keeps
+// enough rows in flight where the general kernel would wait on one short dependent chain per item.
+template <int D, int ROLE, typename TI, typename TO>
+__global__ __launch_bounds__(256) void gather_single_kernel(GatherArgs a, int first, int n) {
+    constexpr int V = RowT<TI>::V, LPR = D / V, GPB = 256 / LPR;
+    const int g = blockIdx.x * GPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
+    const int i0 = 4 * g;
+    if (i0 >= n) return;
+    const TI* __restrict__ src = static_cast<const TI*>(a.src);
+    const int head = cv / a.lanes_per_head;
+    int j[4], orow[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = first + min(i0 + u, n - 1);
+        j[u] = a.it.beg[i];
+        orow[u] = a.it.row[i];
+    }
+    int row[4];
+    float c[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int k = a.via ? a.via[j[u]] : j[u];
+        row[u] = a.row_by_k ? a.rowidx[k] : a.rowidx[j[u]];
+        c[u] = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;
+        if (a.cabs) c[u] = fabsf(c[u]);
+    }
+    float v[4][V];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) load_cols(src + (size_t)row[u] * D + cv * V, v[u]);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        if (i0 + u < n) {
+#pragma unroll
+            for (int q = 0; q < V; ++q) v[u][q] *= c[u];
+            store_cols(static_cast<TO*>(a.out) + (size_t)orow[u] * D + cv * V, v[u]);
+        }
+    }
 }
 
 // out[split_row[s]] = sum of partial rows [split_ptr[s], split_ptr[s+1]).  One workgroup per
 // cut segment: group g of D/4 lanes sums partial rows g, g + G, g + 2G, ... (two at a time),
 // then the G group sums are added in group order through LDS, so the summation order is fixed.
-template <int D>
+template <int D, typename TO>
 __global__ __launch_bounds__(1024) void combine_partials_kernel(const int32_t* __restrict__ split_row,
                                                                 const int32_t* __restrict__ split_ptr,
                                                                 const float* __restrict__ partial,
-                                                                float* __restrict__ out) {
+                                                                TO* __restrict__ out) {
     constexpr int LPR = D / 4, G = 1024 / LPR;
     __shared__ float4 red[1024];
     const int s = blockIdx.x, g = threadIdx.x / LPR, c4 = threadIdx.x % LPR;
@@ -258,7 +307,8 @@ __global__ __launch_bounds__(1024) void combine_partials_kernel(const int32_t* _
     if (g == 0) {
         float4 t = red[c4];
         for (int k = 1; k < G; ++k) fma4(t, 1.f, red[k * LPR + c4]);
-        *reinterpret_cast<float4*>(out + (size_t)split_row[s] * D + c4 * 4) = t;
+        const float tv[4] = {t.x, t.y, t.z, t.w};
+        store_cols(out + (size_t)split_row[s] * D + c4 * 4, tv);
     }
 }
 
@@ -335,58 +385,61 @@ struct NodeSumArgs {
     Items it;             // pairs by source node, ordered by length, never cut
     const int32_t* srcpair_ptr;
     const int32_t* srcpair_idx;
-    const float* dXp;
+    const void* dXp;      // rows of TI
     const int32_t* dst_run_ptr;
     const int32_t* run_rel;
     const float* ds_dst;
     const float* wtp;
     const float* extra;
-    float* dX;
+    void* dX;             // rows of TO
 };
 
-template <int D>
+template <int D, typename TI, typename TO>
 __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
-    constexpr int LPR = D / 4, IPB = 256 / LPR;
-    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+    constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
+    const int i = blockIdx.x * IPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
     if (i >= a.it.n) return;
+    const TI* __restrict__ dXp = static_cast<const TI*>(a.dXp);
     const int u = a.it.row[i];
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (a.extra) acc = *reinterpret_cast<const float4*>(a.extra + (size_t)u * D + c4 * 4);
+    float acc[V], acc1[V];
+    zero_cols(acc);
+    zero_cols(acc1);
+    if (a.extra) load_cols(a.extra + (size_t)u * D + cv * V, acc);
     const int b = a.it.beg[i], e = a.it.end[i];
-    float4 acc1 = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int j = b; j < e; j += 4) {
-        float4 v[4];
+        float v[4][V];
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-            v[t] = j + t < e ? *reinterpret_cast<const float4*>(a.dXp + (size_t)a.srcpair_idx[j + t] * D + c4 * 4)
-                             : make_float4(0.f, 0.f, 0.f, 0.f);
-        fma4(acc, 1.f, v[0]);
-        fma4(acc1, 1.f, v[1]);
-        fma4(acc, 1.f, v[2]);
-        fma4(acc1, 1.f, v[3]);
+        for (int t = 0; t < 4; ++t) {
+            if (j + t < e) load_cols(dXp + (size_t)a.srcpair_idx[j + t] * D + cv * V, v[t]);
+            else zero_cols(v[t]);
+        }
+        fma_cols(acc, 1.f, v[0]);
+        fma_cols(acc1, 1.f, v[1]);
+        fma_cols(acc, 1.f, v[2]);
+        fma_cols(acc1, 1.f, v[3]);
     }
     if (a.ds_dst) {
         const int qb = a.dst_run_ptr[u], qe = a.dst_run_ptr[u + 1];
         for (int q = qb; q < qe; q += 4) {
             float c[4];
-            float4 v[4];
+            float v[4][V];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 c[t] = 0.f;
-                v[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+                zero_cols(v[t]);
                 if (q + t < qe) {
                     c[t] = a.ds_dst[q + t];
-                    v[t] = *reinterpret_cast<const float4*>(a.wtp + (size_t)a.run_rel[q + t] * D + c4 * 4);
+                    load_cols(a.wtp + (size_t)a.run_rel[q + t] * D + cv * V, v[t]);
                 }
             }
-            fma4(acc, c[0], v[0]);
-            fma4(acc1, c[1], v[1]);
-            fma4(acc, c[2], v[2]);
-            fma4(acc1, c[3], v[3]);
+            fma_cols(acc, c[0], v[0]);
+            fma_cols(acc1, c[1], v[1]);
+            fma_cols(acc, c[2], v[2]);
+            fma_cols(acc1, c[3], v[3]);
         }
     }
-    fma4(acc, 1.f, acc1);
-    *reinterpret_cast<float4*>(a.dX + (size_t)u * D + c4 * 4) = acc;
+    fma_cols(acc, 1.f, acc1);
+    store_cols(static_cast<TO*>(a.dX) + (size_t)u * D + cv * V, acc);
 }
 
 // ------------------------------------------------------------------ RGAT parameter-gradient epilogue
@@ -426,6 +479,13 @@ __global__ void relu_grad_kernel(size_t n, const float* __restrict__ ref, const 
                                  float* __restrict__ y) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) y[i] = ref[i] > 0.f ? g[i] : 0.f;
+}
+
+// same on bf16 storage (gradient in, masked gradient out); `ref` is the fp32 layer output
+__global__ void relu_grad_bf16_kernel(size_t n, const float* __restrict__ ref, const bf16_t* __restrict__ g,
+                                      bf16_t* __restrict__ y) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) y[i] = ref[i] > 0.f ? g[i] : (bf16_t)0;
 }
 
 // bfloat16 -> fp32 (exact: the bf16 bits are the upper half of the fp32 word)
@@ -494,23 +554,54 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
     return RGNN_OK;
 }
 
+// Launches KERNEL<DD, ..., TI, TO> for the storage types of a call.  bf16 rows exist at width 128 only.
+#define RGNN_DISPATCH_ROWS(D_, IN16, OUT16, ...)                                                         \
+    do {                                                                                                 \
+        if (!(IN16) && !(OUT16)) { using TI = float; using TO = float; RGNN_DISPATCH_D(D_, __VA_ARGS__); }      \
+        else if ((D_) != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "bf16 rows need width 128, got %d", (int)(D_)); \
+        else if ((IN16) && (OUT16)) { using TI = bf16_t; using TO = bf16_t; constexpr int DD = 128; __VA_ARGS__; } \
+        else if (IN16) { using TI = bf16_t; using TO = float; constexpr int DD = 128; __VA_ARGS__; }            \
+        else { using TI = float; using TO = bf16_t; constexpr int DD = 128; __VA_ARGS__; }                      \
+    } while (0)
+
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
-                         const float* coef, int cstride, int cabs, const float* src, float* out, float* partial,
-                         hipStream_t st, int role, const char* label, const char* combine_label, int heads) {
+                         const float* coef, int cstride, int cabs, const void* src, void* out, float* partial,
+                         hipStream_t st, int role, const char* label, const char* combine_label, int heads,
+                         int src_bf16, int out_bf16) {
     if (L.num_items == 0) return RGNN_OK;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, (D / 4) / heads, src, out, partial};
+    const int lpr = D / (src_bf16 ? 8 : 4);
+    // enough single-entry segments to be worth a launch of their own
+    const int ns = L.num_single >= 4096 ? L.num_single : 0;
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, L.first_single, ns};
     {
         KernelTimer kt(st, label);
-        const dim3 grid(blocks_for(L.num_items, 256 / (D / 4)));
-        if (role == 0) RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 0>), grid, dim3(256), 0, st, a));
-        else if (role == 1) RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 1>), grid, dim3(256), 0, st, a));
-        else RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 2>), grid, dim3(256), 0, st, a));
+        const dim3 grid(blocks_for(L.num_items - ns, 256 / lpr));
+        if (role == 0)
+            RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_sum_kernel<DD, 0, TI, TO>), grid, dim3(256), 0, st, a));
+        else if (role == 1)
+            RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_sum_kernel<DD, 1, TI, TO>), grid, dim3(256), 0, st, a));
+        else
+            RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_sum_kernel<DD, 2, TI, TO>), grid, dim3(256), 0, st, a));
         RGNN_CHECK_LAUNCH();
+        if (ns > 0) {
+            const dim3 sgrid(blocks_for((size_t)(ns + 3) / 4, 256 / lpr));
+            if (role == 0)
+                RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_single_kernel<DD, 0, TI, TO>), sgrid, dim3(256), 0, st, a, L.first_single, ns));
+            else if (role == 1)
+                RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_single_kernel<DD, 1, TI, TO>), sgrid, dim3(256), 0, st, a, L.first_single, ns));
+            else
+                RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_single_kernel<DD, 2, TI, TO>), sgrid, dim3(256), 0, st, a, L.first_single, ns));
+            RGNN_CHECK_LAUNCH();
+        }
     }
     if (L.num_split > 0) {
         KernelTimer kt(st, combine_label);
-        RGNN_DISPATCH_D(D, hipLaunchKernelGGL(combine_partials_kernel<DD>, dim3(L.num_split), dim3(1024), 0, st, L.split_row,
-                                         L.split_ptr, partial, out));
+        if (out_bf16)
+            RGNN_DISPATCH_D(D, hipLaunchKernelGGL((combine_partials_kernel<DD, bf16_t>), dim3(L.num_split), dim3(1024), 0, st,
+                                                  L.split_row, L.split_ptr, partial, static_cast<bf16_t*>(out)));
+        else
+            RGNN_DISPATCH_D(D, hipLaunchKernelGGL((combine_partials_kernel<DD, float>), dim3(L.num_split), dim3(1024), 0, st,
+                                                  L.split_row, L.split_ptr, partial, static_cast<float*>(out)));
         RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;
@@ -528,14 +619,14 @@ rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const f
     return RGNN_OK;
 }
 
-rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const float* dXp, const float* ds_dst, const float* wtp,
-                            const float* extra, float* dX, hipStream_t st) {
+rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const float* ds_dst, const float* wtp,
+                            const float* extra, void* dX, hipStream_t st, int in_bf16, int out_bf16) {
     if (g->N == 0) return RGNN_OK;
     NodeSumArgs a{dev_items(g->srcpair_items), g->idx[RGNN_IDX_SRCPAIR_PTR], g->idx[RGNN_IDX_SRCPAIR_IDX], dXp,
                   g->idx[RGNN_IDX_DST_RUN_PTR], g->idx[RGNN_IDX_RUN_REL], ds_dst, wtp, extra, dX};
     KernelTimer kt(st, "node_grad_sum");
-    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(node_grad_sum_kernel<DD>, dim3(blocks_for((size_t)g->N, 256 / (DD / 4))), dim3(256),
-                                     0, st, a));
+    const dim3 grid(blocks_for((size_t)g->N, 256 / (D / (in_bf16 ? 8 : 4))));
+    RGNN_DISPATCH_ROWS(D, in_bf16, out_bf16, hipLaunchKernelGGL((node_grad_sum_kernel<DD, TI, TO>), grid, dim3(256), 0, st, a));
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
@@ -562,10 +653,15 @@ rgnn_status_t relu_inplace(size_t n, float* x, hipStream_t st) {
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
-rgnn_status_t relu_grad(size_t n, const float* ref, const float* gin, float* y, hipStream_t st) {
+rgnn_status_t relu_grad(size_t n, const float* ref, const void* gin, void* y, hipStream_t st, int bf16) {
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, "relu_grad");
-    hipLaunchKernelGGL(relu_grad_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ref, gin, y);
+    if (bf16)
+        hipLaunchKernelGGL(relu_grad_bf16_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ref,
+                           static_cast<const bf16_t*>(gin), static_cast<bf16_t*>(y));
+    else
+        hipLaunchKernelGGL(relu_grad_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ref,
+                           static_cast<const float*>(gin), static_cast<float*>(y));
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

@@ -1,19 +1,19 @@
 // Typed linear layer on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation,
 // for the bfloat16-input workloads:   Y[i] = A[g(i)] W[seg(i)]   or   Y[i] = A[g(i)] W[seg(i)]^T.
 //
-// Operands that are bf16 at the boundary (X, the given weights) go to the MFMA as they are,
-// so their products are exact.  Operands that only exist in fp32 (intermediate rows such as
-// K, V, Z and incoming gradients; the block-diagonal attention weights with mu/sqrt(dh)
-// folded in) are split on the fly into two bf16 planes, x = hi + lo, and multiplied with two
-// MFMAs, which keeps about 16 mantissa bits: the results stay within ~1e-5 of the fp32 path
-// while the contraction runs at bf16 rate.  At these widths the kernel is bound by HBM
-// traffic, not by the matrix cores, so the extra MFMAs are free.
+// Operands stored as bf16 (X, the given weights, and at width 128 every intermediate row
+// tensor) go to the MFMA as they are, so their products are exact.  Operands that only exist
+// in fp32 (the block-diagonal attention weights with mu/sqrt(dh) folded in; at widths below 128
+// the intermediate rows) are split on the fly into two bf16 planes, x = hi + lo, and multiplied
+// with two MFMAs, which keeps about 16 mantissa bits.  At these widths the kernel is bound by
+// HBM traffic, not by the matrix cores, so the extra MFMAs are free.  The output rows are
+// written as fp32 or rounded to bf16 (nearest even).
 //
 // Same wave-independent structure as the fp32 kernels: a workgroup keeps the segment's weight
 // in LDS (as W_l[out column][contraction index], so a lane reads its B operand, eight
 // consecutive contraction indices of one output column, as one 16-byte vector); each
 // wavefront owns 32-row units, keeps the next unit's rows in flight in registers, and writes
-// its accumulators straight to HBM (two full 128-byte lines per store instruction).
+// its accumulators straight to HBM.
 #include "rgnn_internal.h"
 
 namespace rgnn {
@@ -37,6 +37,13 @@ __device__ __forceinline__ unsigned bf16_rne(float x) {
     unsigned u = __float_as_uint(x);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return u >> 16;
+}
+// two fp32 -> packed bf16 pair (lo in bits 0..15), round to nearest even, one v_cvt_pk_bf16_f32
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned bf16_pack_rne(float lo, float hi) {
+    const v2f v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
 }
 // x = hi + lo (+ ~2^-17 |x|): both as bf16 bits
 __device__ __forceinline__ void bf16_split(float x, unsigned& hi, unsigned& lo) {
@@ -62,10 +69,11 @@ __device__ __forceinline__ int run_end_b(const int32_t* __restrict__ tile_seg, i
 //   A_BF16 A rows are bf16 (exact) / fp32 (split)       W_BF16 weights are bf16 (exact) / fp32 (split)
 //   WT     false: Y = A W  (W stored [CD][OD])          true: Y = A W^T  (W stored [OD][CD])
 //   GATHER rows are read through the gather list        SCATTER outputs are written through it as well
-template <int CD, int OD, bool A_BF16, bool W_BF16, bool WT, bool GATHER, bool SCATTER>
+//   Y_BF16 output rows are stored as bf16 / fp32        ACC    (fp32 output only) Y += result
+template <int CD, int OD, bool A_BF16, bool W_BF16, bool WT, bool GATHER, bool SCATTER, bool Y_BF16, bool ACC>
 __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, const void* __restrict__ Av,
                                                                 const int32_t* __restrict__ gather,
-                                                                const void* __restrict__ Wv, float* __restrict__ Y) {
+                                                                const void* __restrict__ Wv, void* __restrict__ Yv) {
     constexpr int NW = 4;
     constexpr int LS = CD + 8;                                // LDS row stride in bf16 elements (16-byte aligned rows)
     constexpr int OB = OD / 32;
@@ -159,15 +167,55 @@ __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, con
                     }
                 }
             }
-            // accumulators straight to HBM: lanes 0..31 and 32..63 each write one 128-byte line
             const int rows_left = rbnd - (ra + u * 32);
+            if (!Y_BF16) {
+                // accumulators straight to HBM: lanes 0..31 and 32..63 each write one 128-byte line
+                float* __restrict__ Y = static_cast<float*>(Yv);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = acc_row16(v, kh);
-                if (r < rows_left) {
-                    const size_t d = SCATTER ? (size_t)gidx[r] : (size_t)(ra + u * 32 + r);
+                for (int v = 0; v < 16; ++v) {
+                    const int r = acc_row16(v, kh);
+                    if (r < rows_left) {
+                        const size_t d = SCATTER ? (size_t)gidx[r] : (size_t)(ra + u * 32 + r);
 #pragma unroll
-                    for (int b = 0; b < OB; ++b) Y[d * OD + b * 32 + m] = acc[b][v];
+                            for (int b = 0; b < OB; ++b) {
+                            if (ACC) Y[d * OD + b * 32 + m] += acc[b][v];
+                            else Y[d * OD + b * 32 + m] = acc[b][v];
+                        }
+                    }
+                }
+            } else {
+                // bf16 rows go through the wavefront's A area of LDS (free once the operand reads are
+                // done), so that HBM sees whole rows: registers v and v + 1 hold rows r and r + 1 of
+                // column m; neighbouring lanes swap one of the two, an even lane then owns (row r;
+                // columns m, m + 1), an odd lane (row r + 1; columns m - 1, m), and each writes one
+                // packed pair.  Then 16-byte pieces of whole rows are copied out, OD / 8 lanes per row.
+                static_assert(!Y_BF16 || (A_BF16 && OD <= CD), "the output tile is staged in the A area");
+                unsigned short* __restrict__ Y = static_cast<unsigned short*>(Yv);
+                const bool odd = m & 1;
+                wave_lds_fence_b();
+#pragma unroll
+                for (int v = 0; v < 16; v += 2) {
+                    const int r = acc_row16(v, kh) + (odd ? 1 : 0);
+#pragma unroll
+                    for (int b = 0; b < OB; ++b) {
+                        // quad_perm [1, 0, 3, 2]: the neighbouring lane's two values
+                        const float a0 = acc[b][v], a1 = acc[b][v + 1];
+                        const float n0 = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(a0), 0xB1, 0xF, 0xF, true));
+                        const float n1 = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(a1), 0xB1, 0xF, 0xF, true));
+                        const unsigned w = bf16_pack_rne(odd ? n1 : a0, odd ? a1 : n0);
+                        *reinterpret_cast<unsigned*>(Aw + r * LS + b * 32 + (m & ~1)) = w;
+                    }
+                }
+                wave_lds_fence_b();
+                constexpr int LPO = OD / 8, RPP = 64 / LPO;       // lanes per output row, rows per pass
+                const int oc = lane % LPO, orow = lane / LPO;
+#pragma unroll
+                for (int pass = 0; pass < 32 / RPP; ++pass) {
+                    const int r = orow + pass * RPP;
+                    if (r < rows_left) {
+                        const size_t d = SCATTER ? (size_t)gidx[r] : (size_t)(ra + u * 32 + r);
+                        *reinterpret_cast<v4u*>(Y + d * OD + oc * 8) = *reinterpret_cast<const v4u*>(Aw + r * LS + oc * 8);
+                    }
                 }
             }
             wave_lds_fence_b();           // operand reads (and gidx reads) are done before the next unit's rows land
@@ -179,63 +227,72 @@ __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, con
 }
 
 // ---------------------------------------------------------------------------------------
-// Weight gradient on the bf16 matrix cores:  dW[seg] = sum_{i in seg} X[g(i)]^T dY[i],  D x D.
+// Weight gradient on the bf16 matrix cores:  dW[seg] = sum_{i in seg} X[g(i)]^T dY[i],  D x D,
+// X and dY rows stored as bf16.
 // The contraction runs over rows, so the MFMA operands are "eight consecutive rows of one
 // feature": the 64-row tile is stored feature-major in LDS (T[f][row]), transposed while it is
-// written.  Feature row f keeps its eight 16-byte row groups at positions g ^ ((f ^ (f >> 3)) & 7):
-// the 16-byte operand reads of 8 neighbouring features then fall on 8 different bank groups, and
-// the 2-byte transposing writes of the 16 (or 32) lanes sharing a row spread over 8 banks as well.
-// X is used as is when its bf16 original exists, otherwise it and dY are split into hi + lo planes.
-// Each of the four wavefronts owns one 32-feature band of X and all four 32-column blocks of dY
-// (64 accumulator registers), kept across the tiles of a segment and flushed to the chunk's slot.
+// written.  A lane loads the same eight features of four consecutive rows, packs the four
+// values of each feature into one 8-byte word and writes eight such words.  Feature row f keeps
+// its eight 16-byte row groups at positions g ^ ((f ^ (f >> 3)) & 7): the 16-byte operand reads
+// of 8 neighbouring features then fall on 8 different bank groups, and so do the transposing
+// writes of the 16 lanes sharing a row group.  Two LDS buffers alternate, so one barrier per
+// tile is enough.  Each of the four wavefronts owns one 32-feature band of X and all four
+// 32-column blocks of dY (64 accumulator registers), kept across the tiles of a segment and
+// flushed to the chunk's slot.
 __device__ __forceinline__ int tswz(int f, int row) {
     return f * 64 + ((((row >> 3) ^ (f ^ (f >> 3))) & 7) << 3) + (row & 7);
 }
 
-template <int D, bool X_BF16, bool GATHER, bool DYG>
+// rows[k] = eight bf16 of row k (k = 0..3); writes T[f0 + e][row0 .. row0 + 3] for e = 0..7
+__device__ __forceinline__ void transpose4_to_lds(unsigned short* __restrict__ T, int f0, int row0, const v4u (&rows)[4]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const unsigned a0 = rows[0][e >> 1], a1 = rows[1][e >> 1], a2 = rows[2][e >> 1], a3 = rows[3][e >> 1];
+        const unsigned w01 = (e & 1) ? ((a0 >> 16) | (a1 & 0xFFFF0000u)) : ((a0 & 0xFFFFu) | (a1 << 16));
+        const unsigned w23 = (e & 1) ? ((a2 >> 16) | (a3 & 0xFFFF0000u)) : ((a2 & 0xFFFFu) | (a3 << 16));
+        *reinterpret_cast<uint2*>(T + tswz(f0 + e, row0)) = make_uint2(w01, w23);
+    }
+}
+
+template <int D, bool GATHER, bool DYG>
 __global__ __launch_bounds__(256) void typed_linear_wgrad_bf16_kernel(TileArgsB t, const int32_t* __restrict__ chunk_slot,
-                                                                      const void* __restrict__ Xv,
+                                                                      const unsigned short* __restrict__ X,
                                                                       const int32_t* __restrict__ gather,
-                                                                      const float* __restrict__ dY,
+                                                                      const unsigned short* __restrict__ dY,
                                                                       float* __restrict__ part) {
     static_assert(D == 128, "four wavefronts x four 32-column blocks");
     constexpr int TMW = 64;
-    constexpr int XPL = X_BF16 ? 1 : 2;
-    constexpr int LPX = X_BF16 ? D / 8 : D / 4, RPX = 256 / LPX, NXL = TMW / RPX;   // X: lanes/row, rows/pass, passes
-    constexpr int LPY = D / 4, RPY = 256 / LPY, NYL = TMW / RPY;
+    constexpr int LPX = D / 8;                        // lanes per row (16-byte loads)
     constexpr int SLOT = D * D + D;
+    constexpr int BUF = 2 * D * 64;                   // one buffer: X tile and dY tile, feature-major
     extern __shared__ __align__(16) unsigned short lds[];
-    unsigned short* Xt = lds;                         // [XPL][D][64]
-    unsigned short* Yt = lds + XPL * D * 64;          // [2][D][64]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 31, kh = lane >> 5;
-    const int cx = tid % LPX, rx = tid / LPX, cy = tid % LPY, ry = tid / LPY;
+    const int cx = tid % LPX, rq = tid / LPX;         // features 8 cx .. 8 cx + 7 of rows 4 rq .. 4 rq + 3
     v16f acc[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
     const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
-    v4u xr[NXL], yr[NYL];
-    int gi[NXL];
+    v4u xr[4], yr[4];
+    int gi[4];
 #define RGNN_W_FETCH_IDX(TI)                                                        \
     {                                                                               \
         const int row0_ = t.tile_row0[TI], row1_ = t.tile_row1[TI];                 \
-        _Pragma("unroll") for (int it = 0; it < NXL; ++it) {                        \
-            const int row_ = min(row0_ + rx + it * RPX, row1_ - 1);                 \
-            gi[it] = GATHER ? gather[row_] : row_;                                  \
+        _Pragma("unroll") for (int k = 0; k < 4; ++k) {                             \
+            const int row_ = min(row0_ + 4 * rq + k, row1_ - 1);                    \
+            gi[k] = GATHER ? gather[row_] : row_;                                   \
         }                                                                           \
     }
 #define RGNN_W_FETCH(TI)                                                            \
     {                                                                               \
         const int row0_ = t.tile_row0[TI], row1_ = t.tile_row1[TI];                 \
-        _Pragma("unroll") for (int it = 0; it < NXL; ++it)                          \
-            xr[it] = *reinterpret_cast<const v4u*>(static_cast<const char*>(Xv) +   \
-                                                   (size_t)gi[it] * D * (X_BF16 ? 2 : 4) + cx * 16); \
-        _Pragma("unroll") for (int it = 0; it < NYL; ++it) {                        \
-            const int row_ = min(row0_ + ry + it * RPY, row1_ - 1);                 \
-            const size_t s_ = (DYG && GATHER) ? (size_t)gather[row_] : (size_t)row_; \
-            yr[it] = *reinterpret_cast<const v4u*>(dY + s_ * D + cy * 4);           \
+        _Pragma("unroll") for (int k = 0; k < 4; ++k) {                             \
+            xr[k] = *reinterpret_cast<const v4u*>(X + (size_t)gi[k] * D + cx * 8);  \
+            const int row_ = min(row0_ + 4 * rq + k, row1_ - 1);                    \
+            const size_t s_ = (DYG && GATHER) ? (size_t)gi[k] : (size_t)row_;       \
+            yr[k] = *reinterpret_cast<const v4u*>(dY + s_ * D + cx * 8);            \
         }                                                                           \
     }
     if (t0 < t1) {
@@ -263,76 +320,45 @@ __global__ __launch_bounds__(256) void typed_linear_wgrad_bf16_kernel(TileArgsB 
             cur_seg = seg;
         }
         const int rows = t.tile_row1[ti] - t.tile_row0[ti];
-        // transpose the prefetched rows into LDS (rows past the end of the tile as zeros)
+        unsigned short* Xt = lds + ((ti - t0) & 1) * BUF;   // [D][64]
+        unsigned short* Yt = Xt + D * 64;                   // [D][64]
+        // rows past the end of the tile count as zeros
 #pragma unroll
-        for (int it = 0; it < NXL; ++it) {
-            const int r = rx + it * RPX;
-            const bool ok = r < rows;
-            if (X_BF16) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const unsigned w = xr[it][e >> 1];
-                    const unsigned short v = ok ? (unsigned short)((e & 1) ? (w >> 16) : (w & 0xFFFFu)) : (unsigned short)0;
-                    Xt[tswz(cx * 8 + e, r)] = v;
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    unsigned h, l;
-                    bf16_split(ok ? __uint_as_float(xr[it][e]) : 0.f, h, l);
-                    Xt[tswz(cx * 4 + e, r)] = (unsigned short)h;
-                    Xt[D * 64 + tswz(cx * 4 + e, r)] = (unsigned short)l;
-                }
+        for (int k = 0; k < 4; ++k)
+            if (4 * rq + k >= rows) {
+                xr[k] = v4u{0u, 0u, 0u, 0u};
+                yr[k] = v4u{0u, 0u, 0u, 0u};
             }
-        }
-#pragma unroll
-        for (int it = 0; it < NYL; ++it) {
-            const int r = ry + it * RPY;
-            const bool ok = r < rows;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                unsigned h, l;
-                bf16_split(ok ? __uint_as_float(yr[it][e]) : 0.f, h, l);
-                Yt[tswz(cy * 4 + e, r)] = (unsigned short)h;
-                Yt[D * 64 + tswz(cy * 4 + e, r)] = (unsigned short)l;
-            }
-        }
-        __syncthreads();
+        transpose4_to_lds(Xt, cx * 8, 4 * rq, xr);
+        transpose4_to_lds(Yt, cx * 8, 4 * rq, yr);
+        __syncthreads();   // the tile is complete; the other buffer is free once every wavefront is here
         if (ti + 1 < t1) RGNN_W_FETCH(ti + 1)
         if (ti + 2 < t1) RGNN_W_FETCH_IDX(ti + 2)
 #pragma unroll
         for (int s = 0; s < TMW / 16; ++s) {
             const int r0 = 16 * s + 8 * kh;
-            const int fa = wave * 32 + m;
-            const bf16x8 ah = *reinterpret_cast<const bf16x8*>(Xt + tswz(fa, r0));
-            bf16x8 al;
-            if (!X_BF16) al = *reinterpret_cast<const bf16x8*>(Xt + D * 64 + tswz(fa, r0));
+            const bf16x8 ah = *reinterpret_cast<const bf16x8*>(Xt + tswz(wave * 32 + m, r0));
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const int fb = b * 32 + m;
-                const bf16x8 bh = *reinterpret_cast<const bf16x8*>(Yt + tswz(fb, r0));
-                const bf16x8 bl = *reinterpret_cast<const bf16x8*>(Yt + D * 64 + tswz(fb, r0));
+                const bf16x8 bh = *reinterpret_cast<const bf16x8*>(Yt + tswz(b * 32 + m, r0));
                 acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc[b], 0, 0, 0);
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc[b], 0, 0, 0);
-                if (!X_BF16) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc[b], 0, 0, 0);
             }
         }
-        __syncthreads();   // operand reads are done before the next tile is transposed in
     }
 #undef RGNN_W_FETCH_IDX
 #undef RGNN_W_FETCH
 }
 
-template <bool X_BF16, bool GATHER, bool DYG>
+template <bool GATHER, bool DYG>
 static rgnn_status_t launch_wgrad(const TypedLinearWgradBf16Args& a, hipStream_t st) {
     constexpr int D = 128;
-    const size_t lds = sizeof(unsigned short) * ((X_BF16 ? 1 : 2) + 2) * D * 64;
-    auto kern = typed_linear_wgrad_bf16_kernel<D, X_BF16, GATHER, DYG>;
+    const size_t lds = sizeof(unsigned short) * 2 * (2 * D * 64);
+    auto kern = typed_linear_wgrad_bf16_kernel<D, GATHER, DYG>;
     RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_wgrad");
     TileArgsB t{a.tiles->tile_seg, a.tiles->tile_row0, a.tiles->tile_row1, a.tiles->chunk_tile};
-    hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.tiles->chunk_slot, a.X, a.gather, a.dY,
-                       a.part);
+    hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.tiles->chunk_slot,
+                       static_cast<const unsigned short*>(a.X), a.gather, static_cast<const unsigned short*>(a.dY), a.part);
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -342,21 +368,16 @@ rgnn_status_t typed_linear_wgrad_bf16(int d, const TypedLinearWgradBf16Args& a, 
     if (d != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_wgrad_bf16: width %d not supported (128)", d);
     if (a.tiles->num_tiles == 0) return RGNN_OK;
     const bool g = a.gather != nullptr, dg = g && a.dy_gathered;
-    if (a.x_bf16) {
-        if (g && dg) return launch_wgrad<true, true, true>(a, st);
-        if (g) return launch_wgrad<true, true, false>(a, st);
-        return launch_wgrad<true, false, false>(a, st);
-    }
-    if (g && dg) return launch_wgrad<false, true, true>(a, st);
-    if (g) return launch_wgrad<false, true, false>(a, st);
-    return launch_wgrad<false, false, false>(a, st);
+    if (g && dg) return launch_wgrad<true, true>(a, st);
+    if (g) return launch_wgrad<true, false>(a, st);
+    return launch_wgrad<false, false>(a, st);
 }
 
-template <int CD, int OD, bool A_BF16, bool W_BF16, bool WT, bool GATHER, bool SCATTER>
+template <int CD, int OD, bool A_BF16, bool W_BF16, bool WT, bool GATHER, bool SCATTER, bool Y_BF16, bool ACC>
 static rgnn_status_t launch(const TypedLinearBf16Args& a, hipStream_t st) {
     constexpr int LS = CD + 8, APL = A_BF16 ? 1 : 2, WPL = W_BF16 ? 1 : 2;
     const size_t lds = sizeof(unsigned short) * ((size_t)WPL * OD * LS + 4 * (APL * 32 * LS + 64));
-    auto kern = typed_linear_bf16_kernel<CD, OD, A_BF16, W_BF16, WT, GATHER, SCATTER>;
+    auto kern = typed_linear_bf16_kernel<CD, OD, A_BF16, W_BF16, WT, GATHER, SCATTER, Y_BF16, ACC>;
     RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_bf16");
     TileArgsB t{a.tiles->tile_seg, a.tiles->tile_row0, a.tiles->tile_row1, a.tiles->chunk_tile};
@@ -365,22 +386,37 @@ static rgnn_status_t launch(const TypedLinearBf16Args& a, hipStream_t st) {
     return RGNN_OK;
 }
 
-template <int D, bool A_BF16, bool W_BF16, bool WT>
+template <int D, bool A_BF16, bool W_BF16, bool WT, bool Y_BF16, bool ACC = false>
 static rgnn_status_t launch_gs(const TypedLinearBf16Args& a, hipStream_t st) {
     const bool g = a.gather != nullptr, sc = g && a.scatter_out;
-    if (g && sc) return launch<D, D, A_BF16, W_BF16, WT, true, true>(a, st);
-    if (g) return launch<D, D, A_BF16, W_BF16, WT, true, false>(a, st);
-    return launch<D, D, A_BF16, W_BF16, WT, false, false>(a, st);
+    if (g && sc) return launch<D, D, A_BF16, W_BF16, WT, true, true, Y_BF16, ACC>(a, st);
+    if constexpr (ACC) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_bf16: accumulation is built for gathered + scattered rows only");
+    if (g) return launch<D, D, A_BF16, W_BF16, WT, true, false, Y_BF16, false>(a, st);
+    return launch<D, D, A_BF16, W_BF16, WT, false, false, Y_BF16, false>(a, st);
 }
 
+// The combinations the layers use.  Below width 128 only forward products with fp32 results occur
+// (intermediate rows are fp32 there); at width 128 every row operand is bf16.
 template <int D>
 static rgnn_status_t launch_d(const TypedLinearBf16Args& a, hipStream_t st) {
-    // the combinations the layers use
-    if (a.a_bf16 && a.w_bf16 && !a.transpose_w) return launch_gs<D, true, true, false>(a, st);    // X W
-    if (!a.a_bf16 && a.w_bf16 && !a.transpose_w) return launch_gs<D, false, true, false>(a, st);  // Z Wo
-    if (!a.a_bf16 && a.w_bf16 && a.transpose_w) return launch_gs<D, false, true, true>(a, st);    // dY W^T
-    if (!a.a_bf16 && !a.w_bf16 && !a.transpose_w) return launch_gs<D, false, false, false>(a, st); // K Watt_bd
-    if (!a.a_bf16 && !a.w_bf16 && a.transpose_w) return launch_gs<D, false, false, true>(a, st);  // dKa Watt_bd^T
+    if constexpr (D < 128) {
+        if (a.y_bf16 || a.transpose_w || a.accumulate) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_bf16: combination needs width 128");
+        if (a.a_bf16 && a.w_bf16) return launch_gs<D, true, true, false, false>(a, st);      // X W
+        if (!a.a_bf16 && a.w_bf16) return launch_gs<D, false, true, false, false>(a, st);    // Z Wo
+        if (!a.a_bf16 && !a.w_bf16) return launch_gs<D, false, false, false, false>(a, st);  // K Watt_bd
+    } else {
+        if (!a.a_bf16) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_bf16: width 128 takes bf16 rows");
+        if (a.accumulate) {
+            if (a.w_bf16 && a.transpose_w && !a.y_bf16) return launch_gs<D, true, true, true, false, true>(a, st);  // dX += dQ Wq^T
+            RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_bf16: accumulation is built for fp32 results of bf16 W^T only");
+        }
+        if (a.w_bf16 && !a.transpose_w && a.y_bf16) return launch_gs<D, true, true, false, true>(a, st);    // X W -> Hs, K, Q, V
+        if (a.w_bf16 && !a.transpose_w && !a.y_bf16) return launch_gs<D, true, true, false, false>(a, st);  // Z Wo -> out
+        if (!a.w_bf16 && !a.transpose_w && a.y_bf16) return launch_gs<D, true, false, false, true>(a, st);  // K Watt_bd -> Ka
+        if (a.w_bf16 && a.transpose_w && a.y_bf16) return launch_gs<D, true, true, true, true>(a, st);      // dY W^T -> bf16 rows
+        if (a.w_bf16 && a.transpose_w && !a.y_bf16) return launch_gs<D, true, true, true, false>(a, st);    // dK Wk^T -> fp32 dX part
+        if (!a.w_bf16 && a.transpose_w && a.y_bf16) return launch_gs<D, true, false, true, true>(a, st);    // dKa Watt_bd^T
+    }
     RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_bf16: operand combination not built");
 }
 
