@@ -128,6 +128,57 @@ def run_oracle(c):
     return want, tf, tb
 
 
+def train_step_bench(args):
+    """Two-layer RGAT model, full-graph training step (forward, NLL loss, backward, SGD), the
+    protocol of the thesis' evaluation section; one JSON line like the layer benchmark."""
+    import numpy as np
+    import torch
+    from paper_2412_04747_amd import synth, binding as B, autograd as A
+    c = synth.config(args.config, args.scale)
+    if c["layer"] != "rgat":
+        sys.exit("bench.py --train: pick an RGAT workload (--config 2 or 3)")
+    N, R, E, d = c["N"], c["R"], c["E"], c["d_out"]
+    g = A.Graph(N, R, c["src"], c["dst"], c["rel"])
+    torch.manual_seed(synth.SEED0)
+    layers = [A.RgatConv(R, d, c["slope"]), A.RgatConv(R, d, c["slope"])]
+    params = [q for l in layers for q in l.parameters()]
+    X = torch.tensor(c["X"], dtype=torch.float32, device="cuda")
+    rng = np.random.default_rng(synth.SEED0)
+    train = torch.as_tensor(rng.choice(N, max(N // 10, 1), replace=False), device="cuda")
+    labels = torch.as_tensor(rng.integers(0, d, len(train)), device="cuda")
+    opt = torch.optim.SGD(params, lr=1e-3)
+
+    def step():
+        opt.zero_grad(set_to_none=True)
+        h = layers[1](g, torch.relu(layers[0](g, X)))
+        loss = torch.nn.functional.nll_loss(torch.log_softmax(h[train], dim=1), labels)
+        loss.backward()
+        opt.step()
+        return loss
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.rgnn_profile_start()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loss = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    rep = B.rgnn_profile_stop()
+    lib_ms = sum(ms for _, ms in rep.values()) / args.steps
+    print(f"[bench] train step {dt * 1e3 / args.steps:.3f} ms, of which {lib_ms:.3f} ms in the library's kernels; "
+          f"last loss {loss.item():.4f}", file=sys.stderr, flush=True)
+    print(json.dumps({
+        "metric": "edges/sec for 2-layer RGAT training step (fwd + NLL loss + bwd + SGD)",
+        "value": 2 * E * args.steps / dt, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}] graph, two RGAT layers of width {d}, N={N}, R={R}, E={E}; "
+                               "value counts every edge once per layer"},
+        "library_kernel_ms_per_step": lib_ms}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -137,6 +188,9 @@ def main():
                     help="synthetic workload id 1..5 (default 3 = the headline RGAT graph the metric is quoted on)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle leg (no cpu_baseline, no parity)")
+    ap.add_argument("--train", action="store_true",
+                    help="time a full training step instead: two RGAT layers through the autograd front end, "
+                         "log-softmax + NLL loss on 10%% of the nodes, SGD update (RGAT workloads only)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); the multi-GPU sharding is a design note "
@@ -148,6 +202,8 @@ def main():
     from paper_2412_04747_amd.harness import Graph
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.train:
+        return train_step_bench(args)
     t0 = time.time()
     c = synth.config(args.config, args.scale)
     N, R, E, d, T, H = c["N"], c["R"], c["E"], c["d_out"], c["T"], c["H"]
