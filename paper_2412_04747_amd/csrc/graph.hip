@@ -55,126 +55,28 @@ struct Uploader {
     }
 };
 
-// Tiles of `tile_rows` rows over segments seg_ptr[0..S], cut into chunks.
 static void build_tiles(Uploader& U, TileList& t, const std::vector<int32_t>& seg_ptr, int tile_rows,
                         int max_chunks = kMaxChunks) {
-    const int S = (int)seg_ptr.size() - 1;
-    std::vector<int32_t> tseg, r0, r1;
-    for (int s = 0; s < S; ++s)
-        for (int32_t a = seg_ptr[s]; a < seg_ptr[s + 1]; a += tile_rows) {
-            tseg.push_back(s);
-            r0.push_back(a);
-            r1.push_back(std::min<int32_t>(a + tile_rows, seg_ptr[s + 1]));
-        }
-    const int nt = (int)tseg.size();
-    // a chunk pays for one weight-tile load and one weight-gradient flush, so it should span several
-    // tiles; but small inputs still need a few hundred chunks to occupy the compute units
-    const int nc = std::min(max_chunks, std::max(std::min(nt, kMinChunks), nt / kChunkTiles));
-    std::vector<int32_t> ctile(nc + 1, 0), cslot(std::max(nc, 1), 0), sslot(S + 1, 0);
-    int slots = 0;
-    std::vector<int32_t> seg_slots(S, 0);
-    for (int c = 0; c < nc; ++c) {
-        ctile[c] = (int32_t)((int64_t)nt * c / nc);
-        ctile[c + 1] = (int32_t)((int64_t)nt * (c + 1) / nc);
-        cslot[c] = slots;
-        for (int i = ctile[c]; i < ctile[c + 1]; ++i)
-            if (i == ctile[c] || tseg[i] != tseg[i - 1]) {
-                ++slots;
-                seg_slots[tseg[i]]++;
-            }
-    }
-    for (int s = 0; s < S; ++s) sslot[s + 1] = sslot[s] + seg_slots[s];
-    t.tile_rows = tile_rows;
-    t.num_tiles = nt;
-    t.num_chunks = nc;
-    t.num_slots = slots;
-    t.num_segs = S;
-    t.tile_seg = U.up(tseg);
-    t.tile_row0 = U.up(r0);
-    t.tile_row1 = U.up(r1);
-    t.chunk_tile = U.up(ctile);
-    t.chunk_slot = U.up(cslot);
-    t.seg_slot_ptr = U.up(sslot);
+    const TilePlan p = plan_tiles(seg_ptr, tile_rows, max_chunks);
+    t.tile_rows = p.tile_rows; t.num_tiles = p.num_tiles; t.num_chunks = p.num_chunks; t.num_slots = p.num_slots;
+    t.num_segs = p.num_segs;
+    t.tile_seg = U.up(p.tile_seg); t.tile_row0 = U.up(p.tile_row0); t.tile_row1 = U.up(p.tile_row1);
+    t.chunk_tile = U.up(p.chunk_tile); t.chunk_slot = U.up(p.chunk_slot); t.seg_slot_ptr = U.up(p.seg_slot_ptr);
 }
 
-// Items of at most max_len entries over segments ptr[0..S].
-// Segments shorter than `min_len` are left out (their owner handles them elsewhere).
 static void build_items(Uploader& U, ItemList& L, const std::vector<int32_t>& ptr, int max_len, int min_len = 0) {
-    const int S = (int)ptr.size() - 1;
-    std::vector<int32_t> beg, end, row, slot, srow, sptr, pitem, psplit;
-    sptr.push_back(0);
-    int partials = 0;
-    for (int s = 0; s < S; ++s) {
-        const int32_t a = ptr[s], b = ptr[s + 1];
-        if (b - a < min_len) continue;
-        if (b - a <= max_len) {
-            beg.push_back(a); end.push_back(b); row.push_back(s); slot.push_back(-1);
-        } else {
-            for (int32_t c = a; c < b; c += max_len) {
-                pitem.push_back((int32_t)beg.size());
-                psplit.push_back((int32_t)srow.size());
-                beg.push_back(c); end.push_back(std::min<int32_t>(c + max_len, b));
-                row.push_back(s); slot.push_back(partials++);
-            }
-            srow.push_back(s);
-            sptr.push_back(partials);
-        }
-    }
-    // Order the items by length, longest first (stable): the lanes of a wavefront and the
-    // wavefronts of a workgroup then walk items of equal length and finish together, and the
-    // long items are scheduled before the short ones fill the tail.  Among items of equal length
-    // the pieces of cut segments come first, so the whole segments with exactly one entry form
-    // one contiguous range [first_single, first_single + num_single), which has a kernel of its own.
-    {
-        const int n = (int)beg.size();
-        int longest = 0;
-        for (int i = 0; i < n; ++i) longest = std::max(longest, end[i] - beg[i]);
-        auto key = [&](int i) { return 2 * (longest - (end[i] - beg[i])) + (slot[i] < 0 ? 1 : 0); };
-        std::vector<int32_t> cnt(2 * longest + 3, 0), perm(n), inv(n);
-        for (int i = 0; i < n; ++i) cnt[key(i) + 1]++;
-        for (size_t l = 0; l + 1 < cnt.size(); ++l) cnt[l + 1] += cnt[l];
-        for (int i = 0; i < n; ++i) { const int p = cnt[key(i)]++; perm[p] = i; inv[i] = p; }
-        auto apply = [&](std::vector<int32_t>& v) {
-            std::vector<int32_t> t(n);
-            for (int p = 0; p < n; ++p) t[p] = v[perm[p]];
-            v.swap(t);
-        };
-        apply(beg); apply(end); apply(row); apply(slot);
-        for (auto& it : pitem) it = inv[it];
-        L.first_single = n;
-        L.num_single = 0;
-        for (int i = 0; i < n; ++i)
-            if (end[i] - beg[i] == 1 && slot[i] < 0) {
-                if (L.num_single == 0) L.first_single = i;
-                ++L.num_single;
-            }
-    }
-    L.num_items = (int)beg.size();
-    L.num_partials = partials;
-    L.num_split = (int)srow.size();
-    L.beg = U.up(beg); L.end = U.up(end); L.row = U.up(row); L.slot = U.up(slot);
-    L.split_row = U.up(srow); L.split_ptr = U.up(sptr);
-    L.part_item = U.up(pitem); L.part_split = U.up(psplit);
-    std::vector<int32_t> lng;
-    for (int i = 0; i < L.num_items; ++i)
-        if (end[i] - beg[i] > kSerialMax || slot[i] >= 0) lng.push_back(i);
-    L.num_long = (int)lng.size();
-    L.long_item = U.up(lng);
-}
-
-// Longest item for a list of `total` entries: kItemMax on large lists; shorter on small ones, where
-// a few long serial walks would otherwise be the whole run time (never below kSerialMax, so that
-// every item a single lane walks stays short).
-static int item_cut(int64_t total) {
-    int cut = kSerialMax;
-    while (cut < kItemMax && (int64_t)cut * kItemTarget < total) cut *= 2;
-    return cut;
+    const ItemPlan p = plan_items(ptr, max_len, min_len);
+    L.num_items = (int32_t)p.beg.size(); L.num_partials = p.num_partials; L.num_split = p.num_split;
+    L.first_single = p.first_single; L.num_single = p.num_single;
+    L.beg = U.up(p.beg); L.end = U.up(p.end); L.row = U.up(p.row); L.slot = U.up(p.slot);
+    L.split_row = U.up(p.split_row); L.split_ptr = U.up(p.split_ptr);
+    L.part_item = U.up(p.part_item); L.part_split = U.up(p.part_split);
+    L.num_long = (int32_t)p.long_item.size();
+    L.long_item = U.up(p.long_item);
 }
 
 static void build_long(Uploader& U, LongList& L, const std::vector<int32_t>& ptr) {
-    std::vector<int32_t> ids;
-    for (size_t i = 0; i + 1 < ptr.size(); ++i)
-        if (ptr[i + 1] - ptr[i] > kSerialMax) ids.push_back((int32_t)i);
+    const std::vector<int32_t> ids = long_segments(ptr);
     L.n = (int)ids.size();
     L.ids = U.up(ids);
 }

@@ -7,6 +7,7 @@
 #include <string>
 #include <vector>
 #include "../../include/rgnn.h"
+#include "work_lists.h"
 
 namespace rgnn {
 
@@ -119,16 +120,6 @@ struct rgnn_graph {
 };
 
 namespace rgnn {
-
-constexpr int kTileRows = 64;       // rows per typed-linear tile
-constexpr int kMaxChunks = 4096;    // tile chunks (workgroups) of the typed-linear kernels: several per resident
-                                    // workgroup slot, so the hardware dispatcher evens out the tail
-constexpr int kWideChunks = 1024;   // chunk limit of the weight-gradient lists
-constexpr int kMinChunks = 512;     // fewer chunks than this only when there are fewer tiles
-constexpr int kChunkTiles = 8;      // tiles a chunk spans before the chunk count grows beyond kMinChunks
-constexpr int kItemMax = 256;       // longest traversal item (entries)
-constexpr int kItemTarget = 65536;  // lists are cut finer while they yield fewer items than this
-constexpr int kSerialMax = 32;      // longest segment a single lane walks; longer ones get a wavefront
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 

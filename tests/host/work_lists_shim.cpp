@@ -1,0 +1,51 @@
+// Test-only C wrapper around the host planning code of the library (work_lists.h), so that the
+// CPU test suite can check the tile and item plans without a GPU.  Built by tests/test_work_lists.py.
+#include "../../paper_2412_04747_amd/csrc/work_lists.h"
+
+#include <cstring>
+
+static rgnn::ItemPlan g_items;
+static rgnn::TilePlan g_tiles;
+
+static int copy_out(const std::vector<int32_t>& v, int32_t* out, int cap) {
+    if (out && (int)v.size() <= cap && !v.empty()) std::memcpy(out, v.data(), v.size() * sizeof(int32_t));
+    return (int)v.size();
+}
+
+extern "C" {
+
+int wl_plan_items(const int32_t* ptr, int nseg, int max_len, int min_len) {
+    g_items = rgnn::plan_items(std::vector<int32_t>(ptr, ptr + nseg + 1), max_len, min_len);
+    return (int)g_items.beg.size();
+}
+// which: 0 beg, 1 end, 2 row, 3 slot, 4 split_row, 5 split_ptr, 6 part_item, 7 part_split, 8 long_item
+int wl_items_field(int which, int32_t* out, int cap) {
+    const std::vector<int32_t>* f[] = {&g_items.beg, &g_items.end, &g_items.row, &g_items.slot, &g_items.split_row,
+                                       &g_items.split_ptr, &g_items.part_item, &g_items.part_split, &g_items.long_item};
+    return copy_out(*f[which], out, cap);
+}
+void wl_items_scalars(int32_t* out4) {
+    out4[0] = g_items.num_partials; out4[1] = g_items.num_split; out4[2] = g_items.first_single; out4[3] = g_items.num_single;
+}
+
+int wl_plan_tiles(const int32_t* seg_ptr, int nseg, int tile_rows, int max_chunks) {
+    g_tiles = rgnn::plan_tiles(std::vector<int32_t>(seg_ptr, seg_ptr + nseg + 1), tile_rows, max_chunks);
+    return g_tiles.num_tiles;
+}
+// which: 0 tile_seg, 1 tile_row0, 2 tile_row1, 3 chunk_tile, 4 chunk_slot, 5 seg_slot_ptr
+int wl_tiles_field(int which, int32_t* out, int cap) {
+    const std::vector<int32_t>* f[] = {&g_tiles.tile_seg, &g_tiles.tile_row0, &g_tiles.tile_row1, &g_tiles.chunk_tile,
+                                       &g_tiles.chunk_slot, &g_tiles.seg_slot_ptr};
+    return copy_out(*f[which], out, cap);
+}
+void wl_tiles_scalars(int32_t* out3) {
+    out3[0] = g_tiles.num_chunks; out3[1] = g_tiles.num_slots; out3[2] = g_tiles.num_segs;
+}
+int wl_item_cut(long long total) { return rgnn::item_cut(total); }
+int wl_constant(int which) {
+    const int c[] = {rgnn::kTileRows, rgnn::kMaxChunks, rgnn::kWideChunks, rgnn::kMinChunks, rgnn::kChunkTiles,
+                     rgnn::kItemMax, rgnn::kItemTarget, rgnn::kSerialMax};
+    return c[which];
+}
+
+}  // extern "C"

@@ -1,0 +1,180 @@
+"""Host planning of the kernels' work lists (tiles/chunks/slots of the typed-linear kernels,
+items of the traversal kernels), checked on the CPU against what the kernels rely on.
+The planning header is compiled with g++ into a small test library; no GPU is involved."""
+import ctypes as C
+import os
+import subprocess
+import tempfile
+
+import numpy as np
+import pytest
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+K = dict(tile_rows=0, max_chunks=1, wide_chunks=2, min_chunks=3, chunk_tiles=4, item_max=5, item_target=6, serial_max=7)
+
+
+@pytest.fixture(scope="module")
+def wl():
+    out = os.path.join(tempfile.mkdtemp(prefix="rgnn_wl_"), "libwl.so")
+    subprocess.check_call(["g++", "-O1", "-std=c++17", "-shared", "-fPIC", "-Wall", "-Werror", "-o", out,
+                           os.path.join(HERE, "host", "work_lists_shim.cpp")])
+    lib = C.CDLL(out)
+    lib.wl_item_cut.argtypes = [C.c_longlong]
+    return lib
+
+
+def _field(fn, which, n_hint=1 << 22):
+    buf = np.empty(n_hint, np.int32)
+    n = fn(which, buf.ctypes.data_as(C.c_void_p), n_hint)
+    assert n <= n_hint
+    return buf[:n].copy()
+
+
+def plan_items(lib, ptr, max_len, min_len=0):
+    ptr = np.ascontiguousarray(ptr, np.int32)
+    n = lib.wl_plan_items(ptr.ctypes.data_as(C.c_void_p), len(ptr) - 1, max_len, min_len)
+    names = ("beg", "end", "row", "slot", "split_row", "split_ptr", "part_item", "part_split", "long_item")
+    p = {k: _field(lib.wl_items_field, i) for i, k in enumerate(names)}
+    sc = np.zeros(4, np.int32)
+    lib.wl_items_scalars(sc.ctypes.data_as(C.c_void_p))
+    p.update(num_items=n, num_partials=int(sc[0]), num_split=int(sc[1]), first_single=int(sc[2]), num_single=int(sc[3]))
+    return p
+
+
+def plan_tiles(lib, seg_ptr, tile_rows, max_chunks):
+    seg_ptr = np.ascontiguousarray(seg_ptr, np.int32)
+    n = lib.wl_plan_tiles(seg_ptr.ctypes.data_as(C.c_void_p), len(seg_ptr) - 1, tile_rows, max_chunks)
+    names = ("tile_seg", "tile_row0", "tile_row1", "chunk_tile", "chunk_slot", "seg_slot_ptr")
+    p = {k: _field(lib.wl_tiles_field, i) for i, k in enumerate(names)}
+    sc = np.zeros(3, np.int32)
+    lib.wl_tiles_scalars(sc.ctypes.data_as(C.c_void_p))
+    p.update(num_tiles=n, num_chunks=int(sc[0]), num_slots=int(sc[1]), num_segs=int(sc[2]))
+    return p
+
+
+def _segments(rng, S, hubs):
+    """Segment lengths with empty, single-entry, short and a few very long segments."""
+    ln = rng.choice([0, 1, 1, 2, 3, 5, 9, 31, 32, 33, 40], size=S)
+    for h in hubs:
+        ln[rng.integers(0, S)] = h
+    return np.concatenate([[0], np.cumsum(ln)]).astype(np.int32)
+
+
+@pytest.mark.parametrize("max_len,min_len,hubs", [(256, 0, (257, 256, 1000, 5000)), (32, 0, (33, 64, 700)),
+                                                   (64, 2, (65, 129, 300)), (1 << 30, 0, (4000,))])
+def test_items_cover_each_segment_once(wl, max_len, min_len, hubs):
+    rng = np.random.default_rng(7 + max_len % 1000 + min_len)
+    ptr = _segments(rng, 3000, hubs)
+    p = plan_items(wl, ptr, max_len, min_len)
+    serial_max = wl.wl_constant(K["serial_max"])
+    n = p["num_items"]
+    ln = p["end"] - p["beg"]
+    seg_len = np.diff(ptr)
+    # every entry of every kept segment lies in exactly one item of that segment; no item is too long
+    cover = np.zeros(ptr[-1], np.int32)
+    for i in range(n):
+        s = p["row"][i]
+        assert ptr[s] <= p["beg"][i] <= p["end"][i] <= ptr[s + 1]
+        cover[p["beg"][i]:p["end"][i]] += 1
+    kept = np.repeat(seg_len >= min_len, seg_len)
+    assert (cover[kept] == 1).all() and (cover[~kept] == 0).all()
+    assert ln.max() <= max_len
+    # whole segments appear once (also the empty ones, which still own an output row), dropped ones never
+    whole = p["slot"] < 0
+    rows_whole = np.sort(p["row"][whole])
+    expect_whole = np.nonzero((seg_len >= min_len) & (seg_len <= max_len))[0]
+    assert np.array_equal(rows_whole, expect_whole)
+    assert (ln[whole] == seg_len[p["row"][whole]]).all()
+    # longest first, pieces before whole segments of the same length
+    assert (np.diff(ln) <= 0).all()
+    same = np.nonzero(np.diff(ln) == 0)[0]
+    assert not ((p["slot"][same] < 0) & (p["slot"][same + 1] >= 0)).any()
+    # cut segments: partial rows numbered 0..num_partials-1, grouped per segment in split_ptr order
+    cut = np.nonzero(seg_len > max_len)[0]
+    assert p["num_split"] == len(cut) and np.array_equal(p["split_row"], cut)
+    assert p["split_ptr"][0] == 0 and p["split_ptr"][-1] == p["num_partials"]
+    assert np.array_equal(np.sort(p["slot"][~whole]), np.arange(p["num_partials"]))
+    for k, s in enumerate(cut):
+        a, b = p["split_ptr"][k], p["split_ptr"][k + 1]
+        assert b - a == -(-seg_len[s] // max_len)
+        items = p["part_item"][a:b]
+        assert (p["slot"][items] == np.arange(a, b)).all() and (p["row"][items] == s).all()
+        assert (p["part_split"][a:b] == k).all()
+        assert p["beg"][items[0]] == ptr[s] and p["end"][items[-1]] == ptr[s + 1]     # pieces in order
+        assert (p["beg"][items[1:]] == p["end"][items[:-1]]).all()
+    # the single-entry whole segments are one contiguous range
+    single = np.nonzero((ln == 1) & whole)[0]
+    assert p["num_single"] == len(single)
+    if len(single):
+        assert p["first_single"] == single[0] and single[-1] == single[0] + len(single) - 1
+    # long items: more than serial_max entries, or any piece of a cut segment
+    assert np.array_equal(p["long_item"], np.nonzero((ln > serial_max) | ~whole)[0])
+
+
+def test_items_keep_segment_order_within_a_length(wl):
+    """Stable order: among whole segments of equal length the output rows ascend, which keeps the
+    stores of neighbouring lanes close together."""
+    rng = np.random.default_rng(3)
+    ptr = _segments(rng, 2000, (300,))
+    p = plan_items(wl, ptr, 256)
+    ln = p["end"] - p["beg"]
+    for length in (0, 1, 2, 5):
+        rows = p["row"][(ln == length) & (p["slot"] < 0)]
+        assert (np.diff(rows) > 0).all()
+
+
+def test_items_empty_input(wl):
+    p = plan_items(wl, np.zeros(1, np.int32), 256)
+    assert p["num_items"] == 0 and p["num_partials"] == 0 and p["num_single"] == 0 and list(p["split_ptr"]) == [0]
+    p = plan_items(wl, np.zeros(6, np.int32), 256)          # five empty segments
+    assert p["num_items"] == 5 and (p["end"] == p["beg"]).all() and p["num_single"] == 0
+
+
+def test_item_cut_grows_with_the_list(wl):
+    lo, hi, target = wl.wl_constant(K["serial_max"]), wl.wl_constant(K["item_max"]), wl.wl_constant(K["item_target"])
+    cuts = [wl.wl_item_cut(t) for t in (0, 1, 10_000, 200_000, 3_000_000, 10_000_000, 10**9)]
+    assert cuts[0] == lo and cuts[-1] == hi and cuts == sorted(cuts)
+    for t, c in zip((200_000, 3_000_000), cuts[3:5]):
+        assert c == hi or c * target >= t                   # fine enough to yield `target` items, or at the cap
+        assert c & (c - 1) == 0
+
+
+@pytest.mark.parametrize("S,max_chunks", [(1, 4096), (7, 4096), (200, 4096), (200, 1024), (500, 64)])
+def test_tiles_chunks_and_slots(wl, S, max_chunks):
+    rng = np.random.default_rng(11 + S)
+    ln = rng.choice([0, 1, 63, 64, 65, 200, 5000], size=S)
+    ln[rng.integers(0, S)] = 300_000
+    seg_ptr = np.concatenate([[0], np.cumsum(ln)]).astype(np.int32)
+    T = wl.wl_constant(K["tile_rows"])
+    p = plan_tiles(wl, seg_ptr, T, max_chunks)
+    nt, nc = p["num_tiles"], p["num_chunks"]
+    assert p["num_segs"] == S
+    # tiles: in row order, inside one segment, at most T rows, covering every row once
+    assert nt == int(np.sum(-(-ln // T)))
+    rows = p["tile_row1"] - p["tile_row0"]
+    assert (rows > 0).all() and (rows <= T).all()
+    assert (seg_ptr[p["tile_seg"]] <= p["tile_row0"]).all() and (p["tile_row1"] <= seg_ptr[p["tile_seg"] + 1]).all()
+    assert rows.sum() == seg_ptr[-1] and (p["tile_row0"][1:] >= p["tile_row1"][:-1]).all()
+    # chunks: a partition of the tiles into consecutive, nearly equal ranges
+    assert nc <= max_chunks and nc <= max(nt, 1)
+    ct = p["chunk_tile"]
+    assert ct[0] == 0 and ct[-1] == nt and (np.diff(ct) >= 0).all()
+    if nc:
+        assert np.diff(ct).max() - np.diff(ct).min() <= 1
+    # slots: one per (chunk, segment it touches), numbered in chunk order; a segment's slots are consecutive
+    slot_of = []
+    nxt = 0
+    for c in range(nc):
+        assert p["chunk_slot"][c] == nxt
+        segs = p["tile_seg"][ct[c]:ct[c + 1]]
+        for j, s in enumerate(segs):
+            if j == 0 or s != segs[j - 1]:
+                slot_of.append(s)
+                nxt += 1
+    assert p["num_slots"] == nxt
+    slot_of = np.asarray(slot_of, np.int64)
+    assert (np.diff(slot_of) >= 0).all()
+    ssp = p["seg_slot_ptr"]
+    assert ssp[0] == 0 and ssp[-1] == nxt
+    for s in range(S):
+        assert (slot_of[ssp[s]:ssp[s + 1]] == s).all()
