@@ -243,19 +243,24 @@ __device__ __forceinline__ int tswz(int f, int row) {
     return f * 64 + ((((row >> 3) ^ (f ^ (f >> 3))) & 7) << 3) + (row & 7);
 }
 
-// rows[k] = eight bf16 of row k (k = 0..3); writes T[f0 + e][row0 .. row0 + 3] for e = 0..7
-__device__ __forceinline__ void transpose4_to_lds(unsigned short* __restrict__ T, int f0, int row0, const v4u (&rows)[4]) {
+// rows[k] = eight bf16 of row k (k = 0..3) of features f0 .. f0 + 7 (f0 a multiple of 8); writes
+// T[f0 + e][row0 .. row0 + 3] for e = 0..7.  `at` = tswz(f0, row0) and `g8` = 8 * (its row-group
+// position): feature f0 + e sits 64 e further with the group position XOR e.
+__device__ __forceinline__ void transpose4_to_lds(unsigned short* __restrict__ T, int at, int g8, const v4u (&rows)[4]) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const unsigned a0 = rows[0][e >> 1], a1 = rows[1][e >> 1], a2 = rows[2][e >> 1], a3 = rows[3][e >> 1];
         const unsigned w01 = (e & 1) ? ((a0 >> 16) | (a1 & 0xFFFF0000u)) : ((a0 & 0xFFFFu) | (a1 << 16));
         const unsigned w23 = (e & 1) ? ((a2 >> 16) | (a3 & 0xFFFF0000u)) : ((a2 & 0xFFFFu) | (a3 << 16));
-        *reinterpret_cast<uint2*>(T + tswz(f0 + e, row0)) = make_uint2(w01, w23);
+        *reinterpret_cast<uint2*>(T + at - g8 + e * 64 + (g8 ^ (e * 8))) = make_uint2(w01, w23);
     }
 }
 
-template <int D, bool GATHER, bool DYG>
-__global__ __launch_bounds__(256) void typed_linear_wgrad_bf16_kernel(TileArgsB t, const int32_t* __restrict__ chunk_slot,
+#ifndef RGNN_WGRAD_NBUF
+#define RGNN_WGRAD_NBUF 1
+#endif
+template <int D, bool GATHER, bool DYG, int NBUF>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void typed_linear_wgrad_bf16_kernel(TileArgsB t, const int32_t* __restrict__ chunk_slot,
                                                                       const unsigned short* __restrict__ X,
                                                                       const int32_t* __restrict__ gather,
                                                                       const unsigned short* __restrict__ dY,
@@ -275,6 +280,10 @@ __global__ __launch_bounds__(256) void typed_linear_wgrad_bf16_kernel(TileArgsB 
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
     const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
+    // writes: tswz(8 cx, 4 rq) = wat + 8 * (group position);  reads: tswz(32 j + m, 16 s + 8 kh) =
+    // (32 j + m) * 64 + (8 * ((kh ^ m ^ (m >> 3)) & 7) ^ 32 (j & 1) ^ 16 s)
+    const int wat = cx * 512 + 4 * (rq & 1), wg8_0 = (((rq >> 1) ^ cx) & 7) * 8;
+    const int rg8_0 = ((kh ^ m ^ (m >> 3)) & 7) * 8;
     v4u xr[4], yr[4];
     int gi[4];
 #define RGNN_W_FETCH_IDX(TI)                                                        \
@@ -320,7 +329,7 @@ __global__ __launch_bounds__(256) void typed_linear_wgrad_bf16_kernel(TileArgsB 
             cur_seg = seg;
         }
         const int rows = t.tile_row1[ti] - t.tile_row0[ti];
-        unsigned short* Xt = lds + ((ti - t0) & 1) * BUF;   // [D][64]
+        unsigned short* Xt = lds + ((ti - t0) % NBUF) * BUF;   // [D][64]
         unsigned short* Yt = Xt + D * 64;                   // [D][64]
         // rows past the end of the tile count as zeros
 #pragma unroll
@@ -329,21 +338,26 @@ __global__ __launch_bounds__(256) void typed_linear_wgrad_bf16_kernel(TileArgsB 
                 xr[k] = v4u{0u, 0u, 0u, 0u};
                 yr[k] = v4u{0u, 0u, 0u, 0u};
             }
-        transpose4_to_lds(Xt, cx * 8, 4 * rq, xr);
-        transpose4_to_lds(Yt, cx * 8, 4 * rq, yr);
+        // The swizzled LDS positions differ from a per-lane base only by XORs with constants; the
+        // bases are made opaque once per tile so that the 36 positions are recomputed (one XOR each)
+        // rather than kept in registers across the loop.
+        int wg8 = wg8_0, rg8 = rg8_0;
+        asm volatile("" : "+v"(wg8), "+v"(rg8));
+        transpose4_to_lds(Xt, wat + wg8, wg8, xr);
+        transpose4_to_lds(Yt, wat + wg8, wg8, yr);
         __syncthreads();   // the tile is complete; the other buffer is free once every wavefront is here
         if (ti + 1 < t1) RGNN_W_FETCH(ti + 1)
         if (ti + 2 < t1) RGNN_W_FETCH_IDX(ti + 2)
 #pragma unroll
         for (int s = 0; s < TMW / 16; ++s) {
-            const int r0 = 16 * s + 8 * kh;
-            const bf16x8 ah = *reinterpret_cast<const bf16x8*>(Xt + tswz(wave * 32 + m, r0));
+            const bf16x8 ah = *reinterpret_cast<const bf16x8*>(Xt + (wave * 32 + m) * 64 + (rg8 ^ (32 * (wave & 1)) ^ (16 * s)));
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const bf16x8 bh = *reinterpret_cast<const bf16x8*>(Yt + tswz(b * 32 + m, r0));
+                const bf16x8 bh = *reinterpret_cast<const bf16x8*>(Yt + (b * 32 + m) * 64 + (rg8 ^ (32 * (b & 1)) ^ (16 * s)));
                 acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc[b], 0, 0, 0);
             }
         }
+        if (NBUF == 1) __syncthreads();   // operand reads are done before the next tile is transposed in
     }
 #undef RGNN_W_FETCH_IDX
 #undef RGNN_W_FETCH
@@ -351,9 +365,9 @@ __global__ __launch_bounds__(256) void typed_linear_wgrad_bf16_kernel(TileArgsB 
 
 template <bool GATHER, bool DYG>
 static rgnn_status_t launch_wgrad(const TypedLinearWgradBf16Args& a, hipStream_t st) {
-    constexpr int D = 128;
-    const size_t lds = sizeof(unsigned short) * 2 * (2 * D * 64);
-    auto kern = typed_linear_wgrad_bf16_kernel<D, GATHER, DYG>;
+    constexpr int D = 128, NBUF = RGNN_WGRAD_NBUF;
+    const size_t lds = sizeof(unsigned short) * NBUF * (2 * D * 64);
+    auto kern = typed_linear_wgrad_bf16_kernel<D, GATHER, DYG, NBUF>;
     RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_wgrad");
     TileArgsB t{a.tiles->tile_seg, a.tiles->tile_row0, a.tiles->tile_row1, a.tiles->chunk_tile};
