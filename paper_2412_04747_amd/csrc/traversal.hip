@@ -69,17 +69,28 @@ __global__ void segment_scalar_sum_kernel(int n, const int32_t* __restrict__ ptr
     for (int j = b; j < e; ++j) s += val[(size_t)(via ? via[j] : j) * stride + off];
     out[i] = s;
 }
-__global__ void segment_scalar_sum_long_kernel(int n_long, const int32_t* __restrict__ long_ids,
-                                               const int32_t* __restrict__ ptr, const int32_t* __restrict__ via,
-                                               const float* __restrict__ val, int stride, int off,
-                                               float* __restrict__ out) {
-    const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
-    if (w >= n_long) return;
-    const int i = long_ids[w];
-    float t = 0.f;
-    for (int j = ptr[i] + lane; j < ptr[i + 1]; j += 64) t += val[(size_t)(via ? via[j] : j) * stride + off];
-    t = group_sum<64>(t);
-    if (lane == 0) out[i] = t;
+// One 256-thread workgroup per long segment (the hub runs are thousands of entries long): four
+// loads in flight per lane, lane sums added in lane order, then the four wavefronts' sums in order.
+__global__ __launch_bounds__(256) void segment_scalar_sum_long_kernel(int n_long, const int32_t* __restrict__ long_ids,
+                                                                      const int32_t* __restrict__ ptr,
+                                                                      const int32_t* __restrict__ via,
+                                                                      const float* __restrict__ val, int stride, int off,
+                                                                      float* __restrict__ out) {
+    __shared__ float red[4];
+    const int i = long_ids[blockIdx.x];
+    const int b = ptr[i], e = ptr[i + 1];
+    float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+    for (int j = b + (int)threadIdx.x; j < e; j += 1024) {
+        const int j1 = j + 256, j2 = j + 512, j3 = j + 768;
+        t0 += val[(size_t)(via ? via[j] : j) * stride + off];
+        if (j1 < e) t1 += val[(size_t)(via ? via[j1] : j1) * stride + off];
+        if (j2 < e) t2 += val[(size_t)(via ? via[j2] : j2) * stride + off];
+        if (j3 < e) t3 += val[(size_t)(via ? via[j3] : j3) * stride + off];
+    }
+    const float t = group_sum<64>((t0 + t1) + (t2 + t3));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
+    __syncthreads();
+    if (threadIdx.x == 0) out[i] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
 // ------------------------------------------------------------------ edge softmax (RGAT)
@@ -522,8 +533,8 @@ rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng,
                        off, min_len, out);
     RGNN_CHECK_LAUNCH();
     if (lng.n > 0) {
-        hipLaunchKernelGGL(segment_scalar_sum_long_kernel, dim3(blocks_for((size_t)lng.n * 64, 256)), dim3(256), 0, st,
-                           lng.n, lng.ids, ptr, via, val, stride, off, out);
+        hipLaunchKernelGGL(segment_scalar_sum_long_kernel, dim3(lng.n), dim3(256), 0, st, lng.n, lng.ids, ptr, via, val,
+                           stride, off, out);
         RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;

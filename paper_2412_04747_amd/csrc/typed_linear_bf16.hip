@@ -235,10 +235,11 @@ __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, con
 // values of each feature into one 8-byte word and writes eight such words.  Feature row f keeps
 // its eight 16-byte row groups at positions g ^ ((f ^ (f >> 3)) & 7): the 16-byte operand reads
 // of 8 neighbouring features then fall on 8 different bank groups, and so do the transposing
-// writes of the 16 lanes sharing a row group.  Two LDS buffers alternate, so one barrier per
-// tile is enough.  Each of the four wavefronts owns one 32-feature band of X and all four
-// 32-column blocks of dY (64 accumulator registers), kept across the tiles of a segment and
-// flushed to the chunk's slot.
+// writes of the 16 lanes sharing a row group.  Each of the four wavefronts owns one 32-feature
+// band of X and all four 32-column blocks of dY (64 accumulator registers), kept across the tiles
+// of a segment and flushed to the chunk's slot.  The kernel is bound by how many row loads are in
+// flight, so registers are budgeted for three wavefronts per SIMD and one 32 KB tile buffer is
+// used (NBUF = 2 alternates two buffers and saves a barrier per tile, but halves the occupancy).
 __device__ __forceinline__ int tswz(int f, int row) {
     return f * 64 + ((((row >> 3) ^ (f ^ (f >> 3))) & 7) << 3) + (row & 7);
 }
@@ -256,9 +257,6 @@ __device__ __forceinline__ void transpose4_to_lds(unsigned short* __restrict__ T
     }
 }
 
-#ifndef RGNN_WGRAD_NBUF
-#define RGNN_WGRAD_NBUF 1
-#endif
 template <int D, bool GATHER, bool DYG, int NBUF>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void typed_linear_wgrad_bf16_kernel(TileArgsB t, const int32_t* __restrict__ chunk_slot,
                                                                       const unsigned short* __restrict__ X,
@@ -365,7 +363,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 
 template <bool GATHER, bool DYG>
 static rgnn_status_t launch_wgrad(const TypedLinearWgradBf16Args& a, hipStream_t st) {
-    constexpr int D = 128, NBUF = RGNN_WGRAD_NBUF;
+    constexpr int D = 128, NBUF = 1;
     const size_t lds = sizeof(unsigned short) * NBUF * (2 * D * 64);
     auto kern = typed_linear_wgrad_bf16_kernel<D, GATHER, DYG, NBUF>;
     RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
