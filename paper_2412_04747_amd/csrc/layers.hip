@@ -68,6 +68,7 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
         if (d->heads < 1 || d->d_out % d->heads != 0) RGNN_FAIL(RGNN_EINVAL, "heads must divide d_out");
         const int dh = d->d_out / d->heads;
         if (dh != 16 && dh != 32 && dh != 64) RGNN_FAIL(RGNN_EUNSUPPORTED, "HGT needs d_out / heads in {16, 32, 64}, got %d", dh);
+        if ((int64_t)g->N * d->heads > INT32_MAX) RGNN_FAIL(RGNN_EUNSUPPORTED, "HGT needs num_nodes * heads < 2^31");
     }
     return RGNN_OK;
 }

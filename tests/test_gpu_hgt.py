@@ -68,6 +68,22 @@ def test_hub_isolated_and_single_type():
     _run(300, 1, 4, src, dst, rel, ntype, p, 64, 2, "hub")
 
 
+@pytest.mark.parametrize("dtype,d,H", [("f32", 64, 2), ("bf16", 128, 4)])
+def test_many_single_entry_segments(dtype, d, H):
+    """Thousands of destinations with one incoming edge and of pairs with one edge: the batched
+    single-entry aggregation path with one coefficient per head."""
+    rng = np.random.default_rng(78)
+    N, T, R = 8000, 2, 3
+    ntype = (np.arange(N) >= 5000).astype(np.int32)
+    dst = np.concatenate([rng.permutation(N), rng.integers(0, 40, 500)]).astype(np.int32)
+    src = rng.integers(0, N, len(dst)).astype(np.int32)
+    rel = rng.integers(0, R, len(dst)).astype(np.int32)
+    p = synth.hgt_params(rng, N, T, R, d, H, with_mu=True)
+    if dtype == "bf16":
+        p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}
+    _run(N, T, R, src, dst, rel, ntype, p, d, H, f"singles-{dtype}", dtype=dtype)
+
+
 def test_scaled_config4_bf16():
     c = synth.config(4, scale=0.01)          # 20k nodes, 200k edges, 8 node types, 30 relations, d=128, H=4
     c["mu"] = None

@@ -56,6 +56,18 @@ def test_small_random(d):
     _run(500, 6, src, dst, rel, p, d, f"small-d{d}")
 
 
+def test_many_single_edge_destinations():
+    """Thousands of destinations with exactly one incoming edge (softmax weight 1) next to a few
+    busier ones: the batched single-entry aggregation path."""
+    rng = np.random.default_rng(79)
+    N, R, d = 9000, 5, 64
+    dst = np.concatenate([rng.permutation(N), rng.integers(0, 60, 800)]).astype(np.int32)
+    src = rng.integers(0, N, len(dst)).astype(np.int32)
+    rel = rng.integers(0, R, len(dst)).astype(np.int32)
+    p = synth.rgat_params(rng, N, R, d, d)
+    _run(N, R, src, dst, rel, p, d, "singles")
+
+
 def test_config2():
     c = synth.config(2)
     _run(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 64, "C2")

@@ -76,6 +76,25 @@ def test_small_bf16_all_options(d):
     _run(700, 5, src, dst, rel, p, d, "none", "relu", False, tag=f"bf16-d{d}-relu", dtype="bf16")
 
 
+@pytest.mark.parametrize("dtype,d", [("f32", 32), ("bf16", 128)])
+def test_many_single_entry_segments(dtype, d):
+    """Thousands of destinations with exactly one incoming edge and of pairs with exactly one edge:
+    the batched single-entry aggregation path, forward (destination-major) and backward (pair-major)."""
+    rng = np.random.default_rng(77)
+    N, R = 9000, 4
+    dst = rng.permutation(N).astype(np.int32)              # every node: in-degree exactly 1 ...
+    src = rng.integers(0, N, N).astype(np.int32)
+    rel = rng.integers(0, R, N).astype(np.int32)
+    extra = 600                                            # ... except a few with more, and one hub
+    dst = np.concatenate([dst, rng.integers(0, 50, extra).astype(np.int32)])
+    src = np.concatenate([src, rng.integers(0, N, extra).astype(np.int32)])
+    rel = np.concatenate([rel, rng.integers(0, R, extra).astype(np.int32)])
+    p = synth.rgcn_params(rng, N, R, d, d, self_loop=False)
+    if dtype == "bf16":
+        p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}
+    _run(N, R, src, dst, rel, p, d, "in_degree_per_rel", "none", False, tag=f"singles-{dtype}", dtype=dtype)
+
+
 def test_scaled_config5_bf16():
     c = synth.config(5, scale=0.01)          # knowledge-graph shaped: 500 relations, many with a handful of edges
     _run(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 128, "in_degree_per_rel", "none", False, tag="C5/100",
