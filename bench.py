@@ -314,7 +314,10 @@ def main():
         "metric": f"edges/sec for {c['layer'].upper()} layer {'fwd' if fwd_only else 'fwd+bwd'}",
         "value": E * args.steps / dt, "unit": "edges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        # the arithmetic type of the path: fp32 throughout, or bf16 storage / bf16 matrix-core operands with
+        # fp32 accumulation for the bfloat16 workloads
+        "dtype": "bf16" if c["dtype"] == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}]: {c['layer'].upper()} {'fwd' if fwd_only else 'fwd+bwd'}, "
                                f"{c['dtype']} inputs, N={N}, T={T}, R={R}, E={E}, d={d}, H={H}"
                                + ("" if args.scale == 1.0 else f" (scale {args.scale})"),

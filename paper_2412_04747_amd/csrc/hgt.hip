@@ -92,34 +92,62 @@ __global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, co
 // Per-head softmax of att[e][h] (holding logits on entry) over each destination's edges.
 // Short nodes: one lane per (node, head).  Long items and pieces of cut nodes: one wavefront
 // per item, heads in turn; pieces store (max, sum) per head for the finish kernel.
-__global__ void hgt_softmax_kernel(int N, int H, const int32_t* __restrict__ in_ptr, float* __restrict__ att) {
+__global__ __launch_bounds__(256) void hgt_softmax_kernel(int N, int H, const int32_t* __restrict__ in_ptr,
+                                                          float* __restrict__ att) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= N * H) return;
     const int v = t / H, h = t % H;
-    const int b = in_ptr[v], e = in_ptr[v + 1];
-    if (e == b || e - b > kSerialMax) return;
+    const int b = in_ptr[v], len = in_ptr[v + 1] - b;
+    if (len == 0 || len > kSerialMax) return;
+    float l[kSerialMax];               // the logits stay in registers: one read and one write of att
+#pragma unroll
+    for (int c = 0; c < kSerialMax; c += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) l[c + u] = -INFINITY;
+        if (c < len) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (c + u < len) l[c + u] = att[(size_t)(b + c + u) * H + h];
+        }
+    }
     float m = -INFINITY, s = 0.f;
-    for (int j = b; j < e; ++j) m = fmaxf(m, att[(size_t)j * H + h]);
-    for (int j = b; j < e; ++j) s += expf(att[(size_t)j * H + h] - m);
+#pragma unroll
+    for (int k = 0; k < kSerialMax; ++k) m = fmaxf(m, l[k]);
+#pragma unroll
+    for (int k = 0; k < kSerialMax; ++k) s += expf(l[k] - m);
     const float inv = 1.f / s;
-    for (int j = b; j < e; ++j) att[(size_t)j * H + h] = expf(att[(size_t)j * H + h] - m) * inv;
+#pragma unroll
+    for (int k = 0; k < kSerialMax; ++k)
+        if (k < len) att[(size_t)(b + k) * H + h] = expf(l[k] - m) * inv;
 }
-__global__ void hgt_softmax_long_kernel(Items it, int n_long, const int32_t* __restrict__ long_item, int H,
-                                        float* __restrict__ att, float* __restrict__ part_m,
-                                        float* __restrict__ part_s) {
+__global__ __launch_bounds__(256) void hgt_softmax_long_kernel(Items it, int n_long, const int32_t* __restrict__ long_item,
+                                                               int H, float* __restrict__ att, float* __restrict__ part_m,
+                                                               float* __restrict__ part_s) {
+    constexpr int PER = kItemMax / 64;     // an item has at most kItemMax entries
     const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
     if (w >= n_long) return;
     const int i = long_item[w];
     const int bb = it.beg[i], ee = it.end[i], sl = it.slot[i];
     for (int h = 0; h < H; ++h) {
+        float l[PER];
         float m = -INFINITY, s = 0.f;
-        for (int j = bb + lane; j < ee; j += 64) m = fmaxf(m, att[(size_t)j * H + h]);
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int j = bb + lane + 64 * u;
+            l[u] = j < ee ? att[(size_t)j * H + h] : -INFINITY;
+            m = fmaxf(m, l[u]);
+        }
         m = wave_max(m);
-        for (int j = bb + lane; j < ee; j += 64) s += expf(att[(size_t)j * H + h] - m);
+#pragma unroll
+        for (int u = 0; u < PER; ++u) s += expf(l[u] - m);
         s = group_sum<64>(s);
         if (sl < 0) {
             const float inv = 1.f / s;
-            for (int j = bb + lane; j < ee; j += 64) att[(size_t)j * H + h] = expf(att[(size_t)j * H + h] - m) * inv;
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int j = bb + lane + 64 * u;
+                if (j < ee) att[(size_t)j * H + h] = expf(l[u] - m) * inv;
+            }
         } else if (lane == 0) {
             part_m[(size_t)sl * H + h] = m;
             part_s[(size_t)sl * H + h] = s;

@@ -117,47 +117,88 @@ __device__ __forceinline__ float signed_att(float l, float m, float inv) {
 }
 
 // Destinations with at most kSerialMax incoming edges: one lane per node, in node order, so
-// that neighbouring lanes walk neighbouring CSR ranges.  Everything else (longer nodes and
-// the pieces of cut nodes) goes through edge_softmax_long_kernel.
-__global__ void edge_softmax_kernel(SoftmaxArgs a, int N, const int32_t* __restrict__ in_ptr) {
+// that neighbouring lanes walk neighbouring CSR ranges.  The logits stay in registers (the loop
+// over the kSerialMax slots is fully unrolled and predicated), eight index pairs and then eight
+// logit gathers are in flight at a time, and att is written once.  Everything else (longer nodes
+// and the pieces of cut nodes) goes through edge_softmax_long_kernel.
+__global__ __launch_bounds__(256) void edge_softmax_kernel(SoftmaxArgs a, int N, const int32_t* __restrict__ in_ptr) {
     const int v = blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= N) return;
-    const int b = in_ptr[v], e = in_ptr[v + 1];
-    if (e == b || e - b > kSerialMax) return;
-    float m = -INFINITY, s = 0.f;
-    for (int j = b; j < e; ++j) {
-        const float z = a.s_src[a.in_pair[j]] + a.s_dst[a.in_run[j]];
-        const float l = z > 0.f ? z : a.slope * z;
-        a.att[j] = l;
-        m = fmaxf(m, l);
+    const int b = in_ptr[v], len = in_ptr[v + 1] - b;
+    if (len == 0 || len > kSerialMax) return;
+    float l[kSerialMax];
+#pragma unroll
+    for (int c = 0; c < kSerialMax; c += 8) {
+        if (c < len) {
+            int pr[8], rn[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int j = b + min(c + u, len - 1);
+                pr[u] = a.in_pair[j];
+                rn[u] = a.in_run[j];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float z = a.s_src[pr[u]] + a.s_dst[rn[u]];
+                l[c + u] = c + u < len ? (z > 0.f ? z : a.slope * z) : -INFINITY;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) l[c + u] = -INFINITY;
+        }
     }
-    for (int j = b; j < e; ++j) s += expf(a.att[j] - m);
+    float m = -INFINITY, s = 0.f;
+#pragma unroll
+    for (int k = 0; k < kSerialMax; ++k) m = fmaxf(m, l[k]);
+#pragma unroll
+    for (int k = 0; k < kSerialMax; ++k) s += expf(l[k] - m);     // the empty slots add exp(-inf) = 0
     const float inv = 1.f / s;
-    for (int j = b; j < e; ++j) a.att[j] = signed_att(a.att[j], m, inv);
+#pragma unroll
+    for (int k = 0; k < kSerialMax; ++k)
+        if (k < len) a.att[b + k] = signed_att(l[k], m, inv);
 }
 
-// One wavefront per item that is longer than kSerialMax or is a piece of a cut node.
-__global__ void edge_softmax_long_kernel(SoftmaxArgs a, int n_long, const int32_t* __restrict__ long_item) {
+// One wavefront per item that is longer than kSerialMax or is a piece of a cut node.  An item has at
+// most kItemMax entries, kItemMax / 64 per lane, which stay in registers between the passes.
+__global__ __launch_bounds__(256) void edge_softmax_long_kernel(SoftmaxArgs a, int n_long, const int32_t* __restrict__ long_item) {
+    constexpr int PER = kItemMax / 64;
     const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
     if (w >= n_long) return;
     const int i = long_item[w];
     const int bb = a.it.beg[i], ee = a.it.end[i], sl = a.it.slot[i];
+    float l[PER];
+    int pr[PER], rn[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int j = min(bb + lane + 64 * u, ee - 1);
+        pr[u] = a.in_pair[j];
+        rn[u] = a.in_run[j];
+    }
     float m = -INFINITY, s = 0.f;
-    for (int j = bb + lane; j < ee; j += 64) {
-        const float z = a.s_src[a.in_pair[j]] + a.s_dst[a.in_run[j]];
-        const float l = z > 0.f ? z : a.slope * z;
-        a.att[j] = l;
-        m = fmaxf(m, l);
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const float z = a.s_src[pr[u]] + a.s_dst[rn[u]];
+        l[u] = bb + lane + 64 * u < ee ? (z > 0.f ? z : a.slope * z) : -INFINITY;
+        m = fmaxf(m, l[u]);
     }
     m = wave_max(m);
-    for (int j = bb + lane; j < ee; j += 64) s += expf(a.att[j] - m);
+#pragma unroll
+    for (int u = 0; u < PER; ++u) s += expf(l[u] - m);
     s = group_sum<64>(s);
     if (sl < 0) {
         const float inv = 1.f / s;
-        for (int j = bb + lane; j < ee; j += 64) a.att[j] = signed_att(a.att[j], m, inv);
-    } else if (lane == 0) {
-        a.part_m[sl] = m;
-        a.part_s[sl] = s;
+#pragma unroll
+        for (int u = 0; u < PER; ++u)
+            if (bb + lane + 64 * u < ee) a.att[bb + lane + 64 * u] = signed_att(l[u], m, inv);
+    } else {
+        // a piece of a cut node: the finish kernel normalises, from the logits
+#pragma unroll
+        for (int u = 0; u < PER; ++u)
+            if (bb + lane + 64 * u < ee) a.att[bb + lane + 64 * u] = l[u];
+        if (lane == 0) {
+            a.part_m[sl] = m;
+            a.part_s[sl] = s;
+        }
     }
 }
 
@@ -405,19 +446,55 @@ struct NodeSumArgs {
     void* dX;             // rows of TO
 };
 
-template <int D, typename TI, typename TO>
+// RUNS: the destination-run term is present (RGAT); without it the kernel only sums pair rows.
+template <int D, typename TI, typename TO, bool RUNS>
 __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
     constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
     const int i = blockIdx.x * IPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
     if (i >= a.it.n) return;
     const TI* __restrict__ dXp = static_cast<const TI*>(a.dXp);
     const int u = a.it.row[i];
+    const int b = a.it.beg[i], e = a.it.end[i];
+    const int qb = RUNS ? a.dst_run_ptr[u] : 0, qe = RUNS ? a.dst_run_ptr[u + 1] : 0;
     float acc[V], acc1[V];
     zero_cols(acc);
     zero_cols(acc1);
+    // The first four pairs and the first four runs of the node are fetched together (a node has
+    // about as many of either as one batch holds), so their two index -> row chains overlap.
+    int pi[4], rr[4];
+    float c[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        pi[t] = b + t < e ? a.srcpair_idx[b + t] : -1;
+        rr[t] = -1;
+        c[t] = 0.f;
+        if (RUNS && qb + t < qe) {
+            rr[t] = a.run_rel[qb + t];
+            c[t] = a.ds_dst[qb + t];
+        }
+    }
     if (a.extra) load_cols(a.extra + (size_t)u * D + cv * V, acc);
-    const int b = a.it.beg[i], e = a.it.end[i];
-    for (int j = b; j < e; j += 4) {
+    {
+        float v[4][V], w[4][V];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (pi[t] >= 0) load_cols(dXp + (size_t)pi[t] * D + cv * V, v[t]);
+            else zero_cols(v[t]);
+            if (RUNS && rr[t] >= 0) load_cols(a.wtp + (size_t)rr[t] * D + cv * V, w[t]);
+            else zero_cols(w[t]);
+        }
+        fma_cols(acc, 1.f, v[0]);
+        fma_cols(acc1, 1.f, v[1]);
+        fma_cols(acc, 1.f, v[2]);
+        fma_cols(acc1, 1.f, v[3]);
+        if (RUNS) {
+            fma_cols(acc, c[0], w[0]);
+            fma_cols(acc1, c[1], w[1]);
+            fma_cols(acc, c[2], w[2]);
+            fma_cols(acc1, c[3], w[3]);
+        }
+    }
+    for (int j = b + 4; j < e; j += 4) {
         float v[4][V];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -429,25 +506,22 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
         fma_cols(acc, 1.f, v[2]);
         fma_cols(acc1, 1.f, v[3]);
     }
-    if (a.ds_dst) {
-        const int qb = a.dst_run_ptr[u], qe = a.dst_run_ptr[u + 1];
-        for (int q = qb; q < qe; q += 4) {
-            float c[4];
-            float v[4][V];
+    for (int q = qb + 4; q < qe; q += 4) {
+        float cq[4];
+        float v[4][V];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                c[t] = 0.f;
-                zero_cols(v[t]);
-                if (q + t < qe) {
-                    c[t] = a.ds_dst[q + t];
-                    load_cols(a.wtp + (size_t)a.run_rel[q + t] * D + cv * V, v[t]);
-                }
+        for (int t = 0; t < 4; ++t) {
+            cq[t] = 0.f;
+            zero_cols(v[t]);
+            if (q + t < qe) {
+                cq[t] = a.ds_dst[q + t];
+                load_cols(a.wtp + (size_t)a.run_rel[q + t] * D + cv * V, v[t]);
             }
-            fma_cols(acc, c[0], v[0]);
-            fma_cols(acc1, c[1], v[1]);
-            fma_cols(acc, c[2], v[2]);
-            fma_cols(acc1, c[3], v[3]);
         }
+        fma_cols(acc, cq[0], v[0]);
+        fma_cols(acc1, cq[1], v[1]);
+        fma_cols(acc, cq[2], v[2]);
+        fma_cols(acc1, cq[3], v[3]);
     }
     fma_cols(acc, 1.f, acc1);
     store_cols(static_cast<TO*>(a.dX) + (size_t)u * D + cv * V, acc);
@@ -637,7 +711,10 @@ rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const f
                   g->idx[RGNN_IDX_DST_RUN_PTR], g->idx[RGNN_IDX_RUN_REL], ds_dst, wtp, extra, dX};
     KernelTimer kt(st, "node_grad_sum");
     const dim3 grid(blocks_for((size_t)g->N, 256 / (D / (in_bf16 ? 8 : 4))));
-    RGNN_DISPATCH_ROWS(D, in_bf16, out_bf16, hipLaunchKernelGGL((node_grad_sum_kernel<DD, TI, TO>), grid, dim3(256), 0, st, a));
+    if (ds_dst)
+        RGNN_DISPATCH_ROWS(D, in_bf16, out_bf16, hipLaunchKernelGGL((node_grad_sum_kernel<DD, TI, TO, true>), grid, dim3(256), 0, st, a));
+    else
+        RGNN_DISPATCH_ROWS(D, in_bf16, out_bf16, hipLaunchKernelGGL((node_grad_sum_kernel<DD, TI, TO, false>), grid, dim3(256), 0, st, a));
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
