@@ -188,6 +188,8 @@ def main():
                     help="synthetic workload id 1..5 (default 3 = the headline RGAT graph the metric is quoted on)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle leg (no cpu_baseline, no parity)")
+    ap.add_argument("--fwd-only", action="store_true",
+                    help="time the forward call alone (inference: no saved buffer is kept)")
     ap.add_argument("--train", action="store_true",
                     help="time a full training step instead: two RGAT layers through the autograd front end, "
                          "log-softmax + NLL loss on 10%% of the nodes, SGD update (RGAT workloads only)")
@@ -207,7 +209,7 @@ def main():
     t0 = time.time()
     c = synth.config(args.config, args.scale)
     N, R, E, d, T, H = c["N"], c["R"], c["E"], c["d_out"], c["T"], c["H"]
-    fwd_only = c["cid"] == 1
+    fwd_only = c["cid"] == 1 or args.fwd_only
     print(f"[bench] generated config {args.config} ({c['layer']}, {c['dtype']}): N={N} T={T} R={R} E={E} d={d} H={H} "
           f"in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 

@@ -23,6 +23,9 @@
  *     `workspace` and `saved` are caller-provided device buffers of at least the
  *     sizes rgnn_workspace_bytes reports; `saved` must be kept unchanged between
  *     a forward call and its backward call, `workspace` is scratch.
+ *   - Inference: a forward call with saved == NULL keeps nothing for a backward
+ *     call; its `workspace` must then hold fwd_workspace + saved bytes (the
+ *     tensors that would have been saved become scratch).
  *   - Weights are stored [type][d_in][d_out] so that y = x W (row vector times
  *     matrix), as in Eq. (rgcn).
  *   - Gradients are overwritten, not accumulated.

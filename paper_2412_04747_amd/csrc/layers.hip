@@ -200,6 +200,14 @@ size_t stage_bytes(const rgnn_graph_t* g, int layer, const rgnn_layer_desc_t* d,
     return s.c.off;
 }
 
+// Inference calls (saved == NULL): the tensors a backward call would need are still intermediates of
+// the forward, and live behind the forward scratch and the staging area in the workspace.
+void* saved_or_scratch(const rgnn_graph_t* g, int layer, const rgnn_layer_desc_t* d, void* saved, void* workspace,
+                       size_t fwd_carved) {
+    if (saved) return saved;
+    return static_cast<char*>(workspace) + align_up(fwd_carved + stage_bytes(g, layer, d, false));
+}
+
 // Forward typed linear  Y[g(i)] / Y[i] = A[g(i)] W[seg].  In bf16 mode it runs on the bf16 matrix
 // cores: an operand whose bf16 form exists (A16 / W16) is used as is, an fp32-only one is split.
 // y16: the output rows are stored as bf16 (width 128 only).
@@ -391,11 +399,13 @@ extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_d
                                        void* workspace, void* stream) {
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGAT));
     if (!X || !W || !w_s || !w_t || !out) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
-    if (!workspace || !saved) RGNN_FAIL(RGNN_EWORKSPACE, "workspace or saved is NULL");
+    if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, K = desc->d_in;
     RgatFwdWs w; RgatSaved sv;
-    Bf16Stage stg(workspace, carve_rgat_fwd(g, desc, workspace, &w), desc->dtype == RGNN_BF16, st);
+    const size_t carved = carve_rgat_fwd(g, desc, workspace, &w);
+    saved = saved_or_scratch(g, RGNN_LAYER_RGAT, desc, saved, workspace, carved);
+    Bf16Stage stg(workspace, carved, desc->dtype == RGNN_BF16, st);
     X = stg.in(X, (size_t)g->N * K);
     W = stg.in(W, (size_t)g->R * K * D);
     w_s = stg.in(w_s, (size_t)g->R * D);
@@ -478,14 +488,16 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
                                       void* stream) {
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_HGT));
     if (!X || !Wk || !Wq || !Wv || !Wo || !Watt || !Wmsg || !out) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
-    if (!workspace || !saved) RGNN_FAIL(RGNN_EWORKSPACE, "workspace or saved is NULL");
+    if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, H = desc->heads;
     HgtFwdWs w; HgtSaved sv;
     const bool bf16 = desc->dtype == RGNN_BF16, h = rows_bf16(desc);
     const void *X16 = bf16 ? X : nullptr, *Wk16 = bf16 ? Wk : nullptr, *Wq16 = bf16 ? Wq : nullptr,
                *Wv16 = bf16 ? Wv : nullptr, *Wo16 = bf16 ? Wo : nullptr;
-    Bf16Stage stg(workspace, carve_hgt_fwd(g, desc, workspace, &w), bf16, st);
+    const size_t carved = carve_hgt_fwd(g, desc, workspace, &w);
+    saved = saved_or_scratch(g, RGNN_LAYER_HGT, desc, saved, workspace, carved);
+    Bf16Stage stg(workspace, carved, bf16, st);
     const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
     // fp32 copies: at width 128 only of the small per-relation parameters (their expansion is an fp32 kernel)
     const float* X32 = !h ? stg.in(X, (size_t)g->N * D) : nullptr;

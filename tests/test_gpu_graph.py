@@ -101,7 +101,10 @@ def test_layer_argument_errors():
             B.rgnn_rgat_fwd(g.handle, bad, x, x, x, x, x, x, x)
         assert e.value.status == status
     with pytest.raises(B.RgnnError) as e:
-        B.rgnn_rgat_fwd(g.handle, B.make_desc(), x, x, x, x, x, None, x)     # saved missing
+        B.rgnn_rgat_fwd(g.handle, B.make_desc(), x, x, x, x, x, x, None)     # workspace missing
+    assert e.value.status == 5
+    with pytest.raises(B.RgnnError) as e:
+        B.rgnn_rgat_bwd(g.handle, B.make_desc(), x, x, x, x, x, None, x, x, x, x, x, x)   # saved missing in a backward call
     assert e.value.status == 5
     with pytest.raises(B.RgnnError) as e:
         B.rgnn_rgat_fwd(g.handle, B.make_desc(), None, x, x, x, x, x, x)     # X missing
@@ -109,3 +112,39 @@ def test_layer_argument_errors():
     with pytest.raises(B.RgnnError) as e:
         B.rgnn_hgt_fwd(g.handle, B.make_desc(heads=8), x, x, x, x, x, x, x, None, x, x, x)   # d/H = 8 unsupported
     assert e.value.status == 2
+
+
+def test_inference_calls_without_saved_buffer():
+    """saved == NULL: the forward keeps nothing for a backward call and takes the room from a workspace of
+    fwd_workspace + saved bytes; the result is bit-identical to the training-mode forward."""
+    import torch
+    from paper_2412_04747_amd import binding as B
+    from paper_2412_04747_amd.harness import Graph, RgatLayer, HgtLayer, _buf, _stream
+    rng, src, dst, rel, ntype = synth.tiny(8, N=700, R=4, E=6000, T=2)
+    dst[:900] = 3
+    g = Graph(700, 4, src, dst, rel, ntype, 2)
+    for dtype, d in (("f32", 64), ("bf16", 128)):
+        rnd = (lambda v: None if v is None else synth.round_to_bf16(v)) if dtype == "bf16" else (lambda v: v)
+        p = {k: rnd(v) for k, v in synth.rgat_params(rng, 700, 4, d, d).items()}
+        L = RgatLayer(g, d, dtype=dtype)
+        L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
+        L.fwd()
+        ref = L.out.clone()
+        f, _, s = B.rgnn_workspace_bytes(g.handle, B.RGNN_LAYER_RGAT, L.desc)
+        ws = _buf(f + s + 256)
+        L.out.zero_()
+        B.rgnn_rgat_fwd(g.handle, L.desc, L.X, L.W, L.w_s, L.w_t, L.out, None, ws, _stream())
+        torch.cuda.synchronize()
+        assert torch.equal(ref, L.out), ("rgat", dtype)
+        q = {k: rnd(v) for k, v in synth.hgt_params(rng, 700, 2, 4, d, 2, with_mu=True).items()}
+        H = HgtLayer(g, d, 2, with_mu=True, dtype=dtype)
+        H.load(q["X"], q["Wk"], q["Wq"], q["Wv"], q["Wo"], q["Watt"], q["Wmsg"], q["mu"], q["dOut"])
+        H.fwd()
+        ref = H.out.clone()
+        f, _, s = B.rgnn_workspace_bytes(g.handle, B.RGNN_LAYER_HGT, H.desc)
+        ws = _buf(f + s + 256)
+        H.out.zero_()
+        B.rgnn_hgt_fwd(g.handle, H.desc, H.X, H.Wk, H.Wq, H.Wv, H.Wo, H.Watt, H.Wmsg, H.mu, H.out, None, ws, _stream())
+        torch.cuda.synchronize()
+        assert torch.equal(ref, H.out), ("hgt", dtype)
+    g.close()
