@@ -190,6 +190,9 @@ def main():
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle leg (no cpu_baseline, no parity)")
     ap.add_argument("--fwd-only", action="store_true",
                     help="time the forward call alone (inference: no saved buffer is kept)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step into a HIP graph and time its replays (no per-kernel breakdown: the "
+                         "timing events cannot be recorded into a graph)")
     ap.add_argument("--train", action="store_true",
                     help="time a full training step instead: two RGAT layers through the autograd front end, "
                          "log-softmax + NLL loss on 10%% of the nodes, SGD update (RGAT workloads only)")
@@ -249,6 +252,32 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        hip_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            with torch.cuda.graph(hip_graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            hip_graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            hip_graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        print(json.dumps({
+            "metric": f"edges/sec for {c['layer'].upper()} layer {'fwd' if fwd_only else 'fwd+bwd'} (HIP graph replay)",
+            "value": E * args.steps / dt, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": dt * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16" if c["dtype"] == "bf16" else "f32", "data": "synthetic",
+            "config": {"workload": f"configs[{args.config - 1}]: {c['layer'].upper()}, {c['dtype']} inputs, N={N}, R={R}, E={E}, d={d}"},
+            "cpu_baseline": cpu}), flush=True)
+        return
     # untimed clean pass, to show what the profiling events cost
     tc = time.perf_counter()
     for _ in range(args.steps):
