@@ -23,8 +23,8 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 
 def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat"):
     """(bound, bytes, flops) one launch of kernel `name` must move / compute.  Gathered rows are
-    counted once per reference (no cache reuse assumed); index and scalar traffic as listed; see
-    DESIGN.md "Kernels and their rooflines".  Row tensors are 4-byte elements, except in the
+    counted once per reference (no cache reuse assumed); index and scalar traffic as listed in the
+    comments below.  Row tensors are 4-byte elements, except in the
     bfloat16 workloads at width 128, where inputs and intermediate rows are 2-byte elements
     (results handed back to the caller stay fp32)."""
     half = bf16 and d == 128
@@ -198,8 +198,8 @@ def main():
                          "log-softmax + NLL loss on 10%% of the nodes, SGD update (RGAT workloads only)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); the multi-GPU sharding is a design note "
-                 "in DESIGN.md, not code.")
+        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); sharding over several GPUs is a design "
+                 "note, not code.")
 
     import numpy as np
     import torch
