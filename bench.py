@@ -87,12 +87,12 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
     return table.get(name)
 
 
-def make_layer(c, g):
+def make_layer(c, g, heads=0):
     """-> (layer object, forward-only?) for workload dict c on graph g."""
     from paper_2412_04747_amd.harness import RgatLayer, RgcnLayer, HgtLayer
     d, dt = c["d_out"], c["dtype"]
     if c["layer"] == "rgat":
-        L = RgatLayer(g, d, c["slope"], dtype=dt)
+        L = RgatLayer(g, d, c["slope"], dtype=dt, heads=max(heads, 1))
         L.load(c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"])
     elif c["layer"] == "rgcn":
         L = RgcnLayer(g, d, c["norm"], "none", False, dtype=dt)
@@ -108,7 +108,11 @@ def run_oracle(c):
     from oracle import layers as O
     N, s, t, r = c["N"], c["src"], c["dst"], c["rel"]
     t0 = time.time()
-    if c["layer"] == "rgat":
+    if c["layer"] == "rgat" and c["H"] > 1:
+        out = O.rgat_heads_fwd(N, s, t, r, c["X"], c["W"], c["w_s"], c["w_t"], c["H"], c["slope"])
+        tf = time.time() - t0; t0 = time.time()
+        want = O.rgat_heads_bwd(N, s, t, r, c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"], c["H"], c["slope"])
+    elif c["layer"] == "rgat":
         out = O.rgat_fwd(N, s, t, r, c["X"], c["W"], c["w_s"], c["w_t"], c["slope"])
         tf = time.time() - t0; t0 = time.time()
         want = O.rgat_bwd(N, s, t, r, c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"], c["slope"])
@@ -188,6 +192,7 @@ def main():
                     help="synthetic workload id 1..5 (default 3 = the headline RGAT graph the metric is quoted on)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle leg (no cpu_baseline, no parity)")
+    ap.add_argument("--heads", type=int, default=0, help="RGAT workloads: number of attention heads (default 1)")
     ap.add_argument("--fwd-only", action="store_true",
                     help="time the forward call alone (inference: no saved buffer is kept)")
     ap.add_argument("--graph", action="store_true",
@@ -211,6 +216,10 @@ def main():
         return train_step_bench(args)
     t0 = time.time()
     c = synth.config(args.config, args.scale)
+    if args.heads > 1:
+        if c["layer"] != "rgat":
+            sys.exit("bench.py --heads: only the RGAT workloads take a head count")
+        c["H"] = args.heads
     N, R, E, d, T, H = c["N"], c["R"], c["E"], c["d_out"], c["T"], c["H"]
     fwd_only = c["cid"] == 1 or args.fwd_only
     print(f"[bench] generated config {args.config} ({c['layer']}, {c['dtype']}): N={N} T={T} R={R} E={E} d={d} H={H} "
@@ -234,7 +243,7 @@ def main():
     P1 = int(g.info.num_single_pairs) if c["layer"] == "rgat" else 0
     print(f"[bench] graph index built in {time.time() - t0:.1f}s: P/E={P / E:.3f} Q/E={Q / E:.3f} "
           f"max in-degree {g.info.max_in_degree} index {g.info.index_bytes / 2**20:.0f} MiB", file=sys.stderr, flush=True)
-    L = make_layer(c, g)
+    L = make_layer(c, g, args.heads)
 
     def step():
         L.fwd()

@@ -82,7 +82,8 @@ typedef struct {
  *              bfloat16, rounded to nearest even from the fp32 accumulators; results then
  *              agree with an fp64 evaluation to a few 1e-3 relative to the largest entry.
  *   d_in,d_out feature widths.  Supported: d_in == d_out in {32, 64, 128}.
- *   heads      HGT: number of heads H (d_out % H == 0, d_out/H in {16, 32, 64}); RGAT: must be 1.
+ *   heads      number of attention heads H of HGT and RGAT (d_out % H == 0; d_out/H in {16, 32, 64},
+ *              any width for single-head RGAT).
  *   slope      RGAT leaky-ReLU negative slope (the derivative at 0 is `slope`).
  *   norm       RGCN: RGNN_NORM_IN_DEGREE_PER_REL divides each message by c_{v,r},
  *              the number of incoming edges of v with relation r (Eq. (rgcn)).
@@ -183,16 +184,20 @@ rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc
                             void* dW, void* dW0, void* workspace, void* stream);
 
 /*
- * Single-head RGAT (Ch.3 listing "attention calculation in a single-headed RGAT
- * model"; the message of an edge is hs):
+ * RGAT (Ch.3 listing "attention calculation in a single-headed RGAT model"; the
+ * message of an edge is hs):
  *   hs = X[u] W[r];  ht = X[v] W[r];  z_e = hs.w_s[r] + ht.w_t[r];
  *   att_e = softmax over ALL incoming edges of v of leakyrelu(z_e);
  *   out[v] = sum_{e in in(v)} att_e hs.
  *   X [N, d_in]; W [R, d_in, d_out]; w_s, w_t [R, d_out]; out [N, d_out].
+ * With desc.heads = H > 1 the d_out columns form H slices of d_out/H; every head
+ * applies the formulas above to its slice of hs, ht, w_s[r], w_t[r] (its own
+ * logit, its own softmax) and the outputs are concatenated; tensor shapes are
+ * unchanged.
  * Nodes without incoming edges get 0.
  * Backward writes dX [N, d_in], dW [R, d_in, d_out], dw_s, dw_t [R, d_out].
  * Layout of `saved` after the forward (exposed for tests): Hs [P, d_out] fp32,
- * the compact messages, then att [E] fp32 in CSR order holding att_e with the
+ * the compact messages, then att [E, H] fp32 in CSR order holding att_e with the
  * sign bit set when z_e <= 0.
  */
 rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* W,

@@ -95,6 +95,39 @@ def rgat_bwd(N, src, dst, rel, X, W, w_s, w_t, dOut, slope=0.2):
     return dict(dX=dX, dW=dW, dw_s=dws, dw_t=dwt)
 
 
+def _head_slices(d_out, heads):
+    if heads < 1 or d_out % heads:
+        raise ValueError("heads must divide d_out")
+    dh = d_out // heads
+    return [slice(h * dh, (h + 1) * dh) for h in range(heads)]
+
+
+def rgat_heads_fwd(N, src, dst, rel, X, W, w_s, w_t, heads, slope=0.2, want_alpha=False):
+    """Multi-head RGAT: head h is the single-head layer of the listing on the column slice h of
+    W, w_s, w_t (its own logits, its own softmax, its own messages); the outputs are concatenated.
+    alpha, z: [E, heads]."""
+    W, w_s, w_t = _f(W), _f(w_s), _f(w_t)
+    out = np.empty((N, W.shape[2]))
+    alpha = np.zeros((len(src), heads))
+    z = np.zeros((len(src), heads))
+    for h, sl in enumerate(_head_slices(W.shape[2], heads)):
+        o, a, zz = rgat_fwd(N, src, dst, rel, X, W[:, :, sl], w_s[:, sl], w_t[:, sl], slope, want_alpha=True)
+        out[:, sl], alpha[:, h], z[:, h] = o, a, zz
+    return (out, alpha, z) if want_alpha else out
+
+
+def rgat_heads_bwd(N, src, dst, rel, X, W, w_s, w_t, dOut, heads, slope=0.2):
+    """Gradients of the concatenation: each head's parameter slices get that head's gradients, dX is
+    the sum over the heads (every head reads the whole X)."""
+    X, W, w_s, w_t, dOut = _f(X), _f(W), _f(w_s), _f(w_t), _f(dOut)
+    g = dict(dX=np.zeros_like(X), dW=np.empty_like(W), dw_s=np.empty_like(w_s), dw_t=np.empty_like(w_t))
+    for sl in _head_slices(W.shape[2], heads):
+        gh = rgat_bwd(N, src, dst, rel, X, W[:, :, sl], w_s[:, sl], w_t[:, sl], dOut[:, sl], slope)
+        g["dX"] += gh["dX"]
+        g["dW"][:, :, sl], g["dw_s"][:, sl], g["dw_t"][:, sl] = gh["dW"], gh["dw_s"], gh["dw_t"]
+    return g
+
+
 def hgt_fwd(N, src, dst, rel, ntype, X, Wk, Wq, Wv, Wo, Watt, Wmsg, mu=None, want_alpha=False):
     src, dst, rel, ntype = _i(src), _i(dst), _i(rel), _i(ntype)
     X, Wk, Wq, Wv, Wo, Watt, Wmsg, mu = map(_f, (X, Wk, Wq, Wv, Wo, Watt, Wmsg, mu))

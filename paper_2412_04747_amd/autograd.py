@@ -44,11 +44,11 @@ def _f32(t):
 
 class _Rgat(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, graph, slope, X, W, w_s, w_t):
+    def forward(ctx, graph, slope, heads, X, W, w_s, w_t):
         X, W, w_s, w_t = _f32(X), _f32(W), _f32(w_s), _f32(w_t)
         d = W.shape[-1]
-        desc = B.make_desc(B.RGNN_F32, d, d, 1, slope)
-        ws, s = _bufs(graph, B.RGNN_LAYER_RGAT, desc, (d,))
+        desc = B.make_desc(B.RGNN_F32, d, d, heads, slope)
+        ws, s = _bufs(graph, B.RGNN_LAYER_RGAT, desc, (d, heads))
         out = torch.empty(graph.N, d, device=X.device)
         saved = _buf(s)
         B.rgnn_rgat_fwd(graph.handle, desc, X, W, w_s, w_t, out, saved, ws, _stream())
@@ -63,7 +63,7 @@ class _Rgat(torch.autograd.Function):
         dX, dW, dws, dwt = (torch.empty_like(t) for t in (X, W, w_s, w_t))
         B.rgnn_rgat_bwd(ctx.graph.handle, ctx.desc, X, W, w_s, w_t, out, ctx.saved_buf, dOut, dX, dW, dws, dwt, ctx.ws,
                         _stream())
-        return None, None, dX, dW, dws, dwt
+        return None, None, None, dX, dW, dws, dwt
 
 
 class _Rgcn(torch.autograd.Function):
@@ -118,9 +118,10 @@ class _Hgt(torch.autograd.Function):
         return (None, *g, dmu)
 
 
-def rgat(graph, X, W, w_s, w_t, slope=0.2):
-    """Single-head RGAT layer (listing of the RGAT layer in the thesis): out [N, d]."""
-    return _Rgat.apply(graph, float(slope), X, W, w_s, w_t)
+def rgat(graph, X, W, w_s, w_t, slope=0.2, heads=1):
+    """RGAT layer (listing of the single-headed RGAT layer in the thesis; with heads > 1 each head
+    works on its slice of the d columns): out [N, d]."""
+    return _Rgat.apply(graph, float(slope), int(heads), X, W, w_s, w_t)
 
 
 def rgcn(graph, X, W, W0=None, norm="in_degree_per_rel", act="none"):
@@ -138,13 +139,13 @@ def _param(*shape, fan_in):
 
 
 class RgatConv(torch.nn.Module):
-    def __init__(self, num_rels, d, slope=0.2):
+    def __init__(self, num_rels, d, slope=0.2, heads=1):
         super().__init__()
-        self.slope = slope
+        self.slope, self.heads = slope, heads
         self.W, self.w_s, self.w_t = _param(num_rels, d, d, fan_in=d), _param(num_rels, d, fan_in=d), _param(num_rels, d, fan_in=d)
 
     def forward(self, graph, X):
-        return rgat(graph, X, self.W, self.w_s, self.w_t, self.slope)
+        return rgat(graph, X, self.W, self.w_s, self.w_t, self.slope, self.heads)
 
 
 class RgcnConv(torch.nn.Module):

@@ -117,6 +117,7 @@ static rgnn_status_t build(rgnn_graph* g, int format, const int32_t* a, const in
     build_items(U, g->pair_items, out_ptr, item_cut(g->E));
     build_items(U, g->relrun_items, relrun_ptr, item_cut(g->E));
     build_items(U, g->pair_items_multi, out_ptr, item_cut(g->E), 2);
+    build_items(U, g->relpair_items, pair_ptr, item_cut(g->P));
     build_items(U, g->srcpair_items, srcpair_ptr, 1 << 30);
     build_long(U, g->long_runs, run_ptr);
     build_long(U, g->long_pairs, out_ptr);

@@ -92,8 +92,13 @@ __global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, co
 // Per-head softmax of att[e][h] (holding logits on entry) over each destination's edges.
 // Short nodes: one lane per (node, head).  Long items and pieces of cut nodes: one wavefront
 // per item, heads in turn; pieces store (max, sum) per head for the finish kernel.
+// SIGNED: the weight of an edge whose logit is <= 0 is stored negated (its magnitude is the weight).
+__device__ __forceinline__ float soft_out(float l, float m, float inv, bool sgn) {
+    const float a = expf(l - m) * inv;
+    return sgn && !(l > 0.f) ? -a : a;
+}
 __global__ __launch_bounds__(256) void hgt_softmax_kernel(int N, int H, const int32_t* __restrict__ in_ptr,
-                                                          float* __restrict__ att) {
+                                                          float* __restrict__ att, int sgn) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= N * H) return;
     const int v = t / H, h = t % H;
@@ -118,11 +123,11 @@ __global__ __launch_bounds__(256) void hgt_softmax_kernel(int N, int H, const in
     const float inv = 1.f / s;
 #pragma unroll
     for (int k = 0; k < kSerialMax; ++k)
-        if (k < len) att[(size_t)(b + k) * H + h] = expf(l[k] - m) * inv;
+        if (k < len) att[(size_t)(b + k) * H + h] = soft_out(l[k], m, inv, sgn);
 }
 __global__ __launch_bounds__(256) void hgt_softmax_long_kernel(Items it, int n_long, const int32_t* __restrict__ long_item,
                                                                int H, float* __restrict__ att, float* __restrict__ part_m,
-                                                               float* __restrict__ part_s) {
+                                                               float* __restrict__ part_s, int sgn) {
     constexpr int PER = kItemMax / 64;     // an item has at most kItemMax entries
     const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
     if (w >= n_long) return;
@@ -146,7 +151,7 @@ __global__ __launch_bounds__(256) void hgt_softmax_long_kernel(Items it, int n_l
 #pragma unroll
             for (int u = 0; u < PER; ++u) {
                 const int j = bb + lane + 64 * u;
-                if (j < ee) att[(size_t)j * H + h] = expf(l[u] - m) * inv;
+                if (j < ee) att[(size_t)j * H + h] = soft_out(l[u], m, inv, sgn);
             }
         } else if (lane == 0) {
             part_m[(size_t)sl * H + h] = m;
@@ -158,7 +163,7 @@ __global__ void hgt_softmax_finish_kernel(int num_partials, const int32_t* __res
                                           const int32_t* __restrict__ part_split,
                                           const int32_t* __restrict__ split_ptr, Items it, int H,
                                           const float* __restrict__ part_m, const float* __restrict__ part_s,
-                                          float* __restrict__ att) {
+                                          float* __restrict__ att, int sgn) {
     const int t = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
     if (t >= num_partials) return;
     const int sp = part_split[t];
@@ -173,7 +178,7 @@ __global__ void hgt_softmax_finish_kernel(int num_partials, const int32_t* __res
         s = group_sum<64>(s);
         const float inv = 1.f / s;
         for (int j = it.beg[item] + lane; j < it.end[item]; j += 64)
-            att[(size_t)j * H + h] = expf(att[(size_t)j * H + h] - m) * inv;
+            att[(size_t)j * H + h] = soft_out(att[(size_t)j * H + h], m, inv, sgn);
     }
 }
 
@@ -183,7 +188,8 @@ template <int D, typename TI>
 __global__ __launch_bounds__(256) void hgt_edge_dot_bwd_kernel(Items it, int H, const int32_t* __restrict__ in_pair,
                                                                const float* __restrict__ att,
                                                                const TI* __restrict__ M, const TI* __restrict__ dZ,
-                                                               const TI* __restrict__ Z, float* __restrict__ dl) {
+                                                               const TI* __restrict__ Z, float* __restrict__ dl,
+                                                               float slope) {
     constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
     const int i = blockIdx.x * IPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
     if (i >= it.n) return;
@@ -210,7 +216,10 @@ __global__ __launch_bounds__(256) void hgt_edge_dot_bwd_kernel(Items it, int H, 
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const float g = group_sum_dyn(dot_cols(gz, mm[u]), lph);
-            if (cv % lph == 0 && j + u < e) dl[(size_t)(j + u) * H + head] = a[u] * (g - gbar);
+            // slope >= 0: att is signed (negative where the leaky-ReLU took its sloped branch) and the
+            // result is the gradient of the pre-activation logit
+            const float w = slope >= 0.f ? fabsf(a[u]) * (a[u] < 0.f ? slope : 1.f) : a[u];
+            if (cv % lph == 0 && j + u < e) dl[(size_t)(j + u) * H + head] = w * (g - gbar);
         }
     }
 }
@@ -255,17 +264,18 @@ rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const void* Ka, 
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
-rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st) {
+rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st,
+                          int signed_out) {
     const ItemList& L = g->dst_items;
     if (g->E == 0) return RGNN_OK;
     {
         KernelTimer kt(st, "hgt_softmax");
         hipLaunchKernelGGL(hgt_softmax_kernel, dim3(blocks_for((size_t)g->N * H, 256)), dim3(256), 0, st, (int)g->N, H,
-                           g->idx[RGNN_IDX_IN_PTR], att);
+                           g->idx[RGNN_IDX_IN_PTR], att, signed_out);
         RGNN_CHECK_LAUNCH();
         if (L.num_long > 0) {
             hipLaunchKernelGGL(hgt_softmax_long_kernel, dim3(blocks_for((size_t)L.num_long * 64, 256)), dim3(256), 0, st,
-                               dev_items(L), L.num_long, L.long_item, H, att, part_m, part_s);
+                               dev_items(L), L.num_long, L.long_item, H, att, part_m, part_s, signed_out);
             RGNN_CHECK_LAUNCH();
         }
     }
@@ -273,13 +283,13 @@ rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m,
         KernelTimer kt(st, "hgt_softmax.finish");
         hipLaunchKernelGGL(hgt_softmax_finish_kernel, dim3(blocks_for((size_t)L.num_partials * 64, 256)), dim3(256), 0,
                            st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), H, part_m, part_s,
-                           att);
+                           att, signed_out);
         RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;
 }
 rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* att, const void* M, const void* dZ,
-                               const void* Z, float* dl, hipStream_t st, int rows_bf16) {
+                               const void* Z, float* dl, hipStream_t st, int rows_bf16, float slope) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
     KernelTimer kt(st, "hgt_edge_dot_bwd");
@@ -287,12 +297,12 @@ rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* a
         if (D != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "bf16 rows need width 128, got %d", D);
         hipLaunchKernelGGL((hgt_edge_dot_bwd_kernel<128, bf16_t>), dim3(blocks_for(L.num_items, 256 / (128 / 8))), dim3(256), 0,
                            st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], att, static_cast<const bf16_t*>(M),
-                           static_cast<const bf16_t*>(dZ), static_cast<const bf16_t*>(Z), dl);
+                           static_cast<const bf16_t*>(dZ), static_cast<const bf16_t*>(Z), dl, slope);
     } else {
         RGNN_DISPATCH_D(D, hipLaunchKernelGGL((hgt_edge_dot_bwd_kernel<DD, float>), dim3(blocks_for(L.num_items, 256 / (DD / 4))),
                                               dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], att,
                                               static_cast<const float*>(M), static_cast<const float*>(dZ),
-                                              static_cast<const float*>(Z), dl));
+                                              static_cast<const float*>(Z), dl, slope));
     }
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;

@@ -57,7 +57,12 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
     if (d->dtype != RGNN_F32 && d->dtype != RGNN_BF16) RGNN_FAIL(RGNN_EINVAL, "unknown dtype %d", d->dtype);
     if (d->d_in != d->d_out || (d->d_in != 32 && d->d_in != 64 && d->d_in != 128))
         RGNN_FAIL(RGNN_EUNSUPPORTED, "need d_in == d_out in {32, 64, 128}, got %d -> %d", d->d_in, d->d_out);
-    if (layer == RGNN_LAYER_RGAT && d->heads != 1) RGNN_FAIL(RGNN_EUNSUPPORTED, "RGAT supports heads == 1 only");
+    if (layer == RGNN_LAYER_RGAT) {
+        if (d->heads < 1 || d->d_out % d->heads != 0) RGNN_FAIL(RGNN_EINVAL, "heads must divide d_out");
+        const int dh = d->d_out / d->heads;
+        if (d->heads > 1 && dh != 16 && dh != 32 && dh != 64)
+            RGNN_FAIL(RGNN_EUNSUPPORTED, "multi-head RGAT needs d_out / heads in {16, 32, 64}, got %d", dh);
+    }
     if (layer == RGNN_LAYER_RGAT && !(d->slope >= 0.f && d->slope <= 1.f))
         RGNN_FAIL(RGNN_EINVAL, "leaky-ReLU slope must be in [0, 1]");
     if (layer == RGNN_LAYER_RGCN) {
@@ -84,33 +89,36 @@ struct RgatBwdWs {
 size_t carve_rgat_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatSaved* s) {
     Carver c(base);
     s->Hs = c.take<float>((size_t)g->P * d->d_out);
-    s->att = c.take<float>((size_t)g->E);
+    s->att = c.take<float>((size_t)g->E * d->heads);
     return c.off;
 }
 size_t carve_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatFwdWs* w) {
     Carver c(base);
-    w->wtp = c.take<float>((size_t)g->R * d->d_in);
-    w->s_src = c.take<float>((size_t)g->P);
-    w->s_dst = c.take<float>((size_t)g->Q);
-    w->part_m = c.take<float>((size_t)g->dst_items.num_partials);
-    w->part_s = c.take<float>((size_t)g->dst_items.num_partials);
+    const size_t H = d->heads;
+    w->wtp = c.take<float>(H * g->R * d->d_in);
+    w->s_src = c.take<float>((size_t)g->P * H);
+    w->s_dst = c.take<float>((size_t)g->Q * H);
+    w->part_m = c.take<float>((size_t)g->dst_items.num_partials * H);
+    w->part_s = c.take<float>((size_t)g->dst_items.num_partials * H);
     w->partial = c.take<float>((size_t)g->dst_items.num_partials * d->d_out);
     return c.off;
 }
 size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatBwdWs* w) {
     Carver c(base);
-    w->wtp = c.take<float>((size_t)g->R * d->d_in);
+    const size_t H = d->heads;
+    w->wtp = c.take<float>(H * g->R * d->d_in);
     w->wsp = c.take<float>((size_t)g->R * d->d_in);
-    w->adz = c.take<float>((size_t)g->E * 2);
-    w->ds_dst = c.take<float>((size_t)g->Q);
-    w->ds_src = c.take<float>((size_t)g->P);
+    w->adz = c.take<float>((size_t)g->E * std::max<size_t>(2, H));   // (att, dz) pairs, or dz per head
+    w->ds_dst = c.take<float>((size_t)g->Q * H);
+    w->ds_src = c.take<float>((size_t)g->P * H);
     w->G = c.take<float>((size_t)g->P * d->d_out);
     w->dXp = c.take<float>((size_t)g->P * d->d_in);
     w->A = c.take<float>((size_t)g->R * d->d_in);
-    w->U = c.take<float>((size_t)g->R * d->d_in);
+    w->U = c.take<float>(H * g->R * d->d_in);
     w->tl_part = c.take<float>(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles));
-    w->partial = c.take<float>(std::max((size_t)g->pair_items.num_partials * d->d_out,
-                                        (size_t)g->relrun_items.num_partials * d->d_in));
+    const size_t parts = std::max<size_t>({(size_t)g->pair_items.num_partials, (size_t)g->relrun_items.num_partials,
+                                           (size_t)g->relpair_items.num_partials});
+    w->partial = c.take<float>(parts * std::max(d->d_in, d->d_out));
     return c.off;
 }
 
@@ -412,6 +420,21 @@ extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     w_t = stg.in(w_t, (size_t)g->R * D);
     RGNN_TRY(stg.status);
     carve_rgat_saved(g, desc, saved, &sv);
+    if (desc->heads > 1) {
+        // Multi-head: the same steps with one logit, one softmax and one weight per (edge, head).
+        const int H = desc->heads;
+        const float *Xf = static_cast<const float*>(X), *Wf = static_cast<const float*>(W);
+        TypedLinearArgs a{};
+        a.tiles = &g->pair_tiles; a.X = Xf; a.gather = g->idx[RGNN_IDX_PAIR_SRC]; a.W = Wf; a.Y = sv.Hs;
+        RGNN_TRY(typed_linear_fwd(K, D, a, st));
+        RGNN_TRY(head_dot_rows(g->P, D, H, sv.Hs, g->idx[RGNN_IDX_PAIR_REL], static_cast<const float*>(w_s), w.s_src, st));
+        RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, static_cast<const float*>(w_t), w.wtp, st));
+        RGNN_TRY(run_logit_heads(g, K, H, Xf, w.wtp, w.s_dst, st));
+        RGNN_TRY(edge_logit_heads(g, H, w.s_src, w.s_dst, desc->slope, sv.att, st));
+        RGNN_TRY(hgt_softmax(g, H, sv.att, w.part_m, w.part_s, st, 1));
+        return gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, H, 1, sv.Hs, out, w.partial, st, 0,
+                          "aggregate_fwd", "aggregate_fwd.combine", H);
+    }
     // 1. compact messages and the source half of the logit:
     //    Hs[p] = X[pair_src[p]] W[r];  s_src[p] = Hs[p] . w_s[r]
     TypedLinearArgs a{};
@@ -451,6 +474,38 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     const float* Xf = static_cast<const float*>(X);
     const float* Wf = static_cast<const float*>(W);
     const float* dO = static_cast<const float*>(dOut);
+    if (desc->heads > 1) {
+        const int H = desc->heads;
+        const float *ws = static_cast<const float*>(w_s), *wt = static_cast<const float*>(w_t);
+        float* dz = w.adz;                                   // [E][H]
+        // 1. dz[e][h] = |att| (dOut[v].Hs[pair_e] - dOut[v].out[v])_h * (z > 0 ? 1 : slope)
+        RGNN_TRY(hgt_edge_dot_bwd(g, D, H, sv.att, sv.Hs, dO, out, dz, st, 0, desc->slope));
+        // 2. per-head sums over runs and over pairs
+        RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], g->long_runs, nullptr, dz, H, 0, w.ds_dst, st,
+                                    "ds_dst_sum", 0, H));
+        RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], dz, H, 0,
+                                    w.ds_src, st, "ds_src_sum", 0, H));
+        // 3. dHs[p] = sum_{e in out(p)} |att_e| dOut[dst_e] (per head)  +  ds_src[p][h] w_s[r] (per head)
+        RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, sv.att, H, 1, dO, w.G,
+                            w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", H));
+        RGNN_TRY(add_head_rank1(g->P, D, H, w.ds_src, g->idx[RGNN_IDX_PAIR_REL], ws, w.G, st));
+        // 4. dXp = dHs W^T, dW = sum X^T dHs
+        TypedLinearBwdArgs b{};
+        b.tiles = &g->pair_tiles; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
+        b.dW = static_cast<float*>(dW); b.part = w.tl_part;
+        RGNN_TRY(typed_linear_bwd(K, D, b, st));
+        // 5. dw_s[r] = sum over r's pairs of ds_src[p][h] Hs[p] (per head; the pair rows are in relation order)
+        RGNN_TRY(gather_sum(g->relpair_items, D, nullptr, nullptr, 0, w.ds_src, H, 0, sv.Hs, dw_s, w.partial, st, 2,
+                            "src_vec_grad", "src_vec_grad.combine", H));
+        // 6. U[h][r] = sum over r's runs of ds_dst[q][h] X[run_dst[q]];  dw_t and the w_t part of dW from it
+        for (int h = 0; h < H; ++h)
+            RGNN_TRY(gather_sum(g->relrun_items, K, g->idx[RGNN_IDX_RELRUN_IDX], g->idx[RGNN_IDX_RUN_DST], 1, w.ds_dst + h, H, 0,
+                                Xf, w.U + (size_t)h * g->R * K, w.partial, st, 2, "dst_side_wgrad", "dst_side_wgrad.combine"));
+        RGNN_TRY(rgat_heads_param_finish(g->R, K, D, H, Wf, wt, w.U, static_cast<float*>(dW), static_cast<float*>(dw_t), st));
+        // 7. dX[u] = sum over u's pairs of dXp + sum over u's runs and heads of ds_dst[q][h] (W[r] w_t[r])_h
+        RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, wt, w.wtp, st));
+        return node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, nullptr, dX, st, 0, 0, H);
+    }
     // 1. per CSR edge: (att_e, dz_e); for single-edge pairs also G[p] and ds_src[p]
     RGNN_TRY(edge_dot_bwd(g, D, sv.att, sv.Hs, dO, static_cast<const float*>(out), desc->slope, w.adz, w.G, w.ds_src, st));
     // 2. ds_dst[q] = sum over the run's edges of dz;  ds_src[p] = sum over the pair's edges of dz

@@ -1,0 +1,167 @@
+// Pieces of multi-head RGAT that the single-head path does not have.  With H heads the d_out
+// columns split into H slices of d_out / H; head h of an edge uses the slices of hs, ht, w_s[r]
+// and w_t[r] (the single-head formulas of the thesis' RGAT listing, applied per slice, outputs
+// concatenated).  The rest of the multi-head path reuses the typed-linear kernels, the per-head
+// softmax / edge-dot kernels of the HGT layer and the gather-sum with one coefficient per head.
+#include "rgnn_internal.h"
+#include "traversal.h"
+#include "device_utils.h"
+
+namespace rgnn {
+
+// wv[h][r][k] = sum_{n in head h} W[r][k][n] * w[r][n]   (linear operator reordering, per head)
+__global__ void fold_weight_heads_kernel(const float* __restrict__ W, const float* __restrict__ w, int R, int kd, int nd,
+                                         int H, float* __restrict__ wv) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;   // (h, r, k)
+    if (i >= H * R * kd) return;
+    const int dh = nd / H;
+    const int h = i / (R * kd), rk = i % (R * kd), r = rk / kd;
+    const float* Wr = W + (size_t)rk * nd + h * dh;
+    const float* wr = w + (size_t)r * nd + h * dh;
+    float s = 0.f;
+    for (int n = 0; n < dh; ++n) s += Wr[n] * wr[n];
+    wv[i] = s;
+}
+
+// s[i][h] = rows[i][head h] . vec[seg[i]][head h]; one lane group per row
+template <int D>
+__global__ __launch_bounds__(256) void head_dot_rows_kernel(int64_t n, int H, const float* __restrict__ rows,
+                                                            const int32_t* __restrict__ seg,
+                                                            const float* __restrict__ vec, float* __restrict__ s) {
+    constexpr int LPR = D / 4;
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPR;
+    const int c4 = threadIdx.x % LPR;
+    if (i >= n) return;
+    const int lph = LPR / H;
+    const float4 x = *reinterpret_cast<const float4*>(rows + (size_t)i * D + c4 * 4);
+    const float4 v = *reinterpret_cast<const float4*>(vec + (size_t)seg[i] * D + c4 * 4);
+    const float t = group_sum_dyn(dot4(x, v), lph);
+    if (c4 % lph == 0) s[(size_t)i * H + c4 / lph] = t;
+}
+
+// s_dst[q][h] = X[run_dst[q]] . wtp[h][run_rel[q]]: the run's X row is read once, one full-width dot per head
+template <int D>
+__global__ __launch_bounds__(256) void run_logit_heads_kernel(int Q, int R, int H, const int32_t* __restrict__ run_dst,
+                                                              const int32_t* __restrict__ run_rel,
+                                                              const float* __restrict__ X, const float* __restrict__ wtp,
+                                                              float* __restrict__ s_dst) {
+    constexpr int LPR = D / 4;
+    const int q = (blockIdx.x * blockDim.x + threadIdx.x) / LPR, c4 = threadIdx.x % LPR;
+    if (q >= Q) return;
+    const float4 x = *reinterpret_cast<const float4*>(X + (size_t)run_dst[q] * D + c4 * 4);
+    const int r = run_rel[q];
+    for (int h = 0; h < H; ++h) {
+        const float4 w = *reinterpret_cast<const float4*>(wtp + ((size_t)h * R + r) * D + c4 * 4);
+        const float t = group_sum<LPR>(dot4(x, w));
+        if (c4 == 0) s_dst[(size_t)q * H + h] = t;
+    }
+}
+
+// att[e][h] = leakyrelu(s_src[pair_e][h] + s_dst[run_e][h])   (the logits; the softmax follows)
+__global__ void edge_logit_heads_kernel(int64_t total, int H, const int32_t* __restrict__ in_pair,
+                                        const int32_t* __restrict__ in_run, const float* __restrict__ s_src,
+                                        const float* __restrict__ s_dst, float slope, float* __restrict__ att) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int64_t e = i / H;
+    const int h = (int)(i % H);
+    const float z = s_src[(size_t)in_pair[e] * H + h] + s_dst[(size_t)in_run[e] * H + h];
+    att[i] = z > 0.f ? z : slope * z;
+}
+
+// rows[i][head h] += coef[i][h] * vec[seg[i]][head h]
+template <int D>
+__global__ __launch_bounds__(256) void add_head_rank1_kernel(int64_t n, int H, const float* __restrict__ coef,
+                                                             const int32_t* __restrict__ seg,
+                                                             const float* __restrict__ vec, float* __restrict__ rows) {
+    constexpr int LPR = D / 4;
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPR;
+    const int c4 = threadIdx.x % LPR;
+    if (i >= n) return;
+    const float c = coef[(size_t)i * H + c4 / (LPR / H)];
+    float4 x = *reinterpret_cast<const float4*>(rows + (size_t)i * D + c4 * 4);
+    const float4 v = *reinterpret_cast<const float4*>(vec + (size_t)seg[i] * D + c4 * 4);
+    fma4(x, c, v);
+    *reinterpret_cast<float4*>(rows + (size_t)i * D + c4 * 4) = x;
+}
+
+// Per relation r, with U[h][r] = sum_q ds_dst[q][h] X[dst_q] and h(n) the head of column n:
+//   dw_t[r][n] = sum_k U[h(n)][r][k] W[r][k][n];   dW[r][k][n] += U[h(n)][r][k] * w_t[r][n]
+__global__ void rgat_heads_param_finish_kernel(int R, int kd, int nd, int H, const float* __restrict__ W,
+                                               const float* __restrict__ w_t, const float* __restrict__ U,
+                                               float* __restrict__ dW, float* __restrict__ dw_t) {
+    const int r = blockIdx.x, dh = nd / H;
+    const float* Wr = W + (size_t)r * kd * nd;
+    for (int n = threadIdx.x; n < nd; n += blockDim.x) {
+        const float* Ur = U + ((size_t)(n / dh) * R + r) * kd;
+        float t = 0.f;
+        for (int k = 0; k < kd; ++k) t += Ur[k] * Wr[k * nd + n];
+        dw_t[(size_t)r * nd + n] = t;
+    }
+    for (int i = threadIdx.x; i < kd * nd; i += blockDim.x) {
+        const int k = i / nd, n = i % nd;
+        dW[(size_t)r * kd * nd + i] += U[((size_t)(n / dh) * R + r) * kd + k] * w_t[(size_t)r * nd + n];
+    }
+}
+
+// ---------------------------------------------------------------------------------------- launchers
+
+rgnn_status_t fold_weight_heads(int R, int kd, int nd, int H, const float* W, const float* w, float* wv, hipStream_t st) {
+    KernelTimer kt(st, "fold_weight");
+    hipLaunchKernelGGL(fold_weight_heads_kernel, dim3(blocks_for((size_t)H * R * kd, 256)), dim3(256), 0, st, W, w, R, kd,
+                       nd, H, wv);
+    RGNN_CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t head_dot_rows(int64_t n, int D, int H, const float* rows, const int32_t* seg, const float* vec, float* s,
+                            hipStream_t st) {
+    if (n == 0) return RGNN_OK;
+    KernelTimer kt(st, "pair_logit");
+    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(head_dot_rows_kernel<DD>, dim3(blocks_for((size_t)n * (DD / 4), 256)), dim3(256), 0, st,
+                                          n, H, rows, seg, vec, s));
+    RGNN_CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t run_logit_heads(const rgnn_graph* g, int D, int H, const float* X, const float* wtp, float* s_dst,
+                              hipStream_t st) {
+    if (g->Q == 0) return RGNN_OK;
+    KernelTimer kt(st, "run_logit");
+    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(run_logit_heads_kernel<DD>, dim3(blocks_for((size_t)g->Q * (DD / 4), 256)), dim3(256),
+                                          0, st, (int)g->Q, (int)g->R, H, g->idx[RGNN_IDX_RUN_DST], g->idx[RGNN_IDX_RUN_REL], X,
+                                          wtp, s_dst));
+    RGNN_CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t edge_logit_heads(const rgnn_graph* g, int H, const float* s_src, const float* s_dst, float slope, float* att,
+                               hipStream_t st) {
+    if (g->E == 0) return RGNN_OK;
+    KernelTimer kt(st, "edge_logit");
+    const int64_t total = g->E * H;
+    hipLaunchKernelGGL(edge_logit_heads_kernel, dim3(blocks_for((size_t)total, 256)), dim3(256), 0, st, total, H,
+                       g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN], s_src, s_dst, slope, att);
+    RGNN_CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t add_head_rank1(int64_t n, int D, int H, const float* coef, const int32_t* seg, const float* vec, float* rows,
+                             hipStream_t st) {
+    if (n == 0) return RGNN_OK;
+    KernelTimer kt(st, "add_src_logit_grad");
+    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(add_head_rank1_kernel<DD>, dim3(blocks_for((size_t)n * (DD / 4), 256)), dim3(256), 0,
+                                          st, n, H, coef, seg, vec, rows));
+    RGNN_CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+rgnn_status_t rgat_heads_param_finish(int R, int kd, int nd, int H, const float* W, const float* w_t, const float* U,
+                                      float* dW, float* dw_t, hipStream_t st) {
+    KernelTimer kt(st, "rgat_param_finish");
+    hipLaunchKernelGGL(rgat_heads_param_finish_kernel, dim3(R), dim3(256), 0, st, R, kd, nd, H, W, w_t, U, dW, dw_t);
+    RGNN_CHECK_LAUNCH();
+    return RGNN_OK;
+}
+
+}  // namespace rgnn

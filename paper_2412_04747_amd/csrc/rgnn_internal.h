@@ -114,6 +114,7 @@ struct rgnn_graph {
     rgnn::ItemList srcpair_items;          // pairs by source node (never cut)
     int32_t* in_pair_tag = nullptr;        // [E] in_pair with the top bit set when the pair has a single edge
     rgnn::ItemList relrun_items;           // runs by relation
+    rgnn::ItemList relpair_items;          // pairs by relation (rows of the compact tensors are already in this order)
     rgnn::LongList long_runs;              // runs (run_ptr) too long for one lane
     rgnn::LongList long_pairs;             // pairs (out_ptr) too long for one lane
     std::vector<void*> allocs;             // every device allocation, for destroy

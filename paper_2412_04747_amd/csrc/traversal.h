@@ -7,7 +7,8 @@ namespace rgnn {
 rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st);
 rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st);
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
-                                 int stride, int off, float* out, hipStream_t st, const char* label, int min_len = 0);
+                                 int stride, int off, float* out, hipStream_t st, const char* label, int min_len = 0,
+                                 int heads = 1);
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
                            float* part_m, float* part_s, hipStream_t st);
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
@@ -17,7 +18,7 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
                            const float* out, float slope, float* adz, float* G, float* ds_src, hipStream_t st);
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const float* ds_dst, const float* wtp,
-                            const float* extra, void* dX, hipStream_t st, int in_bf16 = 0, int out_bf16 = 0);
+                            const float* extra, void* dX, hipStream_t st, int in_bf16 = 0, int out_bf16 = 0, int heads = 1);
 rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const float* w_s, const float* w_t,
                                 const float* A, const float* U, float* dW, float* dw_s, float* dw_t, hipStream_t st);
 // hgt.hip
@@ -26,9 +27,24 @@ rgnn_status_t hgt_extract(int R, int d, int H, const float* dWbd, const float* W
                           float* dmu, hipStream_t st);
 rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const void* Ka, const void* Q, float* logit,
                              hipStream_t st, int rows_bf16 = 0);
-rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st);
+// signed_out: att = -softmax where the logit is <= 0 (RGAT: the sign bit keeps the leaky-ReLU branch)
+rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st,
+                          int signed_out = 0);
+// slope < 0: dl = att (g - gbar).  slope >= 0 (RGAT, signed att): dl = |att| (g - gbar) * (att < 0 ? slope : 1)
 rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* att, const void* M, const void* dZ,
-                               const void* Z, float* dl, hipStream_t st, int rows_bf16 = 0);
+                               const void* Z, float* dl, hipStream_t st, int rows_bf16 = 0, float slope = -1.f);
+// rgat_heads.hip: pieces of multi-head RGAT
+rgnn_status_t fold_weight_heads(int R, int kd, int nd, int H, const float* W, const float* w, float* wv, hipStream_t st);
+rgnn_status_t head_dot_rows(int64_t n, int D, int H, const float* rows, const int32_t* seg, const float* vec, float* s,
+                            hipStream_t st);
+rgnn_status_t run_logit_heads(const rgnn_graph* g, int D, int H, const float* X, const float* wtp, float* s_dst,
+                              hipStream_t st);
+rgnn_status_t edge_logit_heads(const rgnn_graph* g, int H, const float* s_src, const float* s_dst, float slope, float* att,
+                               hipStream_t st);
+rgnn_status_t add_head_rank1(int64_t n, int D, int H, const float* coef, const int32_t* seg, const float* vec, float* rows,
+                             hipStream_t st);
+rgnn_status_t rgat_heads_param_finish(int R, int kd, int nd, int H, const float* W, const float* w_t, const float* U,
+                                      float* dW, float* dw_t, hipStream_t st);
 rgnn_status_t add3(size_t n, const float* a, const float* b, const float* c, float* out, hipStream_t st);
 
 rgnn_status_t widen_bf16(size_t n, const uint16_t* src, float* dst, hipStream_t st);

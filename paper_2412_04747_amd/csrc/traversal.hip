@@ -55,42 +55,43 @@ __global__ void run_logit_kernel(int Q, const int32_t* __restrict__ run_dst, con
     }
 }
 
-// out[i] = sum_{j in [ptr[i], ptr[i+1])} val[(via ? via[j] : j) * stride + off].
-// One lane per segment of at most kSerialMax entries; the longer ones (listed by the graph
-// index) get one wavefront each in a second kernel.
-__global__ void segment_scalar_sum_kernel(int n, const int32_t* __restrict__ ptr, const int32_t* __restrict__ via,
-                                          const float* __restrict__ val, int stride, int off, int min_len,
-                                          float* __restrict__ out) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+// out[i * heads + h] = sum_{j in [ptr[i], ptr[i+1])} val[(via ? via[j] : j) * stride + off + h],  h < heads.
+// One lane per (segment, head) for segments of at most kSerialMax entries; the longer ones (listed
+// by the graph index) get a workgroup per (segment, head) in a second kernel.
+__global__ void segment_scalar_sum_kernel(int n, int heads, const int32_t* __restrict__ ptr,
+                                          const int32_t* __restrict__ via, const float* __restrict__ val, int stride,
+                                          int off, int min_len, float* __restrict__ out) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n * heads) return;
+    const int i = heads == 1 ? t : t / heads, h = heads == 1 ? 0 : t % heads;
     const int b = ptr[i], e = ptr[i + 1];
     if (e - b > kSerialMax || e - b < min_len) return;
     float s = 0.f;
-    for (int j = b; j < e; ++j) s += val[(size_t)(via ? via[j] : j) * stride + off];
-    out[i] = s;
+    for (int j = b; j < e; ++j) s += val[(size_t)(via ? via[j] : j) * stride + off + h];
+    out[t] = s;
 }
-// One 256-thread workgroup per long segment (the hub runs are thousands of entries long): four
-// loads in flight per lane, lane sums added in lane order, then the four wavefronts' sums in order.
-__global__ __launch_bounds__(256) void segment_scalar_sum_long_kernel(int n_long, const int32_t* __restrict__ long_ids,
+// Four loads in flight per lane, lane sums added in lane order, then the four wavefronts' sums in
+// order (the hub runs are thousands of entries long).
+__global__ __launch_bounds__(256) void segment_scalar_sum_long_kernel(int heads, const int32_t* __restrict__ long_ids,
                                                                       const int32_t* __restrict__ ptr,
                                                                       const int32_t* __restrict__ via,
                                                                       const float* __restrict__ val, int stride, int off,
                                                                       float* __restrict__ out) {
     __shared__ float red[4];
-    const int i = long_ids[blockIdx.x];
+    const int i = long_ids[blockIdx.x], h = blockIdx.y;
     const int b = ptr[i], e = ptr[i + 1];
     float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
     for (int j = b + (int)threadIdx.x; j < e; j += 1024) {
         const int j1 = j + 256, j2 = j + 512, j3 = j + 768;
-        t0 += val[(size_t)(via ? via[j] : j) * stride + off];
-        if (j1 < e) t1 += val[(size_t)(via ? via[j1] : j1) * stride + off];
-        if (j2 < e) t2 += val[(size_t)(via ? via[j2] : j2) * stride + off];
-        if (j3 < e) t3 += val[(size_t)(via ? via[j3] : j3) * stride + off];
+        t0 += val[(size_t)(via ? via[j] : j) * stride + off + h];
+        if (j1 < e) t1 += val[(size_t)(via ? via[j1] : j1) * stride + off + h];
+        if (j2 < e) t2 += val[(size_t)(via ? via[j2] : j2) * stride + off + h];
+        if (j3 < e) t3 += val[(size_t)(via ? via[j3] : j3) * stride + off + h];
     }
     const float t = group_sum<64>((t0 + t1) + (t2 + t3));
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
     __syncthreads();
-    if (threadIdx.x == 0) out[i] = (red[0] + red[1]) + (red[2] + red[3]);
+    if (threadIdx.x == 0) out[(size_t)i * heads + h] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
 // ------------------------------------------------------------------ edge softmax (RGAT)
@@ -228,7 +229,7 @@ __global__ void edge_softmax_finish_kernel(int num_partials, const int32_t* __re
 
 // For item i with entries j in [beg, end):
 //   k   = via ? via[j] : j
-//   row = row_by_k ? rowidx[k] : rowidx[j]
+//   row = rowidx ? (row_by_k ? rowidx[k] : rowidx[j]) : k
 //   c   = coef ? coef[k * cstride + head] : 1     (absolute value if cabs; head = which of the
 //                                                  `heads` equal column groups the lane's columns lie in)
 //   acc += c * src[row]
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
             c[u] = 0.f;
             if (j + u < e) {
                 const int k = a.via ? a.via[j + u] : j + u;
-                row[u] = a.row_by_k ? a.rowidx[k] : a.rowidx[j + u];
+                row[u] = a.rowidx ? (a.row_by_k ? a.rowidx[k] : a.rowidx[j + u]) : k;
                 c[u] = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;
                 if (a.cabs) c[u] = fabsf(c[u]);
             }
@@ -319,7 +320,7 @@ __global__ __launch_bounds__(256) void gather_single_kernel(GatherArgs a, int fi
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int k = a.via ? a.via[j[u]] : j[u];
-        row[u] = a.row_by_k ? a.rowidx[k] : a.rowidx[j[u]];
+        row[u] = a.rowidx ? (a.row_by_k ? a.rowidx[k] : a.rowidx[j[u]]) : k;
         c[u] = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;
         if (a.cabs) c[u] = fabsf(c[u]);
     }
@@ -431,8 +432,8 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
 
 // ------------------------------------------------------------------ dX assembly
 
-// dX[u] = sum_{p in srcpair(u)} dXp[p]  +  sum_{q in runs(u)} ds_dst[q] * wtp[run_rel[q]]  +  extra[u]
-// (second and third terms optional).
+// dX[u] = sum_{p in srcpair(u)} dXp[p]  +  sum_{q in runs(u)} sum_h ds_dst[q][h] * wtp[h][run_rel[q]]  +  extra[u]
+// (second and third terms optional).  The (run, head) pairs of a node are walked as one flat list.
 struct NodeSumArgs {
     Items it;             // pairs by source node, ordered by length, never cut
     const int32_t* srcpair_ptr;
@@ -440,10 +441,12 @@ struct NodeSumArgs {
     const void* dXp;      // rows of TI
     const int32_t* dst_run_ptr;
     const int32_t* run_rel;
-    const float* ds_dst;
-    const float* wtp;
+    const float* ds_dst;  // [Q][heads]
+    const float* wtp;     // [heads][R][D]
     const float* extra;
     void* dX;             // rows of TO
+    int heads;            // run term: sum over (run q, head h) of ds_dst[q][h] * wtp[h][run_rel[q]]
+    int R;
 };
 
 // RUNS: the destination-run term is present (RGAT); without it the kernel only sums pair rows.
@@ -455,7 +458,8 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
     const TI* __restrict__ dXp = static_cast<const TI*>(a.dXp);
     const int u = a.it.row[i];
     const int b = a.it.beg[i], e = a.it.end[i];
-    const int qb = RUNS ? a.dst_run_ptr[u] : 0, qe = RUNS ? a.dst_run_ptr[u + 1] : 0;
+    const int H = a.heads;
+    const int qb = RUNS ? a.dst_run_ptr[u] * H : 0, qe = RUNS ? a.dst_run_ptr[u + 1] * H : 0;
     float acc[V], acc1[V];
     zero_cols(acc);
     zero_cols(acc1);
@@ -469,7 +473,8 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
         rr[t] = -1;
         c[t] = 0.f;
         if (RUNS && qb + t < qe) {
-            rr[t] = a.run_rel[qb + t];
+            const int x = qb + t;
+            rr[t] = H == 1 ? a.run_rel[x] : (x % H) * a.R + a.run_rel[x / H];
             c[t] = a.ds_dst[qb + t];
         }
     }
@@ -515,7 +520,8 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
             zero_cols(v[t]);
             if (q + t < qe) {
                 cq[t] = a.ds_dst[q + t];
-                load_cols(a.wtp + (size_t)a.run_rel[q + t] * D + cv * V, v[t]);
+                const int x = q + t;
+                load_cols(a.wtp + (size_t)(H == 1 ? a.run_rel[x] : (x % H) * a.R + a.run_rel[x / H]) * D + cv * V, v[t]);
             }
         }
         fma_cols(acc, cq[0], v[0]);
@@ -600,15 +606,16 @@ rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float*
 }
 
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
-                                 int stride, int off, float* out, hipStream_t st, const char* label, int min_len) {
+                                 int stride, int off, float* out, hipStream_t st, const char* label, int min_len,
+                                 int heads) {
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, label);
-    hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, ptr, via, val, stride,
-                       off, min_len, out);
+    hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3(blocks_for((size_t)n * heads, 256)), dim3(256), 0, st, n, heads, ptr,
+                       via, val, stride, off, min_len, out);
     RGNN_CHECK_LAUNCH();
     if (lng.n > 0) {
-        hipLaunchKernelGGL(segment_scalar_sum_long_kernel, dim3(lng.n), dim3(256), 0, st, lng.n, lng.ids, ptr, via, val,
-                           stride, off, out);
+        hipLaunchKernelGGL(segment_scalar_sum_long_kernel, dim3(lng.n, heads), dim3(256), 0, st, heads, lng.ids, ptr, via,
+                           val, stride, off, out);
         RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;
@@ -705,10 +712,10 @@ rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const f
 }
 
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const float* ds_dst, const float* wtp,
-                            const float* extra, void* dX, hipStream_t st, int in_bf16, int out_bf16) {
+                            const float* extra, void* dX, hipStream_t st, int in_bf16, int out_bf16, int heads) {
     if (g->N == 0) return RGNN_OK;
     NodeSumArgs a{dev_items(g->srcpair_items), g->idx[RGNN_IDX_SRCPAIR_PTR], g->idx[RGNN_IDX_SRCPAIR_IDX], dXp,
-                  g->idx[RGNN_IDX_DST_RUN_PTR], g->idx[RGNN_IDX_RUN_REL], ds_dst, wtp, extra, dX};
+                  g->idx[RGNN_IDX_DST_RUN_PTR], g->idx[RGNN_IDX_RUN_REL], ds_dst, wtp, extra, dX, heads, (int)g->R};
     KernelTimer kt(st, "node_grad_sum");
     const dim3 grid(blocks_for((size_t)g->N, 256 / (D / (in_bf16 ? 8 : 4))));
     if (ds_dst)

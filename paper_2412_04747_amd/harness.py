@@ -62,10 +62,10 @@ class Graph:
 class RgatLayer:
     """Device buffers for one RGAT layer call pair on a graph."""
 
-    def __init__(self, graph, d, slope=0.2, dtype="f32"):
-        self.g, self.d = graph, d
+    def __init__(self, graph, d, slope=0.2, dtype="f32", heads=1):
+        self.g, self.d, self.H = graph, d, heads
         code, self.tdt = _tdtype(dtype)
-        self.desc = B.make_desc(code, d, d, 1, slope)
+        self.desc = B.make_desc(code, d, d, heads, slope)
         f, b, s = B.rgnn_workspace_bytes(graph.handle, B.RGNN_LAYER_RGAT, self.desc)
         self.ws = _buf(max(f, b))
         self.saved = _buf(s)
@@ -89,13 +89,14 @@ class RgatLayer:
                         self.dX, self.dW, self.dw_s, self.dw_t, self.ws, _stream())
 
     def saved_views(self):
-        """(Hs [P, d], att [E]) as laid out in `saved`."""
+        """(Hs [P, d], att [E] or [E, heads]) as laid out in `saved`."""
         P, E, d = self.g.P, self.g.E, self.d
         al = lambda n: (n + 255) // 256 * 256
         f32 = self.saved.view(torch.float32)
         hs = f32[: P * d].view(P, d)
         off = al(max(P * d, 1) * 4) // 4
-        return hs, f32[off: off + E]
+        att = f32[off: off + E * self.H]
+        return hs, (att if self.H == 1 else att.view(E, self.H))
 
     def grads(self):
         return dict(dX=self.dX, dW=self.dW, dw_s=self.dw_s, dw_t=self.dw_t)

@@ -96,7 +96,7 @@ def test_layer_argument_errors():
     g = Graph(20, 2, src, dst, rel)
     x = torch.zeros(20, 64, device="cuda")
     for bad, status in ((B.make_desc(d_in=48, d_out=48), 2), (B.make_desc(d_in=64, d_out=32), 2),
-                        (B.make_desc(heads=2), 2), (B.make_desc(flags=1), 1), (B.make_desc(dtype=7), 1)):
+                        (B.make_desc(heads=8), 2), (B.make_desc(heads=3), 1), (B.make_desc(flags=1), 1), (B.make_desc(dtype=7), 1)):
         with pytest.raises(B.RgnnError) as e:
             B.rgnn_rgat_fwd(g.handle, bad, x, x, x, x, x, x, x)
         assert e.value.status == status

@@ -68,6 +68,62 @@ def test_many_single_edge_destinations():
     _run(N, R, src, dst, rel, p, d, "singles")
 
 
+def _run_heads(N, R, src, dst, rel, p, d, H, tag, dtype="f32", slope=0.2):
+    import torch
+    from paper_2412_04747_amd.harness import Graph, RgatLayer
+    from parity import TOL_BF16
+    print(f"rgat case {tag}: N={N} R={R} E={len(src)} d={d} heads={H} {dtype}", flush=True)
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    g = Graph(N, R, src, dst, rel)
+    L = RgatLayer(g, d, slope, dtype=dtype, heads=H)
+    L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
+    L.fwd()
+    torch.cuda.synchronize()
+    want, alpha, z = O.rgat_heads_fwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], H, slope, want_alpha=True)
+    check(L.out, want, tol, "out")
+    ix = graph_index.build(N, R, src, dst, rel)
+    _, att = L.saved_views()
+    att = att.cpu().numpy().reshape(len(src), H)
+    check(np.abs(att), alpha[ix["in_eid"]], tol, "att")
+    zz = z[ix["in_eid"]]
+    clear = np.abs(zz) > 1e-3
+    assert np.array_equal(np.signbit(att)[clear], (zz <= 0)[clear])
+    L.bwd()
+    torch.cuda.synchronize()
+    wg = O.rgat_heads_bwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"], H, slope)
+    errs = {k: check(v, wg[k], tol, k) for k, v in L.grads().items()}
+    print("   max rel errors:", {k: f"{v:.1e}" for k, v in errs.items()}, flush=True)
+    first = {k: v.clone() for k, v in L.grads().items()}
+    out1 = L.out.clone()
+    L.fwd(); L.bwd()
+    torch.cuda.synchronize()
+    assert torch.equal(out1, L.out)
+    for k, v in L.grads().items():
+        assert torch.equal(first[k], v), k
+    g.close()
+
+
+@pytest.mark.parametrize("d,H", [(64, 2), (64, 4), (128, 8), (32, 2), (128, 2)])
+def test_multi_head(d, H):
+    rng, src, dst, rel, _ = synth.tiny(160 + d + H, N=800, R=6, E=7000)
+    dst[:1200] = 4                                   # a hub cut into pieces
+    src[:300] = 9; rel[:300] = 2                     # one pair with many edges
+    p = synth.rgat_params(rng, 800, 6, d, d)
+    _run_heads(800, 6, src, dst, rel, p, d, H, f"heads-d{d}-H{H}")
+
+
+def test_multi_head_bf16_inputs_and_empty_relation():
+    rng, src, dst, rel, _ = synth.tiny(171, N=600, R=5, E=5000)
+    rel[rel == 3] = 1                                # relation 3 has no edge
+    p = {k: synth.round_to_bf16(v) for k, v in synth.rgat_params(rng, 600, 5, 64, 64).items()}
+    _run_heads(600, 5, src, dst, rel, p, 64, 4, "heads-bf16", dtype="bf16")
+
+
+def test_multi_head_scaled_config3():
+    c = synth.config(3, scale=0.02)                  # 20k nodes, 200k edges, 200 relations, power-law in-degree
+    _run_heads(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 64, 4, "heads-C3/50")
+
+
 def test_config2():
     c = synth.config(2)
     _run(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 64, "C2")

@@ -140,3 +140,56 @@ def test_backward_matches_finite_differences():
         g = O.rgat_bwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], G)
         for name, key in (("X", "dX"), ("W", "dW"), ("w_s", "dw_s"), ("w_t", "dw_t")):
             assert_close(g[key], central_fd(loss, p, name), 2e-6, key)
+
+
+def _multihead_by_hand(N, src, dst, rel, X, W, w_s, w_t, H, slope=0.2):
+    """Multi-head RGAT written per edge and per head in plain Python, from the listing's formulas
+    applied to column slices (no call into the oracle)."""
+    d = W.shape[2]
+    dh = d // H
+    out = np.zeros((N, d))
+    alpha = np.zeros((len(src), H))
+    for v in range(N):
+        es = [e for e in range(len(src)) if dst[e] == v]
+        if not es:
+            continue
+        hs = {e: X[src[e]] @ W[rel[e]] for e in es}
+        ht = {e: X[v] @ W[rel[e]] for e in es}
+        for h in range(H):
+            c = slice(h * dh, (h + 1) * dh)
+            z = np.array([hs[e][c] @ w_s[rel[e]][c] + ht[e][c] @ w_t[rel[e]][c] for e in es])
+            l = np.where(z > 0, z, slope * z)
+            a = np.exp(l) / np.exp(l).sum()
+            for k, e in enumerate(es):
+                alpha[e, h] = a[k]
+                out[v, c] += a[k] * hs[e][c]
+    return out, alpha
+
+
+def test_multi_head_is_per_slice_attention():
+    """heads > 1: brute force per edge and head on a tiny graph; every head's weights sum to 1 per
+    destination; heads = 1 is the single-head layer."""
+    src, dst, rel, p = _rand(21, N=9, R=3, E=30, d_in=5, d_out=6)
+    for H in (2, 3):
+        out, alpha, _ = O.rgat_heads_fwd(9, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], H, want_alpha=True)
+        want, a_want = _multihead_by_hand(9, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], H)
+        assert_close(out, want, 1e-12, f"out H={H}")
+        assert_close(alpha, a_want, 1e-12, f"alpha H={H}")
+        sums = np.zeros((9, H))
+        np.add.at(sums, dst, alpha)
+        has_in = np.bincount(dst, minlength=9) > 0
+        assert np.allclose(sums[has_in], 1.0, atol=1e-12) and np.all(sums[~has_in] == 0)
+    one = O.rgat_heads_fwd(9, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], 1)
+    assert np.array_equal(one, O.rgat_fwd(9, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"]))
+
+
+def test_multi_head_backward_matches_finite_differences():
+    src, dst, rel, p = _rand(22, N=8, R=3, E=25, d_in=4, d_out=6)
+    H, N = 2, 8
+    _, _, z = O.rgat_heads_fwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], H, want_alpha=True)
+    assert np.abs(z).min() > 1e-3, "sample too close to the leaky-ReLU kink"
+    G = p["dOut"]
+    loss = lambda q: float((O.rgat_heads_fwd(N, src, dst, rel, q["X"], q["W"], q["w_s"], q["w_t"], H) * G).sum())
+    g = O.rgat_heads_bwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], G, H)
+    for name, key in (("X", "dX"), ("W", "dW"), ("w_s", "dw_s"), ("w_t", "dw_t")):
+        assert_close(g[key], central_fd(loss, p, name), 2e-6, key)
