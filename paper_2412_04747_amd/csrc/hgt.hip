@@ -74,12 +74,17 @@ __global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, co
     const int lph = LPR / H, head = cv / lph;
     float q[V];
     load_cols(Q + (size_t)it.row[i] * D + cv * V, q);
+    // pair ids run one batch of four ahead of the rows (positions past the end repeat the last edge)
+    int pr[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) pr[u] = in_pair[min(b + u, e - 1)];
     for (int j = b; j < e; j += 4) {
         float k[4][V];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (j + u < e) load_cols(Ka + (size_t)in_pair[j + u] * D + cv * V, k[u]);
-            else zero_cols(k[u]);
+        for (int u = 0; u < 4; ++u) load_cols(Ka + (size_t)pr[u] * D + cv * V, k[u]);
+        if (j + 4 < e) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) pr[u] = in_pair[min(j + 4 + u, e - 1)];
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -200,17 +205,30 @@ __global__ __launch_bounds__(256) void hgt_edge_dot_bwd_kernel(Items it, int H, 
     float gz[V], zz[V];
     load_cols(dZ + v * D + cv * V, gz);
     load_cols(Z + v * D + cv * V, zz);
+    // pair ids and attention weights run one batch of four ahead of the rows
+    int pr[4];
+    float an[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int jj = min(b + u, e - 1);
+        pr[u] = in_pair[jj];
+        an[u] = att[(size_t)jj * H + head];
+    }
     const float gbar = group_sum_dyn(dot_cols(gz, zz), lph);
     for (int j = b; j < e; j += 4) {
         float mm[4][V];
         float a[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            zero_cols(mm[u]);
-            a[u] = 0.f;
-            if (j + u < e) {
-                load_cols(M + (size_t)in_pair[j + u] * D + cv * V, mm[u]);
-                a[u] = att[(size_t)(j + u) * H + head];
+            load_cols(M + (size_t)pr[u] * D + cv * V, mm[u]);
+            a[u] = an[u];
+        }
+        if (j + 4 < e) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int jj = min(j + 4 + u, e - 1);
+                pr[u] = in_pair[jj];
+                an[u] = att[(size_t)jj * H + head];
             }
         }
 #pragma unroll

@@ -266,31 +266,40 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
     float acc0[V], acc1[V];
     zero_cols(acc0);
     zero_cols(acc1);
-    for (int j = b; j < e; j += 4) {
-        int row[4];
-        float c[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            row[u] = -1;
-            c[u] = 0.f;
-            if (j + u < e) {
-                const int k = a.via ? a.via[j + u] : j + u;
-                row[u] = a.rowidx ? (a.row_by_k ? a.rowidx[k] : a.rowidx[j + u]) : k;
-                c[u] = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;
-                if (a.cabs) c[u] = fabsf(c[u]);
-            }
-        }
-        float v[4][V];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (row[u] >= 0) load_cols(src + (size_t)row[u] * D + cv * V, v[u]);
-            else zero_cols(v[u]);
-        }
-        fma_cols(acc0, c[0], v[0]);
-        fma_cols(acc1, c[1], v[1]);
-        fma_cols(acc0, c[2], v[2]);
-        fma_cols(acc1, c[3], v[3]);
+    // Indices and coefficients run one batch of four ahead of the rows, so that a batch costs one
+    // memory round trip instead of two.  Positions past the end repeat the last entry with a zero
+    // coefficient: every load is unconditional.
+    int row[4];
+    float c[4];
+#define RGNN_GATHER_FETCH_IDX(J)                                                                  \
+    _Pragma("unroll") for (int u = 0; u < 4; ++u) {                                               \
+        const int jj = min((J) + u, e - 1);                                                       \
+        const int k = a.via ? a.via[jj] : jj;                                                     \
+        row[u] = a.rowidx ? (a.row_by_k ? a.rowidx[k] : a.rowidx[jj]) : k;                        \
+        float cc = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;                           \
+        if (a.cabs) cc = fabsf(cc);                                                               \
+        c[u] = (J) + u < e ? cc : 0.f;                                                            \
     }
+    if (b < e) {
+        RGNN_GATHER_FETCH_IDX(b)
+    }
+    for (int j = b; j < e; j += 4) {
+        float v[4][V];
+        float cc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            load_cols(src + (size_t)row[u] * D + cv * V, v[u]);
+            cc[u] = c[u];
+        }
+        if (j + 4 < e) {
+            RGNN_GATHER_FETCH_IDX(j + 4)
+        }
+        fma_cols(acc0, cc[0], v[0]);
+        fma_cols(acc1, cc[1], v[1]);
+        fma_cols(acc0, cc[2], v[2]);
+        fma_cols(acc1, cc[3], v[3]);
+    }
+#undef RGNN_GATHER_FETCH_IDX
     fma_cols(acc0, 1.f, acc1);
     const int slot = a.it.slot[i];
     if (slot < 0) store_cols(static_cast<TO*>(a.out) + (size_t)a.it.row[i] * D + cv * V, acc0);
@@ -398,6 +407,16 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
     const size_t v = (size_t)a.it.row[i];
     const float4 go = *reinterpret_cast<const float4*>(a.dOut + v * D + c4 * 4);
     const float4 ov = *reinterpret_cast<const float4*>(a.out + v * D + c4 * 4);
+    // attention weights and pair ids run one batch of four ahead of the rows (positions past the end
+    // repeat the last edge; their results are not stored)
+    float atn[4];
+    int prn[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int jj = min(b + u, e - 1);
+        atn[u] = a.att[jj];
+        prn[u] = a.in_pair[jj];
+    }
     const float gbar = group_sum<LPR>(dot4(go, ov));
     for (int j = b; j < e; j += 4) {
         float at[4];
@@ -405,13 +424,16 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
         int pr[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            at[u] = 0.f;
-            pr[u] = 0;
-            h[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (j + u < e) {
-                at[u] = a.att[j + u];
-                pr[u] = a.in_pair[j + u];
-                h[u] = *reinterpret_cast<const float4*>(a.Hs + (size_t)(pr[u] & 0x7FFFFFFF) * D + c4 * 4);
+            at[u] = atn[u];
+            pr[u] = prn[u];
+            h[u] = *reinterpret_cast<const float4*>(a.Hs + (size_t)(pr[u] & 0x7FFFFFFF) * D + c4 * 4);
+        }
+        if (j + 4 < e) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int jj = min(j + 4 + u, e - 1);
+                atn[u] = a.att[jj];
+                prn[u] = a.in_pair[jj];
             }
         }
 #pragma unroll
@@ -420,8 +442,9 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
             const float al = fabsf(at[u]);
             const float dl = al * (g - gbar);
             const float dz = dl * (signbit(at[u]) ? a.slope : 1.f);
-            if (c4 == 0 && j + u < e) a.adz[j + u] = make_float2(al, dz);
-            if (pr[u] < 0) {   // single-edge pair (implies j + u < e)
+            const bool live = j + u < e;
+            if (c4 == 0 && live) a.adz[j + u] = make_float2(al, dz);
+            if (live && pr[u] < 0) {   // single-edge pair
                 const size_t p = (size_t)(pr[u] & 0x7FFFFFFF);
                 *reinterpret_cast<float4*>(a.G + p * D + c4 * 4) = make_float4(al * go.x, al * go.y, al * go.z, al * go.w);
                 if (c4 == 0) a.ds_src[p] = dz;
