@@ -29,6 +29,8 @@
  *   - Weights are stored [type][d_in][d_out] so that y = x W (row vector times
  *     matrix), as in Eq. (rgcn).
  *   - Gradients are overwritten, not accumulated.
+ *   - A graph may have no nodes or no edges; a [num_nodes, d] tensor of a graph
+ *     without nodes may be NULL.  Parameter gradients are then written as zeros.
  *   - Index arrays are int32; graphs with 2^31 or more edges are rejected.
  */
 #ifndef RGNN_H

@@ -51,6 +51,9 @@ struct Bf16Stage {
     void reserve(size_t n) { if (on) (void)c.take<float>(n); }
 };
 
+// A [num_nodes, d] tensor may be NULL when the graph has no nodes.
+inline bool missing(const rgnn_graph_t* g, const void* p) { return !p && g->N > 0; }
+
 rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int layer) {
     if (!g || !d) RGNN_FAIL(RGNN_EINVAL, "graph or desc is NULL");
     if (d->flags != 0) RGNN_FAIL(RGNN_EINVAL, "desc.flags must be 0");
@@ -313,7 +316,7 @@ extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_d
                                        void* stream) {
     (void)saved;
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGCN));
-    if (!X || !W || !out) RGNN_FAIL(RGNN_EINVAL, "X, W or out is NULL");
+    if (missing(g, X) || !W || missing(g, out)) RGNN_FAIL(RGNN_EINVAL, "X, W or out is NULL");
     if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out;
@@ -350,9 +353,9 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
                                        void* stream) {
     (void)saved;
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGCN));
-    if (!X || !W || !dOut || !dX || !dW) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
+    if (missing(g, X) || !W || missing(g, dOut) || missing(g, dX) || !dW) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (W0 && !dW0) RGNN_FAIL(RGNN_EINVAL, "dW0 is NULL but W0 is given");
-    if (desc->activation != RGNN_ACT_NONE && !out) RGNN_FAIL(RGNN_EINVAL, "out is needed for the activation's gradient");
+    if (desc->activation != RGNN_ACT_NONE && missing(g, out)) RGNN_FAIL(RGNN_EINVAL, "out is needed for the activation's gradient");
     if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, K = desc->d_in;
@@ -406,7 +409,7 @@ extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_d
                                        const void* W, const void* w_s, const void* w_t, void* out, void* saved,
                                        void* workspace, void* stream) {
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGAT));
-    if (!X || !W || !w_s || !w_t || !out) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
+    if (missing(g, X) || !W || !w_s || !w_t || missing(g, out)) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, K = desc->d_in;
@@ -457,7 +460,7 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
                                        const void* saved, const void* dOut, void* dX, void* dW, void* dw_s,
                                        void* dw_t, void* workspace, void* stream) {
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGAT));
-    if (!X || !W || !w_s || !w_t || !out || !dOut || !dX || !dW || !dw_s || !dw_t)
+    if (missing(g, X) || !W || !w_s || !w_t || missing(g, out) || missing(g, dOut) || missing(g, dX) || !dW || !dw_s || !dw_t)
         RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (!workspace || !saved) RGNN_FAIL(RGNN_EWORKSPACE, "workspace or saved is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -542,7 +545,7 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
                                       const void* Wmsg, const void* mu, void* out, void* saved, void* workspace,
                                       void* stream) {
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_HGT));
-    if (!X || !Wk || !Wq || !Wv || !Wo || !Watt || !Wmsg || !out) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
+    if (missing(g, X) || !Wk || !Wq || !Wv || !Wo || !Watt || !Wmsg || missing(g, out)) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int D = desc->d_out, H = desc->heads;
@@ -598,7 +601,7 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
                                       void* dWatt, void* dWmsg, void* dmu, void* workspace, void* stream) {
     (void)out;
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_HGT));
-    if (!X || !Wk || !Wq || !Wv || !Wo || !Watt || !Wmsg || !dOut || !dX || !dWk || !dWq || !dWv || !dWo || !dWatt || !dWmsg)
+    if (missing(g, X) || !Wk || !Wq || !Wv || !Wo || !Watt || !Wmsg || missing(g, dOut) || missing(g, dX) || !dWk || !dWq || !dWv || !dWo || !dWatt || !dWmsg)
         RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (mu && !dmu) RGNN_FAIL(RGNN_EINVAL, "dmu is NULL but mu is given");
     if (!workspace || !saved) RGNN_FAIL(RGNN_EWORKSPACE, "workspace or saved is NULL");

@@ -148,3 +148,41 @@ def test_inference_calls_without_saved_buffer():
         torch.cuda.synchronize()
         assert torch.equal(ref, H.out), ("hgt", dtype)
     g.close()
+
+
+def test_graph_without_nodes_and_layers_on_it():
+    """N = 0, E = 0: the index is empty, every layer call is a no-op that returns success, and the
+    parameter gradients are written as zeros."""
+    import torch
+    from paper_2412_04747_amd.harness import Graph, RgatLayer, RgcnLayer, HgtLayer
+    e = np.zeros(0, np.int32)
+    g = Graph(0, 3, e, e, e, e, 2)
+    assert (g.P, g.Q, int(g.info.max_in_degree), int(g.info.num_nodes)) == (0, 0, 0, 0)
+    assert list(g.export("in_ptr")) == [0] and list(g.export("pair_ptr")) == [0, 0, 0, 0]
+    rng = np.random.default_rng(5)
+    p = synth.rgat_params(rng, 0, 3, 64, 64)
+    for heads in (1, 2):
+        L = RgatLayer(g, 64, heads=heads)
+        L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
+        for t in (L.dW, L.dw_s, L.dw_t):
+            t.fill_(float("nan"))
+        L.fwd(); L.bwd()
+        torch.cuda.synchronize()
+        assert all(float(t.abs().sum()) == 0.0 for t in (L.dW, L.dw_s, L.dw_t)), heads
+    q = synth.rgcn_params(rng, 0, 3, 32, 32, self_loop=True)
+    C = RgcnLayer(g, 32, "in_degree_per_rel", "relu", True)
+    C.load(q["X"], q["W"], q["W0"], q["dOut"])
+    C.dW.fill_(float("nan")); C.dW0.fill_(float("nan"))
+    C.fwd(); C.bwd()
+    torch.cuda.synchronize()
+    assert float(C.dW.abs().sum()) == 0.0 and float(C.dW0.abs().sum()) == 0.0
+    h = synth.hgt_params(rng, 0, 2, 3, 64, 2, with_mu=True)
+    H = HgtLayer(g, 64, 2, with_mu=True)
+    H.load(h["X"], h["Wk"], h["Wq"], h["Wv"], h["Wo"], h["Watt"], h["Wmsg"], h["mu"], h["dOut"])
+    for t in H.grads().values():
+        t.fill_(float("nan"))
+    H.fwd(); H.bwd()
+    torch.cuda.synchronize()
+    for k, t in H.grads().items():
+        assert float(t.abs().sum()) == 0.0, k
+    g.close()
