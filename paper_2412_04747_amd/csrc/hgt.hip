@@ -1,5 +1,6 @@
-// HGT-specific kernels: block-diagonal expansion of the per-(relation, head) matrices, the
-// per-head edge logits, the per-head edge softmax and the per-head backward edge dot.
+// Kernels of the HGT layer: block-diagonal expansion of the per-(relation, head) matrices, the
+// per-head edge logits, the per-head edge softmax and the per-head backward edge dot.  The last
+// two also serve multi-head RGAT (signed weights, leaky-ReLU slope).
 // (Caption of the thesis figure "HGT and RGAT layer": attention of HGT is an edgewise dot
 // product between the relation-transformed key of the source and the query of the
 // destination; the message depends only on (source node, edge type), so both are stored
