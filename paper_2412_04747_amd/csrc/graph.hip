@@ -111,8 +111,12 @@ static rgnn_status_t build(rgnn_graph* g, int format, const int32_t* a, const in
     build_tiles(U, g->pair_tiles, pair_ptr, kTileRows);
     build_tiles(U, g->node_tiles, ntype_ptr, kTileRows);
     build_tiles(U, g->all_tiles, std::vector<int32_t>{0, (int32_t)g->N}, kTileRows);
-    build_tiles(U, g->pair_tiles_wide, pair_ptr, kTileRows, kWideChunks);
-    build_tiles(U, g->node_tiles_wide, ntype_ptr, kTileRows, kWideChunks);
+    int dev = 0, cus = 0;
+    RGNN_HIP(hipGetDevice(&dev));
+    RGNN_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    const int wide = kWideChunksPerCU * std::max(cus, 1);
+    build_tiles(U, g->pair_tiles_wide, pair_ptr, kTileRows, wide);
+    build_tiles(U, g->node_tiles_wide, ntype_ptr, kTileRows, wide);
     build_items(U, g->dst_items, in_ptr, item_cut(g->E));
     build_items(U, g->pair_items, out_ptr, item_cut(g->E));
     build_items(U, g->relrun_items, relrun_ptr, item_cut(g->E));

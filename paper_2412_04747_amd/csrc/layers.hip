@@ -222,17 +222,20 @@ void* saved_or_scratch(const rgnn_graph_t* g, int layer, const rgnn_layer_desc_t
 // Forward typed linear  Y[g(i)] / Y[i] = A[g(i)] W[seg].  In bf16 mode it runs on the bf16 matrix
 // cores: an operand whose bf16 form exists (A16 / W16) is used as is, an fp32-only one is split.
 // y16: the output rows are stored as bf16 (width 128 only).
-rgnn_status_t tl_fwd(bool bf16, const rgnn::TileList* tiles, int d, const float* A32, const void* A16,
-                     const int32_t* gather, int scatter, const float* W32, const void* W16, void* Y, bool y16,
-                     const char* label, hipStream_t st) {
+// Chunking: the bf16 kernel with the weight in bf16 does best on many short chunks (`tiles`); when
+// the weight has to be split, and in the fp32 kernels, loading a segment's weight costs more and one
+// resident round of long chunks (`wide`) wins.
+rgnn_status_t tl_fwd(bool bf16, const rgnn::TileList* tiles, const rgnn::TileList* wide, int d, const float* A32,
+                     const void* A16, const int32_t* gather, int scatter, const float* W32, const void* W16, void* Y,
+                     bool y16, const char* label, hipStream_t st) {
     if (bf16) {
         TypedLinearBf16Args a{};
-        a.tiles = tiles; a.A = A16 ? A16 : A32; a.a_bf16 = A16 != nullptr; a.gather = gather; a.scatter_out = scatter;
+        a.tiles = W16 ? tiles : wide; a.A = A16 ? A16 : A32; a.a_bf16 = A16 != nullptr; a.gather = gather; a.scatter_out = scatter;
         a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.Y = Y; a.y_bf16 = y16; a.label = label;
         return typed_linear_bf16(d, a, st);
     }
     TypedLinearArgs a{};
-    a.tiles = tiles; a.X = A32; a.gather = gather; a.W = W32; a.Y = static_cast<float*>(Y); a.scatter_out = scatter;
+    a.tiles = wide; a.X = A32; a.gather = gather; a.W = W32; a.Y = static_cast<float*>(Y); a.scatter_out = scatter;
     a.label = label;
     return typed_linear_fwd(d, d, a, st);
 }
@@ -260,7 +263,7 @@ rgnn_status_t tl_bwd(bool rows16, const rgnn::TileList* tiles, const rgnn::TileL
                      bool dx_acc = false) {
     if (rows16) {
         TypedLinearBf16Args a{};
-        a.tiles = tiles; a.A = dY; a.a_bf16 = 1; a.gather = both_gathered ? gather : nullptr; a.scatter_out = both_gathered;
+        a.tiles = W16 ? tiles : wide; a.A = dY; a.a_bf16 = 1; a.gather = both_gathered ? gather : nullptr; a.scatter_out = both_gathered;
         a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.transpose_w = 1; a.Y = dXrow; a.y_bf16 = dx16; a.accumulate = dx_acc; a.label = label;
         RGNN_TRY(typed_linear_bf16(d, a, st));
         TypedLinearWgradBf16Args w{};
@@ -271,7 +274,7 @@ rgnn_status_t tl_bwd(bool rows16, const rgnn::TileList* tiles, const rgnn::TileL
     }
     if (dx_acc) RGNN_FAIL(RGNN_EUNSUPPORTED, "accumulating input gradient needs bf16 rows");
     TypedLinearBwdArgs b{};
-    b.tiles = tiles; b.X = static_cast<const float*>(X); b.gather = gather; b.W = W32; b.dY = static_cast<const float*>(dY);
+    b.tiles = wide; b.X = static_cast<const float*>(X); b.gather = gather; b.W = W32; b.dY = static_cast<const float*>(dY);
     b.dy_gathered = both_gathered; b.dXrow = static_cast<float*>(dXrow); b.scatter_dx = both_gathered; b.dW = dW;
     b.part = part; b.label = label;
     return typed_linear_bwd(d, d, b, st);
@@ -331,7 +334,7 @@ extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     const float* W032 = stg.in(W0, (size_t)desc->d_in * D);
     RGNN_TRY(stg.status);
     // 1. compact messages: Hs[p] = X[pair_src[p]] W[rel(p)]
-    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, X32, X16, g->idx[RGNN_IDX_PAIR_SRC], 0, W32, W16, w.Hs, h, "typed_linear_fwd", st));
+    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, X32, X16, g->idx[RGNN_IDX_PAIR_SRC], 0, W32, W16, w.Hs, h, "typed_linear_fwd", st));
     // 2. out[v] = sum_e (1/c) Hs[pair_e]
     const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, coef, 1, 0, w.Hs, out, w.partial, st, 0,
@@ -428,7 +431,7 @@ extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_d
         const int H = desc->heads;
         const float *Xf = static_cast<const float*>(X), *Wf = static_cast<const float*>(W);
         TypedLinearArgs a{};
-        a.tiles = &g->pair_tiles; a.X = Xf; a.gather = g->idx[RGNN_IDX_PAIR_SRC]; a.W = Wf; a.Y = sv.Hs;
+        a.tiles = &g->pair_tiles_wide; a.X = Xf; a.gather = g->idx[RGNN_IDX_PAIR_SRC]; a.W = Wf; a.Y = sv.Hs;
         RGNN_TRY(typed_linear_fwd(K, D, a, st));
         RGNN_TRY(head_dot_rows(g->P, D, H, sv.Hs, g->idx[RGNN_IDX_PAIR_REL], static_cast<const float*>(w_s), w.s_src, st));
         RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, static_cast<const float*>(w_t), w.wtp, st));
@@ -441,7 +444,7 @@ extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     // 1. compact messages and the source half of the logit:
     //    Hs[p] = X[pair_src[p]] W[r];  s_src[p] = Hs[p] . w_s[r]
     TypedLinearArgs a{};
-    a.tiles = &g->pair_tiles; a.X = static_cast<const float*>(X); a.gather = g->idx[RGNN_IDX_PAIR_SRC];
+    a.tiles = &g->pair_tiles_wide; a.X = static_cast<const float*>(X); a.gather = g->idx[RGNN_IDX_PAIR_SRC];
     a.W = static_cast<const float*>(W); a.Y = sv.Hs; a.vec = static_cast<const float*>(w_s); a.s_out = w.s_src;
     RGNN_TRY(typed_linear_fwd(K, D, a, st));
     // 2. destination half, once per (dst, rel) run, reordered: s_dst[q] = X[dst] . (W[r] w_t[r])
@@ -494,7 +497,7 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         RGNN_TRY(add_head_rank1(g->P, D, H, w.ds_src, g->idx[RGNN_IDX_PAIR_REL], ws, w.G, st));
         // 4. dXp = dHs W^T, dW = sum X^T dHs
         TypedLinearBwdArgs b{};
-        b.tiles = &g->pair_tiles; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
+        b.tiles = &g->pair_tiles_wide; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
         b.dW = static_cast<float*>(dW); b.part = w.tl_part;
         RGNN_TRY(typed_linear_bwd(K, D, b, st));
         // 5. dw_s[r] = sum over r's pairs of ds_src[p][h] Hs[p] (per head; the pair rows are in relation order)
@@ -522,7 +525,7 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     //    A[r] = sum ds_src X
     RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_s), w.wsp, st));
     TypedLinearBwdArgs b{};
-    b.tiles = &g->pair_tiles; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
+    b.tiles = &g->pair_tiles_wide; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
     b.rowscale = w.ds_src; b.vec = w.wsp; b.dW = static_cast<float*>(dW); b.Avec = w.A;
     b.part = w.tl_part;
     RGNN_TRY(typed_linear_bwd(K, D, b, st));
@@ -574,15 +577,15 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     auto R16 = [h](const void* p) { return h ? p : nullptr; };
     auto R32 = [h](const void* p) { return h ? nullptr : static_cast<const float*>(p); };
     // 1. per node type: K, Q, V
-    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, X32, X16, perm, 1, Wk32, Wk16, sv.K, h, "node_linear_k", st));
-    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, X32, X16, perm, 1, Wq32, Wq16, sv.Q, h, "node_linear_q", st));
-    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, X32, X16, perm, 1, Wv32, Wv16, sv.V, h, "node_linear_v", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, &g->node_tiles_wide, D, X32, X16, perm, 1, Wk32, Wk16, sv.K, h, "node_linear_k", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, &g->node_tiles_wide, D, X32, X16, perm, 1, Wq32, Wq16, sv.Q, h, "node_linear_q", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, &g->node_tiles_wide, D, X32, X16, perm, 1, Wv32, Wv16, sv.V, h, "node_linear_v", st));
     // 2. per (relation, head) matrices as block-diagonal d x d weights; mu / sqrt(dh) folded into the attention one
     RGNN_TRY(hgt_expand(g->R, D, H, Watt32, mu32, 1, w.Wbd_att, st));
     RGNN_TRY(hgt_expand(g->R, D, H, Wmsg32, nullptr, 0, w.Wbd_msg, st));
     // 3. compact per pair: Ka[p] = K[src_p] Watt[r], M[p] = V[src_p] Wmsg[r]
-    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, R32(sv.K), R16(sv.K), psrc, 0, w.Wbd_att, nullptr, sv.Ka, h, "pair_linear_att", st));
-    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, D, R32(sv.V), R16(sv.V), psrc, 0, w.Wbd_msg, nullptr, sv.M, h, "pair_linear_msg", st));
+    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, R32(sv.K), R16(sv.K), psrc, 0, w.Wbd_att, nullptr, sv.Ka, h, "pair_linear_att", st));
+    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, R32(sv.V), R16(sv.V), psrc, 0, w.Wbd_msg, nullptr, sv.M, h, "pair_linear_msg", st));
     // 4. per edge and head: logit, softmax over the destination's edges
     RGNN_TRY(hgt_edge_logit(g, D, H, sv.Ka, sv.Q, sv.att, st, h));
     RGNN_TRY(hgt_softmax(g, H, sv.att, w.part_m, w.part_s, st));
@@ -590,7 +593,7 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, H, 0, sv.M, sv.Z, w.partial, st, 0,
                         "aggregate_fwd", "aggregate_fwd.combine", H, h, h));
     // 6. out = Z Wo[type]
-    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, D, R32(sv.Z), R16(sv.Z), perm, 1, Wo32, Wo16, out, false, "node_linear_out", st));
+    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, &g->node_tiles_wide, D, R32(sv.Z), R16(sv.Z), perm, 1, Wo32, Wo16, out, false, "node_linear_out", st));
     return RGNN_OK;
 }
 

@@ -13,7 +13,8 @@ namespace rgnn {
 constexpr int kTileRows = 64;       // rows per typed-linear tile
 constexpr int kMaxChunks = 4096;    // tile chunks (workgroups) of the typed-linear kernels: several per resident
                                     // workgroup slot, so the hardware dispatcher evens out the tail
-constexpr int kWideChunks = 1024;   // chunk limit of the weight-gradient lists
+constexpr int kWideChunksPerCU = 3; // weight-gradient lists: one chunk per workgroup a compute unit can hold (three),
+                                    // so that every chunk is resident at once and none is left for a second round
 constexpr int kMinChunks = 512;     // fewer chunks than this only when there are fewer tiles
 constexpr int kChunkTiles = 8;      // tiles a chunk spans before the chunk count grows beyond kMinChunks
 constexpr int kItemMax = 256;       // longest traversal item (entries)

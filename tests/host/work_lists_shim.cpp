@@ -43,7 +43,7 @@ void wl_tiles_scalars(int32_t* out3) {
 }
 int wl_item_cut(long long total) { return rgnn::item_cut(total); }
 int wl_constant(int which) {
-    const int c[] = {rgnn::kTileRows, rgnn::kMaxChunks, rgnn::kWideChunks, rgnn::kMinChunks, rgnn::kChunkTiles,
+    const int c[] = {rgnn::kTileRows, rgnn::kMaxChunks, rgnn::kWideChunksPerCU, rgnn::kMinChunks, rgnn::kChunkTiles,
                      rgnn::kItemMax, rgnn::kItemTarget, rgnn::kSerialMax};
     return c[which];
 }
