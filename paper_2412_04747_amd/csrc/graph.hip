@@ -11,6 +11,8 @@
 #include <stdio.h>
 #include <string.h>
 #include <algorithm>
+#include <map>
+#include <mutex>
 #include <new>
 
 namespace rgnn {
@@ -21,6 +23,19 @@ void set_error(const char* fmt, ...) {
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
+}
+
+rgnn_status_t allow_dynamic_lds(const void* kernel, size_t bytes) {
+    static std::mutex mu;
+    static std::map<std::pair<const void*, int>, size_t> done;   // (kernel, device) -> limit already set
+    int dev = 0;
+    RGNN_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(mu);
+    size_t& have = done[{kernel, dev}];
+    if (have >= bytes) return RGNN_OK;
+    RGNN_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    have = bytes;
+    return RGNN_OK;
 }
 
 struct Uploader {

@@ -124,6 +124,9 @@ namespace rgnn {
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// Raises a kernel's dynamic LDS limit once per (kernel, device) instead of on every launch.
+rgnn_status_t allow_dynamic_lds(const void* kernel, size_t bytes);
+
 // ---- kernel launchers (typed_linear.hip) --------------------------------
 struct TypedLinearArgs {
     const TileList* tiles;

@@ -682,7 +682,7 @@ template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC>
 static rgnn_status_t launch_fwd_wave(const TypedLinearArgs& a, hipStream_t st) {
     const size_t lds = sizeof(float) * (KD * ND + 4 * 32 * ((KD > ND ? KD : ND) + 4));
     auto kern = typed_linear_fwd_wave_kernel<KD, ND, GATHER, SCATTER, ACCUM, VEC>;
-    RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W, a.Y,
                        a.vec, a.s_out);
@@ -703,7 +703,7 @@ static rgnn_status_t launch_fwd(const TypedLinearArgs& a, hipStream_t st) {
     }
     const size_t lds = sizeof(float) * (KD * ND + TM * (KD + 4) + TM * (ND + 4));
     auto kern = typed_linear_fwd_kernel<KD, ND>;
-    RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
                        a.Y, a.scatter_out, a.accumulate, a.vec, a.s_out);
@@ -738,7 +738,7 @@ static rgnn_status_t launch_bwd_wave(const TypedLinearBwdArgs& a, hipStream_t st
     static_assert(WREG >= KD * ND + KD, "per-wavefront LDS region must hold a weight-gradient copy");
     const size_t lds = sizeof(float) * (KD * (ND + 1) + 8 * WREG);
     auto kern = typed_linear_bwd_wave_kernel<KD, ND, GATHER, DYG, SCATTER, RS>;
-    RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(512), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
                        a.dY, a.dXrow, a.rowscale, a.vec, a.part);
@@ -763,7 +763,7 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
             constexpr int STG = (KD > ND ? KD : ND) + 4;
             const size_t lds = sizeof(float) * (KD * (ND + 1) + TM * STG + TM * (KD + 4) + TM + 256);
             auto kern = typed_linear_bwd_kernel<KD, ND>;
-            RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
             KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
             hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather,
                                a.W, a.dY, a.dy_gathered, a.dXrow, a.scatter_dx, a.rowscale, a.vec, a.part);

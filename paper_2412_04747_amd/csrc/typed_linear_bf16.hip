@@ -366,7 +366,7 @@ static rgnn_status_t launch_wgrad(const TypedLinearWgradBf16Args& a, hipStream_t
     constexpr int D = 128, NBUF = 1;
     const size_t lds = sizeof(unsigned short) * NBUF * (2 * D * 64);
     auto kern = typed_linear_wgrad_bf16_kernel<D, GATHER, DYG, NBUF>;
-    RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_wgrad");
     TileArgsB t{a.tiles->tile_seg, a.tiles->tile_row0, a.tiles->tile_row1, a.tiles->chunk_tile};
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.tiles->chunk_slot,
@@ -390,7 +390,7 @@ static rgnn_status_t launch(const TypedLinearBf16Args& a, hipStream_t st) {
     constexpr int LS = CD + 8, APL = A_BF16 ? 1 : 2, WPL = W_BF16 ? 1 : 2;
     const size_t lds = sizeof(unsigned short) * ((size_t)WPL * OD * LS + 4 * (APL * 32 * LS + 64));
     auto kern = typed_linear_bf16_kernel<CD, OD, A_BF16, W_BF16, WT, GATHER, SCATTER, Y_BF16, ACC>;
-    RGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_bf16");
     TileArgsB t{a.tiles->tile_seg, a.tiles->tile_row0, a.tiles->tile_row1, a.tiles->chunk_tile};
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.A, a.gather, a.W, a.Y);
