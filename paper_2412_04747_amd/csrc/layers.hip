@@ -121,7 +121,7 @@ size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
     w->tl_part = c.take<float>(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles));
     const size_t parts = std::max<size_t>({(size_t)g->pair_items.num_partials, (size_t)g->relrun_items.num_partials,
                                            (size_t)g->relpair_items.num_partials});
-    w->partial = c.take<float>(parts * std::max(d->d_in, d->d_out));
+    w->partial = c.take<float>(parts * std::max(d->d_in, d->d_out) * H);   // the run walk keeps one partial row per head
     return c.off;
 }
 
@@ -504,9 +504,8 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         RGNN_TRY(gather_sum(g->relpair_items, D, nullptr, nullptr, 0, w.ds_src, H, 0, sv.Hs, dw_s, w.partial, st, 2,
                             "src_vec_grad", "src_vec_grad.combine", H));
         // 6. U[h][r] = sum over r's runs of ds_dst[q][h] X[run_dst[q]];  dw_t and the w_t part of dW from it
-        for (int h = 0; h < H; ++h)
-            RGNN_TRY(gather_sum(g->relrun_items, K, g->idx[RGNN_IDX_RELRUN_IDX], g->idx[RGNN_IDX_RUN_DST], 1, w.ds_dst + h, H, 0,
-                                Xf, w.U + (size_t)h * g->R * K, w.partial, st, 2, "dst_side_wgrad", "dst_side_wgrad.combine"));
+        RGNN_TRY(gather_heads_rows(g->relrun_items, K, H, g->R, g->idx[RGNN_IDX_RELRUN_IDX], g->idx[RGNN_IDX_RUN_DST], 1, w.ds_dst,
+                                   Xf, w.U, w.partial, st, "dst_side_wgrad", "dst_side_wgrad.combine"));
         RGNN_TRY(rgat_heads_param_finish(g->R, K, D, H, Wf, wt, w.U, static_cast<float*>(dW), static_cast<float*>(dw_t), st));
         // 7. dX[u] = sum over u's pairs of dXp + sum over u's runs and heads of ds_dst[q][h] (W[r] w_t[r])_h
         RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, wt, w.wtp, st));

@@ -15,6 +15,10 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
                          const float* coef, int cstride, int cabs, const void* src, void* out, float* partial,
                          hipStream_t st, int role, const char* label, const char* combine_label, int heads = 1,
                          int src_bf16 = 0, int out_bf16 = 0);
+// H weighted sums of the same gathered rows in one walk (coef [entries][H]); out [H][out_rows][D]
+rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, const int32_t* via, const int32_t* rowidx,
+                                int row_by_k, const float* coef, const float* src, float* out, float* partial,
+                                hipStream_t st, const char* label, const char* combine_label);
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
                            const float* out, float slope, float* adz, float* G, float* ds_src, hipStream_t st);
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const float* ds_dst, const float* wtp,

@@ -346,6 +346,44 @@ __global__ __launch_bounds__(256) void gather_single_kernel(GatherArgs a, int fi
     }
 }
 
+// NH weighted sums of the same rows in one walk: out[h][row_i] = sum_j coef[k][h] * src[row], k and row as
+// in gather_sum_kernel (fp32 rows).  out is [NH][out_rows][D], the partial rows [NH][num_partials][D].
+template <int D, int NH>
+__global__ __launch_bounds__(256) void gather_heads_rows_kernel(GatherArgs a, int out_rows, int num_partials) {
+    constexpr int LPR = D / 4, IPB = 256 / LPR;
+    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
+    if (i >= a.it.n) return;
+    const float* __restrict__ src = static_cast<const float*>(a.src);
+    const int b = a.it.beg[i], e = a.it.end[i];
+    float4 acc[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) acc[h] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = b; j < e; j += 2) {
+        float4 x[2];
+        float c[2][NH];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int jj = min(j + u, e - 1);
+            const int k = a.via ? a.via[jj] : jj;
+            const int row = a.rowidx ? (a.row_by_k ? a.rowidx[k] : a.rowidx[jj]) : k;
+            x[u] = *reinterpret_cast<const float4*>(src + (size_t)row * D + c4 * 4);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) c[u][h] = j + u < e ? a.coef[(size_t)k * NH + h] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int h = 0; h < NH; ++h) fma4(acc[h], c[u][h], x[u]);
+    }
+    const int slot = a.it.slot[i];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        float* o = slot < 0 ? static_cast<float*>(a.out) + ((size_t)h * out_rows + a.it.row[i]) * D
+                            : a.partial + ((size_t)h * num_partials + slot) * D;
+        *reinterpret_cast<float4*>(o + c4 * 4) = acc[h];
+    }
+}
+
 // out[split_row[s]] = sum of partial rows [split_ptr[s], split_ptr[s+1]).  One workgroup per
 // cut segment: group g of D/4 lanes sums partial rows g, g + G, g + 2G, ... (two at a time),
 // then the G group sums are added in group order through LDS, so the summation order is fixed.
@@ -718,6 +756,34 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
             RGNN_DISPATCH_D(D, hipLaunchKernelGGL((combine_partials_kernel<DD, float>), dim3(L.num_split), dim3(1024), 0, st,
                                                   L.split_row, L.split_ptr, partial, static_cast<float*>(out)));
         RGNN_CHECK_LAUNCH();
+    }
+    return RGNN_OK;
+}
+
+rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, const int32_t* via, const int32_t* rowidx,
+                                int row_by_k, const float* coef, const float* src, float* out, float* partial,
+                                hipStream_t st, const char* label, const char* combine_label) {
+    if (L.num_items == 0) return RGNN_OK;
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, H, 0, 1, src, out, partial, 0, 0};
+    {
+        KernelTimer kt(st, label);
+        const dim3 grid(blocks_for(L.num_items, 256 / (D / 4)));
+#define RGNN_LAUNCH_NH(NH_) RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_heads_rows_kernel<DD, NH_>), grid, dim3(256), 0, st, a, out_rows, L.num_partials))
+        if (H == 2) RGNN_LAUNCH_NH(2);
+        else if (H == 4) RGNN_LAUNCH_NH(4);
+        else if (H == 8) RGNN_LAUNCH_NH(8);
+        else RGNN_FAIL(RGNN_EUNSUPPORTED, "gather_heads_rows: %d heads not built (2, 4, 8)", H);
+#undef RGNN_LAUNCH_NH
+        RGNN_CHECK_LAUNCH();
+    }
+    if (L.num_split > 0) {
+        KernelTimer kt(st, combine_label);
+        for (int h = 0; h < H; ++h) {
+            RGNN_DISPATCH_D(D, hipLaunchKernelGGL((combine_partials_kernel<DD, float>), dim3(L.num_split), dim3(1024), 0, st,
+                                                  L.split_row, L.split_ptr, partial + (size_t)h * L.num_partials * D,
+                                                  out + (size_t)h * out_rows * D));
+            RGNN_CHECK_LAUNCH();
+        }
     }
     return RGNN_OK;
 }
