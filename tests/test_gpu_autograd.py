@@ -118,3 +118,26 @@ def test_rgcn_then_hgt_modules_train():
     check(l1.W0.grad, g1["dW0"], 2 * TOL_F32, "rgcn dW0")
     A.release(g)
     g.close()
+
+
+def test_multi_head_function_matches_the_oracle():
+    import torch
+    from paper_2412_04747_amd import autograd as A
+    N, R, E, d, H = 700, 5, 6000, 64, 4
+    rng, src, dst, rel, _ = synth.tiny(303, N=N, R=R, E=E)
+    p = synth.rgat_params(rng, N, R, d, d)
+    print(f"autograd case rgat heads: N={N} R={R} E={E} d={d} H={H}", flush=True)
+    g = A.Graph(N, R, src, dst, rel)
+    t = lambda a: torch.tensor(a, dtype=torch.float32, device="cuda", requires_grad=True)
+    X, W, ws, wt = t(p["X"]), t(p["W"]), t(p["w_s"]), t(p["w_t"])
+    out = A.rgat(g, X, W, ws, wt, heads=H)
+    out.backward(torch.tensor(p["dOut"], dtype=torch.float32, device="cuda"))
+    torch.cuda.synchronize()
+    f = lambda a: np.asarray(a, dtype=np.float32).astype(np.float64)
+    want = O.rgat_heads_fwd(N, src, dst, rel, f(p["X"]), f(p["W"]), f(p["w_s"]), f(p["w_t"]), H)
+    wg = O.rgat_heads_bwd(N, src, dst, rel, f(p["X"]), f(p["W"]), f(p["w_s"]), f(p["w_t"]), f(p["dOut"]), H)
+    check(out, want, TOL_F32, "out")
+    for tns, k in ((X, "dX"), (W, "dW"), (ws, "dw_s"), (wt, "dw_t")):
+        check(tns.grad, wg[k], TOL_F32, k)
+    A.release(g)
+    g.close()
