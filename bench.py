@@ -31,19 +31,23 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
     r32 = d * 4                       # an fp32 row
     row = d * 2 if half else r32      # an input / intermediate row
     wb = 2 if half else 4             # element size of a given weight
-    if half:
-        rows = {"typed_linear": P, "pair_linear": P, "node_linear": N}
+    # width 128: the backward typed linear is two kernels, "<label>" = dY W^T and "<label>.wgrad"
+    # (bf16 rows: always; fp32 rows: wherever the rank-1 extras of single-head RGAT are not needed)
+    split = d == 128 and (half or layer != "rgat" or H > 1)
+    if split:
+        rows = {"typed_linear": P, "pair_linear": P, "node_linear": N, "self_loop": N}
         key = name.split(".")[0]
         n = next((v for k, v in rows.items() if key.startswith(k)), None)
-        if n is not None:
+        if n is not None and (half or key.endswith("_bwd")):
+            bound = "hbm" if half else "mfma"
             # one row in, one row out (or two rows in for the weight gradient), + the gather index
-            segs = T if key.startswith("node_linear") else R
+            segs = T if key.startswith("node_linear") else (1 if key.startswith("self_loop") else R)
             w2 = d * d * (4 if key.startswith("pair_linear") else wb)       # block-diagonal weights are fp32
             if name.endswith(".wgrad"):
-                return ("hbm", n * (2 * row + 4) + segs * d * d * 4, 2.0 * n * d * d)
+                return (bound, n * (2 * row + 4) + segs * d * d * 4, 2.0 * n * d * d)
             out_row = r32 if key in ("node_linear_out", "node_linear_k_bwd", "node_linear_q_bwd", "node_linear_v_bwd") else row
-            extra = r32 if key in ("node_linear_q_bwd", "node_linear_v_bwd") else 0   # accumulate into dX
-            return ("hbm", n * (row + out_row + extra + 4) + segs * w2, 2.0 * n * d * d)
+            extra = r32 if half and key in ("node_linear_q_bwd", "node_linear_v_bwd") else 0   # accumulate into dX
+            return (bound, n * (row + out_row + extra + 4) + segs * w2, 2.0 * n * d * d)
     w2 = d * d * 4
     pair_fwd = ("mfma", P * (2 * row + 4) + R * w2, 2.0 * P * d * d)        # gathered row + stored row + pair_src
     pair_bwd = ("mfma", P * (3 * row + 4) + R * w2, 4.0 * P * d * d)        # dY row + gathered row + stored row
@@ -192,6 +196,8 @@ def main():
                     help="synthetic workload id 1..5 (default 3 = the headline RGAT graph the metric is quoted on)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle leg (no cpu_baseline, no parity)")
+    ap.add_argument("--dtype", choices=("f32", "bf16"), default=None,
+                    help="override the storage type of the workload's inputs (the values stay the same)")
     ap.add_argument("--heads", type=int, default=0, help="RGAT workloads: number of attention heads (default 1)")
     ap.add_argument("--fwd-only", action="store_true",
                     help="time the forward call alone (inference: no saved buffer is kept)")
@@ -216,6 +222,12 @@ def main():
         return train_step_bench(args)
     t0 = time.time()
     c = synth.config(args.config, args.scale)
+    if args.dtype:
+        if args.dtype == "bf16" and c["dtype"] != "bf16":
+            for k, v in list(c.items()):
+                if isinstance(v, np.ndarray) and v.dtype == np.float32:
+                    c[k] = synth.round_to_bf16(v)
+        c["dtype"] = args.dtype
     if args.heads > 1:
         if c["layer"] != "rgat":
             sys.exit("bench.py --heads: only the RGAT workloads take a head count")

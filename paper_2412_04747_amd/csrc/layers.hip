@@ -240,16 +240,6 @@ rgnn_status_t tl_fwd(bool bf16, const rgnn::TileList* tiles, const rgnn::TileLis
     return typed_linear_fwd(d, d, a, st);
 }
 
-// "<label>.wgrad", with static storage (kernel-timer names must outlive the call)
-const char* wgrad_label(const char* label) {
-    static std::mutex mu;
-    static std::map<std::string, std::string> names;
-    std::lock_guard<std::mutex> lk(mu);
-    auto it = names.find(label);
-    if (it == names.end()) it = names.emplace(label, std::string(label) + ".wgrad").first;
-    return it->second.c_str();
-}
-
 // Backward typed linear: dXrow = dY W^T (rows through `gather` on both sides when `both_gathered`),
 // dW = sum X^T dY.
 //   rows16 (bf16 rows, width 128): X and dY are bf16; two kernels on the bf16 matrix cores (dY W^T with

@@ -16,6 +16,15 @@ static bool g_on = false;
 static std::vector<Record> g_rec;
 static std::mutex g_mu;
 
+const char* wgrad_label(const char* label) {
+    static std::mutex mu;
+    static std::map<std::string, std::string> names;
+    std::lock_guard<std::mutex> lk(mu);
+    auto it = names.find(label);
+    if (it == names.end()) it = names.emplace(label, std::string(label) + ".wgrad").first;
+    return it->second.c_str();
+}
+
 KernelTimer::KernelTimer(hipStream_t st, const char* name) : st_(st), idx_(-1) {
     if (!g_on) return;
     std::lock_guard<std::mutex> lk(g_mu);

@@ -124,6 +124,9 @@ namespace rgnn {
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// "<label>.wgrad", with static storage (kernel-timer names must outlive the call)
+const char* wgrad_label(const char* label);
+
 // Raises a kernel's dynamic LDS limit once per (kernel, device) instead of on every launch.
 rgnn_status_t allow_dynamic_lds(const void* kernel, size_t bytes);
 

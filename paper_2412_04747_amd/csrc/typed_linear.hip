@@ -361,7 +361,8 @@ __device__ __forceinline__ int run_end(const int32_t* __restrict__ tile_seg, int
 //   GATHER   rows are read through the gather list        SCATTER  outputs are written through it as well
 //   ACCUM    forward: Y += result                         VEC      forward: s_out = Y_row . vec[seg]
 //   DYG      backward: dY rows are read through the list  RS       backward: rowscale / Avec / xvec in use
-template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC>
+//   WT       multiply by W[seg]^T (W stored [ND][KD]): the input-gradient product dY W^T
+template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC, bool WT = false>
 __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, const float* __restrict__ X,
                                                                     const int32_t* __restrict__ gather,
                                                                     const float* __restrict__ W, float* __restrict__ Y,
@@ -386,9 +387,21 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
         const int ra = t.tile_row0[ta], rbnd = t.tile_row1[tb - 1];   // rows [ra, rbnd) of this segment
         const int nu = (rbnd - ra + 31) / 32;
         __syncthreads();                                    // every wavefront is done with the previous weight
-        {
+        if (!WT) {
             const float4* Wg = reinterpret_cast<const float4*>(W + (size_t)seg * KD * ND);
             for (int i = tid; i < KD * ND / 4; i += 64 * NW) reinterpret_cast<float4*>(Ws)[i] = Wg[i];
+        } else {
+            // Ws[k][n] = W[n][k]: neighbouring lanes take neighbouring n, so the LDS writes of a
+            // wavefront fall on different banks (the strided global reads hit the cache)
+            const float* Wg = W + (size_t)seg * KD * ND;
+            for (int i = tid; i < ND * (KD / 4); i += 64 * NW) {
+                const int n = i % ND, k4 = i / ND;
+                const float4 w4 = *reinterpret_cast<const float4*>(Wg + (size_t)n * KD + k4 * 4);
+                Ws[(k4 * 4 + 0) * ND + n] = w4.x;
+                Ws[(k4 * 4 + 1) * ND + n] = w4.y;
+                Ws[(k4 * 4 + 2) * ND + n] = w4.z;
+                Ws[(k4 * 4 + 3) * ND + n] = w4.w;
+            }
         }
         __syncthreads();
         float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -674,14 +687,113 @@ __global__ void slot_reduce_kernel(const float* __restrict__ part, const int32_t
 }
 
 // ---------------------------------------------------------------------------------------
+// Weight gradient alone, fp32, for width 128, where the fused backward kernel above no longer fits
+// (a wavefront cannot hold a 128 x 128 gradient):  part[slot] = sum over the chunk's rows of
+// X[g(i)]^T dY[i].  Four wavefronts; each owns a 32-feature band of X and all four 32-column blocks
+// of dY (64 accumulator registers), kept across the tiles of a segment.  The 64-row tile of X and of
+// dY sits row-major in LDS: the MFMA contracts over rows two at a time, so a lane's A operand is
+// X[row 2s + kh][band + m] and its B operand dY[row 2s + kh][block + m], both conflict-free 4-byte
+// reads.  The next tile's rows are in flight in registers while the current one is multiplied.
+template <int D, bool GATHER, bool DYG>
+__global__ __launch_bounds__(256) void typed_linear_wgrad_f32_kernel(TileArgs t, const float* __restrict__ X,
+                                                                     const int32_t* __restrict__ gather,
+                                                                     const float* __restrict__ dY,
+                                                                     float* __restrict__ part) {
+    static_assert(D == 128, "four wavefronts x four 32-column blocks");
+    constexpr int XS = D + 4;                              // LDS row stride
+    constexpr int LPR = D / 4, RPP = 256 / LPR, NL = 64 / RPP;   // lanes per row, rows per pass, passes per tile
+    constexpr int SLOT = D * D + D;
+    extern __shared__ __align__(16) float smem[];
+    float* Xt = smem;                                      // [64][XS]
+    float* Yt = smem + 64 * XS;                            // [64][XS]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 31, kh = lane >> 5;
+    const int cx = tid % LPR, rx = tid / LPR;
+    v16f acc[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+    const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
+    v4f xr[NL], yr[NL];
+    int gi[NL];
+#define RGNN_WF_FETCH_IDX(TI)                                                       \
+    {                                                                               \
+        const int row0_ = t.tile_row0[TI], row1_ = t.tile_row1[TI];                 \
+        _Pragma("unroll") for (int it = 0; it < NL; ++it) {                         \
+            const int row_ = min(row0_ + rx + it * RPP, row1_ - 1);                 \
+            gi[it] = GATHER ? gather[row_] : row_;                                  \
+        }                                                                           \
+    }
+#define RGNN_WF_FETCH(TI)                                                           \
+    {                                                                               \
+        const int row0_ = t.tile_row0[TI], row1_ = t.tile_row1[TI];                 \
+        _Pragma("unroll") for (int it = 0; it < NL; ++it) {                         \
+            xr[it] = *reinterpret_cast<const v4f*>(X + (size_t)gi[it] * D + cx * 4); \
+            const int row_ = min(row0_ + rx + it * RPP, row1_ - 1);                 \
+            const size_t s_ = (DYG && GATHER) ? (size_t)gi[it] : (size_t)row_;      \
+            yr[it] = *reinterpret_cast<const v4f*>(dY + s_ * D + cx * 4);           \
+        }                                                                           \
+    }
+    if (t0 < t1) {
+        RGNN_WF_FETCH_IDX(t0)
+        RGNN_WF_FETCH(t0)
+    }
+    if (t0 + 1 < t1) RGNN_WF_FETCH_IDX(t0 + 1)
+    int cur_seg = -1;
+    int slot = t.chunk_slot[blockIdx.x] - 1;
+    for (int ti = t0; ti <= t1; ++ti) {
+        const int seg = (ti < t1) ? t.tile_seg[ti] : -2;
+        if (seg != cur_seg) {
+            if (cur_seg >= 0) {   // flush: band `wave` of the gradient, four column blocks
+                float* ps = part + (size_t)slot * SLOT;
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        ps[(wave * 32 + acc_row(v, kh)) * D + b * 32 + m] = acc[b][v];
+                        acc[b][v] = 0.f;
+                    }
+                if (tid < D) ps[D * D + tid] = 0.f;      // the slot's vector part is not used here
+            }
+            if (ti == t1) break;
+            ++slot;
+            cur_seg = seg;
+        }
+        const int rows = t.tile_row1[ti] - t.tile_row0[ti];
+#pragma unroll
+        for (int it = 0; it < NL; ++it) {
+            const int r = rx + it * RPP;
+            const bool ok = r < rows;                      // rows past the end of the tile count as zeros
+            const v4f z = {0.f, 0.f, 0.f, 0.f};
+            *reinterpret_cast<v4f*>(Xt + r * XS + cx * 4) = ok ? xr[it] : z;
+            *reinterpret_cast<v4f*>(Yt + r * XS + cx * 4) = ok ? yr[it] : z;
+        }
+        __syncthreads();
+        if (ti + 1 < t1) RGNN_WF_FETCH(ti + 1)
+        if (ti + 2 < t1) RGNN_WF_FETCH_IDX(ti + 2)
+#pragma unroll 4
+        for (int s = 0; s < 32; ++s) {
+            const int r = 2 * s + kh;
+            const float a = Xt[r * XS + wave * 32 + m];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[b] = mfma32(a, Yt[r * XS + b * 32 + m], acc[b]);
+        }
+        __syncthreads();   // operand reads are done before the next tile is written
+    }
+#undef RGNN_WF_FETCH_IDX
+#undef RGNN_WF_FETCH
+}
+
+// ---------------------------------------------------------------------------------------
 static TileArgs tile_args(const TileList& t) {
     return TileArgs{t.tile_seg, t.tile_row0, t.tile_row1, t.chunk_tile, t.chunk_slot};
 }
 
-template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC>
+template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC, bool WT = false>
 static rgnn_status_t launch_fwd_wave(const TypedLinearArgs& a, hipStream_t st) {
     const size_t lds = sizeof(float) * (KD * ND + 4 * 32 * ((KD > ND ? KD : ND) + 4));
-    auto kern = typed_linear_fwd_wave_kernel<KD, ND, GATHER, SCATTER, ACCUM, VEC>;
+    auto kern = typed_linear_fwd_wave_kernel<KD, ND, GATHER, SCATTER, ACCUM, VEC, WT>;
     RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W, a.Y,
@@ -692,7 +804,7 @@ static rgnn_status_t launch_fwd_wave(const TypedLinearArgs& a, hipStream_t st) {
 
 template <int KD, int ND>
 static rgnn_status_t launch_fwd(const TypedLinearArgs& a, hipStream_t st) {
-    if constexpr (KD <= 64 && ND <= 64) {
+    {
         // the combinations the layers use
         const bool g = a.gather != nullptr, sc = g && a.scatter_out, ac = a.accumulate != 0, v = a.vec != nullptr;
         if (g && !sc && !ac && v) return launch_fwd_wave<KD, ND, true, false, false, true>(a, st);
@@ -746,10 +858,46 @@ static rgnn_status_t launch_bwd_wave(const TypedLinearBwdArgs& a, hipStream_t st
     return RGNN_OK;
 }
 
+// Width 128 without the rank-1 extras: dXrow = dY W^T with the forward wave kernel on the transposed
+// weight, then the weight-gradient kernel; two passes over dY, but both near the matrix cores' rate.
+template <int D>
+static rgnn_status_t launch_bwd_split(const TypedLinearBwdArgs& a, hipStream_t st) {
+    const bool g = a.gather != nullptr, dg = g && a.dy_gathered, sc = g && a.scatter_dx;
+    TypedLinearArgs f{};
+    f.tiles = a.tiles; f.X = a.dY; f.gather = dg ? a.gather : nullptr; f.W = a.W; f.Y = a.dXrow;
+    f.scatter_out = sc; f.label = a.label ? a.label : "typed_linear_bwd";
+    if (dg != sc) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: dY gathered and dXrow scattered must go together");
+    if (dg) RGNN_TRY((launch_fwd_wave<D, D, true, true, false, false, true>(f, st)));
+    else RGNN_TRY((launch_fwd_wave<D, D, false, false, false, false, true>(f, st)));
+    const size_t lds = sizeof(float) * 2 * 64 * (D + 4);
+    KernelTimer kt(st, wgrad_label(f.label));
+    if (g && dg) {
+        auto kern = typed_linear_wgrad_f32_kernel<D, true, true>;
+        RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
+        hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.dY, a.part);
+    } else if (g) {
+        auto kern = typed_linear_wgrad_f32_kernel<D, true, false>;
+        RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
+        hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.dY, a.part);
+    } else {
+        auto kern = typed_linear_wgrad_f32_kernel<D, false, false>;
+        RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
+        hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.dY, a.part);
+    }
+    RGNN_HIP(hipGetLastError());
+    return RGNN_OK;
+}
+
 template <int KD, int ND>
 static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
     if (a.tiles->num_tiles > 0) {
         bool done = false;
+        if constexpr (KD == 128 && ND == 128) {
+            if (!a.rowscale) {
+                RGNN_TRY(launch_bwd_split<128>(a, st));
+                done = true;
+            }
+        }
         if constexpr (KD <= 64 && ND <= 64) {
             const bool g = a.gather != nullptr, dg = g && a.dy_gathered, sc = g && a.scatter_dx, rs = a.rowscale != nullptr;
             done = true;
