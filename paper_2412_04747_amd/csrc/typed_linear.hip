@@ -4,10 +4,9 @@
 //                                                   rows are presorted by type so one weight serves a segment)
 // Backward  dXrow[i] = dY[i] W[seg(i)]^T,  dW[s] = sum_{i in s} X[gather[i]]^T dY[i]
 //
-// Rows are cut into 64-row tiles that never straddle a segment; a persistent workgroup of
-// four wavefronts walks a contiguous chunk of tiles and keeps the current segment's weight
-// in LDS, reloading it only when the segment changes.  The 64x64-wide products run on
-// v_mfma_f32_32x32x2_f32.  The K index of the MFMA is a free permutation, so each lane
+// Rows are cut into 64-row tiles that never straddle a segment; a persistent workgroup
+// walks a contiguous chunk of tiles and keeps the current segment's weight in LDS,
+// reloading it only when the segment changes.  The products run on v_mfma_f32_32x32x2_f32.  The K index of the MFMA is a free permutation, so each lane
 // reads its A operand as 16-byte LDS vectors: lane (m, half) owns k = half*K/2 + 0..K/2-1.
 #include "rgnn_internal.h"
 
@@ -37,120 +36,6 @@ struct TileArgs {
 };
 
 constexpr int TM = kTileRows;
-
-// ---------------------------------------------------------------------------------------
-// Forward.  Software pipeline per workgroup: the rows of tile t+1 are fetched from HBM
-// into registers while tile t is multiplied out of LDS, so the gather latency (index, then
-// row) hides behind the MFMAs and the epilogue.  Two barriers per tile: one after the
-// input tile is written to LDS, one after the accumulators are staged for the coalesced
-// 16-byte row stores.
-template <int KD, int ND>
-__global__ __launch_bounds__(256) void typed_linear_fwd_kernel(TileArgs t, const float* __restrict__ X,
-                                                               const int32_t* __restrict__ gather,
-                                                               const float* __restrict__ W, float* __restrict__ Y,
-                                                               int scatter_out, int accumulate,
-                                                               const float* __restrict__ vec, float* __restrict__ s_out) {
-    constexpr int XS = KD + 4, YS = ND + 4;
-    constexpr int CB = ND / 32, NBLK = 2 * CB, NBW = (NBLK + 3) / 4;
-    constexpr int LPRI = KD / 4, RPPI = 256 / LPRI, NX = TM / RPPI;   // input rows: lanes per row, rows per pass, passes
-    constexpr int LPRO = ND / 4, RPPO = 256 / LPRO;
-    extern __shared__ __align__(16) float smem[];
-    float* Ws = smem;                 // [KD][ND]
-    float* Xs = Ws + KD * ND;         // [TM][XS]
-    float* Ys = Xs + TM * XS;         // [TM][YS]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m = lane & 31, kh = lane >> 5, rb = wave & 1;
-    const int ci = tid % LPRI, ri = tid / LPRI;
-    const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
-    float4 xr[NX];
-    int gi[NX];   // source rows of the tile after the one held in xr (-1: past the segment end)
-    auto fetch_idx = [&](int ti) {
-        const int row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
-#pragma unroll
-        for (int it = 0; it < NX; ++it) {
-            const int row = row0 + ri + it * RPPI;
-            gi[it] = row < row1 ? (gather ? gather[row] : row) : -1;
-        }
-    };
-    auto fetch_rows = [&]() {
-#pragma unroll
-        for (int it = 0; it < NX; ++it) {
-            xr[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (gi[it] >= 0) xr[it] = *reinterpret_cast<const float4*>(X + (size_t)gi[it] * KD + ci * 4);
-        }
-    };
-    if (t0 < t1) { fetch_idx(t0); fetch_rows(); }
-    if (t0 + 1 < t1) fetch_idx(t0 + 1);
-    int cur_seg = -1;
-    for (int ti = t0; ti < t1; ++ti) {
-        const int seg = t.tile_seg[ti], row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
-        if (seg != cur_seg) {
-            const float4* Wg = reinterpret_cast<const float4*>(W + (size_t)seg * KD * ND);
-            for (int i = tid; i < KD * ND / 4; i += 256) reinterpret_cast<float4*>(Ws)[i] = Wg[i];
-            cur_seg = seg;
-        }
-#pragma unroll
-        for (int it = 0; it < NX; ++it)
-            *reinterpret_cast<float4*>(Xs + (ri + it * RPPI) * XS + ci * 4) = xr[it];
-        __syncthreads();
-        if (ti + 1 < t1) fetch_rows();      // rows of tile ti+1; their indices were requested a tile earlier
-        if (ti + 2 < t1) fetch_idx(ti + 2);
-        v16f acc[NBW];
-#pragma unroll
-        for (int b = 0; b < NBW; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
-        if (wave < NBLK) {
-#pragma unroll 2
-            for (int tt = 0; tt < KD / 8; ++tt) {
-                const int k0 = kh * (KD / 2) + 4 * tt;
-                const float4 a4 = *reinterpret_cast<const float4*>(Xs + (rb * 32 + m) * XS + k0);
-                const float av[4] = {a4.x, a4.y, a4.z, a4.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int b = 0; b < NBW; ++b) {
-                        const int cb = (wave >> 1) + 2 * b;
-                        acc[b] = mfma32(av[i], Ws[(k0 + i) * ND + cb * 32 + m], acc[b]);
-                    }
-            }
-#pragma unroll
-            for (int b = 0; b < NBW; ++b) {
-                const int cb = (wave >> 1) + 2 * b;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) Ys[(rb * 32 + acc_row(v, kh)) * YS + cb * 32 + m] = acc[b][v];
-            }
-        }
-        __syncthreads();
-        {
-            const int c4 = tid % LPRO;
-            float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (vec) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + c4 * 4);
-            for (int r = tid / LPRO; r < TM; r += RPPO) {
-                const int row = row0 + r;
-                const bool ok = row < row1;
-                float4 y = *reinterpret_cast<const float4*>(Ys + r * YS + c4 * 4);
-                if (ok) {
-                    const size_t d = (scatter_out && gather) ? (size_t)gather[row] : (size_t)row;
-                    float4* yp = reinterpret_cast<float4*>(Y + d * ND + c4 * 4);
-                    if (accumulate) {
-                        const float4 o = *yp;
-                        y.x += o.x; y.y += o.y; y.z += o.z; y.w += o.w;
-                    }
-                    *yp = y;
-                }
-                if (vec) {
-                    float s = y.x * wv.x + y.y * wv.y + y.z * wv.z + y.w * wv.w;
-#pragma unroll
-                    for (int o = LPRO / 2; o > 0; o >>= 1) s += __shfl_xor(s, o);
-                    if (ok && c4 == 0) s_out[row] = s;
-                }
-            }
-        }
-        // no barrier here: the next iteration's writes go to Xs (all MFMA reads of it are
-        // behind the barrier above) and Ys is rewritten only after the next barrier.
-    }
-}
 
 // ---------------------------------------------------------------------------------------
 // Backward tile:
@@ -804,23 +689,14 @@ static rgnn_status_t launch_fwd_wave(const TypedLinearArgs& a, hipStream_t st) {
 
 template <int KD, int ND>
 static rgnn_status_t launch_fwd(const TypedLinearArgs& a, hipStream_t st) {
-    {
-        // the combinations the layers use
-        const bool g = a.gather != nullptr, sc = g && a.scatter_out, ac = a.accumulate != 0, v = a.vec != nullptr;
-        if (g && !sc && !ac && v) return launch_fwd_wave<KD, ND, true, false, false, true>(a, st);
-        if (g && !sc && !ac && !v) return launch_fwd_wave<KD, ND, true, false, false, false>(a, st);
-        if (g && sc && !ac && !v) return launch_fwd_wave<KD, ND, true, true, false, false>(a, st);
-        if (!g && !ac && !v) return launch_fwd_wave<KD, ND, false, false, false, false>(a, st);
-        if (!g && ac && !v) return launch_fwd_wave<KD, ND, false, false, true, false>(a, st);
-    }
-    const size_t lds = sizeof(float) * (KD * ND + TM * (KD + 4) + TM * (ND + 4));
-    auto kern = typed_linear_fwd_kernel<KD, ND>;
-    RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
-    KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
-    hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
-                       a.Y, a.scatter_out, a.accumulate, a.vec, a.s_out);
-    RGNN_HIP(hipGetLastError());
-    return RGNN_OK;
+    // the combinations the layers use
+    const bool g = a.gather != nullptr, sc = g && a.scatter_out, ac = a.accumulate != 0, v = a.vec != nullptr;
+    if (g && !sc && !ac && v) return launch_fwd_wave<KD, ND, true, false, false, true>(a, st);
+    if (g && !sc && !ac && !v) return launch_fwd_wave<KD, ND, true, false, false, false>(a, st);
+    if (g && sc && !ac && !v) return launch_fwd_wave<KD, ND, true, true, false, false>(a, st);
+    if (!g && !ac && !v) return launch_fwd_wave<KD, ND, false, false, false, false>(a, st);
+    if (!g && ac && !v) return launch_fwd_wave<KD, ND, false, false, true, false>(a, st);
+    RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear forward: this combination of gather / scatter / accumulate / vec is not built");
 }
 
 rgnn_status_t typed_linear_fwd(int d_in, int d_out, const TypedLinearArgs& a, hipStream_t st) {
