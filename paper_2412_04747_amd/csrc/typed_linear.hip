@@ -35,181 +35,6 @@ struct TileArgs {
     const int32_t* chunk_slot;
 };
 
-constexpr int TM = kTileRows;
-
-// ---------------------------------------------------------------------------------------
-// Backward tile:
-//   dXrow[i]  = dY[i] W^T + rowscale[i] * xvec[seg]   (MFMA, contraction over the output features;
-//                                                     the rank-1 term is added when the row is stored)
-//   dW[seg]  += X_tile^T dY                           (MFMA, contraction over the tile's rows)
-//   Avec[seg]+= sum_i rowscale[i] X_tile[i]           (vector ALU)
-// With dY_eff = dY + rowscale (x) v, xvec = W v gives dXrow = dY_eff W^T exactly, and the caller
-// completes dW = X^T dY_eff by adding Avec^T (x) v.
-// dW and Avec stay in registers while consecutive tiles share a segment and are flushed to
-// the chunk's partial slot when the segment changes; a second kernel sums the slots of each
-// segment in slot order, so the result does not depend on scheduling.
-template <int KD, int ND>
-__global__ __launch_bounds__(256) void typed_linear_bwd_kernel(TileArgs t, const float* __restrict__ X,
-                                                               const int32_t* __restrict__ gather,
-                                                               const float* __restrict__ W,
-                                                               const float* __restrict__ dY, int dy_gathered,
-                                                               float* __restrict__ dXrow, int scatter_dx,
-                                                               const float* __restrict__ rowscale,
-                                                               const float* __restrict__ vec,
-                                                               float* __restrict__ part) {
-    constexpr int XS = KD + 4, YS = ND + 4, WS = ND + 1;
-    constexpr int STG = (XS > YS ? XS : YS);
-    constexpr int KB = KD / 32, NB = ND / 32;
-    constexpr int DBLK = 2 * KB, DBW = (DBLK + 3) / 4;   // dXrow blocks (row block, k block) per wave
-    constexpr int WBLK = KB * NB, WBW = (WBLK + 3) / 4;  // dW blocks (k block, n block) per wave
-    constexpr int AG = 256 / KD;                         // row groups of the Avec accumulation
-    constexpr int SLOT = KD * ND + KD;
-    extern __shared__ __align__(16) float smem[];
-    float* Ws = smem;                 // [KD][WS]
-    float* dYs = Ws + KD * WS;        // [TM][STG]  (also the dXrow stage)
-    float* Xs = dYs + TM * STG;       // [TM][XS]
-    float* dss = Xs + TM * XS;        // [TM]
-    float* red = dss + TM;            // [256]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m = lane & 31, kh = lane >> 5, rb = wave & 1;
-    v16f accw[WBW];
-#pragma unroll
-    for (int b = 0; b < WBW; ++b)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) accw[b][v] = 0.f;
-    float acca = 0.f;
-    int cur_seg = -1;
-    int slot = t.chunk_slot[blockIdx.x] - 1;
-    const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
-    for (int ti = t0; ti <= t1; ++ti) {
-        const int seg = (ti < t1) ? t.tile_seg[ti] : -2;
-        if (seg != cur_seg) {
-            if (cur_seg >= 0) {  // flush the finished segment's partial sums
-                float* ps = part + (size_t)slot * SLOT;
-                if (wave < WBLK) {
-#pragma unroll
-                    for (int b = 0; b < WBW; ++b) {
-                        const int blk = wave + 4 * b, kb = blk % KB, nb = blk / KB;
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            ps[(kb * 32 + acc_row(v, kh)) * ND + nb * 32 + m] = accw[b][v];
-                            accw[b][v] = 0.f;
-                        }
-                    }
-                }
-                red[tid] = acca;
-                acca = 0.f;
-                __syncthreads();
-                if (tid < KD) {
-                    float s = 0.f;
-#pragma unroll
-                    for (int g2 = 0; g2 < AG; ++g2) s += red[g2 * KD + tid];
-                    ps[KD * ND + tid] = s;
-                }
-                __syncthreads();
-            }
-            if (ti == t1) break;
-            ++slot;
-            const float* Wg = W + (size_t)seg * KD * ND;
-            for (int i = tid; i < KD * ND; i += 256) Ws[(i / ND) * WS + (i % ND)] = Wg[i];
-            cur_seg = seg;
-        }
-        const int row0 = t.tile_row0[ti], row1 = t.tile_row1[ti];
-        if (tid < TM) dss[tid] = (rowscale && row0 + tid < row1) ? rowscale[row0 + tid] : 0.f;
-        {
-            constexpr int LPR = KD / 4, RPP = 256 / LPR;
-            const int c4 = tid % LPR;
-            for (int r = tid / LPR; r < TM; r += RPP) {
-                const int row = row0 + r;
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (row < row1) {
-                    const size_t s = gather ? (size_t)gather[row] : (size_t)row;
-                    v = *reinterpret_cast<const float4*>(X + s * KD + c4 * 4);
-                }
-                *reinterpret_cast<float4*>(Xs + r * XS + c4 * 4) = v;
-            }
-        }
-        {
-            constexpr int LPR = ND / 4, RPP = 256 / LPR;
-            const int c4 = tid % LPR;
-            for (int r = tid / LPR; r < TM; r += RPP) {
-                const int row = row0 + r;
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (row < row1) {
-                    const size_t s = (dy_gathered && gather) ? (size_t)gather[row] : (size_t)row;
-                    v = *reinterpret_cast<const float4*>(dY + s * ND + c4 * 4);
-                }
-                *reinterpret_cast<float4*>(dYs + r * STG + c4 * 4) = v;
-            }
-        }
-        __syncthreads();
-        // dXrow tile: rows x KD, contraction over n
-        v16f accx[DBW];
-#pragma unroll
-        for (int b = 0; b < DBW; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) accx[b][v] = 0.f;
-        if (wave < DBLK) {
-#pragma unroll 2
-            for (int tt = 0; tt < ND / 8; ++tt) {
-                const int n0 = kh * (ND / 2) + 4 * tt;
-                const float4 a4 = *reinterpret_cast<const float4*>(dYs + (rb * 32 + m) * STG + n0);
-                const float av[4] = {a4.x, a4.y, a4.z, a4.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int b = 0; b < DBW; ++b) {
-                        const int cb = (wave >> 1) + 2 * b;
-                        accx[b] = mfma32(av[i], Ws[(cb * 32 + m) * WS + n0 + i], accx[b]);
-                    }
-            }
-        }
-        // dW blocks: KD x ND, contraction over the tile's rows (two rows per MFMA)
-        if (wave < WBLK) {
-#pragma unroll 4
-            for (int s = 0; s < TM / 2; ++s) {
-                const int r = 2 * s + kh;
-#pragma unroll
-                for (int b = 0; b < WBW; ++b) {
-                    const int blk = wave + 4 * b, kb = blk % KB, nb = blk / KB;
-                    accw[b] = mfma32(Xs[r * XS + kb * 32 + m], dYs[r * STG + nb * 32 + m], accw[b]);
-                }
-            }
-        }
-        if (rowscale) {
-            const int k = tid % KD;
-            for (int r = tid / KD; r < TM; r += AG) acca += dss[r] * Xs[r * XS + k];
-        }
-        __syncthreads();  // all reads of dYs done; reuse it to stage dXrow
-        if (wave < DBLK) {
-#pragma unroll
-            for (int b = 0; b < DBW; ++b) {
-                const int cb = (wave >> 1) + 2 * b;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) dYs[(rb * 32 + acc_row(v, kh)) * STG + cb * 32 + m] = accx[b][v];
-            }
-        }
-        __syncthreads();
-        {
-            constexpr int LPR = KD / 4, RPP = 256 / LPR;
-            const int c4 = tid % LPR;
-            float4 xv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (rowscale && vec) xv = *reinterpret_cast<const float4*>(vec + (size_t)seg * KD + c4 * 4);
-            for (int r = tid / LPR; r < TM; r += RPP) {
-                const int row = row0 + r;
-                if (row < row1) {
-                    const size_t d = (scatter_dx && gather) ? (size_t)gather[row] : (size_t)row;
-                    float4 o = *reinterpret_cast<const float4*>(dYs + r * STG + c4 * 4);
-                    const float sc = dss[r];
-                    o.x += sc * xv.x; o.y += sc * xv.y; o.z += sc * xv.z; o.w += sc * xv.w;
-                    *reinterpret_cast<float4*>(dXrow + d * KD + c4 * 4) = o;
-                }
-            }
-        }
-        __syncthreads();
-    }
-}
-
 // ---------------------------------------------------------------------------------------
 // Wave-independent kernels (feature widths up to 64).
 //
@@ -247,12 +72,14 @@ __device__ __forceinline__ int run_end(const int32_t* __restrict__ tile_seg, int
 //   ACCUM    forward: Y += result                         VEC      forward: s_out = Y_row . vec[seg]
 //   DYG      backward: dY rows are read through the list  RS       backward: rowscale / Avec / xvec in use
 //   WT       multiply by W[seg]^T (W stored [ND][KD]): the input-gradient product dY W^T
-template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC, bool WT = false>
+//   ADDV     Y_row += rowscale[row] * vec[seg]  (the rank-1 part of single-head RGAT's input gradient)
+template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC, bool WT = false, bool ADDV = false>
 __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, const float* __restrict__ X,
                                                                     const int32_t* __restrict__ gather,
                                                                     const float* __restrict__ W, float* __restrict__ Y,
                                                                     const float* __restrict__ vec,
-                                                                    float* __restrict__ s_out) {
+                                                                    float* __restrict__ s_out,
+                                                                    const float* __restrict__ rowscale) {
     constexpr int NW = 4;                                   // wavefronts per workgroup
     constexpr int XS = (KD > ND ? KD : ND) + 4;             // row stride of the per-wave stage
     constexpr int CB = ND / 32;
@@ -290,7 +117,7 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
         }
         __syncthreads();
         float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (VEC) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + co * 4);
+        if (VEC || ADDV) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + co * 4);
         // Rows past the end of the run are clamped to its last row, so every load below is
         // unconditional; what they bring in is never stored.
         v4f xr[NX];
@@ -350,6 +177,10 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
                     const float4 o = *yp;
                     y.x += o.x; y.y += o.y; y.z += o.z; y.w += o.w;
                 }
+                if (ADDV) {
+                    const float sc = rowscale[min(row, rbnd - 1)];
+                    y.x += sc * wv.x; y.y += sc * wv.y; y.z += sc * wv.z; y.w += sc * wv.w;
+                }
                 if (ok) *yp = y;
                 if (VEC) {
                     float sdot = y.x * wv.x + y.y * wv.y + y.z * wv.z + y.w * wv.w;
@@ -366,6 +197,14 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
     }
 }
 
+// Backward of a segment's rows:
+//   dXrow[i]  = dY[i] W^T + rowscale[i] * xvec[seg]   (MFMA, contraction over the output features;
+//                                                     the rank-1 term is added when the row is stored)
+//   dW[seg]   = sum_i X[g(i)]^T dY[i]                 (MFMA, contraction over the rows)
+//   Avec[seg] = sum_i rowscale[i] X[g(i)]             (vector ALU)
+// With dY_eff = dY + rowscale (x) v, xvec = W v gives dXrow = dY_eff W^T exactly, and the caller
+// completes dW = X^T dY_eff by adding Avec^T (x) v; dY_eff itself is never formed.
+//
 // Backward, wave-independent: eight wavefronts per workgroup, each owning 32-row units of
 // the run.  Per unit a wavefront forms dXrow = dY W^T (+ rowscale (x) xvec) and adds its
 // rows' contribution to the full KD x ND weight gradient (KB*NB blocks, kept in registers
@@ -579,10 +418,12 @@ __global__ void slot_reduce_kernel(const float* __restrict__ part, const int32_t
 // dY sits row-major in LDS: the MFMA contracts over rows two at a time, so a lane's A operand is
 // X[row 2s + kh][band + m] and its B operand dY[row 2s + kh][block + m], both conflict-free 4-byte
 // reads.  The next tile's rows are in flight in registers while the current one is multiplied.
-template <int D, bool GATHER, bool DYG>
+// RS: the slot's vector part gets sum over the rows of rowscale[i] * X[g(i)] (otherwise zeros).
+template <int D, bool GATHER, bool DYG, bool RS>
 __global__ __launch_bounds__(256) void typed_linear_wgrad_f32_kernel(TileArgs t, const float* __restrict__ X,
                                                                      const int32_t* __restrict__ gather,
                                                                      const float* __restrict__ dY,
+                                                                     const float* __restrict__ rowscale,
                                                                      float* __restrict__ part) {
     static_assert(D == 128, "four wavefronts x four 32-column blocks");
     constexpr int XS = D + 4;                              // LDS row stride
@@ -602,6 +443,8 @@ __global__ __launch_bounds__(256) void typed_linear_wgrad_f32_kernel(TileArgs t,
     const int t0 = t.chunk_tile[blockIdx.x], t1 = t.chunk_tile[blockIdx.x + 1];
     v4f xr[NL], yr[NL];
     int gi[NL];
+    float rs[NL];
+    v4f avec = {0.f, 0.f, 0.f, 0.f};                      // this thread's share of the vector part (columns 4 cx ..)
 #define RGNN_WF_FETCH_IDX(TI)                                                       \
     {                                                                               \
         const int row0_ = t.tile_row0[TI], row1_ = t.tile_row1[TI];                 \
@@ -618,6 +461,7 @@ __global__ __launch_bounds__(256) void typed_linear_wgrad_f32_kernel(TileArgs t,
             const int row_ = min(row0_ + rx + it * RPP, row1_ - 1);                 \
             const size_t s_ = (DYG && GATHER) ? (size_t)gi[it] : (size_t)row_;      \
             yr[it] = *reinterpret_cast<const v4f*>(dY + s_ * D + cx * 4);           \
+            if (RS) rs[it] = rowscale[row_];                                        \
         }                                                                           \
     }
     if (t0 < t1) {
@@ -639,7 +483,21 @@ __global__ __launch_bounds__(256) void typed_linear_wgrad_f32_kernel(TileArgs t,
                         ps[(wave * 32 + acc_row(v, kh)) * D + b * 32 + m] = acc[b][v];
                         acc[b][v] = 0.f;
                     }
-                if (tid < D) ps[D * D + tid] = 0.f;      // the slot's vector part is not used here
+                if (RS) {   // the eight threads sharing a column group add their shares in order, through LDS
+                    __syncthreads();
+                    *reinterpret_cast<v4f*>(Xt + rx * XS + cx * 4) = avec;
+                    avec = v4f{0.f, 0.f, 0.f, 0.f};
+                    __syncthreads();
+                    if (tid < D) {
+                        float sum = 0.f;
+#pragma unroll
+                        for (int r = 0; r < RPP; ++r) sum += Xt[r * XS + tid];
+                        ps[D * D + tid] = sum;
+                    }
+                    __syncthreads();
+                } else if (tid < D) {
+                    ps[D * D + tid] = 0.f;
+                }
             }
             if (ti == t1) break;
             ++slot;
@@ -653,6 +511,7 @@ __global__ __launch_bounds__(256) void typed_linear_wgrad_f32_kernel(TileArgs t,
             const v4f z = {0.f, 0.f, 0.f, 0.f};
             *reinterpret_cast<v4f*>(Xt + r * XS + cx * 4) = ok ? xr[it] : z;
             *reinterpret_cast<v4f*>(Yt + r * XS + cx * 4) = ok ? yr[it] : z;
+            if (RS && ok) avec += rs[it] * xr[it];
         }
         __syncthreads();
         if (ti + 1 < t1) RGNN_WF_FETCH(ti + 1)
@@ -675,14 +534,14 @@ static TileArgs tile_args(const TileList& t) {
     return TileArgs{t.tile_seg, t.tile_row0, t.tile_row1, t.chunk_tile, t.chunk_slot};
 }
 
-template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC, bool WT = false>
-static rgnn_status_t launch_fwd_wave(const TypedLinearArgs& a, hipStream_t st) {
+template <int KD, int ND, bool GATHER, bool SCATTER, bool ACCUM, bool VEC, bool WT = false, bool ADDV = false>
+static rgnn_status_t launch_fwd_wave(const TypedLinearArgs& a, hipStream_t st, const float* rowscale = nullptr) {
     const size_t lds = sizeof(float) * (KD * ND + 4 * 32 * ((KD > ND ? KD : ND) + 4));
-    auto kern = typed_linear_fwd_wave_kernel<KD, ND, GATHER, SCATTER, ACCUM, VEC, WT>;
+    auto kern = typed_linear_fwd_wave_kernel<KD, ND, GATHER, SCATTER, ACCUM, VEC, WT, ADDV>;
     RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W, a.Y,
-                       a.vec, a.s_out);
+                       a.vec, a.s_out, rowscale);
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -734,32 +593,34 @@ static rgnn_status_t launch_bwd_wave(const TypedLinearBwdArgs& a, hipStream_t st
     return RGNN_OK;
 }
 
-// Width 128 without the rank-1 extras: dXrow = dY W^T with the forward wave kernel on the transposed
-// weight, then the weight-gradient kernel; two passes over dY, but both near the matrix cores' rate.
+// Width 128: dXrow = dY W^T (+ rowscale (x) vec) with the forward wave kernel on the transposed weight,
+// then the weight-gradient kernel; two passes over dY, but both near the matrix cores' rate.
 template <int D>
 static rgnn_status_t launch_bwd_split(const TypedLinearBwdArgs& a, hipStream_t st) {
-    const bool g = a.gather != nullptr, dg = g && a.dy_gathered, sc = g && a.scatter_dx;
+    const bool g = a.gather != nullptr, dg = g && a.dy_gathered, sc = g && a.scatter_dx, rs = a.rowscale != nullptr;
     TypedLinearArgs f{};
     f.tiles = a.tiles; f.X = a.dY; f.gather = dg ? a.gather : nullptr; f.W = a.W; f.Y = a.dXrow;
-    f.scatter_out = sc; f.label = a.label ? a.label : "typed_linear_bwd";
+    f.scatter_out = sc; f.vec = a.vec; f.label = a.label ? a.label : "typed_linear_bwd";
     if (dg != sc) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: dY gathered and dXrow scattered must go together");
-    if (dg) RGNN_TRY((launch_fwd_wave<D, D, true, true, false, false, true>(f, st)));
+    if (rs && (dg || !a.vec)) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: rowscale needs vec and ungathered dY");
+    if (rs) RGNN_TRY((launch_fwd_wave<D, D, false, false, false, false, true, true>(f, st, a.rowscale)));
+    else if (dg) RGNN_TRY((launch_fwd_wave<D, D, true, true, false, false, true>(f, st)));
     else RGNN_TRY((launch_fwd_wave<D, D, false, false, false, false, true>(f, st)));
     const size_t lds = sizeof(float) * 2 * 64 * (D + 4);
     KernelTimer kt(st, wgrad_label(f.label));
-    if (g && dg) {
-        auto kern = typed_linear_wgrad_f32_kernel<D, true, true>;
-        RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
-        hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.dY, a.part);
-    } else if (g) {
-        auto kern = typed_linear_wgrad_f32_kernel<D, true, false>;
-        RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
-        hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.dY, a.part);
-    } else {
-        auto kern = typed_linear_wgrad_f32_kernel<D, false, false>;
-        RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
-        hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.dY, a.part);
+#define RGNN_LAUNCH_WGRAD(G_, DG_, RS_)                                                                              \
+    {                                                                                                                \
+        auto kern = typed_linear_wgrad_f32_kernel<D, G_, DG_, RS_>;                                                  \
+        RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));                                       \
+        hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, \
+                           a.dY, a.rowscale, a.part);                                                                \
     }
+    if (g && dg) RGNN_LAUNCH_WGRAD(true, true, false)
+    else if (g && rs) RGNN_LAUNCH_WGRAD(true, false, true)
+    else if (g) RGNN_LAUNCH_WGRAD(true, false, false)
+    else if (!rs) RGNN_LAUNCH_WGRAD(false, false, false)
+    else RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: rowscale needs gathered X");
+#undef RGNN_LAUNCH_WGRAD
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -769,10 +630,8 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
     if (a.tiles->num_tiles > 0) {
         bool done = false;
         if constexpr (KD == 128 && ND == 128) {
-            if (!a.rowscale) {
-                RGNN_TRY(launch_bwd_split<128>(a, st));
-                done = true;
-            }
+            RGNN_TRY(launch_bwd_split<128>(a, st));
+            done = true;
         }
         if constexpr (KD <= 64 && ND <= 64) {
             const bool g = a.gather != nullptr, dg = g && a.dy_gathered, sc = g && a.scatter_dx, rs = a.rowscale != nullptr;
@@ -783,16 +642,7 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
             else if (!g && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, false, false, false, false>(a, st)));
             else done = false;
         }
-        if (!done) {
-            constexpr int STG = (KD > ND ? KD : ND) + 4;
-            const size_t lds = sizeof(float) * (KD * (ND + 1) + TM * STG + TM * (KD + 4) + TM + 256);
-            auto kern = typed_linear_bwd_kernel<KD, ND>;
-            RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
-            KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
-            hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather,
-                               a.W, a.dY, a.dy_gathered, a.dXrow, a.scatter_dx, a.rowscale, a.vec, a.part);
-            RGNN_HIP(hipGetLastError());
-        }
+        if (!done) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: this combination of gather / scatter / rowscale is not built");
     }
     return launch_slot_reduce(KD, ND, a, st);
 }
