@@ -361,6 +361,18 @@ def main():
                 roof["traffic"] = float(f[1]) + float(f[2])
     roof["avg_ms"] = dom["avg_ms"]
     roof["algorithmic_bytes"] = w[1] if w else None
+    # the same for the forward edge-traversal kernel (weighted gather-sum over the destination-major CSR),
+    # the HBM-bound counterpart of the typed linear
+    trav = next((k for k in kernels if k["name"] == "aggregate_fwd" and "GBps" in k), None)
+    roof_trav = None
+    if trav:
+        roof_trav = {"kernel": "aggregate_fwd", "bound": "hbm", "achieved": trav["GBps"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": trav["GBps"] / HBM_PEAK_GBS, "traffic": None, "avg_ms": trav["avg_ms"]}
+        if args.config == 3 and args.scale == 1.0 and os.path.exists(tsv):
+            for ln in open(tsv):
+                f = ln.rstrip("\n").split("\t")
+                if not ln.startswith("#") and f[0] == "aggregate_fwd":
+                    roof_trav["traffic"] = float(f[1]) + float(f[2])
 
     line = {
         "metric": f"edges/sec for {c['layer'].upper()} layer {'fwd' if fwd_only else 'fwd+bwd'}",
@@ -375,6 +387,7 @@ def main():
                                + ("" if args.scale == 1.0 else f" (scale {args.scale})"),
                    "P_over_E": P / E, "Q_over_E": Q / E, "max_in_degree": int(g.info.max_in_degree)},
         "roofline": roof,
+        "roofline_traversal": roof_trav,
         "cpu_baseline": cpu,
         "ms_per_step_without_profiling_events": clean_ms,
         "parity_max_rel_err": parity,
