@@ -83,6 +83,7 @@ static void build_items(Uploader& U, ItemList& L, const std::vector<int32_t>& pt
     const ItemPlan p = plan_items(ptr, max_len, min_len);
     L.num_items = (int32_t)p.beg.size(); L.num_partials = p.num_partials; L.num_split = p.num_split;
     L.first_single = p.first_single; L.num_single = p.num_single;
+    L.first_short = p.first_short; L.num_short = p.num_short;
     L.beg = U.up(p.beg); L.end = U.up(p.end); L.row = U.up(p.row); L.slot = U.up(p.slot);
     L.split_row = U.up(p.split_row); L.split_ptr = U.up(p.split_ptr);
     L.part_item = U.up(p.part_item); L.part_split = U.up(p.part_split);

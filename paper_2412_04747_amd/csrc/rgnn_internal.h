@@ -82,6 +82,8 @@ struct ItemList {
     int32_t* part_split = nullptr; // [num_partials] index into split_* of its segment
     int32_t first_single = 0;      // items [first_single, first_single + num_single) are the whole segments
     int32_t num_single = 0;        // with exactly one entry
+    int32_t first_short = 0;       // items [first_short, first_short + num_short) are the whole segments with
+    int32_t num_short = 0;         // 2..kShortLen entries; the single-entry ones follow directly
 };
 
 }  // namespace rgnn

@@ -306,6 +306,54 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
     else store_cols(a.partial + (size_t)slot * D + cv * V, acc0);
 }
 
+// The whole segments with 2..kShortLen entries, items [first, first + n).  One batch of row loads covers
+// such a segment, so the general kernel would spend its time on the item -> indices -> rows -> store
+// chain; here a group of lanes takes two of them at a time, all loads of both independent (entries
+// past a segment's end repeat its last one with a zero coefficient).
+template <int D, int ROLE, typename TI, typename TO>
+__global__ __launch_bounds__(256) void gather_short_kernel(GatherArgs a, int first, int n) {
+    constexpr int V = RowT<TI>::V, LPR = D / V, GPB = 256 / LPR;
+    const int g = blockIdx.x * GPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
+    const int i0 = 2 * g;
+    if (i0 >= n) return;
+    const TI* __restrict__ src = static_cast<const TI*>(a.src);
+    const int head = cv / a.lanes_per_head;
+    int b[2], e[2], orow[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int i = first + min(i0 + q, n - 1);
+        b[q] = a.it.beg[i];
+        e[q] = a.it.end[i];
+        orow[q] = a.it.row[i];
+    }
+    int row[2][kShortLen];
+    float c[2][kShortLen];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int u = 0; u < kShortLen; ++u) {
+            const int jj = min(b[q] + u, e[q] - 1);
+            const int k = a.via ? a.via[jj] : jj;
+            row[q][u] = a.rowidx ? (a.row_by_k ? a.rowidx[k] : a.rowidx[jj]) : k;
+            float cc = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;
+            if (a.cabs) cc = fabsf(cc);
+            c[q][u] = b[q] + u < e[q] ? cc : 0.f;
+        }
+    float v[2][kShortLen][V];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int u = 0; u < kShortLen; ++u) load_cols(src + (size_t)row[q][u] * D + cv * V, v[q][u]);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        float acc[V];
+        zero_cols(acc);
+#pragma unroll
+        for (int u = 0; u < kShortLen; ++u) fma_cols(acc, c[q][u], v[q][u]);
+        if (i0 + q < n) store_cols(static_cast<TO*>(a.out) + (size_t)orow[q] * D + cv * V, acc);
+    }
+}
+
 // The whole segments with exactly one entry, items [first, first + n): out[row_i] = c * src[row].
 // A group of lanes handles four of them at a time, all loads of the four independent, which keeps
 // enough rows in flight where the general kernel would wait on one short dependent chain per item.
@@ -723,29 +771,31 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
                          int src_bf16, int out_bf16) {
     if (L.num_items == 0) return RGNN_OK;
     const int lpr = D / (src_bf16 ? 8 : 4);
-    // enough single-entry segments to be worth a launch of their own
+    // enough short / single-entry segments to be worth launches of their own; the two ranges are adjacent
     const int ns = L.num_single >= 4096 ? L.num_single : 0;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, L.first_single, ns};
+    const int nsh = L.num_short >= 4096 ? L.num_short : 0;
+    const int skip_first = nsh > 0 ? L.first_short : L.first_single;
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns};
     {
         KernelTimer kt(st, label);
-        const dim3 grid(blocks_for(L.num_items - ns, 256 / lpr));
-        if (role == 0)
-            RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_sum_kernel<DD, 0, TI, TO>), grid, dim3(256), 0, st, a));
-        else if (role == 1)
-            RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_sum_kernel<DD, 1, TI, TO>), grid, dim3(256), 0, st, a));
-        else
-            RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_sum_kernel<DD, 2, TI, TO>), grid, dim3(256), 0, st, a));
-        RGNN_CHECK_LAUNCH();
+        const dim3 grid(blocks_for(L.num_items - nsh - ns, 256 / lpr));
+#define RGNN_LAUNCH_GATHER(KERNEL, GRID, ...)                                                                              \
+    do {                                                                                                                   \
+        if (role == 0) RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((KERNEL<DD, 0, TI, TO>), GRID, dim3(256), 0, st, __VA_ARGS__)); \
+        else if (role == 1) RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((KERNEL<DD, 1, TI, TO>), GRID, dim3(256), 0, st, __VA_ARGS__)); \
+        else RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((KERNEL<DD, 2, TI, TO>), GRID, dim3(256), 0, st, __VA_ARGS__)); \
+        RGNN_CHECK_LAUNCH();                                                                                               \
+    } while (0)
+        if (L.num_items - nsh - ns > 0) RGNN_LAUNCH_GATHER(gather_sum_kernel, grid, a);
+        if (nsh > 0) {
+            const dim3 hgrid(blocks_for((size_t)(nsh + 1) / 2, 256 / lpr));
+            RGNN_LAUNCH_GATHER(gather_short_kernel, hgrid, a, L.first_short, nsh);
+        }
         if (ns > 0) {
             const dim3 sgrid(blocks_for((size_t)(ns + 3) / 4, 256 / lpr));
-            if (role == 0)
-                RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_single_kernel<DD, 0, TI, TO>), sgrid, dim3(256), 0, st, a, L.first_single, ns));
-            else if (role == 1)
-                RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_single_kernel<DD, 1, TI, TO>), sgrid, dim3(256), 0, st, a, L.first_single, ns));
-            else
-                RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((gather_single_kernel<DD, 2, TI, TO>), sgrid, dim3(256), 0, st, a, L.first_single, ns));
-            RGNN_CHECK_LAUNCH();
+            RGNN_LAUNCH_GATHER(gather_single_kernel, sgrid, a, L.first_single, ns);
         }
+#undef RGNN_LAUNCH_GATHER
     }
     if (L.num_split > 0) {
         KernelTimer kt(st, combine_label);

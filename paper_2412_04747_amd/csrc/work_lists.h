@@ -77,10 +77,14 @@ inline TilePlan plan_tiles(const std::vector<int32_t>& seg_ptr, int tile_rows, i
 // elsewhere).  Items are ordered by length, longest first (stable): the lanes of a wavefront and
 // the wavefronts of a workgroup then walk items of equal length and finish together, and the
 // long items are scheduled before the short ones fill the tail.  Among items of equal length
-// the pieces of cut segments come first, so the whole segments with exactly one entry form one
-// contiguous range [first_single, first_single + num_single), which has a kernel of its own.
+// the pieces of cut segments come first; pieces of at most kShortLen entries all come before the
+// whole segments of that size.  So the whole segments with 2..kShortLen entries form one
+// contiguous range [first_short, first_short + num_short), directly followed by those with
+// exactly one entry, [first_single, first_single + num_single); both have kernels of their own.
+constexpr int kShortLen = 4;
+
 struct ItemPlan {
-    int32_t num_partials = 0, num_split = 0, first_single = 0, num_single = 0;
+    int32_t num_partials = 0, num_split = 0, first_single = 0, num_single = 0, first_short = 0, num_short = 0;
     std::vector<int32_t> beg, end, row, slot;      // [num_items]
     std::vector<int32_t> split_row, split_ptr;     // [num_split], [num_split + 1] range of partial rows
     std::vector<int32_t> part_item, part_split;    // [num_partials] item writing the partial row; index into split_*
@@ -111,8 +115,14 @@ inline ItemPlan plan_items(const std::vector<int32_t>& ptr, int max_len, int min
     const int n = (int)L.beg.size();
     int longest = 0;
     for (int i = 0; i < n; ++i) longest = std::max(longest, L.end[i] - L.beg[i]);
-    auto key = [&](int i) { return 2 * (longest - (L.end[i] - L.beg[i])) + (L.slot[i] < 0 ? 1 : 0); };
-    std::vector<int32_t> cnt(2 * longest + 3, 0), perm(n), inv(n);
+    const int short_base = 2 * longest + 2;     // above every key of the longer items
+    auto key = [&](int i) {
+        const int len = L.end[i] - L.beg[i];
+        if (len > kShortLen) return 2 * (longest - len) + (L.slot[i] < 0 ? 1 : 0);
+        if (L.slot[i] >= 0) return short_base;                    // short pieces, before the short whole segments
+        return short_base + 1 + (kShortLen - len);                // whole: kShortLen, ..., 2, 1, 0 entries
+    };
+    std::vector<int32_t> cnt(short_base + kShortLen + 3, 0), perm(n), inv(n);
     for (int i = 0; i < n; ++i) cnt[key(i) + 1]++;
     for (size_t l = 0; l + 1 < cnt.size(); ++l) cnt[l + 1] += cnt[l];
     for (int i = 0; i < n; ++i) { const int p = cnt[key(i)]++; perm[p] = i; inv[i] = p; }
@@ -124,10 +134,16 @@ inline ItemPlan plan_items(const std::vector<int32_t>& ptr, int max_len, int min
     apply(L.beg); apply(L.end); apply(L.row); apply(L.slot);
     for (auto& it : L.part_item) it = inv[it];
     L.first_single = n;
+    L.first_short = n;
     for (int i = 0; i < n; ++i) {
-        if (L.end[i] - L.beg[i] == 1 && L.slot[i] < 0) {
+        const int len = L.end[i] - L.beg[i];
+        if (len == 1 && L.slot[i] < 0) {
             if (L.num_single == 0) L.first_single = i;
             ++L.num_single;
+        }
+        if (len >= 2 && len <= kShortLen && L.slot[i] < 0) {
+            if (L.num_short == 0) L.first_short = i;
+            ++L.num_short;
         }
         if (L.end[i] - L.beg[i] > kSerialMax || L.slot[i] >= 0) L.long_item.push_back(i);
     }

@@ -24,8 +24,9 @@ int wl_items_field(int which, int32_t* out, int cap) {
                                        &g_items.split_ptr, &g_items.part_item, &g_items.part_split, &g_items.long_item};
     return copy_out(*f[which], out, cap);
 }
-void wl_items_scalars(int32_t* out4) {
-    out4[0] = g_items.num_partials; out4[1] = g_items.num_split; out4[2] = g_items.first_single; out4[3] = g_items.num_single;
+void wl_items_scalars(int32_t* out6) {
+    out6[0] = g_items.num_partials; out6[1] = g_items.num_split; out6[2] = g_items.first_single; out6[3] = g_items.num_single;
+    out6[4] = g_items.first_short; out6[5] = g_items.num_short;
 }
 
 int wl_plan_tiles(const int32_t* seg_ptr, int nseg, int tile_rows, int max_chunks) {
@@ -44,7 +45,7 @@ void wl_tiles_scalars(int32_t* out3) {
 int wl_item_cut(long long total) { return rgnn::item_cut(total); }
 int wl_constant(int which) {
     const int c[] = {rgnn::kTileRows, rgnn::kMaxChunks, rgnn::kWideChunksPerCU, rgnn::kMinChunks, rgnn::kChunkTiles,
-                     rgnn::kItemMax, rgnn::kItemTarget, rgnn::kSerialMax};
+                     rgnn::kItemMax, rgnn::kItemTarget, rgnn::kSerialMax, rgnn::kShortLen};
     return c[which];
 }
 

@@ -73,11 +73,13 @@ def test_many_single_entry_segments(dtype, d, H):
     """Thousands of destinations with one incoming edge and of pairs with one edge: the batched
     single-entry aggregation path with one coefficient per head."""
     rng = np.random.default_rng(78)
-    N, T, R = 8000, 2, 3
-    ntype = (np.arange(N) >= 5000).astype(np.int32)
-    dst = np.concatenate([rng.permutation(N), rng.integers(0, 40, 500)]).astype(np.int32)
+    N, T, R = 12000, 2, 3
+    ntype = (np.arange(N) >= 7000).astype(np.int32)
+    more = np.repeat(np.arange(5000), rng.integers(1, 4, 5000))         # 5000 nodes with 2..4 incoming edges
+    dst = np.concatenate([rng.permutation(N), more, rng.integers(0, 40, 500)]).astype(np.int32)
     src = rng.integers(0, N, len(dst)).astype(np.int32)
     rel = rng.integers(0, R, len(dst)).astype(np.int32)
+    src[N:N + 6000] = src[:6000]; rel[N:N + 6000] = rel[:6000]          # 6000 pairs with two edges
     p = synth.hgt_params(rng, N, T, R, d, H, with_mu=True)
     if dtype == "bf16":
         p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}

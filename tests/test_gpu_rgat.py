@@ -60,10 +60,12 @@ def test_many_single_edge_destinations():
     """Thousands of destinations with exactly one incoming edge (softmax weight 1) next to a few
     busier ones: the batched single-entry aggregation path."""
     rng = np.random.default_rng(79)
-    N, R, d = 9000, 5, 64
-    dst = np.concatenate([rng.permutation(N), rng.integers(0, 60, 800)]).astype(np.int32)
+    N, R, d = 12000, 5, 64
+    more = np.repeat(np.arange(5000), rng.integers(1, 4, 5000))         # 5000 nodes with 2..4 incoming edges
+    dst = np.concatenate([rng.permutation(N), more, rng.integers(0, 60, 800)]).astype(np.int32)
     src = rng.integers(0, N, len(dst)).astype(np.int32)
     rel = rng.integers(0, R, len(dst)).astype(np.int32)
+    src[N:N + 6000] = src[:6000]; rel[N:N + 6000] = rel[:6000]          # 6000 pairs with two edges (backward short path)
     p = synth.rgat_params(rng, N, R, d, d)
     _run(N, R, src, dst, rel, p, d, "singles")
 

@@ -78,17 +78,18 @@ def test_small_bf16_all_options(d):
 
 @pytest.mark.parametrize("dtype,d", [("f32", 32), ("bf16", 128)])
 def test_many_single_entry_segments(dtype, d):
-    """Thousands of destinations with exactly one incoming edge and of pairs with exactly one edge:
-    the batched single-entry aggregation path, forward (destination-major) and backward (pair-major)."""
+    """Thousands of destinations with one incoming edge, thousands with two to four, and as many
+    (source, relation) pairs with one or two edges: the batched single-entry and short-segment
+    aggregation paths, forward (destination-major) and backward (pair-major)."""
     rng = np.random.default_rng(77)
-    N, R = 9000, 4
-    dst = rng.permutation(N).astype(np.int32)              # every node: in-degree exactly 1 ...
-    src = rng.integers(0, N, N).astype(np.int32)
-    rel = rng.integers(0, R, N).astype(np.int32)
-    extra = 600                                            # ... except a few with more, and one hub
-    dst = np.concatenate([dst, rng.integers(0, 50, extra).astype(np.int32)])
-    src = np.concatenate([src, rng.integers(0, N, extra).astype(np.int32)])
-    rel = np.concatenate([rel, rng.integers(0, R, extra).astype(np.int32)])
+    N, R = 12000, 4
+    dst = rng.permutation(N).astype(np.int32)              # every node: in-degree at least 1; 7000 of them exactly 1
+    more = np.repeat(np.arange(5000, dtype=np.int32), rng.integers(1, 4, 5000))   # 5000 nodes with 2..4 incoming edges
+    hub = rng.integers(0, 50, 600).astype(np.int32)        # a few busier ones on top
+    dst = np.concatenate([dst, more, hub])
+    src = rng.integers(0, N, len(dst)).astype(np.int32)
+    rel = rng.integers(0, R, len(dst)).astype(np.int32)
+    src[N:N + 6000] = src[:6000]; rel[N:N + 6000] = rel[:6000]   # 6000 (source, relation) pairs with two edges
     p = synth.rgcn_params(rng, N, R, d, d, self_loop=False)
     if dtype == "bf16":
         p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}

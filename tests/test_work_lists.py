@@ -10,7 +10,8 @@ import numpy as np
 import pytest
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-K = dict(tile_rows=0, max_chunks=1, wide_chunks=2, min_chunks=3, chunk_tiles=4, item_max=5, item_target=6, serial_max=7)
+K = dict(tile_rows=0, max_chunks=1, wide_chunks=2, min_chunks=3, chunk_tiles=4, item_max=5, item_target=6, serial_max=7,
+         short_len=8)
 
 
 @pytest.fixture(scope="module")
@@ -35,9 +36,10 @@ def plan_items(lib, ptr, max_len, min_len=0):
     n = lib.wl_plan_items(ptr.ctypes.data_as(C.c_void_p), len(ptr) - 1, max_len, min_len)
     names = ("beg", "end", "row", "slot", "split_row", "split_ptr", "part_item", "part_split", "long_item")
     p = {k: _field(lib.wl_items_field, i) for i, k in enumerate(names)}
-    sc = np.zeros(4, np.int32)
+    sc = np.zeros(6, np.int32)
     lib.wl_items_scalars(sc.ctypes.data_as(C.c_void_p))
-    p.update(num_items=n, num_partials=int(sc[0]), num_split=int(sc[1]), first_single=int(sc[2]), num_single=int(sc[3]))
+    p.update(num_items=n, num_partials=int(sc[0]), num_split=int(sc[1]), first_single=int(sc[2]), num_single=int(sc[3]),
+             first_short=int(sc[4]), num_short=int(sc[5]))
     return p
 
 
@@ -85,10 +87,16 @@ def test_items_cover_each_segment_once(wl, max_len, min_len, hubs):
     expect_whole = np.nonzero((seg_len >= min_len) & (seg_len <= max_len))[0]
     assert np.array_equal(rows_whole, expect_whole)
     assert (ln[whole] == seg_len[p["row"][whole]]).all()
-    # longest first, pieces before whole segments of the same length
-    assert (np.diff(ln) <= 0).all()
-    same = np.nonzero(np.diff(ln) == 0)[0]
-    assert not ((p["slot"][same] < 0) & (p["slot"][same + 1] >= 0)).any()
+    # order: items longer than short_len by length (longest first, pieces before whole segments of the same
+    # length), then the short pieces, then the short whole segments by length
+    short_len = wl.wl_constant(K["short_len"])
+    klass = np.where(ln > short_len, 0, np.where(~(p["slot"] < 0), 1, 2))
+    assert (np.diff(klass) >= 0).all()
+    for kl in (0, 2):
+        sel = np.nonzero(klass == kl)[0]
+        assert (np.diff(ln[sel]) <= 0).all()
+        same = sel[:-1][np.diff(ln[sel]) == 0]
+        assert not ((p["slot"][same] < 0) & (p["slot"][same + 1] >= 0)).any()
     # cut segments: partial rows numbered 0..num_partials-1, grouped per segment in split_ptr order
     cut = np.nonzero(seg_len > max_len)[0]
     assert p["num_split"] == len(cut) and np.array_equal(p["split_row"], cut)
@@ -107,6 +115,13 @@ def test_items_cover_each_segment_once(wl, max_len, min_len, hubs):
     assert p["num_single"] == len(single)
     if len(single):
         assert p["first_single"] == single[0] and single[-1] == single[0] + len(single) - 1
+    # ... preceded directly by the whole segments with 2..short_len entries
+    short = np.nonzero((ln >= 2) & (ln <= short_len) & whole)[0]
+    assert p["num_short"] == len(short)
+    if len(short):
+        assert p["first_short"] == short[0] and short[-1] == short[0] + len(short) - 1
+        if len(single):
+            assert single[0] == short[-1] + 1
     # long items: more than serial_max entries, or any piece of a cut segment
     assert np.array_equal(p["long_item"], np.nonzero((ln > serial_max) | ~whole)[0])
 
@@ -118,7 +133,7 @@ def test_items_keep_segment_order_within_a_length(wl):
     ptr = _segments(rng, 2000, (300,))
     p = plan_items(wl, ptr, 256)
     ln = p["end"] - p["beg"]
-    for length in (0, 1, 2, 5):
+    for length in (0, 1, 2, 4, 5):
         rows = p["row"][(ln == length) & (p["slot"] < 0)]
         assert (np.diff(rows) > 0).all()
 
