@@ -85,7 +85,8 @@ typedef struct {
  *              agree with an fp64 evaluation to a few 1e-3 relative to the largest entry.
  *   d_in,d_out feature widths.  Supported: d_in == d_out in {32, 64, 128}.
  *   heads      number of attention heads H of HGT and RGAT (d_out % H == 0; d_out/H in {16, 32, 64},
- *              any width for single-head RGAT).
+ *              any width for single-head RGAT).  With H > 1, num_nodes * H and num_edges * H
+ *              must stay below 2^31 (EUNSUPPORTED otherwise).
  *   slope      RGAT leaky-ReLU negative slope (the derivative at 0 is `slope`).
  *   norm       RGCN: RGNN_NORM_IN_DEGREE_PER_REL divides each message by c_{v,r},
  *              the number of incoming edges of v with relation r (Eq. (rgcn)).

@@ -105,9 +105,9 @@ __device__ __forceinline__ float soft_out(float l, float m, float inv, bool sgn)
 }
 __global__ __launch_bounds__(256) void hgt_softmax_kernel(int N, int H, const int32_t* __restrict__ in_ptr,
                                                           float* __restrict__ att, int sgn) {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= N * H) return;
-    const int v = t / H, h = t % H;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)N * H) return;
+    const int v = (int)(t / H), h = (int)(t % H);
     const int b = in_ptr[v], len = in_ptr[v + 1] - b;
     if (len == 0 || len > kSerialMax) return;
     float l[kSerialMax];               // the logits stay in registers: one read and one write of att
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) void hgt_softmax_long_kernel(Items it, int n_l
                                                                int H, float* __restrict__ att, float* __restrict__ part_m,
                                                                float* __restrict__ part_s, int sgn) {
     constexpr int PER = kItemMax / 64;     // an item has at most kItemMax entries
-    const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (w >= n_long) return;
     const int i = long_item[w];
     const int bb = it.beg[i], ee = it.end[i], sl = it.slot[i];
@@ -170,7 +170,7 @@ __global__ void hgt_softmax_finish_kernel(int num_partials, const int32_t* __res
                                           const int32_t* __restrict__ split_ptr, Items it, int H,
                                           const float* __restrict__ part_m, const float* __restrict__ part_s,
                                           float* __restrict__ att, int sgn) {
-    const int t = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (t >= num_partials) return;
     const int sp = part_split[t];
     const int p0 = split_ptr[sp], p1 = split_ptr[sp + 1];

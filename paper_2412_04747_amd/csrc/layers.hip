@@ -65,6 +65,8 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
         const int dh = d->d_out / d->heads;
         if (d->heads > 1 && dh != 16 && dh != 32 && dh != 64)
             RGNN_FAIL(RGNN_EUNSUPPORTED, "multi-head RGAT needs d_out / heads in {16, 32, 64}, got %d", dh);
+        if (std::max<int64_t>(g->N, g->E) * d->heads > INT32_MAX)
+            RGNN_FAIL(RGNN_EUNSUPPORTED, "multi-head RGAT needs num_nodes * heads and num_edges * heads < 2^31");
     }
     if (layer == RGNN_LAYER_RGAT && !(d->slope >= 0.f && d->slope <= 1.f))
         RGNN_FAIL(RGNN_EINVAL, "leaky-ReLU slope must be in [0, 1]");
@@ -76,7 +78,8 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
         if (d->heads < 1 || d->d_out % d->heads != 0) RGNN_FAIL(RGNN_EINVAL, "heads must divide d_out");
         const int dh = d->d_out / d->heads;
         if (dh != 16 && dh != 32 && dh != 64) RGNN_FAIL(RGNN_EUNSUPPORTED, "HGT needs d_out / heads in {16, 32, 64}, got %d", dh);
-        if ((int64_t)g->N * d->heads > INT32_MAX) RGNN_FAIL(RGNN_EUNSUPPORTED, "HGT needs num_nodes * heads < 2^31");
+        if (std::max<int64_t>(g->N, g->E) * d->heads > INT32_MAX)
+            RGNN_FAIL(RGNN_EUNSUPPORTED, "HGT needs num_nodes * heads and num_edges * heads < 2^31");
     }
     return RGNN_OK;
 }

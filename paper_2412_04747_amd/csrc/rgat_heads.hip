@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void run_logit_heads_kernel(int Q, int R, int 
                                                               const float* __restrict__ X, const float* __restrict__ wtp,
                                                               float* __restrict__ s_dst) {
     constexpr int LPR = D / 4;
-    const int q = (blockIdx.x * blockDim.x + threadIdx.x) / LPR, c4 = threadIdx.x % LPR;
+    const int q = blockIdx.x * (256 / LPR) + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
     if (q >= Q) return;
     const float4 x = *reinterpret_cast<const float4*>(X + (size_t)run_dst[q] * D + c4 * 4);
     const int r = run_rel[q];

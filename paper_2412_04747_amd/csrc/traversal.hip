@@ -40,7 +40,7 @@ template <int D>
 __global__ void run_logit_kernel(int Q, const int32_t* __restrict__ run_dst, const int32_t* __restrict__ run_rel,
                                  const float* __restrict__ X, const float* __restrict__ wtp, float* __restrict__ s_dst) {
     constexpr int LPR = D / 4;
-    const int q0 = ((blockIdx.x * blockDim.x + threadIdx.x) / LPR) * 4, c4 = threadIdx.x % LPR;
+    const int q0 = (blockIdx.x * (256 / LPR) + threadIdx.x / LPR) * 4, c4 = threadIdx.x % LPR;
     float4 x[4], w[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -61,9 +61,9 @@ __global__ void run_logit_kernel(int Q, const int32_t* __restrict__ run_dst, con
 __global__ void segment_scalar_sum_kernel(int n, int heads, const int32_t* __restrict__ ptr,
                                           const int32_t* __restrict__ via, const float* __restrict__ val, int stride,
                                           int off, int min_len, float* __restrict__ out) {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= n * heads) return;
-    const int i = heads == 1 ? t : t / heads, h = heads == 1 ? 0 : t % heads;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)n * heads) return;
+    const int i = heads == 1 ? (int)t : (int)(t / heads), h = heads == 1 ? 0 : (int)(t % heads);
     const int b = ptr[i], e = ptr[i + 1];
     if (e - b > kSerialMax || e - b < min_len) return;
     float s = 0.f;
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void edge_softmax_kernel(SoftmaxArgs a, int N,
 // most kItemMax entries, kItemMax / 64 per lane, which stay in registers between the passes.
 __global__ __launch_bounds__(256) void edge_softmax_long_kernel(SoftmaxArgs a, int n_long, const int32_t* __restrict__ long_item) {
     constexpr int PER = kItemMax / 64;
-    const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (w >= n_long) return;
     const int i = long_item[w];
     const int bb = a.it.beg[i], ee = a.it.end[i], sl = a.it.slot[i];
@@ -210,7 +210,7 @@ __global__ void edge_softmax_finish_kernel(int num_partials, const int32_t* __re
                                            const int32_t* __restrict__ split_ptr, Items it,
                                            const float* __restrict__ part_m, const float* __restrict__ part_s,
                                            float* __restrict__ att) {
-    const int t = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (t >= num_partials) return;
     const int sp = part_split[t];
     const int p0 = split_ptr[sp], p1 = split_ptr[sp + 1];

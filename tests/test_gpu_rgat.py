@@ -139,6 +139,28 @@ def test_config3_full_size():
     _run(c["N"], c["R"], c["src"], c["dst"], c["rel"], c, 64, "C3", check_saved=False)
 
 
+@pytest.mark.timeout(900)
+def test_pair_tensors_of_more_than_2_to_32_elements():
+    """72M edges over 4M nodes and 200 relations, nearly all (source, relation) pairs distinct: the
+    per-pair tensors hold 68.8M rows of 64, more than 2^32 elements, so any 32-bit element index
+    would wrap.  The leaky ReLU has a kink at z = 0: an edge whose logit is within fp32 rounding of
+    0 may take the other branch on the GPU, which changes its gradient by a finite amount.  Such
+    edges (|z| < 1e-5 by the oracle, a few hundred of 72M) are left out of the graph, so the rest is
+    compared at the usual tolerance."""
+    N, R, E, d = 4_000_000, 200, 72_000_000, 64
+    rng = np.random.default_rng(4242)
+    src, dst, rel = (rng.integers(0, n, E, dtype=np.int32) for n in (N, N, R))
+    p = synth.rgat_params(rng, N, R, d, d)
+    print("large case: generated", flush=True)
+    _, _, z = O.rgat_fwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], 0.2, want_alpha=True)
+    keep = np.abs(z) >= 1e-5
+    print(f"large case: {int((~keep).sum())} edges at the kink left out", flush=True)
+    assert (~keep).sum() < 2000
+    src, dst, rel = src[keep], dst[keep], rel[keep]
+    assert len(np.unique(src.astype(np.int64) * R + rel)) * d > 2 ** 32
+    _run(N, R, src, dst, rel, p, d, "beyond-2^32", check_saved=False)
+
+
 def test_hub_empty_relation_isolated_nodes():
     rng, src, dst, rel, _ = synth.tiny(70, N=300, R=5, E=4000)
     rel[rel == 4] = 0       # relation 4 has no edge
