@@ -220,6 +220,12 @@ rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc
  *   logit_e^h = mu[r,h] ((k^h Watt[r,h]) . q^h) / sqrt(dh); att^h = edge softmax per head;
  *   out[v] = ( ||_h sum_e att_e^h (val^h Wmsg[r,h]) ) Wo[tau(v)].
  * Backward writes dX and the gradient of every weight (dmu ignored when mu is NULL).
+ * When all sources of every relation have one node type (the usual heterogeneous
+ * graph, where an edge type fixes its endpoint types; found when the graph is built,
+ * with or without rel_src_ntype), k^h Watt[r,h] and val^h Wmsg[r,h] are computed as
+ * X[u] (Wk[tau] Watt[r]) and X[u] (Wv[tau] Wmsg[r]) with the weight products formed
+ * first (linear operator reordering, Ch.3 "Linear Operator Reordering"); the result
+ * is the same up to rounding, and `saved` is smaller by the K and V rows.
  */
 rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* Wk,
                            const void* Wq, const void* Wv, const void* Wo, const void* Watt, const void* Wmsg,

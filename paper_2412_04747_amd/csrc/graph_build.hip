@@ -191,6 +191,16 @@ __global__ void k_tag(long long E, const int32_t* in_pair, const int32_t* out_pt
     const int32_t p = in_pair[i];
     tag[i] = (out_ptr[p + 1] - out_ptr[p] == 1) ? (int32_t)((uint32_t)p | 0x80000000u) : p;
 }
+// Pairs are in (relation, source) order: the first pair of a relation records its source's node type,
+// and any pair whose successor in the same relation has a source of another type raises `mixed`.
+__global__ void k_rel_type(long long P, const int32_t* pair_src, const int32_t* pair_rel, const int32_t* ntype,
+                           int32_t* rel_type, int32_t* mixed) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= P) return;
+    const int32_t r = pair_rel[i], t = ntype ? ntype[pair_src[i]] : 0;
+    if (i == 0 || pair_rel[i - 1] != r) rel_type[r] = t;
+    if (i + 1 < P && pair_rel[i + 1] == r && (ntype ? ntype[pair_src[i + 1]] : 0) != t) *mixed = 1;
+}
 __global__ void k_iota_key(long long n, const int32_t* major, u64* key, uint32_t* val) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
@@ -371,6 +381,18 @@ rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, co
     LAUNCH(k_tag, (size_t)E, E, g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_OUT_PTR], g->in_pair_tag);
     RGNN_TRY(keep<float>(g, (size_t)E, &g->out_invc));
     LAUNCH(k_permute_f32, (size_t)E, E, g->idx[RGNN_IDX_OUT_EPOS], g->in_invc, g->out_invc);
+
+    // ---- 8. node type of each relation's sources, if it is a single one
+    RGNN_TRY(keep<int32_t>(g, (size_t)R, &g->rel_src_type));
+    Tmp mixed_t;
+    RGNN_TRY(mixed_t.alloc(sizeof(int32_t)));
+    RGNN_HIP(hipMemset(g->rel_src_type, 0, (size_t)R * sizeof(int32_t)));
+    RGNN_HIP(hipMemset(mixed_t.as<int32_t>(), 0, sizeof(int32_t)));
+    LAUNCH(k_rel_type, (size_t)P, (long long)P, g->idx[RGNN_IDX_PAIR_SRC], g->idx[RGNN_IDX_PAIR_REL], ntype, g->rel_src_type,
+           mixed_t.as<int32_t>());
+    int32_t mixed = 0;
+    RGNN_HIP(hipMemcpy(&mixed, mixed_t.as<int32_t>(), sizeof(int32_t), hipMemcpyDeviceToHost));
+    g->rel_src_tied = mixed == 0;
     RGNN_HIP(hipDeviceSynchronize());
     return RGNN_OK;
 }

@@ -62,6 +62,61 @@ __global__ void hgt_extract_kernel(int d, int H, const float* __restrict__ dWbd,
     if (threadIdx.x == 0) dmu[r * H + h] = red[0] * inv;
 }
 
+// Linear operator reordering (Ch.3 "Linear Operator Reordering": two linear operators in a row may be
+// switched when that leaves a product between weights).  When every pair of a relation r has a source
+// of one node type t(r), K[src] Watt[r] = X[src] (Wk[t(r)] Watt[r]): the per-pair key and message rows
+// come straight from X with a folded per-relation weight, and K and V are never formed.
+//   Wf[r][k][n] = sum over j in the head of n of Wnode[t(r)][k][j] * Wbd[r][j][n]
+__global__ void hgt_fold_kernel(int R, int d, int H, const int32_t* __restrict__ rel_type,
+                                const float* __restrict__ Wnode, const float* __restrict__ Wbd, float* __restrict__ Wf) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)R * d * d) return;
+    const int dh = d / H;
+    const int r = (int)(i / ((size_t)d * d)), k = (int)(i / d % d), n = (int)(i % d);
+    const float* Wn = Wnode + ((size_t)rel_type[r] * d + k) * d;
+    const float* Wb = Wbd + (size_t)r * d * d;
+    const int j0 = n / dh * dh;
+    float s = 0.f;
+    for (int j = j0; j < j0 + dh; ++j) s += Wn[j] * Wb[(size_t)j * d + n];
+    Wf[i] = s;
+}
+
+// dWbd[r][j][n] = sum_k Wnode[t(r)][k][j] * dWf[r][k][n] for j, n in the same head (other entries are not written)
+__global__ void hgt_fold_bwd_rel_kernel(int R, int d, int H, const int32_t* __restrict__ rel_type,
+                                        const float* __restrict__ Wnode, const float* __restrict__ dWf,
+                                        float* __restrict__ dWbd) {
+    const int dh = d / H;
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;    // (r, j, n') with n' inside the head of j
+    if (i >= (size_t)R * d * dh) return;
+    const int r = (int)(i / ((size_t)d * dh)), j = (int)(i / dh % d), n = j / dh * dh + (int)(i % dh);
+    const float* Wn = Wnode + (size_t)rel_type[r] * d * d;
+    const float* G = dWf + (size_t)r * d * d;
+    float s = 0.f;
+    for (int k = 0; k < d; ++k) s += Wn[(size_t)k * d + j] * G[(size_t)k * d + n];
+    dWbd[((size_t)r * d + j) * d + n] = s;
+}
+
+// dWnode[t][k][j] = sum over relations r with t(r) = t, ascending, of sum over n in the head of j of dWf[r][k][n] * Wbd[r][j][n]
+__global__ void hgt_fold_bwd_node_kernel(int T, int R, int d, int H, const int32_t* __restrict__ rel_type,
+                                         const float* __restrict__ Wbd, const float* __restrict__ dWf,
+                                         float* __restrict__ dWnode) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)T * d * d) return;
+    const int dh = d / H;
+    const int t = (int)(i / ((size_t)d * d)), k = (int)(i / d % d), j = (int)(i % d);
+    const int n0 = j / dh * dh;
+    float s = 0.f;
+    for (int r = 0; r < R; ++r) {
+        if (rel_type[r] != t) continue;
+        const float* G = dWf + ((size_t)r * d + k) * d;
+        const float* Wb = Wbd + ((size_t)r * d + j) * d;
+        float p = 0.f;
+        for (int n = n0; n < n0 + dh; ++n) p += G[n] * Wb[n];
+        s += p;
+    }
+    dWnode[i] = s;
+}
+
 // logit[e][h] = Ka[pair_e][h] . Q[v][h]   (Ka already carries mu / sqrt(dh)); TI = storage type of the rows
 template <int D, typename TI>
 __global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, const int32_t* __restrict__ in_pair,
@@ -323,6 +378,25 @@ rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* a
                                               static_cast<const float*>(M), static_cast<const float*>(dZ),
                                               static_cast<const float*>(Z), dl, slope));
     }
+    RGNN_CHECK_LAUNCH();
+    return RGNN_OK;
+}
+rgnn_status_t hgt_fold(int R, int d, int H, const int32_t* rel_type, const float* Wnode, const float* Wbd, float* Wf,
+                       hipStream_t st) {
+    KernelTimer kt(st, "hgt_fold");
+    hipLaunchKernelGGL(hgt_fold_kernel, dim3(blocks_for((size_t)R * d * d, 256)), dim3(256), 0, st, R, d, H, rel_type, Wnode,
+                       Wbd, Wf);
+    RGNN_CHECK_LAUNCH();
+    return RGNN_OK;
+}
+rgnn_status_t hgt_fold_bwd(int T, int R, int d, int H, const int32_t* rel_type, const float* Wnode, const float* Wbd,
+                           const float* dWf, float* dWbd, float* dWnode, hipStream_t st) {
+    KernelTimer kt(st, "hgt_fold_bwd");
+    hipLaunchKernelGGL(hgt_fold_bwd_rel_kernel, dim3(blocks_for((size_t)R * d * (d / H), 256)), dim3(256), 0, st, R, d, H,
+                       rel_type, Wnode, dWf, dWbd);
+    RGNN_CHECK_LAUNCH();
+    hipLaunchKernelGGL(hgt_fold_bwd_node_kernel, dim3(blocks_for((size_t)T * d * d, 256)), dim3(256), 0, st, T, R, d, H,
+                       rel_type, Wbd, dWf, dWnode);
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

@@ -154,10 +154,15 @@ size_t carve_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
 
 // ---- HGT buffers ------------------------------------------------------------------------
 // Row tensors (void*) are bf16 when rows_bf16(desc), fp32 otherwise.
+// Folded path (the graph ties every relation to one source node type): the key and message linears
+// of the nodes are folded into the per-relation weights (Wf = Wk[type] Watt[r], Wv[type] Wmsg[r]), so
+// K, V and their gradients do not exist and the per-pair rows come straight from X.
+inline bool hgt_folded(const rgnn_graph_t* g) { return g->rel_src_tied; }
 struct HgtSaved { void* K; void* Q; void* V; void* Z; void* Ka; void* M; float* att; };
-struct HgtFwdWs { float* Wbd_att; float* Wbd_msg; float* part_m; float* part_s; float* partial; };
+struct HgtFwdWs { float* Wbd_att; float* Wbd_msg; float* Wf_att; float* Wf_msg; float* part_m; float* part_s; float* partial; };
 struct HgtBwdWs {
-    float* Wbd_att; float* Wbd_msg; float* dWbd_att; float* dWbd_msg; void* dZ; float* dl; void* dM; void* dKa;
+    float* Wbd_att; float* Wbd_msg; float* dWbd_att; float* dWbd_msg; float* Wf_att; float* Wf_msg; float* dWf_att;
+    float* dWf_msg; void* dZ; float* dl; void* dM; void* dKa;
     void* dQ; void* dKp; void* dVp; void* dK; void* dV; float* dXk; float* dXq; float* dXv; float* tl_part;
     float* partial;
 };
@@ -165,16 +170,17 @@ struct HgtBwdWs {
 size_t carve_hgt_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtSaved* s) {
     Carver c(base);
     const bool h = rows_bf16(d);
-    const size_t nd = (size_t)g->N * d->d_out, pd = (size_t)g->P * d->d_out;
-    s->K = c.rows(nd, h); s->Q = c.rows(nd, h); s->V = c.rows(nd, h); s->Z = c.rows(nd, h);
+    const size_t nd = (size_t)g->N * d->d_out, pd = (size_t)g->P * d->d_out, kv = hgt_folded(g) ? 0 : nd;
+    s->K = c.rows(kv, h); s->Q = c.rows(nd, h); s->V = c.rows(kv, h); s->Z = c.rows(nd, h);
     s->Ka = c.rows(pd, h); s->M = c.rows(pd, h);
     s->att = c.take<float>((size_t)g->E * d->heads);
     return c.off;
 }
 size_t carve_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtFwdWs* w) {
     Carver c(base);
-    const size_t rdd = (size_t)g->R * d->d_out * d->d_out;
+    const size_t rdd = (size_t)g->R * d->d_out * d->d_out, fdd = hgt_folded(g) ? rdd : 0;
     w->Wbd_att = c.take<float>(rdd); w->Wbd_msg = c.take<float>(rdd);
+    w->Wf_att = c.take<float>(fdd); w->Wf_msg = c.take<float>(fdd);
     w->part_m = c.take<float>((size_t)g->dst_items.num_partials * d->heads);
     w->part_s = c.take<float>((size_t)g->dst_items.num_partials * d->heads);
     w->partial = c.take<float>((size_t)g->dst_items.num_partials * d->d_out);
@@ -183,14 +189,17 @@ size_t carve_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* ba
 size_t carve_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtBwdWs* w) {
     Carver c(base);
     const bool h = rows_bf16(d);
+    const bool fold = hgt_folded(g);
     const size_t D = d->d_out, rdd = (size_t)g->R * D * D, nd = (size_t)g->N * D, pd = (size_t)g->P * D;
     w->Wbd_att = c.take<float>(rdd); w->Wbd_msg = c.take<float>(rdd);
     w->dWbd_att = c.take<float>(rdd); w->dWbd_msg = c.take<float>(rdd);
+    w->Wf_att = c.take<float>(fold ? rdd : 0); w->Wf_msg = c.take<float>(fold ? rdd : 0);
+    w->dWf_att = c.take<float>(fold ? rdd : 0); w->dWf_msg = c.take<float>(fold ? rdd : 0);
     w->dZ = c.rows(nd, h); w->dl = c.take<float>((size_t)g->E * d->heads);
     w->dM = c.rows(pd, h); w->dKa = c.rows(pd, h); w->dQ = c.rows(nd, h);
     w->dKp = c.rows(pd, h); w->dVp = c.rows(pd, h);
-    w->dK = c.rows(nd, h); w->dV = c.rows(nd, h);
-    w->dXk = c.take<float>(h ? 0 : nd); w->dXq = c.take<float>(h ? 0 : nd); w->dXv = c.take<float>(h ? 0 : nd);
+    w->dK = c.rows(fold ? 0 : nd, h); w->dV = c.rows(fold ? 0 : nd, h);
+    w->dXk = c.take<float>(h || fold ? 0 : nd); w->dXq = c.take<float>(h && !fold ? 0 : nd); w->dXv = c.take<float>(h || fold ? 0 : nd);
     w->tl_part = c.take<float>(std::max(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles),
                                         typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->node_tiles)));
     w->partial = c.take<float>((size_t)std::max(g->pair_items.num_partials, g->dst_items.num_partials) * D);
@@ -553,10 +562,11 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     Bf16Stage stg(workspace, carved, bf16, st);
     const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
     // fp32 copies: at width 128 only of the small per-relation parameters (their expansion is an fp32 kernel)
+    const bool fold = hgt_folded(g);
     const float* X32 = !h ? stg.in(X, (size_t)g->N * D) : nullptr;
-    const float* Wk32 = !h ? stg.in(Wk, tdd) : nullptr;
+    const float* Wk32 = !h || fold ? stg.in(Wk, tdd) : nullptr;      // folding multiplies weights in fp32
     const float* Wq32 = !h ? stg.in(Wq, tdd) : nullptr;
-    const float* Wv32 = !h ? stg.in(Wv, tdd) : nullptr;
+    const float* Wv32 = !h || fold ? stg.in(Wv, tdd) : nullptr;
     const float* Wo32 = !h ? stg.in(Wo, tdd) : nullptr;
     const float* Watt32 = stg.in(Watt, rh * dh * dh);
     const float* Wmsg32 = stg.in(Wmsg, rh * dh * dh);
@@ -568,16 +578,27 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     // bf16 form of an intermediate row tensor (nullptr when the rows are fp32) and its fp32 form
     auto R16 = [h](const void* p) { return h ? p : nullptr; };
     auto R32 = [h](const void* p) { return h ? nullptr : static_cast<const float*>(p); };
-    // 1. per node type: K, Q, V
-    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, &g->node_tiles_wide, D, X32, X16, perm, 1, Wk32, Wk16, sv.K, h, "node_linear_k", st));
+    // 1. per node type: Q, and K, V unless they are folded into the per-pair linears
     RGNN_TRY(tl_fwd(bf16, &g->node_tiles, &g->node_tiles_wide, D, X32, X16, perm, 1, Wq32, Wq16, sv.Q, h, "node_linear_q", st));
-    RGNN_TRY(tl_fwd(bf16, &g->node_tiles, &g->node_tiles_wide, D, X32, X16, perm, 1, Wv32, Wv16, sv.V, h, "node_linear_v", st));
+    if (!fold) {
+        RGNN_TRY(tl_fwd(bf16, &g->node_tiles, &g->node_tiles_wide, D, X32, X16, perm, 1, Wk32, Wk16, sv.K, h, "node_linear_k", st));
+        RGNN_TRY(tl_fwd(bf16, &g->node_tiles, &g->node_tiles_wide, D, X32, X16, perm, 1, Wv32, Wv16, sv.V, h, "node_linear_v", st));
+    }
     // 2. per (relation, head) matrices as block-diagonal d x d weights; mu / sqrt(dh) folded into the attention one
     RGNN_TRY(hgt_expand(g->R, D, H, Watt32, mu32, 1, w.Wbd_att, st));
     RGNN_TRY(hgt_expand(g->R, D, H, Wmsg32, nullptr, 0, w.Wbd_msg, st));
     // 3. compact per pair: Ka[p] = K[src_p] Watt[r], M[p] = V[src_p] Wmsg[r]
-    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, R32(sv.K), R16(sv.K), psrc, 0, w.Wbd_att, nullptr, sv.Ka, h, "pair_linear_att", st));
-    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, R32(sv.V), R16(sv.V), psrc, 0, w.Wbd_msg, nullptr, sv.M, h, "pair_linear_msg", st));
+    if (fold) {
+        //    = X[src_p] (Wk[type of r's sources] Watt[r]) and X[src_p] (Wv[type] Wmsg[r])
+        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wk32, w.Wbd_att, w.Wf_att, st));
+        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wv32, w.Wbd_msg, w.Wf_msg, st));
+        //    (rows in the storage of the intermediates: the caller's bf16 X at width 128, its fp32 copy otherwise)
+        RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, X32, R16(X), psrc, 0, w.Wf_att, nullptr, sv.Ka, h, "pair_linear_att", st));
+        RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, X32, R16(X), psrc, 0, w.Wf_msg, nullptr, sv.M, h, "pair_linear_msg", st));
+    } else {
+        RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, R32(sv.K), R16(sv.K), psrc, 0, w.Wbd_att, nullptr, sv.Ka, h, "pair_linear_att", st));
+        RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, R32(sv.V), R16(sv.V), psrc, 0, w.Wbd_msg, nullptr, sv.M, h, "pair_linear_msg", st));
+    }
     // 4. per edge and head: logit, softmax over the destination's edges
     RGNN_TRY(hgt_edge_logit(g, D, H, sv.Ka, sv.Q, sv.att, st, h));
     RGNN_TRY(hgt_softmax(g, H, sv.att, w.part_m, w.part_s, st));
@@ -608,10 +629,11 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
                *Wo16 = bf16 ? Wo : nullptr;
     Bf16Stage stg(workspace, carve_hgt_bwd(g, desc, workspace, &w), bf16, st);
     const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
+    const bool fold = hgt_folded(g);
     const float* X32 = !h ? stg.in(X, (size_t)g->N * D) : nullptr;
-    const float* Wk32 = !h ? stg.in(Wk, tdd) : nullptr;
+    const float* Wk32 = !h || fold ? stg.in(Wk, tdd) : nullptr;
     const float* Wq32 = !h ? stg.in(Wq, tdd) : nullptr;
-    const float* Wv32 = !h ? stg.in(Wv, tdd) : nullptr;
+    const float* Wv32 = !h || fold ? stg.in(Wv, tdd) : nullptr;
     const float* Wo32 = !h ? stg.in(Wo, tdd) : nullptr;
     const float* Watt32 = stg.in(Watt, rh * dh * dh);
     const float* Wmsg32 = stg.in(Wmsg, rh * dh * dh);
@@ -640,6 +662,24 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     // 5. per-pair linears backward
     RGNN_TRY(hgt_expand(g->R, D, H, Watt32, mu32, 1, w.Wbd_att, st));
     RGNN_TRY(hgt_expand(g->R, D, H, Wmsg32, nullptr, 0, w.Wbd_msg, st));
+    if (fold) {
+        // the folded weights take the per-pair gradients straight to X's rows; their own gradients are
+        // unfolded into those of the node-type and of the per-relation matrices
+        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wk32, w.Wbd_att, w.Wf_att, st));
+        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wv32, w.Wbd_msg, w.Wf_msg, st));
+        RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, Xr, psrc, 0, w.Wf_att, nullptr, w.dKa, w.dKp, h, w.dWf_att, w.tl_part,
+                        "pair_linear_att_bwd", st));
+        RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, Xr, psrc, 0, w.Wf_msg, nullptr, w.dM, w.dVp, h, w.dWf_msg, w.tl_part,
+                        "pair_linear_msg_bwd", st));
+        RGNN_TRY(hgt_fold_bwd(g->T, g->R, D, H, g->rel_src_type, Wk32, w.Wbd_att, w.dWf_att, w.dWbd_att, static_cast<float*>(dWk), st));
+        RGNN_TRY(hgt_fold_bwd(g->T, g->R, D, H, g->rel_src_type, Wv32, w.Wbd_msg, w.dWf_msg, w.dWbd_msg, static_cast<float*>(dWv), st));
+        RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_att, Watt32, mu32, 1, static_cast<float*>(dWatt), static_cast<float*>(dmu), st));
+        RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_msg, Wmsg32, nullptr, 0, static_cast<float*>(dWmsg), nullptr, st));
+        // dX = dQ Wq^T + sums over each node's pairs of the two per-pair gradients
+        RGNN_TRY(tl_bwd(h, &g->node_tiles, &g->node_tiles_wide, D, Xr, perm, 1, Wq32, Wq16, w.dQ, w.dXq, false, static_cast<float*>(dWq),
+                        w.tl_part, "node_linear_q_bwd", st));
+        return node_grad_sum(g, D, w.dKp, nullptr, nullptr, w.dXq, dX, st, h, 0, 1, w.dVp);
+    }
     RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, sv.K, psrc, 0, w.Wbd_att, nullptr, w.dKa, w.dKp, h, w.dWbd_att, w.tl_part,
                     "pair_linear_att_bwd", st));
     RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, sv.V, psrc, 0, w.Wbd_msg, nullptr, w.dM, w.dVp, h, w.dWbd_msg, w.tl_part,

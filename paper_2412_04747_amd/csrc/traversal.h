@@ -22,7 +22,16 @@ rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, c
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
                            const float* out, float slope, float* adz, float* G, float* ds_src, hipStream_t st);
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const float* ds_dst, const float* wtp,
-                            const float* extra, void* dX, hipStream_t st, int in_bf16 = 0, int out_bf16 = 0, int heads = 1);
+                            const float* extra, void* dX, hipStream_t st, int in_bf16 = 0, int out_bf16 = 0, int heads = 1,
+                            const void* dXp2 = nullptr);
+// hgt.hip: products of a node-type weight with the expanded per-relation weight of the relation's source type
+//   Wf[r] = Wnode[rel_type[r]] Wbd[r]
+rgnn_status_t hgt_fold(int R, int d, int H, const int32_t* rel_type, const float* Wnode, const float* Wbd, float* Wf,
+                       hipStream_t st);
+//   dWbd[r] (entries inside the head blocks) = Wnode[rel_type[r]]^T dWf[r]
+//   dWnode[t] = sum over the relations r of source type t, in ascending r, of dWf[r] Wbd[r]^T
+rgnn_status_t hgt_fold_bwd(int T, int R, int d, int H, const int32_t* rel_type, const float* Wnode, const float* Wbd,
+                           const float* dWf, float* dWbd, float* dWnode, hipStream_t st);
 rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const float* w_s, const float* w_t,
                                 const float* A, const float* U, float* dW, float* dw_s, float* dw_t, hipStream_t st);
 // hgt.hip

@@ -548,6 +548,7 @@ struct NodeSumArgs {
     const int32_t* srcpair_ptr;
     const int32_t* srcpair_idx;
     const void* dXp;      // rows of TI
+    const void* dXp2;     // MODE 2: a second tensor of per-pair rows, summed with the first
     const int32_t* dst_run_ptr;
     const int32_t* run_rel;
     const float* ds_dst;  // [Q][heads]
@@ -558,13 +559,16 @@ struct NodeSumArgs {
     int R;
 };
 
-// RUNS: the destination-run term is present (RGAT); without it the kernel only sums pair rows.
-template <int D, typename TI, typename TO, bool RUNS>
+// MODE 1: the destination-run term is present (RGAT); MODE 0: the kernel only sums pair rows;
+// MODE 2: pair rows of two tensors (HGT: the key and the message halves of the input gradient).
+template <int D, typename TI, typename TO, int MODE>
 __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
+    constexpr bool RUNS = MODE == 1, TWO = MODE == 2;
     constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
     const int i = blockIdx.x * IPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
     if (i >= a.it.n) return;
     const TI* __restrict__ dXp = static_cast<const TI*>(a.dXp);
+    const TI* __restrict__ dXp2 = static_cast<const TI*>(a.dXp2);
     const int u = a.it.row[i];
     const int b = a.it.beg[i], e = a.it.end[i];
     const int H = a.heads;
@@ -595,12 +599,19 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
             if (pi[t] >= 0) load_cols(dXp + (size_t)pi[t] * D + cv * V, v[t]);
             else zero_cols(v[t]);
             if (RUNS && rr[t] >= 0) load_cols(a.wtp + (size_t)rr[t] * D + cv * V, w[t]);
+            else if (TWO && pi[t] >= 0) load_cols(dXp2 + (size_t)pi[t] * D + cv * V, w[t]);
             else zero_cols(w[t]);
         }
         fma_cols(acc, 1.f, v[0]);
         fma_cols(acc1, 1.f, v[1]);
         fma_cols(acc, 1.f, v[2]);
         fma_cols(acc1, 1.f, v[3]);
+        if (TWO) {
+            fma_cols(acc, 1.f, w[0]);
+            fma_cols(acc1, 1.f, w[1]);
+            fma_cols(acc, 1.f, w[2]);
+            fma_cols(acc1, 1.f, w[3]);
+        }
         if (RUNS) {
             fma_cols(acc, c[0], w[0]);
             fma_cols(acc1, c[1], w[1]);
@@ -609,16 +620,27 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
         }
     }
     for (int j = b + 4; j < e; j += 4) {
-        float v[4][V];
+        float v[4][V], w[4][V];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            if (j + t < e) load_cols(dXp + (size_t)a.srcpair_idx[j + t] * D + cv * V, v[t]);
-            else zero_cols(v[t]);
+            zero_cols(v[t]);
+            zero_cols(w[t]);
+            if (j + t < e) {
+                const size_t p = (size_t)a.srcpair_idx[j + t];
+                load_cols(dXp + p * D + cv * V, v[t]);
+                if (TWO) load_cols(dXp2 + p * D + cv * V, w[t]);
+            }
         }
         fma_cols(acc, 1.f, v[0]);
         fma_cols(acc1, 1.f, v[1]);
         fma_cols(acc, 1.f, v[2]);
         fma_cols(acc1, 1.f, v[3]);
+        if (TWO) {
+            fma_cols(acc, 1.f, w[0]);
+            fma_cols(acc1, 1.f, w[1]);
+            fma_cols(acc, 1.f, w[2]);
+            fma_cols(acc1, 1.f, w[3]);
+        }
     }
     for (int q = qb + 4; q < qe; q += 4) {
         float cq[4];
@@ -851,16 +873,20 @@ rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const f
 }
 
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const float* ds_dst, const float* wtp,
-                            const float* extra, void* dX, hipStream_t st, int in_bf16, int out_bf16, int heads) {
+                            const float* extra, void* dX, hipStream_t st, int in_bf16, int out_bf16, int heads,
+                            const void* dXp2) {
     if (g->N == 0) return RGNN_OK;
-    NodeSumArgs a{dev_items(g->srcpair_items), g->idx[RGNN_IDX_SRCPAIR_PTR], g->idx[RGNN_IDX_SRCPAIR_IDX], dXp,
+    if (ds_dst && dXp2) RGNN_FAIL(RGNN_EINVAL, "node_grad_sum: the run term and a second row tensor exclude each other");
+    NodeSumArgs a{dev_items(g->srcpair_items), g->idx[RGNN_IDX_SRCPAIR_PTR], g->idx[RGNN_IDX_SRCPAIR_IDX], dXp, dXp2,
                   g->idx[RGNN_IDX_DST_RUN_PTR], g->idx[RGNN_IDX_RUN_REL], ds_dst, wtp, extra, dX, heads, (int)g->R};
     KernelTimer kt(st, "node_grad_sum");
     const dim3 grid(blocks_for((size_t)g->N, 256 / (D / (in_bf16 ? 8 : 4))));
     if (ds_dst)
-        RGNN_DISPATCH_ROWS(D, in_bf16, out_bf16, hipLaunchKernelGGL((node_grad_sum_kernel<DD, TI, TO, true>), grid, dim3(256), 0, st, a));
+        RGNN_DISPATCH_ROWS(D, in_bf16, out_bf16, hipLaunchKernelGGL((node_grad_sum_kernel<DD, TI, TO, 1>), grid, dim3(256), 0, st, a));
+    else if (dXp2)
+        RGNN_DISPATCH_ROWS(D, in_bf16, out_bf16, hipLaunchKernelGGL((node_grad_sum_kernel<DD, TI, TO, 2>), grid, dim3(256), 0, st, a));
     else
-        RGNN_DISPATCH_ROWS(D, in_bf16, out_bf16, hipLaunchKernelGGL((node_grad_sum_kernel<DD, TI, TO, false>), grid, dim3(256), 0, st, a));
+        RGNN_DISPATCH_ROWS(D, in_bf16, out_bf16, hipLaunchKernelGGL((node_grad_sum_kernel<DD, TI, TO, 0>), grid, dim3(256), 0, st, a));
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

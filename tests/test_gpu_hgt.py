@@ -86,6 +86,27 @@ def test_many_single_entry_segments(dtype, d, H):
     _run(N, T, R, src, dst, rel, ntype, p, d, H, f"singles-{dtype}", dtype=dtype)
 
 
+@pytest.mark.parametrize("dtype,d,H", [("f32", 64, 2), ("f32", 32, 2), ("f32", 128, 4), ("bf16", 64, 4), ("bf16", 128, 4)])
+def test_relations_tied_to_one_source_type(dtype, d, H):
+    """Every relation draws its sources from one node type, so the library folds the key and message
+    linears of the nodes into the per-relation weights.  Relation 4 has no edge, type 3 is never a
+    source, types 0 and 1 serve several relations, and a hub and a pair with many edges are cut."""
+    rng = np.random.default_rng(311 + d)
+    N, T, R, E = 900, 4, 6, 8000
+    ntype = rng.integers(0, T, N).astype(np.int32)
+    rel_type = np.array([0, 1, 2, 0, 1, 0], np.int32)
+    rel = rng.choice([0, 1, 2, 3, 5], E).astype(np.int32)
+    by_type = [np.nonzero(ntype == t)[0] for t in range(T)]
+    src = np.array([rng.choice(by_type[rel_type[r]]) for r in rel], np.int32)
+    dst = rng.integers(0, N, E).astype(np.int32)
+    dst[:1500] = 13
+    src[:600] = by_type[1][0]; rel[:600] = 1
+    p = synth.hgt_params(rng, N, T, R, d, H, with_mu=True)
+    if dtype == "bf16":
+        p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}
+    _run(N, T, R, src, dst, rel, ntype, p, d, H, f"tied-{dtype}-d{d}", dtype=dtype)
+
+
 def test_scaled_config4_bf16():
     c = synth.config(4, scale=0.01)          # 20k nodes, 200k edges, 8 node types, 30 relations, d=128, H=4
     c["mu"] = None
