@@ -67,8 +67,10 @@ __global__ void hgt_extract_kernel(int d, int H, const float* __restrict__ dWbd,
 // of one node type t(r), K[src] Watt[r] = X[src] (Wk[t(r)] Watt[r]): the per-pair key and message rows
 // come straight from X with a folded per-relation weight, and K and V are never formed.
 //   Wf[r][k][n] = sum over j in the head of n of Wnode[t(r)][k][j] * Wbd[r][j][n]
+// Written as fp32 (Wf) or rounded to bf16 (Wf16), whichever is given.
 __global__ void hgt_fold_kernel(int R, int d, int H, const int32_t* __restrict__ rel_type,
-                                const float* __restrict__ Wnode, const float* __restrict__ Wbd, float* __restrict__ Wf) {
+                                const float* __restrict__ Wnode, const float* __restrict__ Wbd, float* __restrict__ Wf,
+                                bf16_t* __restrict__ Wf16) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (size_t)R * d * d) return;
     const int dh = d / H;
@@ -78,7 +80,8 @@ __global__ void hgt_fold_kernel(int R, int d, int H, const int32_t* __restrict__
     const int j0 = n / dh * dh;
     float s = 0.f;
     for (int j = j0; j < j0 + dh; ++j) s += Wn[j] * Wb[(size_t)j * d + n];
-    Wf[i] = s;
+    if (Wf) Wf[i] = s;
+    if (Wf16) Wf16[i] = (bf16_t)(bf16_pack2(s, 0.f) & 0xFFFFu);
 }
 
 // dWbd[r][j][n] = sum_k Wnode[t(r)][k][j] * dWf[r][k][n] for j, n in the same head (other entries are not written)
@@ -382,10 +385,10 @@ rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* a
     return RGNN_OK;
 }
 rgnn_status_t hgt_fold(int R, int d, int H, const int32_t* rel_type, const float* Wnode, const float* Wbd, float* Wf,
-                       hipStream_t st) {
+                       void* Wf16, hipStream_t st) {
     KernelTimer kt(st, "hgt_fold");
     hipLaunchKernelGGL(hgt_fold_kernel, dim3(blocks_for((size_t)R * d * d, 256)), dim3(256), 0, st, R, d, H, rel_type, Wnode,
-                       Wbd, Wf);
+                       Wbd, Wf, static_cast<bf16_t*>(Wf16));
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

@@ -590,11 +590,13 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     // 3. compact per pair: Ka[p] = K[src_p] Watt[r], M[p] = V[src_p] Wmsg[r]
     if (fold) {
         //    = X[src_p] (Wk[type of r's sources] Watt[r]) and X[src_p] (Wv[type] Wmsg[r])
-        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wk32, w.Wbd_att, w.Wf_att, st));
-        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wv32, w.Wbd_msg, w.Wf_msg, st));
-        //    (rows in the storage of the intermediates: the caller's bf16 X at width 128, its fp32 copy otherwise)
-        RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, X32, R16(X), psrc, 0, w.Wf_att, nullptr, sv.Ka, h, "pair_linear_att", st));
-        RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, X32, R16(X), psrc, 0, w.Wf_msg, nullptr, sv.M, h, "pair_linear_msg", st));
+        //    With bf16 rows the products are rounded to bf16 once (as K and V would have been) and feed the
+        //    matrix cores as they are; rows in the storage of the intermediates: the caller's bf16 X at width
+        //    128, its fp32 copy otherwise.
+        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wk32, w.Wbd_att, h ? nullptr : w.Wf_att, h ? w.Wf_att : nullptr, st));
+        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wv32, w.Wbd_msg, h ? nullptr : w.Wf_msg, h ? w.Wf_msg : nullptr, st));
+        RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, X32, R16(X), psrc, 0, R32(w.Wf_att), R16(w.Wf_att), sv.Ka, h, "pair_linear_att", st));
+        RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, X32, R16(X), psrc, 0, R32(w.Wf_msg), R16(w.Wf_msg), sv.M, h, "pair_linear_msg", st));
     } else {
         RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, R32(sv.K), R16(sv.K), psrc, 0, w.Wbd_att, nullptr, sv.Ka, h, "pair_linear_att", st));
         RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, R32(sv.V), R16(sv.V), psrc, 0, w.Wbd_msg, nullptr, sv.M, h, "pair_linear_msg", st));
@@ -665,12 +667,12 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     if (fold) {
         // the folded weights take the per-pair gradients straight to X's rows; their own gradients are
         // unfolded into those of the node-type and of the per-relation matrices
-        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wk32, w.Wbd_att, w.Wf_att, st));
-        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wv32, w.Wbd_msg, w.Wf_msg, st));
-        RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, Xr, psrc, 0, w.Wf_att, nullptr, w.dKa, w.dKp, h, w.dWf_att, w.tl_part,
-                        "pair_linear_att_bwd", st));
-        RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, Xr, psrc, 0, w.Wf_msg, nullptr, w.dM, w.dVp, h, w.dWf_msg, w.tl_part,
-                        "pair_linear_msg_bwd", st));
+        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wk32, w.Wbd_att, h ? nullptr : w.Wf_att, h ? w.Wf_att : nullptr, st));
+        RGNN_TRY(hgt_fold(g->R, D, H, g->rel_src_type, Wv32, w.Wbd_msg, h ? nullptr : w.Wf_msg, h ? w.Wf_msg : nullptr, st));
+        RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, Xr, psrc, 0, h ? nullptr : w.Wf_att, h ? w.Wf_att : nullptr, w.dKa, w.dKp,
+                        h, w.dWf_att, w.tl_part, "pair_linear_att_bwd", st));
+        RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, Xr, psrc, 0, h ? nullptr : w.Wf_msg, h ? w.Wf_msg : nullptr, w.dM, w.dVp,
+                        h, w.dWf_msg, w.tl_part, "pair_linear_msg_bwd", st));
         RGNN_TRY(hgt_fold_bwd(g->T, g->R, D, H, g->rel_src_type, Wk32, w.Wbd_att, w.dWf_att, w.dWbd_att, static_cast<float*>(dWk), st));
         RGNN_TRY(hgt_fold_bwd(g->T, g->R, D, H, g->rel_src_type, Wv32, w.Wbd_msg, w.dWf_msg, w.dWbd_msg, static_cast<float*>(dWv), st));
         RGNN_TRY(hgt_extract(g->R, D, H, w.dWbd_att, Watt32, mu32, 1, static_cast<float*>(dWatt), static_cast<float*>(dmu), st));

@@ -25,9 +25,9 @@ rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const f
                             const float* extra, void* dX, hipStream_t st, int in_bf16 = 0, int out_bf16 = 0, int heads = 1,
                             const void* dXp2 = nullptr);
 // hgt.hip: products of a node-type weight with the expanded per-relation weight of the relation's source type
-//   Wf[r] = Wnode[rel_type[r]] Wbd[r]
+//   Wf[r] = Wnode[rel_type[r]] Wbd[r], stored as fp32 (Wf) or rounded to bf16 (Wf16); pass one of the two
 rgnn_status_t hgt_fold(int R, int d, int H, const int32_t* rel_type, const float* Wnode, const float* Wbd, float* Wf,
-                       hipStream_t st);
+                       void* Wf16, hipStream_t st);
 //   dWbd[r] (entries inside the head blocks) = Wnode[rel_type[r]]^T dWf[r]
 //   dWnode[t] = sum over the relations r of source type t, in ascending r, of dWf[r] Wbd[r]^T
 rgnn_status_t hgt_fold_bwd(int T, int R, int d, int H, const int32_t* rel_type, const float* Wnode, const float* Wbd,
