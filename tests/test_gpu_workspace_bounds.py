@@ -82,13 +82,19 @@ def test_rgcn_stays_inside_its_buffers(dtype, d, act, w0):
     g.close()
 
 
+@pytest.mark.parametrize("tied", [False, True])
 @pytest.mark.parametrize("dtype,d,H", [("f32", 64, 2), ("bf16", 128, 4), ("bf16", 64, 4)])
-def test_hgt_stays_inside_its_buffers(dtype, d, H):
+def test_hgt_stays_inside_its_buffers(dtype, d, H, tied):
+    """`tied`: every relation's sources have one node type (the source's type is set by its relation),
+    which selects the path with folded weights and a smaller `saved`."""
     import torch
     from paper_2412_04747_amd import binding as B
     from paper_2412_04747_amd.harness import Graph, HgtLayer
     rng, src, dst, rel, ntype = _graph(503, 3000, 12, 40000, T=3)
-    print(f"bounds case hgt {dtype} d={d} H={H}", flush=True)
+    if tied:
+        ntype = (np.arange(3000) % 3).astype(np.int32)
+        src = (src // 3 * 3 + rel % 3).astype(np.int32)          # source type = relation mod 3
+    print(f"bounds case hgt {dtype} d={d} H={H} tied={tied}", flush=True)
     g = Graph(3000, 12, src, dst, rel, ntype, 3)
     L = HgtLayer(g, d, H, with_mu=True, dtype=dtype)
     p = synth.hgt_params(rng, 3000, 3, 12, d, H, with_mu=True)
@@ -96,6 +102,9 @@ def test_hgt_stays_inside_its_buffers(dtype, d, H):
         p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}
     L.load(p["X"], p["Wk"], p["Wq"], p["Wv"], p["Wo"], p["Watt"], p["Wmsg"], p["mu"], p["dOut"])
     f, b, s = B.rgnn_workspace_bytes(g.handle, B.RGNN_LAYER_HGT, L.desc)
+    row = d * (2 if dtype == "bf16" and d == 128 else 4)                 # bytes of one stored row
+    rest = 2 * g.P * row + len(src) * H * 4                              # Ka, M and att
+    assert (s < rest + 3 * 3000 * row) == tied                           # Q, Z and, unless folded, K and V
     wf, L.ws = _guarded(f)
     sv, L.saved = _guarded(s)
     L.fwd()
