@@ -185,6 +185,10 @@ __global__ void k_permute_f32(long long n, const int32_t* idx, const float* src,
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = src[idx[i]];
 }
+__global__ void k_permute_i32(long long n, const int32_t* idx, const int32_t* src, int32_t* dst) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[idx[i]];
+}
 __global__ void k_tag(long long E, const int32_t* in_pair, const int32_t* out_ptr, int32_t* tag) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= E) return;
@@ -359,6 +363,8 @@ rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, co
     RGNN_TRY(sort_pairs(k0.as<u64>(), k1.as<u64>(), v0.as<uint32_t>(), v1.as<uint32_t>(), (size_t)Q, uR * uN));
     LAUNCH(k_sorted_major, (size_t)Q, (long long)Q, (long long)uN, k1.as<u64>(), v1.as<uint32_t>(), flag.as<int32_t>(), g->idx[RGNN_IDX_RELRUN_IDX]);
     LAUNCH(k_lower_bound, (size_t)R + 1, (long long)Q, flag.as<int32_t>(), (long long)R, g->idx[RGNN_IDX_RELRUN_PTR]);
+    RGNN_TRY(keep<int32_t>(g, (size_t)Q, &g->relrun_dst));
+    LAUNCH(k_permute_i32, (size_t)Q, (long long)Q, g->idx[RGNN_IDX_RELRUN_IDX], g->idx[RGNN_IDX_RUN_DST], g->relrun_dst);
 
     // ---- 5. pairs by (src, rel)
     RGNN_TRY(keep_idx(g, RGNN_IDX_SRCPAIR_IDX, (size_t)P));

@@ -506,7 +506,7 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         RGNN_TRY(gather_sum(g->relpair_items, D, nullptr, nullptr, 0, w.ds_src, H, 0, sv.Hs, dw_s, w.partial, st, 2,
                             "src_vec_grad", "src_vec_grad.combine", H));
         // 6. U[h][r] = sum over r's runs of ds_dst[q][h] X[run_dst[q]];  dw_t and the w_t part of dW from it
-        RGNN_TRY(gather_heads_rows(g->relrun_items, K, H, g->R, g->idx[RGNN_IDX_RELRUN_IDX], g->idx[RGNN_IDX_RUN_DST], 1, w.ds_dst,
+        RGNN_TRY(gather_heads_rows(g->relrun_items, K, H, g->R, g->idx[RGNN_IDX_RELRUN_IDX], g->relrun_dst, 0, w.ds_dst,
                                    Xf, w.U, w.partial, st, "dst_side_wgrad", "dst_side_wgrad.combine"));
         RGNN_TRY(rgat_heads_param_finish(g->R, K, D, H, Wf, wt, w.U, static_cast<float*>(dW), static_cast<float*>(dw_t), st));
         // 7. dX[u] = sum over u's pairs of dXp + sum over u's runs and heads of ds_dst[q][h] (W[r] w_t[r])_h
@@ -531,7 +531,7 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     b.part = w.tl_part;
     RGNN_TRY(typed_linear_bwd(K, D, b, st));
     // 5. U[r] = sum over r's runs of ds_dst[q] X[run_dst[q]]
-    RGNN_TRY(gather_sum(g->relrun_items, K, g->idx[RGNN_IDX_RELRUN_IDX], g->idx[RGNN_IDX_RUN_DST], 1, w.ds_dst, 1, 0, Xf,
+    RGNN_TRY(gather_sum(g->relrun_items, K, g->idx[RGNN_IDX_RELRUN_IDX], g->relrun_dst, 0, w.ds_dst, 1, 0, Xf,
                         w.U, w.partial, st, 2, "dst_side_wgrad", "dst_side_wgrad.combine"));
     // 6. dw_s = A W, dw_t = U W, dW += A^T (x) w_s + U^T (x) w_t
     RGNN_TRY(rgat_param_finish(g->R, K, D, Wf, static_cast<const float*>(w_s), static_cast<const float*>(w_t), w.A, w.U,

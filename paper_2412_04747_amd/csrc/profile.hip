@@ -6,13 +6,14 @@
 
 #include <stdio.h>
 #include <string.h>
+#include <atomic>
 #include <map>
 #include <mutex>
 
 namespace rgnn {
 
 struct Record { const char* name; hipEvent_t a, b; };
-static bool g_on = false;
+static std::atomic<bool> g_on{false};
 static std::vector<Record> g_rec;
 static std::mutex g_mu;
 
@@ -29,7 +30,8 @@ KernelTimer::KernelTimer(hipStream_t st, const char* name) : st_(st), idx_(-1) {
     if (!g_on) return;
     std::lock_guard<std::mutex> lk(g_mu);
     Record r{name, nullptr, nullptr};
-    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    if (hipEventCreate(&r.a) != hipSuccess) return;
+    if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
     (void)hipEventRecord(r.a, st_);
     idx_ = (int)g_rec.size();
     g_rec.push_back(r);

@@ -115,6 +115,7 @@ struct rgnn_graph {
     rgnn::ItemList pair_items_multi;       // the same, pairs with two or more edges only
     rgnn::ItemList srcpair_items;          // pairs by source node (never cut)
     int32_t* in_pair_tag = nullptr;        // [E] in_pair with the top bit set when the pair has a single edge
+    int32_t* relrun_dst = nullptr;         // [Q] destination of the runs in (relation, destination) order: run_dst[relrun_idx[i]]
     int32_t* rel_src_type = nullptr;       // [R] node type of the sources of relation r (0 for a relation without edges)
     bool rel_src_tied = false;             // every relation's sources are of one node type (rel_src_type is then valid)
     rgnn::ItemList relrun_items;           // runs by relation
