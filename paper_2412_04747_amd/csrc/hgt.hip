@@ -145,11 +145,16 @@ __global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, co
 #pragma unroll
             for (int u = 0; u < 4; ++u) pr[u] = in_pair[min(j + 4 + u, e - 1)];
         }
+        // lane t < 4 of a head's lanes stores edge j + t (every lane of the head holds all four sums), so the
+        // 4 x H results of a batch leave in one store instruction; heads of fewer than 4 lanes store one by one
+        float mine = 0.f;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const float s = group_sum_dyn(dot_cols(q, k[u]), lph);
-            if (cv % lph == 0 && j + u < e) logit[(size_t)(j + u) * H + head] = s;
+            if (lph >= 4) { if (cv % lph == u) mine = s; }
+            else if (cv % lph == 0 && j + u < e) logit[(size_t)(j + u) * H + head] = s;
         }
+        if (lph >= 4 && cv % lph < 4 && j + cv % lph < e) logit[(size_t)(j + cv % lph) * H + head] = mine;
     }
 }
 
@@ -290,14 +295,18 @@ __global__ __launch_bounds__(256) void hgt_edge_dot_bwd_kernel(Items it, int H, 
                 an[u] = att[(size_t)jj * H + head];
             }
         }
+        float mine = 0.f;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const float g = group_sum_dyn(dot_cols(gz, mm[u]), lph);
             // slope >= 0: att is signed (negative where the leaky-ReLU took its sloped branch) and the
             // result is the gradient of the pre-activation logit
             const float w = slope >= 0.f ? fabsf(a[u]) * (a[u] < 0.f ? slope : 1.f) : a[u];
-            if (cv % lph == 0 && j + u < e) dl[(size_t)(j + u) * H + head] = w * (g - gbar);
+            if (lph >= 4) { if (cv % lph == u) mine = w * (g - gbar); }
+            else if (cv % lph == 0 && j + u < e) dl[(size_t)(j + u) * H + head] = w * (g - gbar);
         }
+        // one store instruction for the 4 x H results of the batch (see hgt_edge_logit_kernel)
+        if (lph >= 4 && cv % lph < 4 && j + cv % lph < e) dl[(size_t)(j + cv % lph) * H + head] = mine;
     }
 }
 

@@ -522,6 +522,7 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
                 prn[u] = a.in_pair[jj];
             }
         }
+        float2 mine = make_float2(0.f, 0.f);   // (att, dz) of edge j + c4: lanes 0..3 of the group store one edge each
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const float g = group_sum<LPR>(dot4(go, h[u]));
@@ -529,13 +530,14 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
             const float dl = al * (g - gbar);
             const float dz = dl * (signbit(at[u]) ? a.slope : 1.f);
             const bool live = j + u < e;
-            if (c4 == 0 && live) a.adz[j + u] = make_float2(al, dz);
+            if (c4 == u) mine = make_float2(al, dz);
             if (live && pr[u] < 0) {   // single-edge pair
                 const size_t p = (size_t)(pr[u] & 0x7FFFFFFF);
                 *reinterpret_cast<float4*>(a.G + p * D + c4 * 4) = make_float4(al * go.x, al * go.y, al * go.z, al * go.w);
                 if (c4 == 0) a.ds_src[p] = dz;
             }
         }
+        if (c4 < 4 && j + c4 < e) a.adz[j + c4] = mine;
     }
 }
 
