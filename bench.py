@@ -49,6 +49,10 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
             extra = r32 if half and key in ("node_linear_q_bwd", "node_linear_v_bwd") else 0   # accumulate into dX
             return (bound, n * (row + out_row + extra + 4) + segs * w2, 2.0 * n * d * d)
     w2 = d * d * 4
+    # single-head RGAT up to width 64: the gradient row of a single-edge pair is not stored per pair; the
+    # backward typed linear reads att_e * dOut[dst_e] through a row selector (one index per pair, one scale
+    # per single-edge pair)
+    sel = layer == "rgat" and H == 1 and d <= 64
     pair_fwd = ("mfma", P * (2 * row + 4) + R * w2, 2.0 * P * d * d)        # gathered row + stored row + pair_src
     pair_bwd = ("mfma", P * (3 * row + 4) + R * w2, 4.0 * P * d * d)        # dY row + gathered row + stored row
     node_fwd = ("mfma", N * (2 * row + 4) + T * w2, 2.0 * N * d * d)
@@ -59,13 +63,13 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
     table = {
         # RGAT: + s_src per pair; backward also reads ds_src
         "typed_linear_fwd": ("mfma", pair_fwd[1] + (P * 4 if layer == "rgat" else 0), pair_fwd[2]),
-        "typed_linear_bwd": ("mfma", pair_bwd[1] + (P * 4 if layer == "rgat" else 0), pair_bwd[2]),
+        "typed_linear_bwd": ("mfma", pair_bwd[1] + (P * 4 if layer == "rgat" else 0) + (P * 4 + P1 * 4 if sel else 0), pair_bwd[2]),
         "self_loop_fwd": ("mfma", N * 3 * r32 + w2, 2.0 * N * d * d),         # X row + out row read and written
         "self_loop_bwd": ("mfma", N * 3 * r32 + w2, 4.0 * N * d * d),
         "aggregate_fwd": agg_dst,
         # per edge: Hs row + in_pair + att + (att, dz) store; per node: dOut row + out row + item;
-        # per single-edge pair (P1 of them): its G row and ds_src
-        "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8) + P1 * (row + 4), 2.0 * E * d),
+        # per single-edge pair (P1 of them): ds_src and its G row, or with the row selector att_e only
+        "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8) + P1 * ((4 if sel else row) + 4), 2.0 * E * d),
         # RGAT: only the E - P1 edges of the P - P1 pairs with several edges; coefficient = the (att, dz) pair.
         # RGCN: every edge; row + out_dst + coefficient
         "aggregate_bwd_pair": ("hbm", (E - P1) * (row + 16) + (P - P1) * (row + 8), 2.0 * (E - P1) * d) if layer == "rgat"

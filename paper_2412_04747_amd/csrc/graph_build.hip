@@ -185,6 +185,12 @@ __global__ void k_permute_f32(long long n, const int32_t* idx, const float* src,
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = src[idx[i]];
 }
+__global__ void k_pair_ysel(long long P, const int32_t* out_ptr, const int32_t* out_dst, int32_t* ysel) {
+    const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    const int32_t b = out_ptr[p];
+    ysel[p] = (out_ptr[p + 1] - b == 1) ? (int32_t)((uint32_t)out_dst[b] | 0x80000000u) : (int32_t)p;
+}
 __global__ void k_permute_i32(long long n, const int32_t* idx, const int32_t* src, int32_t* dst) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = src[idx[i]];
@@ -387,6 +393,8 @@ rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, co
     LAUNCH(k_tag, (size_t)E, E, g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_OUT_PTR], g->in_pair_tag);
     RGNN_TRY(keep<float>(g, (size_t)E, &g->out_invc));
     LAUNCH(k_permute_f32, (size_t)E, E, g->idx[RGNN_IDX_OUT_EPOS], g->in_invc, g->out_invc);
+    RGNN_TRY(keep<int32_t>(g, (size_t)P, &g->pair_ysel));
+    LAUNCH(k_pair_ysel, (size_t)P, (long long)P, g->idx[RGNN_IDX_OUT_PTR], g->idx[RGNN_IDX_OUT_DST], g->pair_ysel);
 
     // ---- 8. node type of each relation's sources, if it is a single one
     RGNN_TRY(keep<int32_t>(g, (size_t)R, &g->rel_src_type));

@@ -88,9 +88,12 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
 struct RgatSaved { float* Hs; float* att; };
 struct RgatFwdWs { float* wtp; float* s_src; float* s_dst; float* part_m; float* part_s; float* partial; };
 struct RgatBwdWs {
-    float* wtp; float* wsp; float* adz; float* ds_dst; float* ds_src; float* G; float* dXp; float* A; float* U;
+    float* wtp; float* wsp; float* adz; float* ds_dst; float* ds_src; float* ysc; float* G; float* dXp; float* A; float* U;
     float* tl_part; float* partial;
 };
+// Single-head RGAT at widths up to 64: the gradient rows of single-edge pairs are not written per pair;
+// the typed-linear backward reads att_e * dOut[dst_e] through its row selector.
+inline bool rgat_row_select(const rgnn_layer_desc_t* d) { return d->heads == 1 && d->d_out <= 64; }
 
 size_t carve_rgat_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatSaved* s) {
     Carver c(base);
@@ -117,6 +120,7 @@ size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
     w->adz = c.take<float>((size_t)g->E * std::max<size_t>(2, H));   // (att, dz) pairs, or dz per head
     w->ds_dst = c.take<float>((size_t)g->Q * H);
     w->ds_src = c.take<float>((size_t)g->P * H);
+    w->ysc = c.take<float>(rgat_row_select(d) ? (size_t)g->P : 0);
     w->G = c.take<float>((size_t)g->P * d->d_out);
     w->dXp = c.take<float>((size_t)g->P * d->d_in);
     w->A = c.take<float>((size_t)g->R * d->d_in);
@@ -513,8 +517,11 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, wt, w.wtp, st));
         return node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, nullptr, dX, st, 0, 0, H);
     }
-    // 1. per CSR edge: (att_e, dz_e); for single-edge pairs also G[p] and ds_src[p]
-    RGNN_TRY(edge_dot_bwd(g, D, sv.att, sv.Hs, dO, static_cast<const float*>(out), desc->slope, w.adz, w.G, w.ds_src, st));
+    // 1. per CSR edge: (att_e, dz_e); for single-edge pairs also ds_src[p] and G[p] = att_e dOut[dst_e] (or, with
+    //    the row selector, only att_e: step 4 then reads the row from dOut)
+    const bool sel = rgat_row_select(desc);
+    RGNN_TRY(edge_dot_bwd(g, D, sv.att, sv.Hs, dO, static_cast<const float*>(out), desc->slope, w.adz, w.G, w.ds_src,
+                          sel ? w.ysc : nullptr, st));
     // 2. ds_dst[q] = sum over the run's edges of dz;  ds_src[p] = sum over the pair's edges of dz
     RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], g->long_runs, nullptr, w.adz, 2, 1, w.ds_dst, st, "ds_dst_sum"));
     RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2, 1, w.ds_src, st, "ds_src_sum", 2));
@@ -529,6 +536,7 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     b.tiles = &g->pair_tiles_wide; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
     b.rowscale = w.ds_src; b.vec = w.wsp; b.dW = static_cast<float*>(dW); b.Avec = w.A;
     b.part = w.tl_part;
+    if (sel) { b.ysel = g->pair_ysel; b.dY_alt = dO; b.yscale = w.ysc; }
     RGNN_TRY(typed_linear_bwd(K, D, b, st));
     // 5. U[r] = sum over r's runs of ds_dst[q] X[run_dst[q]]
     RGNN_TRY(gather_sum(g->relrun_items, K, g->idx[RGNN_IDX_RELRUN_IDX], g->relrun_dst, 0, w.ds_dst, 1, 0, Xf,

@@ -115,6 +115,7 @@ struct rgnn_graph {
     rgnn::ItemList pair_items_multi;       // the same, pairs with two or more edges only
     rgnn::ItemList srcpair_items;          // pairs by source node (never cut)
     int32_t* in_pair_tag = nullptr;        // [E] in_pair with the top bit set when the pair has a single edge
+    int32_t* pair_ysel = nullptr;          // [P] pair id, or for a pair with one edge the top bit | that edge's destination
     int32_t* relrun_dst = nullptr;         // [Q] destination of the runs in (relation, destination) order: run_dst[relrun_idx[i]]
     int32_t* rel_src_type = nullptr;       // [R] node type of the sources of relation r (0 for a relation without edges)
     bool rel_src_tied = false;             // every relation's sources are of one node type (rel_src_type is then valid)
@@ -165,6 +166,11 @@ struct TypedLinearBwdArgs {
     float* Avec;             // [segs][KD] (with rowscale)
     float* part;             // scratch [num_slots][KD*ND + KD]
     const char* label;
+    // Optional row selector (widths up to 64, ungathered dY with rowscale): row i of dY is
+    // ysel[i] < 0 ? yscale[i] * dY_alt[ysel[i] & 0x7FFFFFFF] : dY[ysel[i]].
+    const int32_t* ysel = nullptr;
+    const float* dY_alt = nullptr;
+    const float* yscale = nullptr;
 };
 // bf16 matrix-core variant (typed_linear_bf16.hip): Y[i] = A[g(i)] W[seg]  (or W[seg]^T)
 struct TypedLinearBf16Args {

@@ -19,8 +19,10 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
 rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, const int32_t* via, const int32_t* rowidx,
                                 int row_by_k, const float* coef, const float* src, float* out, float* partial,
                                 hipStream_t st, const char* label, const char* combine_label);
+// yscale (optional, [P]): single-edge pairs get att_e there instead of their row att_e * dOut[v] in G
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
-                           const float* out, float slope, float* adz, float* G, float* ds_src, hipStream_t st);
+                           const float* out, float slope, float* adz, float* G, float* ds_src, float* yscale,
+                           hipStream_t st);
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const float* ds_dst, const float* wtp,
                             const float* extra, void* dX, hipStream_t st, int in_bf16 = 0, int out_bf16 = 0, int heads = 1,
                             const void* dXp2 = nullptr);

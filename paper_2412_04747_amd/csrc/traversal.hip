@@ -481,6 +481,7 @@ struct EdgeDotArgs {
     float2* adz;
     float* G;
     float* ds_src;
+    float* yscale;   // if given, a single-edge pair gets att_e here instead of its row att_e * dOut[v] in G
 };
 
 template <int D>
@@ -533,8 +534,11 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
             if (c4 == u) mine = make_float2(al, dz);
             if (live && pr[u] < 0) {   // single-edge pair
                 const size_t p = (size_t)(pr[u] & 0x7FFFFFFF);
-                *reinterpret_cast<float4*>(a.G + p * D + c4 * 4) = make_float4(al * go.x, al * go.y, al * go.z, al * go.w);
-                if (c4 == 0) a.ds_src[p] = dz;
+                if (!a.yscale) *reinterpret_cast<float4*>(a.G + p * D + c4 * 4) = make_float4(al * go.x, al * go.y, al * go.z, al * go.w);
+                if (c4 == 0) {
+                    a.ds_src[p] = dz;
+                    if (a.yscale) a.yscale[p] = al;
+                }
             }
         }
         if (c4 < 4 && j + c4 < e) a.adz[j + c4] = mine;
@@ -863,10 +867,11 @@ rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, c
 }
 
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
-                           const float* out, float slope, float* adz, float* G, float* ds_src, hipStream_t st) {
+                           const float* out, float slope, float* adz, float* G, float* ds_src, float* yscale,
+                           hipStream_t st) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
-    EdgeDotArgs a{dev_items(L), g->in_pair_tag, att, Hs, dOut, out, slope, reinterpret_cast<float2*>(adz), G, ds_src};
+    EdgeDotArgs a{dev_items(L), g->in_pair_tag, att, Hs, dOut, out, slope, reinterpret_cast<float2*>(adz), G, ds_src, yscale};
     KernelTimer kt(st, "edge_dot_bwd");
     RGNN_DISPATCH_D(D, hipLaunchKernelGGL(edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
                                      0, st, a));

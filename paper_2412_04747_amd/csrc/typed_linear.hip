@@ -210,7 +210,14 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
 // rows' contribution to the full KD x ND weight gradient (KB*NB blocks, kept in registers
 // for the whole run) and to Avec.  At the end of a run the eight wavefronts' partial weight
 // gradients are summed in wavefront order through LDS and written to the chunk's slot.
-template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS>
+//
+// SEL (row selector): row i of dY is either dY[ysel[i]] or, when the top bit of ysel[i] is set, row
+// ysel[i] & 0x7FFFFFFF of a second tensor times yscale[i].  (RGAT: the gradient row of a (source,
+// relation) pair with a single edge is att_e * dOut[dst_e]; it is read from dOut here instead of
+// being written out per pair first.)  A lane keeps the selector and the scale of one row of the unit
+// and hands them to the lanes that load or store that row with a cross-lane read.
+struct RowSelect { const int32_t* sel; const float* alt; const float* scale; };
+template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS, bool SEL = false>
 __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, const float* __restrict__ X,
                                                                     const int32_t* __restrict__ gather,
                                                                     const float* __restrict__ W,
@@ -218,7 +225,8 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
                                                                     float* __restrict__ dXrow,
                                                                     const float* __restrict__ rowscale,
                                                                     const float* __restrict__ vec,
-                                                                    float* __restrict__ part) {
+                                                                    float* __restrict__ part, RowSelect ys) {
+    static_assert(!SEL || !DYG, "the row selector replaces the dY gather");
     constexpr int NW = 8;
     constexpr int XS = KD + 4, YS = (ND > KD ? ND : KD) + 4, WS = ND + 1;
     constexpr int KB = KD / 32, NB = ND / 32, WB = KB * NB;
@@ -261,12 +269,15 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
         v4f xr[NXR], yr[NYR];
         float dsr = 0.f;
         int gi[NXR], gcur[NXR];
+        int ysn = 0;          // SEL: selector of row (lane & 31) of the unit whose rows are fetched next
+        float alr = 1.f;      // SEL: scale of row (lane & 31) of the unit whose rows are in yr
         auto fetch_idx = [&](int u) {
 #pragma unroll
             for (int it = 0; it < NXR; ++it) {
                 const int row = min(ra + u * 32 + rx + it * RPX, rbnd - 1);
                 gi[it] = GATHER ? gather[row] : row;
             }
+            if (SEL) ysn = ys.sel[min(ra + u * 32 + (lane & 31), rbnd - 1)];
         };
         auto fetch = [&](int u) {
 #pragma unroll
@@ -276,10 +287,17 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
             }
 #pragma unroll
             for (int it = 0; it < NYR; ++it) {
-                const size_t s2 = DYG ? (size_t)gi[it] : (size_t)min(ra + u * 32 + ry + it * RPY, rbnd - 1);
-                yr[it] = *reinterpret_cast<const v4f*>(dY + s2 * ND + cy * 4);
+                if (SEL) {
+                    const int sl = __shfl(ysn, ry + it * RPY);
+                    const float* base = sl < 0 ? ys.alt : dY;
+                    yr[it] = *reinterpret_cast<const v4f*>(base + (size_t)(sl & 0x7FFFFFFF) * ND + cy * 4);
+                } else {
+                    const size_t s2 = DYG ? (size_t)gi[it] : (size_t)min(ra + u * 32 + ry + it * RPY, rbnd - 1);
+                    yr[it] = *reinterpret_cast<const v4f*>(dY + s2 * ND + cy * 4);
+                }
             }
             if (RS) dsr = rowscale[min(ra + u * 32 + (lane & 31), rbnd - 1)];
+            if (SEL) alr = ysn < 0 ? ys.scale[min(ra + u * 32 + (lane & 31), rbnd - 1)] : 1.f;
         };
         fetch_idx(wave);
         fetch(wave);
@@ -299,6 +317,10 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
             for (int it = 0; it < NYR; ++it) {
                 const bool ok = ry + it * RPY < rows_left;
                 v4f v = yr[it];
+                if (SEL) {
+                    const float sc = __shfl(alr, ry + it * RPY);
+                    v = v4f{v[0] * sc, v[1] * sc, v[2] * sc, v[3] * sc};
+                }
                 if (!ok) v = v4f{0.f, 0.f, 0.f, 0.f};
                 *reinterpret_cast<v4f*>(Yw + (ry + it * RPY) * YS + cy * 4) = v;
             }
@@ -579,16 +601,16 @@ static rgnn_status_t launch_slot_reduce(int kd, int nd, const TypedLinearBwdArgs
     return RGNN_OK;
 }
 
-template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS>
+template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS, bool SEL = false>
 static rgnn_status_t launch_bwd_wave(const TypedLinearBwdArgs& a, hipStream_t st) {
     constexpr int WREG = 32 * (KD + 4) + 32 * ((ND > KD ? ND : KD) + 4) + 32;
     static_assert(WREG >= KD * ND + KD, "per-wavefront LDS region must hold a weight-gradient copy");
     const size_t lds = sizeof(float) * (KD * (ND + 1) + 8 * WREG);
-    auto kern = typed_linear_bwd_wave_kernel<KD, ND, GATHER, DYG, SCATTER, RS>;
+    auto kern = typed_linear_bwd_wave_kernel<KD, ND, GATHER, DYG, SCATTER, RS, SEL>;
     RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(512), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
-                       a.dY, a.dXrow, a.rowscale, a.vec, a.part);
+                       a.dY, a.dXrow, a.rowscale, a.vec, a.part, RowSelect{a.ysel, a.dY_alt, a.yscale});
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -630,13 +652,17 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
     if (a.tiles->num_tiles > 0) {
         bool done = false;
         if constexpr (KD == 128 && ND == 128) {
+            if (a.ysel) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: no row selector at width 128");
             RGNN_TRY(launch_bwd_split<128>(a, st));
             done = true;
         }
         if constexpr (KD <= 64 && ND <= 64) {
             const bool g = a.gather != nullptr, dg = g && a.dy_gathered, sc = g && a.scatter_dx, rs = a.rowscale != nullptr;
             done = true;
-            if (g && !dg && !sc && rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true>(a, st)));
+            if (a.ysel && !(g && !dg && !sc && rs && a.dY_alt && a.yscale))
+                RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: the row selector needs gathered X, ungathered dY and rowscale");
+            if (a.ysel) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true, true>(a, st)));
+            else if (g && !dg && !sc && rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true>(a, st)));
             else if (g && !dg && !sc && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, false>(a, st)));
             else if (g && dg && sc && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, true, true, false>(a, st)));
             else if (!g && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, false, false, false, false>(a, st)));
