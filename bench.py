@@ -72,8 +72,13 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
         "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8) + P1 * ((4 if sel else row) + 4), 2.0 * E * d),
         # RGAT: only the E - P1 edges of the P - P1 pairs with several edges; coefficient = the (att, dz) pair.
         # RGCN: every edge; row + out_dst + coefficient
+        # RGCN with bf16 rows: likewise only pairs with several edges (the typed-linear backward reads the
+        # others' rows from the per-run rows of run_scaled_rows)
         "aggregate_bwd_pair": ("hbm", (E - P1) * (row + 16) + (P - P1) * (row + 8), 2.0 * (E - P1) * d) if layer == "rgat"
+                              else ("hbm", (E - P1) * (row + 8) + (P - P1) * (row + 8), 2.0 * (E - P1) * d) if half
                               else ("hbm", E * (row + 8) + P * (row + 8), 2.0 * E * d),
+        # per run: dPre row in, scaled row out, run_ptr + run_dst
+        "run_scaled_rows": ("hbm", Q * (2 * row + 8), 1.0 * Q * d),
         # per run: X row + relrun_idx + run_dst + ds_dst
         "dst_side_wgrad": ("hbm", Q * (row + 12), 2.0 * Q * d),
         # per pair: dXp row + srcpair_idx; per run (RGAT): ds_dst + run_rel; per node: result row + 2 ptrs
@@ -256,7 +261,7 @@ def main():
     g = Graph(N, R, c["src"], c["dst"], c["rel"], c.get("ntype") if T > 1 else None, T,
               c.get("rel_src_ntype"), c.get("rel_dst_ntype"))
     P, Q = g.P, g.Q
-    P1 = int(g.info.num_single_pairs) if c["layer"] == "rgat" else 0
+    P1 = int(g.info.num_single_pairs) if c["layer"] in ("rgat", "rgcn") else 0
     print(f"[bench] graph index built in {time.time() - t0:.1f}s: P/E={P / E:.3f} Q/E={Q / E:.3f} "
           f"max in-degree {g.info.max_in_degree} index {g.info.index_bytes / 2**20:.0f} MiB", file=sys.stderr, flush=True)
     L = make_layer(c, g, args.heads)

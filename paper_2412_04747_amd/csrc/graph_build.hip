@@ -191,6 +191,13 @@ __global__ void k_pair_ysel(long long P, const int32_t* out_ptr, const int32_t* 
     const int32_t b = out_ptr[p];
     ysel[p] = (out_ptr[p + 1] - b == 1) ? (int32_t)((uint32_t)out_dst[b] | 0x80000000u) : (int32_t)p;
 }
+__global__ void k_pair_ysel_run(long long P, const int32_t* out_ptr, const int32_t* out_epos, const int32_t* in_run,
+                                int32_t* ysel) {
+    const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    const int32_t b = out_ptr[p];
+    ysel[p] = (out_ptr[p + 1] - b == 1) ? (int32_t)((uint32_t)in_run[out_epos[b]] | 0x80000000u) : (int32_t)p;
+}
 __global__ void k_permute_i32(long long n, const int32_t* idx, const int32_t* src, int32_t* dst) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = src[idx[i]];
@@ -395,6 +402,9 @@ rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, co
     LAUNCH(k_permute_f32, (size_t)E, E, g->idx[RGNN_IDX_OUT_EPOS], g->in_invc, g->out_invc);
     RGNN_TRY(keep<int32_t>(g, (size_t)P, &g->pair_ysel));
     LAUNCH(k_pair_ysel, (size_t)P, (long long)P, g->idx[RGNN_IDX_OUT_PTR], g->idx[RGNN_IDX_OUT_DST], g->pair_ysel);
+    RGNN_TRY(keep<int32_t>(g, (size_t)P, &g->pair_ysel_run));
+    LAUNCH(k_pair_ysel_run, (size_t)P, (long long)P, g->idx[RGNN_IDX_OUT_PTR], g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_IN_RUN],
+           g->pair_ysel_run);
 
     // ---- 8. node type of each relation's sources, if it is a single one
     RGNN_TRY(keep<int32_t>(g, (size_t)R, &g->rel_src_type));

@@ -115,6 +115,7 @@ struct rgnn_graph {
     rgnn::ItemList pair_items_multi;       // the same, pairs with two or more edges only
     rgnn::ItemList srcpair_items;          // pairs by source node (never cut)
     int32_t* in_pair_tag = nullptr;        // [E] in_pair with the top bit set when the pair has a single edge
+    int32_t* pair_ysel_run = nullptr;      // [P] the same with the (destination, relation) run of that edge
     int32_t* pair_ysel = nullptr;          // [P] pair id, or for a pair with one edge the top bit | that edge's destination
     int32_t* relrun_dst = nullptr;         // [Q] destination of the runs in (relation, destination) order: run_dst[relrun_idx[i]]
     int32_t* rel_src_type = nullptr;       // [R] node type of the sources of relation r (0 for a relation without edges)
@@ -186,6 +187,8 @@ struct TypedLinearBf16Args {
     int y_bf16;
     int accumulate;          // 1: Y += result (fp32 Y)
     const char* label;
+    const void* A_alt = nullptr;   // gathered rows only: a gather entry with the top bit set reads row
+                                   // (entry & 0x7FFFFFFF) of this tensor instead of A
 };
 rgnn_status_t typed_linear_bf16(int d, const TypedLinearBf16Args& a, hipStream_t st);
 
@@ -199,6 +202,10 @@ struct TypedLinearWgradBf16Args {
     const void* dY;          // bf16 rows
     float* part;
     const char* label;
+    // optional row selector for dY (ungathered dY only): row i is dY[ysel[i]], or dY_alt[ysel[i] & 0x7FFFFFFF]
+    // when the top bit of ysel[i] is set
+    const int32_t* ysel = nullptr;
+    const void* dY_alt = nullptr;
 };
 rgnn_status_t typed_linear_wgrad_bf16(int d, const TypedLinearWgradBf16Args& a, hipStream_t st);
 rgnn_status_t typed_linear_slot_reduce(int d_in, int d_out, const TileList& tiles, const float* part, float* dW,

@@ -60,6 +60,8 @@ rgnn_status_t add_head_rank1(int64_t n, int D, int H, const float* coef, const i
                              hipStream_t st);
 rgnn_status_t rgat_heads_param_finish(int R, int kd, int nd, int H, const float* W, const float* w_t, const float* U,
                                       float* dW, float* dw_t, hipStream_t st);
+// T[q] = dPre[run_dst[q]] / (entries of run q), bf16 rows of width 128
+rgnn_status_t run_scaled_rows(const rgnn_graph* g, int D, const void* dPre, void* T, hipStream_t st);
 rgnn_status_t add3(size_t n, const float* a, const float* b, const float* c, float* out, hipStream_t st);
 
 rgnn_status_t widen_bf16(size_t n, const uint16_t* src, float* dst, hipStream_t st);

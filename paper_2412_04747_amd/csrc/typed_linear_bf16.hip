@@ -70,10 +70,12 @@ __device__ __forceinline__ int run_end_b(const int32_t* __restrict__ tile_seg, i
 //   WT     false: Y = A W  (W stored [CD][OD])          true: Y = A W^T  (W stored [OD][CD])
 //   GATHER rows are read through the gather list        SCATTER outputs are written through it as well
 //   Y_BF16 output rows are stored as bf16 / fp32        ACC    (fp32 output only) Y += result
+// A gather entry with the top bit set reads row (entry & 0x7FFFFFFF) of Alt instead of A (not with SCATTER).
 template <int CD, int OD, bool A_BF16, bool W_BF16, bool WT, bool GATHER, bool SCATTER, bool Y_BF16, bool ACC>
 __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, const void* __restrict__ Av,
                                                                 const int32_t* __restrict__ gather,
-                                                                const void* __restrict__ Wv, void* __restrict__ Yv) {
+                                                                const void* __restrict__ Wv, void* __restrict__ Yv,
+                                                                const void* __restrict__ Alt) {
     constexpr int NW = 4;
     constexpr int LS = CD + 8;                                // LDS row stride in bf16 elements (16-byte aligned rows)
     constexpr int OB = OD / 32;
@@ -118,7 +120,8 @@ __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, con
     }
 #define RGNN_FETCH_ROWS()                                                       \
     _Pragma("unroll") for (int it = 0; it < NX; ++it) {                         \
-        const char* p_ = static_cast<const char*>(Av) + (size_t)gi[it] * CD * (A_BF16 ? 2 : 4) + ci * 16; \
+        const char* b_ = static_cast<const char*>(GATHER && !SCATTER && gi[it] < 0 ? Alt : Av); \
+        const char* p_ = b_ + (size_t)(GATHER && !SCATTER ? gi[it] & 0x7FFFFFFF : gi[it]) * CD * (A_BF16 ? 2 : 4) + ci * 16; \
         xr[it] = *reinterpret_cast<const v4u*>(p_);                             \
         gcur[it] = gi[it];                                                      \
     }
@@ -257,13 +260,17 @@ __device__ __forceinline__ void transpose4_to_lds(unsigned short* __restrict__ T
     }
 }
 
-template <int D, bool GATHER, bool DYG, int NBUF>
+// SEL: row i of dY is dY[ysel[i]], or dYalt[ysel[i] & 0x7FFFFFFF] when the top bit of ysel[i] is set.
+template <int D, bool GATHER, bool DYG, int NBUF, bool SEL = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void typed_linear_wgrad_bf16_kernel(TileArgsB t, const int32_t* __restrict__ chunk_slot,
                                                                       const unsigned short* __restrict__ X,
                                                                       const int32_t* __restrict__ gather,
                                                                       const unsigned short* __restrict__ dY,
-                                                                      float* __restrict__ part) {
+                                                                      float* __restrict__ part,
+                                                                      const int32_t* __restrict__ ysel,
+                                                                      const unsigned short* __restrict__ dYalt) {
     static_assert(D == 128, "four wavefronts x four 32-column blocks");
+    static_assert(!(SEL && DYG), "the row selector replaces the dY gather");
     constexpr int TMW = 64;
     constexpr int LPX = D / 8;                        // lanes per row (16-byte loads)
     constexpr int SLOT = D * D + D;
@@ -283,13 +290,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const int wat = cx * 512 + 4 * (rq & 1), wg8_0 = (((rq >> 1) ^ cx) & 7) * 8;
     const int rg8_0 = ((kh ^ m ^ (m >> 3)) & 7) * 8;
     v4u xr[4], yr[4];
-    int gi[4];
+    int gi[4], gy[SEL ? 4 : 1];
 #define RGNN_W_FETCH_IDX(TI)                                                        \
     {                                                                               \
         const int row0_ = t.tile_row0[TI], row1_ = t.tile_row1[TI];                 \
         _Pragma("unroll") for (int k = 0; k < 4; ++k) {                             \
             const int row_ = min(row0_ + 4 * rq + k, row1_ - 1);                    \
             gi[k] = GATHER ? gather[row_] : row_;                                   \
+            if (SEL) gy[SEL ? k : 0] = ysel[row_];                                  \
         }                                                                           \
     }
 #define RGNN_W_FETCH(TI)                                                            \
@@ -298,8 +306,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         _Pragma("unroll") for (int k = 0; k < 4; ++k) {                             \
             xr[k] = *reinterpret_cast<const v4u*>(X + (size_t)gi[k] * D + cx * 8);  \
             const int row_ = min(row0_ + 4 * rq + k, row1_ - 1);                    \
-            const size_t s_ = (DYG && GATHER) ? (size_t)gi[k] : (size_t)row_;       \
-            yr[k] = *reinterpret_cast<const v4u*>(dY + s_ * D + cx * 8);            \
+            if (SEL) {                                                              \
+                const int y_ = gy[SEL ? k : 0];                                     \
+                yr[k] = *reinterpret_cast<const v4u*>((y_ < 0 ? dYalt : dY) + (size_t)(y_ & 0x7FFFFFFF) * D + cx * 8); \
+            } else {                                                                \
+                const size_t s_ = (DYG && GATHER) ? (size_t)gi[k] : (size_t)row_;   \
+                yr[k] = *reinterpret_cast<const v4u*>(dY + s_ * D + cx * 8);        \
+            }                                                                       \
         }                                                                           \
     }
     if (t0 < t1) {
@@ -361,16 +374,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 #undef RGNN_W_FETCH
 }
 
-template <bool GATHER, bool DYG>
+template <bool GATHER, bool DYG, bool SEL = false>
 static rgnn_status_t launch_wgrad(const TypedLinearWgradBf16Args& a, hipStream_t st) {
     constexpr int D = 128, NBUF = 1;
     const size_t lds = sizeof(unsigned short) * NBUF * (2 * D * 64);
-    auto kern = typed_linear_wgrad_bf16_kernel<D, GATHER, DYG, NBUF>;
+    auto kern = typed_linear_wgrad_bf16_kernel<D, GATHER, DYG, NBUF, SEL>;
     RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_wgrad");
     TileArgsB t{a.tiles->tile_seg, a.tiles->tile_row0, a.tiles->tile_row1, a.tiles->chunk_tile};
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.tiles->chunk_slot,
-                       static_cast<const unsigned short*>(a.X), a.gather, static_cast<const unsigned short*>(a.dY), a.part);
+                       static_cast<const unsigned short*>(a.X), a.gather, static_cast<const unsigned short*>(a.dY), a.part,
+                       a.ysel, static_cast<const unsigned short*>(a.dY_alt));
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -380,6 +394,10 @@ rgnn_status_t typed_linear_wgrad_bf16(int d, const TypedLinearWgradBf16Args& a, 
     if (d != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_wgrad_bf16: width %d not supported (128)", d);
     if (a.tiles->num_tiles == 0) return RGNN_OK;
     const bool g = a.gather != nullptr, dg = g && a.dy_gathered;
+    if (a.ysel) {
+        if (!g || dg || !a.dY_alt) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_wgrad_bf16: the row selector needs gathered X and ungathered dY");
+        return launch_wgrad<true, false, true>(a, st);
+    }
     if (g && dg) return launch_wgrad<true, true>(a, st);
     if (g) return launch_wgrad<true, false>(a, st);
     return launch_wgrad<false, false>(a, st);
@@ -393,7 +411,7 @@ static rgnn_status_t launch(const TypedLinearBf16Args& a, hipStream_t st) {
     RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_bf16");
     TileArgsB t{a.tiles->tile_seg, a.tiles->tile_row0, a.tiles->tile_row1, a.tiles->chunk_tile};
-    hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.A, a.gather, a.W, a.Y);
+    hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.A, a.gather, a.W, a.Y, a.A_alt);
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -401,6 +419,7 @@ static rgnn_status_t launch(const TypedLinearBf16Args& a, hipStream_t st) {
 template <int D, bool A_BF16, bool W_BF16, bool WT, bool Y_BF16, bool ACC = false>
 static rgnn_status_t launch_gs(const TypedLinearBf16Args& a, hipStream_t st) {
     const bool g = a.gather != nullptr, sc = g && a.scatter_out;
+    if (a.A_alt && !(g && !sc)) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_bf16: a second row tensor needs gathered, unscattered rows");
     if (g && sc) return launch<D, D, A_BF16, W_BF16, WT, true, true, Y_BF16, ACC>(a, st);
     if constexpr (ACC) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_bf16: accumulation is built for gathered + scattered rows only");
     if (g) return launch<D, D, A_BF16, W_BF16, WT, true, false, Y_BF16, false>(a, st);
