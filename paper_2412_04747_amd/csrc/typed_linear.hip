@@ -271,19 +271,29 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
         int gi[NXR], gcur[NXR];
         int ysn = 0;          // SEL: selector of row (lane & 31) of the unit whose rows are fetched next
         float alr = 1.f;      // SEL: scale of row (lane & 31) of the unit whose rows are in yr
+        // LANEIDX: the gather index of row (lane & 31) is kept by that lane and handed to the lanes that
+        // load the row with a cross-lane read (one register instead of NXR); the variants that reuse the
+        // indices for dY or for the scattered store keep them per load.
+        constexpr bool LANEIDX = GATHER && !DYG && !SCATTER;
+        int gsn = 0;
         auto fetch_idx = [&](int u) {
+            if (LANEIDX) {
+                gsn = gather[min(ra + u * 32 + (lane & 31), rbnd - 1)];
+            } else {
 #pragma unroll
-            for (int it = 0; it < NXR; ++it) {
-                const int row = min(ra + u * 32 + rx + it * RPX, rbnd - 1);
-                gi[it] = GATHER ? gather[row] : row;
+                for (int it = 0; it < NXR; ++it) {
+                    const int row = min(ra + u * 32 + rx + it * RPX, rbnd - 1);
+                    gi[it] = GATHER ? gather[row] : row;
+                }
             }
             if (SEL) ysn = ys.sel[min(ra + u * 32 + (lane & 31), rbnd - 1)];
         };
         auto fetch = [&](int u) {
 #pragma unroll
             for (int it = 0; it < NXR; ++it) {
-                xr[it] = *reinterpret_cast<const v4f*>(X + (size_t)gi[it] * KD + cx * 4);
-                gcur[it] = gi[it];
+                const int gx = LANEIDX ? __shfl(gsn, rx + it * RPX) : gi[it];
+                xr[it] = *reinterpret_cast<const v4f*>(X + (size_t)gx * KD + cx * 4);
+                gcur[it] = gx;
             }
 #pragma unroll
             for (int it = 0; it < NYR; ++it) {
