@@ -516,9 +516,9 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], dz, H, 0,
                                     w.ds_src, st, "ds_src_sum", 0, H));
         // 3. dHs[p] = sum_{e in out(p)} |att_e| dOut[dst_e] (per head)  +  ds_src[p][h] w_s[r] (per head)
+        const Rank1 r1{w.ds_src, H, g->idx[RGNN_IDX_PAIR_REL], ws};      // the second term, added when a pair's row is stored
         RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, sv.att, H, 1, dO, w.G,
-                            w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", H));
-        RGNN_TRY(add_head_rank1(g->P, D, H, w.ds_src, g->idx[RGNN_IDX_PAIR_REL], ws, w.G, st));
+                            w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", H, 0, 0, &r1));
         // 4. dXp = dHs W^T, dW = sum X^T dHs
         TypedLinearBwdArgs b{};
         b.tiles = &g->pair_tiles_wide; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;

@@ -69,22 +69,6 @@ __global__ void edge_logit_heads_kernel(int64_t total, int H, const int32_t* __r
     att[i] = z > 0.f ? z : slope * z;
 }
 
-// rows[i][head h] += coef[i][h] * vec[seg[i]][head h]
-template <int D>
-__global__ __launch_bounds__(256) void add_head_rank1_kernel(int64_t n, int H, const float* __restrict__ coef,
-                                                             const int32_t* __restrict__ seg,
-                                                             const float* __restrict__ vec, float* __restrict__ rows) {
-    constexpr int LPR = D / 4;
-    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPR;
-    const int c4 = threadIdx.x % LPR;
-    if (i >= n) return;
-    const float c = coef[(size_t)i * H + c4 / (LPR / H)];
-    float4 x = *reinterpret_cast<const float4*>(rows + (size_t)i * D + c4 * 4);
-    const float4 v = *reinterpret_cast<const float4*>(vec + (size_t)seg[i] * D + c4 * 4);
-    fma4(x, c, v);
-    *reinterpret_cast<float4*>(rows + (size_t)i * D + c4 * 4) = x;
-}
-
 // Per relation r, with U[h][r] = sum_q ds_dst[q][h] X[dst_q] and h(n) the head of column n:
 //   dw_t[r][n] = sum_k U[h(n)][r][k] W[r][k][n];   dW[r][k][n] += U[h(n)][r][k] * w_t[r][n]
 __global__ void rgat_heads_param_finish_kernel(int R, int kd, int nd, int H, const float* __restrict__ W,
@@ -142,16 +126,6 @@ rgnn_status_t edge_logit_heads(const rgnn_graph* g, int H, const float* s_src, c
     const int64_t total = g->E * H;
     hipLaunchKernelGGL(edge_logit_heads_kernel, dim3(blocks_for((size_t)total, 256)), dim3(256), 0, st, total, H,
                        g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN], s_src, s_dst, slope, att);
-    RGNN_CHECK_LAUNCH();
-    return RGNN_OK;
-}
-
-rgnn_status_t add_head_rank1(int64_t n, int D, int H, const float* coef, const int32_t* seg, const float* vec, float* rows,
-                             hipStream_t st) {
-    if (n == 0) return RGNN_OK;
-    KernelTimer kt(st, "add_src_logit_grad");
-    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(add_head_rank1_kernel<DD>, dim3(blocks_for((size_t)n * (DD / 4), 256)), dim3(256), 0,
-                                          st, n, H, coef, seg, vec, rows));
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

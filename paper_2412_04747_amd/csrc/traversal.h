@@ -11,10 +11,12 @@ rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng,
                                  int heads = 1);
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
                            float* part_m, float* part_s, hipStream_t st);
+// Optional rank-1 term of a gather-sum: out[i] += coef[i * stride + head] * vec[seg[i]] (fp32 vec rows of the output width)
+struct Rank1 { const float* coef; int stride; const int32_t* seg; const float* vec; };
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
                          const float* coef, int cstride, int cabs, const void* src, void* out, float* partial,
                          hipStream_t st, int role, const char* label, const char* combine_label, int heads = 1,
-                         int src_bf16 = 0, int out_bf16 = 0);
+                         int src_bf16 = 0, int out_bf16 = 0, const Rank1* r1 = nullptr);
 // H weighted sums of the same gathered rows in one walk (coef [entries][H]); out [H][out_rows][D]
 rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, const int32_t* via, const int32_t* rowidx,
                                 int row_by_k, const float* coef, const float* src, float* out, float* partial,
@@ -56,8 +58,6 @@ rgnn_status_t run_logit_heads(const rgnn_graph* g, int D, int H, const float* X,
                               hipStream_t st);
 rgnn_status_t edge_logit_heads(const rgnn_graph* g, int H, const float* s_src, const float* s_dst, float slope, float* att,
                                hipStream_t st);
-rgnn_status_t add_head_rank1(int64_t n, int D, int H, const float* coef, const int32_t* seg, const float* vec, float* rows,
-                             hipStream_t st);
 rgnn_status_t rgat_heads_param_finish(int R, int kd, int nd, int H, const float* W, const float* w_t, const float* U,
                                       float* dW, float* dw_t, hipStream_t st);
 // T[q] = dPre[run_dst[q]] / (entries of run q), bf16 rows of width 128

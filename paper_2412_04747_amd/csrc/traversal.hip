@@ -248,7 +248,18 @@ struct GatherArgs {
     float* partial;       // fp32 rows
     int skip_first;       // items [skip_first, skip_first + skip_n) are left to gather_single_kernel
     int skip_n;
+    Rank1 r1;             // optional: out[row_i] += r1.coef[row_i][head] * r1.vec[r1.seg[row_i]] (whole segments here,
+                          // cut segments when their pieces are combined)
 };
+
+template <int D, int V>
+__device__ __forceinline__ void add_rank1(const Rank1& r1, int lanes_per_head, size_t row, int cv, float (&acc)[V]) {
+    if (!r1.coef) return;
+    const float c = r1.coef[row * r1.stride + cv / lanes_per_head];
+    float t[V];
+    load_cols(r1.vec + (size_t)r1.seg[row] * D + cv * V, t);
+    fma_cols(acc, c, t);
+}
 
 // ROLE only gives each use its own kernel name in profiler output (0 forward aggregation over
 // destinations, 1 backward aggregation over pairs, 2 destination-side weight gradient).
@@ -302,8 +313,12 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
 #undef RGNN_GATHER_FETCH_IDX
     fma_cols(acc0, 1.f, acc1);
     const int slot = a.it.slot[i];
-    if (slot < 0) store_cols(static_cast<TO*>(a.out) + (size_t)a.it.row[i] * D + cv * V, acc0);
-    else store_cols(a.partial + (size_t)slot * D + cv * V, acc0);
+    if (slot < 0) {
+        add_rank1<D>(a.r1, a.lanes_per_head, (size_t)a.it.row[i], cv, acc0);
+        store_cols(static_cast<TO*>(a.out) + (size_t)a.it.row[i] * D + cv * V, acc0);
+    } else {
+        store_cols(a.partial + (size_t)slot * D + cv * V, acc0);
+    }
 }
 
 // The whole segments with 2..kShortLen entries, items [first, first + n).  One batch of row loads covers
@@ -350,7 +365,10 @@ __global__ __launch_bounds__(256) void gather_short_kernel(GatherArgs a, int fir
         zero_cols(acc);
 #pragma unroll
         for (int u = 0; u < kShortLen; ++u) fma_cols(acc, c[q][u], v[q][u]);
-        if (i0 + q < n) store_cols(static_cast<TO*>(a.out) + (size_t)orow[q] * D + cv * V, acc);
+        if (i0 + q < n) {
+            add_rank1<D>(a.r1, a.lanes_per_head, (size_t)orow[q], cv, acc);
+            store_cols(static_cast<TO*>(a.out) + (size_t)orow[q] * D + cv * V, acc);
+        }
     }
 }
 
@@ -389,6 +407,7 @@ __global__ __launch_bounds__(256) void gather_single_kernel(GatherArgs a, int fi
         if (i0 + u < n) {
 #pragma unroll
             for (int q = 0; q < V; ++q) v[u][q] *= c[u];
+            add_rank1<D>(a.r1, a.lanes_per_head, (size_t)orow[u], cv, v[u]);
             store_cols(static_cast<TO*>(a.out) + (size_t)orow[u] * D + cv * V, v[u]);
         }
     }
@@ -439,7 +458,7 @@ template <int D, typename TO>
 __global__ __launch_bounds__(1024) void combine_partials_kernel(const int32_t* __restrict__ split_row,
                                                                 const int32_t* __restrict__ split_ptr,
                                                                 const float* __restrict__ partial,
-                                                                TO* __restrict__ out) {
+                                                                TO* __restrict__ out, Rank1 r1, int lanes_per_head) {
     constexpr int LPR = D / 4, G = 1024 / LPR;
     __shared__ float4 red[1024];
     const int s = blockIdx.x, g = threadIdx.x / LPR, c4 = threadIdx.x % LPR;
@@ -455,7 +474,8 @@ __global__ __launch_bounds__(1024) void combine_partials_kernel(const int32_t* _
     if (g == 0) {
         float4 t = red[c4];
         for (int k = 1; k < G; ++k) fma4(t, 1.f, red[k * LPR + c4]);
-        const float tv[4] = {t.x, t.y, t.z, t.w};
+        float tv[4] = {t.x, t.y, t.z, t.w};
+        add_rank1<D>(r1, lanes_per_head, (size_t)split_row[s], c4, tv);
         store_cols(out + (size_t)split_row[s] * D + c4 * 4, tv);
     }
 }
@@ -825,14 +845,15 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
                          const float* coef, int cstride, int cabs, const void* src, void* out, float* partial,
                          hipStream_t st, int role, const char* label, const char* combine_label, int heads,
-                         int src_bf16, int out_bf16) {
+                         int src_bf16, int out_bf16, const Rank1* r1) {
     if (L.num_items == 0) return RGNN_OK;
+    const Rank1 r1v = r1 ? *r1 : Rank1{nullptr, 0, nullptr, nullptr};
     const int lpr = D / (src_bf16 ? 8 : 4);
     // enough short / single-entry segments to be worth launches of their own; the two ranges are adjacent
     const int ns = L.num_single >= 4096 ? L.num_single : 0;
     const int nsh = L.num_short >= 4096 ? L.num_short : 0;
     const int skip_first = nsh > 0 ? L.first_short : L.first_single;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns};
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns, r1v};
     {
         KernelTimer kt(st, label);
         const dim3 grid(blocks_for(L.num_items - nsh - ns, 256 / lpr));
@@ -858,10 +879,10 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
         KernelTimer kt(st, combine_label);
         if (out_bf16)
             RGNN_DISPATCH_D(D, hipLaunchKernelGGL((combine_partials_kernel<DD, bf16_t>), dim3(L.num_split), dim3(1024), 0, st,
-                                                  L.split_row, L.split_ptr, partial, static_cast<bf16_t*>(out)));
+                                                  L.split_row, L.split_ptr, partial, static_cast<bf16_t*>(out), r1v, (DD / 4) / heads));
         else
             RGNN_DISPATCH_D(D, hipLaunchKernelGGL((combine_partials_kernel<DD, float>), dim3(L.num_split), dim3(1024), 0, st,
-                                                  L.split_row, L.split_ptr, partial, static_cast<float*>(out)));
+                                                  L.split_row, L.split_ptr, partial, static_cast<float*>(out), r1v, (DD / 4) / heads));
         RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;
@@ -871,7 +892,7 @@ rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, c
                                 int row_by_k, const float* coef, const float* src, float* out, float* partial,
                                 hipStream_t st, const char* label, const char* combine_label) {
     if (L.num_items == 0) return RGNN_OK;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, H, 0, 1, src, out, partial, 0, 0};
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, H, 0, 1, src, out, partial, 0, 0, Rank1{nullptr, 0, nullptr, nullptr}};
     {
         KernelTimer kt(st, label);
         const dim3 grid(blocks_for(L.num_items, 256 / (D / 4)));
@@ -888,7 +909,7 @@ rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, c
         for (int h = 0; h < H; ++h) {
             RGNN_DISPATCH_D(D, hipLaunchKernelGGL((combine_partials_kernel<DD, float>), dim3(L.num_split), dim3(1024), 0, st,
                                                   L.split_row, L.split_ptr, partial + (size_t)h * L.num_partials * D,
-                                                  out + (size_t)h * out_rows * D));
+                                                  out + (size_t)h * out_rows * D, Rank1{nullptr, 0, nullptr, nullptr}, 1));
             RGNN_CHECK_LAUNCH();
         }
     }
