@@ -697,23 +697,33 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
             fma_cols(acc1, 1.f, w[3]);
         }
     }
-    for (int q = qb + 4; q < qe; q += 4) {
-        float cq[4];
-        float v[4][V];
+    if (RUNS && qb + 4 < qe) {
+        // row ids and coefficients of a batch are fetched while the rows of the batch before are in flight
+        // (entries past the end repeat the last one with a zero coefficient)
+        int rn[4];
+        float cn[4];
+#define RGNN_RUN_FETCH_IDX(Q0)                                                                   \
+    _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                              \
+        const int x = min((Q0) + t, qe - 1);                                                     \
+        rn[t] = H == 1 ? a.run_rel[x] : (x % H) * a.R + a.run_rel[x / H];                        \
+        cn[t] = (Q0) + t < qe ? a.ds_dst[x] : 0.f;                                               \
+    }
+        RGNN_RUN_FETCH_IDX(qb + 4)
+        for (int q = qb + 4; q < qe; q += 4) {
+            float cq[4];
+            float v[4][V];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            cq[t] = 0.f;
-            zero_cols(v[t]);
-            if (q + t < qe) {
-                cq[t] = a.ds_dst[q + t];
-                const int x = q + t;
-                load_cols(a.wtp + (size_t)(H == 1 ? a.run_rel[x] : (x % H) * a.R + a.run_rel[x / H]) * D + cv * V, v[t]);
+            for (int t = 0; t < 4; ++t) {
+                load_cols(a.wtp + (size_t)rn[t] * D + cv * V, v[t]);
+                cq[t] = cn[t];
             }
+            if (q + 4 < qe) RGNN_RUN_FETCH_IDX(q + 4)
+            fma_cols(acc, cq[0], v[0]);
+            fma_cols(acc1, cq[1], v[1]);
+            fma_cols(acc, cq[2], v[2]);
+            fma_cols(acc1, cq[3], v[3]);
         }
-        fma_cols(acc, cq[0], v[0]);
-        fma_cols(acc1, cq[1], v[1]);
-        fma_cols(acc, cq[2], v[2]);
-        fma_cols(acc1, cq[3], v[3]);
+#undef RGNN_RUN_FETCH_IDX
     }
     fma_cols(acc, 1.f, acc1);
     store_cols(static_cast<TO*>(a.dX) + (size_t)u * D + cv * V, acc);
