@@ -264,10 +264,10 @@ __device__ __forceinline__ void add_rank1(const Rank1& r1, int lanes_per_head, s
 // ROLE only gives each use its own kernel name in profiler output (0 forward aggregation over
 // destinations, 1 backward aggregation over pairs, 2 destination-side weight gradient).
 // TI / TO: storage type of the gathered rows and of the output rows (float or bf16_t).
-template <int D, int ROLE, typename TI, typename TO>
-__global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
+template <int D, typename TI, typename TO, bool R1>
+__device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
     constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
-    int i = blockIdx.x * IPB + threadIdx.x / LPR;
+    int i = blk * IPB + threadIdx.x / LPR;
     const int cv = threadIdx.x % LPR;
     if (i >= a.it.n - a.skip_n) return;
     if (i >= a.skip_first) i += a.skip_n;      // the single-entry segments have their own kernel
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
     fma_cols(acc0, 1.f, acc1);
     const int slot = a.it.slot[i];
     if (slot < 0) {
-        add_rank1<D>(a.r1, a.lanes_per_head, (size_t)a.it.row[i], cv, acc0);
+        if (R1) add_rank1<D>(a.r1, a.lanes_per_head, (size_t)a.it.row[i], cv, acc0);
         store_cols(static_cast<TO*>(a.out) + (size_t)a.it.row[i] * D + cv * V, acc0);
     } else {
         store_cols(a.partial + (size_t)slot * D + cv * V, acc0);
@@ -325,10 +325,10 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a) {
 // such a segment, so the general kernel would spend its time on the item -> indices -> rows -> store
 // chain; here a group of lanes takes two of them at a time, all loads of both independent (entries
 // past a segment's end repeat its last one with a zero coefficient).
-template <int D, int ROLE, typename TI, typename TO>
-__global__ __launch_bounds__(256) void gather_short_kernel(GatherArgs a, int first, int n) {
+template <int D, typename TI, typename TO, bool R1>
+__device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int first, int n) {
     constexpr int V = RowT<TI>::V, LPR = D / V, GPB = 256 / LPR;
-    const int g = blockIdx.x * GPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
+    const int g = blk * GPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
     const int i0 = 2 * g;
     if (i0 >= n) return;
     const TI* __restrict__ src = static_cast<const TI*>(a.src);
@@ -366,7 +366,7 @@ __global__ __launch_bounds__(256) void gather_short_kernel(GatherArgs a, int fir
 #pragma unroll
         for (int u = 0; u < kShortLen; ++u) fma_cols(acc, c[q][u], v[q][u]);
         if (i0 + q < n) {
-            add_rank1<D>(a.r1, a.lanes_per_head, (size_t)orow[q], cv, acc);
+            if (R1) add_rank1<D>(a.r1, a.lanes_per_head, (size_t)orow[q], cv, acc);
             store_cols(static_cast<TO*>(a.out) + (size_t)orow[q] * D + cv * V, acc);
         }
     }
@@ -375,10 +375,10 @@ __global__ __launch_bounds__(256) void gather_short_kernel(GatherArgs a, int fir
 // The whole segments with exactly one entry, items [first, first + n): out[row_i] = c * src[row].
 // A group of lanes handles four of them at a time, all loads of the four independent, which keeps
 // enough rows in flight where the general kernel would wait on one short dependent chain per item.
-template <int D, int ROLE, typename TI, typename TO>
-__global__ __launch_bounds__(256) void gather_single_kernel(GatherArgs a, int first, int n) {
+template <int D, typename TI, typename TO, bool R1>
+__device__ __forceinline__ void gather_single(const GatherArgs& a, int blk, int first, int n) {
     constexpr int V = RowT<TI>::V, LPR = D / V, GPB = 256 / LPR;
-    const int g = blockIdx.x * GPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
+    const int g = blk * GPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
     const int i0 = 4 * g;
     if (i0 >= n) return;
     const TI* __restrict__ src = static_cast<const TI*>(a.src);
@@ -407,11 +407,32 @@ __global__ __launch_bounds__(256) void gather_single_kernel(GatherArgs a, int fi
         if (i0 + u < n) {
 #pragma unroll
             for (int q = 0; q < V; ++q) v[u][q] *= c[u];
-            add_rank1<D>(a.r1, a.lanes_per_head, (size_t)orow[u], cv, v[u]);
+            if (R1) add_rank1<D>(a.r1, a.lanes_per_head, (size_t)orow[u], cv, v[u]);
             store_cols(static_cast<TO*>(a.out) + (size_t)orow[u] * D + cv * V, v[u]);
         }
     }
 }
+
+// fp32 rows: one launch for the three kinds of items: the first blocks walk the general items (longest
+// first), the next ones the 2..kShortLen-entry segments, the last ones the single-entry segments, so the
+// short work fills the machine while the long items drain.  bf16 rows: a launch per kind (a lane holds
+// twice the columns there, and the registers of the short-segment path would cost the general walk
+// its occupancy).
+struct GatherRanges { int general_blocks, short_blocks, short_first, short_n, single_first, single_n; };
+// R1: the rank-1 term of GatherArgs::r1 is present (fp32 rows only).
+template <int D, int ROLE, typename TI, typename TO, bool R1 = false>
+__global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a, GatherRanges r) {
+    const int blk = blockIdx.x;
+    if (blk < r.general_blocks) gather_general<D, TI, TO, R1>(a, blk);
+    else if (blk < r.general_blocks + r.short_blocks) gather_short<D, TI, TO, R1>(a, blk - r.general_blocks, r.short_first, r.short_n);
+    else gather_single<D, TI, TO, R1>(a, blk - r.general_blocks - r.short_blocks, r.single_first, r.single_n);
+}
+template <int D, int ROLE, typename TI, typename TO>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(7))) void gather_general_kernel(GatherArgs a) { gather_general<D, TI, TO, false>(a, blockIdx.x); }
+template <int D, int ROLE, typename TI, typename TO>
+__global__ __launch_bounds__(256) void gather_short_kernel(GatherArgs a, int first, int n) { gather_short<D, TI, TO, false>(a, blockIdx.x, first, n); }
+template <int D, int ROLE, typename TI, typename TO>
+__global__ __launch_bounds__(256) void gather_single_kernel(GatherArgs a, int first, int n) { gather_single<D, TI, TO, false>(a, blockIdx.x, first, n); }
 
 // NH weighted sums of the same rows in one walk: out[h][row_i] = sum_j coef[k][h] * src[row], k and row as
 // in gather_sum_kernel (fp32 rows).  out is [NH][out_rows][D], the partial rows [NH][num_partials][D].
@@ -866,7 +887,12 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
     GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns, r1v};
     {
         KernelTimer kt(st, label);
-        const dim3 grid(blocks_for(L.num_items - nsh - ns, 256 / lpr));
+        GatherRanges r{};
+        r.general_blocks = (int)blocks_for(L.num_items - nsh - ns, 256 / lpr);
+        r.short_blocks = nsh > 0 ? (int)blocks_for((size_t)(nsh + 1) / 2, 256 / lpr) : 0;
+        r.short_first = L.first_short; r.short_n = nsh; r.single_first = L.first_single; r.single_n = ns;
+        const int single_blocks = ns > 0 ? (int)blocks_for((size_t)(ns + 3) / 4, 256 / lpr) : 0;
+        const dim3 grid(r.general_blocks + r.short_blocks + single_blocks);
 #define RGNN_LAUNCH_GATHER(KERNEL, GRID, ...)                                                                              \
     do {                                                                                                                   \
         if (role == 0) RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((KERNEL<DD, 0, TI, TO>), GRID, dim3(256), 0, st, __VA_ARGS__)); \
@@ -874,14 +900,18 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
         else RGNN_DISPATCH_ROWS(D, src_bf16, out_bf16, hipLaunchKernelGGL((KERNEL<DD, 2, TI, TO>), GRID, dim3(256), 0, st, __VA_ARGS__)); \
         RGNN_CHECK_LAUNCH();                                                                                               \
     } while (0)
-        if (L.num_items - nsh - ns > 0) RGNN_LAUNCH_GATHER(gather_sum_kernel, grid, a);
-        if (nsh > 0) {
-            const dim3 hgrid(blocks_for((size_t)(nsh + 1) / 2, 256 / lpr));
-            RGNN_LAUNCH_GATHER(gather_short_kernel, hgrid, a, L.first_short, nsh);
-        }
-        if (ns > 0) {
-            const dim3 sgrid(blocks_for((size_t)(ns + 3) / 4, 256 / lpr));
-            RGNN_LAUNCH_GATHER(gather_single_kernel, sgrid, a, L.first_single, ns);
+        if (r1 && (src_bf16 || out_bf16 || role != 1)) RGNN_FAIL(RGNN_EUNSUPPORTED, "gather_sum: the rank-1 term is built for fp32 rows of the pair-major walk");
+        if (r1) {
+            if (grid.x > 0) {
+                RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 1, float, float, true>), grid, dim3(256), 0, st, a, r));
+                RGNN_CHECK_LAUNCH();
+            }
+        } else if (!src_bf16) {
+            if (grid.x > 0) RGNN_LAUNCH_GATHER(gather_sum_kernel, grid, a, r);
+        } else {
+            if (r.general_blocks > 0) RGNN_LAUNCH_GATHER(gather_general_kernel, dim3(r.general_blocks), a);
+            if (nsh > 0) RGNN_LAUNCH_GATHER(gather_short_kernel, dim3(r.short_blocks), a, L.first_short, nsh);
+            if (ns > 0) RGNN_LAUNCH_GATHER(gather_single_kernel, dim3(single_blocks), a, L.first_single, ns);
         }
 #undef RGNN_LAUNCH_GATHER
     }
