@@ -378,6 +378,7 @@ rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, co
     LAUNCH(k_lower_bound, (size_t)R + 1, (long long)Q, flag.as<int32_t>(), (long long)R, g->idx[RGNN_IDX_RELRUN_PTR]);
     RGNN_TRY(keep<int32_t>(g, (size_t)Q, &g->relrun_dst));
     LAUNCH(k_permute_i32, (size_t)Q, (long long)Q, g->idx[RGNN_IDX_RELRUN_IDX], g->idx[RGNN_IDX_RUN_DST], g->relrun_dst);
+    g->idx[RGNN_IDX_RELRUN_DST] = g->relrun_dst; g->idx_len[RGNN_IDX_RELRUN_DST] = Q;
 
     // ---- 5. pairs by (src, rel)
     RGNN_TRY(keep_idx(g, RGNN_IDX_SRCPAIR_IDX, (size_t)P));
@@ -398,6 +399,7 @@ rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, co
     // ---- 7. pair ids tagged with "single edge"
     RGNN_TRY(keep<int32_t>(g, (size_t)E, &g->in_pair_tag));
     LAUNCH(k_tag, (size_t)E, E, g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_OUT_PTR], g->in_pair_tag);
+    g->idx[RGNN_IDX_IN_PAIR_TAG] = g->in_pair_tag; g->idx_len[RGNN_IDX_IN_PAIR_TAG] = E;
     RGNN_TRY(keep<float>(g, (size_t)E, &g->out_invc));
     LAUNCH(k_permute_f32, (size_t)E, E, g->idx[RGNN_IDX_OUT_EPOS], g->in_invc, g->out_invc);
     RGNN_TRY(keep<int32_t>(g, (size_t)P, &g->pair_ysel));
@@ -405,6 +407,8 @@ rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, co
     RGNN_TRY(keep<int32_t>(g, (size_t)P, &g->pair_ysel_run));
     LAUNCH(k_pair_ysel_run, (size_t)P, (long long)P, g->idx[RGNN_IDX_OUT_PTR], g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_IN_RUN],
            g->pair_ysel_run);
+    g->idx[RGNN_IDX_PAIR_SEL_DST] = g->pair_ysel; g->idx_len[RGNN_IDX_PAIR_SEL_DST] = P;
+    g->idx[RGNN_IDX_PAIR_SEL_RUN] = g->pair_ysel_run; g->idx_len[RGNN_IDX_PAIR_SEL_RUN] = P;
 
     // ---- 8. node type of each relation's sources, if it is a single one
     RGNN_TRY(keep<int32_t>(g, (size_t)R, &g->rel_src_type));
@@ -417,6 +421,7 @@ rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, co
     int32_t mixed = 0;
     RGNN_HIP(hipMemcpy(&mixed, mixed_t.as<int32_t>(), sizeof(int32_t), hipMemcpyDeviceToHost));
     g->rel_src_tied = mixed == 0;
+    g->idx[RGNN_IDX_REL_SRC_TYPE] = g->rel_src_type; g->idx_len[RGNN_IDX_REL_SRC_TYPE] = R;
     RGNN_HIP(hipDeviceSynchronize());
     return RGNN_OK;
 }

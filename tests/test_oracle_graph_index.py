@@ -44,6 +44,14 @@ def _brute(N, R, src, dst, rel, ntype, T):
     perm = sorted(range(N), key=lambda n: (int(ntype[n]), n))
     ix["ntype_perm"] = perm
     ix["ntype_ptr"] = [sum(1 for n in range(N) if ntype[n] < t) for t in range(T + 1)]
+    # derived lookups; a set top bit reads as a negative int32
+    top = lambda x: x - (1 << 31)
+    edges_of = [[pos for pos in range(E) if ix["in_pair"][pos] == p] for p in range(len(pairs))]
+    ix["relrun_dst"] = [runs[q][0] for q in rr]
+    ix["in_pair_tag"] = [top(p) if len(edges_of[p]) == 1 else p for p in ix["in_pair"]]
+    ix["pair_sel_dst"] = [top(edges[edges_of[p][0]][0]) if len(edges_of[p]) == 1 else p for p in range(len(pairs))]
+    ix["pair_sel_run"] = [top(in_run[edges_of[p][0]]) if len(edges_of[p]) == 1 else p for p in range(len(pairs))]
+    ix["rel_src_type"] = [next((int(ntype[s]) for r, s in pairs if r == k), 0) for k in range(R)]
     return ix, len(pairs), len(runs)
 
 
