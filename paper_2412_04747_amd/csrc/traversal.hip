@@ -246,7 +246,7 @@ struct GatherArgs {
     const void* src;      // rows of TI
     void* out;            // rows of TO
     float* partial;       // fp32 rows
-    int skip_first;       // items [skip_first, skip_first + skip_n) are left to gather_single_kernel
+    int skip_first;       // items [skip_first, skip_first + skip_n) are left to the short-segment and single-entry walks
     int skip_n;
     Rank1 r1;             // optional: out[row_i] += r1.coef[row_i][head] * r1.vec[r1.seg[row_i]] (whole segments here,
                           // cut segments when their pieces are combined)
