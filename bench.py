@@ -362,7 +362,7 @@ def main():
                 "frac": gb / HBM_PEAK_GBS, "traffic": None}
     # HBM bytes per launch from rocprofv3 counters (two --pmc runs of this same command, calibrated
     # against the 1 GiB copy above); only valid for the full-size default workload.
-    tsv = os.path.join(ROOT, "profiles", "rgat_c3_hbm_traffic.tsv")
+    tsv = os.path.join(ROOT, "profiles", "rgat_c3_hbm_traffic_per_label.txt")
     if args.config == 3 and args.scale == 1.0 and os.path.exists(tsv):
         for ln in open(tsv):
             f = ln.rstrip("\n").split("\t")
