@@ -67,6 +67,8 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
         "self_loop_fwd": ("mfma", N * 3 * r32 + w2, 2.0 * N * d * d),         # X row + out row read and written
         "self_loop_bwd": ("mfma", N * 3 * r32 + w2, 4.0 * N * d * d),
         "aggregate_fwd": agg_dst,
+        # the same sum edge by edge with atomic adds: + in_run and run_dst per edge, and the zero fill
+        "aggregate_fwd_edge_parallel": ("hbm", agg_dst[1] + E * 8 + N * r32, 2.0 * E * d),
         # per edge: Hs row + in_pair + att + (att, dz) store; per node: dOut row + out row + item;
         # per single-edge pair (P1 of them): ds_src and its G row, or with the row selector att_e only
         "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8) + P1 * ((4 if sel else row) + 4), 2.0 * E * d),
@@ -100,12 +102,12 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
     return table.get(name)
 
 
-def make_layer(c, g, heads=0):
+def make_layer(c, g, heads=0, flags=0):
     """-> (layer object, forward-only?) for workload dict c on graph g."""
     from paper_2412_04747_amd.harness import RgatLayer, RgcnLayer, HgtLayer
     d, dt = c["d_out"], c["dtype"]
     if c["layer"] == "rgat":
-        L = RgatLayer(g, d, c["slope"], dtype=dt, heads=max(heads, 1))
+        L = RgatLayer(g, d, c["slope"], dtype=dt, heads=max(heads, 1), flags=flags)
         L.load(c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"])
     elif c["layer"] == "rgcn":
         L = RgcnLayer(g, d, c["norm"], "none", False, dtype=dt)
@@ -208,6 +210,8 @@ def main():
     ap.add_argument("--dtype", choices=("f32", "bf16"), default=None,
                     help="override the storage type of the workload's inputs (the values stay the same)")
     ap.add_argument("--heads", type=int, default=0, help="RGAT workloads: number of attention heads (default 1)")
+    ap.add_argument("--edge-parallel", action="store_true",
+                    help="single-head RGAT: forward aggregation edge by edge with atomic adds (comparison schedule)")
     ap.add_argument("--fwd-only", action="store_true",
                     help="time the forward call alone (inference: no saved buffer is kept)")
     ap.add_argument("--graph", action="store_true",
@@ -264,7 +268,9 @@ def main():
     P1 = int(g.info.num_single_pairs) if c["layer"] in ("rgat", "rgcn") else 0
     print(f"[bench] graph index built in {time.time() - t0:.1f}s: P/E={P / E:.3f} Q/E={Q / E:.3f} "
           f"max in-degree {g.info.max_in_degree} index {g.info.index_bytes / 2**20:.0f} MiB", file=sys.stderr, flush=True)
-    L = make_layer(c, g, args.heads)
+    if args.edge_parallel and (c["layer"] != "rgat" or args.heads > 1):
+        sys.exit("bench.py --edge-parallel: single-head RGAT workloads only")
+    L = make_layer(c, g, args.heads, 1 if args.edge_parallel else 0)
 
     def step():
         L.fwd()

@@ -90,7 +90,14 @@ typedef struct {
  *   slope      RGAT leaky-ReLU negative slope (the derivative at 0 is `slope`).
  *   norm       RGCN: RGNN_NORM_IN_DEGREE_PER_REL divides each message by c_{v,r},
  *              the number of incoming edges of v with relation r (Eq. (rgcn)).
- *   activation RGCN: sigma of Eq. (rgcn), RGNN_ACT_NONE or RGNN_ACT_RELU. */
+ *   activation RGCN: sigma of Eq. (rgcn), RGNN_ACT_NONE or RGNN_ACT_RELU.
+ *   flags      0, or RGNN_FLAG_EDGE_PARALLEL_AGGREGATION (single-head RGAT forward, fp32): the weighted
+ *              sum over a destination's incoming edges is formed edge by edge with atomic adds on the
+ *              output rows (the thesis's traversal template, Alg. "traversal template": partial results
+ *              are added atomically to global memory) instead of by the destination-segment walk.  Same
+ *              result up to the order of the additions, which then varies from run to run; kept so that
+ *              the two schedules can be compared. */
+#define RGNN_FLAG_EDGE_PARALLEL_AGGREGATION 1u
 typedef struct {
     int32_t dtype;
     int32_t d_in;
@@ -99,7 +106,7 @@ typedef struct {
     float slope;
     int32_t norm;
     int32_t activation;
-    uint32_t flags;              /* reserved, must be 0 */
+    uint32_t flags;              /* 0, or RGNN_FLAG_* bits */
 } rgnn_layer_desc_t;
 
 /* Message of the last failing call made by this thread ("" if none). */

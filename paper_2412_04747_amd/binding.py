@@ -19,6 +19,7 @@ RGNN_F32, RGNN_BF16 = 0, 1
 RGNN_LAYER_RGCN, RGNN_LAYER_RGAT, RGNN_LAYER_HGT = 0, 1, 2
 RGNN_NORM_NONE, RGNN_NORM_IN_DEGREE_PER_REL = 0, 1
 RGNN_ACT_NONE, RGNN_ACT_RELU = 0, 1
+RGNN_FLAG_EDGE_PARALLEL_AGGREGATION = 1
 RGNN_MEM_HOST, RGNN_MEM_DEVICE = 0, 1
 RGNN_COO, RGNN_CSR_DST = 0, 1
 

@@ -56,7 +56,9 @@ inline bool missing(const rgnn_graph_t* g, const void* p) { return !p && g->N > 
 
 rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int layer) {
     if (!g || !d) RGNN_FAIL(RGNN_EINVAL, "graph or desc is NULL");
-    if (d->flags != 0) RGNN_FAIL(RGNN_EINVAL, "desc.flags must be 0");
+    if (d->flags & ~RGNN_FLAG_EDGE_PARALLEL_AGGREGATION) RGNN_FAIL(RGNN_EINVAL, "unknown bits in desc.flags");
+    if (d->flags && (layer != RGNN_LAYER_RGAT || d->heads != 1))
+        RGNN_FAIL(RGNN_EUNSUPPORTED, "edge-parallel aggregation is built for single-head RGAT only");
     if (d->dtype != RGNN_F32 && d->dtype != RGNN_BF16) RGNN_FAIL(RGNN_EINVAL, "unknown dtype %d", d->dtype);
     if (d->d_in != d->d_out || (d->d_in != 32 && d->d_in != 64 && d->d_in != 128))
         RGNN_FAIL(RGNN_EUNSUPPORTED, "need d_in == d_out in {32, 64, 128}, got %d -> %d", d->d_in, d->d_out);
@@ -477,6 +479,8 @@ extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     // 3. edge softmax over each destination's incoming edges
     RGNN_TRY(edge_softmax(g, w.s_src, w.s_dst, desc->slope, sv.att, w.part_m, w.part_s, st));
     // 4. out[v] = sum_e att_e Hs[pair_e]
+    if (desc->flags & RGNN_FLAG_EDGE_PARALLEL_AGGREGATION)
+        return aggregate_edge_parallel(g, D, sv.att, sv.Hs, static_cast<float*>(out), st);
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, 1, 1, sv.Hs,
                         static_cast<float*>(out), w.partial, st, 0, "aggregate_fwd", "aggregate_fwd.combine"));
     return RGNN_OK;

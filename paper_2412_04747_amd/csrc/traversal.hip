@@ -501,6 +501,52 @@ __global__ __launch_bounds__(1024) void combine_partials_kernel(const int32_t* _
     }
 }
 
+// ------------------------------------------------------------------ edge-parallel aggregation (comparison schedule)
+
+// out[dst_e] += |att_e| * Hs[pair_e] over equal shares of the CSR edge list: a lane group takes
+// kEdgeChunk consecutive edges, sums in registers while the destination stays the same and adds the sum
+// to the output row with atomic adds when it changes (the thesis' traversal template: partial
+// aggregation in the thread, then atomicAdd to global memory).  Work is balanced by construction (no
+// work lists), the price is the atomics.  out must be zero on entry.  The destination of a CSR edge is
+// run_dst[in_run[e]].
+constexpr int kEdgeChunk = 16;
+template <int D>
+__global__ __launch_bounds__(256) void aggregate_edge_parallel_kernel(int64_t E, const int32_t* __restrict__ in_pair,
+                                                                      const int32_t* __restrict__ in_run,
+                                                                      const int32_t* __restrict__ run_dst,
+                                                                      const float* __restrict__ att,
+                                                                      const float* __restrict__ Hs, float* __restrict__ out) {
+    constexpr int LPR = D / 4, GPB = 256 / LPR;
+    const int64_t e0 = ((int64_t)blockIdx.x * GPB + threadIdx.x / LPR) * kEdgeChunk;
+    const int c4 = threadIdx.x % LPR;
+    if (e0 >= E) return;
+    const int64_t e1 = e0 + kEdgeChunk < E ? e0 + kEdgeChunk : E;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    int cur = run_dst[in_run[e0]];
+    auto flush = [&](int v) {
+        // the hardware's fp32 add on memory (no compare-and-swap loop); ordinary device memory
+        float* o = out + (size_t)v * D + c4 * 4;
+        unsafeAtomicAdd(o + 0, acc.x);
+        unsafeAtomicAdd(o + 1, acc.y);
+        unsafeAtomicAdd(o + 2, acc.z);
+        unsafeAtomicAdd(o + 3, acc.w);
+    };
+    for (int64_t e = e0; e < e1; ++e) {
+        const int v = run_dst[in_run[e]];
+        if (v != cur) {
+            flush(cur);
+            acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            cur = v;
+        }
+        fma4(acc, fabsf(att[e]), *reinterpret_cast<const float4*>(Hs + (size_t)in_pair[e] * D + c4 * 4));
+    }
+    flush(cur);
+}
+__global__ void zero_f32_kernel(size_t n, float* __restrict__ x) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) x[i] = 0.f;
+}
+
 // ------------------------------------------------------------------ backward per-edge dot (RGAT)
 
 // For every CSR edge e of destination v:  g_e = dOut[v] . Hs[pair_e];
@@ -953,6 +999,21 @@ rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, c
             RGNN_CHECK_LAUNCH();
         }
     }
+    return RGNN_OK;
+}
+
+rgnn_status_t aggregate_edge_parallel(const rgnn_graph* g, int D, const float* att, const float* Hs, float* out,
+                                      hipStream_t st) {
+    if (g->N == 0) return RGNN_OK;
+    KernelTimer kt(st, "aggregate_fwd_edge_parallel");
+    const size_t n = (size_t)g->N * D;
+    hipLaunchKernelGGL(zero_f32_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, out);   // a kernel, not a memset: callers may capture
+    RGNN_CHECK_LAUNCH();
+    if (g->E == 0) return RGNN_OK;
+    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(aggregate_edge_parallel_kernel<DD>, dim3(blocks_for(((size_t)g->E + kEdgeChunk - 1) / kEdgeChunk, 256 / (DD / 4))),
+                                          dim3(256), 0, st, g->E, g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN],
+                                          g->idx[RGNN_IDX_RUN_DST], att, Hs, out));
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 

@@ -63,10 +63,10 @@ class Graph:
 class RgatLayer:
     """Device buffers for one RGAT layer call pair on a graph."""
 
-    def __init__(self, graph, d, slope=0.2, dtype="f32", heads=1):
+    def __init__(self, graph, d, slope=0.2, dtype="f32", heads=1, flags=0):
         self.g, self.d, self.H = graph, d, heads
         code, self.tdt = _tdtype(dtype)
-        self.desc = B.make_desc(code, d, d, heads, slope)
+        self.desc = B.make_desc(code, d, d, heads, slope, flags=flags)
         f, b, s = B.rgnn_workspace_bytes(graph.handle, B.RGNN_LAYER_RGAT, self.desc)
         self.ws = _buf(max(f, b))
         self.saved = _buf(s)

@@ -94,9 +94,12 @@ def test_layer_argument_errors():
     from paper_2412_04747_amd.harness import Graph
     _, src, dst, rel, _ = synth.tiny(7, 20, 2, 50)
     g = Graph(20, 2, src, dst, rel)
-    x = torch.zeros(20, 64, device="cuda")
+    # every pointer argument is a buffer far larger than any tensor or workspace of this 20-node graph, so a
+    # descriptor that a later version accepts cannot make one of these calls write out of bounds
+    x = torch.zeros(1 << 24, device="cuda")
     for bad, status in ((B.make_desc(d_in=48, d_out=48), 2), (B.make_desc(d_in=64, d_out=32), 2),
-                        (B.make_desc(heads=8), 2), (B.make_desc(heads=3), 1), (B.make_desc(flags=1), 1), (B.make_desc(dtype=7), 1)):
+                        (B.make_desc(heads=8), 2), (B.make_desc(heads=3), 1), (B.make_desc(flags=2), 1), (B.make_desc(flags=1, heads=2), 2),
+                        (B.make_desc(dtype=7), 1)):
         with pytest.raises(B.RgnnError) as e:
             B.rgnn_rgat_fwd(g.handle, bad, x, x, x, x, x, x, x)
         assert e.value.status == status

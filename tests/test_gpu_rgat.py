@@ -161,6 +161,32 @@ def test_pair_tensors_of_more_than_2_to_32_elements():
     _run(N, R, src, dst, rel, p, d, "beyond-2^32", check_saved=False)
 
 
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_edge_parallel_aggregation_flag(d):
+    """The comparison schedule of the forward aggregation (atomic adds per edge): same result within the
+    fp32 tolerance (the order of the additions is not fixed), backward unchanged."""
+    import torch
+    from paper_2412_04747_amd import binding as B
+    from paper_2412_04747_amd.harness import Graph, RgatLayer
+    N, R, E = 600, 5, 6000
+    rng, src, dst, rel, _ = synth.tiny(71 + d, N=N, R=R, E=E)
+    dst[:2000] = 17                                    # a hub: thousands of atomic adds on one row
+    p = synth.rgat_params(rng, N, R, d, d)
+    print(f"rgat case edge-parallel d={d}", flush=True)
+    g = Graph(N, R, src, dst, rel)
+    L = RgatLayer(g, d, flags=B.RGNN_FLAG_EDGE_PARALLEL_AGGREGATION)
+    L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
+    L.fwd(); L.bwd()
+    torch.cuda.synchronize()
+    check(L.out, O.rgat_fwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"]), TOL_F32, "out")
+    wg = O.rgat_bwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
+    for k, v in L.grads().items():
+        check(v, wg[k], TOL_F32, k)
+    with pytest.raises(B.RgnnError):                   # not with several heads
+        RgatLayer(g, d, heads=2, flags=B.RGNN_FLAG_EDGE_PARALLEL_AGGREGATION)
+    g.close()
+
+
 def test_hub_empty_relation_isolated_nodes():
     rng, src, dst, rel, _ = synth.tiny(70, N=300, R=5, E=4000)
     rel[rel == 4] = 0       # relation 4 has no edge
