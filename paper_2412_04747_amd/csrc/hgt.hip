@@ -170,7 +170,8 @@ __global__ __launch_bounds__(256) void hgt_softmax_kernel(int N, int H, const in
                                                           float* __restrict__ att, int sgn) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= (int64_t)N * H) return;
-    const int v = (int)(t / H), h = (int)(t % H);
+    const int lh = 31 - __clz(H);                 // the head count is a power of two
+    const int v = (int)(t >> lh), h = (int)(t & (H - 1));
     const int b = in_ptr[v], len = in_ptr[v + 1] - b;
     if (len == 0 || len > kSerialMax) return;
     float l[kSerialMax];               // the logits stay in registers: one read and one write of att

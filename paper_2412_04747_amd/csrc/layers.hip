@@ -70,6 +70,9 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
         if (std::max<int64_t>(g->N, g->E) * d->heads > INT32_MAX)
             RGNN_FAIL(RGNN_EUNSUPPORTED, "multi-head RGAT needs num_nodes * heads and num_edges * heads < 2^31");
     }
+    // with the widths and head widths allowed above the head count is a power of two; the kernels index with shifts
+    if ((layer == RGNN_LAYER_RGAT || layer == RGNN_LAYER_HGT) && (d->heads & (d->heads - 1)))
+        RGNN_FAIL(RGNN_EUNSUPPORTED, "the head count must be a power of two, got %d", d->heads);
     if (layer == RGNN_LAYER_RGAT && !(d->slope >= 0.f && d->slope <= 1.f))
         RGNN_FAIL(RGNN_EINVAL, "leaky-ReLU slope must be in [0, 1]");
     if (layer == RGNN_LAYER_RGCN) {

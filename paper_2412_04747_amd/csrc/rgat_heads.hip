@@ -9,14 +9,15 @@
 
 namespace rgnn {
 
-// wv[h][r][k] = sum_{n in head h} W[r][k][n] * w[r][n]   (linear operator reordering, per head)
+// wv[r][h][k] = sum_{n in head h} W[r][k][n] * w[r][n]   (linear operator reordering, per head; the H vectors
+// of a relation are adjacent, so the walks that need all of them touch one short block)
 __global__ void fold_weight_heads_kernel(const float* __restrict__ W, const float* __restrict__ w, int R, int kd, int nd,
                                          int H, float* __restrict__ wv) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;   // (h, r, k)
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;   // (r, h, k)
     if (i >= H * R * kd) return;
     const int dh = nd / H;
-    const int h = i / (R * kd), rk = i % (R * kd), r = rk / kd;
-    const float* Wr = W + (size_t)rk * nd + h * dh;
+    const int r = i / (H * kd), h = i / kd % H, k = i % kd;
+    const float* Wr = W + ((size_t)r * kd + k) * nd + h * dh;
     const float* wr = w + (size_t)r * nd + h * dh;
     float s = 0.f;
     for (int n = 0; n < dh; ++n) s += Wr[n] * wr[n];
@@ -39,7 +40,7 @@ __global__ __launch_bounds__(256) void head_dot_rows_kernel(int64_t n, int H, co
     if (c4 % lph == 0) s[(size_t)i * H + c4 / lph] = t;
 }
 
-// s_dst[q][h] = X[run_dst[q]] . wtp[h][run_rel[q]]: the run's X row is read once, one full-width dot per head
+// s_dst[q][h] = X[run_dst[q]] . wtp[run_rel[q]][h]: the run's X row is read once, one full-width dot per head
 template <int D>
 __global__ __launch_bounds__(256) void run_logit_heads_kernel(int Q, int R, int H, const int32_t* __restrict__ run_dst,
                                                               const int32_t* __restrict__ run_rel,
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(256) void run_logit_heads_kernel(int Q, int R, int 
     const float4 x = *reinterpret_cast<const float4*>(X + (size_t)run_dst[q] * D + c4 * 4);
     const int r = run_rel[q];
     for (int h = 0; h < H; ++h) {
-        const float4 w = *reinterpret_cast<const float4*>(wtp + ((size_t)h * R + r) * D + c4 * 4);
+        const float4 w = *reinterpret_cast<const float4*>(wtp + ((size_t)r * H + h) * D + c4 * 4);
         const float t = group_sum<LPR>(dot4(x, w));
         if (c4 == 0) s_dst[(size_t)q * H + h] = t;
     }
@@ -63,8 +64,9 @@ __global__ void edge_logit_heads_kernel(int64_t total, int H, const int32_t* __r
                                         const float* __restrict__ s_dst, float slope, float* __restrict__ att) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
-    const int64_t e = i / H;
-    const int h = (int)(i % H);
+    const int lh = 31 - __clz(H);                 // the head count is a power of two
+    const int64_t e = i >> lh;
+    const int h = (int)(i & (H - 1));
     const float z = s_src[(size_t)in_pair[e] * H + h] + s_dst[(size_t)in_run[e] * H + h];
     att[i] = z > 0.f ? z : slope * z;
 }

@@ -63,7 +63,8 @@ __global__ void segment_scalar_sum_kernel(int n, int heads, const int32_t* __res
                                           int off, int min_len, float* __restrict__ out) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= (int64_t)n * heads) return;
-    const int i = heads == 1 ? (int)t : (int)(t / heads), h = heads == 1 ? 0 : (int)(t % heads);
+    const int lh = 31 - __clz(heads);            // the head count is a power of two (checked by the launcher)
+    const int i = (int)(t >> lh), h = (int)(t & (heads - 1));
     const int b = ptr[i], e = ptr[i + 1];
     if (e - b > kSerialMax || e - b < min_len) return;
     float s = 0.f;
@@ -663,7 +664,7 @@ __global__ __launch_bounds__(256) void run_scaled_rows_kernel(int Q, const int32
 
 // ------------------------------------------------------------------ dX assembly
 
-// dX[u] = sum_{p in srcpair(u)} dXp[p]  +  sum_{q in runs(u)} sum_h ds_dst[q][h] * wtp[h][run_rel[q]]  +  extra[u]
+// dX[u] = sum_{p in srcpair(u)} dXp[p]  +  sum_{q in runs(u)} sum_h ds_dst[q][h] * wtp[run_rel[q]][h]  +  extra[u]
 // (second and third terms optional).  The (run, head) pairs of a node are walked as one flat list.
 struct NodeSumArgs {
     Items it;             // pairs by source node, ordered by length, never cut
@@ -674,10 +675,10 @@ struct NodeSumArgs {
     const int32_t* dst_run_ptr;
     const int32_t* run_rel;
     const float* ds_dst;  // [Q][heads]
-    const float* wtp;     // [heads][R][D]
+    const float* wtp;     // [R][heads][D]
     const float* extra;
     void* dX;             // rows of TO
-    int heads;            // run term: sum over (run q, head h) of ds_dst[q][h] * wtp[h][run_rel[q]]
+    int heads;            // run term: sum over (run q, head h) of ds_dst[q][h] * wtp[run_rel[q]][h]
     int R;
 };
 
@@ -693,8 +694,8 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
     const TI* __restrict__ dXp2 = static_cast<const TI*>(a.dXp2);
     const int u = a.it.row[i];
     const int b = a.it.beg[i], e = a.it.end[i];
-    const int H = a.heads;
-    const int qb = RUNS ? a.dst_run_ptr[u] * H : 0, qe = RUNS ? a.dst_run_ptr[u + 1] * H : 0;
+    const int H = a.heads, lh = 31 - __clz(H);      // the head count is a power of two
+    const int qb = RUNS ? a.dst_run_ptr[u] << lh : 0, qe = RUNS ? a.dst_run_ptr[u + 1] << lh : 0;
     float acc[V], acc1[V];
     zero_cols(acc);
     zero_cols(acc1);
@@ -709,7 +710,7 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
         c[t] = 0.f;
         if (RUNS && qb + t < qe) {
             const int x = qb + t;
-            rr[t] = H == 1 ? a.run_rel[x] : (x % H) * a.R + a.run_rel[x / H];
+            rr[t] = (a.run_rel[x >> lh] << lh) + (x & (H - 1));
             c[t] = a.ds_dst[qb + t];
         }
     }
@@ -772,7 +773,7 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
 #define RGNN_RUN_FETCH_IDX(Q0)                                                                   \
     _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                              \
         const int x = min((Q0) + t, qe - 1);                                                     \
-        rn[t] = H == 1 ? a.run_rel[x] : (x % H) * a.R + a.run_rel[x / H];                        \
+        rn[t] = (a.run_rel[x >> lh] << lh) + (x & (H - 1));                        \
         cn[t] = (Q0) + t < qe ? a.ds_dst[x] : 0.f;                                               \
     }
         RGNN_RUN_FETCH_IDX(qb + 4)
@@ -871,6 +872,7 @@ rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float*
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
                                  int stride, int off, float* out, hipStream_t st, const char* label, int min_len,
                                  int heads) {
+    if (heads < 1 || (heads & (heads - 1))) RGNN_FAIL(RGNN_EUNSUPPORTED, "segment_scalar_sum: the head count must be a power of two, got %d", heads);
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, label);
     hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3(blocks_for((size_t)n * heads, 256)), dim3(256), 0, st, n, heads, ptr,
@@ -1046,6 +1048,7 @@ rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const f
                             const void* dXp2) {
     if (g->N == 0) return RGNN_OK;
     if (ds_dst && dXp2) RGNN_FAIL(RGNN_EINVAL, "node_grad_sum: the run term and a second row tensor exclude each other");
+    if (heads < 1 || (heads & (heads - 1))) RGNN_FAIL(RGNN_EUNSUPPORTED, "node_grad_sum: the head count must be a power of two, got %d", heads);
     NodeSumArgs a{dev_items(g->srcpair_items), g->idx[RGNN_IDX_SRCPAIR_PTR], g->idx[RGNN_IDX_SRCPAIR_IDX], dXp, dXp2,
                   g->idx[RGNN_IDX_DST_RUN_PTR], g->idx[RGNN_IDX_RUN_REL], ds_dst, wtp, extra, dX, heads, (int)g->R};
     KernelTimer kt(st, "node_grad_sum");
