@@ -46,14 +46,30 @@ def test_rgat_fwd_bwd_replays():
     g.close()
 
 
-def test_hgt_bf16_fwd_bwd_replays():
+@pytest.mark.parametrize("T", [3, 1])
+def test_hgt_bf16_fwd_bwd_replays(T):
+    """T = 3: random node types, relations mix source types; T = 1: the path with folded weights."""
     from paper_2412_04747_amd.harness import Graph, HgtLayer
-    rng, src, dst, rel, ntype = synth.tiny(402, N=2500, R=5, E=20000, T=3)
+    rng, src, dst, rel, ntype = synth.tiny(402, N=2500, R=5, E=20000, T=T)
     dst[:1500] = 9
-    print("hipgraph case hgt bf16: N=2500 T=3 R=5 E=20000 d=128 H=4", flush=True)
-    p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in synth.hgt_params(rng, 2500, 3, 5, 128, 4, with_mu=True).items()}
-    g = Graph(2500, 5, src, dst, rel, ntype, 3)
+    print(f"hipgraph case hgt bf16: N=2500 T={T} R=5 E=20000 d=128 H=4", flush=True)
+    p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in synth.hgt_params(rng, 2500, T, 5, 128, 4, with_mu=True).items()}
+    g = Graph(2500, 5, src, dst, rel, ntype if T > 1 else None, T)
     L = HgtLayer(g, 128, 4, with_mu=True, dtype="bf16")
     L.load(p["X"], p["Wk"], p["Wq"], p["Wv"], p["Wo"], p["Watt"], p["Wmsg"], p["mu"], p["dOut"])
+    _capture_and_replay(L, lambda: [L.out] + list(L.grads().values()))
+    g.close()
+
+
+def test_rgcn_bf16_fwd_bwd_replays():
+    """bf16 rows: per-run scaled rows and the row selector of the backward typed linear."""
+    from paper_2412_04747_amd.harness import Graph, RgcnLayer
+    rng, src, dst, rel, _ = synth.tiny(403, N=3000, R=7, E=25000)
+    dst[:1800] = 4
+    print("hipgraph case rgcn bf16: N=3000 R=7 E=25000 d=128", flush=True)
+    p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in synth.rgcn_params(rng, 3000, 7, 128, 128, self_loop=True).items()}
+    g = Graph(3000, 7, src, dst, rel)
+    L = RgcnLayer(g, 128, "in_degree_per_rel", "relu", True, dtype="bf16")
+    L.load(p["X"], p["W"], p["W0"], p["dOut"])
     _capture_and_replay(L, lambda: [L.out] + list(L.grads().values()))
     g.close()
