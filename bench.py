@@ -75,12 +75,10 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
         # RGAT: only the E - P1 edges of the P - P1 pairs with several edges; coefficient = the (att, dz) pair.
         # RGCN: every edge; row + out_dst + coefficient
         # RGCN with bf16 rows: likewise only pairs with several edges (the typed-linear backward reads the
-        # others' rows from the per-run rows of run_scaled_rows)
+        # others' rows straight from the destinations' gradient rows)
         "aggregate_bwd_pair": ("hbm", (E - P1) * (row + 16) + (P - P1) * (row + 8), 2.0 * (E - P1) * d) if layer == "rgat"
                               else ("hbm", (E - P1) * (row + 8) + (P - P1) * (row + 8), 2.0 * (E - P1) * d) if half
                               else ("hbm", E * (row + 8) + P * (row + 8), 2.0 * E * d),
-        # per run: dPre row in, scaled row out, run_ptr + run_dst
-        "run_scaled_rows": ("hbm", Q * (2 * row + 8), 1.0 * Q * d),
         # per run: X row + relrun_idx + run_dst + ds_dst
         "dst_side_wgrad": ("hbm", Q * (row + 12), 2.0 * Q * d),
         # per pair: dXp row + srcpair_idx; per run (RGAT): ds_dst + run_rel; per node: result row + 2 ptrs

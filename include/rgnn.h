@@ -169,9 +169,8 @@ enum {
     RGNN_IDX_RELRUN_DST = 23, /* [Q] run_dst[relrun_idx[i]]: destinations in (rel, dst) order */
     RGNN_IDX_IN_PAIR_TAG = 24,/* [E] in_pair, with the top bit set when the pair has no other edge */
     RGNN_IDX_PAIR_SEL_DST = 25,/* [P] pair id, or for a pair with one edge: top bit | destination of that edge */
-    RGNN_IDX_PAIR_SEL_RUN = 26,/* [P] pair id, or for a pair with one edge: top bit | run id of that edge */
-    RGNN_IDX_REL_SRC_TYPE = 27,/* [R] node type of the source of the relation's first pair (0 if it has no edge) */
-    RGNN_IDX_COUNT = 28
+    RGNN_IDX_REL_SRC_TYPE = 26,/* [R] node type of the source of the relation's first pair (0 if it has no edge) */
+    RGNN_IDX_COUNT = 27
 };
 
 /* Copy index array `which` to host memory.  `bytes` must equal 4 * its length,

@@ -14,8 +14,8 @@ Canonical orders (every array is int32 and must match the library bit for bit):
   * srcpair: pair ids sorted by (src, rel);
   * node-type segments: node ids sorted by (type, id);
   * derived lookups: relrun_dst = run_dst in relrun order; in_pair_tag = in_pair with bit 31 set
-    when the pair has a single edge; pair_sel_dst / pair_sel_run = the pair id, or for a pair with a
-    single edge bit 31 | that edge's destination / run id; rel_src_type = node type of the source of
+    when the pair has a single edge; pair_sel_dst = the pair id, or for a pair with a single edge
+    bit 31 | that edge's destination; rel_src_type = node type of the source of
     the relation's first pair (0 for a relation without edges).
 Test infrastructure only.
 """
@@ -66,9 +66,8 @@ def build(N, R, src, dst, rel, ntype=None, T=1):
     single = np.diff(out_ptr) == 1                       # pairs with exactly one edge
     first_epos = out_epos[out_ptr[:-1][single]] if P else np.zeros(0, np.int64)
     pair_ids = np.arange(P, dtype=np.int64)
-    pair_sel_dst, pair_sel_run = pair_ids.copy(), pair_ids.copy()
+    pair_sel_dst = pair_ids.copy()
     pair_sel_dst[single] = TOP | in_dst[first_epos]
-    pair_sel_run[single] = TOP | in_run[first_epos]
     in_pair_tag = np.where(single[in_pair], TOP | in_pair, in_pair) if E else np.zeros(0, np.int64)
     relrun_dst = run_dst[relrun_idx]
     rel_src_type = np.zeros(R, np.int64)
@@ -80,7 +79,7 @@ def build(N, R, src, dst, rel, ntype=None, T=1):
         return np.where(a >= TOP, a - (TOP << 1), a)
 
     idx = dict(relrun_dst=relrun_dst, in_pair_tag=wrap(in_pair_tag), pair_sel_dst=wrap(pair_sel_dst),
-               pair_sel_run=wrap(pair_sel_run), rel_src_type=rel_src_type,
+               rel_src_type=rel_src_type,
                in_ptr=in_ptr, in_src=in_src, in_rel=in_rel, in_eid=in_eid, in_pair=in_pair,
                in_run=in_run, in_cnt=in_cnt,
                pair_ptr=pair_ptr, pair_src=pair_src, pair_rel=pair_rel,

@@ -26,7 +26,7 @@ RGNN_COO, RGNN_CSR_DST = 0, 1
 INDEX_NAMES = ["in_ptr", "in_src", "in_rel", "in_eid", "in_pair", "in_run", "in_cnt", "pair_ptr", "pair_src",
                "pair_rel", "run_ptr", "run_dst", "run_rel", "dst_run_ptr", "relrun_ptr", "relrun_idx", "out_ptr",
                "out_epos", "out_dst", "srcpair_ptr", "srcpair_idx", "ntype_ptr", "ntype_perm", "relrun_dst", "in_pair_tag",
-               "pair_sel_dst", "pair_sel_run", "rel_src_type"]
+               "pair_sel_dst", "rel_src_type"]
 
 EXPORTS = ["rgnn_last_error", "rgnn_graph_create", "rgnn_graph_destroy", "rgnn_graph_info", "rgnn_graph_export",
            "rgnn_workspace_bytes", "rgnn_rgcn_fwd", "rgnn_rgcn_bwd", "rgnn_rgat_fwd", "rgnn_rgat_bwd",

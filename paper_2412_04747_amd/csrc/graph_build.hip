@@ -191,12 +191,11 @@ __global__ void k_pair_ysel(long long P, const int32_t* out_ptr, const int32_t* 
     const int32_t b = out_ptr[p];
     ysel[p] = (out_ptr[p + 1] - b == 1) ? (int32_t)((uint32_t)out_dst[b] | 0x80000000u) : (int32_t)p;
 }
-__global__ void k_pair_ysel_run(long long P, const int32_t* out_ptr, const int32_t* out_epos, const int32_t* in_run,
-                                int32_t* ysel) {
+__global__ void k_pair_scale(long long P, const int32_t* out_ptr, const float* out_invc, float* scale) {
     const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= P) return;
     const int32_t b = out_ptr[p];
-    ysel[p] = (out_ptr[p + 1] - b == 1) ? (int32_t)((uint32_t)in_run[out_epos[b]] | 0x80000000u) : (int32_t)p;
+    scale[p] = (out_ptr[p + 1] - b == 1) ? out_invc[b] : 1.f;
 }
 __global__ void k_permute_i32(long long n, const int32_t* idx, const int32_t* src, int32_t* dst) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -404,11 +403,9 @@ rgnn_status_t build_index_device(rgnn_graph* g, int format, const int32_t* a, co
     LAUNCH(k_permute_f32, (size_t)E, E, g->idx[RGNN_IDX_OUT_EPOS], g->in_invc, g->out_invc);
     RGNN_TRY(keep<int32_t>(g, (size_t)P, &g->pair_ysel));
     LAUNCH(k_pair_ysel, (size_t)P, (long long)P, g->idx[RGNN_IDX_OUT_PTR], g->idx[RGNN_IDX_OUT_DST], g->pair_ysel);
-    RGNN_TRY(keep<int32_t>(g, (size_t)P, &g->pair_ysel_run));
-    LAUNCH(k_pair_ysel_run, (size_t)P, (long long)P, g->idx[RGNN_IDX_OUT_PTR], g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_IN_RUN],
-           g->pair_ysel_run);
     g->idx[RGNN_IDX_PAIR_SEL_DST] = g->pair_ysel; g->idx_len[RGNN_IDX_PAIR_SEL_DST] = P;
-    g->idx[RGNN_IDX_PAIR_SEL_RUN] = g->pair_ysel_run; g->idx_len[RGNN_IDX_PAIR_SEL_RUN] = P;
+    RGNN_TRY(keep<float>(g, (size_t)P, &g->pair_scale));
+    LAUNCH(k_pair_scale, (size_t)P, (long long)P, g->idx[RGNN_IDX_OUT_PTR], g->out_invc, g->pair_scale);
 
     // ---- 8. node type of each relation's sources, if it is a single one
     RGNN_TRY(keep<int32_t>(g, (size_t)R, &g->rel_src_type));

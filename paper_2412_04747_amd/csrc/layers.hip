@@ -139,7 +139,7 @@ size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
 
 // ---- RGCN buffers -----------------------------------------------------------------------
 struct RgcnFwdWs { void* Hs; float* partial; };
-struct RgcnBwdWs { void* dPre; float* dPre32; void* T; void* G; void* dXp; float* dX0; float* tl_part; float* partial; };
+struct RgcnBwdWs { void* dPre; float* dPre32; void* G; void* dXp; float* dX0; float* tl_part; float* partial; };
 
 size_t carve_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgcnFwdWs* w) {
     Carver c(base);
@@ -152,7 +152,6 @@ size_t carve_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
     const bool h = rows_bf16(d), relu = d->activation == RGNN_ACT_RELU;
     w->dPre = c.rows(relu ? (size_t)g->N * d->d_out : 0, h);
     w->dPre32 = c.take<float>(relu && h ? (size_t)g->N * d->d_out : 0);   // fp32 copy for the self-loop kernels
-    w->T = c.rows(h && d->norm == RGNN_NORM_IN_DEGREE_PER_REL ? (size_t)g->Q * d->d_out : 0, h);   // per-run scaled rows
     w->G = c.rows((size_t)g->P * d->d_out, h);
     w->dXp = c.rows((size_t)g->P * d->d_in, h);
     w->dX0 = c.take<float>((size_t)g->N * d->d_in);
@@ -270,21 +269,22 @@ rgnn_status_t tl_fwd(bool bf16, const rgnn::TileList* tiles, const rgnn::TileLis
 //   otherwise: the fused fp32 kernel on fp32 X, W, dY.
 //   wide: the same tiles in fewer chunks, for the weight-gradient kernel;  dx_acc: dXrow += (fp32 dXrow, rows16)
 //   ysel / y_alt (rows16, dY not gathered): row i of dY is dY[ysel[i]], or y_alt[ysel[i] & 0x7FFFFFFF] when the
-//     top bit of ysel[i] is set
+//     top bit of ysel[i] is set; with yscale it is also multiplied by yscale[i]
 rgnn_status_t tl_bwd(bool rows16, const rgnn::TileList* tiles, const rgnn::TileList* wide, int d, const void* X,
                      const int32_t* gather, int both_gathered, const float* W32, const void* W16, const void* dY,
                      void* dXrow, bool dx16, float* dW, float* part, const char* label, hipStream_t st,
-                     bool dx_acc = false, const int32_t* ysel = nullptr, const void* y_alt = nullptr) {
+                     bool dx_acc = false, const int32_t* ysel = nullptr, const void* y_alt = nullptr,
+                     const float* yscale = nullptr) {
     if (ysel && (!rows16 || both_gathered)) RGNN_FAIL(RGNN_EUNSUPPORTED, "row selector: bf16 rows and ungathered dY only");
     if (rows16) {
         TypedLinearBf16Args a{};
         a.tiles = W16 ? tiles : wide; a.A = dY; a.a_bf16 = 1; a.gather = both_gathered ? gather : ysel; a.scatter_out = both_gathered;
-        a.A_alt = y_alt;
+        a.A_alt = y_alt; a.rowscale = ysel ? yscale : nullptr;
         a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.transpose_w = 1; a.Y = dXrow; a.y_bf16 = dx16; a.accumulate = dx_acc; a.label = label;
         RGNN_TRY(typed_linear_bf16(d, a, st));
         TypedLinearWgradBf16Args w{};
         w.tiles = wide; w.X = X; w.gather = gather; w.dy_gathered = both_gathered; w.dY = dY; w.part = part;
-        w.label = wgrad_label(label); w.ysel = ysel; w.dY_alt = y_alt;
+        w.label = wgrad_label(label); w.ysel = ysel; w.dY_alt = y_alt; w.yscale = yscale;
         RGNN_TRY(typed_linear_wgrad_bf16(d, w, st));
         return typed_linear_slot_reduce(d, d, *wide, part, dW, nullptr, st);
     }
@@ -405,24 +405,16 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
     //    (coefficients from the pair-major copy, so no per-edge indirection is left)
     const float* ocoef = coef ? g->out_invc : nullptr;
-    //    With bf16 rows the row of a pair with a single edge is not written per pair: it is dPre[dst_e], or under
-    //    the normalisation row run(e) of T[q] = dPre[dst_q] / c_q (one row per run, fewer than pairs), and the
-    //    typed-linear backward reads it from there through its row selector.
-    const int32_t* ysel = nullptr;
-    const void* y_alt = nullptr;
-    if (h) {
-        ysel = coef ? g->pair_ysel_run : g->pair_ysel;
-        y_alt = dPre;
-        if (coef) {
-            RGNN_TRY(run_scaled_rows(g, D, dPre, w.T, st));
-            y_alt = w.T;
-        }
-    }
+    //    With bf16 rows the row of a pair with a single edge is not written per pair: the typed-linear backward
+    //    reads dPre[dst_e] through its row selector and multiplies it by 1/c_e on the way in.
+    const int32_t* ysel = h ? g->pair_ysel : nullptr;
+    const void* y_alt = h ? dPre : nullptr;
+    const float* yscale = h && coef ? g->pair_scale : nullptr;
     RGNN_TRY(gather_sum(h ? g->pair_items_multi : g->pair_items, D, nullptr, g->idx[RGNN_IDX_OUT_DST], 0, ocoef, 1, 0, dPre, w.G,
                         w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", 1, h, h));
     // 2. per pair dXp = dHs W^T; dW[r] = sum X^T dHs
     RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, h ? X : static_cast<const void*>(X32), g->idx[RGNN_IDX_PAIR_SRC], 0, W32, W16, w.G,
-                    w.dXp, h, static_cast<float*>(dW), w.tl_part, "typed_linear_bwd", st, false, ysel, y_alt));
+                    w.dXp, h, static_cast<float*>(dW), w.tl_part, "typed_linear_bwd", st, false, ysel, y_alt, yscale));
     // 3. self-loop: dX0 = dPre W0^T, dW0 = X^T dPre
     if (W0) {
         TypedLinearBwdArgs s{};

@@ -115,7 +115,7 @@ struct rgnn_graph {
     rgnn::ItemList pair_items_multi;       // the same, pairs with two or more edges only
     rgnn::ItemList srcpair_items;          // pairs by source node (never cut)
     int32_t* in_pair_tag = nullptr;        // [E] in_pair with the top bit set when the pair has a single edge
-    int32_t* pair_ysel_run = nullptr;      // [P] the same with the (destination, relation) run of that edge
+    float* pair_scale = nullptr;           // [P] 1 / c_{v,r} of the only edge of a single-edge pair, 1 for the other pairs
     int32_t* pair_ysel = nullptr;          // [P] pair id, or for a pair with one edge the top bit | that edge's destination
     int32_t* relrun_dst = nullptr;         // [Q] destination of the runs in (relation, destination) order: run_dst[relrun_idx[i]]
     int32_t* rel_src_type = nullptr;       // [R] node type of the sources of relation r (0 for a relation without edges)
@@ -189,6 +189,7 @@ struct TypedLinearBf16Args {
     const char* label;
     const void* A_alt = nullptr;   // gathered rows only: a gather entry with the top bit set reads row
                                    // (entry & 0x7FFFFFFF) of this tensor instead of A
+    const float* rowscale = nullptr;   // bf16 rows only: row i of the tiles is multiplied by rowscale[i]
 };
 rgnn_status_t typed_linear_bf16(int d, const TypedLinearBf16Args& a, hipStream_t st);
 
@@ -206,6 +207,7 @@ struct TypedLinearWgradBf16Args {
     // when the top bit of ysel[i] is set
     const int32_t* ysel = nullptr;
     const void* dY_alt = nullptr;
+    const float* yscale = nullptr;   // with ysel: row i is also multiplied by yscale[i]
 };
 rgnn_status_t typed_linear_wgrad_bf16(int d, const TypedLinearWgradBf16Args& a, hipStream_t st);
 rgnn_status_t typed_linear_slot_reduce(int d_in, int d_out, const TileList& tiles, const float* part, float* dW,

@@ -63,8 +63,6 @@ rgnn_status_t rgat_heads_param_finish(int R, int kd, int nd, int H, const float*
 // out[v] = sum_e |att_e| Hs[pair_e] edge by edge with atomic adds (zeroes out first); fp32 rows
 rgnn_status_t aggregate_edge_parallel(const rgnn_graph* g, int D, const float* att, const float* Hs, float* out,
                                       hipStream_t st);
-// T[q] = dPre[run_dst[q]] / (entries of run q), bf16 rows of width 128
-rgnn_status_t run_scaled_rows(const rgnn_graph* g, int D, const void* dPre, void* T, hipStream_t st);
 rgnn_status_t add3(size_t n, const float* a, const float* b, const float* c, float* out, hipStream_t st);
 
 rgnn_status_t widen_bf16(size_t n, const uint16_t* src, float* dst, hipStream_t st);

@@ -633,35 +633,6 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
     }
 }
 
-// T[q] = dPre[run_dst[q]] / (entries of run q): the gradient row an RGCN edge of run q carries back
-// under the 1/c_{v,r} normalisation (Eq. (rgcn)), once per (destination, relation) run.  bf16 rows.
-template <int D>
-__global__ __launch_bounds__(256) void run_scaled_rows_kernel(int Q, const int32_t* __restrict__ run_ptr,
-                                                              const int32_t* __restrict__ run_dst,
-                                                              const bf16_t* __restrict__ dPre, bf16_t* __restrict__ T) {
-    constexpr int V = 8, LPR = D / V, GPB = 256 / LPR;
-    // four consecutive runs per lane group, all loads independent (positions past the end repeat the last run)
-    const int q0 = (blockIdx.x * GPB + threadIdx.x / LPR) * 4, cv = threadIdx.x % LPR;
-    if (q0 >= Q) return;
-    int dst[4];
-    float c[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int q = min(q0 + u, Q - 1);
-        dst[u] = run_dst[q];
-        c[u] = 1.f / (float)(run_ptr[q + 1] - run_ptr[q]);
-    }
-    float v[4][V];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) load_cols(dPre + (size_t)dst[u] * D + cv * V, v[u]);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-#pragma unroll
-        for (int k = 0; k < V; ++k) v[u][k] *= c[u];
-        if (q0 + u < Q) store_cols(T + (size_t)(q0 + u) * D + cv * V, v[u]);
-    }
-}
-
 // ------------------------------------------------------------------ dX assembly
 
 // dX[u] = sum_{p in srcpair(u)} dXp[p]  +  sum_{q in runs(u)} sum_h ds_dst[q][h] * wtp[run_rel[q]][h]  +  extra[u]
@@ -1015,17 +986,6 @@ rgnn_status_t aggregate_edge_parallel(const rgnn_graph* g, int D, const float* a
     RGNN_DISPATCH_D(D, hipLaunchKernelGGL(aggregate_edge_parallel_kernel<DD>, dim3(blocks_for(((size_t)g->E + kEdgeChunk - 1) / kEdgeChunk, 256 / (DD / 4))),
                                           dim3(256), 0, st, g->E, g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN],
                                           g->idx[RGNN_IDX_RUN_DST], att, Hs, out));
-    RGNN_CHECK_LAUNCH();
-    return RGNN_OK;
-}
-
-rgnn_status_t run_scaled_rows(const rgnn_graph* g, int D, const void* dPre, void* T, hipStream_t st) {
-    if (g->Q == 0) return RGNN_OK;
-    if (D != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "run_scaled_rows: bf16 rows need width 128, got %d", D);
-    KernelTimer kt(st, "run_scaled_rows");
-    hipLaunchKernelGGL(run_scaled_rows_kernel<128>, dim3(blocks_for(((size_t)g->Q + 3) / 4, 256 / (128 / 8))), dim3(256), 0, st, (int)g->Q,
-                       g->idx[RGNN_IDX_RUN_PTR], g->idx[RGNN_IDX_RUN_DST], static_cast<const bf16_t*>(dPre),
-                       static_cast<bf16_t*>(T));
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

@@ -51,6 +51,15 @@ __device__ __forceinline__ void bf16_split(float x, unsigned& hi, unsigned& lo) 
     lo = bf16_rne(x - __uint_as_float(hi << 16));
 }
 
+// eight bf16 (four packed pairs) times s, rounded to nearest even again
+__device__ __forceinline__ v4u bf16x8_scale(v4u x, float s) {
+    v4u y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        y[e] = bf16_pack_rne(__uint_as_float(x[e] << 16) * s, __uint_as_float(x[e] & 0xFFFF0000u) * s);
+    return y;
+}
+
 struct TileArgsB {
     const int32_t* tile_seg;
     const int32_t* tile_row0;
@@ -71,11 +80,14 @@ __device__ __forceinline__ int run_end_b(const int32_t* __restrict__ tile_seg, i
 //   GATHER rows are read through the gather list        SCATTER outputs are written through it as well
 //   Y_BF16 output rows are stored as bf16 / fp32        ACC    (fp32 output only) Y += result
 // A gather entry with the top bit set reads row (entry & 0x7FFFFFFF) of Alt instead of A (not with SCATTER).
+// rowscale (optional, bf16 A only): row i of the tiles is multiplied by rowscale[i] (and rounded to bf16
+// again) on its way into LDS; the lane that holds a row's factor hands it to the lanes that store the row.
 template <int CD, int OD, bool A_BF16, bool W_BF16, bool WT, bool GATHER, bool SCATTER, bool Y_BF16, bool ACC>
 __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, const void* __restrict__ Av,
                                                                 const int32_t* __restrict__ gather,
                                                                 const void* __restrict__ Wv, void* __restrict__ Yv,
-                                                                const void* __restrict__ Alt) {
+                                                                const void* __restrict__ Alt,
+                                                                const float* __restrict__ rowscale) {
     constexpr int NW = 4;
     constexpr int LS = CD + 8;                                // LDS row stride in bf16 elements (16-byte aligned rows)
     constexpr int OB = OD / 32;
@@ -113,18 +125,21 @@ __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, con
         __syncthreads();
         v4u xr[NX];                                           // 16 bytes per load: 8 bf16 or 4 floats
         int gi[NX], gcur[NX];
+        float scn = 1.f, sc = 1.f;                            // rowscale of row (lane & 31): next unit's, and of the rows in xr
 #define RGNN_FETCH_IDX(U)                                                       \
     _Pragma("unroll") for (int it = 0; it < NX; ++it) {                         \
         const int row_ = min(ra + (U) * 32 + ri + it * RPI, rbnd - 1);          \
         gi[it] = GATHER ? gather[row_] : row_;                                  \
-    }
+    }                                                                           \
+    if (A_BF16 && rowscale) scn = rowscale[min(ra + (U) * 32 + (lane & 31), rbnd - 1)];
 #define RGNN_FETCH_ROWS()                                                       \
     _Pragma("unroll") for (int it = 0; it < NX; ++it) {                         \
         const char* b_ = static_cast<const char*>(GATHER && !SCATTER && gi[it] < 0 ? Alt : Av); \
         const char* p_ = b_ + (size_t)(GATHER && !SCATTER ? gi[it] & 0x7FFFFFFF : gi[it]) * CD * (A_BF16 ? 2 : 4) + ci * 16; \
         xr[it] = *reinterpret_cast<const v4u*>(p_);                             \
         gcur[it] = gi[it];                                                      \
-    }
+    }                                                                           \
+    sc = scn;
         RGNN_FETCH_IDX(wave)
         RGNN_FETCH_ROWS()
         RGNN_FETCH_IDX(wave + NW)
@@ -133,7 +148,9 @@ __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, con
             for (int it = 0; it < NX; ++it) {
                 const int r = ri + it * RPI;
                 if (A_BF16) {
-                    *reinterpret_cast<v4u*>(Aw + r * LS + ci * 8) = xr[it];
+                    v4u x = xr[it];
+                    if (rowscale) x = bf16x8_scale(x, __shfl(sc, r));
+                    *reinterpret_cast<v4u*>(Aw + r * LS + ci * 8) = x;
                 } else {
                     unsigned h[4], l[4];
 #pragma unroll
@@ -260,7 +277,8 @@ __device__ __forceinline__ void transpose4_to_lds(unsigned short* __restrict__ T
     }
 }
 
-// SEL: row i of dY is dY[ysel[i]], or dYalt[ysel[i] & 0x7FFFFFFF] when the top bit of ysel[i] is set.
+// SEL: row i of dY is dY[ysel[i]], or dYalt[ysel[i] & 0x7FFFFFFF] when the top bit of ysel[i] is set; with
+// yscale the row is also multiplied by yscale[i] (rounded to bf16 again) before it enters the tile.
 template <int D, bool GATHER, bool DYG, int NBUF, bool SEL = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void typed_linear_wgrad_bf16_kernel(TileArgsB t, const int32_t* __restrict__ chunk_slot,
                                                                       const unsigned short* __restrict__ X,
@@ -268,7 +286,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                                                                       const unsigned short* __restrict__ dY,
                                                                       float* __restrict__ part,
                                                                       const int32_t* __restrict__ ysel,
-                                                                      const unsigned short* __restrict__ dYalt) {
+                                                                      const unsigned short* __restrict__ dYalt,
+                                                                      const float* __restrict__ yscale) {
     static_assert(D == 128, "four wavefronts x four 32-column blocks");
     static_assert(!(SEL && DYG), "the row selector replaces the dY gather");
     constexpr int TMW = 64;
@@ -291,6 +310,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const int rg8_0 = ((kh ^ m ^ (m >> 3)) & 7) * 8;
     v4u xr[4], yr[4];
     int gi[4], gy[SEL ? 4 : 1];
+    float ysn = 1.f, ysc = 1.f;   // yscale of row 16 * wave + (lane & 15): next tile's, and of the rows in yr
 #define RGNN_W_FETCH_IDX(TI)                                                        \
     {                                                                               \
         const int row0_ = t.tile_row0[TI], row1_ = t.tile_row1[TI];                 \
@@ -299,6 +319,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             gi[k] = GATHER ? gather[row_] : row_;                                   \
             if (SEL) gy[SEL ? k : 0] = ysel[row_];                                  \
         }                                                                           \
+        if (SEL && yscale) ysn = yscale[min(row0_ + 16 * wave + (lane & 15), row1_ - 1)]; \
     }
 #define RGNN_W_FETCH(TI)                                                            \
     {                                                                               \
@@ -314,6 +335,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                 yr[k] = *reinterpret_cast<const v4u*>(dY + s_ * D + cx * 8);        \
             }                                                                       \
         }                                                                           \
+        ysc = ysn;                                                                  \
     }
     if (t0 < t1) {
         RGNN_W_FETCH_IDX(t0)
@@ -355,6 +377,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         int wg8 = wg8_0, rg8 = rg8_0;
         asm volatile("" : "+v"(wg8), "+v"(rg8));
         transpose4_to_lds(Xt, wat + wg8, wg8, xr);
+        if (SEL && yscale) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) yr[k] = bf16x8_scale(yr[k], __shfl(ysc, 4 * ((lane >> 4) & 3) + k));
+        }
         transpose4_to_lds(Yt, wat + wg8, wg8, yr);
         __syncthreads();   // the tile is complete; the other buffer is free once every wavefront is here
         if (ti + 1 < t1) RGNN_W_FETCH(ti + 1)
@@ -384,7 +410,7 @@ static rgnn_status_t launch_wgrad(const TypedLinearWgradBf16Args& a, hipStream_t
     TileArgsB t{a.tiles->tile_seg, a.tiles->tile_row0, a.tiles->tile_row1, a.tiles->chunk_tile};
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.tiles->chunk_slot,
                        static_cast<const unsigned short*>(a.X), a.gather, static_cast<const unsigned short*>(a.dY), a.part,
-                       a.ysel, static_cast<const unsigned short*>(a.dY_alt));
+                       a.ysel, static_cast<const unsigned short*>(a.dY_alt), a.yscale);
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -411,7 +437,7 @@ static rgnn_status_t launch(const TypedLinearBf16Args& a, hipStream_t st) {
     RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_bf16");
     TileArgsB t{a.tiles->tile_seg, a.tiles->tile_row0, a.tiles->tile_row1, a.tiles->chunk_tile};
-    hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.A, a.gather, a.W, a.Y, a.A_alt);
+    hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, t, a.A, a.gather, a.W, a.Y, a.A_alt, a.rowscale);
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -420,6 +446,7 @@ template <int D, bool A_BF16, bool W_BF16, bool WT, bool Y_BF16, bool ACC = fals
 static rgnn_status_t launch_gs(const TypedLinearBf16Args& a, hipStream_t st) {
     const bool g = a.gather != nullptr, sc = g && a.scatter_out;
     if (a.A_alt && !(g && !sc)) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_bf16: a second row tensor needs gathered, unscattered rows");
+    if (a.rowscale && !A_BF16) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_bf16: the row scale is built for bf16 rows");
     if (g && sc) return launch<D, D, A_BF16, W_BF16, WT, true, true, Y_BF16, ACC>(a, st);
     if constexpr (ACC) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed_linear_bf16: accumulation is built for gathered + scattered rows only");
     if (g) return launch<D, D, A_BF16, W_BF16, WT, true, false, Y_BF16, false>(a, st);

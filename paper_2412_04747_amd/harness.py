@@ -45,7 +45,7 @@ class Graph:
         length = {"in_ptr": N + 1, "pair_ptr": R + 1, "pair_src": P, "pair_rel": P, "run_ptr": Q + 1, "run_dst": Q,
                   "run_rel": Q, "dst_run_ptr": N + 1, "relrun_ptr": R + 1, "relrun_idx": Q, "out_ptr": P + 1,
                   "srcpair_ptr": N + 1, "srcpair_idx": P, "ntype_ptr": T + 1, "ntype_perm": N, "relrun_dst": Q,
-                  "pair_sel_dst": P, "pair_sel_run": P, "rel_src_type": R}.get(name, E)
+                  "pair_sel_dst": P, "rel_src_type": R}.get(name, E)
         return B.rgnn_graph_export(self.handle, which, length)
 
     def close(self):

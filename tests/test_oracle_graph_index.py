@@ -50,7 +50,6 @@ def _brute(N, R, src, dst, rel, ntype, T):
     ix["relrun_dst"] = [runs[q][0] for q in rr]
     ix["in_pair_tag"] = [top(p) if len(edges_of[p]) == 1 else p for p in ix["in_pair"]]
     ix["pair_sel_dst"] = [top(edges[edges_of[p][0]][0]) if len(edges_of[p]) == 1 else p for p in range(len(pairs))]
-    ix["pair_sel_run"] = [top(in_run[edges_of[p][0]]) if len(edges_of[p]) == 1 else p for p in range(len(pairs))]
     ix["rel_src_type"] = [next((int(ntype[s]) for r, s in pairs if r == k), 0) for k in range(R)]
     return ix, len(pairs), len(runs)
 
