@@ -32,3 +32,30 @@ def test_algorithmic_work_counts():
     # bf16 rows at width 128 halve the row bytes of the intermediates
     half = bench.algorithmic_work("aggregate_fwd", E, N, P, Q, R, T, 128, 4, 0, bf16=True, layer="hgt")[1]
     assert half == E * (256 + 4 + 16) + N * (256 + 8)
+
+
+import json
+
+import pytest
+
+
+@pytest.mark.gpu
+def test_bench_line_has_the_contract_fields():
+    """One short run of bench.py on the small RGAT workload: exactly one JSON line on stdout with the
+    fields the harness reads, the roofline object of the dominant kernel and the oracle's CPU baseline."""
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--config", "2", "--steps", "3", "--warmup", "1"],
+                       capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert k in d, k
+    assert d["n_gpus"] == 1 and d["steps"] == 3 and d["warmup"] == 1 and d["vs_baseline"] is None
+    assert d["unit"] == "edges/s" and d["value"] > 0 and d["data"] == "synthetic" and "workload" in d["config"]
+    roof = d["roofline"]
+    assert roof["bound"] in ("hbm", "mfma", "alu") and roof["unit"] in ("GB/s", "TFLOP/s")
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9 and "traffic" in roof
+    cpu = d["cpu_baseline"]
+    assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["unit"] == "edges/s" and cpu["sample"]
