@@ -65,6 +65,16 @@ __device__ __forceinline__ void load_cols(const float* __restrict__ p, float (&v
         v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
     }
 }
+// the same with a non-temporal hint: rows that are gathered once and not read again soon
+typedef float rgnn_v4f __attribute__((ext_vector_type(4)));
+template <int V>
+__device__ __forceinline__ void load_cols_nt(const float* __restrict__ p, float (&v)[V]) {
+#pragma unroll
+    for (int q = 0; q < V / 4; ++q) {
+        const rgnn_v4f t = __builtin_nontemporal_load(reinterpret_cast<const rgnn_v4f*>(p) + q);
+        v[4 * q] = t[0]; v[4 * q + 1] = t[1]; v[4 * q + 2] = t[2]; v[4 * q + 3] = t[3];
+    }
+}
 template <int V>
 __device__ __forceinline__ void load_cols(const bf16_t* __restrict__ p, float (&v)[V]) {
     if constexpr (V == 8) {
@@ -78,6 +88,20 @@ __device__ __forceinline__ void load_cols(const bf16_t* __restrict__ p, float (&
         const uint2 t = *reinterpret_cast<const uint2*>(p);
         v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
         v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+    }
+}
+typedef unsigned rgnn_v4u __attribute__((ext_vector_type(4)));
+template <int V>
+__device__ __forceinline__ void load_cols_nt(const bf16_t* __restrict__ p, float (&v)[V]) {
+    if constexpr (V == 8) {
+        const rgnn_v4u t = __builtin_nontemporal_load(reinterpret_cast<const rgnn_v4u*>(p));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v[2 * q] = __uint_as_float(t[q] << 16);
+            v[2 * q + 1] = __uint_as_float(t[q] & 0xFFFF0000u);
+        }
+    } else {
+        load_cols(p, v);
     }
 }
 template <int V>

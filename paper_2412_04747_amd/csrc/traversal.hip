@@ -262,10 +262,13 @@ __device__ __forceinline__ void add_rank1(const Rank1& r1, int lanes_per_head, s
     fma_cols(acc, c, t);
 }
 
-// ROLE only gives each use its own kernel name in profiler output (0 forward aggregation over
-// destinations, 1 backward aggregation over pairs, 2 destination-side weight gradient).
+// ROLE gives each use its own kernel name in profiler output (0 forward aggregation over destinations,
+// 1 backward aggregation over pairs, 2 destination-side weight gradient).  The forward aggregation
+// gathers rows of the large per-pair tensor, most of them once: with fp32 rows those loads carry the
+// non-temporal hint (NT; it did not pay for the 2-byte rows, whose pairs are shared by more edges in the
+// workloads that use them); the other two gather rows of node tensors, which are reused and stay cached.
 // TI / TO: storage type of the gathered rows and of the output rows (float or bf16_t).
-template <int D, typename TI, typename TO, bool R1>
+template <int D, typename TI, typename TO, bool R1, bool NT>
 __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
     constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
     int i = blk * IPB + threadIdx.x / LPR;
@@ -300,7 +303,8 @@ __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
         float cc[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            load_cols(src + (size_t)row[u] * D + cv * V, v[u]);
+            if (NT && sizeof(TI) == 4) load_cols_nt(src + (size_t)row[u] * D + cv * V, v[u]);
+            else load_cols(src + (size_t)row[u] * D + cv * V, v[u]);
             cc[u] = c[u];
         }
         if (j + 4 < e) {
@@ -326,7 +330,7 @@ __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
 // such a segment, so the general kernel would spend its time on the item -> indices -> rows -> store
 // chain; here a group of lanes takes two of them at a time, all loads of both independent (entries
 // past a segment's end repeat its last one with a zero coefficient).
-template <int D, typename TI, typename TO, bool R1>
+template <int D, typename TI, typename TO, bool R1, bool NT>
 __device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int first, int n) {
     constexpr int V = RowT<TI>::V, LPR = D / V, GPB = 256 / LPR;
     const int g = blk * GPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
@@ -359,7 +363,10 @@ __device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int f
 #pragma unroll
     for (int q = 0; q < 2; ++q)
 #pragma unroll
-        for (int u = 0; u < kShortLen; ++u) load_cols(src + (size_t)row[q][u] * D + cv * V, v[q][u]);
+        for (int u = 0; u < kShortLen; ++u) {
+            if (NT && sizeof(TI) == 4) load_cols_nt(src + (size_t)row[q][u] * D + cv * V, v[q][u]);
+            else load_cols(src + (size_t)row[q][u] * D + cv * V, v[q][u]);
+        }
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         float acc[V];
@@ -376,7 +383,7 @@ __device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int f
 // The whole segments with exactly one entry, items [first, first + n): out[row_i] = c * src[row].
 // A group of lanes handles four of them at a time, all loads of the four independent, which keeps
 // enough rows in flight where the general kernel would wait on one short dependent chain per item.
-template <int D, typename TI, typename TO, bool R1>
+template <int D, typename TI, typename TO, bool R1, bool NT>
 __device__ __forceinline__ void gather_single(const GatherArgs& a, int blk, int first, int n) {
     constexpr int V = RowT<TI>::V, LPR = D / V, GPB = 256 / LPR;
     const int g = blk * GPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
@@ -402,7 +409,10 @@ __device__ __forceinline__ void gather_single(const GatherArgs& a, int blk, int 
     }
     float v[4][V];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) load_cols(src + (size_t)row[u] * D + cv * V, v[u]);
+    for (int u = 0; u < 4; ++u) {
+        if (NT && sizeof(TI) == 4) load_cols_nt(src + (size_t)row[u] * D + cv * V, v[u]);
+        else load_cols(src + (size_t)row[u] * D + cv * V, v[u]);
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         if (i0 + u < n) {
@@ -424,16 +434,16 @@ struct GatherRanges { int general_blocks, short_blocks, short_first, short_n, si
 template <int D, int ROLE, typename TI, typename TO, bool R1 = false>
 __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a, GatherRanges r) {
     const int blk = blockIdx.x;
-    if (blk < r.general_blocks) gather_general<D, TI, TO, R1>(a, blk);
-    else if (blk < r.general_blocks + r.short_blocks) gather_short<D, TI, TO, R1>(a, blk - r.general_blocks, r.short_first, r.short_n);
-    else gather_single<D, TI, TO, R1>(a, blk - r.general_blocks - r.short_blocks, r.single_first, r.single_n);
+    if (blk < r.general_blocks) gather_general<D, TI, TO, R1, ROLE == 0>(a, blk);
+    else if (blk < r.general_blocks + r.short_blocks) gather_short<D, TI, TO, R1, ROLE == 0>(a, blk - r.general_blocks, r.short_first, r.short_n);
+    else gather_single<D, TI, TO, R1, ROLE == 0>(a, blk - r.general_blocks - r.short_blocks, r.single_first, r.single_n);
 }
 template <int D, int ROLE, typename TI, typename TO>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(7))) void gather_general_kernel(GatherArgs a) { gather_general<D, TI, TO, false>(a, blockIdx.x); }
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(7))) void gather_general_kernel(GatherArgs a) { gather_general<D, TI, TO, false, ROLE == 0>(a, blockIdx.x); }
 template <int D, int ROLE, typename TI, typename TO>
-__global__ __launch_bounds__(256) void gather_short_kernel(GatherArgs a, int first, int n) { gather_short<D, TI, TO, false>(a, blockIdx.x, first, n); }
+__global__ __launch_bounds__(256) void gather_short_kernel(GatherArgs a, int first, int n) { gather_short<D, TI, TO, false, ROLE == 0>(a, blockIdx.x, first, n); }
 template <int D, int ROLE, typename TI, typename TO>
-__global__ __launch_bounds__(256) void gather_single_kernel(GatherArgs a, int first, int n) { gather_single<D, TI, TO, false>(a, blockIdx.x, first, n); }
+__global__ __launch_bounds__(256) void gather_single_kernel(GatherArgs a, int first, int n) { gather_single<D, TI, TO, false, ROLE == 0>(a, blockIdx.x, first, n); }
 
 // NH weighted sums of the same rows in one walk: out[h][row_i] = sum_j coef[k][h] * src[row], k and row as
 // in gather_sum_kernel (fp32 rows).  out is [NH][out_rows][D], the partial rows [NH][num_partials][D].
@@ -601,7 +611,10 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
         for (int u = 0; u < 4; ++u) {
             at[u] = atn[u];
             pr[u] = prn[u];
-            h[u] = *reinterpret_cast<const float4*>(a.Hs + (size_t)(pr[u] & 0x7FFFFFFF) * D + c4 * 4);
+            {   // the per-pair rows are a large tensor read about once per edge: non-temporal
+                const rgnn_v4f t = __builtin_nontemporal_load(reinterpret_cast<const rgnn_v4f*>(a.Hs + (size_t)(pr[u] & 0x7FFFFFFF) * D + c4 * 4));
+                h[u] = make_float4(t[0], t[1], t[2], t[3]);
+            }
         }
         if (j + 4 < e) {
 #pragma unroll
@@ -690,7 +703,7 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
         float v[4][V], w[4][V];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            if (pi[t] >= 0) load_cols(dXp + (size_t)pi[t] * D + cv * V, v[t]);
+            if (pi[t] >= 0) load_cols_nt(dXp + (size_t)pi[t] * D + cv * V, v[t]);
             else zero_cols(v[t]);
             if (RUNS && rr[t] >= 0) load_cols(a.wtp + (size_t)rr[t] * D + cv * V, w[t]);
             else if (TWO && pi[t] >= 0) load_cols(dXp2 + (size_t)pi[t] * D + cv * V, w[t]);
@@ -721,7 +734,7 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
             zero_cols(w[t]);
             if (j + t < e) {
                 const size_t p = (size_t)a.srcpair_idx[j + t];
-                load_cols(dXp + p * D + cv * V, v[t]);
+                load_cols_nt(dXp + p * D + cv * V, v[t]);
                 if (TWO) load_cols(dXp2 + p * D + cv * V, w[t]);
             }
         }
