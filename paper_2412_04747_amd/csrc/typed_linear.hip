@@ -181,7 +181,10 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
                     const float sc = rowscale[min(row, rbnd - 1)];
                     y.x += sc * wv.x; y.y += sc * wv.y; y.z += sc * wv.z; y.w += sc * wv.w;
                 }
-                if (ok) *yp = y;
+                if (ok) {   // rows of a large tensor that is read again only after it has left the caches: non-temporal
+                    const v4f yv = {y.x, y.y, y.z, y.w};
+                    __builtin_nontemporal_store(yv, reinterpret_cast<v4f*>(yp));
+                }
                 if (VEC) {
                     float sdot = y.x * wv.x + y.y * wv.y + y.z * wv.z + y.w * wv.w;
 #pragma unroll
@@ -387,7 +390,10 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
                     o.x += sc * xv.x; o.y += sc * xv.y; o.z += sc * xv.z; o.w += sc * xv.w;
                 }
                 const size_t d = SCATTER ? (size_t)gout[it] : (size_t)(ra + u * 32 + r);
-                if (r < rows_left) *reinterpret_cast<float4*>(dXrow + d * KD + cx * 4) = o;
+                if (r < rows_left) {
+                    const v4f ov = {o.x, o.y, o.z, o.w};
+                    __builtin_nontemporal_store(ov, reinterpret_cast<v4f*>(dXrow + d * KD + cx * 4));
+                }
             }
             wave_lds_fence();
         }
