@@ -234,7 +234,7 @@ __global__ __launch_bounds__(256) void typed_linear_bf16_kernel(TileArgsB t, con
                     const int r = orow + pass * RPP;
                     if (r < rows_left) {
                         const size_t d = SCATTER ? (size_t)gidx[r] : (size_t)(ra + u * 32 + r);
-                        *reinterpret_cast<v4u*>(Y + d * OD + oc * 8) = *reinterpret_cast<const v4u*>(Aw + r * LS + oc * 8);
+                        __builtin_nontemporal_store(*reinterpret_cast<const v4u*>(Aw + r * LS + oc * 8), reinterpret_cast<v4u*>(Y + d * OD + oc * 8));
                     }
                 }
             }
