@@ -266,7 +266,9 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
         for (int b = 0; b < WB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) accw[b][v] = 0.f;
-        float acca = 0.f;                                   // Avec[k = lane] (lanes < KD)
+        float pa[KB];                                       // partial of Avec[kb * 32 + m] over the rows of parity kh
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) pa[kb] = 0.f;
         // Rows past the end of the run are clamped to its last row (loads stay unconditional)
         // and zeroed when they are written to LDS, so they add nothing to the weight gradient.
         v4f xr[NXR], yr[NYR];
@@ -337,44 +339,86 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
                 if (!ok) v = v4f{0.f, 0.f, 0.f, 0.f};
                 *reinterpret_cast<v4f*>(Yw + (ry + it * RPY) * YS + cy * 4) = v;
             }
-            if (RS && lane < 32) dsw[lane] = lane < rows_left ? dsr : 0.f;
+            const float dsc = RS && (lane & 31) < rows_left ? dsr : 0.f;   // rowscale of row (lane & 31), zero past the end
+            if (RS && lane < 32) dsw[lane] = dsc;
             wave_lds_fence();
             fetch(u + NW);
             fetch_idx(u + 2 * NW);
-            // dXrow unit: 32 x KD, contraction over the output features
+            // The wavefront that is in its MFMA section goes first at instruction issue: the other wavefront
+            // of the SIMD then fills the gaps with its loads and stores instead of interleaving its own MFMAs.
+            __builtin_amdgcn_s_setprio(2);
+            // dXrow unit: 32 x KD, contraction over the output features.  The LDS operands of both MFMA
+            // sections are read ahead of the MFMAs that use them (a ring of B operands two steps deep here,
+            // one step in the weight-gradient section), so a wavefront alone on its SIMD keeps the pipe fed.
             v16f accx[KB];
 #pragma unroll
             for (int b = 0; b < KB; ++b)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) accx[b][v] = 0.f;
-#pragma unroll 2
-            for (int tt = 0; tt < ND / 8; ++tt) {
-                const int n0 = kh * (ND / 2) + 4 * tt;
-                const float4 a4 = *reinterpret_cast<const float4*>(Yw + m * YS + n0);
-                const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+            {
+                const float* yrow = Yw + m * YS + kh * (ND / 2);
+                const float* wcol = Ws + m * WS + kh * (ND / 2);
+                float bq[3][KB];
+                float4 a4 = *reinterpret_cast<const float4*>(yrow), a4n = a4;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int b = 0; b < KB; ++b) {
+                    bq[0][b] = wcol[b * 32 * WS];
+                    bq[1][b] = wcol[b * 32 * WS + 1];
+                }
 #pragma unroll
-                    for (int b = 0; b < KB; ++b) accx[b] = mfma32(av[i], Ws[(b * 32 + m) * WS + n0 + i], accx[b]);
+                for (int s2 = 0; s2 < ND / 2; ++s2) {
+                    if (s2 + 2 < ND / 2) {
+#pragma unroll
+                        for (int b = 0; b < KB; ++b) bq[(s2 + 2) % 3][b] = wcol[b * 32 * WS + s2 + 2];
+                    }
+                    if (s2 % 4 == 0 && s2 + 4 < ND / 2) a4n = *reinterpret_cast<const float4*>(yrow + s2 + 4);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const float av = s2 % 4 == 0 ? a4.x : s2 % 4 == 1 ? a4.y : s2 % 4 == 2 ? a4.z : a4.w;
+#pragma unroll
+                    for (int b = 0; b < KB; ++b) accx[b] = mfma32(av, bq[s2 % 3][b], accx[b]);
+                    if (s2 % 4 == 3) a4 = a4n;
+                }
             }
-            // weight gradient: KD x ND, contraction over the unit's 32 rows (two rows per MFMA)
-#pragma unroll 4
-            for (int s2 = 0; s2 < 16; ++s2) {
-                const int r = 2 * s2 + kh;
+            // weight gradient: KD x ND, contraction over the unit's 32 rows (two rows per MFMA).  The rows'
+            // contribution to Avec rides along: lane (m, kh) holds X[2 s + kh][kb * 32 + m] as its A operand
+            // and adds rowscale[2 s + kh] times it to its partial of column kb * 32 + m.
+            {
                 float av[KB], bv[NB];
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb) av[kb] = Xw[r * XS + kb * 32 + m];
+                for (int kb = 0; kb < KB; ++kb) av[kb] = Xw[kh * XS + kb * 32 + m];
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) bv[nb] = Yw[r * YS + nb * 32 + m];
+                for (int nb = 0; nb < NB; ++nb) bv[nb] = Yw[kh * YS + nb * 32 + m];
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
+                for (int s2 = 0; s2 < 16; ++s2) {
+                    float an[KB], bn[NB];
+                    if (s2 + 1 < 16) {
+                        const int r = 2 * (s2 + 1) + kh;
 #pragma unroll
-                    for (int kb = 0; kb < KB; ++kb) accw[nb * KB + kb] = mfma32(av[kb], bv[nb], accw[nb * KB + kb]);
+                        for (int kb = 0; kb < KB; ++kb) an[kb] = Xw[r * XS + kb * 32 + m];
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) bn[nb] = Yw[r * YS + nb * 32 + m];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (RS) {
+                        const float w0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, dsc), 2 * s2));
+                        const float w1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, dsc), 2 * s2 + 1));
+                        const float w = kh ? w1 : w0;
+#pragma unroll
+                        for (int kb = 0; kb < KB; ++kb) pa[kb] += w * av[kb];
+                    }
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int kb = 0; kb < KB; ++kb) accw[nb * KB + kb] = mfma32(av[kb], bv[nb], accw[nb * KB + kb]);
+                    if (s2 + 1 < 16) {
+#pragma unroll
+                        for (int kb = 0; kb < KB; ++kb) av[kb] = an[kb];
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) bv[nb] = bn[nb];
+                    }
+                }
             }
-            if (RS && lane < KD) {
-#pragma unroll 8
-                for (int r = 0; r < 32; ++r) acca += dsw[r] * Xw[r * XS + lane];
-            }
+            __builtin_amdgcn_s_setprio(0);
             wave_lds_fence();             // all reads of Yw are done before it becomes the dXrow stage
 #pragma unroll
             for (int b = 0; b < KB; ++b)
@@ -409,6 +453,12 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
                         mine[(kb * 32 + acc_row(v, kh)) * ND + nb * 32 + m] = accw[nb * KB + kb][v];
+            float acca = 0.f;                               // Avec[k = lane] (lanes < KD): both row parities added
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const float both = pa[kb] + __shfl_xor(pa[kb], 32);
+                if (kh == kb) acca = both;
+            }
             if (lane < KD) mine[KD * ND + lane] = acca;
         }
         __syncthreads();
