@@ -56,43 +56,59 @@ __global__ void run_logit_kernel(int Q, const int32_t* __restrict__ run_dst, con
 }
 
 // out[i * heads + h] = sum_{j in [ptr[i], ptr[i+1])} val[(via ? via[j] : j) * stride + off + h],  h < heads.
-// One lane per (segment, head) for segments of at most kSerialMax entries; the longer ones (listed
-// by the graph index) get a workgroup per (segment, head) in a second kernel.
-__global__ void segment_scalar_sum_kernel(int n, int heads, const int32_t* __restrict__ ptr,
-                                          const int32_t* __restrict__ via, const float* __restrict__ val, int stride,
-                                          int off, int min_len, float* __restrict__ out) {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (int64_t)n * heads) return;
+// One launch: the first n_long * heads workgroups take one (long segment, head) each (segments of more
+// than kSerialMax entries, listed by the graph index; the hub runs are thousands of entries long), the
+// others one lane per (segment, head) for the segments up to that length.  The long ones come first so
+// that the few workgroups that walk a hub run start at once and the short segments fill the machine
+// around them.
+__global__ __launch_bounds__(256) void segment_scalar_sum_kernel(int n, int heads, const int32_t* __restrict__ ptr,
+                                                                 const int32_t* __restrict__ via,
+                                                                 const float* __restrict__ val, int stride, int off,
+                                                                 int min_len, float* __restrict__ out, int n_long,
+                                                                 const int32_t* __restrict__ long_ids) {
+    __shared__ float red[4];
     const int lh = 31 - __clz(heads);            // the head count is a power of two (checked by the launcher)
+    const int long_blocks = n_long << lh;
+    if ((int)blockIdx.x < long_blocks) {
+        // four loads in flight per lane, lane sums added in lane order, then the four wavefronts' sums in order
+        const int i = long_ids[blockIdx.x >> lh], h = blockIdx.x & (heads - 1);
+        const int b = ptr[i], e = ptr[i + 1];
+        float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+        for (int j = b + (int)threadIdx.x; j < e; j += 1024) {
+            const int j1 = j + 256, j2 = j + 512, j3 = j + 768;
+            t0 += val[(size_t)(via ? via[j] : j) * stride + off + h];
+            if (j1 < e) t1 += val[(size_t)(via ? via[j1] : j1) * stride + off + h];
+            if (j2 < e) t2 += val[(size_t)(via ? via[j2] : j2) * stride + off + h];
+            if (j3 < e) t3 += val[(size_t)(via ? via[j3] : j3) * stride + off + h];
+        }
+        const float t = group_sum<64>((t0 + t1) + (t2 + t3));
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
+        __syncthreads();
+        if (threadIdx.x == 0) out[(size_t)i * heads + h] = (red[0] + red[1]) + (red[2] + red[3]);
+        return;
+    }
+    const int64_t t = (int64_t)(blockIdx.x - long_blocks) * 256 + threadIdx.x;
+    if (t >= (int64_t)n * heads) return;
     const int i = (int)(t >> lh), h = (int)(t & (heads - 1));
     const int b = ptr[i], e = ptr[i + 1];
     if (e - b > kSerialMax || e - b < min_len) return;
+    // four entries per step, every load unconditional (positions past the end repeat the last entry and
+    // add zero), so that a lane has four values in flight instead of one; the sum keeps the entry order
     float s = 0.f;
-    for (int j = b; j < e; ++j) s += val[(size_t)(via ? via[j] : j) * stride + off + h];
-    out[t] = s;
-}
-// Four loads in flight per lane, lane sums added in lane order, then the four wavefronts' sums in
-// order (the hub runs are thousands of entries long).
-__global__ __launch_bounds__(256) void segment_scalar_sum_long_kernel(int heads, const int32_t* __restrict__ long_ids,
-                                                                      const int32_t* __restrict__ ptr,
-                                                                      const int32_t* __restrict__ via,
-                                                                      const float* __restrict__ val, int stride, int off,
-                                                                      float* __restrict__ out) {
-    __shared__ float red[4];
-    const int i = long_ids[blockIdx.x], h = blockIdx.y;
-    const int b = ptr[i], e = ptr[i + 1];
-    float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
-    for (int j = b + (int)threadIdx.x; j < e; j += 1024) {
-        const int j1 = j + 256, j2 = j + 512, j3 = j + 768;
-        t0 += val[(size_t)(via ? via[j] : j) * stride + off + h];
-        if (j1 < e) t1 += val[(size_t)(via ? via[j1] : j1) * stride + off + h];
-        if (j2 < e) t2 += val[(size_t)(via ? via[j2] : j2) * stride + off + h];
-        if (j3 < e) t3 += val[(size_t)(via ? via[j3] : j3) * stride + off + h];
+    for (int j = b; j < e; j += 4) {
+        int id[4];
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int jj = min(j + u, e - 1);
+            id[u] = via ? via[jj] : jj;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = val[(size_t)id[u] * stride + off + h];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s += j + u < e ? v[u] : 0.f;
     }
-    const float t = group_sum<64>((t0 + t1) + (t2 + t3));
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
-    __syncthreads();
-    if (threadIdx.x == 0) out[(size_t)i * heads + h] = (red[0] + red[1]) + (red[2] + red[3]);
+    out[t] = s;
 }
 
 // ------------------------------------------------------------------ edge softmax (RGAT)
@@ -859,14 +875,10 @@ rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng,
     if (heads < 1 || (heads & (heads - 1))) RGNN_FAIL(RGNN_EUNSUPPORTED, "segment_scalar_sum: the head count must be a power of two, got %d", heads);
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, label);
-    hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3(blocks_for((size_t)n * heads, 256)), dim3(256), 0, st, n, heads, ptr,
-                       via, val, stride, off, min_len, out);
+    const size_t long_blocks = (size_t)lng.n * heads;
+    hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3((unsigned)(long_blocks + blocks_for((size_t)n * heads, 256))), dim3(256), 0, st, n,
+                       heads, ptr, via, val, stride, off, min_len, out, lng.n, lng.ids);
     RGNN_CHECK_LAUNCH();
-    if (lng.n > 0) {
-        hipLaunchKernelGGL(segment_scalar_sum_long_kernel, dim3(lng.n, heads), dim3(256), 0, st, heads, lng.ids, ptr, via,
-                           val, stride, off, out);
-        RGNN_CHECK_LAUNCH();
-    }
     return RGNN_OK;
 }
 
