@@ -229,6 +229,10 @@ __global__ __launch_bounds__(256) void hgt_softmax_long_kernel(Items it, int n_l
         }
     }
 }
+// Cut nodes: one wavefront per piece.  The head count is a power of two, so lane l always meets head
+// l & (H - 1): it combines that head's (m, sum) over the node's pieces (the lanes of a head take the
+// pieces in turn and are then reduced across the wavefront), and the piece's att entries, H per edge
+// and contiguous, are normalised with consecutive lanes on consecutive addresses.
 __global__ void hgt_softmax_finish_kernel(int num_partials, const int32_t* __restrict__ part_item,
                                           const int32_t* __restrict__ part_split,
                                           const int32_t* __restrict__ split_ptr, Items it, int H,
@@ -239,17 +243,16 @@ __global__ void hgt_softmax_finish_kernel(int num_partials, const int32_t* __res
     const int sp = part_split[t];
     const int p0 = split_ptr[sp], p1 = split_ptr[sp + 1];
     const int item = part_item[t];
-    for (int h = 0; h < H; ++h) {
-        float m = -INFINITY;
-        for (int p = p0 + lane; p < p1; p += 64) m = fmaxf(m, part_m[(size_t)p * H + h]);
-        m = wave_max(m);
-        float s = 0.f;
-        for (int p = p0 + lane; p < p1; p += 64) s += part_s[(size_t)p * H + h] * expf(part_m[(size_t)p * H + h] - m);
-        s = group_sum<64>(s);
-        const float inv = 1.f / s;
-        for (int j = it.beg[item] + lane; j < it.end[item]; j += 64)
-            att[(size_t)j * H + h] = soft_out(att[(size_t)j * H + h], m, inv, sgn);
-    }
+    const int lh = 31 - __clz(H), h = lane & (H - 1), step = 64 >> lh;
+    float m = -INFINITY;
+    for (int p = p0 + (lane >> lh); p < p1; p += step) m = fmaxf(m, part_m[(size_t)p * H + h]);
+    for (int o = 32; o >= H; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    float s = 0.f;
+    for (int p = p0 + (lane >> lh); p < p1; p += step) s += part_s[(size_t)p * H + h] * expf(part_m[(size_t)p * H + h] - m);
+    for (int o = 32; o >= H; o >>= 1) s += __shfl_xor(s, o);
+    const float inv = 1.f / s;
+    const size_t a0 = (size_t)it.beg[item] * H, a1 = (size_t)it.end[item] * H;
+    for (size_t x = a0 + lane; x < a1; x += 64) att[x] = soft_out(att[x], m, inv, sgn);   // a0 and 64 are multiples of H: entry x is head h
 }
 
 // dl[e][h] = att[e][h] * (dZ[v][h] . M[pair_e][h] - dZ[v][h] . Z[v][h])
