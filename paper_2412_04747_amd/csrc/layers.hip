@@ -539,12 +539,15 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     const bool sel = rgat_row_select(desc);
     RGNN_TRY(edge_dot_bwd(g, D, sv.att, sv.Hs, dO, static_cast<const float*>(out), desc->slope, w.adz, w.G, w.ds_src,
                           sel ? w.ysc : nullptr, st));
-    // 2. ds_dst[q] = sum over the run's edges of dz;  ds_src[p] = sum over the pair's edges of dz
+    // 2. ds_dst[q] = sum over the run's edges of dz
     RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], g->long_runs, nullptr, w.adz, 2, 1, w.ds_dst, st, "ds_dst_sum"));
-    RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2, 1, w.ds_src, st, "ds_src_sum", 2));
-    // 3. G[p] = sum_{e in out(p)} att_e dOut[dst_e] for the pairs with several edges (step 1 wrote the others)
+    // 3. for the pairs with several edges (step 1 wrote the others): G[p] = sum_{e in out(p)} att_e dOut[dst_e] and, in
+    //    the same walk over (att_e, dz_e), ds_src[p] = sum of dz_e; the pairs with more edges than a lane sums
+    //    (among them the ones the walk cuts into pieces) get ds_src from the workgroup-per-segment sum afterwards
     RGNN_TRY(gather_sum(g->pair_items_multi, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.adz, 2, 0, dO, w.G,
-                        w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine"));
+                        w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", 1, 0, 0, nullptr, w.ds_src));
+    RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2, 1, w.ds_src, st,
+                                "ds_src_sum", 2, 1, true));
     // 4. with dHs[p] = G[p] + ds_src[p] w_s[r]:
     //    dXp[p] = dHs[p] W[r]^T = G[p] W[r]^T + ds_src[p] (W[r] w_s[r]);  dW[r] = sum X^T G (+ A^T (x) w_s in step 6);
     //    A[r] = sum ds_src X

@@ -267,6 +267,8 @@ struct GatherArgs {
     int skip_n;
     Rank1 r1;             // optional: out[row_i] += r1.coef[row_i][head] * r1.vec[r1.seg[row_i]] (whole segments here,
                           // cut segments when their pieces are combined)
+    float* sum2;          // optional (S2 kernels): sum2[row_i] = sum_j coef[k * cstride + 1] for the whole segments, added
+                          // in entry order; the caller sums the cut segments itself
 };
 
 template <int D, int V>
@@ -284,7 +286,7 @@ __device__ __forceinline__ void add_rank1(const Rank1& r1, int lanes_per_head, s
 // non-temporal hint (NT; it did not pay for the 2-byte rows, whose pairs are shared by more edges in the
 // workloads that use them); the other two gather rows of node tensors, which are reused and stay cached.
 // TI / TO: storage type of the gathered rows and of the output rows (float or bf16_t).
-template <int D, typename TI, typename TO, bool R1, bool NT>
+template <int D, typename TI, typename TO, bool R1, bool NT, bool S2 = false>
 __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
     constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
     int i = blk * IPB + threadIdx.x / LPR;
@@ -301,7 +303,7 @@ __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
     // memory round trip instead of two.  Positions past the end repeat the last entry with a zero
     // coefficient: every load is unconditional.
     int row[4];
-    float c[4];
+    float c[4], c2[S2 ? 4 : 1], s2 = 0.f;
 #define RGNN_GATHER_FETCH_IDX(J)                                                                  \
     _Pragma("unroll") for (int u = 0; u < 4; ++u) {                                               \
         const int jj = min((J) + u, e - 1);                                                       \
@@ -310,6 +312,7 @@ __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
         float cc = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;                           \
         if (a.cabs) cc = fabsf(cc);                                                               \
         c[u] = (J) + u < e ? cc : 0.f;                                                            \
+        if (S2) c2[S2 ? u : 0] = (J) + u < e ? a.coef[(size_t)k * a.cstride + 1] : 0.f;           \
     }
     if (b < e) {
         RGNN_GATHER_FETCH_IDX(b)
@@ -322,6 +325,7 @@ __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
             if (NT && sizeof(TI) == 4) load_cols_nt(src + (size_t)row[u] * D + cv * V, v[u]);
             else load_cols(src + (size_t)row[u] * D + cv * V, v[u]);
             cc[u] = c[u];
+            if (S2) s2 += c2[S2 ? u : 0];
         }
         if (j + 4 < e) {
             RGNN_GATHER_FETCH_IDX(j + 4)
@@ -337,6 +341,7 @@ __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
     if (slot < 0) {
         if (R1) add_rank1<D>(a.r1, a.lanes_per_head, (size_t)a.it.row[i], cv, acc0);
         store_cols(static_cast<TO*>(a.out) + (size_t)a.it.row[i] * D + cv * V, acc0);
+        if (S2 && cv == 0) a.sum2[a.it.row[i]] = s2;
     } else {
         store_cols(a.partial + (size_t)slot * D + cv * V, acc0);
     }
@@ -346,7 +351,7 @@ __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
 // such a segment, so the general kernel would spend its time on the item -> indices -> rows -> store
 // chain; here a group of lanes takes two of them at a time, all loads of both independent (entries
 // past a segment's end repeat its last one with a zero coefficient).
-template <int D, typename TI, typename TO, bool R1, bool NT>
+template <int D, typename TI, typename TO, bool R1, bool NT, bool S2 = false>
 __device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int first, int n) {
     constexpr int V = RowT<TI>::V, LPR = D / V, GPB = 256 / LPR;
     const int g = blk * GPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
@@ -363,7 +368,7 @@ __device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int f
         orow[q] = a.it.row[i];
     }
     int row[2][kShortLen];
-    float c[2][kShortLen];
+    float c[2][kShortLen], s2[2] = {0.f, 0.f};
 #pragma unroll
     for (int q = 0; q < 2; ++q)
 #pragma unroll
@@ -374,6 +379,7 @@ __device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int f
             float cc = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;
             if (a.cabs) cc = fabsf(cc);
             c[q][u] = b[q] + u < e[q] ? cc : 0.f;
+            if (S2) s2[q] += b[q] + u < e[q] ? a.coef[(size_t)k * a.cstride + 1] : 0.f;
         }
     float v[2][kShortLen][V];
 #pragma unroll
@@ -392,6 +398,7 @@ __device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int f
         if (i0 + q < n) {
             if (R1) add_rank1<D>(a.r1, a.lanes_per_head, (size_t)orow[q], cv, acc);
             store_cols(static_cast<TO*>(a.out) + (size_t)orow[q] * D + cv * V, acc);
+            if (S2 && cv == 0) a.sum2[orow[q]] = s2[q];
         }
     }
 }
@@ -453,6 +460,15 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a, GatherRan
     if (blk < r.general_blocks) gather_general<D, TI, TO, R1, ROLE == 0>(a, blk);
     else if (blk < r.general_blocks + r.short_blocks) gather_short<D, TI, TO, R1, ROLE == 0>(a, blk - r.general_blocks, r.short_first, r.short_n);
     else gather_single<D, TI, TO, R1, ROLE == 0>(a, blk - r.general_blocks - r.short_blocks, r.single_first, r.single_n);
+}
+// The pair-major walk that also sums the second coefficient of every entry per segment (GatherArgs::sum2; fp32
+// rows, lists without single-entry segments), held to the register budget of eight wavefronts per SIMD like the
+// plain walk.
+template <int D>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void gather_sum_s2_kernel(GatherArgs a, GatherRanges r) {
+    const int blk = blockIdx.x;
+    if (blk < r.general_blocks) gather_general<D, float, float, false, false, true>(a, blk);
+    else gather_short<D, float, float, false, false, true>(a, blk - r.general_blocks, r.short_first, r.short_n);
 }
 template <int D, int ROLE, typename TI, typename TO>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(7))) void gather_general_kernel(GatherArgs a) { gather_general<D, TI, TO, false, ROLE == 0>(a, blockIdx.x); }
@@ -871,11 +887,12 @@ rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float*
 
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
                                  int stride, int off, float* out, hipStream_t st, const char* label, int min_len,
-                                 int heads) {
+                                 int heads, bool long_only) {
     if (heads < 1 || (heads & (heads - 1))) RGNN_FAIL(RGNN_EUNSUPPORTED, "segment_scalar_sum: the head count must be a power of two, got %d", heads);
-    if (n == 0) return RGNN_OK;
+    if (n == 0 || (long_only && lng.n == 0)) return RGNN_OK;
     KernelTimer kt(st, label);
     const size_t long_blocks = (size_t)lng.n * heads;
+    if (long_only) n = 0;   // only the first kind of workgroups: the caller has summed the segments of up to kSerialMax entries
     hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3((unsigned)(long_blocks + blocks_for((size_t)n * heads, 256))), dim3(256), 0, st, n,
                        heads, ptr, via, val, stride, off, min_len, out, lng.n, lng.ids);
     RGNN_CHECK_LAUNCH();
@@ -920,7 +937,7 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
                          const float* coef, int cstride, int cabs, const void* src, void* out, float* partial,
                          hipStream_t st, int role, const char* label, const char* combine_label, int heads,
-                         int src_bf16, int out_bf16, const Rank1* r1) {
+                         int src_bf16, int out_bf16, const Rank1* r1, float* sum2) {
     if (L.num_items == 0) return RGNN_OK;
     const Rank1 r1v = r1 ? *r1 : Rank1{nullptr, 0, nullptr, nullptr};
     const int lpr = D / (src_bf16 ? 8 : 4);
@@ -928,7 +945,7 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
     const int ns = L.num_single >= 4096 ? L.num_single : 0;
     const int nsh = L.num_short >= 4096 ? L.num_short : 0;
     const int skip_first = nsh > 0 ? L.first_short : L.first_single;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns, r1v};
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns, r1v, sum2};
     {
         KernelTimer kt(st, label);
         GatherRanges r{};
@@ -945,9 +962,16 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
         RGNN_CHECK_LAUNCH();                                                                                               \
     } while (0)
         if (r1 && (src_bf16 || out_bf16 || role != 1)) RGNN_FAIL(RGNN_EUNSUPPORTED, "gather_sum: the rank-1 term is built for fp32 rows of the pair-major walk");
+        if (sum2 && (src_bf16 || out_bf16 || role != 1 || r1 || heads != 1 || !coef || cstride < 2 || ns > 0 || L.num_single > 0))
+            RGNN_FAIL(RGNN_EUNSUPPORTED, "gather_sum: the second sum is built for fp32 rows of the single-head pair-major walk over lists without single-entry segments");
         if (r1) {
             if (grid.x > 0) {
                 RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 1, float, float, true>), grid, dim3(256), 0, st, a, r));
+                RGNN_CHECK_LAUNCH();
+            }
+        } else if (sum2) {
+            if (grid.x > 0) {
+                RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_s2_kernel<DD>), grid, dim3(256), 0, st, a, r));
                 RGNN_CHECK_LAUNCH();
             }
         } else if (!src_bf16) {
@@ -976,7 +1000,7 @@ rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, c
                                 int row_by_k, const float* coef, const float* src, float* out, float* partial,
                                 hipStream_t st, const char* label, const char* combine_label) {
     if (L.num_items == 0) return RGNN_OK;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, H, 0, 1, src, out, partial, 0, 0, Rank1{nullptr, 0, nullptr, nullptr}};
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, H, 0, 1, src, out, partial, 0, 0, Rank1{nullptr, 0, nullptr, nullptr}, nullptr};
     {
         KernelTimer kt(st, label);
         const dim3 grid(blocks_for(L.num_items, 256 / (D / 4)));
