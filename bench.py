@@ -72,11 +72,12 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
         # per edge: Hs row + in_pair + att + (att, dz) store; per node: dOut row + out row + item;
         # per single-edge pair (P1 of them): ds_src and its G row, or with the row selector att_e only
         "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8) + P1 * ((4 if sel else row) + 4), 2.0 * E * d),
-        # RGAT: only the E - P1 edges of the P - P1 pairs with several edges; coefficient = the (att, dz) pair.
+        # RGAT: only the E - P1 edges of the P - P1 pairs with several edges; coefficient = the (att, dz) pair;
+        # with one head the walk also writes ds_src per pair.
         # RGCN: every edge; row + out_dst + coefficient
         # RGCN with bf16 rows: likewise only pairs with several edges (the typed-linear backward reads the
         # others' rows straight from the destinations' gradient rows)
-        "aggregate_bwd_pair": ("hbm", (E - P1) * (row + 16) + (P - P1) * (row + 8), 2.0 * (E - P1) * d) if layer == "rgat"
+        "aggregate_bwd_pair": ("hbm", (E - P1) * (row + 16) + (P - P1) * (row + 8 + (4 if H == 1 else 0)), 2.0 * (E - P1) * d) if layer == "rgat"
                               else ("hbm", (E - P1) * (row + 8) + (P - P1) * (row + 8), 2.0 * (E - P1) * d) if half
                               else ("hbm", E * (row + 8) + P * (row + 8), 2.0 * E * d),
         # per run: X row + relrun_idx + run_dst + ds_dst
