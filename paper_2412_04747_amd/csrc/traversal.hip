@@ -816,27 +816,53 @@ __global__ __launch_bounds__(256) void node_grad_sum_kernel(NodeSumArgs a) {
 // ------------------------------------------------------------------ RGAT parameter-gradient epilogue
 
 // Per relation r:  dw_s[r] = A[r] W[r];  dw_t[r] = U[r] W[r];  dW[r] += A[r]^T (x) w_s[r] + U[r]^T (x) w_t[r]
-// where A[r] = sum_p ds_src[p] X[src_p] and U[r] = sum_q ds_dst[q] X[dst_q].
-__global__ void rgat_param_finish_kernel(int kd, int nd, const float* __restrict__ W, const float* __restrict__ w_s,
-                                         const float* __restrict__ w_t, const float* __restrict__ A,
-                                         const float* __restrict__ U, float* __restrict__ dW,
-                                         float* __restrict__ dw_s, float* __restrict__ dw_t) {
-    const int r = blockIdx.x;
+// where A[r] = sum_p ds_src[p] X[src_p] and U[r] = sum_q ds_dst[q] X[dst_q].  Workgroup (r, 0) forms the two
+// vectors (the 256 / nd lanes of a column take the k index in turn and are added in order through LDS);
+// workgroups (r, 1 + j) update 1024 consecutive elements of dW[r] each, four per lane.  nd is a power of two.
+__global__ __launch_bounds__(256) void rgat_param_finish_kernel(int kd, int nd, const float* __restrict__ W,
+                                                                const float* __restrict__ w_s, const float* __restrict__ w_t,
+                                                                const float* __restrict__ A, const float* __restrict__ U,
+                                                                float* __restrict__ dW, float* __restrict__ dw_s,
+                                                                float* __restrict__ dw_t) {
+    __shared__ float red[2][256];
+    const int r = blockIdx.x, tid = threadIdx.x, ln = 31 - __clz(nd);
     const float* Wr = W + (size_t)r * kd * nd;
     const float* Ar = A + (size_t)r * kd;
     const float* Ur = U + (size_t)r * kd;
-    for (int n = threadIdx.x; n < nd; n += blockDim.x) {
+    if (blockIdx.y == 0) {
+        const int n = tid & (nd - 1), ks = tid >> ln, KS = 256 >> ln;
         float s = 0.f, t = 0.f;
-        for (int k = 0; k < kd; ++k) {
-            s += Ar[k] * Wr[k * nd + n];
-            t += Ur[k] * Wr[k * nd + n];
+        for (int k = ks; k < kd; k += KS) {
+            const float w = Wr[k * nd + n];
+            s += Ar[k] * w;
+            t += Ur[k] * w;
         }
-        dw_s[(size_t)r * nd + n] = s;
-        dw_t[(size_t)r * nd + n] = t;
+        red[0][tid] = s;
+        red[1][tid] = t;
+        __syncthreads();
+        if (ks == 0) {
+            for (int q = 1; q < KS; ++q) {
+                s += red[0][q * nd + n];
+                t += red[1][q * nd + n];
+            }
+            dw_s[(size_t)r * nd + n] = s;
+            dw_t[(size_t)r * nd + n] = t;
+        }
+        return;
     }
-    for (int i = threadIdx.x; i < kd * nd; i += blockDim.x)
-        dW[(size_t)r * kd * nd + i] +=
-            Ar[i / nd] * w_s[(size_t)r * nd + i % nd] + Ur[i / nd] * w_t[(size_t)r * nd + i % nd];
+    const int i = ((blockIdx.y - 1) * 256 + tid) * 4;
+    if (i >= kd * nd) return;
+    const int k = i >> ln, n = i & (nd - 1);
+    const float a = Ar[k], u = Ur[k];
+    const float4 ws = *reinterpret_cast<const float4*>(w_s + (size_t)r * nd + n);
+    const float4 wt = *reinterpret_cast<const float4*>(w_t + (size_t)r * nd + n);
+    float4* o = reinterpret_cast<float4*>(dW + (size_t)r * kd * nd + i);
+    float4 v = *o;
+    v.x += a * ws.x + u * wt.x;
+    v.y += a * ws.y + u * wt.y;
+    v.z += a * ws.z + u * wt.z;
+    v.w += a * ws.w + u * wt.w;
+    *o = v;
 }
 
 // ------------------------------------------------------------------ elementwise
@@ -1075,7 +1101,8 @@ rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const f
 rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const float* w_s, const float* w_t,
                                 const float* A, const float* U, float* dW, float* dw_s, float* dw_t, hipStream_t st) {
     KernelTimer kt(st, "rgat_param_finish");
-    hipLaunchKernelGGL(rgat_param_finish_kernel, dim3(R), dim3(256), 0, st, kd, nd, W, w_s, w_t, A, U, dW, dw_s, dw_t);
+    hipLaunchKernelGGL(rgat_param_finish_kernel, dim3(R, 1 + (kd * nd + 1023) / 1024), dim3(256), 0, st, kd, nd, W, w_s, w_t, A, U, dW, dw_s,
+                       dw_t);
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
