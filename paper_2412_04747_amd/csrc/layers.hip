@@ -551,7 +551,7 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     // 4. with dHs[p] = G[p] + ds_src[p] w_s[r]:
     //    dXp[p] = dHs[p] W[r]^T = G[p] W[r]^T + ds_src[p] (W[r] w_s[r]);  dW[r] = sum X^T G (+ A^T (x) w_s in step 6);
     //    A[r] = sum ds_src X
-    RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_s), w.wsp, st));
+    RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_s), w.wsp, st, static_cast<const float*>(w_t), w.wtp));   // wtp: step 7
     TypedLinearBwdArgs b{};
     b.tiles = &g->pair_tiles_wide; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
     b.rowscale = w.ds_src; b.vec = w.wsp; b.dW = static_cast<float*>(dW); b.Avec = w.A;
@@ -565,7 +565,6 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     RGNN_TRY(rgat_param_finish(g->R, K, D, Wf, static_cast<const float*>(w_s), static_cast<const float*>(w_t), w.A, w.U,
                                static_cast<float*>(dW), static_cast<float*>(dw_s), static_cast<float*>(dw_t), st));
     // 7. dX[u] = sum over u's pairs of dXp + sum over u's runs of ds_dst[q] (W[r] w_t[r])
-    RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_t), w.wtp, st));
     RGNN_TRY(node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, nullptr, static_cast<float*>(dX), st));
     return RGNN_OK;
 }

@@ -4,7 +4,9 @@
 
 namespace rgnn {
 
-rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st);
+// wv[r] = W[r] w[r]; optionally a second vector per relation in the same pass (wv2[r] = W[r] w2[r])
+rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st,
+                          const float* w2 = nullptr, float* wv2 = nullptr);
 rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st);
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
                                  int stride, int off, float* out, hipStream_t st, const char* label, int min_len = 0,

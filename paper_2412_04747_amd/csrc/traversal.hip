@@ -22,16 +22,27 @@ namespace rgnn {
 // ------------------------------------------------------------------ small dense helpers
 
 // wv[r][k] = sum_n W[r][k][n] * w[r][n]      (linear operator reordering, Ch.3: x (W w) instead of (x W) w)
-__global__ void fold_weight_kernel(const float* __restrict__ W, const float* __restrict__ w, int kd, int nd,
-                                   int total, float* __restrict__ wv) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;  // (r, k)
+// for one vector per relation or two (w2 / wv2 optional) in the same pass over W.  Eight lanes per weight row,
+// 16-byte loads; nd is a multiple of 32.
+__global__ __launch_bounds__(256) void fold_weight_kernel(const float* __restrict__ W, const float* __restrict__ w,
+                                                          const float* __restrict__ w2, int kd, int nd, int total,
+                                                          float* __restrict__ wv, float* __restrict__ wv2) {
+    const int i = (blockIdx.x * 256 + threadIdx.x) >> 3, l = threadIdx.x & 7;  // (r, k)
     if (i >= total) return;
     const int r = i / kd;
     const float* Wr = W + (size_t)i * nd;
-    const float* wr = w + (size_t)r * nd;
-    float s = 0.f;
-    for (int n = 0; n < nd; ++n) s += Wr[n] * wr[n];
-    wv[i] = s;
+    float s = 0.f, s2 = 0.f;
+    for (int n = 4 * l; n < nd; n += 32) {
+        const float4 x = *reinterpret_cast<const float4*>(Wr + n);
+        s += dot4(x, *reinterpret_cast<const float4*>(w + (size_t)r * nd + n));
+        if (w2) s2 += dot4(x, *reinterpret_cast<const float4*>(w2 + (size_t)r * nd + n));
+    }
+    s = group_sum<8>(s);
+    s2 = group_sum<8>(s2);
+    if (l == 0) {
+        wv[i] = s;
+        if (w2) wv2[i] = s2;
+    }
 }
 
 // s_dst[q] = X[run_dst[q]] . wtp[run_rel[q]]; each lane group takes four consecutive runs so
@@ -894,10 +905,12 @@ __global__ void widen_bf16_kernel(size_t n, const uint16_t* __restrict__ src, fl
 // ==================================================================== host launchers
 
 
-rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st) {
+rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st, const float* w2,
+                          float* wv2) {
     const int total = R * kd;
+    if (nd % 32) RGNN_FAIL(RGNN_EUNSUPPORTED, "fold_weight: width %d is not a multiple of 32", nd);
     KernelTimer kt(st, "fold_weight");
-    hipLaunchKernelGGL(fold_weight_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, st, W, w, kd, nd, total, wv);
+    hipLaunchKernelGGL(fold_weight_kernel, dim3(blocks_for((size_t)total * 8, 256)), dim3(256), 0, st, W, w, w2, kd, nd, total, wv, wv2);
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
