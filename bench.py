@@ -50,8 +50,8 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
             return (bound, n * (row + out_row + extra + 4) + segs * w2, 2.0 * n * d * d)
     w2 = d * d * 4
     # single-head RGAT up to width 64: the gradient row of a single-edge pair is not stored per pair; the
-    # backward typed linear reads att_e * dOut[dst_e] through a row selector (one index per pair, one scale
-    # per single-edge pair)
+    # backward typed linear reads att_e * dOut[dst_e] through a row selector (one index per pair; ds_src[p] and
+    # the scale come as one pair of floats per pair)
     sel = layer == "rgat" and H == 1 and d <= 64
     pair_fwd = ("mfma", P * (2 * row + 4) + R * w2, 2.0 * P * d * d)        # gathered row + stored row + pair_src
     pair_bwd = ("mfma", P * (3 * row + 4) + R * w2, 4.0 * P * d * d)        # dY row + gathered row + stored row
@@ -63,7 +63,7 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
     table = {
         # RGAT: + s_src per pair; backward also reads ds_src
         "typed_linear_fwd": ("mfma", pair_fwd[1] + (P * 4 if layer == "rgat" else 0), pair_fwd[2]),
-        "typed_linear_bwd": ("mfma", pair_bwd[1] + (P * 4 if layer == "rgat" else 0) + (P * 4 + P1 * 4 if sel else 0), pair_bwd[2]),
+        "typed_linear_bwd": ("mfma", pair_bwd[1] + (P * 4 if layer == "rgat" else 0) + (P * 8 if sel else 0), pair_bwd[2]),
         "self_loop_fwd": ("mfma", N * 3 * r32 + w2, 2.0 * N * d * d),         # X row + out row read and written
         "self_loop_bwd": ("mfma", N * 3 * r32 + w2, 4.0 * N * d * d),
         "aggregate_fwd": agg_dst,

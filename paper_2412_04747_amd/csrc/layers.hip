@@ -93,7 +93,7 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
 struct RgatSaved { float* Hs; float* att; };
 struct RgatFwdWs { float* wtp; float* s_src; float* s_dst; float* part_m; float* part_s; float* partial; };
 struct RgatBwdWs {
-    float* wtp; float* wsp; float* adz; float* ds_dst; float* ds_src; float* ysc; float* G; float* dXp; float* A; float* U;
+    float* wtp; float* wsp; float* adz; float* ds_dst; float* ds_src; float* G; float* dXp; float* A; float* U;
     float* tl_part; float* partial;
 };
 // Single-head RGAT at widths up to 64: the gradient rows of single-edge pairs are not written per pair;
@@ -124,8 +124,8 @@ size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
     w->wsp = c.take<float>((size_t)g->R * d->d_in);
     w->adz = c.take<float>((size_t)g->E * std::max<size_t>(2, H));   // (att, dz) pairs, or dz per head
     w->ds_dst = c.take<float>((size_t)g->Q * H);
-    w->ds_src = c.take<float>((size_t)g->P * H);
-    w->ysc = c.take<float>(rgat_row_select(d) ? (size_t)g->P : 0);
+    // with the row selector: (ds_src[p], att of the pair's only edge) interleaved, one pair of floats per p
+    w->ds_src = c.take<float>(rgat_row_select(d) ? 2 * (size_t)g->P : (size_t)g->P * H);
     w->G = c.take<float>((size_t)g->P * d->d_out);
     w->dXp = c.take<float>((size_t)g->P * d->d_in);
     w->A = c.take<float>((size_t)g->R * d->d_in);
@@ -535,28 +535,31 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         return node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, nullptr, dX, st, 0, 0, H);
     }
     // 1. per CSR edge: (att_e, dz_e); for single-edge pairs also ds_src[p] and G[p] = att_e dOut[dst_e] (or, with
-    //    the row selector, only att_e: step 4 then reads the row from dOut)
+    //    the row selector, only att_e: step 4 then reads the row from dOut).  With the selector ds_src[p] and that
+    //    att_e are stored side by side (one 8-byte store here, one 8-byte load per row in step 4): w.ds_src then
+    //    holds P pairs of floats and ds_src[p] is element 2 p.
     const bool sel = rgat_row_select(desc);
+    const int dss = sel ? 2 : 1;
     RGNN_TRY(edge_dot_bwd(g, D, sv.att, sv.Hs, dO, static_cast<const float*>(out), desc->slope, w.adz, w.G, w.ds_src,
-                          sel ? w.ysc : nullptr, st));
+                          sel ? w.ds_src : nullptr, st));
     // 2. ds_dst[q] = sum over the run's edges of dz
     RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], g->long_runs, nullptr, w.adz, 2, 1, w.ds_dst, st, "ds_dst_sum"));
     // 3. for the pairs with several edges (step 1 wrote the others): G[p] = sum_{e in out(p)} att_e dOut[dst_e] and, in
     //    the same walk over (att_e, dz_e), ds_src[p] = sum of dz_e; the pairs with more edges than a lane sums
     //    (among them the ones the walk cuts into pieces) get ds_src from the workgroup-per-segment sum afterwards
     RGNN_TRY(gather_sum(g->pair_items_multi, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.adz, 2, 0, dO, w.G,
-                        w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", 1, 0, 0, nullptr, w.ds_src));
+                        w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", 1, 0, 0, nullptr, w.ds_src, dss));
     RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2, 1, w.ds_src, st,
-                                "ds_src_sum", 2, 1, true));
+                                "ds_src_sum", 2, 1, true, dss));
     // 4. with dHs[p] = G[p] + ds_src[p] w_s[r]:
     //    dXp[p] = dHs[p] W[r]^T = G[p] W[r]^T + ds_src[p] (W[r] w_s[r]);  dW[r] = sum X^T G (+ A^T (x) w_s in step 6);
     //    A[r] = sum ds_src X
     RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_s), w.wsp, st, static_cast<const float*>(w_t), w.wtp));   // wtp: step 7
     TypedLinearBwdArgs b{};
     b.tiles = &g->pair_tiles_wide; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
-    b.rowscale = w.ds_src; b.vec = w.wsp; b.dW = static_cast<float*>(dW); b.Avec = w.A;
+    b.rowscale = sel ? nullptr : w.ds_src; b.vec = w.wsp; b.dW = static_cast<float*>(dW); b.Avec = w.A;
     b.part = w.tl_part;
-    if (sel) { b.ysel = g->pair_ysel; b.dY_alt = dO; b.yscale = w.ysc; }
+    if (sel) { b.ysel = g->pair_ysel; b.dY_alt = dO; b.ds_yscale = reinterpret_cast<const float2*>(w.ds_src); }
     RGNN_TRY(typed_linear_bwd(K, D, b, st));
     // 5. U[r] = sum over r's runs of ds_dst[q] X[run_dst[q]]
     RGNN_TRY(gather_sum(g->relrun_items, K, g->idx[RGNN_IDX_RELRUN_IDX], g->relrun_dst, 0, w.ds_dst, 1, 0, Xf,

@@ -167,11 +167,13 @@ struct TypedLinearBwdArgs {
     float* Avec;             // [segs][KD] (with rowscale)
     float* part;             // scratch [num_slots][KD*ND + KD]
     const char* label;
-    // Optional row selector (widths up to 64, ungathered dY with rowscale): row i of dY is
-    // ysel[i] < 0 ? yscale[i] * dY_alt[ysel[i] & 0x7FFFFFFF] : dY[ysel[i]].
+    // Optional row selector (widths up to 64, ungathered dY): row i of dY is
+    // ysel[i] < 0 ? scale_i * dY_alt[ysel[i] & 0x7FFFFFFF] : dY[ysel[i]].  rowscale[i] and scale_i then come
+    // interleaved as ds_yscale[i] = (rowscale_i, scale_i) and `rowscale` stays null (scale_i is read only where
+    // the top bit of ysel[i] is set).
     const int32_t* ysel = nullptr;
     const float* dY_alt = nullptr;
-    const float* yscale = nullptr;
+    const float2* ds_yscale = nullptr;
 };
 // bf16 matrix-core variant (typed_linear_bf16.hip): Y[i] = A[g(i)] W[seg]  (or W[seg]^T)
 struct TypedLinearBf16Args {

@@ -10,7 +10,7 @@ rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w,
 rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st);
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
                                  int stride, int off, float* out, hipStream_t st, const char* label, int min_len = 0,
-                                 int heads = 1, bool long_only = false);
+                                 int heads = 1, bool long_only = false, int ostride = 1);
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
                            float* part_m, float* part_s, hipStream_t st);
 // Optional rank-1 term of a gather-sum: out[i] += coef[i * stride + head] * vec[seg[i]] (fp32 vec rows of the output width)
@@ -18,14 +18,16 @@ struct Rank1 { const float* coef; int stride; const int32_t* seg; const float* v
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
                          const float* coef, int cstride, int cabs, const void* src, void* out, float* partial,
                          hipStream_t st, int role, const char* label, const char* combine_label, int heads = 1,
-                         int src_bf16 = 0, int out_bf16 = 0, const Rank1* r1 = nullptr, float* sum2 = nullptr);
+                         int src_bf16 = 0, int out_bf16 = 0, const Rank1* r1 = nullptr, float* sum2 = nullptr,
+                         int sum2_stride = 1);
 // H weighted sums of the same gathered rows in one walk (coef [entries][H]); out [H][out_rows][D]
 rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, const int32_t* via, const int32_t* rowidx,
                                 int row_by_k, const float* coef, const float* src, float* out, float* partial,
                                 hipStream_t st, const char* label, const char* combine_label);
-// yscale (optional, [P]): single-edge pairs get att_e there instead of their row att_e * dOut[v] in G
+// dsy (optional, [P] pairs of floats): a single-edge pair gets (dz_e, att_e) there instead of ds_src[p] and its
+// row att_e * dOut[v] in G
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
-                           const float* out, float slope, float* adz, float* G, float* ds_src, float* yscale,
+                           const float* out, float slope, float* adz, float* G, float* ds_src, float* dsy,
                            hipStream_t st);
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const float* ds_dst, const float* wtp,
                             const float* extra, void* dX, hipStream_t st, int in_bf16 = 0, int out_bf16 = 0, int heads = 1,

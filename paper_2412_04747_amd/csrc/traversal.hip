@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void segment_scalar_sum_kernel(int n, int head
                                                                  const int32_t* __restrict__ via,
                                                                  const float* __restrict__ val, int stride, int off,
                                                                  int min_len, float* __restrict__ out, int n_long,
-                                                                 const int32_t* __restrict__ long_ids) {
+                                                                 const int32_t* __restrict__ long_ids, int ostride) {
     __shared__ float red[4];
     const int lh = 31 - __clz(heads);            // the head count is a power of two (checked by the launcher)
     const int long_blocks = n_long << lh;
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void segment_scalar_sum_kernel(int n, int head
         const float t = group_sum<64>((t0 + t1) + (t2 + t3));
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
         __syncthreads();
-        if (threadIdx.x == 0) out[(size_t)i * heads + h] = (red[0] + red[1]) + (red[2] + red[3]);
+        if (threadIdx.x == 0) out[((size_t)i * heads + h) * ostride] = (red[0] + red[1]) + (red[2] + red[3]);
         return;
     }
     const int64_t t = (int64_t)(blockIdx.x - long_blocks) * 256 + threadIdx.x;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256) void segment_scalar_sum_kernel(int n, int head
 #pragma unroll
         for (int u = 0; u < 4; ++u) s += j + u < e ? v[u] : 0.f;
     }
-    out[t] = s;
+    out[t * ostride] = s;
 }
 
 // ------------------------------------------------------------------ edge softmax (RGAT)
@@ -278,8 +278,8 @@ struct GatherArgs {
     int skip_n;
     Rank1 r1;             // optional: out[row_i] += r1.coef[row_i][head] * r1.vec[r1.seg[row_i]] (whole segments here,
                           // cut segments when their pieces are combined)
-    float* sum2;          // optional (S2 kernels): sum2[row_i] = sum_j coef[k * cstride + 1] for the whole segments, added
-                          // in entry order; the caller sums the cut segments itself
+    float* sum2;          // optional (S2 kernels): sum2[row_i * sum2_stride] = sum_j coef[k * cstride + 1] for the whole
+    int sum2_stride;      // segments, added in entry order; the caller sums the cut segments itself
 };
 
 template <int D, int V>
@@ -352,7 +352,7 @@ __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
     if (slot < 0) {
         if (R1) add_rank1<D>(a.r1, a.lanes_per_head, (size_t)a.it.row[i], cv, acc0);
         store_cols(static_cast<TO*>(a.out) + (size_t)a.it.row[i] * D + cv * V, acc0);
-        if (S2 && cv == 0) a.sum2[a.it.row[i]] = s2;
+        if (S2 && cv == 0) a.sum2[(size_t)a.it.row[i] * a.sum2_stride] = s2;
     } else {
         store_cols(a.partial + (size_t)slot * D + cv * V, acc0);
     }
@@ -409,7 +409,7 @@ __device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int f
         if (i0 + q < n) {
             if (R1) add_rank1<D>(a.r1, a.lanes_per_head, (size_t)orow[q], cv, acc);
             store_cols(static_cast<TO*>(a.out) + (size_t)orow[q] * D + cv * V, acc);
-            if (S2 && cv == 0) a.sum2[orow[q]] = s2[q];
+            if (S2 && cv == 0) a.sum2[(size_t)orow[q] * a.sum2_stride] = s2[q];
         }
     }
 }
@@ -622,7 +622,8 @@ struct EdgeDotArgs {
     float2* adz;
     float* G;
     float* ds_src;
-    float* yscale;   // if given, a single-edge pair gets att_e here instead of its row att_e * dOut[v] in G
+    float2* dsy;     // if given, a single-edge pair gets (dz_e, att_e) here in one store instead of ds_src[p] and its
+                     // row att_e * dOut[v] in G
 };
 
 template <int D>
@@ -678,10 +679,10 @@ __global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
             if (c4 == u) mine = make_float2(al, dz);
             if (live && pr[u] < 0) {   // single-edge pair
                 const size_t p = (size_t)(pr[u] & 0x7FFFFFFF);
-                if (!a.yscale) *reinterpret_cast<float4*>(a.G + p * D + c4 * 4) = make_float4(al * go.x, al * go.y, al * go.z, al * go.w);
+                if (!a.dsy) *reinterpret_cast<float4*>(a.G + p * D + c4 * 4) = make_float4(al * go.x, al * go.y, al * go.z, al * go.w);
                 if (c4 == 0) {
-                    a.ds_src[p] = dz;
-                    if (a.yscale) a.yscale[p] = al;
+                    if (a.dsy) a.dsy[p] = make_float2(dz, al);
+                    else a.ds_src[p] = dz;
                 }
             }
         }
@@ -926,14 +927,14 @@ rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float*
 
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
                                  int stride, int off, float* out, hipStream_t st, const char* label, int min_len,
-                                 int heads, bool long_only) {
+                                 int heads, bool long_only, int ostride) {
     if (heads < 1 || (heads & (heads - 1))) RGNN_FAIL(RGNN_EUNSUPPORTED, "segment_scalar_sum: the head count must be a power of two, got %d", heads);
     if (n == 0 || (long_only && lng.n == 0)) return RGNN_OK;
     KernelTimer kt(st, label);
     const size_t long_blocks = (size_t)lng.n * heads;
     if (long_only) n = 0;   // only the first kind of workgroups: the caller has summed the segments of up to kSerialMax entries
     hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3((unsigned)(long_blocks + blocks_for((size_t)n * heads, 256))), dim3(256), 0, st, n,
-                       heads, ptr, via, val, stride, off, min_len, out, lng.n, lng.ids);
+                       heads, ptr, via, val, stride, off, min_len, out, lng.n, lng.ids, ostride);
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
@@ -976,7 +977,7 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,
                          const float* coef, int cstride, int cabs, const void* src, void* out, float* partial,
                          hipStream_t st, int role, const char* label, const char* combine_label, int heads,
-                         int src_bf16, int out_bf16, const Rank1* r1, float* sum2) {
+                         int src_bf16, int out_bf16, const Rank1* r1, float* sum2, int sum2_stride) {
     if (L.num_items == 0) return RGNN_OK;
     const Rank1 r1v = r1 ? *r1 : Rank1{nullptr, 0, nullptr, nullptr};
     const int lpr = D / (src_bf16 ? 8 : 4);
@@ -984,7 +985,7 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
     const int ns = L.num_single >= 4096 ? L.num_single : 0;
     const int nsh = L.num_short >= 4096 ? L.num_short : 0;
     const int skip_first = nsh > 0 ? L.first_short : L.first_single;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns, r1v, sum2};
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns, r1v, sum2, sum2_stride};
     {
         KernelTimer kt(st, label);
         GatherRanges r{};
@@ -1039,7 +1040,7 @@ rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, c
                                 int row_by_k, const float* coef, const float* src, float* out, float* partial,
                                 hipStream_t st, const char* label, const char* combine_label) {
     if (L.num_items == 0) return RGNN_OK;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, H, 0, 1, src, out, partial, 0, 0, Rank1{nullptr, 0, nullptr, nullptr}, nullptr};
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, H, 0, 1, src, out, partial, 0, 0, Rank1{nullptr, 0, nullptr, nullptr}, nullptr, 1};
     {
         KernelTimer kt(st, label);
         const dim3 grid(blocks_for(L.num_items, 256 / (D / 4)));
@@ -1079,11 +1080,12 @@ rgnn_status_t aggregate_edge_parallel(const rgnn_graph* g, int D, const float* a
 }
 
 rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
-                           const float* out, float slope, float* adz, float* G, float* ds_src, float* yscale,
+                           const float* out, float slope, float* adz, float* G, float* ds_src, float* dsy,
                            hipStream_t st) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
-    EdgeDotArgs a{dev_items(L), g->in_pair_tag, att, Hs, dOut, out, slope, reinterpret_cast<float2*>(adz), G, ds_src, yscale};
+    EdgeDotArgs a{dev_items(L), g->in_pair_tag, att, Hs, dOut, out, slope, reinterpret_cast<float2*>(adz), G, ds_src,
+                  reinterpret_cast<float2*>(dsy)};
     KernelTimer kt(st, "edge_dot_bwd");
     RGNN_DISPATCH_D(D, hipLaunchKernelGGL(edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
                                      0, st, a));

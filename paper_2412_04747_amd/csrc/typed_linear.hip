@@ -215,11 +215,12 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
 // gradients are summed in wavefront order through LDS and written to the chunk's slot.
 //
 // SEL (row selector): row i of dY is either dY[ysel[i]] or, when the top bit of ysel[i] is set, row
-// ysel[i] & 0x7FFFFFFF of a second tensor times yscale[i].  (RGAT: the gradient row of a (source,
+// ysel[i] & 0x7FFFFFFF of a second tensor times a per-row scale; rowscale[i] and that scale come as one
+// (rowscale, scale) pair per row.  (RGAT: the gradient row of a (source,
 // relation) pair with a single edge is att_e * dOut[dst_e]; it is read from dOut here instead of
 // being written out per pair first.)  A lane keeps the selector and the scale of one row of the unit
 // and hands them to the lanes that load or store that row with a cross-lane read.
-struct RowSelect { const int32_t* sel; const float* alt; const float* scale; };
+struct RowSelect { const int32_t* sel; const float* alt; const float2* ds_scale; };
 template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS, bool SEL = false>
 __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, const float* __restrict__ X,
                                                                     const int32_t* __restrict__ gather,
@@ -311,8 +312,13 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
                     yr[it] = *reinterpret_cast<const v4f*>(dY + s2 * ND + cy * 4);
                 }
             }
-            if (RS) dsr = rowscale[min(ra + u * 32 + (lane & 31), rbnd - 1)];
-            if (SEL) alr = ysn < 0 ? ys.scale[min(ra + u * 32 + (lane & 31), rbnd - 1)] : 1.f;
+            if (SEL) {
+                const float2 pr = ys.ds_scale[min(ra + u * 32 + (lane & 31), rbnd - 1)];
+                dsr = pr.x;
+                alr = ysn < 0 ? pr.y : 1.f;
+            } else if (RS) {
+                dsr = rowscale[min(ra + u * 32 + (lane & 31), rbnd - 1)];
+            }
         };
         fetch_idx(wave);
         fetch(wave);
@@ -676,7 +682,7 @@ static rgnn_status_t launch_bwd_wave(const TypedLinearBwdArgs& a, hipStream_t st
     RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(512), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
-                       a.dY, a.dXrow, a.rowscale, a.vec, a.part, RowSelect{a.ysel, a.dY_alt, a.yscale});
+                       a.dY, a.dXrow, a.rowscale, a.vec, a.part, RowSelect{a.ysel, a.dY_alt, a.ds_yscale});
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -725,8 +731,8 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
         if constexpr (KD <= 64 && ND <= 64) {
             const bool g = a.gather != nullptr, dg = g && a.dy_gathered, sc = g && a.scatter_dx, rs = a.rowscale != nullptr;
             done = true;
-            if (a.ysel && !(g && !dg && !sc && rs && a.dY_alt && a.yscale))
-                RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: the row selector needs gathered X, ungathered dY and rowscale");
+            if (a.ysel && !(g && !dg && !sc && !rs && a.vec && a.dY_alt && a.ds_yscale))
+                RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: the row selector needs gathered X, ungathered dY, vec and the (rowscale, scale) pairs");
             if (a.ysel) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true, true>(a, st)));
             else if (g && !dg && !sc && rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true>(a, st)));
             else if (g && !dg && !sc && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, false>(a, st)));
