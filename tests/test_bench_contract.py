@@ -22,8 +22,8 @@ def test_algorithmic_work_counts():
     assert bound == "hbm" and nbytes == E * (row + 8) + N * (row + 8) and flops == 2.0 * E * d
     bound, nbytes, flops = bench.algorithmic_work("typed_linear_bwd", E, N, P, Q, R, T, d, H, P1)
     assert bound == "mfma" and flops == 4.0 * P * d * d
-    # dY row + gathered X row + stored row, the gather index, ds_src, the row selector and the single-edge scales
-    assert nbytes == P * (3 * row + 4) + R * d * d * 4 + P * 4 + P * 4 + P1 * 4
+    # dY row + gathered X row + stored row, the gather index, the row selector and the (ds_src, scale) pair per row
+    assert nbytes == P * (3 * row + 4) + R * d * d * 4 + P * 4 + P * 8
     # a single-edge pair costs the edge-dot kernel two scalars, not a row, where the row selector is used
     with_sel = bench.algorithmic_work("edge_dot_bwd", E, N, P, Q, R, T, d, H, P1)[1]
     without = bench.algorithmic_work("edge_dot_bwd", E, N, P, Q, R, T, 128, H, P1)[1]
