@@ -78,8 +78,16 @@ __global__ void hgt_fold_kernel(int R, int d, int H, const int32_t* __restrict__
     const float* Wn = Wnode + ((size_t)rel_type[r] * d + k) * d;
     const float* Wb = Wbd + (size_t)r * d * d;
     const int j0 = n / dh * dh;
-    float s = 0.f;
-    for (int j = j0; j < j0 + dh; ++j) s += Wn[j] * Wb[(size_t)j * d + n];
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;      // dh is a multiple of 16: four independent chains
+#pragma unroll 2
+    for (int j = j0; j < j0 + dh; j += 4) {
+        const float4 w4 = *reinterpret_cast<const float4*>(Wn + j);
+        s0 += w4.x * Wb[(size_t)j * d + n];
+        s1 += w4.y * Wb[(size_t)(j + 1) * d + n];
+        s2 += w4.z * Wb[(size_t)(j + 2) * d + n];
+        s3 += w4.w * Wb[(size_t)(j + 3) * d + n];
+    }
+    const float s = (s0 + s1) + (s2 + s3);
     if (Wf) Wf[i] = s;
     if (Wf16) Wf16[i] = (bf16_t)(bf16_pack2(s, 0.f) & 0xFFFFu);
 }
@@ -94,9 +102,16 @@ __global__ void hgt_fold_bwd_rel_kernel(int R, int d, int H, const int32_t* __re
     const int r = (int)(i / ((size_t)d * dh)), j = (int)(i / dh % d), n = j / dh * dh + (int)(i % dh);
     const float* Wn = Wnode + (size_t)rel_type[r] * d * d;
     const float* G = dWf + (size_t)r * d * d;
-    float s = 0.f;
-    for (int k = 0; k < d; ++k) s += Wn[(size_t)k * d + j] * G[(size_t)k * d + n];
-    dWbd[((size_t)r * d + j) * d + n] = s;
+    // four partial sums over k = 4 i + q keep eight independent loads in flight (d is a multiple of 32)
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll 2
+    for (int k = 0; k < d; k += 4) {
+        s0 += Wn[(size_t)k * d + j] * G[(size_t)k * d + n];
+        s1 += Wn[(size_t)(k + 1) * d + j] * G[(size_t)(k + 1) * d + n];
+        s2 += Wn[(size_t)(k + 2) * d + j] * G[(size_t)(k + 2) * d + n];
+        s3 += Wn[(size_t)(k + 3) * d + j] * G[(size_t)(k + 3) * d + n];
+    }
+    dWbd[((size_t)r * d + j) * d + n] = (s0 + s1) + (s2 + s3);
 }
 
 // dWnode[t][k][j] = sum over relations r with t(r) = t, ascending, of sum over n in the head of j of dWf[r][k][n] * Wbd[r][j][n]
@@ -113,8 +128,11 @@ __global__ void hgt_fold_bwd_node_kernel(int T, int R, int d, int H, const int32
         if (rel_type[r] != t) continue;
         const float* G = dWf + ((size_t)r * d + k) * d;
         const float* Wb = Wbd + ((size_t)r * d + j) * d;
-        float p = 0.f;
-        for (int n = n0; n < n0 + dh; ++n) p += G[n] * Wb[n];
+        float p = 0.f;     // dh is a multiple of 16 and n0 of dh: 16-byte loads
+        for (int n = n0; n < n0 + dh; n += 4) {
+            const float4 gv = *reinterpret_cast<const float4*>(G + n), wv = *reinterpret_cast<const float4*>(Wb + n);
+            p += (gv.x * wv.x + gv.y * wv.y) + (gv.z * wv.z + gv.w * wv.w);
+        }
         s += p;
     }
     dWnode[i] = s;
