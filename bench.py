@@ -61,8 +61,8 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
     agg_dst = ("hbm", E * (row + 4 + 4 * H) + N * (out_dst + 8), 2.0 * E * d)  # row + in_pair + coefficient(s); out row + item
     agg_pair = ("hbm", E * (row + 8 + 4 * H) + P * (row + 8), 2.0 * E * d)    # row + out_epos + out_dst + coefficient(s)
     table = {
-        # RGAT: + s_src per pair; backward also reads ds_src
-        "typed_linear_fwd": ("mfma", pair_fwd[1] + (P * 4 if layer == "rgat" else 0), pair_fwd[2]),
+        # RGAT: + s_src per pair and head; backward also reads ds_src
+        "typed_linear_fwd": ("mfma", pair_fwd[1] + (P * 4 * H if layer == "rgat" else 0), pair_fwd[2]),
         "typed_linear_bwd": ("mfma", pair_bwd[1] + (P * 4 if layer == "rgat" else 0) + (P * 8 if sel else 0), pair_bwd[2]),
         "self_loop_fwd": ("mfma", N * 3 * r32 + w2, 2.0 * N * d * d),         # X row + out row read and written
         "self_loop_bwd": ("mfma", N * 3 * r32 + w2, 4.0 * N * d * d),

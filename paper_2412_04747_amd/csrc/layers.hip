@@ -453,8 +453,8 @@ extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_d
         const float *Xf = static_cast<const float*>(X), *Wf = static_cast<const float*>(W);
         TypedLinearArgs a{};
         a.tiles = &g->pair_tiles_wide; a.X = Xf; a.gather = g->idx[RGNN_IDX_PAIR_SRC]; a.W = Wf; a.Y = sv.Hs;
+        a.vec = static_cast<const float*>(w_s); a.s_out = w.s_src; a.s_heads = H;   // s_src[p][h] = Hs[p] . w_s[r] per slice
         RGNN_TRY(typed_linear_fwd(K, D, a, st));
-        RGNN_TRY(head_dot_rows(g->P, D, H, sv.Hs, g->idx[RGNN_IDX_PAIR_REL], static_cast<const float*>(w_s), w.s_src, st));
         RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, static_cast<const float*>(w_t), w.wtp, st));
         RGNN_TRY(run_logit_heads(g, K, H, Xf, w.wtp, w.s_dst, st));
         RGNN_TRY(edge_logit_heads(g, H, w.s_src, w.s_dst, desc->slope, sv.att, st));

@@ -24,22 +24,6 @@ __global__ void fold_weight_heads_kernel(const float* __restrict__ W, const floa
     wv[i] = s;
 }
 
-// s[i][h] = rows[i][head h] . vec[seg[i]][head h]; one lane group per row
-template <int D>
-__global__ __launch_bounds__(256) void head_dot_rows_kernel(int64_t n, int H, const float* __restrict__ rows,
-                                                            const int32_t* __restrict__ seg,
-                                                            const float* __restrict__ vec, float* __restrict__ s) {
-    constexpr int LPR = D / 4;
-    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPR;
-    const int c4 = threadIdx.x % LPR;
-    if (i >= n) return;
-    const int lph = LPR / H;
-    const float4 x = *reinterpret_cast<const float4*>(rows + (size_t)i * D + c4 * 4);
-    const float4 v = *reinterpret_cast<const float4*>(vec + (size_t)seg[i] * D + c4 * 4);
-    const float t = group_sum_dyn(dot4(x, v), lph);
-    if (c4 % lph == 0) s[(size_t)i * H + c4 / lph] = t;
-}
-
 // s_dst[q][h] = X[run_dst[q]] . wtp[run_rel[q]][h]: the run's X row is read once, one full-width dot per head
 template <int D>
 __global__ __launch_bounds__(256) void run_logit_heads_kernel(int Q, int R, int H, const int32_t* __restrict__ run_dst,
@@ -96,16 +80,6 @@ rgnn_status_t fold_weight_heads(int R, int kd, int nd, int H, const float* W, co
     KernelTimer kt(st, "fold_weight");
     hipLaunchKernelGGL(fold_weight_heads_kernel, dim3(blocks_for((size_t)H * R * kd, 256)), dim3(256), 0, st, W, w, R, kd,
                        nd, H, wv);
-    RGNN_CHECK_LAUNCH();
-    return RGNN_OK;
-}
-
-rgnn_status_t head_dot_rows(int64_t n, int D, int H, const float* rows, const int32_t* seg, const float* vec, float* s,
-                            hipStream_t st) {
-    if (n == 0) return RGNN_OK;
-    KernelTimer kt(st, "pair_logit");
-    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(head_dot_rows_kernel<DD>, dim3(blocks_for((size_t)n * (DD / 4), 256)), dim3(256), 0, st,
-                                          n, H, rows, seg, vec, s));
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

@@ -146,8 +146,9 @@ struct TypedLinearArgs {
     float* Y;                // output rows
     int scatter_out;         // 1: row i writes Y[gather[i]], 0: Y[i]
     int accumulate;          // 1: Y += result
-    const float* vec;        // optional [segs][ND]: s_out[i] = Y_row . vec[seg]
-    float* s_out;
+    const float* vec;        // optional [segs][ND]: s_out[i][h] = Y_row . vec[seg] over the h-th of s_heads column slices
+    float* s_out;            // [rows][s_heads]
+    int s_heads = 1;         // a power of two with ND / s_heads >= 16
     const char* label;       // name in the timing report (nullptr: default)
 };
 rgnn_status_t typed_linear_fwd(int d_in, int d_out, const TypedLinearArgs& a, hipStream_t st);

@@ -56,8 +56,6 @@ rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* a
                                const void* Z, float* dl, hipStream_t st, int rows_bf16 = 0, float slope = -1.f);
 // rgat_heads.hip: pieces of multi-head RGAT
 rgnn_status_t fold_weight_heads(int R, int kd, int nd, int H, const float* W, const float* w, float* wv, hipStream_t st);
-rgnn_status_t head_dot_rows(int64_t n, int D, int H, const float* rows, const int32_t* seg, const float* vec, float* s,
-                            hipStream_t st);
 rgnn_status_t run_logit_heads(const rgnn_graph* g, int D, int H, const float* X, const float* wtp, float* s_dst,
                               hipStream_t st);
 rgnn_status_t edge_logit_heads(const rgnn_graph* g, int H, const float* s_src, const float* s_dst, float slope, float* att,

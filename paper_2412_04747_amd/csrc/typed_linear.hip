@@ -69,7 +69,8 @@ __device__ __forceinline__ int run_end(const int32_t* __restrict__ tile_seg, int
 // compiler has to wait for every outstanding memory operation (the prefetched rows and the
 // previous unit's stores) at each use.
 //   GATHER   rows are read through the gather list        SCATTER  outputs are written through it as well
-//   ACCUM    forward: Y += result                         VEC      forward: s_out = Y_row . vec[seg]
+//   ACCUM    forward: Y += result                         VEC      forward: s_out = Y_row . vec[seg], per head:
+//                                                                  s_out[row][h] over the h-th of s_heads column slices
 //   DYG      backward: dY rows are read through the list  RS       backward: rowscale / Avec / xvec in use
 //   WT       multiply by W[seg]^T (W stored [ND][KD]): the input-gradient product dY W^T
 //   ADDV     Y_row += rowscale[row] * vec[seg]  (the rank-1 part of single-head RGAT's input gradient)
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
                                                                     const float* __restrict__ W, float* __restrict__ Y,
                                                                     const float* __restrict__ vec,
                                                                     float* __restrict__ s_out,
-                                                                    const float* __restrict__ rowscale) {
+                                                                    const float* __restrict__ rowscale, int s_heads) {
     constexpr int NW = 4;                                   // wavefronts per workgroup
     constexpr int XS = (KD > ND ? KD : ND) + 4;             // row stride of the per-wave stage
     constexpr int CB = ND / 32;
@@ -118,6 +119,8 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
         __syncthreads();
         float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
         if (VEC || ADDV) wv = *reinterpret_cast<const float4*>(vec + (size_t)seg * ND + co * 4);
+        // lanes per head of an output row (a power of two, like the head count), and its log2
+        const int lls = (31 - __clz(LPRO)) - (VEC ? 31 - __clz(s_heads) : 0), lph = 1 << lls;
         // Rows past the end of the run are clamped to its last row, so every load below is
         // unconditional; what they bring in is never stored.
         v4f xr[NX];
@@ -186,10 +189,14 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
                     __builtin_nontemporal_store(yv, reinterpret_cast<v4f*>(yp));
                 }
                 if (VEC) {
+                    // the lanes of a head's column slice are added (the slices are aligned groups of lph lanes)
                     float sdot = y.x * wv.x + y.y * wv.y + y.z * wv.z + y.w * wv.w;
 #pragma unroll
-                    for (int o = LPRO / 2; o > 0; o >>= 1) sdot += __shfl_xor(sdot, o);
-                    if (ok && co == 0) s_out[row] = sdot;
+                    for (int o = LPRO / 2; o > 0; o >>= 1) {
+                        const float other = __shfl_xor(sdot, o);
+                        if (o < lph) sdot += other;
+                    }
+                    if (ok && (co & (lph - 1)) == 0) s_out[(size_t)row * s_heads + (co >> lls)] = sdot;
                 }
             }
             wave_lds_fence();             // the stage is read out before the next unit's rows overwrite it
@@ -635,7 +642,7 @@ static rgnn_status_t launch_fwd_wave(const TypedLinearArgs& a, hipStream_t st, c
     RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_fwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(256), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W, a.Y,
-                       a.vec, a.s_out, rowscale);
+                       a.vec, a.s_out, rowscale, a.s_heads);
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -644,6 +651,8 @@ template <int KD, int ND>
 static rgnn_status_t launch_fwd(const TypedLinearArgs& a, hipStream_t st) {
     // the combinations the layers use
     const bool g = a.gather != nullptr, sc = g && a.scatter_out, ac = a.accumulate != 0, v = a.vec != nullptr;
+    if (v && (a.s_heads < 1 || (a.s_heads & (a.s_heads - 1)) || a.s_heads > ND / 4))
+        RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear: %d heads for the row-vector products at width %d", a.s_heads, ND);
     if (g && !sc && !ac && v) return launch_fwd_wave<KD, ND, true, false, false, true>(a, st);
     if (g && !sc && !ac && !v) return launch_fwd_wave<KD, ND, true, false, false, false>(a, st);
     if (g && sc && !ac && !v) return launch_fwd_wave<KD, ND, true, true, false, false>(a, st);
