@@ -223,6 +223,26 @@ rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc
                             void* stream);
 
 /*
+ * rgnn_rgat_fwd for callers that cannot allocate device memory or have no workspace to hand over: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels and
+ * bit-identical results as rgnn_rgat_fwd, but the forward scratch is a buffer of RGNN_STATIC_SCRATCH_BYTES that
+ * lives inside the library (one copy per GPU, held until the process ends) instead of a `workspace` argument.
+ * The call allocates nothing.  X, W, w_s, w_t, out and `saved` are the caller's, as in rgnn_rgat_fwd; with
+ * saved == NULL (inference) the tensors that would have been saved are placed in the static buffer as well.
+ *   - The scratch a call needs is the forward size rgnn_workspace_bytes reports (plus, with saved == NULL, that
+ *     size rounded up to 256 and the saved size); a call that needs more than RGNN_STATIC_SCRATCH_BYTES fails
+ *     with RGNN_EWORKSPACE before anything is enqueued.
+ *   - Every call on a GPU uses that GPU's one buffer: calls that overlap in time on one GPU (two streams, two
+ *     threads) race; serialise them.  The buffer keeps the previous call's contents; no kernel of the forward
+ *     reads scratch it has not written in the same call, so nothing has to be cleared.
+ *   - The buffer's device address is looked up once per GPU, by rgnn_graph_create on the graph's GPU or else by
+ *     the first call of this function there; make that first call outside a stream capture.
+ */
+#define RGNN_STATIC_SCRATCH_BYTES (64u << 20)
+rgnn_status_t rgnn_rgat_fwd_static(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* W,
+                                   const void* w_s, const void* w_t, void* out, void* saved, void* stream);
+
+/*
  * HGT (caption of the figure "HGT and RGAT layer"): per node type tau(n) the
  * linears Wk, Wq, Wv, Wo [T, d, d]; per relation and head the attention and
  * message matrices Watt, Wmsg [R, H, dh, dh] (dh = d/H); optional prior mu [R, H]

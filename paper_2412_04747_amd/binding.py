@@ -22,6 +22,7 @@ RGNN_ACT_NONE, RGNN_ACT_RELU = 0, 1
 RGNN_FLAG_EDGE_PARALLEL_AGGREGATION = 1
 RGNN_MEM_HOST, RGNN_MEM_DEVICE = 0, 1
 RGNN_COO, RGNN_CSR_DST = 0, 1
+RGNN_STATIC_SCRATCH_BYTES = 64 << 20
 
 INDEX_NAMES = ["in_ptr", "in_src", "in_rel", "in_eid", "in_pair", "in_run", "in_cnt", "pair_ptr", "pair_src",
                "pair_rel", "run_ptr", "run_dst", "run_rel", "dst_run_ptr", "relrun_ptr", "relrun_idx", "out_ptr",
@@ -30,7 +31,7 @@ INDEX_NAMES = ["in_ptr", "in_src", "in_rel", "in_eid", "in_pair", "in_run", "in_
 
 EXPORTS = ["rgnn_last_error", "rgnn_graph_create", "rgnn_graph_destroy", "rgnn_graph_info", "rgnn_graph_export",
            "rgnn_workspace_bytes", "rgnn_rgcn_fwd", "rgnn_rgcn_bwd", "rgnn_rgat_fwd", "rgnn_rgat_bwd",
-           "rgnn_hgt_fwd", "rgnn_hgt_bwd", "rgnn_profile_start", "rgnn_profile_stop"]
+           "rgnn_hgt_fwd", "rgnn_hgt_bwd", "rgnn_profile_start", "rgnn_profile_stop", "rgnn_rgat_fwd_static"]
 
 
 class RgnnError(RuntimeError):
@@ -132,6 +133,11 @@ def rgnn_rgcn_bwd(g, desc, X, W, W0, out, saved, dOut, dX, dW, dW0, workspace, s
 def rgnn_rgat_fwd(g, desc, X, W, w_s, w_t, out, saved, workspace, stream=None):
     _check(lib().rgnn_rgat_fwd(g, C.byref(desc), _ptr(X), _ptr(W), _ptr(w_s), _ptr(w_t), _ptr(out), _ptr(saved),
                                _ptr(workspace), _ptr(stream)))
+
+
+def rgnn_rgat_fwd_static(g, desc, X, W, w_s, w_t, out, saved, stream=None):
+    _check(lib().rgnn_rgat_fwd_static(g, C.byref(desc), _ptr(X), _ptr(W), _ptr(w_s), _ptr(w_t), _ptr(out),
+                                      _ptr(saved), _ptr(stream)))
 
 
 def rgnn_rgat_bwd(g, desc, X, W, w_s, w_t, out, saved, dOut, dX, dW, dw_s, dw_t, workspace, stream=None):

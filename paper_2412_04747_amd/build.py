@@ -2,6 +2,7 @@
 import glob
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -16,15 +17,20 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def _compile(src: str, verbose: bool) -> str:
+    obj = os.path.join(CSRC, os.path.basename(src)[:-4] + ".o")
+    cmd = ["hipcc", *FLAGS, "-c", src, "-o", obj]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd, stderr=None if verbose else subprocess.DEVNULL)
+    return obj
+
+
 def build(verbose: bool = False) -> str:
-    objs = []
-    for src in sources():
-        obj = os.path.join(CSRC, os.path.basename(src)[:-4] + ".o")
-        cmd = ["hipcc", *FLAGS, "-c", src, "-o", obj]
-        if verbose:
-            print(" ".join(cmd))
-        subprocess.check_call(cmd, stderr=None if verbose else subprocess.DEVNULL)
-        objs.append(obj)
+    # one hipcc process per translation unit, a few at a time
+    jobs = max(1, min(8, os.cpu_count() or 1, int(os.environ.get("MAX_JOBS", "8"))))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        objs = list(pool.map(lambda s: _compile(s, verbose), sources()))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     return LIB
 

@@ -171,6 +171,10 @@ extern "C" rgnn_status_t rgnn_graph_create(rgnn_graph_t** gout, int64_t num_node
         const long double bound = (long double)std::max<int64_t>(num_nodes, 1) * std::max<int64_t>(num_nodes, 1) * num_rels;
         if (bound >= 9.2e18L) RGNN_FAIL(RGNN_EUNSUPPORTED, "N*N*R must be below 2^63 for the 64-bit sort keys");
     }
+    {   // set-up work for the entry point that allocates nothing: its scratch buffer's address on this device
+        void* scratch_ptr = nullptr;
+        RGNN_TRY(static_scratch(&scratch_ptr));
+    }
     rgnn_graph* g = new (std::nothrow) rgnn_graph();
     if (!g) RGNN_FAIL(RGNN_ENOMEM, "out of host memory");
     g->N = num_nodes; g->E = num_edges; g->R = num_rels; g->T = num_ntypes;

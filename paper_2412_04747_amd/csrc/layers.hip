@@ -429,9 +429,62 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
 
 // =========================================================================== RGAT
 
+namespace {
+
+// The library's own scratch for rgnn_rgat_fwd_static: device memory inside the code object, one copy per GPU,
+// held until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// device address it yields (per device) is what kernels and carve-outs use.
+static __device__ __align__(256) unsigned char scratch[RGNN_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+}  // namespace
+
+namespace rgnn {
+// Address of the static scratch array on the current device; looked up once per device and kept.
+rgnn_status_t static_scratch(void** p) {
+    int dev = 0;
+    RGNN_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) RGNN_FAIL(RGNN_EUNSUPPORTED, "device ordinal %d is beyond the %d the library tracks", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        RGNN_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) RGNN_FAIL(RGNN_EHIP, "hipGetSymbolAddress returned a null address for the static scratch");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *p = g_scratch_ptr[dev];
+    return RGNN_OK;
+}
+}  // namespace rgnn
+
+static rgnn_status_t rgat_fwd_impl(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* W,
+                                   const void* w_s, const void* w_t, void* out, void* saved, void* workspace, void* stream);
+
 extern "C" rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
                                        const void* W, const void* w_s, const void* w_t, void* out, void* saved,
                                        void* workspace, void* stream) {
+    return rgat_fwd_impl(g, desc, X, W, w_s, w_t, out, saved, workspace, stream);
+}
+
+extern "C" rgnn_status_t rgnn_rgat_fwd_static(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
+                                              const void* W, const void* w_s, const void* w_t, void* out, void* saved,
+                                              void* stream) {
+    size_t need = 0, sv = 0;
+    RGNN_TRY(rgnn_workspace_bytes(g, RGNN_LAYER_RGAT, desc, &need, nullptr, &sv));
+    if (!saved) need = align_up(need) + sv;      // inference: the would-be saved tensors are scratch too
+    if (need > (size_t)RGNN_STATIC_SCRATCH_BYTES)
+        RGNN_FAIL(RGNN_EWORKSPACE, "rgnn_rgat_fwd_static: this call needs %zu bytes of scratch, the static buffer holds %zu",
+                  need, (size_t)RGNN_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    RGNN_TRY(static_scratch(&ws));
+    return rgat_fwd_impl(g, desc, X, W, w_s, w_t, out, saved, ws, stream);
+}
+
+static rgnn_status_t rgat_fwd_impl(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* W,
+                                   const void* w_s, const void* w_t, void* out, void* saved, void* workspace, void* stream) {
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGAT));
     if (missing(g, X) || !W || !w_s || !w_t || missing(g, out)) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");

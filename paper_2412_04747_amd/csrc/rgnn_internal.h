@@ -137,6 +137,9 @@ const char* wgrad_label(const char* label);
 // Raises a kernel's dynamic LDS limit once per (kernel, device) instead of on every launch.
 rgnn_status_t allow_dynamic_lds(const void* kernel, size_t bytes);
 
+// Device address of the library's static scratch buffer on the current device (layers.hip); resolved once per device.
+rgnn_status_t static_scratch(void** p);
+
 // ---- kernel launchers (typed_linear.hip) --------------------------------
 struct TypedLinearArgs {
     const TileList* tiles;
