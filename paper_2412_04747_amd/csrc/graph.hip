@@ -38,6 +38,23 @@ rgnn_status_t allow_dynamic_lds(const void* kernel, size_t bytes) {
     return RGNN_OK;
 }
 
+rgnn_status_t resident_blocks_per_cu(const void* kernel, int threads, size_t lds, int* out) {
+    static std::mutex mu;
+    static std::map<std::pair<const void*, std::pair<int, size_t>>, int> done;   // (kernel, (device, lds)) -> blocks
+    int dev = 0;
+    RGNN_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(mu);
+    auto key = std::make_pair(kernel, std::make_pair(dev, lds));
+    auto it = done.find(key);
+    if (it == done.end()) {
+        int n = 0;
+        RGNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, lds));
+        it = done.emplace(key, std::max(n, 1)).first;
+    }
+    *out = it->second;
+    return RGNN_OK;
+}
+
 struct Uploader {
     rgnn_graph* g;
     rgnn_status_t st = RGNN_OK;
@@ -130,6 +147,7 @@ static rgnn_status_t build(rgnn_graph* g, int format, const int32_t* a, const in
     int dev = 0, cus = 0;
     RGNN_HIP(hipGetDevice(&dev));
     RGNN_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    g->num_cus = std::max(cus, 1);
     const int wide = kWideChunksPerCU * std::max(cus, 1);
     build_tiles(U, g->pair_tiles_wide, pair_ptr, kTileRows, wide);
     build_tiles(U, g->node_tiles_wide, ntype_ptr, kTileRows, wide);

@@ -90,8 +90,10 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
 }
 
 // ---- RGAT buffers -----------------------------------------------------------------------
-struct RgatSaved { float* Hs; float* att; };
-struct RgatFwdWs { float* wtp; float* s_src; float* s_dst; float* part_m; float* part_s; float* partial; };
+// Single head: Hs, the destination halves of the logits per run and (max, sum) of every destination's softmax.
+// Several heads: Hs and the attention weights per (edge, head).
+struct RgatSaved { float* Hs; float* att; float* s_dst; float* ms; };
+struct RgatFwdWs { float* wtp; float* s_src; float* s_dst; float* att; float* part_m; float* part_s; float* part_ms; float* partial; };
 struct RgatBwdWs {
     float* wtp; float* wsp; float* adz; float* ds_dst; float* ds_src; float* G; float* dXp; float* A; float* U;
     float* tl_part; float* partial;
@@ -99,22 +101,40 @@ struct RgatBwdWs {
 // Single-head RGAT at widths up to 64: the gradient rows of single-edge pairs are not written per pair;
 // the typed-linear backward reads att_e * dOut[dst_e] through its row selector.
 inline bool rgat_row_select(const rgnn_layer_desc_t* d) { return d->heads == 1 && d->d_out <= 64; }
+inline bool rgat_edge_parallel(const rgnn_layer_desc_t* d) { return (d->flags & RGNN_FLAG_EDGE_PARALLEL_AGGREGATION) != 0; }
 
 size_t carve_rgat_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatSaved* s) {
     Carver c(base);
     s->Hs = c.take<float>((size_t)g->P * d->d_out);
-    s->att = c.take<float>((size_t)g->E * d->heads);
+    s->att = s->s_dst = s->ms = nullptr;
+    if (d->heads > 1) {
+        s->att = c.take<float>((size_t)g->E * d->heads);
+    } else {
+        s->s_dst = c.take<float>((size_t)g->Q);
+        s->ms = c.take<float>(2 * (size_t)g->N);
+    }
     return c.off;
 }
 size_t carve_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatFwdWs* w) {
     Carver c(base);
-    const size_t H = d->heads;
+    const size_t H = d->heads, parts = (size_t)g->dst_items.num_partials;
     w->wtp = c.take<float>(H * g->R * d->d_in);
-    w->s_src = c.take<float>((size_t)g->P * H);
-    w->s_dst = c.take<float>((size_t)g->Q * H);
-    w->part_m = c.take<float>((size_t)g->dst_items.num_partials * H);
-    w->part_s = c.take<float>((size_t)g->dst_items.num_partials * H);
-    w->partial = c.take<float>((size_t)g->dst_items.num_partials * d->d_out);
+    w->s_src = w->s_dst = w->att = w->part_m = w->part_s = w->part_ms = nullptr;
+    if (H > 1) {
+        w->s_src = c.take<float>((size_t)g->P * H);
+        w->s_dst = c.take<float>((size_t)g->Q * H);
+        w->part_m = c.take<float>(parts * H);
+        w->part_s = c.take<float>(parts * H);
+    } else if (rgat_edge_parallel(d)) {
+        // the comparison schedule: per-pair source logits, a softmax pass of its own, attention weights per edge
+        w->s_src = c.take<float>((size_t)g->P);
+        w->att = c.take<float>((size_t)g->E);
+        w->part_m = c.take<float>(parts);
+        w->part_s = c.take<float>(parts);
+    } else {
+        w->part_ms = c.take<float>(2 * parts);
+    }
+    w->partial = c.take<float>(parts * d->d_out);
     return c.off;
 }
 size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatBwdWs* w) {
@@ -515,23 +535,25 @@ static rgnn_status_t rgat_fwd_impl(const rgnn_graph_t* g, const rgnn_layer_desc_
         return gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, H, 1, sv.Hs, out, w.partial, st, 0,
                           "aggregate_fwd", "aggregate_fwd.combine", H);
     }
-    // 1. compact messages and the source half of the logit:
-    //    Hs[p] = X[pair_src[p]] W[r];  s_src[p] = Hs[p] . w_s[r]
+    const float *Xf = static_cast<const float*>(X), *Wf = static_cast<const float*>(W);
+    const bool edge_par = rgat_edge_parallel(desc);
+    // 1. compact messages: Hs[p] = X[pair_src[p]] W[r]
+    //    (the comparison schedule also takes the source half of the logit per pair, s_src[p] = Hs[p] . w_s[r])
     TypedLinearArgs a{};
-    a.tiles = &g->pair_tiles_wide; a.X = static_cast<const float*>(X); a.gather = g->idx[RGNN_IDX_PAIR_SRC];
-    a.W = static_cast<const float*>(W); a.Y = sv.Hs; a.vec = static_cast<const float*>(w_s); a.s_out = w.s_src;
+    a.tiles = &g->pair_tiles_wide; a.X = Xf; a.gather = g->idx[RGNN_IDX_PAIR_SRC]; a.W = Wf; a.Y = sv.Hs;
+    if (edge_par) { a.vec = static_cast<const float*>(w_s); a.s_out = w.s_src; }
     RGNN_TRY(typed_linear_fwd(K, D, a, st));
     // 2. destination half, once per (dst, rel) run, reordered: s_dst[q] = X[dst] . (W[r] w_t[r])
-    RGNN_TRY(fold_weight(g->R, K, D, static_cast<const float*>(W), static_cast<const float*>(w_t), w.wtp, st));
-    RGNN_TRY(run_logit(g, K, static_cast<const float*>(X), w.wtp, w.s_dst, st));
-    // 3. edge softmax over each destination's incoming edges
-    RGNN_TRY(edge_softmax(g, w.s_src, w.s_dst, desc->slope, sv.att, w.part_m, w.part_s, st));
-    // 4. out[v] = sum_e att_e Hs[pair_e]
-    if (desc->flags & RGNN_FLAG_EDGE_PARALLEL_AGGREGATION)
-        return aggregate_edge_parallel(g, D, sv.att, sv.Hs, static_cast<float*>(out), st);
-    RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, 1, 1, sv.Hs,
-                        static_cast<float*>(out), w.partial, st, 0, "aggregate_fwd", "aggregate_fwd.combine"));
-    return RGNN_OK;
+    RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_t), w.wtp, st));
+    RGNN_TRY(run_logit(g, K, Xf, w.wtp, sv.s_dst, st));
+    if (edge_par) {
+        // 3'. edge softmax in a pass of its own, then edge-by-edge aggregation with atomic adds
+        RGNN_TRY(edge_softmax(g, w.s_src, sv.s_dst, desc->slope, w.att, w.part_m, w.part_s, st, sv.ms));
+        return aggregate_edge_parallel(g, D, w.att, sv.Hs, static_cast<float*>(out), st);
+    }
+    // 3. one walk per destination: logit from the gathered row, running-maximum softmax, weighted sum
+    return rgat_aggregate_fwd(g, D, sv.Hs, static_cast<const float*>(w_s), sv.s_dst, desc->slope, static_cast<float*>(out),
+                              sv.ms, w.partial, w.part_ms, st);
 }
 
 extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
@@ -587,14 +609,14 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, wt, w.wtp, st));
         return node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, nullptr, dX, st, 0, 0, H);
     }
-    // 1. per CSR edge: (att_e, dz_e); for single-edge pairs also ds_src[p] and G[p] = att_e dOut[dst_e] (or, with
+    // 1. per CSR edge: (att_e, dz_e), att_e recomputed from the gathered row and the saved (m, s); for single-edge pairs also ds_src[p] and G[p] = att_e dOut[dst_e] (or, with
     //    the row selector, only att_e: step 4 then reads the row from dOut).  With the selector ds_src[p] and that
     //    att_e are stored side by side (one 8-byte store here, one 8-byte load per row in step 4): w.ds_src then
     //    holds P pairs of floats and ds_src[p] is element 2 p.
     const bool sel = rgat_row_select(desc);
     const int dss = sel ? 2 : 1;
-    RGNN_TRY(edge_dot_bwd(g, D, sv.att, sv.Hs, dO, static_cast<const float*>(out), desc->slope, w.adz, w.G, w.ds_src,
-                          sel ? w.ds_src : nullptr, st));
+    RGNN_TRY(rgat_edge_dot_bwd(g, D, sv.Hs, static_cast<const float*>(w_s), sv.s_dst, sv.ms, dO, static_cast<const float*>(out),
+                               desc->slope, w.adz, w.G, w.ds_src, sel ? w.ds_src : nullptr, st));
     // 2. ds_dst[q] = sum over the run's edges of dz
     RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], g->long_runs, nullptr, w.adz, 2, 1, w.ds_dst, st, "ds_dst_sum"));
     // 3. for the pairs with several edges (step 1 wrote the others): G[p] = sum_{e in out(p)} att_e dOut[dst_e] and, in

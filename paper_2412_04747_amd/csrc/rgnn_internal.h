@@ -99,6 +99,7 @@ struct LongList {
 struct rgnn_graph {
     int64_t N = 0, E = 0, P = 0, Q = 0;
     int32_t R = 0, T = 0;
+    int num_cus = 0;                       // compute units of the device the graph lives on
     int64_t max_in_degree = 0, max_pair_out_degree = 0, num_single_pairs = 0;
     size_t index_bytes = 0;
     int32_t* idx[RGNN_IDX_COUNT] = {};     // device arrays, see RGNN_IDX_*

@@ -11,8 +11,22 @@ rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float*
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
                                  int stride, int off, float* out, hipStream_t st, const char* label, int min_len = 0,
                                  int heads = 1, bool long_only = false, int ostride = 1);
+// ms (optional, [N] pairs of floats): (max, sum of exp) of the logits of every destination with edges
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
-                           float* part_m, float* part_s, hipStream_t st);
+                           float* part_m, float* part_s, hipStream_t st, float* ms = nullptr);
+// rgat_fused.hip: single-head RGAT with the edge softmax fused into the traversal.
+//   forward: out[v] = sum_e att_e Hs[pair_e] with att = softmax over v's edges of leakyrelu(Hs[pair_e] . w_s[r_e] + s_dst[run_e]);
+//   ms[v] = (max logit, sum of exp(logit - max)) as pairs of floats; partial / part_ms: scratch rows and (m, s) pairs of the
+//   pieces of cut destinations
+rgnn_status_t rgat_aggregate_fwd(const rgnn_graph* g, int D, const float* Hs, const float* w_s, const float* s_dst,
+                                 float slope, float* out, float* ms, float* partial, float* part_ms, hipStream_t st);
+//   backward: adz[e] = (att_e, dz_e) with att_e recomputed from the gathered row and ms; the only edge of a single-edge
+//   pair also writes dsy[p] = (dz_e, att_e), or without dsy: ds_src[p] = dz_e and G[p] = att_e dOut[v]
+rgnn_status_t rgat_edge_dot_bwd(const rgnn_graph* g, int D, const float* Hs, const float* w_s, const float* s_dst,
+                                const float* ms, const float* dOut, const float* out, float slope, float* adz, float* G,
+                                float* ds_src, float* dsy, hipStream_t st);
+// workgroups of `threads` threads with `lds` bytes of dynamic LDS that stay resident per compute unit (cached per kernel)
+rgnn_status_t resident_blocks_per_cu(const void* kernel, int threads, size_t lds, int* out);
 // Optional rank-1 term of a gather-sum: out[i] += coef[i * stride + head] * vec[seg[i]] (fp32 vec rows of the output width)
 struct Rank1 { const float* coef; int stride; const int32_t* seg; const float* vec; };
 rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int32_t* rowidx, int row_by_k,

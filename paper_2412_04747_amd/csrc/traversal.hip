@@ -138,6 +138,7 @@ struct SoftmaxArgs {
     float* att;
     float* part_m;
     float* part_s;
+    float2* ms;      // optional [N]: (max, sum of exp) of every destination with edges
 };
 
 __device__ __forceinline__ float signed_att(float l, float m, float inv) {
@@ -185,6 +186,7 @@ __global__ __launch_bounds__(256) void edge_softmax_kernel(SoftmaxArgs a, int N,
 #pragma unroll
     for (int k = 0; k < kSerialMax; ++k)
         if (k < len) a.att[b + k] = signed_att(l[k], m, inv);
+    if (a.ms) a.ms[v] = make_float2(m, s);
 }
 
 // One wavefront per item that is longer than kSerialMax or is a piece of a cut node.  An item has at
@@ -219,6 +221,7 @@ __global__ __launch_bounds__(256) void edge_softmax_long_kernel(SoftmaxArgs a, i
 #pragma unroll
         for (int u = 0; u < PER; ++u)
             if (bb + lane + 64 * u < ee) a.att[bb + lane + 64 * u] = signed_att(l[u], m, inv);
+        if (a.ms && lane == 0) a.ms[a.it.row[i]] = make_float2(m, s);
     } else {
         // a piece of a cut node: the finish kernel normalises, from the logits
 #pragma unroll
@@ -237,7 +240,7 @@ __global__ void edge_softmax_finish_kernel(int num_partials, const int32_t* __re
                                            const int32_t* __restrict__ part_split,
                                            const int32_t* __restrict__ split_ptr, Items it,
                                            const float* __restrict__ part_m, const float* __restrict__ part_s,
-                                           float* __restrict__ att) {
+                                           float* __restrict__ att, float2* __restrict__ ms) {
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (t >= num_partials) return;
     const int sp = part_split[t];
@@ -251,6 +254,7 @@ __global__ void edge_softmax_finish_kernel(int num_partials, const int32_t* __re
     const float inv = 1.f / s;
     const int item = part_item[t];
     for (int j = it.beg[item] + lane; j < it.end[item]; j += 64) att[j] = signed_att(att[j], m, inv);
+    if (ms && t == p0 && lane == 0) ms[it.row[item]] = make_float2(m, s);     // the node's first piece records its totals
 }
 
 // ------------------------------------------------------------------ weighted gather-sum
@@ -940,10 +944,11 @@ rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng,
 }
 
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
-                           float* part_m, float* part_s, hipStream_t st) {
+                           float* part_m, float* part_s, hipStream_t st, float* ms) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0) return RGNN_OK;
-    SoftmaxArgs a{dev_items(L), g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN], s_src, s_dst, slope, att, part_m, part_s};
+    SoftmaxArgs a{dev_items(L), g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN], s_src, s_dst, slope, att, part_m, part_s,
+                  reinterpret_cast<float2*>(ms)};
     {
         KernelTimer kt(st, "edge_softmax");
         hipLaunchKernelGGL(edge_softmax_kernel, dim3(blocks_for((size_t)g->N, 256)), dim3(256), 0, st, a, (int)g->N,
@@ -958,7 +963,8 @@ rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float*
     if (L.num_partials > 0) {
         KernelTimer kt(st, "edge_softmax.finish");
         hipLaunchKernelGGL(edge_softmax_finish_kernel, dim3(blocks_for((size_t)L.num_partials * 64, 256)), dim3(256), 0,
-                           st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), part_m, part_s, att);
+                           st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), part_m, part_s, att,
+                           reinterpret_cast<float2*>(ms));
         RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;

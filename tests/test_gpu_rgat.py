@@ -23,14 +23,22 @@ def _run(N, R, src, dst, rel, p, d, tag, slope=0.2, check_saved=True):
     check(L.out, want, TOL_F32, "out")
     if check_saved and len(src):
         ix = graph_index.build(N, R, src, dst, rel)
-        hs, att = L.saved_views()
-        att = att.cpu().numpy()
-        a_want = alpha[ix["in_eid"]]
-        check(np.abs(att), a_want, TOL_F32, "att")
-        # the sign bit carries z_e <= 0 wherever z_e is not within rounding of 0
-        zz = z[ix["in_eid"]]
-        clear = np.abs(zz) > 1e-4
-        assert np.array_equal(np.signbit(att)[clear], (zz <= 0)[clear])
+        hs, s_dst, ms = (t.cpu().numpy() for t in L.saved_views())
+        # what the forward keeps: the destination half of the logit per run, and per destination the
+        # maximum m of the leaky-ReLU logits and s = sum exp(l - m); the backward rebuilds att from them
+        X64, W64 = p["X"].astype(np.float64), p["W"].astype(np.float64)
+        ht = np.einsum("qi,qij->qj", X64[ix["run_dst"]], W64[ix["run_rel"]])
+        check(s_dst, (ht * p["w_t"].astype(np.float64)[ix["run_rel"]]).sum(1), TOL_F32, "s_dst")
+        zz = z[ix["in_eid"]]                                   # logits in CSR order
+        l = np.where(zz > 0, zz, slope * zz)
+        deg = np.diff(ix["in_ptr"])
+        has = deg > 0
+        m_want = np.maximum.reduceat(l, ix["in_ptr"][:-1][has])
+        s_want = np.add.reduceat(np.exp(l - np.repeat(m_want, deg[has])), ix["in_ptr"][:-1][has])
+        assert np.abs(ms[has, 0] - m_want).max() <= TOL_F32 * max(np.abs(l).max(), 1.0)
+        check(ms[has, 1], s_want, TOL_F32, "softmax sum")
+        v_of = np.repeat(np.arange(N), deg)
+        check(np.exp(l - ms[v_of, 0].astype(np.float64)) / ms[v_of, 1], alpha[ix["in_eid"]], TOL_F32, "att from (m, s)")
         pair_hs = np.einsum("pi,pij->pj", p["X"].astype(np.float64)[ix["pair_src"]], p["W"].astype(np.float64)[ix["pair_rel"]])
         check(hs, pair_hs, TOL_F32, "Hs")
     L.bwd()
