@@ -6,8 +6,9 @@ backward are the C-ABI calls of `binding`; PyTorch only owns the memory, the str
 tape.  Everything is fp32 (the training protocol of the thesis' evaluation section: full-graph
 training of a two-layer model with a negative-log-likelihood loss).
 
-The workspace of a (graph, layer kind, width) combination is allocated once and reused by
-every call, so calls on one graph must not overlap on different streams.
+The workspace of a (layer kind, width, options) combination is allocated once per graph, kept on the
+`Graph` object and dropped by `Graph.close()`; every call of that combination on the graph reuses it,
+so such calls must not overlap on different streams.
 """
 import math
 
@@ -16,22 +17,23 @@ import torch
 from . import binding as B
 from .harness import Graph, _buf, _stream
 
-_workspaces = {}
-
 
 def _bufs(graph, layer, desc, key):
-    """(workspace, saved size) for a layer configuration on a graph; the workspace is cached."""
-    k = (id(graph), layer) + key
-    if k not in _workspaces:
+    """(workspace, saved size) for a layer configuration on a graph.  The workspace lives in
+    `graph.workspaces` (sized by rgnn_workspace_bytes for this very graph), so it can neither outlive
+    the graph nor be handed to another one."""
+    if graph.handle is None:
+        raise RuntimeError("the graph has been closed")
+    k = (layer,) + key
+    if k not in graph.workspaces:
         f, b, s = B.rgnn_workspace_bytes(graph.handle, layer, desc)
-        _workspaces[k] = (_buf(max(f, b)), s)
-    return _workspaces[k]
+        graph.workspaces[k] = (_buf(max(f, b)), s)
+    return graph.workspaces[k]
 
 
 def release(graph):
-    """Drop the cached workspaces of a graph (call before closing it)."""
-    for k in [k for k in _workspaces if k[0] == id(graph)]:
-        del _workspaces[k]
+    """Drop the cached workspaces of a graph (Graph.close() does the same)."""
+    graph.workspaces.clear()
 
 
 def _f32(t):

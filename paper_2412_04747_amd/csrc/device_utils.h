@@ -15,12 +15,60 @@ struct Items {
 };
 inline Items dev_items(const ItemList& L) { return Items{L.num_items, L.beg, L.end, L.row, L.slot}; }
 
-// sum over an aligned group of W lanes (W a power of two, at most 64)
+// Cross-lane moves inside a row of 16 lanes on the VALU (DPP), no LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm:[1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm:[2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;    // lane i <-> 7 - i within each 8 lanes
+constexpr int kDppMirror = 0x140;        // lane i <-> 15 - i within each 16 lanes
+constexpr int kDppRowBcast0 = 0x150;     // + n: every lane of a row reads the row's lane n
+
+// sum over an aligned group of W lanes (W a power of two, at most 64); every lane of the group gets the
+// same bits.  Up to 16 lanes the exchange partners are chosen so that each step is one DPP add: after
+// the two quad steps a quad holds one value, so mirroring a half row (then the row) pairs different
+// quads (halves) just as a butterfly would.
 template <int W>
 __device__ __forceinline__ float group_sum(float v) {
-#pragma unroll
-    for (int o = W / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if (W >= 2) v += dpp_move<kDppQuadSwap1>(v);
+    if (W >= 4) v += dpp_move<kDppQuadSwap2>(v);
+    if (W >= 8) v += dpp_move<kDppHalfMirror>(v);
+    if (W >= 16) v += dpp_move<kDppMirror>(v);
+    if (W >= 32) v += __shfl_xor(v, 16);
+    if (W >= 64) v += __shfl_xor(v, 32);
     return v;
+}
+// value held by lane `lane` of the caller's aligned group of W lanes; with W == 16 and a `lane` the compiler
+// can fold to a constant this is one DPP move
+template <int W, typename Tv>
+__device__ __forceinline__ Tv group_lane(Tv v, int lane) {
+    if constexpr (W == 16) {
+        switch (lane) {
+            case 0: return dpp_move<kDppRowBcast0 + 0>(v);
+            case 1: return dpp_move<kDppRowBcast0 + 1>(v);
+            case 2: return dpp_move<kDppRowBcast0 + 2>(v);
+            case 3: return dpp_move<kDppRowBcast0 + 3>(v);
+            case 4: return dpp_move<kDppRowBcast0 + 4>(v);
+            case 5: return dpp_move<kDppRowBcast0 + 5>(v);
+            case 6: return dpp_move<kDppRowBcast0 + 6>(v);
+            case 7: return dpp_move<kDppRowBcast0 + 7>(v);
+            case 8: return dpp_move<kDppRowBcast0 + 8>(v);
+            case 9: return dpp_move<kDppRowBcast0 + 9>(v);
+            case 10: return dpp_move<kDppRowBcast0 + 10>(v);
+            case 11: return dpp_move<kDppRowBcast0 + 11>(v);
+            case 12: return dpp_move<kDppRowBcast0 + 12>(v);
+            case 13: return dpp_move<kDppRowBcast0 + 13>(v);
+            case 14: return dpp_move<kDppRowBcast0 + 14>(v);
+            default: return dpp_move<kDppRowBcast0 + 15>(v);
+        }
+    }
+    return __shfl(v, lane, W);
 }
 __device__ __forceinline__ float group_sum_dyn(float v, int w) {
     for (int o = w / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);

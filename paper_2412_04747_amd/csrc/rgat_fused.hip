@@ -92,20 +92,21 @@ __device__ __forceinline__ void fwd_general(const FusedArgs& a, const float* ws_
                 nrn = a.in_run[jj];
             }
             const int cend = min(LPR, e - jc);
-            for (int k = 0; k < cend; k += 4) {
-                float4 h[4], w[4];
-                float sd[4];
+#pragma unroll
+            for (int k = 0; k < LPR; k += 4) {
+                if (k >= cend) break;
+                float4 h[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int pr = __shfl(cpr, k + u, LPR), rl = __shfl(crl, k + u, LPR);
-                    sd[u] = __shfl(csd, k + u, LPR);
+                    const int pr = group_lane<LPR>(cpr, k + u);
                     h[u] = load_row_nt(a.Hs + (size_t)pr * D + c * 4);
-                    w[u] = ws_row<D, LDSW>(a, ws_lds, rl, c);
                 }
+                __builtin_amdgcn_sched_barrier(0);      // the w_s rows are read when the message rows arrive, not held meanwhile
                 float l[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const float z = group_sum<LPR>(dot4(h[u], w[u])) + sd[u];
+                    const float4 w = ws_row<D, LDSW>(a, ws_lds, group_lane<LPR>(crl, k + u), c);
+                    const float z = group_sum<LPR>(dot4(h[u], w)) + group_lane<LPR>(csd, k + u);
                     l[u] = k + u < cend ? leaky(z, a.slope) : -INFINITY;
                 }
                 const float mn = fmaxf(fmaxf(m, fmaxf(l[0], l[1])), fmaxf(l[2], l[3]));
@@ -161,22 +162,23 @@ __device__ __forceinline__ void fwd_short(const FusedArgs& a, const float* ws_ld
             rl[q][u] = a.in_rel[jj];
             rn[q][u] = a.in_run[jj];
         }
-    float4 h[2][kShortLen], w[2][kShortLen];
+    float4 h[2][kShortLen];
     float sd[2][kShortLen];
 #pragma unroll
     for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int u = 0; u < kShortLen; ++u) {
             h[q][u] = load_row_nt(a.Hs + (size_t)pr[q][u] * D + c * 4);
-            w[q][u] = ws_row<D, LDSW>(a, ws_lds, rl[q][u], c);
             sd[q][u] = a.s_dst[rn[q][u]];
         }
+    __builtin_amdgcn_sched_barrier(0);      // the w_s rows are read when the message rows arrive, not held meanwhile
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         float l[kShortLen], m = -INFINITY;
 #pragma unroll
         for (int u = 0; u < kShortLen; ++u) {
-            const float z = group_sum<LPR>(dot4(h[q][u], w[q][u])) + sd[q][u];
+            const float4 w = ws_row<D, LDSW>(a, ws_lds, rl[q][u], c);
+            const float z = group_sum<LPR>(dot4(h[q][u], w)) + sd[q][u];
             l[u] = b[q] + u < e[q] ? leaky(z, a.slope) : -INFINITY;
             m = fmaxf(m, l[u]);
         }
@@ -214,17 +216,18 @@ __device__ __forceinline__ void fwd_single(const FusedArgs& a, const float* ws_l
         rl[u] = a.in_rel[j[u]];
         rn[u] = a.in_run[j[u]];
     }
-    float4 h[4], w[4];
+    float4 h[4];
     float sd[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         h[u] = load_row_nt(a.Hs + (size_t)pr[u] * D + c * 4);
-        w[u] = ws_row<D, LDSW>(a, ws_lds, rl[u], c);
         sd[u] = a.s_dst[rn[u]];
     }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        const float z = group_sum<LPR>(dot4(h[u], w[u])) + sd[u];
+        const float4 w = ws_row<D, LDSW>(a, ws_lds, rl[u], c);
+        const float z = group_sum<LPR>(dot4(h[u], w)) + sd[u];
         if (i0 + u < a.single_n) {
             *reinterpret_cast<float4*>(a.out + (size_t)orow[u] * D + c * 4) = h[u];
             if (c == 0) a.ms[orow[u]] = make_float2(leaky(z, a.slope), 1.f);
@@ -339,22 +342,22 @@ __device__ __forceinline__ void bwd_item(const FusedArgs& a, const float* ws_lds
             nrn = a.in_run[jj];
         }
         const int cend = min(LPR, e - jc);
-        for (int k = 0; k < cend; k += 4) {
-            float4 h[4], w[4];
-            float sd[4];
+#pragma unroll
+        for (int k = 0; k < LPR; k += 4) {
+            if (k >= cend) break;
+            float4 h[4];
             int pr[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                pr[u] = __shfl(cpr, k + u, LPR);
-                const int rl = __shfl(crl, k + u, LPR);
-                sd[u] = __shfl(csd, k + u, LPR);
+                pr[u] = group_lane<LPR>(cpr, k + u);
                 h[u] = load_row_nt(a.Hs + (size_t)(pr[u] & 0x7FFFFFFF) * D + c * 4);
-                w[u] = ws_row<D, LDSW>(a, ws_lds, rl, c);
             }
+            __builtin_amdgcn_sched_barrier(0);      // the w_s rows are read when the message rows arrive, not held meanwhile
             float2 mine = make_float2(0.f, 0.f);      // (att, dz) of edge jc + k + c: lanes 0..3 of the group store one each
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const float z = group_sum<LPR>(dot4(h[u], w[u])) + sd[u];
+                const float4 w = ws_row<D, LDSW>(a, ws_lds, group_lane<LPR>(crl, k + u), c);
+                const float z = group_sum<LPR>(dot4(h[u], w)) + group_lane<LPR>(csd, k + u);
                 const float g = group_sum<LPR>(dot4(go, h[u]));
                 const float al = __expf(leaky(z, a.slope) - m) * inv;
                 const float dz = al * (g - gbar) * (z > 0.f ? 1.f : a.slope);

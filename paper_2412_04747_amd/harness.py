@@ -33,11 +33,14 @@ class Graph:
     def __init__(self, N, R, src, dst, rel, ntype=None, T=1, rel_src_ntype=None, rel_dst_ntype=None):
         i32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.int32)
         torch.cuda.init()
+        self.workspaces = {}
+        self.handle = None
         self.N, self.R, self.T, self.E = int(N), int(R), int(T), len(src)
         self.handle = B.rgnn_graph_create(N, T, R, self.E, B.RGNN_COO, i32(src), i32(dst), i32(rel), i32(ntype),
                                           i32(rel_src_ntype), i32(rel_dst_ntype), B.RGNN_MEM_HOST)
         self.info = B.rgnn_graph_info(self.handle)
         self.P, self.Q = int(self.info.num_pairs), int(self.info.num_runs)
+        self.workspaces = {}       # scratch buffers the autograd front end keeps per layer configuration
 
     def export(self, name):
         which = B.INDEX_NAMES.index(name)
@@ -49,6 +52,7 @@ class Graph:
         return B.rgnn_graph_export(self.handle, which, length)
 
     def close(self):
+        self.workspaces.clear()
         if self.handle is not None:
             B.rgnn_graph_destroy(self.handle)
             self.handle = None

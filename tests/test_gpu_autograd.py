@@ -59,11 +59,11 @@ def test_two_layer_rgat_nll():
     g1 = O.rgat_bwd(N, src, dst, rel, q1["X"], q1["W"], q1["w_s"], q1["w_t"], g2["dX"] * (a1 > 0))
 
     assert abs(loss.item() - want_loss) <= 1e-4 * abs(want_loss)
-    check(X.grad, g1["dX"], 2 * TOL_F32, "dX")
+    check(X.grad, g1["dX"], TOL_F32, "dX")
     for tns, k in zip(P1, ("dW", "dw_s", "dw_t")):
-        check(tns.grad, g1[k], 2 * TOL_F32, "layer1 " + k)
+        check(tns.grad, g1[k], TOL_F32, "layer1 " + k)
     for tns, k in zip(P2, ("dW", "dw_s", "dw_t")):
-        check(tns.grad, g2[k], 2 * TOL_F32, "layer2 " + k)
+        check(tns.grad, g2[k], TOL_F32, "layer2 " + k)
     A.release(g)
     g.close()
 
@@ -109,13 +109,13 @@ def test_rgcn_then_hgt_modules_train():
     a1 = O.rgcn_fwd(N, src, dst, rel, f(X), f(l1.W), f(l1.W0), "in_degree_per_rel", "relu")
     hp = [f(q) for q in (l2.Wk, l2.Wq, l2.Wv, l2.Wo, l2.Watt, l2.Wmsg, l2.mu)]
     a2 = O.hgt_fwd(N, src, dst, rel, ntype, a1, *hp)
-    check(out, a2, 2 * TOL_F32, "out")
+    check(out, a2, TOL_F32, "out")
     g2 = O.hgt_bwd(N, src, dst, rel, ntype, a1, *hp, f(dOut))
     g1 = O.rgcn_bwd(N, src, dst, rel, f(X), f(l1.W), f(l1.W0), g2["dX"], "in_degree_per_rel", "relu", out=a1)
     for q, k in zip((l2.Wk, l2.Wq, l2.Wv, l2.Wo, l2.Watt, l2.Wmsg, l2.mu), ("dWk", "dWq", "dWv", "dWo", "dWatt", "dWmsg", "dmu")):
-        check(q.grad, g2[k], 2 * TOL_F32, "hgt " + k)
-    check(l1.W.grad, g1["dW"], 2 * TOL_F32, "rgcn dW")
-    check(l1.W0.grad, g1["dW0"], 2 * TOL_F32, "rgcn dW0")
+        check(q.grad, g2[k], TOL_F32, "hgt " + k)
+    check(l1.W.grad, g1["dW"], TOL_F32, "rgcn dW")
+    check(l1.W0.grad, g1["dW0"], TOL_F32, "rgcn dW0")
     A.release(g)
     g.close()
 
@@ -141,3 +141,44 @@ def test_multi_head_function_matches_the_oracle():
         check(tns.grad, wg[k], TOL_F32, k)
     A.release(g)
     g.close()
+
+
+def test_workspaces_live_and_die_with_their_graph():
+    """The front end keeps its scratch buffers on the Graph object: a graph that is dropped takes them along,
+    and a later, larger graph (even one that lands on the same Python id) gets buffers of its own size."""
+    import gc
+    import torch
+    from paper_2412_04747_amd import autograd as A, binding as B
+    d = 64
+
+    def run(N, R, E, seed):
+        rng, src, dst, rel, _ = synth.tiny(seed, N=N, R=R, E=E)
+        p = synth.rgat_params(rng, N, R, d, d)
+        g = A.Graph(N, R, src, dst, rel)
+        t = lambda a: torch.tensor(a, dtype=torch.float32, device="cuda", requires_grad=True)
+        out = A.rgat(g, t(p["X"]), t(p["W"]), t(p["w_s"]), t(p["w_t"]))
+        out.sum().backward()
+        torch.cuda.synchronize()
+        f, b, _ = B.rgnn_workspace_bytes(g.handle, B.RGNN_LAYER_RGAT, B.make_desc(B.RGNN_F32, d, d, 1, 0.2))
+        (ws, _), = g.workspaces.values()
+        assert ws.numel() >= max(f, b)
+        return g, max(f, b)
+
+    print("autograd case workspace lifetime", flush=True)
+    small, need_small = run(200, 3, 1500, 311)
+    small_id = id(small)
+    small.close()
+    assert small.workspaces == {}
+    with pytest.raises(RuntimeError):
+        A._bufs(small, B.RGNN_LAYER_RGAT, B.make_desc(), (64, 1))       # a closed graph hands out nothing
+    del small
+    gc.collect()
+    for seed in range(312, 320):                                         # several tries at recycling the id
+        big, need_big = run(3000, 6, 40000, seed)
+        assert need_big > need_small
+        reused = id(big) == small_id
+        big.close()
+        del big
+        gc.collect()
+        if reused:
+            break

@@ -119,37 +119,61 @@ def test_layer_argument_errors():
 
 def test_inference_calls_without_saved_buffer():
     """saved == NULL: the forward keeps nothing for a backward call and takes the room from a workspace of
-    fwd_workspace + saved bytes; the result is bit-identical to the training-mode forward."""
+    exactly fwd_workspace + saved bytes (guard zones on both sides stay intact).  The result is checked against
+    the oracle, and is bit-identical to the training-mode forward."""
     import torch
+    from oracle import layers as O
     from paper_2412_04747_amd import binding as B
-    from paper_2412_04747_amd.harness import Graph, RgatLayer, HgtLayer, _buf, _stream
-    rng, src, dst, rel, ntype = synth.tiny(8, N=700, R=4, E=6000, T=2)
+    from paper_2412_04747_amd.harness import Graph, RgatLayer, HgtLayer, _stream
+    from parity import check, TOL_F32, TOL_BF16
+    GUARD = 1 << 20
+
+    def guarded(n):
+        big = torch.full((GUARD + n + GUARD,), 0xA5, dtype=torch.uint8, device="cuda")
+        return big, big[GUARD:GUARD + n]
+
+    def intact(big, n, what):
+        assert bool((big[:GUARD] == 0xA5).all()) and bool((big[GUARD + n:] == 0xA5).all()), what
+
+    N, R, T = 700, 4, 2
+    rng, src, dst, rel, ntype = synth.tiny(8, N=N, R=R, E=6000, T=T)
     dst[:900] = 3
-    g = Graph(700, 4, src, dst, rel, ntype, 2)
-    for dtype, d in (("f32", 64), ("bf16", 128)):
+    g = Graph(N, R, src, dst, rel, ntype, T)
+    for dtype, d, heads in (("f32", 64, 1), ("bf16", 128, 1), ("bf16", 64, 1), ("f32", 64, 2)):
+        print(f"inference case {dtype} d={d} heads={heads}", flush=True)
+        tol = TOL_BF16 if dtype == "bf16" else TOL_F32
         rnd = (lambda v: None if v is None else synth.round_to_bf16(v)) if dtype == "bf16" else (lambda v: v)
-        p = {k: rnd(v) for k, v in synth.rgat_params(rng, 700, 4, d, d).items()}
-        L = RgatLayer(g, d, dtype=dtype)
+        p = {k: rnd(v) for k, v in synth.rgat_params(rng, N, R, d, d).items()}
+        L = RgatLayer(g, d, dtype=dtype, heads=heads)
         L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
         L.fwd()
         ref = L.out.clone()
         f, _, s = B.rgnn_workspace_bytes(g.handle, B.RGNN_LAYER_RGAT, L.desc)
-        ws = _buf(f + s + 256)
-        L.out.zero_()
+        big, ws = guarded(f + s)
+        L.out.fill_(float("nan"))
         B.rgnn_rgat_fwd(g.handle, L.desc, L.X, L.W, L.w_s, L.w_t, L.out, None, ws, _stream())
         torch.cuda.synchronize()
+        intact(big, f + s, ("rgat", dtype, d))
         assert torch.equal(ref, L.out), ("rgat", dtype)
-        q = {k: rnd(v) for k, v in synth.hgt_params(rng, 700, 2, 4, d, 2, with_mu=True).items()}
+        want = (O.rgat_fwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"]) if heads == 1 else
+                O.rgat_heads_fwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], heads))
+        check(L.out, want, tol, f"rgat inference {dtype} d={d} heads={heads}")
+        if heads > 1:
+            continue
+        q = {k: rnd(v) for k, v in synth.hgt_params(rng, N, T, R, d, 2, with_mu=True).items()}
         H = HgtLayer(g, d, 2, with_mu=True, dtype=dtype)
         H.load(q["X"], q["Wk"], q["Wq"], q["Wv"], q["Wo"], q["Watt"], q["Wmsg"], q["mu"], q["dOut"])
         H.fwd()
         ref = H.out.clone()
         f, _, s = B.rgnn_workspace_bytes(g.handle, B.RGNN_LAYER_HGT, H.desc)
-        ws = _buf(f + s + 256)
-        H.out.zero_()
+        big, ws = guarded(f + s)
+        H.out.fill_(float("nan"))
         B.rgnn_hgt_fwd(g.handle, H.desc, H.X, H.Wk, H.Wq, H.Wv, H.Wo, H.Watt, H.Wmsg, H.mu, H.out, None, ws, _stream())
         torch.cuda.synchronize()
+        intact(big, f + s, ("hgt", dtype, d))
         assert torch.equal(ref, H.out), ("hgt", dtype)
+        want = O.hgt_fwd(N, src, dst, rel, ntype, *[q[k] for k in ("X", "Wk", "Wq", "Wv", "Wo", "Watt", "Wmsg", "mu")])
+        check(H.out, want, tol, f"hgt inference {dtype} d={d}")
     g.close()
 
 

@@ -10,12 +10,14 @@ from parity import check, TOL_F32
 pytestmark = pytest.mark.gpu
 
 
-def _run(N, R, src, dst, rel, p, d, tag, slope=0.2, check_saved=True):
+def _run(N, R, src, dst, rel, p, d, tag, slope=0.2, check_saved=True, dtype="f32"):
     import torch
     from paper_2412_04747_amd.harness import Graph, RgatLayer
-    print(f"rgat case {tag}: N={N} R={R} E={len(src)} d={d}", flush=True)
+    from parity import TOL_BF16
+    print(f"rgat case {tag}: N={N} R={R} E={len(src)} d={d} {dtype}", flush=True)
+    TOL_F32 = TOL_BF16 if dtype == "bf16" else 1e-4        # the tolerance of this case, under the name used below
     g = Graph(N, R, src, dst, rel)
-    L = RgatLayer(g, d, slope)
+    L = RgatLayer(g, d, slope, dtype=dtype)
     L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
     L.fwd()
     torch.cuda.synchronize()
@@ -62,6 +64,16 @@ def test_small_random(d):
     rng, src, dst, rel, _ = synth.tiny(60 + d, N=500, R=6, E=4000)
     p = synth.rgat_params(rng, 500, 6, d, d)
     _run(500, 6, src, dst, rel, p, d, f"small-d{d}")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_single_head_bf16_inputs(d):
+    """bf16 X, W, w_s, w_t, dOut (rounded once on the host; the oracle consumes the rounded values in fp64),
+    fp32 sums and fp32 results: single-head RGAT against the oracle at the bf16 tolerance."""
+    rng, src, dst, rel, _ = synth.tiny(90 + d, N=600, R=5, E=5000)
+    dst[:900] = 7                                    # a hub cut into pieces
+    p = {k: synth.round_to_bf16(v) for k, v in synth.rgat_params(rng, 600, 5, d, d).items()}
+    _run(600, 5, src, dst, rel, p, d, f"bf16-d{d}", dtype="bf16")
 
 
 def test_many_single_edge_destinations():

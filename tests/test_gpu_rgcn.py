@@ -59,6 +59,52 @@ def test_hub_and_isolated_nodes():
     _run(400, 3, src, dst, rel, p, 64, "in_degree_per_rel", "none", True, tag="hub")
 
 
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_relu_backward_from_the_gpus_own_output(dtype, d):
+    """The ReLU mask of the backward call is taken from the `out` the GPU's own forward wrote (the other cases
+    hand both sides the oracle's `out`).  So that no mask bit hangs on rounding, the inputs are built with
+    every pre-activation at least 1e-3 away from 0: sources and destinations are disjoint node sets and the
+    self-loop weight is the identity, hence a destination's own feature row shifts its own pre-activation only (a source's row
+    also moves its destinations, so the nudging is repeated until nothing is left inside the margin)."""
+    import torch
+    from paper_2412_04747_amd.harness import Graph, RgcnLayer
+    N, R, E = 800, 4, 6000
+    rng = np.random.default_rng(611)
+    src = rng.integers(0, N // 2, E).astype(np.int32)
+    dst = rng.integers(N // 2, N, E).astype(np.int32)
+    dst[:900] = N // 2 + 3                                       # a hub
+    rel = rng.integers(0, R, E).astype(np.int32)
+    p = synth.rgcn_params(rng, N, R, d, d, self_loop=True)
+    p["W0"] = np.eye(d, dtype=np.float32)
+    if dtype == "bf16":
+        p = {k: synth.round_to_bf16(v) for k, v in p.items()}
+    margin = 4e-3 if dtype == "f32" else 3e-2                    # bf16: a step of X's grid is up to 2^-8 of |x|
+    for _ in range(4):
+        pre = O.rgcn_fwd(N, src, dst, rel, p["X"], p["W"], p["W0"], "in_degree_per_rel", "none")
+        near = np.abs(pre) < margin
+        if not near.any():
+            break
+        X = p["X"].astype(np.float64)
+        X[near] += np.where(pre[near] >= 0, 2 * margin, -2 * margin)
+        p["X"] = synth.round_to_bf16(X.astype(np.float32)) if dtype == "bf16" else X.astype(np.float32)
+    pre = O.rgcn_fwd(N, src, dst, rel, p["X"], p["W"], p["W0"], "in_degree_per_rel", "none")
+    assert np.abs(pre).min() >= 1e-3
+    print(f"rgcn case relu-own-out {dtype} d={d}: min |pre-activation| {np.abs(pre).min():.2e}", flush=True)
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    g = Graph(N, R, src, dst, rel)
+    L = RgcnLayer(g, d, "in_degree_per_rel", "relu", True, dtype=dtype)
+    L.load(p["X"], p["W"], p["W0"], p["dOut"])
+    L.fwd(); L.bwd()                                             # `out` stays the GPU's
+    torch.cuda.synchronize()
+    want = O.rgcn_fwd(N, src, dst, rel, p["X"], p["W"], p["W0"], "in_degree_per_rel", "relu")
+    check(L.out, want, tol, "out")
+    assert np.array_equal(L.out.cpu().numpy() > 0, want > 0)
+    wg = O.rgcn_bwd(N, src, dst, rel, p["X"], p["W"], p["W0"], p["dOut"], "in_degree_per_rel", "relu", out=want)
+    for k, v in L.grads().items():
+        check(v, wg[k], tol, k)
+    g.close()
+
+
 def test_empty_graph():
     rng = np.random.default_rng(0)
     p = synth.rgcn_params(rng, 10, 2, 32, 32, self_loop=True)
