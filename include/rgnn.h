@@ -91,13 +91,27 @@ typedef struct {
  *   norm       RGCN: RGNN_NORM_IN_DEGREE_PER_REL divides each message by c_{v,r},
  *              the number of incoming edges of v with relation r (Eq. (rgcn)).
  *   activation RGCN: sigma of Eq. (rgcn), RGNN_ACT_NONE or RGNN_ACT_RELU.
- *   flags      0, or RGNN_FLAG_EDGE_PARALLEL_AGGREGATION (single-head RGAT forward, fp32): the weighted
- *              sum over a destination's incoming edges is formed edge by edge with atomic adds on the
- *              output rows (the thesis's traversal template, Alg. "traversal template": partial results
- *              are added atomically to global memory) instead of by the destination-segment walk.  Same
- *              result up to the order of the additions, which then varies from run to run; kept so that
- *              the two schedules can be compared. */
+ *   flags      0, or a combination of RGNN_FLAG_* bits.  Each bit forces an alternative to a schedule or layout
+ *              the library would otherwise pick for the graph (rgnn_schedule reports the pick); results agree
+ *              within rounding, and all but the first are bit-reproducible.  They exist so that the choices can
+ *              be compared on a given graph (thesis Ch.3: no schedule or layout fits every graph). */
+/* single-head RGAT forward: the weighted sum over a destination's incoming edges is formed edge by edge with atomic
+ * adds on the output rows (the thesis's traversal template, Alg. "traversal template": partial results are added
+ * atomically to global memory) instead of by the destination-segment walk; the order of the additions then varies
+ * from run to run.  Implies RGNN_FLAG_SEPARATE_SOFTMAX. */
 #define RGNN_FLAG_EDGE_PARALLEL_AGGREGATION 1u
+/* every segment takes the general walk: no batched kernels for the segments with one or with 2..4 entries */
+#define RGNN_FLAG_NO_BATCHED_WALKS 2u
+/* single-head RGAT (width <= 64), RGCN with bf16 rows: the gradient row of every (source, relation) pair is
+ * written per pair, also for the pairs with one edge, instead of being read through the row selector */
+#define RGNN_FLAG_NO_ROW_SELECT 4u
+/* HGT: keep the key / message node linears and the per-relation matrices apart even when every relation's
+ * sources have one node type (`saved` then holds the K and V rows as well) */
+#define RGNN_FLAG_NO_WEIGHT_FOLDING 8u
+/* single-head RGAT forward: source logit per pair as an epilogue of the typed linear, edge softmax as a pass of its
+ * own that stores one attention weight per edge, then the weighted sum (three passes instead of the fused walk) */
+#define RGNN_FLAG_SEPARATE_SOFTMAX 16u
+#define RGNN_FLAG_ALL 31u
 typedef struct {
     int32_t dtype;
     int32_t d_in;
@@ -182,6 +196,29 @@ rgnn_status_t rgnn_graph_export(const rgnn_graph_t* g, int32_t which, void* host
  * pointer may be NULL. */
 rgnn_status_t rgnn_workspace_bytes(const rgnn_graph_t* g, int32_t layer, const rgnn_layer_desc_t* desc,
                                    size_t* fwd_workspace, size_t* bwd_workspace, size_t* saved);
+
+/* What the library picks for a layer configuration on a graph (1 = yes). */
+typedef struct {
+    int32_t item_len;            /* longest traversal item in edges: longer segments (hub nodes) are cut into pieces */
+    int32_t tile_chunks;         /* workgroups of the typed-linear kernels over the pair tiles (short chunks) */
+    int32_t wide_chunks;         /* the same tiles in one resident round of long chunks (fp32 kernels, weight gradients) */
+    int32_t rows_bf16;           /* intermediate row tensors stored as bfloat16 */
+    int32_t row_select;          /* single-edge pairs: gradient row read through the row selector, not materialised */
+    int32_t hgt_folded;          /* HGT key / message linears folded into the per-relation weights */
+    int32_t fused_softmax;       /* single-head RGAT: edge softmax fused into the aggregation walk */
+    int32_t ws_in_lds;           /* ... with w_s held in LDS */
+    int32_t edge_parallel;       /* forward aggregation edge by edge with atomic adds */
+    int32_t dst_batched_single;  /* destination-major walk: batched kernel phase for destinations with one edge */
+    int32_t dst_batched_short;   /* ... and for those with 2..4 edges */
+    int32_t pair_walk_multi_only;/* pair-major backward walk visits only the pairs with several edges */
+    int32_t pair_batched_single; /* pair-major walk: batched phase for pairs with one edge */
+    int32_t pair_batched_short;  /* ... and for those with 2..4 edges */
+} rgnn_schedule_t;
+
+/* The schedule and layout choices a call of `layer` with `desc` makes on this graph: from the statistics of the
+ * graph index (item and segment counts, source types per relation), the descriptor (dtype, width, heads) and
+ * desc.flags.  No device work.  Errors as rgnn_workspace_bytes. */
+rgnn_status_t rgnn_schedule(const rgnn_graph_t* g, int32_t layer, const rgnn_layer_desc_t* desc, rgnn_schedule_t* out);
 
 /*
  * RGCN (Eq. (rgcn)):  out[v] = act( X[v] W0 + sum_{e=(u->v,r)} (1/c_{v,r}) X[u] W[r] ).

@@ -20,6 +20,10 @@ RGNN_LAYER_RGCN, RGNN_LAYER_RGAT, RGNN_LAYER_HGT = 0, 1, 2
 RGNN_NORM_NONE, RGNN_NORM_IN_DEGREE_PER_REL = 0, 1
 RGNN_ACT_NONE, RGNN_ACT_RELU = 0, 1
 RGNN_FLAG_EDGE_PARALLEL_AGGREGATION = 1
+RGNN_FLAG_NO_BATCHED_WALKS = 2
+RGNN_FLAG_NO_ROW_SELECT = 4
+RGNN_FLAG_NO_WEIGHT_FOLDING = 8
+RGNN_FLAG_SEPARATE_SOFTMAX = 16
 RGNN_MEM_HOST, RGNN_MEM_DEVICE = 0, 1
 RGNN_COO, RGNN_CSR_DST = 0, 1
 RGNN_STATIC_SCRATCH_BYTES = 64 << 20
@@ -31,7 +35,7 @@ INDEX_NAMES = ["in_ptr", "in_src", "in_rel", "in_eid", "in_pair", "in_run", "in_
 
 EXPORTS = ["rgnn_last_error", "rgnn_graph_create", "rgnn_graph_destroy", "rgnn_graph_info", "rgnn_graph_export",
            "rgnn_workspace_bytes", "rgnn_rgcn_fwd", "rgnn_rgcn_bwd", "rgnn_rgat_fwd", "rgnn_rgat_bwd",
-           "rgnn_hgt_fwd", "rgnn_hgt_bwd", "rgnn_profile_start", "rgnn_profile_stop", "rgnn_rgat_fwd_static"]
+           "rgnn_hgt_fwd", "rgnn_hgt_bwd", "rgnn_profile_start", "rgnn_profile_stop", "rgnn_rgat_fwd_static", "rgnn_schedule"]
 
 
 class RgnnError(RuntimeError):
@@ -50,6 +54,16 @@ class GraphInfo(C.Structure):
 class LayerDesc(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("heads", C.c_int32),
                 ("slope", C.c_float), ("norm", C.c_int32), ("activation", C.c_int32), ("flags", C.c_uint32)]
+
+
+class Schedule(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in (
+        "item_len", "tile_chunks", "wide_chunks", "rows_bf16", "row_select", "hgt_folded", "fused_softmax", "ws_in_lds",
+        "edge_parallel", "dst_batched_single", "dst_batched_short", "pair_walk_multi_only", "pair_batched_single",
+        "pair_batched_short")]
+
+    def as_dict(self):
+        return {k: int(getattr(self, k)) for k, _ in self._fields_}
 
 
 _lib = None
@@ -118,6 +132,13 @@ def rgnn_workspace_bytes(g, layer, desc):
     f, b, s = C.c_size_t(), C.c_size_t(), C.c_size_t()
     _check(lib().rgnn_workspace_bytes(g, C.c_int32(layer), C.byref(desc), C.byref(f), C.byref(b), C.byref(s)))
     return f.value, b.value, s.value
+
+
+def rgnn_schedule(g, layer, desc):
+    """The schedule / layout choices of a layer configuration on a graph, as a dict."""
+    out = Schedule()
+    _check(lib().rgnn_schedule(g, C.c_int32(layer), C.byref(desc), C.byref(out)))
+    return out.as_dict()
 
 
 def rgnn_rgcn_fwd(g, desc, X, W, W0, out, saved, workspace, stream=None):

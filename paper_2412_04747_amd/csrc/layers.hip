@@ -3,6 +3,7 @@
 // synchronisation; everything is enqueued on the caller's stream.
 #include "rgnn_internal.h"
 #include "traversal.h"
+#include "schedule.h"
 
 #include <map>
 #include <mutex>
@@ -56,9 +57,9 @@ inline bool missing(const rgnn_graph_t* g, const void* p) { return !p && g->N > 
 
 rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int layer) {
     if (!g || !d) RGNN_FAIL(RGNN_EINVAL, "graph or desc is NULL");
-    if (d->flags & ~RGNN_FLAG_EDGE_PARALLEL_AGGREGATION) RGNN_FAIL(RGNN_EINVAL, "unknown bits in desc.flags");
-    if (d->flags && (layer != RGNN_LAYER_RGAT || d->heads != 1))
-        RGNN_FAIL(RGNN_EUNSUPPORTED, "edge-parallel aggregation is built for single-head RGAT only");
+    if (d->flags & ~RGNN_FLAG_ALL) RGNN_FAIL(RGNN_EINVAL, "unknown bits in desc.flags");
+    if ((d->flags & (RGNN_FLAG_EDGE_PARALLEL_AGGREGATION | RGNN_FLAG_SEPARATE_SOFTMAX)) && (layer != RGNN_LAYER_RGAT || d->heads != 1))
+        RGNN_FAIL(RGNN_EUNSUPPORTED, "the edge-parallel aggregation and the separate softmax pass are schedules of single-head RGAT only");
     if (d->dtype != RGNN_F32 && d->dtype != RGNN_BF16) RGNN_FAIL(RGNN_EINVAL, "unknown dtype %d", d->dtype);
     if (d->d_in != d->d_out || (d->d_in != 32 && d->d_in != 64 && d->d_in != 128))
         RGNN_FAIL(RGNN_EUNSUPPORTED, "need d_in == d_out in {32, 64, 128}, got %d -> %d", d->d_in, d->d_out);
@@ -100,8 +101,9 @@ struct RgatBwdWs {
 };
 // Single-head RGAT at widths up to 64: the gradient rows of single-edge pairs are not written per pair;
 // the typed-linear backward reads att_e * dOut[dst_e] through its row selector.
-inline bool rgat_row_select(const rgnn_layer_desc_t* d) { return d->heads == 1 && d->d_out <= 64; }
+inline bool rgat_row_select(const rgnn_layer_desc_t* d) { return sched_row_select(RGNN_LAYER_RGAT, d->dtype, d->d_out, d->heads, d->flags); }
 inline bool rgat_edge_parallel(const rgnn_layer_desc_t* d) { return (d->flags & RGNN_FLAG_EDGE_PARALLEL_AGGREGATION) != 0; }
+inline bool rgat_fused(const rgnn_layer_desc_t* d) { return sched_fused_softmax(d->heads, d->flags); }
 
 size_t carve_rgat_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatSaved* s) {
     Carver c(base);
@@ -125,8 +127,8 @@ size_t carve_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
         w->s_dst = c.take<float>((size_t)g->Q * H);
         w->part_m = c.take<float>(parts * H);
         w->part_s = c.take<float>(parts * H);
-    } else if (rgat_edge_parallel(d)) {
-        // the comparison schedule: per-pair source logits, a softmax pass of its own, attention weights per edge
+    } else if (!rgat_fused(d)) {
+        // the comparison schedules: per-pair source logits, a softmax pass of its own, attention weights per edge
         w->s_src = c.take<float>((size_t)g->P);
         w->att = c.take<float>((size_t)g->E);
         w->part_m = c.take<float>(parts);
@@ -186,7 +188,7 @@ size_t carve_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
 // Folded path (the graph ties every relation to one source node type): the key and message linears
 // of the nodes are folded into the per-relation weights (Wf = Wk[type] Watt[r], Wv[type] Wmsg[r]), so
 // K, V and their gradients do not exist and the per-pair rows come straight from X.
-inline bool hgt_folded(const rgnn_graph_t* g) { return g->rel_src_tied; }
+inline bool hgt_folded(const rgnn_graph_t* g, const rgnn_layer_desc_t* d) { return sched_hgt_folded(g->rel_src_tied, d->flags); }
 struct HgtSaved { void* K; void* Q; void* V; void* Z; void* Ka; void* M; float* att; };
 struct HgtFwdWs { float* Wbd_att; float* Wbd_msg; float* Wf_att; float* Wf_msg; float* part_m; float* part_s; float* partial; };
 struct HgtBwdWs {
@@ -199,7 +201,7 @@ struct HgtBwdWs {
 size_t carve_hgt_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtSaved* s) {
     Carver c(base);
     const bool h = rows_bf16(d);
-    const size_t nd = (size_t)g->N * d->d_out, pd = (size_t)g->P * d->d_out, kv = hgt_folded(g) ? 0 : nd;
+    const size_t nd = (size_t)g->N * d->d_out, pd = (size_t)g->P * d->d_out, kv = hgt_folded(g, d) ? 0 : nd;
     s->K = c.rows(kv, h); s->Q = c.rows(nd, h); s->V = c.rows(kv, h); s->Z = c.rows(nd, h);
     s->Ka = c.rows(pd, h); s->M = c.rows(pd, h);
     s->att = c.take<float>((size_t)g->E * d->heads);
@@ -207,7 +209,7 @@ size_t carve_hgt_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* 
 }
 size_t carve_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtFwdWs* w) {
     Carver c(base);
-    const size_t rdd = (size_t)g->R * d->d_out * d->d_out, fdd = hgt_folded(g) ? rdd : 0;
+    const size_t rdd = (size_t)g->R * d->d_out * d->d_out, fdd = hgt_folded(g, d) ? rdd : 0;
     w->Wbd_att = c.take<float>(rdd); w->Wbd_msg = c.take<float>(rdd);
     w->Wf_att = c.take<float>(fdd); w->Wf_msg = c.take<float>(fdd);
     w->part_m = c.take<float>((size_t)g->dst_items.num_partials * d->heads);
@@ -218,7 +220,7 @@ size_t carve_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* ba
 size_t carve_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtBwdWs* w) {
     Carver c(base);
     const bool h = rows_bf16(d);
-    const bool fold = hgt_folded(g);
+    const bool fold = hgt_folded(g, d);
     const size_t D = d->d_out, rdd = (size_t)g->R * D * D, nd = (size_t)g->N * D, pd = (size_t)g->P * D;
     w->Wbd_att = c.take<float>(rdd); w->Wbd_msg = c.take<float>(rdd);
     w->dWbd_att = c.take<float>(rdd); w->dWbd_msg = c.take<float>(rdd);
@@ -348,6 +350,22 @@ extern "C" rgnn_status_t rgnn_workspace_bytes(const rgnn_graph_t* g, int32_t lay
     return RGNN_OK;
 }
 
+extern "C" rgnn_status_t rgnn_schedule(const rgnn_graph_t* g, int32_t layer, const rgnn_layer_desc_t* desc, rgnn_schedule_t* out) {
+    if (layer != RGNN_LAYER_RGCN && layer != RGNN_LAYER_RGAT && layer != RGNN_LAYER_HGT)
+        RGNN_FAIL(RGNN_EINVAL, "unknown layer %d", layer);
+    RGNN_TRY(check_desc(g, desc, layer));
+    if (!out) RGNN_FAIL(RGNN_EINVAL, "out is NULL");
+    ScheduleIn in;
+    in.layer = layer; in.dtype = desc->dtype; in.d = desc->d_out; in.heads = layer == RGNN_LAYER_RGCN ? 1 : desc->heads;
+    in.flags = desc->flags; in.R = g->R; in.rel_src_tied = g->rel_src_tied;
+    in.item_len = item_cut(g->E); in.tile_chunks = g->pair_tiles.num_chunks; in.wide_chunks = g->pair_tiles_wide.num_chunks;
+    in.dst = {g->dst_items.num_single, g->dst_items.num_short};
+    in.pair = {g->pair_items.num_single, g->pair_items.num_short};
+    in.pair_multi = {g->pair_items_multi.num_single, g->pair_items_multi.num_short};
+    *out = pick_schedule(in);
+    return RGNN_OK;
+}
+
 // =========================================================================== RGCN
 
 extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X,
@@ -355,6 +373,7 @@ extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_d
                                        void* stream) {
     (void)saved;
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGCN));
+    ScheduleFlagsScope sched_scope(desc->flags);
     if (missing(g, X) || !W || missing(g, out)) RGNN_FAIL(RGNN_EINVAL, "X, W or out is NULL");
     if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -392,6 +411,7 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
                                        void* stream) {
     (void)saved;
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGCN));
+    ScheduleFlagsScope sched_scope(desc->flags);
     if (missing(g, X) || !W || missing(g, dOut) || missing(g, dX) || !dW) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (W0 && !dW0) RGNN_FAIL(RGNN_EINVAL, "dW0 is NULL but W0 is given");
     if (desc->activation != RGNN_ACT_NONE && missing(g, out)) RGNN_FAIL(RGNN_EINVAL, "out is needed for the activation's gradient");
@@ -427,10 +447,11 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     const float* ocoef = coef ? g->out_invc : nullptr;
     //    With bf16 rows the row of a pair with a single edge is not written per pair: the typed-linear backward
     //    reads dPre[dst_e] through its row selector and multiplies it by 1/c_e on the way in.
-    const int32_t* ysel = h ? g->pair_ysel : nullptr;
-    const void* y_alt = h ? dPre : nullptr;
-    const float* yscale = h && coef ? g->pair_scale : nullptr;
-    RGNN_TRY(gather_sum(h ? g->pair_items_multi : g->pair_items, D, nullptr, g->idx[RGNN_IDX_OUT_DST], 0, ocoef, 1, 0, dPre, w.G,
+    const bool sel = sched_row_select(RGNN_LAYER_RGCN, desc->dtype, D, 1, desc->flags);
+    const int32_t* ysel = sel ? g->pair_ysel : nullptr;
+    const void* y_alt = sel ? dPre : nullptr;
+    const float* yscale = sel && coef ? g->pair_scale : nullptr;
+    RGNN_TRY(gather_sum(sel ? g->pair_items_multi : g->pair_items, D, nullptr, g->idx[RGNN_IDX_OUT_DST], 0, ocoef, 1, 0, dPre, w.G,
                         w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", 1, h, h));
     // 2. per pair dXp = dHs W^T; dW[r] = sum X^T dHs
     RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, h ? X : static_cast<const void*>(X32), g->idx[RGNN_IDX_PAIR_SRC], 0, W32, W16, w.G,
@@ -506,6 +527,7 @@ extern "C" rgnn_status_t rgnn_rgat_fwd_static(const rgnn_graph_t* g, const rgnn_
 static rgnn_status_t rgat_fwd_impl(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* W,
                                    const void* w_s, const void* w_t, void* out, void* saved, void* workspace, void* stream) {
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGAT));
+    ScheduleFlagsScope sched_scope(desc->flags);
     if (missing(g, X) || !W || !w_s || !w_t || missing(g, out)) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -536,20 +558,23 @@ static rgnn_status_t rgat_fwd_impl(const rgnn_graph_t* g, const rgnn_layer_desc_
                           "aggregate_fwd", "aggregate_fwd.combine", H);
     }
     const float *Xf = static_cast<const float*>(X), *Wf = static_cast<const float*>(W);
-    const bool edge_par = rgat_edge_parallel(desc);
+    const bool fused = rgat_fused(desc);
     // 1. compact messages: Hs[p] = X[pair_src[p]] W[r]
-    //    (the comparison schedule also takes the source half of the logit per pair, s_src[p] = Hs[p] . w_s[r])
+    //    (the comparison schedules also take the source half of the logit per pair, s_src[p] = Hs[p] . w_s[r])
     TypedLinearArgs a{};
     a.tiles = &g->pair_tiles_wide; a.X = Xf; a.gather = g->idx[RGNN_IDX_PAIR_SRC]; a.W = Wf; a.Y = sv.Hs;
-    if (edge_par) { a.vec = static_cast<const float*>(w_s); a.s_out = w.s_src; }
+    if (!fused) { a.vec = static_cast<const float*>(w_s); a.s_out = w.s_src; }
     RGNN_TRY(typed_linear_fwd(K, D, a, st));
     // 2. destination half, once per (dst, rel) run, reordered: s_dst[q] = X[dst] . (W[r] w_t[r])
     RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_t), w.wtp, st));
     RGNN_TRY(run_logit(g, K, Xf, w.wtp, sv.s_dst, st));
-    if (edge_par) {
-        // 3'. edge softmax in a pass of its own, then edge-by-edge aggregation with atomic adds
+    if (!fused) {
+        // 3'. edge softmax in a pass of its own (one attention weight per edge, and (max, sum) per destination for the
+        //     backward call), then the weighted sum: by the destination-segment walk, or edge by edge with atomic adds
         RGNN_TRY(edge_softmax(g, w.s_src, sv.s_dst, desc->slope, w.att, w.part_m, w.part_s, st, sv.ms));
-        return aggregate_edge_parallel(g, D, w.att, sv.Hs, static_cast<float*>(out), st);
+        if (rgat_edge_parallel(desc)) return aggregate_edge_parallel(g, D, w.att, sv.Hs, static_cast<float*>(out), st);
+        return gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, w.att, 1, 1, sv.Hs, static_cast<float*>(out),
+                          w.partial, st, 0, "aggregate_fwd", "aggregate_fwd.combine");
     }
     // 3. one walk per destination: logit from the gathered row, running-maximum softmax, weighted sum
     return rgat_aggregate_fwd(g, D, sv.Hs, static_cast<const float*>(w_s), sv.s_dst, desc->slope, static_cast<float*>(out),
@@ -561,6 +586,7 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
                                        const void* saved, const void* dOut, void* dX, void* dW, void* dw_s,
                                        void* dw_t, void* workspace, void* stream) {
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_RGAT));
+    ScheduleFlagsScope sched_scope(desc->flags);
     if (missing(g, X) || !W || !w_s || !w_t || missing(g, out) || missing(g, dOut) || missing(g, dX) || !dW || !dw_s || !dw_t)
         RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (!workspace || !saved) RGNN_FAIL(RGNN_EWORKSPACE, "workspace or saved is NULL");
@@ -654,6 +680,7 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
                                       const void* Wmsg, const void* mu, void* out, void* saved, void* workspace,
                                       void* stream) {
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_HGT));
+    ScheduleFlagsScope sched_scope(desc->flags);
     if (missing(g, X) || !Wk || !Wq || !Wv || !Wo || !Watt || !Wmsg || missing(g, out)) RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (!workspace) RGNN_FAIL(RGNN_EWORKSPACE, "workspace is NULL");
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -667,7 +694,7 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
     Bf16Stage stg(workspace, carved, bf16, st);
     const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
     // fp32 copies: at width 128 only of the small per-relation parameters (their expansion is an fp32 kernel)
-    const bool fold = hgt_folded(g);
+    const bool fold = hgt_folded(g, desc);
     const float* X32 = !h ? stg.in(X, (size_t)g->N * D) : nullptr;
     const float* Wk32 = !h || fold ? stg.in(Wk, tdd) : nullptr;      // folding multiplies weights in fp32
     const float* Wq32 = !h ? stg.in(Wq, tdd) : nullptr;
@@ -724,6 +751,7 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
                                       void* dWatt, void* dWmsg, void* dmu, void* workspace, void* stream) {
     (void)out;
     RGNN_TRY(check_desc(g, desc, RGNN_LAYER_HGT));
+    ScheduleFlagsScope sched_scope(desc->flags);
     if (missing(g, X) || !Wk || !Wq || !Wv || !Wo || !Watt || !Wmsg || missing(g, dOut) || missing(g, dX) || !dWk || !dWq || !dWv || !dWo || !dWatt || !dWmsg)
         RGNN_FAIL(RGNN_EINVAL, "a required tensor pointer is NULL");
     if (mu && !dmu) RGNN_FAIL(RGNN_EINVAL, "dmu is NULL but mu is given");
@@ -736,7 +764,7 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
                *Wo16 = bf16 ? Wo : nullptr;
     Bf16Stage stg(workspace, carve_hgt_bwd(g, desc, workspace, &w), bf16, st);
     const size_t tdd = (size_t)g->T * D * D, rh = (size_t)g->R * H, dh = D / H;
-    const bool fold = hgt_folded(g);
+    const bool fold = hgt_folded(g, desc);
     const float* X32 = !h ? stg.in(X, (size_t)g->N * D) : nullptr;
     const float* Wk32 = !h || fold ? stg.in(Wk, tdd) : nullptr;
     const float* Wq32 = !h ? stg.in(Wq, tdd) : nullptr;

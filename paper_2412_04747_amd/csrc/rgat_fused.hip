@@ -19,6 +19,7 @@
 #include "rgnn_internal.h"
 #include "traversal.h"
 #include "device_utils.h"
+#include "schedule.h"
 
 namespace rgnn {
 
@@ -392,7 +393,6 @@ __global__ __launch_bounds__(kFusedThreads) void rgat_edge_dot_bwd_kernel(FusedA
 
 // Launch with as many workgroups as stay resident at once (LDS, registers and wavefront slots decide), never more
 // than the work needs: the grid-stride loops then see the items in list order, longest first, on every workgroup.
-constexpr size_t kWsLdsMax = 64 * 1024;
 template <typename K>
 rgnn_status_t launch_fused(K kernel, const rgnn_graph* g, size_t lds, size_t groups_needed, int lanes_per_row,
                            const FusedArgs& a, hipStream_t st) {
@@ -414,8 +414,8 @@ rgnn_status_t rgat_aggregate_fwd(const rgnn_graph* g, int D, const float* Hs, co
                                  float slope, float* out, float* ms, float* partial, float* part_ms, hipStream_t st) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0) return RGNN_OK;
-    const int ns = L.num_single >= 4096 ? L.num_single : 0;
-    const int nsh = L.num_short >= 4096 ? L.num_short : 0;
+    const int ns = batched_count(L.num_single, current_schedule_flags());
+    const int nsh = batched_count(L.num_short, current_schedule_flags());
     FusedArgs a{};
     a.it = dev_items(L); a.in_pair = g->idx[RGNN_IDX_IN_PAIR]; a.in_rel = g->idx[RGNN_IDX_IN_REL]; a.in_run = g->idx[RGNN_IDX_IN_RUN];
     a.Hs = Hs; a.w_s = w_s; a.s_dst = s_dst; a.slope = slope; a.R = g->R;
@@ -423,7 +423,7 @@ rgnn_status_t rgat_aggregate_fwd(const rgnn_graph* g, int D, const float* Hs, co
     a.general_n = L.num_items - nsh - ns; a.skip_first = nsh > 0 ? L.first_short : L.first_single; a.skip_n = nsh + ns;
     a.short_first = L.first_short; a.short_n = nsh; a.single_first = L.first_single; a.single_n = ns;
     const size_t lds = (size_t)g->R * D * sizeof(float);
-    const bool ldsw = lds <= kWsLdsMax;
+    const bool ldsw = sched_ws_in_lds(g->R, D);
     const size_t groups = std::max<size_t>({(size_t)a.general_n, (size_t)(nsh + 1) / 2, (size_t)(ns + 3) / 4});
     {
         KernelTimer kt(st, "aggregate_fwd");
@@ -452,7 +452,7 @@ rgnn_status_t rgat_edge_dot_bwd(const rgnn_graph* g, int D, const float* Hs, con
     a.dOut = dOut; a.fout = out; a.adz = reinterpret_cast<float2*>(adz); a.G = G; a.ds_src = ds_src;
     a.dsy = reinterpret_cast<float2*>(dsy);
     const size_t lds = (size_t)g->R * D * sizeof(float);
-    const bool ldsw = lds <= kWsLdsMax;
+    const bool ldsw = sched_ws_in_lds(g->R, D);
     KernelTimer kt(st, "edge_dot_bwd");
     if (ldsw) RGNN_DISPATCH_D(D, RGNN_TRY(launch_fused(rgat_edge_dot_bwd_kernel<DD, true>, g, lds, (size_t)L.num_items, DD / 4, a, st)));
     else RGNN_DISPATCH_D(D, RGNN_TRY(launch_fused(rgat_edge_dot_bwd_kernel<DD, false>, g, 0, (size_t)L.num_items, DD / 4, a, st)));

@@ -4,6 +4,15 @@
 
 namespace rgnn {
 
+// desc.flags of the layer call in progress on this thread: the launchers consult it where they choose between
+// the batched and the general walk (set by the entry points for the duration of a call).
+uint32_t current_schedule_flags();
+struct ScheduleFlagsScope {
+    explicit ScheduleFlagsScope(uint32_t flags);
+    ~ScheduleFlagsScope();
+    uint32_t prev;
+};
+
 // wv[r] = W[r] w[r]; optionally a second vector per relation in the same pass (wv2[r] = W[r] w2[r])
 rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w, float* wv, hipStream_t st,
                           const float* w2 = nullptr, float* wv2 = nullptr);

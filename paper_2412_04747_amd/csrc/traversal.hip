@@ -16,8 +16,14 @@
 #include "rgnn_internal.h"
 #include "traversal.h"
 #include "device_utils.h"
+#include "schedule.h"
 
 namespace rgnn {
+
+static thread_local uint32_t g_schedule_flags = 0;
+uint32_t current_schedule_flags() { return g_schedule_flags; }
+ScheduleFlagsScope::ScheduleFlagsScope(uint32_t flags) : prev(g_schedule_flags) { g_schedule_flags = flags; }
+ScheduleFlagsScope::~ScheduleFlagsScope() { g_schedule_flags = prev; }
 
 // ------------------------------------------------------------------ small dense helpers
 
@@ -988,8 +994,8 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
     const Rank1 r1v = r1 ? *r1 : Rank1{nullptr, 0, nullptr, nullptr};
     const int lpr = D / (src_bf16 ? 8 : 4);
     // enough short / single-entry segments to be worth launches of their own; the two ranges are adjacent
-    const int ns = L.num_single >= 4096 ? L.num_single : 0;
-    const int nsh = L.num_short >= 4096 ? L.num_short : 0;
+    const int ns = batched_count(L.num_single, current_schedule_flags());
+    const int nsh = batched_count(L.num_short, current_schedule_flags());
     const int skip_first = nsh > 0 ? L.first_short : L.first_single;
     GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns, r1v, sum2, sum2_stride};
     {

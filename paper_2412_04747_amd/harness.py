@@ -111,12 +111,12 @@ class RgatLayer:
 
 
 class RgcnLayer:
-    def __init__(self, graph, d, norm="in_degree_per_rel", act="none", self_loop=False, dtype="f32"):
+    def __init__(self, graph, d, norm="in_degree_per_rel", act="none", self_loop=False, dtype="f32", flags=0):
         self.g, self.d, self.self_loop = graph, d, self_loop
         code, self.tdt = _tdtype(dtype)
         self.desc = B.make_desc(code, d, d, 1, 0.0,
                                 B.RGNN_NORM_IN_DEGREE_PER_REL if norm == "in_degree_per_rel" else B.RGNN_NORM_NONE,
-                                B.RGNN_ACT_RELU if act == "relu" else B.RGNN_ACT_NONE)
+                                B.RGNN_ACT_RELU if act == "relu" else B.RGNN_ACT_NONE, flags)
         f, b, s = B.rgnn_workspace_bytes(graph.handle, B.RGNN_LAYER_RGCN, self.desc)
         self.ws = _buf(max(f, b))
         self.saved = _buf(s)
@@ -145,10 +145,10 @@ class RgcnLayer:
 
 
 class HgtLayer:
-    def __init__(self, graph, d, heads, with_mu=True, dtype="f32"):
+    def __init__(self, graph, d, heads, with_mu=True, dtype="f32", flags=0):
         self.g, self.d, self.H = graph, d, heads
         code, self.tdt = _tdtype(dtype)
-        self.desc = B.make_desc(code, d, d, heads)
+        self.desc = B.make_desc(code, d, d, heads, flags=flags)
         f, b, s = B.rgnn_workspace_bytes(graph.handle, B.RGNN_LAYER_HGT, self.desc)
         self.ws = _buf(max(f, b))
         self.saved = _buf(s)

@@ -151,10 +151,11 @@ def typed_graph(rng, N, T, R, E, type_zipf=1.0, rel_zipf=1.0, alpha=2.1, max_deg
 # Named workloads
 # ----------------------------------------------------------------------------
 
-def config(cid: int, scale: float = 1.0) -> dict:
+def config(cid: int, scale: float = 1.0, graph_only: bool = False) -> dict:
     """Workload `cid` in 1..5.  `scale` < 1 shrinks node and edge counts (used
     by CPU-side tests); 1.0 is the size the benchmark and full-size parity
-    tests run."""
+    tests run.  `graph_only` leaves the feature and weight tensors out (the
+    graph is drawn first, so it is the same either way)."""
     rng = np.random.default_rng(SEED0 + cid)
     s = lambda n: max(16, int(round(n * scale)))
     if cid == 1:      # RGCN fwd, fp32
@@ -162,25 +163,25 @@ def config(cid: int, scale: float = 1.0) -> dict:
         src, dst, rel = graph_uniform(rng, N, R, E)
         g = dict(layer="rgcn", dtype="f32", N=N, T=1, R=R, E=E, d_in=d, d_out=d, H=1,
                  norm="in_degree_per_rel", src=src, dst=dst, rel=rel)
-        g.update(rgcn_params(rng, N, R, d, d))
+        params = lambda: rgcn_params(rng, N, R, d, d)
     elif cid == 2:    # RGAT fwd+bwd, fp32
         N, R, E, d = s(20000), 50, s(200000), 64
         src, dst, rel = graph_skewed(rng, N, R, E, 1.1, 2.1)
         g = dict(layer="rgat", dtype="f32", N=N, T=1, R=R, E=E, d_in=d, d_out=d, H=1,
                  slope=0.2, src=src, dst=dst, rel=rel)
-        g.update(rgat_params(rng, N, R, d, d))
+        params = lambda: rgat_params(rng, N, R, d, d)
     elif cid == 3:    # RGAT fwd+bwd, fp32, headline
         N, R, E, d = s(1000000), 200, s(10000000), 64
         src, dst, rel = graph_skewed(rng, N, R, E, 1.2, 2.1, max_deg=50000.0 * scale)
         g = dict(layer="rgat", dtype="f32", N=N, T=1, R=R, E=E, d_in=d, d_out=d, H=1,
                  slope=0.2, src=src, dst=dst, rel=rel)
-        g.update(rgat_params(rng, N, R, d, d))
+        params = lambda: rgat_params(rng, N, R, d, d)
     elif cid == 4:    # HGT fwd+bwd, bf16 inputs
         N, T, R, E, d, H = s(2000000), 8, 30, s(20000000), 128, 4
         src, dst, rel, ntype, rst, rdt = typed_graph(rng, N, T, R, E)
         g = dict(layer="hgt", dtype="bf16", N=N, T=T, R=R, E=E, d_in=d, d_out=d, H=H,
                  src=src, dst=dst, rel=rel, ntype=ntype, rel_src_ntype=rst, rel_dst_ntype=rdt)
-        g.update(hgt_params(rng, N, T, R, d, H))
+        params = lambda: hgt_params(rng, N, T, R, d, H)
     elif cid == 5:    # RGCN fwd+bwd, knowledge-graph shaped, bf16 inputs
         N, R, E, d = s(2500000), 500, s(16000000), 128
         # 400 Zipf(1.0) relations plus a tail of 100 relations with 1..99 edges each
@@ -190,9 +191,11 @@ def config(cid: int, scale: float = 1.0) -> dict:
         src, dst, rel = graph_skewed(rng, N, R, E, 1.0, 2.1, max_deg=50000.0 * scale, rel_probs=p / p.sum())
         g = dict(layer="rgcn", dtype="bf16", N=N, T=1, R=R, E=E, d_in=d, d_out=d, H=1,
                  norm="in_degree_per_rel", src=src, dst=dst, rel=rel)
-        g.update(rgcn_params(rng, N, R, d, d, x_var=1.0))
+        params = lambda: rgcn_params(rng, N, R, d, d, x_var=1.0)
     else:
         raise ValueError(cid)
+    if not graph_only:
+        g.update(params())
     if g["dtype"] == "bf16":
         for k, v in list(g.items()):
             if isinstance(v, np.ndarray) and v.dtype == np.float32:

@@ -1,6 +1,7 @@
 // Test-only C wrapper around the host planning code of the library (work_lists.h), so that the
 // CPU test suite can check the tile and item plans without a GPU.  Built by tests/test_work_lists.py.
 #include "../../paper_2412_04747_amd/csrc/work_lists.h"
+#include "../../paper_2412_04747_amd/csrc/schedule.h"
 
 #include <cstring>
 
@@ -47,6 +48,20 @@ int wl_constant(int which) {
     const int c[] = {rgnn::kTileRows, rgnn::kMaxChunks, rgnn::kWideChunksPerCU, rgnn::kMinChunks, rgnn::kChunkTiles,
                      rgnn::kItemMax, rgnn::kItemTarget, rgnn::kSerialMax, rgnn::kShortLen};
     return c[which];
+}
+
+// in: layer, dtype, d, heads, flags, R, rel_src_tied, total entries of the destination-major list (edges),
+//     single / short counts of the destination list, of the pair list, of the multi-edge pair list   (14 ints)
+// out: the fields of rgnn_schedule_t in declaration order (14 ints); tile chunk counts are passed through as 0
+void wl_pick_schedule(const long long* in, int32_t* out) {
+    rgnn::ScheduleIn s;
+    s.layer = (int)in[0]; s.dtype = (int)in[1]; s.d = (int)in[2]; s.heads = (int)in[3]; s.flags = (uint32_t)in[4];
+    s.R = (int)in[5]; s.rel_src_tied = in[6] != 0; s.item_len = rgnn::item_cut(in[7]);
+    s.dst = {(int32_t)in[8], (int32_t)in[9]}; s.pair = {(int32_t)in[10], (int32_t)in[11]};
+    s.pair_multi = {(int32_t)in[12], (int32_t)in[13]};
+    const rgnn_schedule_t r = rgnn::pick_schedule(s);
+    static_assert(sizeof(r) == 14 * sizeof(int32_t), "rgnn_schedule_t is fourteen int32 fields");
+    std::memcpy(out, &r, sizeof(r));
 }
 
 }  // extern "C"

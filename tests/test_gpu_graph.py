@@ -98,7 +98,7 @@ def test_layer_argument_errors():
     # descriptor that a later version accepts cannot make one of these calls write out of bounds
     x = torch.zeros(1 << 24, device="cuda")
     for bad, status in ((B.make_desc(d_in=48, d_out=48), 2), (B.make_desc(d_in=64, d_out=32), 2),
-                        (B.make_desc(heads=8), 2), (B.make_desc(heads=3), 1), (B.make_desc(flags=2), 1), (B.make_desc(flags=1, heads=2), 2),
+                        (B.make_desc(heads=8), 2), (B.make_desc(heads=3), 1), (B.make_desc(flags=64), 1), (B.make_desc(flags=1, heads=2), 2), (B.make_desc(flags=16, heads=2), 2),
                         (B.make_desc(dtype=7), 1)):
         with pytest.raises(B.RgnnError) as e:
             B.rgnn_rgat_fwd(g.handle, bad, x, x, x, x, x, x, x)

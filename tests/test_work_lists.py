@@ -193,3 +193,92 @@ def test_tiles_chunks_and_slots(wl, S, max_chunks):
     assert ssp[0] == 0 and ssp[-1] == nxt
     for s in range(S):
         assert (slot_of[ssp[s]:ssp[s + 1]] == s).all()
+
+
+# ---------------------------------------------------------------- schedule / layout choice per graph
+
+SCHEDULE_FIELDS = ("item_len", "tile_chunks", "wide_chunks", "rows_bf16", "row_select", "hgt_folded", "fused_softmax",
+                   "ws_in_lds", "edge_parallel", "dst_batched_single", "dst_batched_short", "pair_walk_multi_only",
+                   "pair_batched_single", "pair_batched_short")
+LAYER = dict(rgcn=0, rgat=1, hgt=2)
+
+
+def graph_counts(c):
+    """What the choice depends on, counted from the edge list: destinations with one / with 2..4 incoming edges,
+    (source, relation) pairs with one / with 2..4 edges, and whether every relation's sources have one node type."""
+    N, R = c["N"], c["R"]
+    indeg = np.bincount(c["dst"], minlength=N)
+    _, outdeg = np.unique(c["rel"].astype(np.int64) * N + c["src"], return_counts=True)
+    cnt = lambda deg, lo, hi: int(((deg >= lo) & (deg <= hi)).sum())
+    tied = True
+    if c["T"] > 1:
+        st = c["ntype"][c["src"]]
+        tied = all(len(np.unique(st[c["rel"] == r])) <= 1 for r in range(R))
+    return dict(dst=(cnt(indeg, 1, 1), cnt(indeg, 2, 4)), pair=(cnt(outdeg, 1, 1), cnt(outdeg, 2, 4)),
+                pair_multi=(0, cnt(outdeg, 2, 4)), tied=tied)
+
+
+def pick(lib, c, k, heads=None, flags=0, dtype=None):
+    dt = dtype or c["dtype"]
+    a = np.array([LAYER[c["layer"]], 1 if dt == "bf16" else 0, c["d_out"], heads or c["H"], flags, c["R"], int(k["tied"]),
+                  c["E"], *k["dst"], *k["pair"], *k["pair_multi"]], dtype=np.int64)
+    out = np.zeros(len(SCHEDULE_FIELDS), np.int32)
+    lib.wl_pick_schedule(a.ctypes.data_as(C.c_void_p), out.ctypes.data_as(C.c_void_p))
+    return dict(zip(SCHEDULE_FIELDS, (int(v) for v in out)))
+
+
+# The pick for each of the five workloads (tile chunk counts depend on the device's compute-unit count and are
+# not part of this table).  Fields not listed are 0.
+EXPECTED_PICK = {
+    1: dict(item_len=32),
+    2: dict(item_len=32, row_select=1, fused_softmax=1, ws_in_lds=1, dst_batched_short=1, pair_walk_multi_only=1,
+            pair_batched_short=1),
+    3: dict(item_len=256, row_select=1, fused_softmax=1, ws_in_lds=1, dst_batched_single=1, dst_batched_short=1,
+            pair_walk_multi_only=1, pair_batched_short=1),
+    4: dict(item_len=256, rows_bf16=1, hgt_folded=1, dst_batched_single=1, dst_batched_short=1, pair_batched_single=1,
+            pair_batched_short=1),
+    5: dict(item_len=256, rows_bf16=1, row_select=1, dst_batched_single=1, dst_batched_short=1, pair_walk_multi_only=1,
+            pair_batched_short=1),
+}
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+def test_schedule_pick_for_the_five_workloads(wl, cid):
+    import sys
+    sys.path.insert(0, os.path.dirname(HERE))
+    from paper_2412_04747_amd import synth
+    c = synth.config(cid, graph_only=True)
+    got = pick(wl, c, graph_counts(c))
+    want = dict.fromkeys(SCHEDULE_FIELDS, 0)
+    want.update(EXPECTED_PICK[cid])
+    assert got == want, {k: (got[k], want[k]) for k in got if got[k] != want[k]}
+
+
+def test_schedule_flags_force_the_alternatives(wl):
+    import sys
+    sys.path.insert(0, os.path.dirname(HERE))
+    from paper_2412_04747_amd import synth
+    c = synth.config(2, graph_only=True)
+    k = graph_counts(c)
+    k["dst"] = (5000, 5000); k["pair"] = (9000, 7000); k["pair_multi"] = (0, 7000)
+    base = pick(wl, c, k)
+    assert base["dst_batched_single"] and base["dst_batched_short"] and base["pair_batched_short"] and base["row_select"]
+    assert base["fused_softmax"] and base["ws_in_lds"] and not base["edge_parallel"]
+    nb = pick(wl, c, k, flags=2)
+    assert not any(nb[f] for f in ("dst_batched_single", "dst_batched_short", "pair_batched_single", "pair_batched_short"))
+    assert {f: v for f, v in nb.items() if "batched" not in f} == {f: v for f, v in base.items() if "batched" not in f}
+    assert not pick(wl, c, k, flags=4)["row_select"] and pick(wl, c, k, flags=4)["pair_walk_multi_only"]
+    sep = pick(wl, c, k, flags=16)
+    assert not sep["fused_softmax"] and not sep["ws_in_lds"] and not sep["edge_parallel"]
+    ep = pick(wl, c, k, flags=1)
+    assert ep["edge_parallel"] and not ep["fused_softmax"]
+    heads = pick(wl, c, k, heads=4)
+    assert not heads["fused_softmax"] and not heads["row_select"] and not heads["pair_walk_multi_only"]
+    assert heads["pair_batched_single"]                     # several heads: the pair-major walk takes every pair
+    big_r = dict(c, R=300)                                  # 300 x 64 floats = 75 KB: w_s no longer fits the LDS budget
+    assert pick(wl, big_r, k)["fused_softmax"] and not pick(wl, big_r, k)["ws_in_lds"]
+    c4 = synth.config(4, scale=0.001, graph_only=True)
+    k4 = graph_counts(c4)
+    assert k4["tied"] and pick(wl, c4, k4)["hgt_folded"] and not pick(wl, c4, k4, flags=8)["hgt_folded"]
+    assert not pick(wl, c4, dict(k4, tied=False))["hgt_folded"]
+    assert pick(wl, c4, k4, dtype="f32")["rows_bf16"] == 0
