@@ -19,14 +19,79 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
+BF16_MFMA_PEAK_TFLOPS = 2500.0
+TRAFFIC_TSV = os.path.join(ROOT, "profiles", "rgat_c3_hbm_traffic_per_label.txt")
 
 
-def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat"):
-    """(bound, bytes, flops) one launch of kernel `name` must move / compute.  Gathered rows are
-    counted once per reference (no cache reuse assumed); index and scalar traffic as listed in the
-    comments below.  Row tensors are 4-byte elements, except in the
-    bfloat16 workloads at width 128, where inputs and intermediate rows are 2-byte elements
-    (results handed back to the caller stay fp32)."""
+def library_sha16():
+    """Hash of the HIP sources the library is built from: ties a committed counter summary to the kernels it measured."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2412_04747_amd", "csrc", "*.h*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def counter_traffic(label, sha):
+    """(bytes per step, source note) for a kernel label from the committed rocprofv3 --pmc summary of this command
+    (FETCH_SIZE + WRITE_SIZE, calibrated), or (None, why) when the summary was taken from other kernel sources."""
+    if not os.path.exists(TRAFFIC_TSV):
+        return None, "no counter summary committed"
+    rel = os.path.relpath(TRAFFIC_TSV, ROOT)
+    rows, file_sha = {}, None
+    for ln in open(TRAFFIC_TSV):
+        if ln.startswith("# lib_sha16:"):
+            file_sha = ln.split(":", 1)[1].strip()
+        elif not ln.startswith("#"):
+            f = ln.rstrip("\n").split("\t")
+            rows[f[0]] = float(f[1]) + float(f[2])
+    if file_sha != sha:
+        return None, f"{rel} was measured on other kernel sources ({file_sha}, now {sha}): stale, not used"
+    if label not in rows:
+        return None, f"{rel} has no row for {label}"
+    return rows[label], f"{rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command at lib_sha16 {sha}; not measured by this run)"
+
+
+def step_rooflines(kern_ms, E, N, P, P1, d):
+    """Single-head RGAT: the traversal steps as wholes (all kernels that implement a step, the step's algorithmic
+    bytes per edge / node / pair as the hot-path table of the design notes lists them) against the HBM peak."""
+    row = 4 * d
+    steps = {
+        # S3 forward traversal: per edge the message row, pair id, a logit scalar and a 4-byte weight or its
+        # equivalent (272 B at d = 64); per node the output row and 8 bytes of offsets / statistics
+        "S3_traversal_fwd": (E * (row + 16) + N * (row + 8),
+                             ("aggregate_fwd", "aggregate_fwd.combine", "edge_softmax", "edge_softmax.finish", "aggregate_fwd_edge_parallel")),
+        # S4 backward, destination-major: per edge the message row, index, weight, dz store; per node the gradient row
+        "S4_traversal_bwd_dst": (E * (row + 12) + N * row, ("edge_dot_bwd", "ds_dst_sum")),
+        # S5 backward, pair-major, over the pairs with several edges (the others are served by the row selector):
+        # per edge the gradient row, position, weight, dz, destination; per pair the stored row and its offset
+        "S5_traversal_bwd_pair": ((E - P1) * (row + 16) + (P - P1) * (row + 4),
+                                  ("aggregate_bwd_pair", "aggregate_bwd_pair.combine", "ds_src_sum")),
+    }
+    out = {}
+    for k, (nbytes, names) in steps.items():
+        ms = sum(kern_ms.get(n, 0.0) for n in names)
+        if ms > 0:
+            gbs = nbytes / ms / 1e6
+            out[k] = {"bound": "hbm", "bytes": nbytes, "ms": ms, "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                      "frac": gbs / HBM_PEAK_GBS, "kernels": [n for n in names if n in kern_ms]}
+    return out
+
+
+def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat", sched=None, n_dst=None):
+    """(bound, bytes, flops) one launch of kernel `name` must move / compute, or None where no model is kept
+    (the small reduce / combine / finish kernels).  Gathered rows are counted once per reference (no cache
+    reuse assumed) except where the reuse is structural: the runs of one destination are adjacent, so the
+    per-run logit kernel reads a destination's row once (n_dst = destinations with an incoming edge).
+    Index and scalar traffic as listed in the comments below.  Row tensors are 4-byte elements, except in
+    the bfloat16 workloads at width 128, where inputs and intermediate rows are 2-byte elements (results
+    handed back to the caller stay fp32).  `sched` is the library's pick for the call (rgnn_schedule)."""
+    if name.endswith((".reduce", ".combine", ".finish")):
+        return None
+    sched = sched or {}
+    n_dst = N if n_dst is None else n_dst
     half = bf16 and d == 128
     r32 = d * 4                       # an fp32 row
     row = d * 2 if half else r32      # an input / intermediate row
@@ -46,13 +111,15 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
             if name.endswith(".wgrad"):
                 return (bound, n * (2 * row + 4) + segs * d * d * 4, 2.0 * n * d * d)
             out_row = r32 if key in ("node_linear_out", "node_linear_k_bwd", "node_linear_q_bwd", "node_linear_v_bwd") else row
-            extra = r32 if half and key in ("node_linear_q_bwd", "node_linear_v_bwd") else 0   # accumulate into dX
+            # unfolded, bf16 rows: the second and third node linear accumulate into dX (read + write of the fp32 row)
+            extra = r32 if half and not sched.get("hgt_folded") and key in ("node_linear_q_bwd", "node_linear_v_bwd") else 0
             return (bound, n * (row + out_row + extra + 4) + segs * w2, 2.0 * n * d * d)
     w2 = d * d * 4
     # single-head RGAT up to width 64: the gradient row of a single-edge pair is not stored per pair; the
     # backward typed linear reads att_e * dOut[dst_e] through a row selector (one index per pair; ds_src[p] and
     # the scale come as one pair of floats per pair)
-    sel = layer == "rgat" and H == 1 and d <= 64
+    sel = bool(sched.get("row_select", layer == "rgat" and H == 1 and d <= 64)) and layer == "rgat"
+    fused = bool(sched.get("fused_softmax", layer == "rgat" and H == 1))       # single-head RGAT: softmax inside the walks
     pair_fwd = ("mfma", P * (2 * row + 4) + R * w2, 2.0 * P * d * d)        # gathered row + stored row + pair_src
     pair_bwd = ("mfma", P * (3 * row + 4) + R * w2, 4.0 * P * d * d)        # dY row + gathered row + stored row
     node_fwd = ("mfma", N * (2 * row + 4) + T * w2, 2.0 * N * d * d)
@@ -62,16 +129,19 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
     agg_pair = ("hbm", E * (row + 8 + 4 * H) + P * (row + 8), 2.0 * E * d)    # row + out_epos + out_dst + coefficient(s)
     table = {
         # RGAT: + s_src per pair and head; backward also reads ds_src
-        "typed_linear_fwd": ("mfma", pair_fwd[1] + (P * 4 * H if layer == "rgat" else 0), pair_fwd[2]),
+        "typed_linear_fwd": ("mfma", pair_fwd[1] + (P * 4 * H if layer == "rgat" and not fused else 0), pair_fwd[2]),
         "typed_linear_bwd": ("mfma", pair_bwd[1] + (P * 4 if layer == "rgat" else 0) + (P * 8 if sel else 0), pair_bwd[2]),
         "self_loop_fwd": ("mfma", N * 3 * r32 + w2, 2.0 * N * d * d),         # X row + out row read and written
         "self_loop_bwd": ("mfma", N * 3 * r32 + w2, 4.0 * N * d * d),
-        "aggregate_fwd": agg_dst,
+        # fused single-head RGAT walk: row + in_pair + in_rel + in_run per edge, s_dst per run, out row + (m, s) + item per node
+        "aggregate_fwd": ("hbm", E * (row + 12) + Q * 4 + N * (r32 + 16), 4.0 * E * d) if fused else agg_dst,
         # the same sum edge by edge with atomic adds: + in_run and run_dst per edge, and the zero fill
         "aggregate_fwd_edge_parallel": ("hbm", agg_dst[1] + E * 8 + N * r32, 2.0 * E * d),
         # per edge: Hs row + in_pair + att + (att, dz) store; per node: dOut row + out row + item;
         # per single-edge pair (P1 of them): ds_src and its G row, or with the row selector att_e only
-        "edge_dot_bwd": ("hbm", E * (row + 16) + N * (2 * row + 8) + P1 * ((4 if sel else row) + 4), 2.0 * E * d),
+        # (fused: att is recomputed, so in_rel, in_run and s_dst are read instead of att, and (m, s) per node)
+        "edge_dot_bwd": ("hbm", E * (row + 20) + Q * 4 + N * (2 * row + 16) + P1 * ((4 if sel else row) + 4), 4.0 * E * d) if fused
+                        else ("hbm", E * (row + 16) + N * (2 * row + 8) + P1 * ((4 if sel else row) + 4), 2.0 * E * d),
         # RGAT: only the E - P1 edges of the P - P1 pairs with several edges; coefficient = the (att, dz) pair;
         # with one head the walk also writes ds_src per pair.
         # RGCN: every edge; row + out_dst + coefficient
@@ -86,7 +156,8 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
         "node_grad_sum": ("hbm", P * (row + 4) + (Q * 8 if layer == "rgat" else 0) + N * (out_dst + 8), 1.0 * P * d),
         # per edge: in_pair, in_run, s_src, s_dst, att write (reads of its own writes not counted)
         "edge_softmax": ("hbm", E * 20 + N * 8, 10.0 * E),
-        "run_logit": ("hbm", Q * (row + 12), 2.0 * Q * d),
+        # per run: run_dst, run_rel, s_dst; per destination with edges: its X row (its runs are adjacent)
+        "run_logit": ("hbm", Q * 12 + n_dst * row, 2.0 * Q * d),
         # HGT
         "node_linear_k": node_fwd, "node_linear_q": node_fwd, "node_linear_v": node_fwd, "node_linear_out": node_fwd,
         "node_linear_k_bwd": node_bwd, "node_linear_q_bwd": node_bwd, "node_linear_v_bwd": node_bwd,
@@ -109,10 +180,10 @@ def make_layer(c, g, heads=0, flags=0):
         L = RgatLayer(g, d, c["slope"], dtype=dt, heads=max(heads, 1), flags=flags)
         L.load(c["X"], c["W"], c["w_s"], c["w_t"], c["dOut"])
     elif c["layer"] == "rgcn":
-        L = RgcnLayer(g, d, c["norm"], "none", False, dtype=dt)
+        L = RgcnLayer(g, d, c["norm"], "none", False, dtype=dt, flags=flags)
         L.load(c["X"], c["W"], None, c["dOut"])
     else:
-        L = HgtLayer(g, d, c["H"], with_mu=False, dtype=dt)
+        L = HgtLayer(g, d, c["H"], with_mu=False, dtype=dt, flags=flags)
         L.load(c["X"], c["Wk"], c["Wq"], c["Wv"], c["Wo"], c["Watt"], c["Wmsg"], None, c["dOut"])
     return L
 
@@ -211,6 +282,12 @@ def main():
     ap.add_argument("--heads", type=int, default=0, help="RGAT workloads: number of attention heads (default 1)")
     ap.add_argument("--edge-parallel", action="store_true",
                     help="single-head RGAT: forward aggregation edge by edge with atomic adds (comparison schedule)")
+    ap.add_argument("--no-batched", action="store_true", help="force the general walk for every segment (desc.flags)")
+    ap.add_argument("--no-row-select", action="store_true",
+                    help="write the gradient rows of single-edge pairs per pair instead of reading them through the row selector")
+    ap.add_argument("--no-folding", action="store_true", help="HGT: keep node linears and per-relation matrices apart")
+    ap.add_argument("--separate-softmax", action="store_true",
+                    help="single-head RGAT: edge softmax as a pass of its own with one attention weight per edge")
     ap.add_argument("--fwd-only", action="store_true",
                     help="time the forward call alone (inference: no saved buffer is kept)")
     ap.add_argument("--graph", action="store_true",
@@ -267,9 +344,15 @@ def main():
     P1 = int(g.info.num_single_pairs) if c["layer"] in ("rgat", "rgcn") else 0
     print(f"[bench] graph index built in {time.time() - t0:.1f}s: P/E={P / E:.3f} Q/E={Q / E:.3f} "
           f"max in-degree {g.info.max_in_degree} index {g.info.index_bytes / 2**20:.0f} MiB", file=sys.stderr, flush=True)
-    if args.edge_parallel and (c["layer"] != "rgat" or args.heads > 1):
-        sys.exit("bench.py --edge-parallel: single-head RGAT workloads only")
-    L = make_layer(c, g, args.heads, 1 if args.edge_parallel else 0)
+    if (args.edge_parallel or args.separate_softmax) and (c["layer"] != "rgat" or args.heads > 1):
+        sys.exit("bench.py --edge-parallel / --separate-softmax: single-head RGAT workloads only")
+    flags = ((B.RGNN_FLAG_EDGE_PARALLEL_AGGREGATION if args.edge_parallel else 0) | (B.RGNN_FLAG_NO_BATCHED_WALKS if args.no_batched else 0)
+             | (B.RGNN_FLAG_NO_ROW_SELECT if args.no_row_select else 0) | (B.RGNN_FLAG_NO_WEIGHT_FOLDING if args.no_folding else 0)
+             | (B.RGNN_FLAG_SEPARATE_SOFTMAX if args.separate_softmax else 0))
+    L = make_layer(c, g, args.heads, flags)
+    sched = B.rgnn_schedule(g.handle, {"rgcn": B.RGNN_LAYER_RGCN, "rgat": B.RGNN_LAYER_RGAT, "hgt": B.RGNN_LAYER_HGT}[c["layer"]], L.desc)
+    n_dst = int(np.count_nonzero(np.bincount(c["dst"], minlength=N)))
+    print(f"[bench] schedule picked by the library (flags {flags}): {sched}", file=sys.stderr, flush=True)
 
     def step():
         L.fwd()
@@ -341,10 +424,12 @@ def main():
             parity[k] = float(np.abs(a - want[k]).max() / max(np.abs(want[k]).max(), 1e-30))
         print(f"[bench] max relative error vs oracle: {parity}", file=sys.stderr, flush=True)
 
+    half = c["dtype"] == "bf16" and d == 128
+    work = lambda name: algorithmic_work(name, E, N, P, Q, R, T, d, H, P1, c["dtype"] == "bf16", c["layer"], sched, n_dst)
     kernels = []
     for name, (n, ms) in rep.items():
         avg_ms = ms / n
-        w = algorithmic_work(name, E, N, P, Q, R, T, d, H, P1, c["dtype"] == "bf16", c["layer"])
+        w = work(name)
         row = {"name": name, "launches_per_step": n / args.steps, "avg_ms": avg_ms, "ms_per_step": ms / args.steps}
         if w:
             row["GBps"] = w[1] / avg_ms / 1e6
@@ -357,36 +442,31 @@ def main():
             gb=f"{r['GBps']:.0f}" if "GBps" in r else "-", tf=f"{r['TFLOPs']:.1f}" if "TFLOPs" in r else "-", **r),
             file=sys.stderr, flush=True)
     dom = kernels[0]
-    w = algorithmic_work(dom["name"], E, N, P, Q, R, T, d, H, P1, c["dtype"] == "bf16", c["layer"])
+    w = work(dom["name"])
+    mfma_peak = BF16_MFMA_PEAK_TFLOPS if half else FP32_MFMA_PEAK_TFLOPS
     if w and w[0] == "mfma":
-        roof = {"kernel": dom["name"], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": FP32_MFMA_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": dom["TFLOPs"] / FP32_MFMA_PEAK_TFLOPS, "traffic": None}
+        roof = {"kernel": dom["name"], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": mfma_peak,
+                "unit": "TFLOP/s", "frac": dom["TFLOPs"] / mfma_peak, "traffic": None}
     else:
         gb = dom.get("GBps", 0.0)
         roof = {"kernel": dom["name"], "bound": "hbm", "achieved": gb, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": gb / HBM_PEAK_GBS, "traffic": None}
-    # HBM bytes per launch from rocprofv3 counters (two --pmc runs of this same command, calibrated
-    # against the 1 GiB copy above); only valid for the full-size default workload.
-    tsv = os.path.join(ROOT, "profiles", "rgat_c3_hbm_traffic_per_label.txt")
-    if args.config == 3 and args.scale == 1.0 and os.path.exists(tsv):
-        for ln in open(tsv):
-            f = ln.rstrip("\n").split("\t")
-            if not ln.startswith("#") and f[0] == dom["name"]:
-                roof["traffic"] = float(f[1]) + float(f[2])
+    # HBM bytes per launch from rocprofv3 counters: not measurable from inside this process, so they come from the
+    # committed summary of two --pmc runs of this same command (calibrated against the 1 GiB copy above), and only
+    # while that summary was taken from the kernel sources this run uses.
+    sha = library_sha16()
+    default_run = args.config == 3 and args.scale == 1.0 and flags == 0 and args.heads <= 1 and not args.dtype and not fwd_only
+    if default_run:
+        roof["traffic"], roof["traffic_source"] = counter_traffic(dom["name"], sha)
+    else:
+        roof["traffic_source"] = "no counter summary is kept for this workload / schedule"
     roof["avg_ms"] = dom["avg_ms"]
     roof["algorithmic_bytes"] = w[1] if w else None
-    # the same for the forward edge-traversal kernel (weighted gather-sum over the destination-major CSR),
-    # the HBM-bound counterpart of the typed linear
-    trav = next((k for k in kernels if k["name"] == "aggregate_fwd" and "GBps" in k), None)
-    roof_trav = None
-    if trav:
-        roof_trav = {"kernel": "aggregate_fwd", "bound": "hbm", "achieved": trav["GBps"], "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": trav["GBps"] / HBM_PEAK_GBS, "traffic": None, "avg_ms": trav["avg_ms"]}
-        if args.config == 3 and args.scale == 1.0 and os.path.exists(tsv):
-            for ln in open(tsv):
-                f = ln.rstrip("\n").split("\t")
-                if not ln.startswith("#") and f[0] == "aggregate_fwd":
-                    roof_trav["traffic"] = float(f[1]) + float(f[2])
+    kern_ms = {k["name"]: k["ms_per_step"] for k in kernels}
+    steps_roof = step_rooflines(kern_ms, E, N, P, P1, d) if c["layer"] == "rgat" and H == 1 and not fwd_only else None
+    if steps_roof:
+        for k, v in steps_roof.items():
+            print(f"[bench] {k:24s} {v['ms']:.3f} ms  {v['achieved']:.0f} GB/s = {v['frac']:.2f} of HBM peak", file=sys.stderr, flush=True)
 
     line = {
         "metric": f"edges/sec for {c['layer'].upper()} layer {'fwd' if fwd_only else 'fwd+bwd'}",
@@ -401,7 +481,9 @@ def main():
                                + ("" if args.scale == 1.0 else f" (scale {args.scale})"),
                    "P_over_E": P / E, "Q_over_E": Q / E, "max_in_degree": int(g.info.max_in_degree)},
         "roofline": roof,
-        "roofline_traversal": roof_trav,
+        "roofline_steps": steps_roof,
+        "schedule": sched,
+        "lib_sha16": sha,
         "cpu_baseline": cpu,
         "ms_per_step_without_profiling_events": clean_ms,
         "parity_max_rel_err": parity,

@@ -18,8 +18,13 @@ def test_algorithmic_work_counts():
     import bench
     E, N, P, Q, R, T, d, H, P1 = 1000, 100, 700, 400, 5, 1, 64, 1, 500
     row = d * 4
+    # single-head RGAT: the fused walk reads row + three indices per edge, s_dst per run; out row + (m, s) + item per node
     bound, nbytes, flops = bench.algorithmic_work("aggregate_fwd", E, N, P, Q, R, T, d, H, P1)
-    assert bound == "hbm" and nbytes == E * (row + 8) + N * (row + 8) and flops == 2.0 * E * d
+    assert bound == "hbm" and nbytes == E * (row + 12) + Q * 4 + N * (row + 16) and flops == 4.0 * E * d
+    # with the softmax in a pass of its own (or several heads): row + pair id + one weight per edge and head
+    sep = bench.algorithmic_work("aggregate_fwd", E, N, P, Q, R, T, d, H, P1, sched={"fused_softmax": 0, "row_select": 1})
+    assert sep[1] == E * (row + 8) + N * (row + 8) and sep[2] == 2.0 * E * d
+    assert bench.algorithmic_work("typed_linear_fwd", E, N, P, Q, R, T, d, H, P1)[1] == P * (2 * row + 4) + R * d * d * 4
     bound, nbytes, flops = bench.algorithmic_work("typed_linear_bwd", E, N, P, Q, R, T, d, H, P1)
     assert bound == "mfma" and flops == 4.0 * P * d * d
     # dY row + gathered X row + stored row, the gather index, the row selector and the (ds_src, scale) pair per row
@@ -27,8 +32,17 @@ def test_algorithmic_work_counts():
     # a single-edge pair costs the edge-dot kernel two scalars, not a row, where the row selector is used
     with_sel = bench.algorithmic_work("edge_dot_bwd", E, N, P, Q, R, T, d, H, P1)[1]
     without = bench.algorithmic_work("edge_dot_bwd", E, N, P, Q, R, T, 128, H, P1)[1]
-    assert with_sel == E * (row + 16) + N * (2 * row + 8) + P1 * 8
-    assert without == E * (512 + 16) + N * (2 * 512 + 8) + P1 * (512 + 4)
+    assert with_sel == E * (row + 20) + Q * 4 + N * (2 * row + 16) + P1 * 8
+    assert without == E * (512 + 20) + Q * 4 + N * (2 * 512 + 16) + P1 * (512 + 4)
+    # reuse that is structural is not charged: the runs of a destination are adjacent, its row is read once
+    assert bench.algorithmic_work("run_logit", E, N, P, Q, R, T, d, H, P1, n_dst=90)[1] == Q * 12 + 90 * row
+    # the small reduce / combine / finish kernels carry no byte model (and so no GB/s figure)
+    for name in ("typed_linear_bwd.reduce", "aggregate_fwd.combine", "edge_softmax.finish", "node_linear_q_bwd.reduce"):
+        assert bench.algorithmic_work(name, E, N, P, Q, R, T, 128, 4, 0, bf16=True, layer="hgt") is None
+    # HGT with bf16 rows: the query linear's backward accumulates into dX only on the unfolded path
+    acc = bench.algorithmic_work("node_linear_q_bwd", E, N, P, Q, R, T, 128, 4, 0, bf16=True, layer="hgt", sched={"hgt_folded": 0})[1]
+    fold = bench.algorithmic_work("node_linear_q_bwd", E, N, P, Q, R, T, 128, 4, 0, bf16=True, layer="hgt", sched={"hgt_folded": 1})[1]
+    assert acc - fold == N * 512
     # bf16 rows at width 128 halve the row bytes of the intermediates
     half = bench.algorithmic_work("aggregate_fwd", E, N, P, Q, R, T, 128, 4, 0, bf16=True, layer="hgt")[1]
     assert half == E * (256 + 4 + 16) + N * (256 + 8)
@@ -57,5 +71,30 @@ def test_bench_line_has_the_contract_fields():
     roof = d["roofline"]
     assert roof["bound"] in ("hbm", "mfma", "alu") and roof["unit"] in ("GB/s", "TFLOP/s")
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9 and "traffic" in roof
+    assert "traffic_source" in roof and d["lib_sha16"] and d["schedule"]["fused_softmax"] == 1
+    # no kernel is priced above the machine: algorithmic GB/s within the HBM peak, TFLOP/s within the fp32 MFMA peak
+    for k in d["kernels"]:
+        assert k.get("GBps", 0.0) <= 8000.0 and k.get("TFLOPs", 0.0) <= 157.3, k
+    for k, v in d["roofline_steps"].items():
+        assert 0.0 < v["frac"] <= 1.0 and abs(v["achieved"] - v["bytes"] / v["ms"] / 1e6) < 1e-6 * v["achieved"], k
+    assert set(d["roofline_steps"]) == {"S3_traversal_fwd", "S4_traversal_bwd_dst", "S5_traversal_bwd_pair"}
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["unit"] == "edges/s" and cpu["sample"]
+
+
+def test_counter_traffic_is_tied_to_the_kernel_sources(tmp_path, monkeypatch):
+    """roofline.traffic comes from a committed counter summary and is dropped (null, with the reason) as soon as the
+    summary was taken from other kernel sources than the ones in the tree."""
+    sys.path.insert(0, ROOT)
+    import bench
+    sha = bench.library_sha16()
+    assert len(sha) == 16 and sha == bench.library_sha16()
+    f = tmp_path / "traffic.txt"
+    monkeypatch.setattr(bench, "TRAFFIC_TSV", str(f))
+    f.write_text(f"# header\n# lib_sha16: {sha}\ntyped_linear_bwd\t3000\t2000\n")
+    val, src = bench.counter_traffic("typed_linear_bwd", sha)
+    assert val == 5000.0 and "not measured by this run" in src
+    assert bench.counter_traffic("edge_dot_bwd", sha)[0] is None
+    f.write_text("# lib_sha16: 0123456789abcdef\ntyped_linear_bwd\t3000\t2000\n")
+    val, src = bench.counter_traffic("typed_linear_bwd", sha)
+    assert val is None and "stale" in src
