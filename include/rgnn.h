@@ -141,7 +141,11 @@ const char* rgnn_last_error(void);
  *
  * Edges may be in any order, with duplicates and self-loops.  The index is
  * canonical: destination-major CSR sorted by (dst, rel, src, input edge id);
- * pair ids are ranks in ascending (rel, src) order.  Synchronises the device.
+ * pair ids are ranks in ascending (rel, src) order.
+ * Streams: the build runs on the default (NULL) stream and the call returns only after
+ * hipDeviceSynchronize(), so on return the index is complete and may be used by layer calls on
+ * any stream without further ordering; work the caller has in flight on other streams is waited
+ * for as well.  It is the one call that allocates device memory (freed by rgnn_graph_destroy).
  * Errors: EINVAL for NULLs / negative sizes / ids out of range / type mismatch,
  * EUNSUPPORTED for E >= 2^31 or N*N*R >= 2^63, ENOMEM, EHIP.  *g is NULL on failure.
  */

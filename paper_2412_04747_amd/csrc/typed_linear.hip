@@ -491,8 +491,8 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
 // dW[s] (and Avec[s]) = sum of the partial slots of segment s, in slot order.
 __global__ void slot_reduce_kernel(const float* __restrict__ part, const int32_t* __restrict__ seg_slot_ptr,
                                    int kn, int kd, float* __restrict__ dW, float* __restrict__ Avec) {
-    const int seg = blockIdx.y;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int seg = blockIdx.x;                 // segments on the x dimension: their count has no 65535 limit there
+    const int i = blockIdx.y * blockDim.x + threadIdx.x;
     const int slot_sz = kn + kd;
     if (i >= slot_sz) return;
     // four partial sums keep four loads in flight; they are combined in a fixed order
@@ -676,7 +676,7 @@ size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t) {
 static rgnn_status_t launch_slot_reduce(int kd, int nd, const TypedLinearBwdArgs& a, hipStream_t st) {
     const int kn = kd * nd;
     KernelTimer kt(st, "typed_linear_bwd.reduce");
-    hipLaunchKernelGGL(slot_reduce_kernel, dim3((kn + kd + 255) / 256, a.tiles->num_segs), dim3(256), 0, st, a.part,
+    hipLaunchKernelGGL(slot_reduce_kernel, dim3(a.tiles->num_segs, (kn + kd + 255) / 256), dim3(256), 0, st, a.part,
                        a.tiles->seg_slot_ptr, kn, kd, a.dW, a.Avec);
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
@@ -758,7 +758,7 @@ rgnn_status_t typed_linear_slot_reduce(int d_in, int d_out, const TileList& tile
                                        float* Avec, hipStream_t st) {
     const int kn = d_in * d_out;
     KernelTimer kt(st, "typed_linear_bwd.reduce");
-    hipLaunchKernelGGL(slot_reduce_kernel, dim3((kn + d_in + 255) / 256, tiles.num_segs), dim3(256), 0, st, part,
+    hipLaunchKernelGGL(slot_reduce_kernel, dim3(tiles.num_segs, (kn + d_in + 255) / 256), dim3(256), 0, st, part,
                        tiles.seg_slot_ptr, kn, d_in, dW, Avec);
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;

@@ -213,3 +213,38 @@ def test_graph_without_nodes_and_layers_on_it():
     for k, t in H.grads().items():
         assert float(t.abs().sum()) == 0.0, k
     g.close()
+
+
+def test_graph_create_stream_contract():
+    """rgnn_graph_create runs on the default stream and synchronises the device before it returns: the index is
+    complete on return, whatever the caller has in flight on other streams, and layer calls on any stream may
+    use it at once."""
+    import torch
+    from paper_2412_04747_amd.harness import Graph, RgatLayer
+    N, R, E, d = 5000, 7, 60000, 64
+    rng, src, dst, rel, _ = synth.tiny(41, N=N, R=R, E=E)
+    p = synth.rgat_params(rng, N, R, d, d)
+    side, other = torch.cuda.Stream(), torch.cuda.Stream()
+    a = torch.randn(4096, 4096, device="cuda")
+    with torch.cuda.stream(side):                   # a few hundred milliseconds of work in flight on a side stream
+        for _ in range(40):
+            a = a @ a * 1e-3
+    g = Graph(N, R, src, dst, rel)                  # returns with everything, the side stream's work included, finished
+    assert side.query()
+    ix = graph_index.build(N, R, src, dst, rel)
+    for name in ("in_ptr", "in_pair", "out_epos", "srcpair_idx"):
+        assert np.array_equal(g.export(name), ix[name]), name
+    L = RgatLayer(g, d)
+    L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
+    L.fwd(); L.bwd()
+    torch.cuda.synchronize()
+    ref = {k: v.clone() for k, v in dict(out=L.out, **L.grads()).items()}
+    g2 = Graph(N, R, src, dst, rel)                 # a second index, used straight away from a non-default stream
+    L2 = RgatLayer(g2, d)
+    with torch.cuda.stream(other):
+        L2.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
+        L2.fwd(); L2.bwd()
+    other.synchronize()
+    for k, v in dict(out=L2.out, **L2.grads()).items():
+        assert torch.equal(v, ref[k]), k
+    g.close(); g2.close()

@@ -76,6 +76,18 @@ def test_single_head_bf16_inputs(d):
     _run(600, 5, src, dst, rel, p, d, f"bf16-d{d}", dtype="bf16")
 
 
+def test_more_relations_than_a_grid_dimension_holds():
+    """70,000 relations, nearly all without an edge: per-relation launches must not put the relation index on a grid
+    dimension limited to 65,535, and w_s (9 MB) no longer fits in LDS, so the fused walks read it through the caches."""
+    N, R, E, d = 300, 70000, 3000, 32
+    rng = np.random.default_rng(97)
+    src, dst = rng.integers(0, N, E).astype(np.int32), rng.integers(0, N, E).astype(np.int32)
+    rel = rng.choice(np.array([0, 1, 65534, 65535, 65536, 69999]), E).astype(np.int32)
+    dst[:700] = 5
+    p = synth.rgat_params(rng, N, R, d, d)
+    _run(N, R, src, dst, rel, p, d, "R=70000", check_saved=False)
+
+
 def test_many_single_edge_destinations():
     """Thousands of destinations with exactly one incoming edge (softmax weight 1) next to a few
     busier ones: the batched single-entry aggregation path."""
