@@ -209,7 +209,7 @@ typedef struct {
     int32_t rows_bf16;           /* intermediate row tensors stored as bfloat16 */
     int32_t row_select;          /* single-edge pairs: gradient row read through the row selector, not materialised */
     int32_t hgt_folded;          /* HGT key / message linears folded into the per-relation weights */
-    int32_t fused_softmax;       /* single-head RGAT: edge softmax fused into the aggregation walk */
+    int32_t fused_softmax;       /* RGAT: edge softmax fused into the aggregation walk */
     int32_t ws_in_lds;           /* ... with w_s held in LDS */
     int32_t edge_parallel;       /* forward aggregation edge by edge with atomic adds */
     int32_t dst_batched_single;  /* destination-major walk: batched kernel phase for destinations with one edge */
@@ -252,13 +252,11 @@ rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc
  * Nodes without incoming edges get 0.
  * Backward writes dX [N, d_in], dW [R, d_in, d_out], dw_s, dw_t [R, d_out].
  * Layout of `saved` after the forward (exposed for tests), each part starting at a
- * multiple of 256 bytes: Hs [P, d_out] fp32, the compact messages; then, for one
- * head, s_dst [Q] fp32, the destination half ht . w_t[r] of the logit per
- * (destination, relation) run, and ms [N, 2] fp32 = (max_e l_e, sum_e exp(l_e - max))
- * over the incoming edges of each destination that has any, l_e = leakyrelu(z_e): the
- * attention weight of an edge is exp(l_e - m) / s and is recomputed by the backward
- * call; for several heads, att [E, H] fp32 in CSR order holding att_e with the sign
- * bit set when z_e <= 0.
+ * multiple of 256 bytes: Hs [P, d_out] fp32, the compact messages; s_dst [Q, H] fp32,
+ * the destination half ht . w_t[r] of the logit per (destination, relation) run and
+ * head; ms [N, H, 2] fp32 = (max_e l_e, sum_e exp(l_e - max)) per head over the incoming
+ * edges of each destination that has any, l_e = leakyrelu(z_e): the attention weight
+ * of an edge is exp(l_e - m) / s and is recomputed by the backward call.
  */
 rgnn_status_t rgnn_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc, const void* X, const void* W,
                             const void* w_s, const void* w_t, void* out, void* saved, void* workspace,

@@ -91,10 +91,9 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
 }
 
 // ---- RGAT buffers -----------------------------------------------------------------------
-// Single head: Hs, the destination halves of the logits per run and (max, sum) of every destination's softmax.
-// Several heads: Hs and the attention weights per (edge, head).
-struct RgatSaved { float* Hs; float* att; float* s_dst; float* ms; };
-struct RgatFwdWs { float* wtp; float* s_src; float* s_dst; float* att; float* part_m; float* part_s; float* part_ms; float* partial; };
+// Hs, the destination halves of the logits per (run, head) and (max, sum) of every (destination, head) softmax.
+struct RgatSaved { float* Hs; float* s_dst; float* ms; };
+struct RgatFwdWs { float* wtp; float* s_src; float* att; float* part_m; float* part_s; float* part_ms; float* partial; };
 struct RgatBwdWs {
     float* wtp; float* wsp; float* adz; float* ds_dst; float* ds_src; float* G; float* dXp; float* A; float* U;
     float* tl_part; float* partial;
@@ -103,38 +102,28 @@ struct RgatBwdWs {
 // the typed-linear backward reads att_e * dOut[dst_e] through its row selector.
 inline bool rgat_row_select(const rgnn_layer_desc_t* d) { return sched_row_select(RGNN_LAYER_RGAT, d->dtype, d->d_out, d->heads, d->flags); }
 inline bool rgat_edge_parallel(const rgnn_layer_desc_t* d) { return (d->flags & RGNN_FLAG_EDGE_PARALLEL_AGGREGATION) != 0; }
-inline bool rgat_fused(const rgnn_layer_desc_t* d) { return sched_fused_softmax(d->heads, d->flags); }
+inline bool rgat_fused(const rgnn_layer_desc_t* d) { return sched_fused_softmax(d->flags); }
 
 size_t carve_rgat_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatSaved* s) {
     Carver c(base);
     s->Hs = c.take<float>((size_t)g->P * d->d_out);
-    s->att = s->s_dst = s->ms = nullptr;
-    if (d->heads > 1) {
-        s->att = c.take<float>((size_t)g->E * d->heads);
-    } else {
-        s->s_dst = c.take<float>((size_t)g->Q);
-        s->ms = c.take<float>(2 * (size_t)g->N);
-    }
+    s->s_dst = c.take<float>((size_t)g->Q * d->heads);
+    s->ms = c.take<float>(2 * (size_t)g->N * d->heads);
     return c.off;
 }
 size_t carve_rgat_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgatFwdWs* w) {
     Carver c(base);
     const size_t H = d->heads, parts = (size_t)g->dst_items.num_partials;
     w->wtp = c.take<float>(H * g->R * d->d_in);
-    w->s_src = w->s_dst = w->att = w->part_m = w->part_s = w->part_ms = nullptr;
-    if (H > 1) {
-        w->s_src = c.take<float>((size_t)g->P * H);
-        w->s_dst = c.take<float>((size_t)g->Q * H);
-        w->part_m = c.take<float>(parts * H);
-        w->part_s = c.take<float>(parts * H);
-    } else if (!rgat_fused(d)) {
-        // the comparison schedules: per-pair source logits, a softmax pass of its own, attention weights per edge
+    w->s_src = w->att = w->part_m = w->part_s = w->part_ms = nullptr;
+    if (!rgat_fused(d)) {
+        // the comparison schedules (one head): per-pair source logits, a softmax pass of its own, attention weights per edge
         w->s_src = c.take<float>((size_t)g->P);
         w->att = c.take<float>((size_t)g->E);
         w->part_m = c.take<float>(parts);
         w->part_s = c.take<float>(parts);
     } else {
-        w->part_ms = c.take<float>(2 * parts);
+        w->part_ms = c.take<float>(2 * parts * H);
     }
     w->partial = c.take<float>(parts * d->d_out);
     return c.off;
@@ -144,7 +133,7 @@ size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
     const size_t H = d->heads;
     w->wtp = c.take<float>(H * g->R * d->d_in);
     w->wsp = c.take<float>((size_t)g->R * d->d_in);
-    w->adz = c.take<float>((size_t)g->E * std::max<size_t>(2, H));   // (att, dz) pairs, or dz per head
+    w->adz = c.take<float>((size_t)g->E * 2 * H);                    // per edge: att per head, then dz per head
     w->ds_dst = c.take<float>((size_t)g->Q * H);
     // with the row selector: (ds_src[p], att of the pair's only edge) interleaved, one pair of floats per p
     w->ds_src = c.take<float>(rgat_row_select(d) ? 2 * (size_t)g->P : (size_t)g->P * H);
@@ -542,21 +531,6 @@ static rgnn_status_t rgat_fwd_impl(const rgnn_graph_t* g, const rgnn_layer_desc_
     w_t = stg.in(w_t, (size_t)g->R * D);
     RGNN_TRY(stg.status);
     carve_rgat_saved(g, desc, saved, &sv);
-    if (desc->heads > 1) {
-        // Multi-head: the same steps with one logit, one softmax and one weight per (edge, head).
-        const int H = desc->heads;
-        const float *Xf = static_cast<const float*>(X), *Wf = static_cast<const float*>(W);
-        TypedLinearArgs a{};
-        a.tiles = &g->pair_tiles_wide; a.X = Xf; a.gather = g->idx[RGNN_IDX_PAIR_SRC]; a.W = Wf; a.Y = sv.Hs;
-        a.vec = static_cast<const float*>(w_s); a.s_out = w.s_src; a.s_heads = H;   // s_src[p][h] = Hs[p] . w_s[r] per slice
-        RGNN_TRY(typed_linear_fwd(K, D, a, st));
-        RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, static_cast<const float*>(w_t), w.wtp, st));
-        RGNN_TRY(run_logit_heads(g, K, H, Xf, w.wtp, w.s_dst, st));
-        RGNN_TRY(edge_logit_heads(g, H, w.s_src, w.s_dst, desc->slope, sv.att, st));
-        RGNN_TRY(hgt_softmax(g, H, sv.att, w.part_m, w.part_s, st, 1));
-        return gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, H, 1, sv.Hs, out, w.partial, st, 0,
-                          "aggregate_fwd", "aggregate_fwd.combine", H);
-    }
     const float *Xf = static_cast<const float*>(X), *Wf = static_cast<const float*>(W);
     const bool fused = rgat_fused(desc);
     // 1. compact messages: Hs[p] = X[pair_src[p]] W[r]
@@ -565,9 +539,15 @@ static rgnn_status_t rgat_fwd_impl(const rgnn_graph_t* g, const rgnn_layer_desc_
     a.tiles = &g->pair_tiles_wide; a.X = Xf; a.gather = g->idx[RGNN_IDX_PAIR_SRC]; a.W = Wf; a.Y = sv.Hs;
     if (!fused) { a.vec = static_cast<const float*>(w_s); a.s_out = w.s_src; }
     RGNN_TRY(typed_linear_fwd(K, D, a, st));
-    // 2. destination half, once per (dst, rel) run, reordered: s_dst[q] = X[dst] . (W[r] w_t[r])
-    RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_t), w.wtp, st));
-    RGNN_TRY(run_logit(g, K, Xf, w.wtp, sv.s_dst, st));
+    // 2. destination half, once per (dst, rel) run, reordered: s_dst[q] = X[dst] . (W[r] w_t[r])  (per head: the head's columns)
+    const int H = desc->heads;
+    if (H > 1) {
+        RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, static_cast<const float*>(w_t), w.wtp, st));
+        RGNN_TRY(run_logit_heads(g, K, H, Xf, w.wtp, sv.s_dst, st));
+    } else {
+        RGNN_TRY(fold_weight(g->R, K, D, Wf, static_cast<const float*>(w_t), w.wtp, st));
+        RGNN_TRY(run_logit(g, K, Xf, w.wtp, sv.s_dst, st));
+    }
     if (!fused) {
         // 3'. edge softmax in a pass of its own (one attention weight per edge, and (max, sum) per destination for the
         //     backward call), then the weighted sum: by the destination-segment walk, or edge by edge with atomic adds
@@ -577,7 +557,7 @@ static rgnn_status_t rgat_fwd_impl(const rgnn_graph_t* g, const rgnn_layer_desc_
                           w.partial, st, 0, "aggregate_fwd", "aggregate_fwd.combine");
     }
     // 3. one walk per destination: logit from the gathered row, running-maximum softmax, weighted sum
-    return rgat_aggregate_fwd(g, D, sv.Hs, static_cast<const float*>(w_s), sv.s_dst, desc->slope, static_cast<float*>(out),
+    return rgat_aggregate_fwd(g, D, H, sv.Hs, static_cast<const float*>(w_s), sv.s_dst, desc->slope, static_cast<float*>(out),
                               sv.ms, w.partial, w.part_ms, st);
 }
 
@@ -607,17 +587,18 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     if (desc->heads > 1) {
         const int H = desc->heads;
         const float *ws = static_cast<const float*>(w_s), *wt = static_cast<const float*>(w_t);
-        float* dz = w.adz;                                   // [E][H]
-        // 1. dz[e][h] = |att| (dOut[v].Hs[pair_e] - dOut[v].out[v])_h * (z > 0 ? 1 : slope)
-        RGNN_TRY(hgt_edge_dot_bwd(g, D, H, sv.att, sv.Hs, dO, out, dz, st, 0, desc->slope));
-        // 2. per-head sums over runs and over pairs
-        RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], g->long_runs, nullptr, dz, H, 0, w.ds_dst, st,
+        // 1. per CSR edge and head: att recomputed from the gathered row and the saved (m, s), and
+        //    dz = att (dOut[v].Hs[pair_e] - dOut[v].out[v])_h * (z > 0 ? 1 : slope);  adz[e] = (att[0..H), dz[0..H))
+        RGNN_TRY(rgat_edge_dot_bwd(g, D, H, sv.Hs, ws, sv.s_dst, sv.ms, dO, static_cast<const float*>(out), desc->slope, w.adz,
+                                   nullptr, nullptr, nullptr, st));
+        // 2. per-head sums of dz over runs and over pairs
+        RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], g->long_runs, nullptr, w.adz, 2 * H, H, w.ds_dst, st,
                                     "ds_dst_sum", 0, H));
-        RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], dz, H, 0,
+        RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2 * H, H,
                                     w.ds_src, st, "ds_src_sum", 0, H));
-        // 3. dHs[p] = sum_{e in out(p)} |att_e| dOut[dst_e] (per head)  +  ds_src[p][h] w_s[r] (per head)
+        // 3. dHs[p] = sum_{e in out(p)} att_e dOut[dst_e] (per head)  +  ds_src[p][h] w_s[r] (per head)
         const Rank1 r1{w.ds_src, H, g->idx[RGNN_IDX_PAIR_REL], ws};      // the second term, added when a pair's row is stored
-        RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, sv.att, H, 1, dO, w.G,
+        RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.adz, 2 * H, 0, dO, w.G,
                             w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", H, 0, 0, &r1));
         // 4. dXp = dHs W^T, dW = sum X^T dHs
         TypedLinearBwdArgs b{};
@@ -641,7 +622,7 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     //    holds P pairs of floats and ds_src[p] is element 2 p.
     const bool sel = rgat_row_select(desc);
     const int dss = sel ? 2 : 1;
-    RGNN_TRY(rgat_edge_dot_bwd(g, D, sv.Hs, static_cast<const float*>(w_s), sv.s_dst, sv.ms, dO, static_cast<const float*>(out),
+    RGNN_TRY(rgat_edge_dot_bwd(g, D, 1, sv.Hs, static_cast<const float*>(w_s), sv.s_dst, sv.ms, dO, static_cast<const float*>(out),
                                desc->slope, w.adz, w.G, w.ds_src, sel ? w.ds_src : nullptr, st));
     // 2. ds_dst[q] = sum over the run's edges of dz
     RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], g->long_runs, nullptr, w.adz, 2, 1, w.ds_dst, st, "ds_dst_sum"));

@@ -1,4 +1,4 @@
-// Single-head RGAT traversal, forward and backward, with the edge softmax fused into the walks
+// RGAT traversal (one head or several), forward and backward, with the edge softmax fused into the walks
 // (thesis Ch.3 listing "attention calculation in a single-headed RGAT model": logit, softmax over
 // the incoming edges of a destination, weighted sum of the messages).
 //
@@ -11,6 +11,9 @@
 //
 // Backward, same walk: the edge's row is gathered again for g_e = dOut[v] . Hs[pair_e]; the logit is
 // recomputed from that row exactly as in the forward pass and att_e = exp(l_e - m_v) / s_v.
+//
+// Several heads: the D/4 lanes of a row split into H groups of LPH lanes, one per head (column slice); every
+// head has its own logit, running maximum and sum, and the reductions run over the head's LPH lanes only.
 //
 // Work distribution: persistent workgroups, each holding w_s in LDS, take the items of the
 // destination-major list (longest first) in a grid-stride loop; a group of D/4 lanes owns an item.
@@ -34,21 +37,22 @@ struct FusedArgs {
     const int32_t* in_run;    // [E]
     const float* Hs;          // [P][D]
     const float* w_s;         // [R][D]
-    const float* s_dst;       // [Q]
+    const float* s_dst;       // [Q][H]
     float slope;
     int R;
+    int own_singles;          // backward: the only edge of a single-edge pair writes that pair's entries (one head)
     // forward
     float* out;               // [N][D]
-    float2* ms;               // [N] (m, s) of the destination's softmax
+    float2* ms;               // [N][H] (m, s) of the destination's softmax
     float* partial;           // [num_partials][D] unnormalised sums of the pieces of cut destinations
-    float2* part_ms;          // [num_partials]
+    float2* part_ms;          // [num_partials][H]
     int general_n;            // items [0, skip_first) and [skip_first + skip_n, n) take the general walk
     int skip_first, skip_n;
     int short_first, short_n, single_first, single_n;
     // backward
     const float* dOut;        // [N][D]
     const float* fout;        // [N][D] forward output
-    float2* adz;              // [E] (att_e, dz_e)
+    float* adz;               // [E][2][H]: att_e per head, then dz_e per head
     float* G;                 // [P][D] (only without dsy)
     float* ds_src;            // [P]    (only without dsy)
     float2* dsy;              // [P] (dz_e, att_e) of the only edge of a single-edge pair
@@ -70,9 +74,10 @@ __device__ __forceinline__ float4 load_row_nt(const float* p) {
 // ---------------------------------------------------------------- forward
 
 // General items: any length, whole destinations or pieces of cut ones.
-template <int D, bool LDSW>
+template <int D, int LPH, bool LDSW>
 __device__ __forceinline__ void fwd_general(const FusedArgs& a, const float* ws_lds, int i, int c) {
-    constexpr int LPR = D / 4;
+    constexpr int LPR = D / 4, H = LPR / LPH;
+    const int head = c / LPH;
     const int b = a.it.beg[i], e = a.it.end[i];
     const int slot = a.it.slot[i];
     const size_t v = (size_t)a.it.row[i];
@@ -81,8 +86,10 @@ __device__ __forceinline__ void fwd_general(const FusedArgs& a, const float* ws_
     if (b < e) {
         // indices of chunk 0 (entries past the end repeat the last edge; they get weight zero)
         int jj = min(b + c, e - 1);
-        int cpr = a.in_pair[jj], crl = a.in_rel[jj];
-        float csd = a.s_dst[a.in_run[jj]];
+        // one head: lane c also fetches the destination half of edge c's logit; several heads: the run id, and every
+        // lane reads its own head's entry when the batch is formed
+        int cpr = a.in_pair[jj], crl = a.in_rel[jj], crn = a.in_run[jj];
+        float csd = H == 1 ? a.s_dst[crn] : 0.f;
         for (int jc = b; jc < e; jc += LPR) {
             const bool more = jc + LPR < e;
             int npr = cpr, nrl = crl, nrn = 0;
@@ -97,17 +104,19 @@ __device__ __forceinline__ void fwd_general(const FusedArgs& a, const float* ws_
             for (int k = 0; k < LPR; k += 4) {
                 if (k >= cend) break;
                 float4 h[4];
+                float sd[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int pr = group_lane<LPR>(cpr, k + u);
                     h[u] = load_row_nt(a.Hs + (size_t)pr * D + c * 4);
+                    if (H > 1) sd[u] = a.s_dst[(size_t)group_lane<LPR>(crn, k + u) * H + head];
                 }
                 __builtin_amdgcn_sched_barrier(0);      // the w_s rows are read when the message rows arrive, not held meanwhile
                 float l[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const float4 w = ws_row<D, LDSW>(a, ws_lds, group_lane<LPR>(crl, k + u), c);
-                    const float z = group_sum<LPR>(dot4(h[u], w)) + group_lane<LPR>(csd, k + u);
+                    const float z = group_sum<LPH>(dot4(h[u], w)) + (H == 1 ? group_lane<LPR>(csd, k + u) : sd[u]);
                     l[u] = k + u < cend ? leaky(z, a.slope) : -INFINITY;
                 }
                 const float mn = fmaxf(fmaxf(m, fmaxf(l[0], l[1])), fmaxf(l[2], l[3]));
@@ -123,9 +132,10 @@ __device__ __forceinline__ void fwd_general(const FusedArgs& a, const float* ws_
                 m = mn;
             }
             if (more) {
-                csd = a.s_dst[nrn];
+                if (H == 1) csd = a.s_dst[nrn];
                 cpr = npr;
                 crl = nrl;
+                crn = nrn;
             }
         }
     }
@@ -133,17 +143,18 @@ __device__ __forceinline__ void fwd_general(const FusedArgs& a, const float* ws_
     if (slot < 0) {
         const float inv = s > 0.f ? 1.f / s : 0.f;           // a destination without edges gets the zero row
         *reinterpret_cast<float4*>(a.out + v * D + c * 4) = make_float4(acc0.x * inv, acc0.y * inv, acc0.z * inv, acc0.w * inv);
-        if (c == 0) a.ms[v] = make_float2(b < e ? m : 0.f, b < e ? s : 1.f);
+        if (c % LPH == 0) a.ms[v * H + head] = make_float2(b < e ? m : 0.f, b < e ? s : 1.f);
     } else {
         *reinterpret_cast<float4*>(a.partial + (size_t)slot * D + c * 4) = acc0;
-        if (c == 0) a.part_ms[slot] = make_float2(m, s);
+        if (c % LPH == 0) a.part_ms[(size_t)slot * H + head] = make_float2(m, s);
     }
 }
 
 // Whole destinations with 2..kShortLen edges: two per lane group, every load of both independent.
-template <int D, bool LDSW>
+template <int D, int LPH, bool LDSW>
 __device__ __forceinline__ void fwd_short(const FusedArgs& a, const float* ws_lds, int g2, int c) {
-    constexpr int LPR = D / 4;
+    constexpr int LPR = D / 4, H = LPR / LPH;
+    const int head = c / LPH;
     const int i0 = 2 * g2;
     int b[2], e[2], orow[2];
 #pragma unroll
@@ -170,7 +181,7 @@ __device__ __forceinline__ void fwd_short(const FusedArgs& a, const float* ws_ld
 #pragma unroll
         for (int u = 0; u < kShortLen; ++u) {
             h[q][u] = load_row_nt(a.Hs + (size_t)pr[q][u] * D + c * 4);
-            sd[q][u] = a.s_dst[rn[q][u]];
+            sd[q][u] = a.s_dst[(size_t)rn[q][u] * H + head];
         }
     __builtin_amdgcn_sched_barrier(0);      // the w_s rows are read when the message rows arrive, not held meanwhile
 #pragma unroll
@@ -179,7 +190,7 @@ __device__ __forceinline__ void fwd_short(const FusedArgs& a, const float* ws_ld
 #pragma unroll
         for (int u = 0; u < kShortLen; ++u) {
             const float4 w = ws_row<D, LDSW>(a, ws_lds, rl[q][u], c);
-            const float z = group_sum<LPR>(dot4(h[q][u], w)) + sd[q][u];
+            const float z = group_sum<LPH>(dot4(h[q][u], w)) + sd[q][u];
             l[u] = b[q] + u < e[q] ? leaky(z, a.slope) : -INFINITY;
             m = fmaxf(m, l[u]);
         }
@@ -194,15 +205,16 @@ __device__ __forceinline__ void fwd_short(const FusedArgs& a, const float* ws_ld
         if (i0 + q < a.short_n) {
             const float inv = 1.f / s;
             *reinterpret_cast<float4*>(a.out + (size_t)orow[q] * D + c * 4) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
-            if (c == 0) a.ms[orow[q]] = make_float2(m, s);
+            if (c % LPH == 0) a.ms[(size_t)orow[q] * H + head] = make_float2(m, s);
         }
     }
 }
 
 // Whole destinations with one edge (attention weight 1): four per lane group.
-template <int D, bool LDSW>
+template <int D, int LPH, bool LDSW>
 __device__ __forceinline__ void fwd_single(const FusedArgs& a, const float* ws_lds, int g4, int c) {
-    constexpr int LPR = D / 4;
+    constexpr int LPR = D / 4, H = LPR / LPH;
+    const int head = c / LPH;
     const int i0 = 4 * g4;
     int j[4], orow[4], pr[4], rl[4], rn[4];
 #pragma unroll
@@ -222,16 +234,16 @@ __device__ __forceinline__ void fwd_single(const FusedArgs& a, const float* ws_l
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         h[u] = load_row_nt(a.Hs + (size_t)pr[u] * D + c * 4);
-        sd[u] = a.s_dst[rn[u]];
+        sd[u] = a.s_dst[(size_t)rn[u] * H + head];
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const float4 w = ws_row<D, LDSW>(a, ws_lds, rl[u], c);
-        const float z = group_sum<LPR>(dot4(h[u], w)) + sd[u];
+        const float z = group_sum<LPH>(dot4(h[u], w)) + sd[u];
         if (i0 + u < a.single_n) {
             *reinterpret_cast<float4*>(a.out + (size_t)orow[u] * D + c * 4) = h[u];
-            if (c == 0) a.ms[orow[u]] = make_float2(leaky(z, a.slope), 1.f);
+            if (c % LPH == 0) a.ms[(size_t)orow[u] * H + head] = make_float2(leaky(z, a.slope), 1.f);
         }
     }
 }
@@ -248,52 +260,62 @@ __device__ __forceinline__ const float* stage_ws(const FusedArgs& a) {
     return ws_lds;
 }
 
-template <int D, bool LDSW>
+template <int D, int LPH, bool LDSW>
 __global__ __launch_bounds__(kFusedThreads) void rgat_aggregate_fwd_kernel(FusedArgs a) {
     constexpr int LPR = D / 4, GPB = kFusedThreads / LPR;
     const float* ws_lds = stage_ws<D, LDSW>(a);
     const int grp = threadIdx.x / LPR, c = threadIdx.x % LPR;
     const int stride = gridDim.x * GPB, first = blockIdx.x * GPB + grp;
-    for (int i = first; i < a.general_n; i += stride) fwd_general<D, LDSW>(a, ws_lds, i >= a.skip_first ? i + a.skip_n : i, c);
-    for (int g2 = first; 2 * g2 < a.short_n; g2 += stride) fwd_short<D, LDSW>(a, ws_lds, g2, c);
-    for (int g4 = first; 4 * g4 < a.single_n; g4 += stride) fwd_single<D, LDSW>(a, ws_lds, g4, c);
+    for (int i = first; i < a.general_n; i += stride) fwd_general<D, LPH, LDSW>(a, ws_lds, i >= a.skip_first ? i + a.skip_n : i, c);
+    for (int g2 = first; 2 * g2 < a.short_n; g2 += stride) fwd_short<D, LPH, LDSW>(a, ws_lds, g2, c);
+    for (int g4 = first; 4 * g4 < a.single_n; g4 += stride) fwd_single<D, LPH, LDSW>(a, ws_lds, g4, c);
 }
 
 // Cut destinations: out[v] = sum_i exp(m_i - M) partial_i / S with M = max_i m_i, S = sum_i s_i exp(m_i - M) over the
-// destination's pieces i, in piece order.  One workgroup per cut destination.
-template <int D>
+// destination's pieces i, in piece order, per head.  One workgroup per cut destination; a lane works on the head its
+// columns belong to (every lane walks the piece statistics of its head itself: a destination has few pieces).
+template <int D, int LPH>
 __global__ __launch_bounds__(1024) void rgat_combine_fwd_kernel(const int32_t* __restrict__ split_row,
                                                                 const int32_t* __restrict__ split_ptr,
                                                                 const float* __restrict__ partial,
                                                                 const float2* __restrict__ part_ms, float* __restrict__ out,
                                                                 float2* __restrict__ ms) {
-    constexpr int LPR = D / 4, G = 1024 / LPR;
+    constexpr int LPR = D / 4, G = 1024 / LPR, H = LPR / LPH;
     __shared__ float4 red[1024];
-    __shared__ float redw[16];
-    const int sidx = blockIdx.x, g = threadIdx.x / LPR, c = threadIdx.x % LPR, wv = threadIdx.x >> 6;
+    __shared__ float redw[H][16];
+    const int sidx = blockIdx.x, g = threadIdx.x / LPR, c = threadIdx.x % LPR, head = c / LPH;
     const int p0 = split_ptr[sidx], p1 = split_ptr[sidx + 1];
+    // maximum and sum per head over the pieces: thread t takes head t % H of pieces t / H, t / H + 1024 / H, ...;
+    // the lanes of a wavefront that share a head are reduced with a butterfly over the strides H, 2H, ..., 32, the
+    // sixteen wavefronts' results are combined in wavefront order
+    const int rh = threadIdx.x % H, wv = threadIdx.x >> 6;
     float mloc = -INFINITY;
-    for (int p = p0 + (int)threadIdx.x; p < p1; p += 1024) mloc = fmaxf(mloc, part_ms[p].x);
-    mloc = wave_max(mloc);
-    if ((threadIdx.x & 63) == 0) redw[wv] = mloc;
+    for (int p = p0 + (int)threadIdx.x / H; p < p1; p += 1024 / H) mloc = fmaxf(mloc, part_ms[(size_t)p * H + rh].x);
+#pragma unroll
+    for (int o = 32; o >= H; o >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, o));
+    if ((threadIdx.x & 63) < H) redw[rh][wv] = mloc;
     __syncthreads();
-    float M = redw[0];
-    for (int k = 1; k < 16; ++k) M = fmaxf(M, redw[k]);
+    float M = redw[head][0];
+    for (int k = 1; k < 16; ++k) M = fmaxf(M, redw[head][k]);
+    float Mr = redw[rh][0];
+    for (int k = 1; k < 16; ++k) Mr = fmaxf(Mr, redw[rh][k]);
     __syncthreads();
     float sloc = 0.f;
-    for (int p = p0 + (int)threadIdx.x; p < p1; p += 1024) {
-        const float2 t = part_ms[p];
-        sloc += t.y * __expf(t.x - M);
+    for (int p = p0 + (int)threadIdx.x / H; p < p1; p += 1024 / H) {
+        const float2 t = part_ms[(size_t)p * H + rh];
+        sloc += t.y * __expf(t.x - Mr);
     }
-    sloc = group_sum<64>(sloc);
-    if ((threadIdx.x & 63) == 0) redw[wv] = sloc;
+#pragma unroll
+    for (int o = 32; o >= H; o >>= 1) sloc += __shfl_xor(sloc, o);
+    if ((threadIdx.x & 63) < H) redw[rh][wv] = sloc;
     __syncthreads();
-    float S = redw[0];
-    for (int k = 1; k < 16; ++k) S += redw[k];
+    float S = redw[head][0];
+    for (int k = 1; k < 16; ++k) S += redw[head][k];
     float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
     for (int p = p0 + g; p < p1; p += 2 * G) {
-        fma4(acc0, __expf(part_ms[p].x - M), *reinterpret_cast<const float4*>(partial + (size_t)p * D + c * 4));
-        if (p + G < p1) fma4(acc1, __expf(part_ms[p + G].x - M), *reinterpret_cast<const float4*>(partial + (size_t)(p + G) * D + c * 4));
+        fma4(acc0, __expf(part_ms[(size_t)p * H + head].x - M), *reinterpret_cast<const float4*>(partial + (size_t)p * D + c * 4));
+        if (p + G < p1)
+            fma4(acc1, __expf(part_ms[(size_t)(p + G) * H + head].x - M), *reinterpret_cast<const float4*>(partial + (size_t)(p + G) * D + c * 4));
     }
     fma4(acc0, 1.f, acc1);
     red[threadIdx.x] = acc0;
@@ -304,7 +326,7 @@ __global__ __launch_bounds__(1024) void rgat_combine_fwd_kernel(const int32_t* _
         const float inv = 1.f / S;
         const size_t v = (size_t)split_row[sidx];
         *reinterpret_cast<float4*>(out + v * D + c * 4) = make_float4(t.x * inv, t.y * inv, t.z * inv, t.w * inv);
-        if (c == 0) ms[v] = make_float2(M, S);
+        if (c % LPH == 0) ms[v * H + head] = make_float2(M, S);
     }
 }
 
@@ -319,19 +341,20 @@ __global__ __launch_bounds__(1024) void rgat_combine_fwd_kernel(const int32_t* _
 // pair-major backward aggregation and writes them here: (dz_e, att_e) into dsy[p] (the typed-linear
 // backward then reads the pair's gradient row as att_e * dOut[v]), or, without dsy, ds_src[p] = dz_e
 // and the row G[p] = att_e * dOut[v] itself.
-template <int D, bool LDSW>
+template <int D, int LPH, bool LDSW>
 __device__ __forceinline__ void bwd_item(const FusedArgs& a, const float* ws_lds, int i, int c) {
-    constexpr int LPR = D / 4;
+    constexpr int LPR = D / 4, H = LPR / LPH;
+    const int head = c / LPH;
     const int b = a.it.beg[i], e = a.it.end[i];
     if (b >= e) return;
     const size_t v = (size_t)a.it.row[i];
     const float4 go = *reinterpret_cast<const float4*>(a.dOut + v * D + c * 4);
     const float4 ov = *reinterpret_cast<const float4*>(a.fout + v * D + c * 4);
-    const float2 st = a.ms[v];
+    const float2 st = a.ms[v * H + head];
     int jj = min(b + c, e - 1);
-    int cpr = a.in_pair[jj], crl = a.in_rel[jj];
-    float csd = a.s_dst[a.in_run[jj]];
-    const float gbar = group_sum<LPR>(dot4(go, ov));
+    int cpr = a.in_pair[jj], crl = a.in_rel[jj], crn = a.in_run[jj];
+    float csd = H == 1 ? a.s_dst[crn] : 0.f;
+    const float gbar = group_sum<LPH>(dot4(go, ov));
     const float m = st.x, inv = 1.f / st.y;
     for (int jc = b; jc < e; jc += LPR) {
         const bool more = jc + LPR < e;
@@ -347,23 +370,25 @@ __device__ __forceinline__ void bwd_item(const FusedArgs& a, const float* ws_lds
         for (int k = 0; k < LPR; k += 4) {
             if (k >= cend) break;
             float4 h[4];
+            float sd[4];
             int pr[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 pr[u] = group_lane<LPR>(cpr, k + u);
                 h[u] = load_row_nt(a.Hs + (size_t)(pr[u] & 0x7FFFFFFF) * D + c * 4);
+                if (H > 1) sd[u] = a.s_dst[(size_t)group_lane<LPR>(crn, k + u) * H + head];
             }
             __builtin_amdgcn_sched_barrier(0);      // the w_s rows are read when the message rows arrive, not held meanwhile
-            float2 mine = make_float2(0.f, 0.f);      // (att, dz) of edge jc + k + c: lanes 0..3 of the group store one each
+            float2 mine = make_float2(0.f, 0.f);      // (att, dz) of edge jc + k + (c % LPH): lanes 0..3 of a head store one each
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const float4 w = ws_row<D, LDSW>(a, ws_lds, group_lane<LPR>(crl, k + u), c);
-                const float z = group_sum<LPR>(dot4(h[u], w)) + group_lane<LPR>(csd, k + u);
-                const float g = group_sum<LPR>(dot4(go, h[u]));
+                const float z = group_sum<LPH>(dot4(h[u], w)) + (H == 1 ? group_lane<LPR>(csd, k + u) : sd[u]);
+                const float g = group_sum<LPH>(dot4(go, h[u]));
                 const float al = __expf(leaky(z, a.slope) - m) * inv;
                 const float dz = al * (g - gbar) * (z > 0.f ? 1.f : a.slope);
-                if (c == u) mine = make_float2(al, dz);
-                if (k + u < cend && pr[u] < 0) {     // single-edge pair
+                if (c % LPH == u) mine = make_float2(al, dz);
+                if (H == 1 && a.own_singles && k + u < cend && pr[u] < 0) {     // single-edge pair
                     const size_t p = (size_t)(pr[u] & 0x7FFFFFFF);
                     if (!a.dsy) *reinterpret_cast<float4*>(a.G + p * D + c * 4) = make_float4(al * go.x, al * go.y, al * go.z, al * go.w);
                     if (c == 0) {
@@ -372,23 +397,33 @@ __device__ __forceinline__ void bwd_item(const FusedArgs& a, const float* ws_lds
                     }
                 }
             }
-            if (c < 4 && k + c < cend) a.adz[jc + k + c] = mine;
+            const int t = c % LPH;
+            if (t < 4 && k + t < cend) {
+                float* o = a.adz + (size_t)(jc + k + t) * 2 * H + head;
+                if (H == 1) {
+                    *reinterpret_cast<float2*>(o) = mine;
+                } else {
+                    o[0] = mine.x;
+                    o[H] = mine.y;
+                }
+            }
         }
         if (more) {
-            csd = a.s_dst[nrn];
+            if (H == 1) csd = a.s_dst[nrn];
             cpr = npr;
             crl = nrl;
+            crn = nrn;
         }
     }
 }
 
-template <int D, bool LDSW>
+template <int D, int LPH, bool LDSW>
 __global__ __launch_bounds__(kFusedThreads) void rgat_edge_dot_bwd_kernel(FusedArgs a) {
     constexpr int LPR = D / 4, GPB = kFusedThreads / LPR;
     const float* ws_lds = stage_ws<D, LDSW>(a);
     const int grp = threadIdx.x / LPR, c = threadIdx.x % LPR;
     const int stride = gridDim.x * GPB;
-    for (int i = blockIdx.x * GPB + grp; i < a.it.n; i += stride) bwd_item<D, LDSW>(a, ws_lds, i, c);
+    for (int i = blockIdx.x * GPB + grp; i < a.it.n; i += stride) bwd_item<D, LPH, LDSW>(a, ws_lds, i, c);
 }
 
 // Launch with as many workgroups as stay resident at once (LDS, registers and wavefront slots decide), never more
@@ -410,7 +445,24 @@ rgnn_status_t launch_fused(K kernel, const rgnn_graph* g, size_t lds, size_t gro
 
 }  // namespace
 
-rgnn_status_t rgat_aggregate_fwd(const rgnn_graph* g, int D, const float* Hs, const float* w_s, const float* s_dst,
+// Runs the statement with DD = width and LL = lanes per head for the (width, heads) combinations the layer accepts
+// (head widths 16, 32, 64, or one head of any width): LL = DD / 4 / heads.
+#define RGNN_DISPATCH_DH(D_, H_, ...)                                                                              \
+    do {                                                                                                           \
+        const int lph_ = (D_) / 4 / (H_);                                                                          \
+        if ((D_) == 64 && lph_ == 16) { constexpr int DD = 64, LL = 16; __VA_ARGS__; }                             \
+        else if ((D_) == 64 && lph_ == 8) { constexpr int DD = 64, LL = 8; __VA_ARGS__; }                          \
+        else if ((D_) == 64 && lph_ == 4) { constexpr int DD = 64, LL = 4; __VA_ARGS__; }                          \
+        else if ((D_) == 32 && lph_ == 8) { constexpr int DD = 32, LL = 8; __VA_ARGS__; }                          \
+        else if ((D_) == 32 && lph_ == 4) { constexpr int DD = 32, LL = 4; __VA_ARGS__; }                          \
+        else if ((D_) == 128 && lph_ == 32) { constexpr int DD = 128, LL = 32; __VA_ARGS__; }                      \
+        else if ((D_) == 128 && lph_ == 16) { constexpr int DD = 128, LL = 16; __VA_ARGS__; }                      \
+        else if ((D_) == 128 && lph_ == 8) { constexpr int DD = 128, LL = 8; __VA_ARGS__; }                        \
+        else if ((D_) == 128 && lph_ == 4) { constexpr int DD = 128, LL = 4; __VA_ARGS__; }                        \
+        else RGNN_FAIL(RGNN_EUNSUPPORTED, "fused RGAT traversal: width %d with %d heads is not built", (int)(D_), (int)(H_)); \
+    } while (0)
+
+rgnn_status_t rgat_aggregate_fwd(const rgnn_graph* g, int D, int H, const float* Hs, const float* w_s, const float* s_dst,
                                  float slope, float* out, float* ms, float* partial, float* part_ms, hipStream_t st) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0) return RGNN_OK;
@@ -427,35 +479,35 @@ rgnn_status_t rgat_aggregate_fwd(const rgnn_graph* g, int D, const float* Hs, co
     const size_t groups = std::max<size_t>({(size_t)a.general_n, (size_t)(nsh + 1) / 2, (size_t)(ns + 3) / 4});
     {
         KernelTimer kt(st, "aggregate_fwd");
-        if (ldsw) RGNN_DISPATCH_D(D, RGNN_TRY(launch_fused(rgat_aggregate_fwd_kernel<DD, true>, g, lds, groups, DD / 4, a, st)));
-        else RGNN_DISPATCH_D(D, RGNN_TRY(launch_fused(rgat_aggregate_fwd_kernel<DD, false>, g, 0, groups, DD / 4, a, st)));
+        if (ldsw) RGNN_DISPATCH_DH(D, H, RGNN_TRY(launch_fused(rgat_aggregate_fwd_kernel<DD, LL, true>, g, lds, groups, DD / 4, a, st)));
+        else RGNN_DISPATCH_DH(D, H, RGNN_TRY(launch_fused(rgat_aggregate_fwd_kernel<DD, LL, false>, g, 0, groups, DD / 4, a, st)));
     }
     if (L.num_split > 0) {
         KernelTimer kt(st, "aggregate_fwd.combine");
-        RGNN_DISPATCH_D(D, hipLaunchKernelGGL((rgat_combine_fwd_kernel<DD>), dim3(L.num_split), dim3(1024), 0, st, L.split_row,
-                                              L.split_ptr, partial, reinterpret_cast<const float2*>(part_ms), out,
-                                              reinterpret_cast<float2*>(ms)));
+        RGNN_DISPATCH_DH(D, H, hipLaunchKernelGGL((rgat_combine_fwd_kernel<DD, LL>), dim3(L.num_split), dim3(1024), 0, st, L.split_row,
+                                                  L.split_ptr, partial, reinterpret_cast<const float2*>(part_ms), out,
+                                                  reinterpret_cast<float2*>(ms)));
         RGNN_CHECK_LAUNCH();
     }
     return RGNN_OK;
 }
 
-rgnn_status_t rgat_edge_dot_bwd(const rgnn_graph* g, int D, const float* Hs, const float* w_s, const float* s_dst,
+rgnn_status_t rgat_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* Hs, const float* w_s, const float* s_dst,
                                 const float* ms, const float* dOut, const float* out, float slope, float* adz, float* G,
                                 float* ds_src, float* dsy, hipStream_t st) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
     FusedArgs a{};
     a.it = dev_items(L); a.in_pair = g->in_pair_tag; a.in_rel = g->idx[RGNN_IDX_IN_REL]; a.in_run = g->idx[RGNN_IDX_IN_RUN];
-    a.Hs = Hs; a.w_s = w_s; a.s_dst = s_dst; a.slope = slope; a.R = g->R;
+    a.Hs = Hs; a.w_s = w_s; a.s_dst = s_dst; a.slope = slope; a.R = g->R; a.own_singles = H == 1;
     a.ms = reinterpret_cast<float2*>(const_cast<float*>(ms));
-    a.dOut = dOut; a.fout = out; a.adz = reinterpret_cast<float2*>(adz); a.G = G; a.ds_src = ds_src;
+    a.dOut = dOut; a.fout = out; a.adz = adz; a.G = G; a.ds_src = ds_src;
     a.dsy = reinterpret_cast<float2*>(dsy);
     const size_t lds = (size_t)g->R * D * sizeof(float);
     const bool ldsw = sched_ws_in_lds(g->R, D);
     KernelTimer kt(st, "edge_dot_bwd");
-    if (ldsw) RGNN_DISPATCH_D(D, RGNN_TRY(launch_fused(rgat_edge_dot_bwd_kernel<DD, true>, g, lds, (size_t)L.num_items, DD / 4, a, st)));
-    else RGNN_DISPATCH_D(D, RGNN_TRY(launch_fused(rgat_edge_dot_bwd_kernel<DD, false>, g, 0, (size_t)L.num_items, DD / 4, a, st)));
+    if (ldsw) RGNN_DISPATCH_DH(D, H, RGNN_TRY(launch_fused(rgat_edge_dot_bwd_kernel<DD, LL, true>, g, lds, (size_t)L.num_items, DD / 4, a, st)));
+    else RGNN_DISPATCH_DH(D, H, RGNN_TRY(launch_fused(rgat_edge_dot_bwd_kernel<DD, LL, false>, g, 0, (size_t)L.num_items, DD / 4, a, st)));
     return RGNN_OK;
 }
 

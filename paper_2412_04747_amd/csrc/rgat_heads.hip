@@ -24,35 +24,34 @@ __global__ void fold_weight_heads_kernel(const float* __restrict__ W, const floa
     wv[i] = s;
 }
 
-// s_dst[q][h] = X[run_dst[q]] . wtp[run_rel[q]][h]: the run's X row is read once, one full-width dot per head
+// s_dst[q][h] = X[run_dst[q]] . wtp[run_rel[q]][h]: the run's X row is read once, one full-width dot per head; a lane
+// group takes four consecutive runs so that four row reads (and the heads' folded vectors) are in flight per lane
 template <int D>
 __global__ __launch_bounds__(256) void run_logit_heads_kernel(int Q, int R, int H, const int32_t* __restrict__ run_dst,
                                                               const int32_t* __restrict__ run_rel,
                                                               const float* __restrict__ X, const float* __restrict__ wtp,
                                                               float* __restrict__ s_dst) {
     constexpr int LPR = D / 4;
-    const int q = blockIdx.x * (256 / LPR) + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
-    if (q >= Q) return;
-    const float4 x = *reinterpret_cast<const float4*>(X + (size_t)run_dst[q] * D + c4 * 4);
-    const int r = run_rel[q];
-    for (int h = 0; h < H; ++h) {
-        const float4 w = *reinterpret_cast<const float4*>(wtp + ((size_t)r * H + h) * D + c4 * 4);
-        const float t = group_sum<LPR>(dot4(x, w));
-        if (c4 == 0) s_dst[(size_t)q * H + h] = t;
+    const int q0 = (blockIdx.x * (256 / LPR) + threadIdx.x / LPR) * 4, c4 = threadIdx.x % LPR;
+    if (q0 >= Q) return;
+    float4 x[4];
+    int r[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int q = min(q0 + u, Q - 1);
+        x[u] = *reinterpret_cast<const float4*>(X + (size_t)run_dst[q] * D + c4 * 4);
+        r[u] = run_rel[q];
     }
-}
-
-// att[e][h] = leakyrelu(s_src[pair_e][h] + s_dst[run_e][h])   (the logits; the softmax follows)
-__global__ void edge_logit_heads_kernel(int64_t total, int H, const int32_t* __restrict__ in_pair,
-                                        const int32_t* __restrict__ in_run, const float* __restrict__ s_src,
-                                        const float* __restrict__ s_dst, float slope, float* __restrict__ att) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= total) return;
-    const int lh = 31 - __clz(H);                 // the head count is a power of two
-    const int64_t e = i >> lh;
-    const int h = (int)(i & (H - 1));
-    const float z = s_src[(size_t)in_pair[e] * H + h] + s_dst[(size_t)in_run[e] * H + h];
-    att[i] = z > 0.f ? z : slope * z;
+    for (int h = 0; h < H; ++h) {
+        float4 w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w[u] = *reinterpret_cast<const float4*>(wtp + ((size_t)r[u] * H + h) * D + c4 * 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float t = group_sum<LPR>(dot4(x[u], w[u]));
+            if (c4 == 0 && q0 + u < Q) s_dst[(size_t)(q0 + u) * H + h] = t;
+        }
+    }
 }
 
 // Per relation r, with U[h][r] = sum_q ds_dst[q][h] X[dst_q] and h(n) the head of column n:
@@ -88,20 +87,9 @@ rgnn_status_t run_logit_heads(const rgnn_graph* g, int D, int H, const float* X,
                               hipStream_t st) {
     if (g->Q == 0) return RGNN_OK;
     KernelTimer kt(st, "run_logit");
-    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(run_logit_heads_kernel<DD>, dim3(blocks_for((size_t)g->Q * (DD / 4), 256)), dim3(256),
+    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(run_logit_heads_kernel<DD>, dim3(blocks_for((size_t)((g->Q + 3) / 4) * (DD / 4), 256)), dim3(256),
                                           0, st, (int)g->Q, (int)g->R, H, g->idx[RGNN_IDX_RUN_DST], g->idx[RGNN_IDX_RUN_REL], X,
                                           wtp, s_dst));
-    RGNN_CHECK_LAUNCH();
-    return RGNN_OK;
-}
-
-rgnn_status_t edge_logit_heads(const rgnn_graph* g, int H, const float* s_src, const float* s_dst, float slope, float* att,
-                               hipStream_t st) {
-    if (g->E == 0) return RGNN_OK;
-    KernelTimer kt(st, "edge_logit");
-    const int64_t total = g->E * H;
-    hipLaunchKernelGGL(edge_logit_heads_kernel, dim3(blocks_for((size_t)total, 256)), dim3(256), 0, st, total, H,
-                       g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN], s_src, s_dst, slope, att);
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

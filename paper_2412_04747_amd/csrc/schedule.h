@@ -41,10 +41,10 @@ inline bool sched_row_select(int layer, int dtype, int d, int heads, uint32_t fl
 inline bool sched_hgt_folded(bool rel_src_tied, uint32_t flags) {
     return rel_src_tied && !flag_set(flags, RGNN_FLAG_NO_WEIGHT_FOLDING);
 }
-// single-head RGAT: edge softmax fused into the aggregation walk (otherwise a pass of its own that stores one
+// RGAT: edge softmax fused into the aggregation walk (otherwise, one head only, a pass of its own that stores one
 // attention weight per edge); the edge-parallel comparison schedule needs the per-edge weights
-inline bool sched_fused_softmax(int heads, uint32_t flags) {
-    return heads == 1 && !flag_set(flags, RGNN_FLAG_SEPARATE_SOFTMAX) && !flag_set(flags, RGNN_FLAG_EDGE_PARALLEL_AGGREGATION);
+inline bool sched_fused_softmax(uint32_t flags) {
+    return !flag_set(flags, RGNN_FLAG_SEPARATE_SOFTMAX) && !flag_set(flags, RGNN_FLAG_EDGE_PARALLEL_AGGREGATION);
 }
 inline bool sched_ws_in_lds(int R, int d) { return (size_t)R * d * sizeof(float) <= kWsLdsMax; }
 
@@ -66,7 +66,7 @@ inline rgnn_schedule_t pick_schedule(const ScheduleIn& in) {
     s.rows_bf16 = sched_rows_bf16(in.dtype, in.d) && in.layer != RGNN_LAYER_RGAT;
     s.row_select = sched_row_select(in.layer, in.dtype, in.d, in.heads, in.flags);
     s.hgt_folded = in.layer == RGNN_LAYER_HGT && sched_hgt_folded(in.rel_src_tied, in.flags);
-    s.fused_softmax = in.layer == RGNN_LAYER_RGAT && sched_fused_softmax(in.heads, in.flags);
+    s.fused_softmax = in.layer == RGNN_LAYER_RGAT && sched_fused_softmax(in.flags);
     s.ws_in_lds = s.fused_softmax && sched_ws_in_lds(in.R, in.d);
     s.edge_parallel = in.layer == RGNN_LAYER_RGAT && flag_set(in.flags, RGNN_FLAG_EDGE_PARALLEL_AGGREGATION);
     s.dst_batched_single = batched_count(in.dst.single, in.flags) > 0;

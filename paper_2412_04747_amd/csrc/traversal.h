@@ -23,15 +23,15 @@ rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng,
 // ms (optional, [N] pairs of floats): (max, sum of exp) of the logits of every destination with edges
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
                            float* part_m, float* part_s, hipStream_t st, float* ms = nullptr);
-// rgat_fused.hip: single-head RGAT with the edge softmax fused into the traversal.
-//   forward: out[v] = sum_e att_e Hs[pair_e] with att = softmax over v's edges of leakyrelu(Hs[pair_e] . w_s[r_e] + s_dst[run_e]);
-//   ms[v] = (max logit, sum of exp(logit - max)) as pairs of floats; partial / part_ms: scratch rows and (m, s) pairs of the
+// rgat_fused.hip: RGAT (H heads; head h owns column slice h) with the edge softmax fused into the traversal.
+//   forward: out[v] = sum_e att_e Hs[pair_e] per head, att = softmax over v's edges of leakyrelu(Hs[pair_e] . w_s[r_e] + s_dst[run_e][h]);
+//   ms[v][h] = (max logit, sum of exp(logit - max)) as pairs of floats; partial / part_ms: scratch rows and (m, s) pairs of the
 //   pieces of cut destinations
-rgnn_status_t rgat_aggregate_fwd(const rgnn_graph* g, int D, const float* Hs, const float* w_s, const float* s_dst,
+rgnn_status_t rgat_aggregate_fwd(const rgnn_graph* g, int D, int H, const float* Hs, const float* w_s, const float* s_dst,
                                  float slope, float* out, float* ms, float* partial, float* part_ms, hipStream_t st);
-//   backward: adz[e] = (att_e, dz_e) with att_e recomputed from the gathered row and ms; the only edge of a single-edge
-//   pair also writes dsy[p] = (dz_e, att_e), or without dsy: ds_src[p] = dz_e and G[p] = att_e dOut[v]
-rgnn_status_t rgat_edge_dot_bwd(const rgnn_graph* g, int D, const float* Hs, const float* w_s, const float* s_dst,
+//   backward: adz[e] = (att_e[0..H), dz_e[0..H)) with att_e recomputed from the gathered row and ms; one head: the only edge
+//   of a single-edge pair also writes dsy[p] = (dz_e, att_e), or without dsy: ds_src[p] = dz_e and G[p] = att_e dOut[v]
+rgnn_status_t rgat_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* Hs, const float* w_s, const float* s_dst,
                                 const float* ms, const float* dOut, const float* out, float slope, float* adz, float* G,
                                 float* ds_src, float* dsy, hipStream_t st);
 // workgroups of `threads` threads with `lds` bytes of dynamic LDS that stay resident per compute unit (cached per kernel)
@@ -81,8 +81,6 @@ rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* a
 rgnn_status_t fold_weight_heads(int R, int kd, int nd, int H, const float* W, const float* w, float* wv, hipStream_t st);
 rgnn_status_t run_logit_heads(const rgnn_graph* g, int D, int H, const float* X, const float* wtp, float* s_dst,
                               hipStream_t st);
-rgnn_status_t edge_logit_heads(const rgnn_graph* g, int H, const float* s_src, const float* s_dst, float slope, float* att,
-                               hipStream_t st);
 rgnn_status_t rgat_heads_param_finish(int R, int kd, int nd, int H, const float* W, const float* w_t, const float* U,
                                       float* dW, float* dw_t, hipStream_t st);
 // out[v] = sum_e |att_e| Hs[pair_e] edge by edge with atomic adds (zeroes out first); fp32 rows

@@ -94,17 +94,15 @@ class RgatLayer:
                         self.dX, self.dW, self.dw_s, self.dw_t, self.ws, _stream())
 
     def saved_views(self):
-        """The parts of `saved`: (Hs [P, d], s_dst [Q], ms [N, 2]) for one head, (Hs, att [E, heads]) for several."""
-        P, E, Q, N, d = self.g.P, self.g.E, self.g.Q, self.g.N, self.d
+        """The parts of `saved`: Hs [P, d], s_dst [Q, heads], ms [N, heads, 2]."""
+        P, Q, N, d, H = self.g.P, self.g.Q, self.g.N, self.d, self.H
         al = lambda n: (max(n, 1) * 4 + 255) // 256 * 256 // 4
         f32 = self.saved.view(torch.float32)
         hs = f32[: P * d].view(P, d)
         off = al(P * d)
-        if self.H > 1:
-            return hs, f32[off: off + E * self.H].view(E, self.H)
-        s_dst = f32[off: off + Q]
-        off += al(Q)
-        return hs, s_dst, f32[off: off + 2 * N].view(N, 2)
+        s_dst = f32[off: off + Q * H].view(Q, H)
+        off += al(Q * H)
+        return hs, s_dst, f32[off: off + 2 * N * H].view(N, H, 2)
 
     def grads(self):
         return dict(dX=self.dX, dW=self.dW, dw_s=self.dw_s, dw_t=self.dw_t)

@@ -26,6 +26,7 @@ def _run(N, R, src, dst, rel, p, d, tag, slope=0.2, check_saved=True, dtype="f32
     if check_saved and len(src):
         ix = graph_index.build(N, R, src, dst, rel)
         hs, s_dst, ms = (t.cpu().numpy() for t in L.saved_views())
+        s_dst, ms = s_dst[:, 0], ms[:, 0]
         # what the forward keeps: the destination half of the logit per run, and per destination the
         # maximum m of the leaky-ReLU logits and s = sum exp(l - m); the backward rebuilds att from them
         X64, W64 = p["X"].astype(np.float64), p["W"].astype(np.float64)
@@ -116,12 +117,12 @@ def _run_heads(N, R, src, dst, rel, p, d, H, tag, dtype="f32", slope=0.2):
     want, alpha, z = O.rgat_heads_fwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], H, slope, want_alpha=True)
     check(L.out, want, tol, "out")
     ix = graph_index.build(N, R, src, dst, rel)
-    _, att = L.saved_views()
-    att = att.cpu().numpy().reshape(len(src), H)
-    check(np.abs(att), alpha[ix["in_eid"]], tol, "att")
-    zz = z[ix["in_eid"]]
-    clear = np.abs(zz) > 1e-3
-    assert np.array_equal(np.signbit(att)[clear], (zz <= 0)[clear])
+    # the backward rebuilds the attention weights from what the forward keeps: (max, sum) per (destination, head)
+    _, _, ms = (t.cpu().numpy().astype(np.float64) for t in L.saved_views())
+    zz = z[ix["in_eid"]]                                   # [E, H] logits in CSR order
+    l = np.where(zz > 0, zz, slope * zz)
+    v_of = np.repeat(np.arange(N), np.diff(ix["in_ptr"]))
+    check(np.exp(l - ms[v_of, :, 0]) / ms[v_of, :, 1], alpha[ix["in_eid"]], tol, "att from (m, s)")
     L.bwd()
     torch.cuda.synchronize()
     wg = O.rgat_heads_bwd(N, src, dst, rel, p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"], H, slope)

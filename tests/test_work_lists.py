@@ -273,7 +273,7 @@ def test_schedule_flags_force_the_alternatives(wl):
     ep = pick(wl, c, k, flags=1)
     assert ep["edge_parallel"] and not ep["fused_softmax"]
     heads = pick(wl, c, k, heads=4)
-    assert not heads["fused_softmax"] and not heads["row_select"] and not heads["pair_walk_multi_only"]
+    assert heads["fused_softmax"] and not heads["row_select"] and not heads["pair_walk_multi_only"]
     assert heads["pair_batched_single"]                     # several heads: the pair-major walk takes every pair
     big_r = dict(c, R=300)                                  # 300 x 64 floats = 75 KB: w_s no longer fits the LDS budget
     assert pick(wl, big_r, k)["fused_softmax"] and not pick(wl, big_r, k)["ws_in_lds"]
