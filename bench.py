@@ -153,7 +153,10 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
         # per run: X row + relrun_idx + run_dst + ds_dst
         "dst_side_wgrad": ("hbm", Q * (row + 12), 2.0 * Q * d),
         # per pair: dXp row + srcpair_idx; per run (RGAT): ds_dst + run_rel; per node: result row + 2 ptrs
-        "node_grad_sum": ("hbm", P * (row + 4) + (Q * 8 if layer == "rgat" else 0) + N * (out_dst + 8), 1.0 * P * d),
+        # (HGT on the folded path: two per-pair tensors are summed and the query part, an fp32 row per node, is added;
+        #  the result is the layer's fp32 dX.  Several heads: one ds_dst per run and head.)
+        "node_grad_sum": ("hbm", P * (2 * row + 4) + N * (2 * r32 + 8), 2.0 * P * d) if layer == "hgt" and sched.get("hgt_folded")
+                         else ("hbm", P * (row + 4) + (Q * (4 + 4 * H) if layer == "rgat" else 0) + N * (out_dst + 8), 1.0 * P * d),
         # per edge: in_pair, in_run, s_src, s_dst, att write (reads of its own writes not counted)
         "edge_softmax": ("hbm", E * 20 + N * 8, 10.0 * E),
         # per run: run_dst, run_rel, s_dst; per destination with edges: its X row (its runs are adjacent)
