@@ -55,8 +55,8 @@ def counter_traffic(label, sha):
 
 
 def step_rooflines(kern_ms, E, N, P, P1, d):
-    """Single-head RGAT: the traversal steps as wholes (all kernels that implement a step, the step's algorithmic
-    bytes per edge / node / pair as the hot-path table of the design notes lists them) against the HBM peak."""
+    """Single-head RGAT: the traversal steps as wholes against the HBM peak: all kernels that implement a step, over
+    the bytes the step itself needs per edge / node / pair (listed with each step below), whatever else the kernels move."""
     row = 4 * d
     steps = {
         # S3 forward traversal: per edge the message row, pair id, a logit scalar and a 4-byte weight or its
