@@ -115,11 +115,12 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
             extra = r32 if half and not sched.get("hgt_folded") and key in ("node_linear_q_bwd", "node_linear_v_bwd") else 0
             return (bound, n * (row + out_row + extra + 4) + segs * w2, 2.0 * n * d * d)
     w2 = d * d * 4
-    # single-head RGAT up to width 64: the gradient row of a single-edge pair is not stored per pair; the
+    # RGAT up to width 64: the gradient row of a single-edge pair is not stored per pair; the
     # backward typed linear reads att_e * dOut[dst_e] through a row selector (one index per pair; ds_src[p] and
-    # the scale come as one pair of floats per pair)
+    # the scale come as one pair of floats per pair and head)
     sel = bool(sched.get("row_select", layer == "rgat" and H == 1 and d <= 64)) and layer == "rgat"
     fused = bool(sched.get("fused_softmax", layer == "rgat" and H == 1))       # single-head RGAT: softmax inside the walks
+    P1s = P1 if sel or H == 1 else 0      # single-edge pairs that the edge walk / the row selector serve
     pair_fwd = ("mfma", P * (2 * row + 4) + R * w2, 2.0 * P * d * d)        # gathered row + stored row + pair_src
     pair_bwd = ("mfma", P * (3 * row + 4) + R * w2, 4.0 * P * d * d)        # dY row + gathered row + stored row
     node_fwd = ("mfma", N * (2 * row + 4) + T * w2, 2.0 * N * d * d)
@@ -130,24 +131,25 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
     table = {
         # RGAT: + s_src per pair and head; backward also reads ds_src
         "typed_linear_fwd": ("mfma", pair_fwd[1] + (P * 4 * H if layer == "rgat" and not fused else 0), pair_fwd[2]),
-        "typed_linear_bwd": ("mfma", pair_bwd[1] + (P * 4 if layer == "rgat" else 0) + (P * 8 if sel else 0), pair_bwd[2]),
+        "typed_linear_bwd": ("mfma", pair_bwd[1] + ((P * (4 + 8 * H) if sel else P * 4 if H == 1 else 0) if layer == "rgat" else 0), pair_bwd[2]),
         "self_loop_fwd": ("mfma", N * 3 * r32 + w2, 2.0 * N * d * d),         # X row + out row read and written
         "self_loop_bwd": ("mfma", N * 3 * r32 + w2, 4.0 * N * d * d),
-        # fused single-head RGAT walk: row + in_pair + in_rel + in_run per edge, s_dst per run, out row + (m, s) + item per node
-        "aggregate_fwd": ("hbm", E * (row + 12) + Q * 4 + N * (r32 + 16), 4.0 * E * d) if fused else agg_dst,
+        # fused RGAT walk: row + in_pair + in_rel + in_run per edge, s_dst per run and head, out row + item + (m, s) per head per node
+        "aggregate_fwd": ("hbm", E * (row + 12) + Q * 4 * H + N * (r32 + 8 + 8 * H), 4.0 * E * d) if fused else agg_dst,
         # the same sum edge by edge with atomic adds: + in_run and run_dst per edge, and the zero fill
         "aggregate_fwd_edge_parallel": ("hbm", agg_dst[1] + E * 8 + N * r32, 2.0 * E * d),
         # per edge: Hs row + in_pair + att + (att, dz) store; per node: dOut row + out row + item;
         # per single-edge pair (P1 of them): ds_src and its G row, or with the row selector att_e only
         # (fused: att is recomputed, so in_rel, in_run and s_dst are read instead of att, and (m, s) per node)
-        "edge_dot_bwd": ("hbm", E * (row + 20) + Q * 4 + N * (2 * row + 16) + P1 * ((4 if sel else row) + 4), 4.0 * E * d) if fused
+        # (several heads: (att, dz), s_dst, (m, s) and the single-edge pairs' entries once per head)
+        "edge_dot_bwd": ("hbm", E * (row + 12 + 8 * H) + Q * 4 * H + N * (2 * row + 8 + 8 * H) + P1s * ((4 * H if sel else row) + 4 * H), 4.0 * E * d) if fused
                         else ("hbm", E * (row + 16) + N * (2 * row + 8) + P1 * ((4 if sel else row) + 4), 2.0 * E * d),
         # RGAT: only the E - P1 edges of the P - P1 pairs with several edges; coefficient = the (att, dz) pair;
         # with one head the walk also writes ds_src per pair.
         # RGCN: every edge; row + out_dst + coefficient
         # RGCN with bf16 rows: likewise only pairs with several edges (the typed-linear backward reads the
         # others' rows straight from the destinations' gradient rows)
-        "aggregate_bwd_pair": ("hbm", (E - P1) * (row + 16) + (P - P1) * (row + 8 + (4 if H == 1 else 0)), 2.0 * (E - P1) * d) if layer == "rgat"
+        "aggregate_bwd_pair": ("hbm", (E - P1s) * (row + 8 + 8 * H) + (P - P1s) * (row + 8 + 4 * H), 2.0 * (E - P1s) * d) if layer == "rgat"
                               else ("hbm", (E - P1) * (row + 8) + (P - P1) * (row + 8), 2.0 * (E - P1) * d) if half
                               else ("hbm", E * (row + 8) + P * (row + 8), 2.0 * E * d),
         # per run: X row + relrun_idx + run_dst + ds_dst

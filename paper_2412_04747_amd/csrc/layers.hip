@@ -136,7 +136,8 @@ size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
     w->adz = c.take<float>((size_t)g->E * 2 * H);                    // per edge: att per head, then dz per head
     w->ds_dst = c.take<float>((size_t)g->Q * H);
     // with the row selector: (ds_src[p], att of the pair's only edge) interleaved, one pair of floats per p
-    w->ds_src = c.take<float>(rgat_row_select(d) ? 2 * (size_t)g->P : (size_t)g->P * H);
+    //   (several heads: 2 H floats per p, ds_src[p][0..H) then, for a pair with one edge, that edge's att[0..H))
+    w->ds_src = c.take<float>(2 * (size_t)g->P * H);
     w->G = c.take<float>((size_t)g->P * d->d_out);
     w->dXp = c.take<float>((size_t)g->P * d->d_in);
     w->A = c.take<float>((size_t)g->R * d->d_in);
@@ -589,24 +590,30 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         const float *ws = static_cast<const float*>(w_s), *wt = static_cast<const float*>(w_t);
         // 1. per CSR edge and head: att recomputed from the gathered row and the saved (m, s), and
         //    dz = att (dOut[v].Hs[pair_e] - dOut[v].out[v])_h * (z > 0 ? 1 : slope);  adz[e] = (att[0..H), dz[0..H))
+        //    With the row selector the only edge of a single-edge pair also writes that pair's (dz[0..H), att[0..H)) into
+        //    ds_src[p], which holds 2 H floats per pair.
+        const bool sel = rgat_row_select(desc);
         RGNN_TRY(rgat_edge_dot_bwd(g, D, H, sv.Hs, ws, sv.s_dst, sv.ms, dO, static_cast<const float*>(out), desc->slope, w.adz,
-                                   nullptr, nullptr, nullptr, st));
-        // 2. per-head sums of dz over runs and over pairs
+                                   nullptr, nullptr, sel ? w.ds_src : nullptr, st));
+        // 2. per-head sums of dz over runs and over pairs: ds_src[p][h] is element p * 2 H + h (step 1 wrote the pairs
+        //    with one edge when the selector is on)
         RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], g->long_runs, nullptr, w.adz, 2 * H, H, w.ds_dst, st,
                                     "ds_dst_sum", 0, H));
         RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2 * H, H,
-                                    w.ds_src, st, "ds_src_sum", 0, H));
-        // 3. dHs[p] = sum_{e in out(p)} att_e dOut[dst_e] (per head)  +  ds_src[p][h] w_s[r] (per head)
-        const Rank1 r1{w.ds_src, H, g->idx[RGNN_IDX_PAIR_REL], ws};      // the second term, added when a pair's row is stored
-        RGNN_TRY(gather_sum(g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.adz, 2 * H, 0, dO, w.G,
-                            w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", H, 0, 0, &r1));
+                                    w.ds_src, st, "ds_src_sum", sel ? 2 : 0, H, false, 2 * H));
+        // 3. dHs[p] = sum_{e in out(p)} att_e dOut[dst_e] (per head)  +  ds_src[p][h] w_s[r] (per head); with the
+        //    selector only for the pairs with several edges: step 4 forms the other rows from dOut as it reads them
+        const Rank1 r1{w.ds_src, 2 * H, g->idx[RGNN_IDX_PAIR_REL], ws};      // the second term, added when a pair's row is stored
+        RGNN_TRY(gather_sum(sel ? g->pair_items_multi : g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.adz,
+                            2 * H, 0, dO, w.G, w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", H, 0, 0, &r1));
         // 4. dXp = dHs W^T, dW = sum X^T dHs
         TypedLinearBwdArgs b{};
         b.tiles = &g->pair_tiles_wide; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
         b.dW = static_cast<float*>(dW); b.part = w.tl_part;
+        if (sel) { b.ysel = g->pair_ysel; b.dY_alt = dO; b.hcoef = w.ds_src; b.wvec = ws; b.sel_heads = H; }
         RGNN_TRY(typed_linear_bwd(K, D, b, st));
         // 5. dw_s[r] = sum over r's pairs of ds_src[p][h] Hs[p] (per head; the pair rows are in relation order)
-        RGNN_TRY(gather_sum(g->relpair_items, D, nullptr, nullptr, 0, w.ds_src, H, 0, sv.Hs, dw_s, w.partial, st, 2,
+        RGNN_TRY(gather_sum(g->relpair_items, D, nullptr, nullptr, 0, w.ds_src, 2 * H, 0, sv.Hs, dw_s, w.partial, st, 2,
                             "src_vec_grad", "src_vec_grad.combine", H));
         // 6. U[h][r] = sum over r's runs of ds_dst[q][h] X[run_dst[q]];  dw_t and the w_t part of dW from it
         RGNN_TRY(gather_heads_rows(g->relrun_items, K, H, g->R, g->idx[RGNN_IDX_RELRUN_IDX], g->relrun_dst, 0, w.ds_dst,

@@ -40,7 +40,7 @@ struct FusedArgs {
     const float* s_dst;       // [Q][H]
     float slope;
     int R;
-    int own_singles;          // backward: the only edge of a single-edge pair writes that pair's entries (one head)
+    int own_singles;          // backward: the only edge of a single-edge pair writes that pair's entries
     // forward
     float* out;               // [N][D]
     float2* ms;               // [N][H] (m, s) of the destination's softmax
@@ -55,7 +55,7 @@ struct FusedArgs {
     float* adz;               // [E][2][H]: att_e per head, then dz_e per head
     float* G;                 // [P][D] (only without dsy)
     float* ds_src;            // [P]    (only without dsy)
-    float2* dsy;              // [P] (dz_e, att_e) of the only edge of a single-edge pair
+    float2* dsy;              // [P] (dz_e, att_e) of the only edge of a single-edge pair; H > 1: [P][2][H] floats, dz then att
 };
 
 __device__ __forceinline__ float leaky(float z, float slope) { return z > 0.f ? z : slope * z; }
@@ -340,7 +340,8 @@ __global__ __launch_bounds__(1024) void rgat_combine_fwd_kernel(const int32_t* _
 // An edge that is the only edge of its (source, relation) pair also owns that pair's entries of the
 // pair-major backward aggregation and writes them here: (dz_e, att_e) into dsy[p] (the typed-linear
 // backward then reads the pair's gradient row as att_e * dOut[v]), or, without dsy, ds_src[p] = dz_e
-// and the row G[p] = att_e * dOut[v] itself.
+// and the row G[p] = att_e * dOut[v] itself.  With several heads only the first form exists, and dsy
+// holds 2 H floats per pair: dz_e per head, then att_e per head.
 template <int D, int LPH, bool LDSW>
 __device__ __forceinline__ void bwd_item(const FusedArgs& a, const float* ws_lds, int i, int c) {
     constexpr int LPR = D / 4, H = LPR / LPH;
@@ -395,6 +396,11 @@ __device__ __forceinline__ void bwd_item(const FusedArgs& a, const float* ws_lds
                         if (a.dsy) a.dsy[p] = make_float2(dz, al);
                         else a.ds_src[p] = dz;
                     }
+                }
+                if (H > 1 && a.own_singles && k + u < cend && pr[u] < 0 && c % LPH == 0) {
+                    float* hc = reinterpret_cast<float*>(a.dsy) + (size_t)(pr[u] & 0x7FFFFFFF) * 2 * H;
+                    hc[head] = dz;
+                    hc[H + head] = al;
                 }
             }
             const int t = c % LPH;
@@ -499,7 +505,7 @@ rgnn_status_t rgat_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* 
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
     FusedArgs a{};
     a.it = dev_items(L); a.in_pair = g->in_pair_tag; a.in_rel = g->idx[RGNN_IDX_IN_REL]; a.in_run = g->idx[RGNN_IDX_IN_RUN];
-    a.Hs = Hs; a.w_s = w_s; a.s_dst = s_dst; a.slope = slope; a.R = g->R; a.own_singles = H == 1;
+    a.Hs = Hs; a.w_s = w_s; a.s_dst = s_dst; a.slope = slope; a.R = g->R; a.own_singles = H == 1 || dsy != nullptr;
     a.ms = reinterpret_cast<float2*>(const_cast<float*>(ms));
     a.dOut = dOut; a.fout = out; a.adz = adz; a.G = G; a.ds_src = ds_src;
     a.dsy = reinterpret_cast<float2*>(dsy);

@@ -179,6 +179,11 @@ struct TypedLinearBwdArgs {
     const int32_t* ysel = nullptr;
     const float* dY_alt = nullptr;
     const float2* ds_yscale = nullptr;
+    // Per-head row selector (widths up to 64, sel_heads in {2, 4}, instead of rowscale / vec / ds_yscale): a selected
+    // row is dY_alt[row] * a[h] + b[h] * wvec[seg] on the columns of head h, (b[0..H), a[0..H)) = hcoef[i] for row i
+    const float* hcoef = nullptr;    // [rows][2][sel_heads]
+    const float* wvec = nullptr;     // [segs][ND]
+    int sel_heads = 0;
 };
 // bf16 matrix-core variant (typed_linear_bf16.hip): Y[i] = A[g(i)] W[seg]  (or W[seg]^T)
 struct TypedLinearBf16Args {

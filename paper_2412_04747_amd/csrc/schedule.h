@@ -28,11 +28,11 @@ inline int batched_count(int count, uint32_t flags) {
 // bf16 inputs at width 128: every row tensor (inputs, intermediates, saved tensors, incoming gradients) is bf16 storage
 inline bool sched_rows_bf16(int dtype, int d) { return dtype == RGNN_BF16 && d == 128; }
 // The gradient row of a (source, relation) pair with one edge is not materialised: the typed-linear backward reads
-// it from the destination's gradient row through a row selector.  Built for single-head RGAT up to width 64 (the
-// fused fp32 backward kernel) and for RGCN with bf16 rows.
+// it from the destination's gradient row through a row selector.  Built for RGAT up to width 64 with one, two or
+// four heads (the fused fp32 backward kernel) and for RGCN with bf16 rows.
 inline bool sched_row_select(int layer, int dtype, int d, int heads, uint32_t flags) {
     if (flag_set(flags, RGNN_FLAG_NO_ROW_SELECT)) return false;
-    if (layer == RGNN_LAYER_RGAT) return heads == 1 && d <= 64;
+    if (layer == RGNN_LAYER_RGAT) return d <= 64 && (heads == 1 || ((heads == 2 || heads == 4) && d % (4 * heads) == 0));
     if (layer == RGNN_LAYER_RGCN) return sched_rows_bf16(dtype, d);
     return false;
 }

@@ -19,7 +19,7 @@ rgnn_status_t fold_weight(int R, int kd, int nd, const float* W, const float* w,
 rgnn_status_t run_logit(const rgnn_graph* g, int D, const float* X, const float* wtp, float* s_dst, hipStream_t st);
 rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng, const int32_t* via, const float* val,
                                  int stride, int off, float* out, hipStream_t st, const char* label, int min_len = 0,
-                                 int heads = 1, bool long_only = false, int ostride = 1);
+                                 int heads = 1, bool long_only = false, int ostride = 0);   // ostride 0: heads
 // ms (optional, [N] pairs of floats): (max, sum of exp) of the logits of every destination with edges
 rgnn_status_t edge_softmax(const rgnn_graph* g, const float* s_src, const float* s_dst, float slope, float* att,
                            float* part_m, float* part_s, hipStream_t st, float* ms = nullptr);

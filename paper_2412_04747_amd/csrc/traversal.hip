@@ -72,7 +72,7 @@ __global__ void run_logit_kernel(int Q, const int32_t* __restrict__ run_dst, con
     }
 }
 
-// out[i * heads + h] = sum_{j in [ptr[i], ptr[i+1])} val[(via ? via[j] : j) * stride + off + h],  h < heads.
+// out[i * ostride + h] = sum_{j in [ptr[i], ptr[i+1])} val[(via ? via[j] : j) * stride + off + h],  h < heads.
 // One launch: the first n_long * heads workgroups take one (long segment, head) each (segments of more
 // than kSerialMax entries, listed by the graph index; the hub runs are thousands of entries long), the
 // others one lane per (segment, head) for the segments up to that length.  The long ones come first so
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void segment_scalar_sum_kernel(int n, int head
         const float t = group_sum<64>((t0 + t1) + (t2 + t3));
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
         __syncthreads();
-        if (threadIdx.x == 0) out[((size_t)i * heads + h) * ostride] = (red[0] + red[1]) + (red[2] + red[3]);
+        if (threadIdx.x == 0) out[(size_t)i * ostride + h] = (red[0] + red[1]) + (red[2] + red[3]);
         return;
     }
     const int64_t t = (int64_t)(blockIdx.x - long_blocks) * 256 + threadIdx.x;
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void segment_scalar_sum_kernel(int n, int head
 #pragma unroll
         for (int u = 0; u < 4; ++u) s += j + u < e ? v[u] : 0.f;
     }
-    out[t * ostride] = s;
+    out[(size_t)i * ostride + h] = s;
 }
 
 // ------------------------------------------------------------------ edge softmax (RGAT)
@@ -942,6 +942,7 @@ rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng,
     if (n == 0 || (long_only && lng.n == 0)) return RGNN_OK;
     KernelTimer kt(st, label);
     const size_t long_blocks = (size_t)lng.n * heads;
+    if (ostride <= 0) ostride = heads;
     if (long_only) n = 0;   // only the first kind of workgroups: the caller has summed the segments of up to kSerialMax entries
     hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3((unsigned)(long_blocks + blocks_for((size_t)n * heads, 256))), dim3(256), 0, st, n,
                        heads, ptr, via, val, stride, off, min_len, out, lng.n, lng.ids, ostride);

@@ -227,8 +227,14 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
 // relation) pair with a single edge is att_e * dOut[dst_e]; it is read from dOut here instead of
 // being written out per pair first.)  A lane keeps the selector and the scale of one row of the unit
 // and hands them to the lanes that load or store that row with a cross-lane read.
-struct RowSelect { const int32_t* sel; const float* alt; const float2* ds_scale; };
-template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS, bool SEL = false>
+//
+// HS > 0 (row selector with HS heads, instead of RS): the columns form HS equal slices; a selected row is
+//   dY_alt[row] * a[h] + b[h] * wvec[seg]   on the columns of slice h,
+// with (b[0..HS), a[0..HS)) = hcoef[i] per row i.  (Multi-head RGAT: the complete gradient row of a single-edge
+// pair, att_e^h dOut[dst_e] + dz_e^h w_s[r] per head, is formed while the row is staged; rows that are not
+// selected come from dY as they are.)  The lane that owns a row keeps its 2 HS coefficients.
+struct RowSelect { const int32_t* sel; const float* alt; const float2* ds_scale; const float* hcoef; const float* wvec; };
+template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS, bool SEL = false, int HS = 0>
 __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, const float* __restrict__ X,
                                                                     const int32_t* __restrict__ gather,
                                                                     const float* __restrict__ W,
@@ -238,6 +244,7 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
                                                                     const float* __restrict__ vec,
                                                                     float* __restrict__ part, RowSelect ys) {
     static_assert(!SEL || !DYG, "the row selector replaces the dY gather");
+    static_assert(HS == 0 || (SEL && !RS && (HS == 2 || HS == 4)), "per-head row selector: two or four heads, no rowscale");
     constexpr int NW = 8;
     constexpr int XS = KD + 4, YS = (ND > KD ? ND : KD) + 4, WS = ND + 1;
     constexpr int KB = KD / 32, NB = ND / 32, WB = KB * NB;
@@ -269,6 +276,7 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
         __syncthreads();
         float4 xv = make_float4(0.f, 0.f, 0.f, 0.f);
         if (RS && vec) xv = *reinterpret_cast<const float4*>(vec + (size_t)seg * KD + cx * 4);
+        if (HS) xv = *reinterpret_cast<const float4*>(ys.wvec + (size_t)seg * ND + cy * 4);   // this lane's columns of wvec[seg]
         v16f accw[WB];
 #pragma unroll
         for (int b = 0; b < WB; ++b)
@@ -284,6 +292,10 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
         int gi[NXR], gcur[NXR];
         int ysn = 0;          // SEL: selector of row (lane & 31) of the unit whose rows are fetched next
         float alr = 1.f;      // SEL: scale of row (lane & 31) of the unit whose rows are in yr
+        // HS: (b[h0], b[h0 + 1], a[h0], a[h0 + 1]) of row (lane & 31) of the unit whose rows are in yr, (0, 0, 1, 1) for a
+        // row that is not selected; with four heads the upper half of the wavefront keeps heads 2 and 3 (h0 = 2)
+        float hcf[4] = {0.f, 0.f, 1.f, 1.f};
+        const int h0 = HS == 4 ? 2 * (lane >> 5) : 0;
         // LANEIDX: the gather index of row (lane & 31) is kept by that lane and handed to the lanes that
         // load the row with a cross-lane read (one register instead of NXR); the variants that reuse the
         // indices for dY or for the scattered store keep them per load.
@@ -319,7 +331,13 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
                     yr[it] = *reinterpret_cast<const v4f*>(dY + s2 * ND + cy * 4);
                 }
             }
-            if (SEL) {
+            if (HS) {
+                const float* hp = ys.hcoef + (size_t)min(ra + u * 32 + (lane & 31), rbnd - 1) * 2 * HS + h0;
+                const float2 bb = *reinterpret_cast<const float2*>(hp), aa = *reinterpret_cast<const float2*>(hp + HS);
+                const bool on = ysn < 0;
+                hcf[0] = on ? bb.x : 0.f; hcf[1] = on ? bb.y : 0.f;
+                hcf[2] = on ? aa.x : 1.f; hcf[3] = on ? aa.y : 1.f;
+            } else if (SEL) {
                 const float2 pr = ys.ds_scale[min(ra + u * 32 + (lane & 31), rbnd - 1)];
                 dsr = pr.x;
                 alr = ysn < 0 ? pr.y : 1.f;
@@ -345,7 +363,15 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
             for (int it = 0; it < NYR; ++it) {
                 const bool ok = ry + it * RPY < rows_left;
                 v4f v = yr[it];
-                if (SEL) {
+                if (HS) {
+                    // coefficients of this lane's head from the lane that keeps them for the row
+                    const int hd = cy / (LPRY / HS);
+                    const int from = ry + it * RPY + (HS == 4 ? 32 * (hd >> 1) : 0);
+                    const float b0 = __shfl(hcf[0], from), b1 = __shfl(hcf[1], from);
+                    const float a0 = __shfl(hcf[2], from), a1 = __shfl(hcf[3], from);
+                    const float bq = hd & 1 ? b1 : b0, aq = hd & 1 ? a1 : a0;
+                    v = v4f{v[0] * aq + bq * xv.x, v[1] * aq + bq * xv.y, v[2] * aq + bq * xv.z, v[3] * aq + bq * xv.w};
+                } else if (SEL) {
                     const float sc = __shfl(alr, ry + it * RPY);
                     v = v4f{v[0] * sc, v[1] * sc, v[2] * sc, v[3] * sc};
                 }
@@ -682,16 +708,16 @@ static rgnn_status_t launch_slot_reduce(int kd, int nd, const TypedLinearBwdArgs
     return RGNN_OK;
 }
 
-template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS, bool SEL = false>
+template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS, bool SEL = false, int HS = 0>
 static rgnn_status_t launch_bwd_wave(const TypedLinearBwdArgs& a, hipStream_t st) {
     constexpr int WREG = 32 * (KD + 4) + 32 * ((ND > KD ? ND : KD) + 4) + 32;
     static_assert(WREG >= KD * ND + KD, "per-wavefront LDS region must hold a weight-gradient copy");
     const size_t lds = sizeof(float) * (KD * (ND + 1) + 8 * WREG);
-    auto kern = typed_linear_bwd_wave_kernel<KD, ND, GATHER, DYG, SCATTER, RS, SEL>;
+    auto kern = typed_linear_bwd_wave_kernel<KD, ND, GATHER, DYG, SCATTER, RS, SEL, HS>;
     RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     KernelTimer kt(st, a.label ? a.label : "typed_linear_bwd");
     hipLaunchKernelGGL(kern, dim3(a.tiles->num_chunks), dim3(512), lds, st, tile_args(*a.tiles), a.X, a.gather, a.W,
-                       a.dY, a.dXrow, a.rowscale, a.vec, a.part, RowSelect{a.ysel, a.dY_alt, a.ds_yscale});
+                       a.dY, a.dXrow, a.rowscale, a.vec, a.part, RowSelect{a.ysel, a.dY_alt, a.ds_yscale, a.hcoef, a.wvec});
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -740,9 +766,14 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
         if constexpr (KD <= 64 && ND <= 64) {
             const bool g = a.gather != nullptr, dg = g && a.dy_gathered, sc = g && a.scatter_dx, rs = a.rowscale != nullptr;
             done = true;
-            if (a.ysel && !(g && !dg && !sc && !rs && a.vec && a.dY_alt && a.ds_yscale))
+            if (a.ysel && a.hcoef) {
+                if (!(g && !dg && !sc && !rs && a.dY_alt && a.wvec) || (a.sel_heads != 2 && a.sel_heads != 4) || ND % (4 * a.sel_heads))
+                    RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: the per-head row selector needs gathered X, ungathered dY, no rowscale, 2 or 4 heads of a multiple of 4 columns");
+                if (a.sel_heads == 2) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, false, true, 2>(a, st)));
+                else RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, false, true, 4>(a, st)));
+            } else if (a.ysel && !(g && !dg && !sc && !rs && a.vec && a.dY_alt && a.ds_yscale))
                 RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: the row selector needs gathered X, ungathered dY, vec and the (rowscale, scale) pairs");
-            if (a.ysel) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true, true>(a, st)));
+            else if (a.ysel) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true, true>(a, st)));
             else if (g && !dg && !sc && rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true>(a, st)));
             else if (g && !dg && !sc && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, false>(a, st)));
             else if (g && dg && sc && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, true, true, false>(a, st)));

@@ -103,14 +103,14 @@ def test_many_single_edge_destinations():
     _run(N, R, src, dst, rel, p, d, "singles")
 
 
-def _run_heads(N, R, src, dst, rel, p, d, H, tag, dtype="f32", slope=0.2):
+def _run_heads(N, R, src, dst, rel, p, d, H, tag, dtype="f32", slope=0.2, flags=0):
     import torch
     from paper_2412_04747_amd.harness import Graph, RgatLayer
     from parity import TOL_BF16
     print(f"rgat case {tag}: N={N} R={R} E={len(src)} d={d} heads={H} {dtype}", flush=True)
     tol = TOL_BF16 if dtype == "bf16" else TOL_F32
     g = Graph(N, R, src, dst, rel)
-    L = RgatLayer(g, d, slope, dtype=dtype, heads=H)
+    L = RgatLayer(g, d, slope, dtype=dtype, heads=H, flags=flags)
     L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
     L.fwd()
     torch.cuda.synchronize()
@@ -145,6 +145,16 @@ def test_multi_head(d, H):
     src[:300] = 9; rel[:300] = 2                     # one pair with many edges
     p = synth.rgat_params(rng, 800, 6, d, d)
     _run_heads(800, 6, src, dst, rel, p, d, H, f"heads-d{d}-H{H}")
+
+
+@pytest.mark.parametrize("d,H", [(64, 4), (32, 2)])
+def test_multi_head_rows_written_per_pair(d, H):
+    # the schedule without the row selector: every pair's gradient row is stored, also for the pairs with one edge
+    rng, src, dst, rel, _ = synth.tiny(190 + d + H, N=800, R=6, E=7000)
+    dst[:1200] = 4
+    src[:300] = 9; rel[:300] = 2
+    p = synth.rgat_params(rng, 800, 6, d, d)
+    _run_heads(800, 6, src, dst, rel, p, d, H, f"heads-d{d}-H{H}-noselect", flags=4)       # RGNN_FLAG_NO_ROW_SELECT
 
 
 def test_multi_head_bf16_inputs_and_empty_relation():

@@ -273,8 +273,11 @@ def test_schedule_flags_force_the_alternatives(wl):
     ep = pick(wl, c, k, flags=1)
     assert ep["edge_parallel"] and not ep["fused_softmax"]
     heads = pick(wl, c, k, heads=4)
-    assert heads["fused_softmax"] and not heads["row_select"] and not heads["pair_walk_multi_only"]
-    assert heads["pair_batched_single"]                     # several heads: the pair-major walk takes every pair
+    assert heads["fused_softmax"] and heads["row_select"] and heads["pair_walk_multi_only"]
+    assert not heads["pair_batched_single"]                 # two or four heads: the row selector serves the single-edge pairs
+    eight = pick(wl, c, k, heads=8)
+    assert eight["fused_softmax"] and not eight["row_select"] and not eight["pair_walk_multi_only"]
+    assert eight["pair_batched_single"]                     # other head counts: the pair-major walk takes every pair
     big_r = dict(c, R=300)                                  # 300 x 64 floats = 75 KB: w_s no longer fits the LDS budget
     assert pick(wl, big_r, k)["fused_softmax"] and not pick(wl, big_r, k)["ws_in_lds"]
     c4 = synth.config(4, scale=0.001, graph_only=True)
