@@ -600,12 +600,15 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         RGNN_TRY(segment_scalar_sum((int)g->Q, g->idx[RGNN_IDX_RUN_PTR], g->long_runs, nullptr, w.adz, 2 * H, H, w.ds_dst, st,
                                     "ds_dst_sum", 0, H));
         RGNN_TRY(segment_scalar_sum((int)g->P, g->idx[RGNN_IDX_OUT_PTR], g->long_pairs, g->idx[RGNN_IDX_OUT_EPOS], w.adz, 2 * H, H,
-                                    w.ds_src, st, "ds_src_sum", sel ? 2 : 0, H, false, 2 * H));
-        // 3. dHs[p] = sum_{e in out(p)} att_e dOut[dst_e] (per head)  +  ds_src[p][h] w_s[r] (per head); with the
-        //    selector only for the pairs with several edges: step 4 forms the other rows from dOut as it reads them
+                                    w.ds_src, st, "ds_src_sum", sel ? 2 : 0, H, sel, 2 * H));
+        // 3. dHs[p] = sum_{e in out(p)} att_e dOut[dst_e] (per head)  +  ds_src[p][h] w_s[r] (per head).  With the
+        //    selector only for the pairs with several edges (step 4 forms the other rows from dOut as it reads them),
+        //    and the walk sums ds_src[p][h] itself over the same (att, dz) entries; step 2 then covered only the pairs
+        //    with more edges than a lane sums, among them the ones the walk cuts into pieces.
         const Rank1 r1{w.ds_src, 2 * H, g->idx[RGNN_IDX_PAIR_REL], ws};      // the second term, added when a pair's row is stored
         RGNN_TRY(gather_sum(sel ? g->pair_items_multi : g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.adz,
-                            2 * H, 0, dO, w.G, w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", H, 0, 0, &r1));
+                            2 * H, 0, dO, w.G, w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", H, 0, 0, &r1,
+                            sel ? w.ds_src : nullptr, 2 * H));
         // 4. dXp = dHs W^T, dW = sum X^T dHs
         TypedLinearBwdArgs b{};
         b.tiles = &g->pair_tiles_wide; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;

@@ -128,6 +128,62 @@ __global__ __launch_bounds__(256) void segment_scalar_sum_kernel(int n, int head
     out[(size_t)i * ostride + h] = s;
 }
 
+// The same sums for HV = 2 or 4 heads whose values lie side by side (stride, off and ostride multiples of HV, val
+// and out aligned to HV floats): one lane per segment adds all HV heads at once with vector loads, one workgroup per
+// long segment.  The order of the additions per head is the one of the kernel above.
+template <int HV>
+__global__ __launch_bounds__(256) void segment_vec_sum_kernel(int n, const int32_t* __restrict__ ptr,
+                                                              const int32_t* __restrict__ via, const float* __restrict__ val,
+                                                              int stride, int off, int min_len, float* __restrict__ out,
+                                                              int n_long, const int32_t* __restrict__ long_ids, int ostride) {
+    struct __align__(4 * HV) Vec { float v[HV]; };
+    __shared__ float red[4][HV];
+    auto load = [&](int j) { return *reinterpret_cast<const Vec*>(val + (size_t)(via ? via[j] : j) * stride + off); };
+    if ((int)blockIdx.x < n_long) {
+        const int i = long_ids[blockIdx.x];
+        const int b = ptr[i], e = ptr[i + 1];
+        float t[4][HV];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int h = 0; h < HV; ++h) t[u][h] = 0.f;
+        for (int j = b + (int)threadIdx.x; j < e; j += 1024) {
+            Vec x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x[u] = load(min(j + 256 * u, e - 1));
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int h = 0; h < HV; ++h) t[u][h] += j + 256 * u < e ? x[u].v[h] : 0.f;
+        }
+#pragma unroll
+        for (int h = 0; h < HV; ++h) {
+            const float w = group_sum<64>((t[0][h] + t[1][h]) + (t[2][h] + t[3][h]));
+            if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6][h] = w;
+        }
+        __syncthreads();
+        if (threadIdx.x < HV) out[(size_t)i * ostride + threadIdx.x] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+        return;
+    }
+    const int64_t i = (int64_t)(blockIdx.x - n_long) * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int b = ptr[i], e = ptr[i + 1];
+    if (e - b > kSerialMax || e - b < min_len) return;
+    Vec s;
+#pragma unroll
+    for (int h = 0; h < HV; ++h) s.v[h] = 0.f;
+    for (int j = b; j < e; j += 4) {
+        Vec x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u] = load(min(j + u, e - 1));
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int h = 0; h < HV; ++h) s.v[h] += j + u < e ? x[u].v[h] : 0.f;
+    }
+    *reinterpret_cast<Vec*>(out + (size_t)i * ostride) = s;
+}
+
 // ------------------------------------------------------------------ edge softmax (RGAT)
 
 // Per item of the destination-major list: l_e = leakyrelu(s_src[pair] + s_dst[run]) is
@@ -288,9 +344,20 @@ struct GatherArgs {
     int skip_n;
     Rank1 r1;             // optional: out[row_i] += r1.coef[row_i][head] * r1.vec[r1.seg[row_i]] (whole segments here,
                           // cut segments when their pieces are combined)
-    float* sum2;          // optional (S2 kernels): sum2[row_i * sum2_stride] = sum_j coef[k * cstride + 1] for the whole
-    int sum2_stride;      // segments, added in entry order; the caller sums the cut segments itself
+    float* sum2;          // optional (S2 kernels): sum2[row_i * sum2_stride + head] = sum_j coef[k * cstride + s2off + head]
+    int sum2_stride;      // for the whole segments, added in entry order; the caller sums the cut segments itself.  With
+    int s2off;            // r1.vec set, the walk also adds that sum times r1.vec[r1.seg[row_i]] to the row (r1.coef then
+                          // serves only the cut segments, where their pieces are combined)
 };
+
+// the rank-1 term of a whole segment whose coefficient the walk has just summed
+template <int D, int V>
+__device__ __forceinline__ void add_rank1_own(const Rank1& r1, float c, size_t row, int cv, float (&acc)[V]) {
+    if (!r1.vec) return;
+    float t[V];
+    load_cols(r1.vec + (size_t)r1.seg[row] * D + cv * V, t);
+    fma_cols(acc, c, t);
+}
 
 template <int D, int V>
 __device__ __forceinline__ void add_rank1(const Rank1& r1, int lanes_per_head, size_t row, int cv, float (&acc)[V]) {
@@ -333,7 +400,7 @@ __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
         float cc = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;                           \
         if (a.cabs) cc = fabsf(cc);                                                               \
         c[u] = (J) + u < e ? cc : 0.f;                                                            \
-        if (S2) c2[S2 ? u : 0] = (J) + u < e ? a.coef[(size_t)k * a.cstride + 1] : 0.f;           \
+        if (S2) c2[S2 ? u : 0] = (J) + u < e ? a.coef[(size_t)k * a.cstride + a.s2off + head] : 0.f; \
     }
     if (b < e) {
         RGNN_GATHER_FETCH_IDX(b)
@@ -361,8 +428,9 @@ __device__ __forceinline__ void gather_general(const GatherArgs& a, int blk) {
     const int slot = a.it.slot[i];
     if (slot < 0) {
         if (R1) add_rank1<D>(a.r1, a.lanes_per_head, (size_t)a.it.row[i], cv, acc0);
+        if (S2) add_rank1_own<D>(a.r1, s2, (size_t)a.it.row[i], cv, acc0);
         store_cols(static_cast<TO*>(a.out) + (size_t)a.it.row[i] * D + cv * V, acc0);
-        if (S2 && cv == 0) a.sum2[(size_t)a.it.row[i] * a.sum2_stride] = s2;
+        if (S2 && cv % a.lanes_per_head == 0) a.sum2[(size_t)a.it.row[i] * a.sum2_stride + head] = s2;
     } else {
         store_cols(a.partial + (size_t)slot * D + cv * V, acc0);
     }
@@ -400,7 +468,7 @@ __device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int f
             float cc = a.coef ? a.coef[(size_t)k * a.cstride + head] : 1.f;
             if (a.cabs) cc = fabsf(cc);
             c[q][u] = b[q] + u < e[q] ? cc : 0.f;
-            if (S2) s2[q] += b[q] + u < e[q] ? a.coef[(size_t)k * a.cstride + 1] : 0.f;
+            if (S2) s2[q] += b[q] + u < e[q] ? a.coef[(size_t)k * a.cstride + a.s2off + head] : 0.f;
         }
     float v[2][kShortLen][V];
 #pragma unroll
@@ -418,8 +486,9 @@ __device__ __forceinline__ void gather_short(const GatherArgs& a, int blk, int f
         for (int u = 0; u < kShortLen; ++u) fma_cols(acc, c[q][u], v[q][u]);
         if (i0 + q < n) {
             if (R1) add_rank1<D>(a.r1, a.lanes_per_head, (size_t)orow[q], cv, acc);
+            if (S2) add_rank1_own<D>(a.r1, s2[q], (size_t)orow[q], cv, acc);
             store_cols(static_cast<TO*>(a.out) + (size_t)orow[q] * D + cv * V, acc);
-            if (S2 && cv == 0) a.sum2[(size_t)orow[q] * a.sum2_stride] = s2[q];
+            if (S2 && cv % a.lanes_per_head == 0) a.sum2[(size_t)orow[q] * a.sum2_stride + head] = s2[q];
         }
     }
 }
@@ -482,9 +551,9 @@ __global__ __launch_bounds__(256) void gather_sum_kernel(GatherArgs a, GatherRan
     else if (blk < r.general_blocks + r.short_blocks) gather_short<D, TI, TO, R1, ROLE == 0>(a, blk - r.general_blocks, r.short_first, r.short_n);
     else gather_single<D, TI, TO, R1, ROLE == 0>(a, blk - r.general_blocks - r.short_blocks, r.single_first, r.single_n);
 }
-// The pair-major walk that also sums the second coefficient of every entry per segment (GatherArgs::sum2; fp32
-// rows, lists without single-entry segments), held to the register budget of eight wavefronts per SIMD like the
-// plain walk.
+// The pair-major walk that also sums the second coefficient of every entry per segment and head (GatherArgs::sum2;
+// fp32 rows, lists without single-entry segments), held to the register budget of eight wavefronts per SIMD like
+// the plain walk.
 template <int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) void gather_sum_s2_kernel(GatherArgs a, GatherRanges r) {
     const int blk = blockIdx.x;
@@ -944,6 +1013,13 @@ rgnn_status_t segment_scalar_sum(int n, const int32_t* ptr, const LongList& lng,
     const size_t long_blocks = (size_t)lng.n * heads;
     if (ostride <= 0) ostride = heads;
     if (long_only) n = 0;   // only the first kind of workgroups: the caller has summed the segments of up to kSerialMax entries
+    if ((heads == 2 || heads == 4) && stride % heads == 0 && off % heads == 0 && ostride % heads == 0) {
+        const dim3 grid((unsigned)(lng.n + blocks_for((size_t)n, 256)));
+        if (heads == 2) hipLaunchKernelGGL(segment_vec_sum_kernel<2>, grid, dim3(256), 0, st, n, ptr, via, val, stride, off, min_len, out, lng.n, lng.ids, ostride);
+        else hipLaunchKernelGGL(segment_vec_sum_kernel<4>, grid, dim3(256), 0, st, n, ptr, via, val, stride, off, min_len, out, lng.n, lng.ids, ostride);
+        RGNN_CHECK_LAUNCH();
+        return RGNN_OK;
+    }
     hipLaunchKernelGGL(segment_scalar_sum_kernel, dim3((unsigned)(long_blocks + blocks_for((size_t)n * heads, 256))), dim3(256), 0, st, n,
                        heads, ptr, via, val, stride, off, min_len, out, lng.n, lng.ids, ostride);
     RGNN_CHECK_LAUNCH();
@@ -998,7 +1074,7 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
     const int ns = batched_count(L.num_single, current_schedule_flags());
     const int nsh = batched_count(L.num_short, current_schedule_flags());
     const int skip_first = nsh > 0 ? L.first_short : L.first_single;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns, r1v, sum2, sum2_stride};
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, cstride, cabs, lpr / heads, src, out, partial, skip_first, nsh + ns, r1v, sum2, sum2_stride, heads};
     {
         KernelTimer kt(st, label);
         GatherRanges r{};
@@ -1015,9 +1091,9 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
         RGNN_CHECK_LAUNCH();                                                                                               \
     } while (0)
         if (r1 && (src_bf16 || out_bf16 || role != 1)) RGNN_FAIL(RGNN_EUNSUPPORTED, "gather_sum: the rank-1 term is built for fp32 rows of the pair-major walk");
-        if (sum2 && (src_bf16 || out_bf16 || role != 1 || r1 || heads != 1 || !coef || cstride < 2 || ns > 0 || L.num_single > 0))
-            RGNN_FAIL(RGNN_EUNSUPPORTED, "gather_sum: the second sum is built for fp32 rows of the single-head pair-major walk over lists without single-entry segments");
-        if (r1) {
+        if (sum2 && (src_bf16 || out_bf16 || role != 1 || !coef || cstride < 2 * heads || ns > 0 || L.num_single > 0))
+            RGNN_FAIL(RGNN_EUNSUPPORTED, "gather_sum: the second sum is built for fp32 rows of the pair-major walk over lists without single-entry segments");
+        if (r1 && !sum2) {
             if (grid.x > 0) {
                 RGNN_DISPATCH_D(D, hipLaunchKernelGGL((gather_sum_kernel<DD, 1, float, float, true>), grid, dim3(256), 0, st, a, r));
                 RGNN_CHECK_LAUNCH();
@@ -1053,7 +1129,7 @@ rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, c
                                 int row_by_k, const float* coef, const float* src, float* out, float* partial,
                                 hipStream_t st, const char* label, const char* combine_label) {
     if (L.num_items == 0) return RGNN_OK;
-    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, H, 0, 1, src, out, partial, 0, 0, Rank1{nullptr, 0, nullptr, nullptr}, nullptr, 1};
+    GatherArgs a{dev_items(L), via, rowidx, row_by_k, coef, H, 0, 1, src, out, partial, 0, 0, Rank1{nullptr, 0, nullptr, nullptr}, nullptr, 1, 1};
     {
         KernelTimer kt(st, label);
         const dim3 grid(blocks_for(L.num_items, 256 / (D / 4)));
