@@ -140,9 +140,9 @@ size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
     w->ds_src = c.take<float>(2 * (size_t)g->P * H);
     w->G = c.take<float>((size_t)g->P * d->d_out);
     w->dXp = c.take<float>((size_t)g->P * d->d_in);
-    w->A = c.take<float>((size_t)g->R * d->d_in);
+    w->A = c.take<float>(H * g->R * d->d_in);
     w->U = c.take<float>(H * g->R * d->d_in);
-    w->tl_part = c.take<float>(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles));
+    w->tl_part = c.take<float>(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles, (int)H));
     const size_t parts = std::max<size_t>({(size_t)g->pair_items.num_partials, (size_t)g->relrun_items.num_partials,
                                            (size_t)g->relpair_items.num_partials});
     w->partial = c.take<float>(parts * std::max(d->d_in, d->d_out) * H);   // the run walk keeps one partial row per head
@@ -609,19 +609,22 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         RGNN_TRY(gather_sum(sel ? g->pair_items_multi : g->pair_items, D, g->idx[RGNN_IDX_OUT_EPOS], g->idx[RGNN_IDX_OUT_DST], 0, w.adz,
                             2 * H, 0, dO, w.G, w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", H, 0, 0, &r1,
                             sel ? w.ds_src : nullptr, 2 * H));
-        // 4. dXp = dHs W^T, dW = sum X^T dHs
+        // 4. dXp = dHs W^T, dW = sum X^T dHs; with the selector also A[r][h] = sum over r's pairs of ds_src[p][h] X[src_p]
         TypedLinearBwdArgs b{};
         b.tiles = &g->pair_tiles_wide; b.X = Xf; b.gather = g->idx[RGNN_IDX_PAIR_SRC]; b.W = Wf; b.dY = w.G; b.dXrow = w.dXp;
         b.dW = static_cast<float*>(dW); b.part = w.tl_part;
-        if (sel) { b.ysel = g->pair_ysel; b.dY_alt = dO; b.hcoef = w.ds_src; b.wvec = ws; b.sel_heads = H; }
+        if (sel) { b.ysel = g->pair_ysel; b.dY_alt = dO; b.hcoef = w.ds_src; b.wvec = ws; b.sel_heads = H; b.Avec = w.A; }
         RGNN_TRY(typed_linear_bwd(K, D, b, st));
-        // 5. dw_s[r] = sum over r's pairs of ds_src[p][h] Hs[p] (per head; the pair rows are in relation order)
-        RGNN_TRY(gather_sum(g->relpair_items, D, nullptr, nullptr, 0, w.ds_src, 2 * H, 0, sv.Hs, dw_s, w.partial, st, 2,
-                            "src_vec_grad", "src_vec_grad.combine", H));
+        // 5. dw_s[r] = sum over r's pairs of ds_src[p][h] Hs[p] (per head; the pair rows are in relation order);
+        //    with the selector from A instead, in step 6: dw_s[r] = (A[r][h] W[r]) on the columns of head h
+        if (!sel)
+            RGNN_TRY(gather_sum(g->relpair_items, D, nullptr, nullptr, 0, w.ds_src, 2 * H, 0, sv.Hs, dw_s, w.partial, st, 2,
+                                "src_vec_grad", "src_vec_grad.combine", H));
         // 6. U[h][r] = sum over r's runs of ds_dst[q][h] X[run_dst[q]];  dw_t and the w_t part of dW from it
         RGNN_TRY(gather_heads_rows(g->relrun_items, K, H, g->R, g->idx[RGNN_IDX_RELRUN_IDX], g->relrun_dst, 0, w.ds_dst,
                                    Xf, w.U, w.partial, st, "dst_side_wgrad", "dst_side_wgrad.combine"));
-        RGNN_TRY(rgat_heads_param_finish(g->R, K, D, H, Wf, wt, w.U, static_cast<float*>(dW), static_cast<float*>(dw_t), st));
+        RGNN_TRY(rgat_heads_param_finish(g->R, K, D, H, Wf, wt, w.U, sel ? w.A : nullptr, static_cast<float*>(dW),
+                                         static_cast<float*>(dw_s), static_cast<float*>(dw_t), st));
         // 7. dX[u] = sum over u's pairs of dXp + sum over u's runs and heads of ds_dst[q][h] (W[r] w_t[r])_h
         RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, wt, w.wtp, st));
         return node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, nullptr, dX, st, 0, 0, H);

@@ -56,9 +56,12 @@ __global__ __launch_bounds__(256) void run_logit_heads_kernel(int Q, int R, int 
 
 // Per relation r, with U[h][r] = sum_q ds_dst[q][h] X[dst_q] and h(n) the head of column n:
 //   dw_t[r][n] = sum_k U[h(n)][r][k] W[r][k][n];   dW[r][k][n] += U[h(n)][r][k] * w_t[r][n]
+// and, where A[r][h] = sum_p ds_src[p][h] X[src_p] is given (otherwise the caller forms dw_s from the message rows),
+//   dw_s[r][n] = sum_k A[r][h(n)][k] W[r][k][n]
 __global__ void rgat_heads_param_finish_kernel(int R, int kd, int nd, int H, const float* __restrict__ W,
                                                const float* __restrict__ w_t, const float* __restrict__ U,
-                                               float* __restrict__ dW, float* __restrict__ dw_t) {
+                                               const float* __restrict__ A, float* __restrict__ dW,
+                                               float* __restrict__ dw_s, float* __restrict__ dw_t) {
     const int r = blockIdx.x, dh = nd / H;
     const float* Wr = W + (size_t)r * kd * nd;
     for (int n = threadIdx.x; n < nd; n += blockDim.x) {
@@ -66,6 +69,12 @@ __global__ void rgat_heads_param_finish_kernel(int R, int kd, int nd, int H, con
         float t = 0.f;
         for (int k = 0; k < kd; ++k) t += Ur[k] * Wr[k * nd + n];
         dw_t[(size_t)r * nd + n] = t;
+        if (A) {
+            const float* Ar = A + ((size_t)r * H + n / dh) * kd;
+            float s = 0.f;
+            for (int k = 0; k < kd; ++k) s += Ar[k] * Wr[k * nd + n];
+            dw_s[(size_t)r * nd + n] = s;
+        }
     }
     for (int i = threadIdx.x; i < kd * nd; i += blockDim.x) {
         const int k = i / nd, n = i % nd;
@@ -95,9 +104,9 @@ rgnn_status_t run_logit_heads(const rgnn_graph* g, int D, int H, const float* X,
 }
 
 rgnn_status_t rgat_heads_param_finish(int R, int kd, int nd, int H, const float* W, const float* w_t, const float* U,
-                                      float* dW, float* dw_t, hipStream_t st) {
+                                      const float* A, float* dW, float* dw_s, float* dw_t, hipStream_t st) {
     KernelTimer kt(st, "rgat_param_finish");
-    hipLaunchKernelGGL(rgat_heads_param_finish_kernel, dim3(R), dim3(256), 0, st, R, kd, nd, H, W, w_t, U, dW, dw_t);
+    hipLaunchKernelGGL(rgat_heads_param_finish_kernel, dim3(R), dim3(256), 0, st, R, kd, nd, H, W, w_t, U, A, dW, dw_s, dw_t);
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

@@ -169,7 +169,7 @@ struct TypedLinearBwdArgs {
     const float* rowscale;   // optional [rows]: A[seg] = sum_i rowscale[i] X_row_i
     const float* vec;        // optional [segs][KD] (with rowscale): dXrow[i] += rowscale[i] * vec[seg]
     float* dW;               // [segs][KD][ND]
-    float* Avec;             // [segs][KD] (with rowscale)
+    float* Avec;             // [segs][KD] (with rowscale); [segs][sel_heads][KD] = sum over the rows of hcoef[i][h] X[g(i)] (with hcoef)
     float* part;             // scratch [num_slots][KD*ND + KD]
     const char* label;
     // Optional row selector (widths up to 64, ungathered dY): row i of dY is
@@ -225,7 +225,7 @@ rgnn_status_t typed_linear_wgrad_bf16(int d, const TypedLinearWgradBf16Args& a, 
 rgnn_status_t typed_linear_slot_reduce(int d_in, int d_out, const TileList& tiles, const float* part, float* dW,
                                        float* Avec, hipStream_t st);
 
-size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t);
+size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t, int vectors = 1);   // vectors: of a slot's vector part
 rgnn_status_t typed_linear_bwd(int d_in, int d_out, const TypedLinearBwdArgs& a, hipStream_t st);
 
 }  // namespace rgnn

@@ -81,8 +81,8 @@ rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* a
 rgnn_status_t fold_weight_heads(int R, int kd, int nd, int H, const float* W, const float* w, float* wv, hipStream_t st);
 rgnn_status_t run_logit_heads(const rgnn_graph* g, int D, int H, const float* X, const float* wtp, float* s_dst,
                               hipStream_t st);
-rgnn_status_t rgat_heads_param_finish(int R, int kd, int nd, int H, const float* W, const float* w_t, const float* U,
-                                      float* dW, float* dw_t, hipStream_t st);
+rgnn_status_t rgat_heads_param_finish(int R, int kd, int nd, int H, const float* W, const float* w_t, const float* U, const float* A,
+                                      float* dW, float* dw_s, float* dw_t, hipStream_t st);
 // out[v] = sum_e |att_e| Hs[pair_e] edge by edge with atomic adds (zeroes out first); fp32 rows
 rgnn_status_t aggregate_edge_parallel(const rgnn_graph* g, int D, const float* att, const float* Hs, float* out,
                                       hipStream_t st);

@@ -232,7 +232,8 @@ __global__ __launch_bounds__(256) void typed_linear_fwd_wave_kernel(TileArgs t, 
 //   dY_alt[row] * a[h] + b[h] * wvec[seg]   on the columns of slice h,
 // with (b[0..HS), a[0..HS)) = hcoef[i] per row i.  (Multi-head RGAT: the complete gradient row of a single-edge
 // pair, att_e^h dOut[dst_e] + dz_e^h w_s[r] per head, is formed while the row is staged; rows that are not
-// selected come from dY as they are.)  The lane that owns a row keeps its 2 HS coefficients.
+// selected come from dY as they are.)  The slot's vector part then holds HS vectors, sum over the rows of
+// b[h] * X[g(i)] for h < HS (selected or not: b is the row's rowscale per head).
 struct RowSelect { const int32_t* sel; const float* alt; const float2* ds_scale; const float* hcoef; const float* wvec; };
 template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS, bool SEL = false, int HS = 0>
 __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, const float* __restrict__ X,
@@ -248,7 +249,8 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
     constexpr int NW = 8;
     constexpr int XS = KD + 4, YS = (ND > KD ? ND : KD) + 4, WS = ND + 1;
     constexpr int KB = KD / 32, NB = ND / 32, WB = KB * NB;
-    constexpr int SLOT = KD * ND + KD;
+    constexpr int NA = HS ? HS : 1;                         // vectors in a slot's vector part
+    constexpr int SLOT = KD * ND + NA * KD;
     constexpr int LPRX = KD / 4, RPX = 64 / LPRX, NXR = 32 / RPX;
     constexpr int LPRY = ND / 4, RPY = 64 / LPRY, NYR = 32 / RPY;
     constexpr int WREG = 32 * XS + 32 * YS + 32;            // floats of LDS per wavefront
@@ -283,8 +285,12 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) accw[b][v] = 0.f;
         float pa[KB];                                       // partial of Avec[kb * 32 + m] over the rows of parity kh
+        v4f pah[HS ? KB : 1];                               // HS: the same for heads 0..3 (element h)
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) pa[kb] = 0.f;
+        for (int kb = 0; kb < KB; ++kb) {
+            pa[kb] = 0.f;
+            pah[HS ? kb : 0] = v4f{0.f, 0.f, 0.f, 0.f};
+        }
         // Rows past the end of the run are clamped to its last row (loads stay unconditional)
         // and zeroed when they are written to LDS, so they add nothing to the weight gradient.
         v4f xr[NXR], yr[NYR];
@@ -292,9 +298,10 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
         int gi[NXR], gcur[NXR];
         int ysn = 0;          // SEL: selector of row (lane & 31) of the unit whose rows are fetched next
         float alr = 1.f;      // SEL: scale of row (lane & 31) of the unit whose rows are in yr
-        // HS: (b[h0], b[h0 + 1], a[h0], a[h0 + 1]) of row (lane & 31) of the unit whose rows are in yr, (0, 0, 1, 1) for a
-        // row that is not selected; with four heads the upper half of the wavefront keeps heads 2 and 3 (h0 = 2)
+        // HS: (b[h0], b[h0 + 1], a[h0], a[h0 + 1]) of row (lane & 31) of the unit whose rows are in yr, a = 1 for a row
+        // that is not selected (hon false); with four heads the upper half of the wavefront keeps heads 2 and 3 (h0 = 2)
         float hcf[4] = {0.f, 0.f, 1.f, 1.f};
+        bool hon = false;
         const int h0 = HS == 4 ? 2 * (lane >> 5) : 0;
         // LANEIDX: the gather index of row (lane & 31) is kept by that lane and handed to the lanes that
         // load the row with a cross-lane read (one register instead of NXR); the variants that reuse the
@@ -334,9 +341,9 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
             if (HS) {
                 const float* hp = ys.hcoef + (size_t)min(ra + u * 32 + (lane & 31), rbnd - 1) * 2 * HS + h0;
                 const float2 bb = *reinterpret_cast<const float2*>(hp), aa = *reinterpret_cast<const float2*>(hp + HS);
-                const bool on = ysn < 0;
-                hcf[0] = on ? bb.x : 0.f; hcf[1] = on ? bb.y : 0.f;
-                hcf[2] = on ? aa.x : 1.f; hcf[3] = on ? aa.y : 1.f;
+                hon = ysn < 0;
+                hcf[0] = bb.x; hcf[1] = bb.y;
+                hcf[2] = hon ? aa.x : 1.f; hcf[3] = hon ? aa.y : 1.f;
             } else if (SEL) {
                 const float2 pr = ys.ds_scale[min(ra + u * 32 + (lane & 31), rbnd - 1)];
                 dsr = pr.x;
@@ -367,7 +374,7 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
                     // coefficients of this lane's head from the lane that keeps them for the row
                     const int hd = cy / (LPRY / HS);
                     const int from = ry + it * RPY + (HS == 4 ? 32 * (hd >> 1) : 0);
-                    const float b0 = __shfl(hcf[0], from), b1 = __shfl(hcf[1], from);
+                    const float b0 = __shfl(hon ? hcf[0] : 0.f, from), b1 = __shfl(hon ? hcf[1] : 0.f, from);
                     const float a0 = __shfl(hcf[2], from), a1 = __shfl(hcf[3], from);
                     const float bq = hd & 1 ? b1 : b0, aq = hd & 1 ? a1 : a0;
                     v = v4f{v[0] * aq + bq * xv.x, v[1] * aq + bq * xv.y, v[2] * aq + bq * xv.z, v[3] * aq + bq * xv.w};
@@ -380,6 +387,14 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
             }
             const float dsc = RS && (lane & 31) < rows_left ? dsr : 0.f;   // rowscale of row (lane & 31), zero past the end
             if (RS && lane < 32) dsw[lane] = dsc;
+            if (HS) {
+                // the row's rowscale per head goes into the four spare floats that end its row of Xw (zero past the end);
+                // the weight-gradient section reads them back row by row
+                static_assert(XS - KD == 4, "the spare floats of an X row hold the per-head rowscale");
+                const bool ok = (lane & 31) < rows_left;
+                if (HS == 4 || lane < 32)
+                    *reinterpret_cast<float2*>(Xw + (lane & 31) * XS + KD + h0) = make_float2(ok ? hcf[0] : 0.f, ok ? hcf[1] : 0.f);
+            }
             wave_lds_fence();
             fetch(u + NW);
             fetch_idx(u + 2 * NW);
@@ -420,9 +435,14 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
             }
             // weight gradient: KD x ND, contraction over the unit's 32 rows (two rows per MFMA).  The rows'
             // contribution to Avec rides along: lane (m, kh) holds X[2 s + kh][kb * 32 + m] as its A operand
-            // and adds rowscale[2 s + kh] times it to its partial of column kb * 32 + m.
+            // and adds rowscale[2 s + kh] times it to its partial of column kb * 32 + m.  With heads, a 4x4x1 MFMA
+            // does that for four heads at once: each group of four lanes forms the outer product of the rowscale of
+            // its row for heads 0..3 (lane j of the group brings head j's) with the group's four X values, and lane
+            // (m, kh) gets the four heads' partials of its column.
             {
                 float av[KB], bv[NB];
+                float c1 = 0.f, c1n = 0.f;
+                if (HS) c1 = Xw[kh * XS + KD + (lane & (HS - 1))];
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb) av[kb] = Xw[kh * XS + kb * 32 + m];
 #pragma unroll
@@ -436,6 +456,7 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
                         for (int kb = 0; kb < KB; ++kb) an[kb] = Xw[r * XS + kb * 32 + m];
 #pragma unroll
                         for (int nb = 0; nb < NB; ++nb) bn[nb] = Yw[r * YS + nb * 32 + m];
+                        if (HS) c1n = Xw[r * XS + KD + (lane & (HS - 1))];
                     }
                     __builtin_amdgcn_sched_barrier(0);
                     if (RS) {
@@ -445,10 +466,16 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
 #pragma unroll
                         for (int kb = 0; kb < KB; ++kb) pa[kb] += w * av[kb];
                     }
+                    if (HS) {
+#pragma unroll
+                        for (int kb = 0; kb < KB; ++kb) pah[HS ? kb : 0] = __builtin_amdgcn_mfma_f32_4x4x1f32(c1, av[kb], pah[HS ? kb : 0], 0, 0, 0);
+                        c1 = c1n;
+                    }
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                         for (int kb = 0; kb < KB; ++kb) accw[nb * KB + kb] = mfma32(av[kb], bv[nb], accw[nb * KB + kb]);
+
                     if (s2 + 1 < 16) {
 #pragma unroll
                         for (int kb = 0; kb < KB; ++kb) av[kb] = an[kb];
@@ -484,7 +511,7 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
         // all threads add the eight copies in wavefront order.
         __syncthreads();
         {
-            float* mine = smem + KD * WS + wave * WREG;      // holds KD*ND + KD floats (checked on the host)
+            float* mine = smem + KD * WS + wave * WREG;      // holds a slot's floats (checked on the host)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -492,13 +519,17 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
                         mine[(kb * 32 + acc_row(v, kh)) * ND + nb * 32 + m] = accw[nb * KB + kb][v];
-            float acca = 0.f;                               // Avec[k = lane] (lanes < KD): both row parities added
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                const float both = pa[kb] + __shfl_xor(pa[kb], 32);
-                if (kh == kb) acca = both;
+            for (int h = 0; h < NA; ++h) {
+                float acca = 0.f;                           // Avec[h][k = lane] (lanes < KD): both row parities added
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    const float mine_p = HS ? pah[HS ? kb : 0][h & 3] : pa[kb];
+                    const float both = mine_p + __shfl_xor(mine_p, 32);
+                    if (kh == kb) acca = both;
+                }
+                if (lane < KD) mine[KD * ND + h * KD + lane] = acca;
             }
-            if (lane < KD) mine[KD * ND + lane] = acca;
         }
         __syncthreads();
         {
@@ -514,7 +545,7 @@ __global__ __launch_bounds__(512) void typed_linear_bwd_wave_kernel(TileArgs t, 
     }
 }
 
-// dW[s] (and Avec[s]) = sum of the partial slots of segment s, in slot order.
+// dW[s] (and Avec[s]) = sum of the partial slots of segment s, in slot order; kd = floats of a slot's vector part.
 __global__ void slot_reduce_kernel(const float* __restrict__ part, const int32_t* __restrict__ seg_slot_ptr,
                                    int kn, int kd, float* __restrict__ dW, float* __restrict__ Avec) {
     const int seg = blockIdx.x;                 // segments on the x dimension: their count has no 65535 limit there
@@ -695,15 +726,15 @@ rgnn_status_t typed_linear_fwd(int d_in, int d_out, const TypedLinearArgs& a, hi
     RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear: d_in = %d, d_out = %d not supported (need equal, 32/64/128)", d_in, d_out);
 }
 
-size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t) {
-    return (size_t)std::max(t.num_slots, 1) * ((size_t)d_in * d_out + d_in);
+size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t, int vectors) {
+    return (size_t)std::max(t.num_slots, 1) * ((size_t)d_in * d_out + (size_t)std::max(vectors, 1) * d_in);
 }
 
-static rgnn_status_t launch_slot_reduce(int kd, int nd, const TypedLinearBwdArgs& a, hipStream_t st) {
-    const int kn = kd * nd;
+static rgnn_status_t launch_slot_reduce(int kd, int nd, const TypedLinearBwdArgs& a, hipStream_t st, int vectors = 1) {
+    const int kn = kd * nd, kv = kd * vectors;
     KernelTimer kt(st, "typed_linear_bwd.reduce");
-    hipLaunchKernelGGL(slot_reduce_kernel, dim3(a.tiles->num_segs, (kn + kd + 255) / 256), dim3(256), 0, st, a.part,
-                       a.tiles->seg_slot_ptr, kn, kd, a.dW, a.Avec);
+    hipLaunchKernelGGL(slot_reduce_kernel, dim3(a.tiles->num_segs, (kn + kv + 255) / 256), dim3(256), 0, st, a.part,
+                       a.tiles->seg_slot_ptr, kn, kv, a.dW, a.Avec);
     RGNN_HIP(hipGetLastError());
     return RGNN_OK;
 }
@@ -711,7 +742,7 @@ static rgnn_status_t launch_slot_reduce(int kd, int nd, const TypedLinearBwdArgs
 template <int KD, int ND, bool GATHER, bool DYG, bool SCATTER, bool RS, bool SEL = false, int HS = 0>
 static rgnn_status_t launch_bwd_wave(const TypedLinearBwdArgs& a, hipStream_t st) {
     constexpr int WREG = 32 * (KD + 4) + 32 * ((ND > KD ? ND : KD) + 4) + 32;
-    static_assert(WREG >= KD * ND + KD, "per-wavefront LDS region must hold a weight-gradient copy");
+    static_assert(WREG >= KD * ND + (HS ? HS : 1) * KD, "per-wavefront LDS region must hold a weight-gradient copy");
     const size_t lds = sizeof(float) * (KD * (ND + 1) + 8 * WREG);
     auto kern = typed_linear_bwd_wave_kernel<KD, ND, GATHER, DYG, SCATTER, RS, SEL, HS>;
     RGNN_TRY(allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
@@ -782,7 +813,7 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
         }
         if (!done) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: this combination of gather / scatter / rowscale is not built");
     }
-    return launch_slot_reduce(KD, ND, a, st);
+    return launch_slot_reduce(KD, ND, a, st, KD <= 64 && a.ysel && a.hcoef ? a.sel_heads : 1);
 }
 
 rgnn_status_t typed_linear_slot_reduce(int d_in, int d_out, const TileList& tiles, const float* part, float* dW,
