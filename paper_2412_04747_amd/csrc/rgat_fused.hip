@@ -403,14 +403,17 @@ __device__ __forceinline__ void bwd_item(const FusedArgs& a, const float* ws_lds
                     hc[H + head] = al;
                 }
             }
-            const int t = c % LPH;
-            if (t < 4 && k + t < cend) {
-                float* o = a.adz + (size_t)(jc + k + t) * 2 * H + head;
-                if (H == 1) {
-                    *reinterpret_cast<float2*>(o) = mine;
-                } else {
-                    o[0] = mine.x;
-                    o[H] = mine.y;
+            if (H == 1) {
+                if (c < 4 && k + c < cend) *reinterpret_cast<float2*>(a.adz + (size_t)(jc + k + c) * 2) = mine;
+            } else {
+                // lane (head h, t) holds edge k + t of head h; the values change lanes so that lane t * H + h stores them:
+                // the H lanes of an edge then write neighbouring floats
+                const int t = c / H, h = c % H;
+                const float al = __shfl(mine.x, h * LPH + t, LPR), dz = __shfl(mine.y, h * LPH + t, LPR);
+                if (c < 4 * H && k + t < cend) {
+                    float* o = a.adz + (size_t)(jc + k + t) * 2 * H + h;
+                    o[0] = al;
+                    o[H] = dz;
                 }
             }
         }
