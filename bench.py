@@ -169,7 +169,9 @@ def algorithmic_work(name, E, N, P, Q, R, T, d, H, P1=0, bf16=False, layer="rgat
         "node_linear_out_bwd": node_bwd,
         "pair_linear_att": pair_fwd, "pair_linear_msg": pair_fwd,
         "pair_linear_att_bwd": pair_bwd, "pair_linear_msg_bwd": pair_bwd,
-        "hgt_edge_logit": ("hbm", E * (row + 4 + 4 * H) + N * (row + 8), 2.0 * E * d),
+        # with the softmax in the same walk: + (max, sum) kept in registers; the weights overwrite the logits
+        # (one more 4-byte store per edge and head for the destinations of more than four edges, counted for all)
+        "hgt_edge_logit": ("hbm", E * (row + 4 + 8 * H) + N * (row + 8), 2.0 * E * d + 10.0 * E * H),
         "hgt_edge_dot_bwd": ("hbm", E * (row + 4 + 8 * H) + N * (2 * row + 8), 2.0 * E * d),
         "hgt_softmax": ("hbm", E * H * 8 + N * 8, 10.0 * E * H),
         "aggregate_bwd_msg": agg_pair, "aggregate_bwd_key": agg_pair, "aggregate_bwd_query": agg_dst,

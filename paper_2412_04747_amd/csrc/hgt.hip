@@ -138,11 +138,16 @@ __global__ void hgt_fold_bwd_node_kernel(int T, int R, int d, int H, const int32
     dWnode[i] = s;
 }
 
-// logit[e][h] = Ka[pair_e][h] . Q[v][h]   (Ka already carries mu / sqrt(dh)); TI = storage type of the rows
-template <int D, typename TI>
+// logit[e][h] = Ka[pair_e][h] . Q[v][h]   (Ka already carries mu / sqrt(dh)); TI = storage type of the rows.
+// SM (heads of at least four lanes): the per-head softmax over the destination's edges rides along.  The lanes of a
+// head keep a running maximum and the sum of exp(logit - maximum) over the batches; a whole destination then
+// turns the logits it has just written into weights (each lane re-reads the entries it stored itself), a piece of a
+// cut destination stores its (maximum, sum) per head for the finish kernel, which normalises the pieces' entries.
+template <int D, typename TI, bool SM>
 __global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, const int32_t* __restrict__ in_pair,
                                                              const TI* __restrict__ Ka, const TI* __restrict__ Q,
-                                                             float* __restrict__ logit) {
+                                                             float* logit, float* __restrict__ part_m,
+                                                             float* __restrict__ part_s) {
     constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
     const int i = blockIdx.x * IPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
     if (i >= it.n) return;
@@ -155,6 +160,9 @@ __global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, co
     int pr[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) pr[u] = in_pair[min(b + u, e - 1)];
+    float mx = -INFINITY, sum = 0.f;
+    const int sl = SM ? it.slot[i] : -1;
+    const bool one = SM && e - b <= 4 && sl < 0;
     for (int j = b; j < e; j += 4) {
         float k[4][V];
 #pragma unroll
@@ -165,14 +173,38 @@ __global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, co
         }
         // lane t < 4 of a head's lanes stores edge j + t (every lane of the head holds all four sums), so the
         // 4 x H results of a batch leave in one store instruction; heads of fewer than 4 lanes store one by one
-        float mine = 0.f;
+        float mine = 0.f, sv[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const float s = group_sum_dyn(dot_cols(q, k[u]), lph);
+            sv[u] = j + u < e ? s : -INFINITY;
             if (lph >= 4) { if (cv % lph == u) mine = s; }
             else if (cv % lph == 0 && j + u < e) logit[(size_t)(j + u) * H + head] = s;
         }
+        if (SM) {
+            const float mn = fmaxf(fmaxf(mx, fmaxf(sv[0], sv[1])), fmaxf(sv[2], sv[3]));     // sv[0] is finite: j < e
+            sum = sum * __expf(mx - mn) + ((__expf(sv[0] - mn) + __expf(sv[1] - mn)) + (__expf(sv[2] - mn) + __expf(sv[3] - mn)));
+            mx = mn;
+            if (one) mine = __expf(mine - mx) / sum;      // a whole destination of up to four edges: the weights at once
+        }
         if (lph >= 4 && cv % lph < 4 && j + cv % lph < e) logit[(size_t)(j + cv % lph) * H + head] = mine;
+    }
+    if (SM) {
+        if (one) return;
+        const int t = cv % lph;
+        if (sl >= 0) {
+            if (t == 0) {
+                part_m[(size_t)sl * H + head] = mx;
+                part_s[(size_t)sl * H + head] = sum;
+            }
+            return;
+        }
+        if (t >= 4) return;
+        const float inv = 1.f / sum;
+        for (int j = b + t; j < e; j += 4) {
+            float* x = logit + (size_t)j * H + head;
+            *x = __expf(*x - mx) * inv;
+        }
     }
 }
 
@@ -213,6 +245,55 @@ __global__ __launch_bounds__(256) void hgt_softmax_kernel(int N, int H, const in
     for (int k = 0; k < kSerialMax; ++k)
         if (k < len) att[(size_t)(b + k) * H + h] = soft_out(l[k], m, inv, sgn);
 }
+// The same for HV = 2 or 4 heads with eight lanes per node: lane g takes edges g, g + 8, ... of the node and reads or
+// writes the HV heads of an edge as one vector (they are contiguous), so the lanes of a node cover a contiguous
+// stretch of att; maximum and sum are reduced over the eight lanes.  The logits stay in registers between the passes.
+template <int HV>
+__global__ __launch_bounds__(256) void hgt_softmax_group_kernel(int N, const int32_t* __restrict__ in_ptr, float* __restrict__ att, int sgn) {
+    struct __align__(4 * HV) Vec { float v[HV]; };
+    constexpr int G = 8, PER = kSerialMax / G;
+    const int v = blockIdx.x * (256 / G) + threadIdx.x / G, gl = threadIdx.x % G;
+    if (v >= N) return;
+    const int b = in_ptr[v], len = in_ptr[v + 1] - b;
+    if (len == 0 || len > kSerialMax) return;
+    Vec* row = reinterpret_cast<Vec*>(att) + b;
+    Vec l[PER];
+    float m[HV], s[HV];
+#pragma unroll
+    for (int h = 0; h < HV; ++h) { m[h] = -INFINITY; s[h] = 0.f; }
+#pragma unroll
+    for (int it = 0; it < PER; ++it) {
+#pragma unroll
+        for (int h = 0; h < HV; ++h) l[it].v[h] = -INFINITY;
+        if (it * G < len) {
+            if (it * G + gl < len) l[it] = row[it * G + gl];
+#pragma unroll
+            for (int h = 0; h < HV; ++h) m[h] = fmaxf(m[h], l[it].v[h]);
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < HV; ++h) {
+        m[h] = fmaxf(m[h], dpp_move<kDppQuadSwap1>(m[h]));
+        m[h] = fmaxf(m[h], dpp_move<kDppQuadSwap2>(m[h]));
+        m[h] = fmaxf(m[h], dpp_move<kDppHalfMirror>(m[h]));
+    }
+#pragma unroll
+    for (int it = 0; it < PER; ++it)
+        if (it * G < len) {
+#pragma unroll
+            for (int h = 0; h < HV; ++h) s[h] += expf(l[it].v[h] - m[h]);      // exp(-inf) = 0 past the end
+        }
+#pragma unroll
+    for (int h = 0; h < HV; ++h) s[h] = 1.f / group_sum<G>(s[h]);
+#pragma unroll
+    for (int it = 0; it < PER; ++it)
+        if (it * G + gl < len) {
+            Vec o;
+#pragma unroll
+            for (int h = 0; h < HV; ++h) o.v[h] = soft_out(l[it].v[h], m[h], s[h], sgn);
+            row[it * G + gl] = o;
+        }
+}
 __global__ __launch_bounds__(256) void hgt_softmax_long_kernel(Items it, int n_long, const int32_t* __restrict__ long_item,
                                                                int H, float* __restrict__ att, float* __restrict__ part_m,
                                                                float* __restrict__ part_s, int sgn) {
@@ -245,6 +326,61 @@ __global__ __launch_bounds__(256) void hgt_softmax_long_kernel(Items it, int n_l
             part_m[(size_t)sl * H + h] = m;
             part_s[(size_t)sl * H + h] = s;
         }
+    }
+}
+// The long items with HV = 2 or 4 heads: a lane reads and writes the HV heads of an edge as one vector, so the
+// wavefront moves through the item's stretch of att once instead of once per head.
+template <int HV>
+__global__ __launch_bounds__(256) void hgt_softmax_long_vec_kernel(Items it, int n_long, const int32_t* __restrict__ long_item,
+                                                                   float* __restrict__ att, float* __restrict__ part_m,
+                                                                   float* __restrict__ part_s, int sgn) {
+    struct __align__(4 * HV) Vec { float v[HV]; };
+    constexpr int PER = kItemMax / 64;
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (w >= n_long) return;
+    const int i = long_item[w];
+    const int bb = it.beg[i], ee = it.end[i], sl = it.slot[i];
+    Vec* row = reinterpret_cast<Vec*>(att);
+    Vec l[PER];
+    float m[HV], s[HV];
+#pragma unroll
+    for (int h = 0; h < HV; ++h) { m[h] = -INFINITY; s[h] = 0.f; }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int j = bb + lane + 64 * u;
+#pragma unroll
+        for (int h = 0; h < HV; ++h) l[u].v[h] = -INFINITY;
+        if (j < ee) l[u] = row[j];
+#pragma unroll
+        for (int h = 0; h < HV; ++h) m[h] = fmaxf(m[h], l[u].v[h]);
+    }
+#pragma unroll
+    for (int h = 0; h < HV; ++h) {
+        m[h] = wave_max(m[h]);
+#pragma unroll
+        for (int u = 0; u < PER; ++u) s[h] += expf(l[u].v[h] - m[h]);
+        s[h] = group_sum<64>(s[h]);
+    }
+    if (sl < 0) {
+#pragma unroll
+        for (int h = 0; h < HV; ++h) s[h] = 1.f / s[h];
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int j = bb + lane + 64 * u;
+            if (j < ee) {
+                Vec o;
+#pragma unroll
+                for (int h = 0; h < HV; ++h) o.v[h] = soft_out(l[u].v[h], m[h], s[h], sgn);
+                row[j] = o;
+            }
+        }
+    } else if (lane < HV) {
+#pragma unroll
+        for (int h = 0; h < HV; ++h)
+            if (lane == h) {
+                part_m[(size_t)sl * HV + h] = m[h];
+                part_s[(size_t)sl * HV + h] = s[h];
+            }
     }
 }
 // Cut nodes: one wavefront per piece.  The head count is a power of two, so lane l always meets head
@@ -354,22 +490,38 @@ rgnn_status_t hgt_extract(int R, int d, int H, const float* dWbd, const float* W
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
+// part_m / part_s given: the softmax is taken in the same walk (logit then holds the attention weights) where a head
+// spans at least four lanes; otherwise, and without them, logit holds the logits and hgt_softmax follows.
+static bool hgt_softmax_rides(int D, int H, int rows_bf16) { return (D / (rows_bf16 ? 8 : 4)) / H >= 4; }
 rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const void* Ka, const void* Q, float* logit,
-                             hipStream_t st, int rows_bf16) {
+                             hipStream_t st, int rows_bf16, float* part_m, float* part_s) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
-    KernelTimer kt(st, "hgt_edge_logit");
-    if (rows_bf16) {
-        if (D != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "bf16 rows need width 128, got %d", D);
-        hipLaunchKernelGGL((hgt_edge_logit_kernel<128, bf16_t>), dim3(blocks_for(L.num_items, 256 / (128 / 8))), dim3(256), 0, st,
-                           dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], static_cast<const bf16_t*>(Ka),
-                           static_cast<const bf16_t*>(Q), logit);
-    } else {
-        RGNN_DISPATCH_D(D, hipLaunchKernelGGL((hgt_edge_logit_kernel<DD, float>), dim3(blocks_for(L.num_items, 256 / (DD / 4))),
-                                              dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR],
-                                              static_cast<const float*>(Ka), static_cast<const float*>(Q), logit));
+    const bool sm = part_m && part_s && hgt_softmax_rides(D, H, rows_bf16);
+    {
+        KernelTimer kt(st, "hgt_edge_logit");
+        if (rows_bf16) {
+            if (D != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "bf16 rows need width 128, got %d", D);
+            const dim3 grid(blocks_for(L.num_items, 256 / (128 / 8)));
+            if (sm)
+                hipLaunchKernelGGL((hgt_edge_logit_kernel<128, bf16_t, true>), grid, dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR],
+                                   static_cast<const bf16_t*>(Ka), static_cast<const bf16_t*>(Q), logit, part_m, part_s);
+            else
+                hipLaunchKernelGGL((hgt_edge_logit_kernel<128, bf16_t, false>), grid, dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR],
+                                   static_cast<const bf16_t*>(Ka), static_cast<const bf16_t*>(Q), logit, part_m, part_s);
+        } else if (sm) {
+            RGNN_DISPATCH_D(D, hipLaunchKernelGGL((hgt_edge_logit_kernel<DD, float, true>), dim3(blocks_for(L.num_items, 256 / (DD / 4))),
+                                                  dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR],
+                                                  static_cast<const float*>(Ka), static_cast<const float*>(Q), logit, part_m, part_s));
+        } else {
+            RGNN_DISPATCH_D(D, hipLaunchKernelGGL((hgt_edge_logit_kernel<DD, float, false>), dim3(blocks_for(L.num_items, 256 / (DD / 4))),
+                                                  dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR],
+                                                  static_cast<const float*>(Ka), static_cast<const float*>(Q), logit, part_m, part_s));
+        }
+        RGNN_CHECK_LAUNCH();
     }
-    RGNN_CHECK_LAUNCH();
+    if (sm) return hgt_softmax_finish(g, H, logit, part_m, part_s, st);
+    if (part_m && part_s) return hgt_softmax(g, H, logit, part_m, part_s, st);
     return RGNN_OK;
 }
 rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st,
@@ -378,22 +530,37 @@ rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m,
     if (g->E == 0) return RGNN_OK;
     {
         KernelTimer kt(st, "hgt_softmax");
-        hipLaunchKernelGGL(hgt_softmax_kernel, dim3(blocks_for((size_t)g->N * H, 256)), dim3(256), 0, st, (int)g->N, H,
-                           g->idx[RGNN_IDX_IN_PTR], att, signed_out);
+        if (H == 4)
+            hipLaunchKernelGGL(hgt_softmax_group_kernel<4>, dim3(blocks_for((size_t)g->N, 32)), dim3(256), 0, st, (int)g->N, g->idx[RGNN_IDX_IN_PTR], att, signed_out);
+        else if (H == 2)
+            hipLaunchKernelGGL(hgt_softmax_group_kernel<2>, dim3(blocks_for((size_t)g->N, 32)), dim3(256), 0, st, (int)g->N, g->idx[RGNN_IDX_IN_PTR], att, signed_out);
+        else
+            hipLaunchKernelGGL(hgt_softmax_kernel, dim3(blocks_for((size_t)g->N * H, 256)), dim3(256), 0, st, (int)g->N, H,
+                               g->idx[RGNN_IDX_IN_PTR], att, signed_out);
         RGNN_CHECK_LAUNCH();
         if (L.num_long > 0) {
-            hipLaunchKernelGGL(hgt_softmax_long_kernel, dim3(blocks_for((size_t)L.num_long * 64, 256)), dim3(256), 0, st,
-                               dev_items(L), L.num_long, L.long_item, H, att, part_m, part_s, signed_out);
+            const dim3 grid(blocks_for((size_t)L.num_long * 64, 256));
+            if (H == 4)
+                hipLaunchKernelGGL(hgt_softmax_long_vec_kernel<4>, grid, dim3(256), 0, st, dev_items(L), L.num_long, L.long_item, att, part_m, part_s, signed_out);
+            else if (H == 2)
+                hipLaunchKernelGGL(hgt_softmax_long_vec_kernel<2>, grid, dim3(256), 0, st, dev_items(L), L.num_long, L.long_item, att, part_m, part_s, signed_out);
+            else
+                hipLaunchKernelGGL(hgt_softmax_long_kernel, grid, dim3(256), 0, st, dev_items(L), L.num_long, L.long_item, H, att, part_m, part_s,
+                                   signed_out);
             RGNN_CHECK_LAUNCH();
         }
     }
-    if (L.num_partials > 0) {
-        KernelTimer kt(st, "hgt_softmax.finish");
-        hipLaunchKernelGGL(hgt_softmax_finish_kernel, dim3(blocks_for((size_t)L.num_partials * 64, 256)), dim3(256), 0,
-                           st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), H, part_m, part_s,
-                           att, signed_out);
-        RGNN_CHECK_LAUNCH();
-    }
+    return hgt_softmax_finish(g, H, att, part_m, part_s, st, signed_out);
+}
+rgnn_status_t hgt_softmax_finish(const rgnn_graph* g, int H, float* att, const float* part_m, const float* part_s, hipStream_t st,
+                                 int signed_out) {
+    const ItemList& L = g->dst_items;
+    if (L.num_partials == 0) return RGNN_OK;
+    KernelTimer kt(st, "hgt_softmax.finish");
+    hipLaunchKernelGGL(hgt_softmax_finish_kernel, dim3(blocks_for((size_t)L.num_partials * 64, 256)), dim3(256), 0,
+                       st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), H, part_m, part_s,
+                       att, signed_out);
+    RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* att, const void* M, const void* dZ,

@@ -728,8 +728,7 @@ extern "C" rgnn_status_t rgnn_hgt_fwd(const rgnn_graph_t* g, const rgnn_layer_de
         RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, R32(sv.V), R16(sv.V), psrc, 0, w.Wbd_msg, nullptr, sv.M, h, "pair_linear_msg", st));
     }
     // 4. per edge and head: logit, softmax over the destination's edges
-    RGNN_TRY(hgt_edge_logit(g, D, H, sv.Ka, sv.Q, sv.att, st, h));
-    RGNN_TRY(hgt_softmax(g, H, sv.att, w.part_m, w.part_s, st));
+    RGNN_TRY(hgt_edge_logit(g, D, H, sv.Ka, sv.Q, sv.att, st, h, w.part_m, w.part_s));     // logits, then softmax per head
     // 5. Z[v][h] = sum_e att[e][h] M[pair_e][h]
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, sv.att, H, 0, sv.M, sv.Z, w.partial, st, 0,
                         "aggregate_fwd", "aggregate_fwd.combine", H, h, h));

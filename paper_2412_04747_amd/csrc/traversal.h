@@ -69,8 +69,12 @@ rgnn_status_t rgat_param_finish(int R, int kd, int nd, const float* W, const flo
 rgnn_status_t hgt_expand(int R, int d, int H, const float* W, const float* mu, int scaled, float* Wbd, hipStream_t st);
 rgnn_status_t hgt_extract(int R, int d, int H, const float* dWbd, const float* W, const float* mu, int scaled, float* dW,
                           float* dmu, hipStream_t st);
+// with part_m / part_s: followed by the per-head softmax over each destination's edges (in the same walk where the
+// lane layout allows), so that logit holds the attention weights afterwards
 rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const void* Ka, const void* Q, float* logit,
-                             hipStream_t st, int rows_bf16 = 0);
+                             hipStream_t st, int rows_bf16 = 0, float* part_m = nullptr, float* part_s = nullptr);
+rgnn_status_t hgt_softmax_finish(const rgnn_graph* g, int H, float* att, const float* part_m, const float* part_s, hipStream_t st,
+                                 int signed_out = 0);
 // signed_out: att = -softmax where the logit is <= 0 (RGAT: the sign bit keeps the leaky-ReLU branch)
 rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st,
                           int signed_out = 0);
