@@ -102,7 +102,7 @@ typedef struct {
 #define RGNN_FLAG_EDGE_PARALLEL_AGGREGATION 1u
 /* every segment takes the general walk: no batched kernels for the segments with one or with 2..4 entries */
 #define RGNN_FLAG_NO_BATCHED_WALKS 2u
-/* single-head RGAT (width <= 64), RGCN with bf16 rows: the gradient row of every (source, relation) pair is
+/* RGAT with 1, 2 or 4 heads (width <= 64), RGCN with bf16 rows: the gradient row of every (source, relation) pair is
  * written per pair, also for the pairs with one edge, instead of being read through the row selector */
 #define RGNN_FLAG_NO_ROW_SELECT 4u
 /* HGT: keep the key / message node linears and the per-relation matrices apart even when every relation's
