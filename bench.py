@@ -403,13 +403,21 @@ def main():
             "config": {"workload": f"configs[{args.config - 1}]: {c['layer'].upper()}, {c['dtype']} inputs, N={N}, R={R}, E={E}, d={d}"},
             "cpu_baseline": cpu}), flush=True)
         return
-    # untimed clean pass, to show what the profiling events cost
+    # Pass 1 (not the timed region): the same K steps with HIP events around every kernel launch, for the per-kernel
+    # table and to find the dominant kernel.
+    B.rgnn_profile_select(None)
+    B.rgnn_profile_start()
+    torch.cuda.synchronize()
     tc = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    clean_ms = (time.perf_counter() - tc) * 1e3 / args.steps
-
+    all_events_ms = (time.perf_counter() - tc) * 1e3 / args.steps
+    rep = B.rgnn_profile_stop()
+    dom_name = max(rep.items(), key=lambda kv: kv[1][1])[0]
+    # Timed region: K steps, HIP events only around the dominant kernel (two per step), whose average duration over
+    # exactly these steps goes into the roofline entry.
+    B.rgnn_profile_select(dom_name)
     B.rgnn_profile_start()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -417,8 +425,10 @@ def main():
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    rep = B.rgnn_profile_stop()
+    dom_rep = B.rgnn_profile_stop()
+    B.rgnn_profile_select(None)
     ms_per_step = dt * 1e3 / args.steps
+    dom_n, dom_ms = dom_rep[dom_name]
 
     parity = None
     if want is not None:
@@ -448,8 +458,12 @@ def main():
         print("[bench] {name:28s} {ms_per_step:8.3f} ms/step  avg {avg_ms:8.3f} ms  {gb:>9s} GB/s {tf:>8s} TF/s".format(
             gb=f"{r['GBps']:.0f}" if "GBps" in r else "-", tf=f"{r['TFLOPs']:.1f}" if "TFLOPs" in r else "-", **r),
             file=sys.stderr, flush=True)
-    dom = kernels[0]
-    w = work(dom["name"])
+    # the dominant kernel's row, re-measured over the timed region
+    w = work(dom_name)
+    dom = {"name": dom_name, "avg_ms": dom_ms / dom_n}
+    if w:
+        dom["GBps"] = w[1] / dom["avg_ms"] / 1e6
+        dom["TFLOPs"] = w[2] / dom["avg_ms"] / 1e9
     mfma_peak = BF16_MFMA_PEAK_TFLOPS if half else FP32_MFMA_PEAK_TFLOPS
     if w and w[0] == "mfma":
         roof = {"kernel": dom["name"], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": mfma_peak,
@@ -468,6 +482,7 @@ def main():
     else:
         roof["traffic_source"] = "no counter summary is kept for this workload / schedule"
     roof["avg_ms"] = dom["avg_ms"]
+    roof["launches_timed"] = dom_n
     roof["algorithmic_bytes"] = w[1] if w else None
     kern_ms = {k["name"]: k["ms_per_step"] for k in kernels}
     steps_roof = step_rooflines(kern_ms, E, N, P, P1, d) if c["layer"] == "rgat" and H == 1 and not fwd_only else None
@@ -492,7 +507,8 @@ def main():
         "schedule": sched,
         "lib_sha16": sha,
         "cpu_baseline": cpu,
-        "ms_per_step_without_profiling_events": clean_ms,
+        # the separate pass with events around every kernel, which the `kernels` table and `roofline_steps` come from
+        "ms_per_step_with_events_on_every_kernel": all_events_ms,
         "parity_max_rel_err": parity,
         "kernels": kernels,
     }

@@ -321,6 +321,10 @@ rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* desc,
  */
 rgnn_status_t rgnn_profile_start(void);
 rgnn_status_t rgnn_profile_stop(char* report, size_t report_bytes);
+/* Restricts the timing to the kernels launched under one name (a host string of at most 63 characters, copied), so
+ * that a timed run carries two events per step instead of two per kernel; NULL or "" times every kernel again.
+ * Takes effect at the next rgnn_profile_start().  RGNN_EINVAL if the name is too long. */
+rgnn_status_t rgnn_profile_select(const char* name);
 
 #ifdef __cplusplus
 }

@@ -35,7 +35,7 @@ INDEX_NAMES = ["in_ptr", "in_src", "in_rel", "in_eid", "in_pair", "in_run", "in_
 
 EXPORTS = ["rgnn_last_error", "rgnn_graph_create", "rgnn_graph_destroy", "rgnn_graph_info", "rgnn_graph_export",
            "rgnn_workspace_bytes", "rgnn_rgcn_fwd", "rgnn_rgcn_bwd", "rgnn_rgat_fwd", "rgnn_rgat_bwd",
-           "rgnn_hgt_fwd", "rgnn_hgt_bwd", "rgnn_profile_start", "rgnn_profile_stop", "rgnn_rgat_fwd_static", "rgnn_schedule"]
+           "rgnn_hgt_fwd", "rgnn_hgt_bwd", "rgnn_profile_start", "rgnn_profile_stop", "rgnn_profile_select", "rgnn_rgat_fwd_static", "rgnn_schedule"]
 
 
 class RgnnError(RuntimeError):
@@ -178,6 +178,10 @@ def rgnn_hgt_bwd(g, desc, X, Wk, Wq, Wv, Wo, Watt, Wmsg, mu, out, saved, dOut, d
                               _ptr(Wmsg), _ptr(mu), _ptr(out), _ptr(saved), _ptr(dOut), _ptr(dX), _ptr(dWk),
                               _ptr(dWq), _ptr(dWv), _ptr(dWo), _ptr(dWatt), _ptr(dWmsg), _ptr(dmu),
                               _ptr(workspace), _ptr(stream)))
+
+
+def rgnn_profile_select(name=None):
+    _check(lib().rgnn_profile_select(name.encode() if name else None))
 
 
 def rgnn_profile_start():

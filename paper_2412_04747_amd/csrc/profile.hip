@@ -14,6 +14,8 @@ namespace rgnn {
 
 struct Record { const char* name; hipEvent_t a, b; };
 static std::atomic<bool> g_on{false};
+static char g_only[64] = "";       // name filter in force while profiling is on (empty: every kernel)
+static char g_only_next[64] = "";  // the filter rgnn_profile_start() will put in force
 static std::vector<Record> g_rec;
 static std::mutex g_mu;
 
@@ -29,6 +31,7 @@ const char* wgrad_label(const char* label) {
 KernelTimer::KernelTimer(hipStream_t st, const char* name) : st_(st), idx_(-1) {
     if (!g_on) return;
     std::lock_guard<std::mutex> lk(g_mu);
+    if (g_only[0] && strcmp(g_only, name) != 0) return;
     Record r{name, nullptr, nullptr};
     if (hipEventCreate(&r.a) != hipSuccess) return;
     if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
@@ -50,7 +53,16 @@ extern "C" rgnn_status_t rgnn_profile_start(void) {
     std::lock_guard<std::mutex> lk(g_mu);
     for (auto& r : g_rec) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     g_rec.clear();
+    memcpy(g_only, g_only_next, sizeof(g_only));
     g_on = true;
+    return RGNN_OK;
+}
+
+extern "C" rgnn_status_t rgnn_profile_select(const char* name) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (name && strlen(name) >= sizeof(g_only_next)) RGNN_FAIL(RGNN_EINVAL, "rgnn_profile_select: the name is longer than %zu characters", sizeof(g_only_next) - 1);
+    memset(g_only_next, 0, sizeof(g_only_next));
+    if (name) strcpy(g_only_next, name);
     return RGNN_OK;
 }
 

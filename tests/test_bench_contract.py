@@ -72,6 +72,9 @@ def test_bench_line_has_the_contract_fields():
     assert roof["bound"] in ("hbm", "mfma", "alu") and roof["unit"] in ("GB/s", "TFLOP/s")
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9 and "traffic" in roof
     assert "traffic_source" in roof and d["lib_sha16"] and d["schedule"]["fused_softmax"] == 1
+    # the dominant kernel is timed over exactly the steps of the timed region (one launch per step here)
+    assert roof["launches_timed"] == 3 and roof["avg_ms"] > 0 and d["ms_per_step_with_events_on_every_kernel"] > 0
+    assert roof["kernel"] in {k["name"] for k in d["kernels"]}
     # no kernel is priced above the machine: algorithmic GB/s within the HBM peak, TFLOP/s within the fp32 MFMA peak
     for k in d["kernels"]:
         assert k.get("GBps", 0.0) <= 8000.0 and k.get("TFLOPs", 0.0) <= 157.3, k
