@@ -337,12 +337,17 @@ def main():
     want = None
     if not args.no_oracle:
         from oracle import layers as O
-        want, t_f, t_b = run_oracle(c)
-        if fwd_only:
-            t_b = 0.0
-        cpu = {"value": E / (t_f + t_b), "unit": "edges/s", "cores": O.num_threads(), "kind": "oracle",
-               "sample": f"full workload, 1 repetition (fwd {t_f:.2f}s + bwd {t_b:.2f}s)"}
-        print(f"[bench] oracle fwd {t_f:.2f}s bwd {t_b:.2f}s on {O.num_threads()} threads", file=sys.stderr, flush=True)
+        # the whole workload, repeated until about ten seconds of CPU work are timed (at most eight times)
+        t_f = t_b = 0.0
+        reps = 0
+        while reps < 8 and (reps == 0 or t_f + t_b < 10.0):
+            want, tf1, tb1 = run_oracle(c)
+            t_f += tf1
+            t_b += 0.0 if fwd_only else tb1
+            reps += 1
+        cpu = {"value": E * reps / (t_f + t_b), "unit": "edges/s", "cores": O.num_threads(), "kind": "oracle",
+               "sample": f"full workload, {reps} repetition{'s' if reps > 1 else ''} (fwd {t_f:.2f}s + bwd {t_b:.2f}s in all)"}
+        print(f"[bench] oracle x{reps}: fwd {t_f:.2f}s bwd {t_b:.2f}s on {O.num_threads()} threads", file=sys.stderr, flush=True)
 
     t0 = time.time()
     g = Graph(N, R, c["src"], c["dst"], c["rel"], c.get("ntype") if T > 1 else None, T,
