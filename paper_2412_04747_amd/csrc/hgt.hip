@@ -1,6 +1,5 @@
 // Kernels of the HGT layer: block-diagonal expansion of the per-(relation, head) matrices, the
-// per-head edge logits, the per-head edge softmax and the per-head backward edge dot.  The last
-// two also serve multi-head RGAT (signed weights, leaky-ReLU slope).
+// per-head edge logits, the per-head edge softmax and the per-head backward edge dot.
 // (Caption of the thesis figure "HGT and RGAT layer": attention of HGT is an edgewise dot
 // product between the relation-transformed key of the source and the query of the
 // destination; the message depends only on (source node, edge type), so both are stored
@@ -208,16 +207,14 @@ __global__ __launch_bounds__(256) void hgt_edge_logit_kernel(Items it, int H, co
     }
 }
 
-// Per-head softmax of att[e][h] (holding logits on entry) over each destination's edges.
+// Per-head softmax of att[e][h] (holding logits on entry) over each destination's edges, as a pass of its own: for
+// the shapes whose heads span fewer than four lanes (bf16 rows with 16 columns per head); the others take the
+// softmax in the logit walk.
 // Short nodes: one lane per (node, head).  Long items and pieces of cut nodes: one wavefront
 // per item, heads in turn; pieces store (max, sum) per head for the finish kernel.
-// SIGNED: the weight of an edge whose logit is <= 0 is stored negated (its magnitude is the weight).
-__device__ __forceinline__ float soft_out(float l, float m, float inv, bool sgn) {
-    const float a = expf(l - m) * inv;
-    return sgn && !(l > 0.f) ? -a : a;
-}
+__device__ __forceinline__ float soft_out(float l, float m, float inv) { return expf(l - m) * inv; }
 __global__ __launch_bounds__(256) void hgt_softmax_kernel(int N, int H, const int32_t* __restrict__ in_ptr,
-                                                          float* __restrict__ att, int sgn) {
+                                                          float* __restrict__ att) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= (int64_t)N * H) return;
     const int lh = 31 - __clz(H);                 // the head count is a power of two
@@ -243,60 +240,11 @@ __global__ __launch_bounds__(256) void hgt_softmax_kernel(int N, int H, const in
     const float inv = 1.f / s;
 #pragma unroll
     for (int k = 0; k < kSerialMax; ++k)
-        if (k < len) att[(size_t)(b + k) * H + h] = soft_out(l[k], m, inv, sgn);
-}
-// The same for HV = 2 or 4 heads with eight lanes per node: lane g takes edges g, g + 8, ... of the node and reads or
-// writes the HV heads of an edge as one vector (they are contiguous), so the lanes of a node cover a contiguous
-// stretch of att; maximum and sum are reduced over the eight lanes.  The logits stay in registers between the passes.
-template <int HV>
-__global__ __launch_bounds__(256) void hgt_softmax_group_kernel(int N, const int32_t* __restrict__ in_ptr, float* __restrict__ att, int sgn) {
-    struct __align__(4 * HV) Vec { float v[HV]; };
-    constexpr int G = 8, PER = kSerialMax / G;
-    const int v = blockIdx.x * (256 / G) + threadIdx.x / G, gl = threadIdx.x % G;
-    if (v >= N) return;
-    const int b = in_ptr[v], len = in_ptr[v + 1] - b;
-    if (len == 0 || len > kSerialMax) return;
-    Vec* row = reinterpret_cast<Vec*>(att) + b;
-    Vec l[PER];
-    float m[HV], s[HV];
-#pragma unroll
-    for (int h = 0; h < HV; ++h) { m[h] = -INFINITY; s[h] = 0.f; }
-#pragma unroll
-    for (int it = 0; it < PER; ++it) {
-#pragma unroll
-        for (int h = 0; h < HV; ++h) l[it].v[h] = -INFINITY;
-        if (it * G < len) {
-            if (it * G + gl < len) l[it] = row[it * G + gl];
-#pragma unroll
-            for (int h = 0; h < HV; ++h) m[h] = fmaxf(m[h], l[it].v[h]);
-        }
-    }
-#pragma unroll
-    for (int h = 0; h < HV; ++h) {
-        m[h] = fmaxf(m[h], dpp_move<kDppQuadSwap1>(m[h]));
-        m[h] = fmaxf(m[h], dpp_move<kDppQuadSwap2>(m[h]));
-        m[h] = fmaxf(m[h], dpp_move<kDppHalfMirror>(m[h]));
-    }
-#pragma unroll
-    for (int it = 0; it < PER; ++it)
-        if (it * G < len) {
-#pragma unroll
-            for (int h = 0; h < HV; ++h) s[h] += expf(l[it].v[h] - m[h]);      // exp(-inf) = 0 past the end
-        }
-#pragma unroll
-    for (int h = 0; h < HV; ++h) s[h] = 1.f / group_sum<G>(s[h]);
-#pragma unroll
-    for (int it = 0; it < PER; ++it)
-        if (it * G + gl < len) {
-            Vec o;
-#pragma unroll
-            for (int h = 0; h < HV; ++h) o.v[h] = soft_out(l[it].v[h], m[h], s[h], sgn);
-            row[it * G + gl] = o;
-        }
+        if (k < len) att[(size_t)(b + k) * H + h] = soft_out(l[k], m, inv);
 }
 __global__ __launch_bounds__(256) void hgt_softmax_long_kernel(Items it, int n_long, const int32_t* __restrict__ long_item,
                                                                int H, float* __restrict__ att, float* __restrict__ part_m,
-                                                               float* __restrict__ part_s, int sgn) {
+                                                               float* __restrict__ part_s) {
     constexpr int PER = kItemMax / 64;     // an item has at most kItemMax entries
     const int w = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (w >= n_long) return;
@@ -320,67 +268,12 @@ __global__ __launch_bounds__(256) void hgt_softmax_long_kernel(Items it, int n_l
 #pragma unroll
             for (int u = 0; u < PER; ++u) {
                 const int j = bb + lane + 64 * u;
-                if (j < ee) att[(size_t)j * H + h] = soft_out(l[u], m, inv, sgn);
+                if (j < ee) att[(size_t)j * H + h] = soft_out(l[u], m, inv);
             }
         } else if (lane == 0) {
             part_m[(size_t)sl * H + h] = m;
             part_s[(size_t)sl * H + h] = s;
         }
-    }
-}
-// The long items with HV = 2 or 4 heads: a lane reads and writes the HV heads of an edge as one vector, so the
-// wavefront moves through the item's stretch of att once instead of once per head.
-template <int HV>
-__global__ __launch_bounds__(256) void hgt_softmax_long_vec_kernel(Items it, int n_long, const int32_t* __restrict__ long_item,
-                                                                   float* __restrict__ att, float* __restrict__ part_m,
-                                                                   float* __restrict__ part_s, int sgn) {
-    struct __align__(4 * HV) Vec { float v[HV]; };
-    constexpr int PER = kItemMax / 64;
-    const int w = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-    if (w >= n_long) return;
-    const int i = long_item[w];
-    const int bb = it.beg[i], ee = it.end[i], sl = it.slot[i];
-    Vec* row = reinterpret_cast<Vec*>(att);
-    Vec l[PER];
-    float m[HV], s[HV];
-#pragma unroll
-    for (int h = 0; h < HV; ++h) { m[h] = -INFINITY; s[h] = 0.f; }
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-        const int j = bb + lane + 64 * u;
-#pragma unroll
-        for (int h = 0; h < HV; ++h) l[u].v[h] = -INFINITY;
-        if (j < ee) l[u] = row[j];
-#pragma unroll
-        for (int h = 0; h < HV; ++h) m[h] = fmaxf(m[h], l[u].v[h]);
-    }
-#pragma unroll
-    for (int h = 0; h < HV; ++h) {
-        m[h] = wave_max(m[h]);
-#pragma unroll
-        for (int u = 0; u < PER; ++u) s[h] += expf(l[u].v[h] - m[h]);
-        s[h] = group_sum<64>(s[h]);
-    }
-    if (sl < 0) {
-#pragma unroll
-        for (int h = 0; h < HV; ++h) s[h] = 1.f / s[h];
-#pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            const int j = bb + lane + 64 * u;
-            if (j < ee) {
-                Vec o;
-#pragma unroll
-                for (int h = 0; h < HV; ++h) o.v[h] = soft_out(l[u].v[h], m[h], s[h], sgn);
-                row[j] = o;
-            }
-        }
-    } else if (lane < HV) {
-#pragma unroll
-        for (int h = 0; h < HV; ++h)
-            if (lane == h) {
-                part_m[(size_t)sl * HV + h] = m[h];
-                part_s[(size_t)sl * HV + h] = s[h];
-            }
     }
 }
 // Cut nodes: one wavefront per piece.  The head count is a power of two, so lane l always meets head
@@ -391,7 +284,7 @@ __global__ void hgt_softmax_finish_kernel(int num_partials, const int32_t* __res
                                           const int32_t* __restrict__ part_split,
                                           const int32_t* __restrict__ split_ptr, Items it, int H,
                                           const float* __restrict__ part_m, const float* __restrict__ part_s,
-                                          float* __restrict__ att, int sgn) {
+                                          float* __restrict__ att) {
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (t >= num_partials) return;
     const int sp = part_split[t];
@@ -406,7 +299,7 @@ __global__ void hgt_softmax_finish_kernel(int num_partials, const int32_t* __res
     for (int o = 32; o >= H; o >>= 1) s += __shfl_xor(s, o);
     const float inv = 1.f / s;
     const size_t a0 = (size_t)it.beg[item] * H, a1 = (size_t)it.end[item] * H;
-    for (size_t x = a0 + lane; x < a1; x += 64) att[x] = soft_out(att[x], m, inv, sgn);   // a0 and 64 are multiples of H: entry x is head h
+    for (size_t x = a0 + lane; x < a1; x += 64) att[x] = soft_out(att[x], m, inv);   // a0 and 64 are multiples of H: entry x is head h
 }
 
 // dl[e][h] = att[e][h] * (dZ[v][h] . M[pair_e][h] - dZ[v][h] . Z[v][h])
@@ -415,8 +308,7 @@ template <int D, typename TI>
 __global__ __launch_bounds__(256) void hgt_edge_dot_bwd_kernel(Items it, int H, const int32_t* __restrict__ in_pair,
                                                                const float* __restrict__ att,
                                                                const TI* __restrict__ M, const TI* __restrict__ dZ,
-                                                               const TI* __restrict__ Z, float* __restrict__ dl,
-                                                               float slope) {
+                                                               const TI* __restrict__ Z, float* __restrict__ dl) {
     constexpr int V = RowT<TI>::V, LPR = D / V, IPB = 256 / LPR;
     const int i = blockIdx.x * IPB + threadIdx.x / LPR, cv = threadIdx.x % LPR;
     if (i >= it.n) return;
@@ -457,9 +349,7 @@ __global__ __launch_bounds__(256) void hgt_edge_dot_bwd_kernel(Items it, int H, 
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const float g = group_sum_dyn(dot_cols(gz, mm[u]), lph);
-            // slope >= 0: att is signed (negative where the leaky-ReLU took its sloped branch) and the
-            // result is the gradient of the pre-activation logit
-            const float w = slope >= 0.f ? fabsf(a[u]) * (a[u] < 0.f ? slope : 1.f) : a[u];
+            const float w = a[u];
             if (lph >= 4) { if (cv % lph == u) mine = w * (g - gbar); }
             else if (cv % lph == 0 && j + u < e) dl[(size_t)(j + u) * H + head] = w * (g - gbar);
         }
@@ -524,47 +414,34 @@ rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const void* Ka, 
     if (part_m && part_s) return hgt_softmax(g, H, logit, part_m, part_s, st);
     return RGNN_OK;
 }
-rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st,
-                          int signed_out) {
+rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st) {
     const ItemList& L = g->dst_items;
     if (g->E == 0) return RGNN_OK;
     {
         KernelTimer kt(st, "hgt_softmax");
-        if (H == 4)
-            hipLaunchKernelGGL(hgt_softmax_group_kernel<4>, dim3(blocks_for((size_t)g->N, 32)), dim3(256), 0, st, (int)g->N, g->idx[RGNN_IDX_IN_PTR], att, signed_out);
-        else if (H == 2)
-            hipLaunchKernelGGL(hgt_softmax_group_kernel<2>, dim3(blocks_for((size_t)g->N, 32)), dim3(256), 0, st, (int)g->N, g->idx[RGNN_IDX_IN_PTR], att, signed_out);
-        else
-            hipLaunchKernelGGL(hgt_softmax_kernel, dim3(blocks_for((size_t)g->N * H, 256)), dim3(256), 0, st, (int)g->N, H,
-                               g->idx[RGNN_IDX_IN_PTR], att, signed_out);
+        hipLaunchKernelGGL(hgt_softmax_kernel, dim3(blocks_for((size_t)g->N * H, 256)), dim3(256), 0, st, (int)g->N, H,
+                           g->idx[RGNN_IDX_IN_PTR], att);
         RGNN_CHECK_LAUNCH();
         if (L.num_long > 0) {
-            const dim3 grid(blocks_for((size_t)L.num_long * 64, 256));
-            if (H == 4)
-                hipLaunchKernelGGL(hgt_softmax_long_vec_kernel<4>, grid, dim3(256), 0, st, dev_items(L), L.num_long, L.long_item, att, part_m, part_s, signed_out);
-            else if (H == 2)
-                hipLaunchKernelGGL(hgt_softmax_long_vec_kernel<2>, grid, dim3(256), 0, st, dev_items(L), L.num_long, L.long_item, att, part_m, part_s, signed_out);
-            else
-                hipLaunchKernelGGL(hgt_softmax_long_kernel, grid, dim3(256), 0, st, dev_items(L), L.num_long, L.long_item, H, att, part_m, part_s,
-                                   signed_out);
+            hipLaunchKernelGGL(hgt_softmax_long_kernel, dim3(blocks_for((size_t)L.num_long * 64, 256)), dim3(256), 0, st,
+                               dev_items(L), L.num_long, L.long_item, H, att, part_m, part_s);
             RGNN_CHECK_LAUNCH();
         }
     }
-    return hgt_softmax_finish(g, H, att, part_m, part_s, st, signed_out);
+    return hgt_softmax_finish(g, H, att, part_m, part_s, st);
 }
-rgnn_status_t hgt_softmax_finish(const rgnn_graph* g, int H, float* att, const float* part_m, const float* part_s, hipStream_t st,
-                                 int signed_out) {
+rgnn_status_t hgt_softmax_finish(const rgnn_graph* g, int H, float* att, const float* part_m, const float* part_s, hipStream_t st) {
     const ItemList& L = g->dst_items;
     if (L.num_partials == 0) return RGNN_OK;
     KernelTimer kt(st, "hgt_softmax.finish");
     hipLaunchKernelGGL(hgt_softmax_finish_kernel, dim3(blocks_for((size_t)L.num_partials * 64, 256)), dim3(256), 0,
                        st, L.num_partials, L.part_item, L.part_split, L.split_ptr, dev_items(L), H, part_m, part_s,
-                       att, signed_out);
+                       att);
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }
 rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* att, const void* M, const void* dZ,
-                               const void* Z, float* dl, hipStream_t st, int rows_bf16, float slope) {
+                               const void* Z, float* dl, hipStream_t st, int rows_bf16) {
     const ItemList& L = g->dst_items;
     if (L.num_items == 0 || g->E == 0) return RGNN_OK;
     KernelTimer kt(st, "hgt_edge_dot_bwd");
@@ -572,12 +449,12 @@ rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* a
         if (D != 128) RGNN_FAIL(RGNN_EUNSUPPORTED, "bf16 rows need width 128, got %d", D);
         hipLaunchKernelGGL((hgt_edge_dot_bwd_kernel<128, bf16_t>), dim3(blocks_for(L.num_items, 256 / (128 / 8))), dim3(256), 0,
                            st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], att, static_cast<const bf16_t*>(M),
-                           static_cast<const bf16_t*>(dZ), static_cast<const bf16_t*>(Z), dl, slope);
+                           static_cast<const bf16_t*>(dZ), static_cast<const bf16_t*>(Z), dl);
     } else {
         RGNN_DISPATCH_D(D, hipLaunchKernelGGL((hgt_edge_dot_bwd_kernel<DD, float>), dim3(blocks_for(L.num_items, 256 / (DD / 4))),
                                               dim3(256), 0, st, dev_items(L), H, g->idx[RGNN_IDX_IN_PAIR], att,
                                               static_cast<const float*>(M), static_cast<const float*>(dZ),
-                                              static_cast<const float*>(Z), dl, slope));
+                                              static_cast<const float*>(Z), dl));
     }
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;

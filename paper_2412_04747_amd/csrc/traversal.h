@@ -47,11 +47,6 @@ rgnn_status_t gather_sum(const ItemList& L, int D, const int32_t* via, const int
 rgnn_status_t gather_heads_rows(const ItemList& L, int D, int H, int out_rows, const int32_t* via, const int32_t* rowidx,
                                 int row_by_k, const float* coef, const float* src, float* out, float* partial,
                                 hipStream_t st, const char* label, const char* combine_label);
-// dsy (optional, [P] pairs of floats): a single-edge pair gets (dz_e, att_e) there instead of ds_src[p] and its
-// row att_e * dOut[v] in G
-rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
-                           const float* out, float slope, float* adz, float* G, float* ds_src, float* dsy,
-                           hipStream_t st);
 rgnn_status_t node_grad_sum(const rgnn_graph* g, int D, const void* dXp, const float* ds_dst, const float* wtp,
                             const float* extra, void* dX, hipStream_t st, int in_bf16 = 0, int out_bf16 = 0, int heads = 1,
                             const void* dXp2 = nullptr);
@@ -73,14 +68,11 @@ rgnn_status_t hgt_extract(int R, int d, int H, const float* dWbd, const float* W
 // lane layout allows), so that logit holds the attention weights afterwards
 rgnn_status_t hgt_edge_logit(const rgnn_graph* g, int D, int H, const void* Ka, const void* Q, float* logit,
                              hipStream_t st, int rows_bf16 = 0, float* part_m = nullptr, float* part_s = nullptr);
-rgnn_status_t hgt_softmax_finish(const rgnn_graph* g, int H, float* att, const float* part_m, const float* part_s, hipStream_t st,
-                                 int signed_out = 0);
-// signed_out: att = -softmax where the logit is <= 0 (RGAT: the sign bit keeps the leaky-ReLU branch)
-rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st,
-                          int signed_out = 0);
-// slope < 0: dl = att (g - gbar).  slope >= 0 (RGAT, signed att): dl = |att| (g - gbar) * (att < 0 ? slope : 1)
+rgnn_status_t hgt_softmax_finish(const rgnn_graph* g, int H, float* att, const float* part_m, const float* part_s, hipStream_t st);
+rgnn_status_t hgt_softmax(const rgnn_graph* g, int H, float* att, float* part_m, float* part_s, hipStream_t st);
+// dl = att (g - gbar)
 rgnn_status_t hgt_edge_dot_bwd(const rgnn_graph* g, int D, int H, const float* att, const void* M, const void* dZ,
-                               const void* Z, float* dl, hipStream_t st, int rows_bf16 = 0, float slope = -1.f);
+                               const void* Z, float* dl, hipStream_t st, int rows_bf16 = 0);
 // rgat_heads.hip: pieces of multi-head RGAT
 rgnn_status_t fold_weight_heads(int R, int kd, int nd, int H, const float* W, const float* w, float* wv, hipStream_t st);
 rgnn_status_t run_logit_heads(const rgnn_graph* g, int D, int H, const float* X, const float* wtp, float* s_dst,

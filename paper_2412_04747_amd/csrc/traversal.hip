@@ -680,95 +680,6 @@ __global__ void zero_f32_kernel(size_t n, float* __restrict__ x) {
     if (i < n) x[i] = 0.f;
 }
 
-// ------------------------------------------------------------------ backward per-edge dot (RGAT)
-
-// For every CSR edge e of destination v:  g_e = dOut[v] . Hs[pair_e];
-// with gbar_v = sum_e att_e g_e = dOut[v] . out[v] (because out[v] = sum_e att_e Hs[pair_e]):
-//   dl_e = att_e (g_e - gbar_v);  dz_e = dl_e * (z_e > 0 ? 1 : slope);   adz[e] = (att_e, dz_e).
-// No reduction over the segment is needed, so pieces of cut nodes are independent.
-// An edge that is the only edge of its (source, relation) pair also owns that pair's rows of the
-// backward aggregation, G[p] = att_e dOut[v] and ds_src[p] = dz_e, and writes them here (the
-// destination's dOut row is already in registers); the pair-major walk then only visits pairs
-// with several edges.  in_pair carries the "single edge" flag in its top bit.
-struct EdgeDotArgs {
-    Items it;
-    const int32_t* in_pair;
-    const float* att;
-    const float* Hs;
-    const float* dOut;
-    const float* out;
-    float slope;
-    float2* adz;
-    float* G;
-    float* ds_src;
-    float2* dsy;     // if given, a single-edge pair gets (dz_e, att_e) here in one store instead of ds_src[p] and its
-                     // row att_e * dOut[v] in G
-};
-
-template <int D>
-__global__ __launch_bounds__(256) void edge_dot_bwd_kernel(EdgeDotArgs a) {
-    constexpr int LPR = D / 4, IPB = 256 / LPR;
-    const int i = blockIdx.x * IPB + threadIdx.x / LPR, c4 = threadIdx.x % LPR;
-    if (i >= a.it.n) return;
-    const int b = a.it.beg[i], e = a.it.end[i];
-    if (e == b) return;
-    const size_t v = (size_t)a.it.row[i];
-    const float4 go = *reinterpret_cast<const float4*>(a.dOut + v * D + c4 * 4);
-    const float4 ov = *reinterpret_cast<const float4*>(a.out + v * D + c4 * 4);
-    // attention weights and pair ids run one batch of four ahead of the rows (positions past the end
-    // repeat the last edge; their results are not stored)
-    float atn[4];
-    int prn[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int jj = min(b + u, e - 1);
-        atn[u] = a.att[jj];
-        prn[u] = a.in_pair[jj];
-    }
-    const float gbar = group_sum<LPR>(dot4(go, ov));
-    for (int j = b; j < e; j += 4) {
-        float at[4];
-        float4 h[4];
-        int pr[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            at[u] = atn[u];
-            pr[u] = prn[u];
-            {   // the per-pair rows are a large tensor read about once per edge: non-temporal
-                const rgnn_v4f t = __builtin_nontemporal_load(reinterpret_cast<const rgnn_v4f*>(a.Hs + (size_t)(pr[u] & 0x7FFFFFFF) * D + c4 * 4));
-                h[u] = make_float4(t[0], t[1], t[2], t[3]);
-            }
-        }
-        if (j + 4 < e) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int jj = min(j + 4 + u, e - 1);
-                atn[u] = a.att[jj];
-                prn[u] = a.in_pair[jj];
-            }
-        }
-        float2 mine = make_float2(0.f, 0.f);   // (att, dz) of edge j + c4: lanes 0..3 of the group store one edge each
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float g = group_sum<LPR>(dot4(go, h[u]));
-            const float al = fabsf(at[u]);
-            const float dl = al * (g - gbar);
-            const float dz = dl * (signbit(at[u]) ? a.slope : 1.f);
-            const bool live = j + u < e;
-            if (c4 == u) mine = make_float2(al, dz);
-            if (live && pr[u] < 0) {   // single-edge pair
-                const size_t p = (size_t)(pr[u] & 0x7FFFFFFF);
-                if (!a.dsy) *reinterpret_cast<float4*>(a.G + p * D + c4 * 4) = make_float4(al * go.x, al * go.y, al * go.z, al * go.w);
-                if (c4 == 0) {
-                    if (a.dsy) a.dsy[p] = make_float2(dz, al);
-                    else a.ds_src[p] = dz;
-                }
-            }
-        }
-        if (c4 < 4 && j + c4 < e) a.adz[j + c4] = mine;
-    }
-}
-
 // ------------------------------------------------------------------ dX assembly
 
 // dX[u] = sum_{p in srcpair(u)} dXp[p]  +  sum_{q in runs(u)} sum_h ds_dst[q][h] * wtp[run_rel[q]][h]  +  extra[u]
@@ -1164,20 +1075,6 @@ rgnn_status_t aggregate_edge_parallel(const rgnn_graph* g, int D, const float* a
     RGNN_DISPATCH_D(D, hipLaunchKernelGGL(aggregate_edge_parallel_kernel<DD>, dim3(blocks_for(((size_t)g->E + kEdgeChunk - 1) / kEdgeChunk, 256 / (DD / 4))),
                                           dim3(256), 0, st, g->E, g->idx[RGNN_IDX_IN_PAIR], g->idx[RGNN_IDX_IN_RUN],
                                           g->idx[RGNN_IDX_RUN_DST], att, Hs, out));
-    RGNN_CHECK_LAUNCH();
-    return RGNN_OK;
-}
-
-rgnn_status_t edge_dot_bwd(const rgnn_graph* g, int D, const float* att, const float* Hs, const float* dOut,
-                           const float* out, float slope, float* adz, float* G, float* ds_src, float* dsy,
-                           hipStream_t st) {
-    const ItemList& L = g->dst_items;
-    if (L.num_items == 0 || g->E == 0) return RGNN_OK;
-    EdgeDotArgs a{dev_items(L), g->in_pair_tag, att, Hs, dOut, out, slope, reinterpret_cast<float2*>(adz), G, ds_src,
-                  reinterpret_cast<float2*>(dsy)};
-    KernelTimer kt(st, "edge_dot_bwd");
-    RGNN_DISPATCH_D(D, hipLaunchKernelGGL(edge_dot_bwd_kernel<DD>, dim3(blocks_for(L.num_items, 256 / (DD / 4))), dim3(256),
-                                     0, st, a));
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

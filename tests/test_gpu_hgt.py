@@ -50,7 +50,7 @@ def test_small_typed(d, H, mu):
     _run(600, 3, 5, src, dst, rel, ntype, p, d, H, f"small-d{d}-H{H}")
 
 
-@pytest.mark.parametrize("d,H", [(64, 2), (32, 2), (128, 4)])
+@pytest.mark.parametrize("d,H", [(64, 2), (32, 2), (128, 4), (128, 8)])     # (128, 8): softmax as a pass of its own
 def test_small_typed_bf16(d, H):
     rng, src, dst, rel, ntype = synth.tiny(190 + d, N=700, R=6, E=6000, T=3)
     dst[:900] = 5                                   # a hub cut into pieces
