@@ -28,7 +28,8 @@
  *     tensors that would have been saved become scratch).
  *   - Weights are stored [type][d_in][d_out] so that y = x W (row vector times
  *     matrix), as in Eq. (rgcn).
- *   - Gradients are overwritten, not accumulated.
+ *   - Gradients are overwritten, unless desc.flags carries RGNN_FLAG_ACCUMULATE (then every gradient output of
+ *     the backward call is added to what the buffer holds).
  *   - A graph may have no nodes or no edges; a [num_nodes, d] tensor of a graph
  *     without nodes may be NULL.  Parameter gradients are then written as zeros.
  *   - Index arrays are int32; graphs with 2^31 or more edges are rejected.
@@ -111,7 +112,11 @@ typedef struct {
 /* single-head RGAT forward: source logit per pair as an epilogue of the typed linear, edge softmax as a pass of its
  * own that stores one attention weight per edge, then the weighted sum (three passes instead of the fused walk) */
 #define RGNN_FLAG_SEPARATE_SOFTMAX 16u
-#define RGNN_FLAG_ALL 31u
+/* backward calls: every gradient output is added to the buffer's contents instead of overwriting them (dX in the
+ * kernel that writes it; the parameter gradients are formed in the workspace and added at the end, so
+ * rgnn_workspace_bytes() asks for their size on top).  Forward calls ignore the bit. */
+#define RGNN_FLAG_ACCUMULATE 32u
+#define RGNN_FLAG_ALL 63u
 typedef struct {
     int32_t dtype;
     int32_t d_in;

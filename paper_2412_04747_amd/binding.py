@@ -24,6 +24,7 @@ RGNN_FLAG_NO_BATCHED_WALKS = 2
 RGNN_FLAG_NO_ROW_SELECT = 4
 RGNN_FLAG_NO_WEIGHT_FOLDING = 8
 RGNN_FLAG_SEPARATE_SOFTMAX = 16
+RGNN_FLAG_ACCUMULATE = 32
 RGNN_MEM_HOST, RGNN_MEM_DEVICE = 0, 1
 RGNN_COO, RGNN_CSR_DST = 0, 1
 RGNN_STATIC_SCRATCH_BYTES = 64 << 20

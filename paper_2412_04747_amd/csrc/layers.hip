@@ -90,6 +90,29 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
     return RGNN_OK;
 }
 
+// ---- RGNN_FLAG_ACCUMULATE ---------------------------------------------------------------
+// The input gradient is accumulated by the kernel that writes it (it reads the row it is about to store).  The
+// parameter gradients are small and written by many different kernels, so under the flag they are formed in
+// workspace buffers of their own and added to the caller's at the end of the call.
+inline bool grads_accumulate(const rgnn_layer_desc_t* d) { return (d->flags & RGNN_FLAG_ACCUMULATE) != 0; }
+struct GradAcc {
+    static constexpr int kMax = 8;
+    int n = 0;
+    float* tmp[kMax];
+    float* dst[kMax];
+    size_t len[kMax];
+    // where the backward pass is to write this gradient: the workspace buffer if there is one, else the caller's
+    void* route(float* tmp_buf, void* dst_buf, size_t count) {
+        if (!tmp_buf || !dst_buf) return dst_buf;
+        tmp[n] = tmp_buf; dst[n] = static_cast<float*>(dst_buf); len[n] = count; ++n;
+        return tmp_buf;
+    }
+    rgnn_status_t flush(hipStream_t st) const {
+        for (int i = 0; i < n; ++i) RGNN_TRY(add_into(len[i], tmp[i], dst[i], st));
+        return RGNN_OK;
+    }
+};
+
 // ---- RGAT buffers -----------------------------------------------------------------------
 // Hs, the destination halves of the logits per (run, head) and (max, sum) of every (destination, head) softmax.
 struct RgatSaved { float* Hs; float* s_dst; float* ms; };
@@ -97,6 +120,7 @@ struct RgatFwdWs { float* wtp; float* s_src; float* att; float* part_m; float* p
 struct RgatBwdWs {
     float* wtp; float* wsp; float* adz; float* ds_dst; float* ds_src; float* G; float* dXp; float* A; float* U;
     float* tl_part; float* partial;
+    float* acc_dW; float* acc_dws; float* acc_dwt;      // RGNN_FLAG_ACCUMULATE: the parameter gradients of this call
 };
 // Single-head RGAT at widths up to 64: the gradient rows of single-edge pairs are not written per pair;
 // the typed-linear backward reads att_e * dOut[dst_e] through its row selector.
@@ -146,12 +170,16 @@ size_t carve_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
     const size_t parts = std::max<size_t>({(size_t)g->pair_items.num_partials, (size_t)g->relrun_items.num_partials,
                                            (size_t)g->relpair_items.num_partials});
     w->partial = c.take<float>(parts * std::max(d->d_in, d->d_out) * H);   // the run walk keeps one partial row per head
+    const bool acc = grads_accumulate(d);
+    w->acc_dW = acc ? c.take<float>((size_t)g->R * d->d_in * d->d_out) : nullptr;
+    w->acc_dws = acc ? c.take<float>((size_t)g->R * d->d_out) : nullptr;
+    w->acc_dwt = acc ? c.take<float>((size_t)g->R * d->d_out) : nullptr;
     return c.off;
 }
 
 // ---- RGCN buffers -----------------------------------------------------------------------
 struct RgcnFwdWs { void* Hs; float* partial; };
-struct RgcnBwdWs { void* dPre; float* dPre32; void* G; void* dXp; float* dX0; float* tl_part; float* partial; };
+struct RgcnBwdWs { void* dPre; float* dPre32; void* G; void* dXp; float* dX0; float* tl_part; float* partial; float* acc_dW; float* acc_dW0; };
 
 size_t carve_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, RgcnFwdWs* w) {
     Carver c(base);
@@ -170,6 +198,9 @@ size_t carve_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* b
     w->tl_part = c.take<float>(std::max(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles),
                                         typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->all_tiles)));
     w->partial = c.take<float>((size_t)g->pair_items.num_partials * d->d_out);
+    const bool acc = grads_accumulate(d);
+    w->acc_dW = acc ? c.take<float>((size_t)g->R * d->d_in * d->d_out) : nullptr;
+    w->acc_dW0 = acc ? c.take<float>((size_t)d->d_in * d->d_out) : nullptr;
     return c.off;
 }
 
@@ -186,6 +217,7 @@ struct HgtBwdWs {
     float* dWf_msg; void* dZ; float* dl; void* dM; void* dKa;
     void* dQ; void* dKp; void* dVp; void* dK; void* dV; float* dXk; float* dXq; float* dXv; float* tl_part;
     float* partial;
+    float* acc_node[4]; float* acc_rel[2]; float* acc_mu;     // RGNN_FLAG_ACCUMULATE: dWk, dWq, dWv, dWo; dWatt, dWmsg; dmu
 };
 
 size_t carve_hgt_saved(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* base, HgtSaved* s) {
@@ -224,6 +256,11 @@ size_t carve_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, void* ba
     w->tl_part = c.take<float>(std::max(typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->pair_tiles),
                                         typed_linear_bwd_scratch_floats(d->d_in, d->d_out, g->node_tiles)));
     w->partial = c.take<float>((size_t)std::max(g->pair_items.num_partials, g->dst_items.num_partials) * D);
+    const bool acc = grads_accumulate(d);
+    const size_t dh = D / d->heads;
+    for (int i = 0; i < 4; ++i) w->acc_node[i] = acc ? c.take<float>((size_t)g->T * D * D) : nullptr;
+    for (int i = 0; i < 2; ++i) w->acc_rel[i] = acc ? c.take<float>((size_t)g->R * d->heads * dh * dh) : nullptr;
+    w->acc_mu = acc ? c.take<float>((size_t)g->R * d->heads) : nullptr;
     return c.off;
 }
 
@@ -417,6 +454,10 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     const float* W032 = stg.in(W0, (size_t)K * D);
     const float* dO32 = (!h || W0) ? stg.in(dOut, (size_t)g->N * D) : nullptr;
     RGNN_TRY(stg.status);
+    const bool acc = grads_accumulate(desc);
+    GradAcc ga;
+    dW = ga.route(w.acc_dW, dW, (size_t)g->R * K * D);
+    dW0 = ga.route(w.acc_dW0, dW0, (size_t)K * D);
     // gradient before the activation, in the storage the traversal reads (dPre) and, where an fp32
     // kernel needs it, in fp32 (dPre32)
     const void* dPre = h ? dOut : dO32;
@@ -453,9 +494,12 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
         s.dXrow = w.dX0; s.dW = static_cast<float*>(dW0); s.part = w.tl_part; s.label = "self_loop_bwd";
         RGNN_TRY(typed_linear_bwd(K, D, s, st));
     }
-    // 4. dX[u] = sum over u's pairs of dXp (+ dX0[u])
-    RGNN_TRY(node_grad_sum(g, K, w.dXp, nullptr, nullptr, W0 ? w.dX0 : nullptr, dX, st, h, 0));
-    return RGNN_OK;
+    // 4. dX[u] = sum over u's pairs of dXp (+ dX0[u]) (+ what dX holds, when gradients accumulate)
+    const float* extra = W0 ? w.dX0 : nullptr;
+    if (acc && W0) RGNN_TRY(add_into((size_t)g->N * K, static_cast<const float*>(dX), w.dX0, st));
+    else if (acc) extra = static_cast<const float*>(dX);
+    RGNN_TRY(node_grad_sum(g, K, w.dXp, nullptr, nullptr, extra, dX, st, h, 0));
+    return ga.flush(st);
 }
 
 // =========================================================================== RGAT
@@ -585,6 +629,12 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     const float* Xf = static_cast<const float*>(X);
     const float* Wf = static_cast<const float*>(W);
     const float* dO = static_cast<const float*>(dOut);
+    const bool acc = grads_accumulate(desc);
+    GradAcc ga;
+    dW = ga.route(w.acc_dW, dW, (size_t)g->R * K * D);
+    dw_s = ga.route(w.acc_dws, dw_s, (size_t)g->R * D);
+    dw_t = ga.route(w.acc_dwt, dw_t, (size_t)g->R * D);
+    const float* dX_old = acc ? static_cast<const float*>(dX) : nullptr;      // added by the kernel that writes dX
     if (desc->heads > 1) {
         const int H = desc->heads;
         const float *ws = static_cast<const float*>(w_s), *wt = static_cast<const float*>(w_t);
@@ -627,7 +677,8 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
                                          static_cast<float*>(dw_s), static_cast<float*>(dw_t), st));
         // 7. dX[u] = sum over u's pairs of dXp + sum over u's runs and heads of ds_dst[q][h] (W[r] w_t[r])_h
         RGNN_TRY(fold_weight_heads(g->R, K, D, H, Wf, wt, w.wtp, st));
-        return node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, nullptr, dX, st, 0, 0, H);
+        RGNN_TRY(node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, dX_old, dX, st, 0, 0, H));
+        return ga.flush(st);
     }
     // 1. per CSR edge: (att_e, dz_e), att_e recomputed from the gathered row and the saved (m, s); for single-edge pairs also ds_src[p] and G[p] = att_e dOut[dst_e] (or, with
     //    the row selector, only att_e: step 4 then reads the row from dOut).  With the selector ds_src[p] and that
@@ -663,8 +714,8 @@ extern "C" rgnn_status_t rgnn_rgat_bwd(const rgnn_graph_t* g, const rgnn_layer_d
     RGNN_TRY(rgat_param_finish(g->R, K, D, Wf, static_cast<const float*>(w_s), static_cast<const float*>(w_t), w.A, w.U,
                                static_cast<float*>(dW), static_cast<float*>(dw_s), static_cast<float*>(dw_t), st));
     // 7. dX[u] = sum over u's pairs of dXp + sum over u's runs of ds_dst[q] (W[r] w_t[r])
-    RGNN_TRY(node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, nullptr, static_cast<float*>(dX), st));
-    return RGNN_OK;
+    RGNN_TRY(node_grad_sum(g, K, w.dXp, w.ds_dst, w.wtp, dX_old, static_cast<float*>(dX), st));
+    return ga.flush(st);
 }
 
 // =========================================================================== HGT
@@ -774,6 +825,12 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     const void* dOr = h ? dOut : static_cast<const void*>(dO32);
     const int32_t* perm = g->idx[RGNN_IDX_NTYPE_PERM];
     const int32_t* psrc = g->idx[RGNN_IDX_PAIR_SRC];
+    const bool acc = grads_accumulate(desc);
+    GradAcc ga;
+    dWk = ga.route(w.acc_node[0], dWk, tdd); dWq = ga.route(w.acc_node[1], dWq, tdd);
+    dWv = ga.route(w.acc_node[2], dWv, tdd); dWo = ga.route(w.acc_node[3], dWo, tdd);
+    dWatt = ga.route(w.acc_rel[0], dWatt, rh * dh * dh); dWmsg = ga.route(w.acc_rel[1], dWmsg, rh * dh * dh);
+    dmu = ga.route(w.acc_mu, dmu, rh);
     // 1. output linear: dZ = dOut Wo^T, dWo = Z^T dOut
     RGNN_TRY(tl_bwd(h, &g->node_tiles, &g->node_tiles_wide, D, sv.Z, perm, 1, Wo32, Wo16, dOr, w.dZ, h, static_cast<float*>(dWo), w.tl_part,
                     "node_linear_out_bwd", st));
@@ -806,7 +863,9 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
         // dX = dQ Wq^T + sums over each node's pairs of the two per-pair gradients
         RGNN_TRY(tl_bwd(h, &g->node_tiles, &g->node_tiles_wide, D, Xr, perm, 1, Wq32, Wq16, w.dQ, w.dXq, false, static_cast<float*>(dWq),
                         w.tl_part, "node_linear_q_bwd", st));
-        return node_grad_sum(g, D, w.dKp, nullptr, nullptr, w.dXq, dX, st, h, 0, 1, w.dVp);
+        if (acc) RGNN_TRY(add_into((size_t)g->N * D, static_cast<const float*>(dX), w.dXq, st));
+        RGNN_TRY(node_grad_sum(g, D, w.dKp, nullptr, nullptr, w.dXq, dX, st, h, 0, 1, w.dVp));
+        return ga.flush(st);
     }
     RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, sv.K, psrc, 0, w.Wbd_att, nullptr, w.dKa, w.dKp, h, w.dWbd_att, w.tl_part,
                     "pair_linear_att_bwd", st));
@@ -820,11 +879,14 @@ extern "C" rgnn_status_t rgnn_hgt_bwd(const rgnn_graph_t* g, const rgnn_layer_de
     // 7. node linears backward and dX
     //    (bf16 rows: the three input gradients are accumulated into dX by the kernels themselves)
     RGNN_TRY(tl_bwd(h, &g->node_tiles, &g->node_tiles_wide, D, Xr, perm, 1, Wk32, Wk16, w.dK, h ? dX : static_cast<void*>(w.dXk),
-                    false, static_cast<float*>(dWk), w.tl_part, "node_linear_k_bwd", st));
+                    false, static_cast<float*>(dWk), w.tl_part, "node_linear_k_bwd", st, h && acc));
     RGNN_TRY(tl_bwd(h, &g->node_tiles, &g->node_tiles_wide, D, Xr, perm, 1, Wq32, Wq16, w.dQ, h ? dX : static_cast<void*>(w.dXq),
                     false, static_cast<float*>(dWq), w.tl_part, "node_linear_q_bwd", st, h));
     RGNN_TRY(tl_bwd(h, &g->node_tiles, &g->node_tiles_wide, D, Xr, perm, 1, Wv32, Wv16, w.dV, h ? dX : static_cast<void*>(w.dXv),
                     false, static_cast<float*>(dWv), w.tl_part, "node_linear_v_bwd", st, h));
-    if (!h) RGNN_TRY(add3((size_t)g->N * D, w.dXk, w.dXq, w.dXv, static_cast<float*>(dX), st));
-    return RGNN_OK;
+    if (!h) {
+        if (acc) RGNN_TRY(add_into((size_t)g->N * D, static_cast<const float*>(dX), w.dXk, st));
+        RGNN_TRY(add3((size_t)g->N * D, w.dXk, w.dXq, w.dXv, static_cast<float*>(dX), st));
+    }
+    return ga.flush(st);
 }

@@ -85,6 +85,7 @@ rgnn_status_t aggregate_edge_parallel(const rgnn_graph* g, int D, const float* a
 rgnn_status_t add3(size_t n, const float* a, const float* b, const float* c, float* out, hipStream_t st);
 
 rgnn_status_t widen_bf16(size_t n, const uint16_t* src, float* dst, hipStream_t st);
+rgnn_status_t add_into(size_t n, const float* src, float* dst, hipStream_t st);     // dst += src
 rgnn_status_t relu_inplace(size_t n, float* x, hipStream_t st);
 rgnn_status_t relu_grad(size_t n, const float* ref, const void* gin, void* y, hipStream_t st, int bf16 = 0);
 

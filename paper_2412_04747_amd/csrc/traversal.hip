@@ -887,6 +887,12 @@ __global__ void relu_grad_bf16_kernel(size_t n, const float* __restrict__ ref, c
     if (i < n) y[i] = ref[i] > 0.f ? g[i] : (bf16_t)0;
 }
 
+// dst += src
+__global__ void add_into_kernel(size_t n, const float* __restrict__ src, float* __restrict__ dst) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] += src[i];
+}
+
 // bfloat16 -> fp32 (exact: the bf16 bits are the upper half of the fp32 word)
 __global__ void widen_bf16_kernel(size_t n, const uint16_t* __restrict__ src, float* __restrict__ dst) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1112,6 +1118,13 @@ rgnn_status_t widen_bf16(size_t n, const uint16_t* src, float* dst, hipStream_t 
     if (n == 0) return RGNN_OK;
     KernelTimer kt(st, "widen_bf16");
     hipLaunchKernelGGL(widen_bf16_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, src, dst);
+    RGNN_CHECK_LAUNCH();
+    return RGNN_OK;
+}
+rgnn_status_t add_into(size_t n, const float* src, float* dst, hipStream_t st) {
+    if (n == 0) return RGNN_OK;
+    KernelTimer kt(st, "add_into");
+    hipLaunchKernelGGL(add_into_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, n, src, dst);
     RGNN_CHECK_LAUNCH();
     return RGNN_OK;
 }

@@ -31,15 +31,17 @@ def _graph(seed, N, R, E, T=1):
     return rng, src, dst, rel, ntype
 
 
-@pytest.mark.parametrize("dtype,d,heads", [("f32", 64, 1), ("f32", 32, 2), ("bf16", 128, 4), ("f32", 128, 1)])
-def test_rgat_stays_inside_its_buffers(dtype, d, heads):
+# flags 32: gradients accumulate (the parameter gradients of the call then live in the workspace too)
+@pytest.mark.parametrize("dtype,d,heads,flags", [("f32", 64, 1, 0), ("f32", 32, 2, 0), ("bf16", 128, 4, 0), ("f32", 128, 1, 0),
+                                                 ("f32", 64, 1, 32), ("f32", 64, 4, 32)])
+def test_rgat_stays_inside_its_buffers(dtype, d, heads, flags):
     import torch
     from paper_2412_04747_amd import binding as B
     from paper_2412_04747_amd.harness import Graph, RgatLayer
     rng, src, dst, rel, _ = _graph(501, 3000, 40, 40000)
     print(f"bounds case rgat {dtype} d={d} heads={heads}", flush=True)
     g = Graph(3000, 40, src, dst, rel)
-    L = RgatLayer(g, d, dtype=dtype, heads=heads)
+    L = RgatLayer(g, d, dtype=dtype, heads=heads, flags=flags)
     p = synth.rgat_params(rng, 3000, 40, d, d)
     if dtype == "bf16":
         p = {k: synth.round_to_bf16(v) for k, v in p.items()}
@@ -57,15 +59,16 @@ def test_rgat_stays_inside_its_buffers(dtype, d, heads):
     g.close()
 
 
-@pytest.mark.parametrize("dtype,d,act,w0", [("f32", 64, "relu", True), ("bf16", 128, "relu", True), ("bf16", 128, "none", False)])
-def test_rgcn_stays_inside_its_buffers(dtype, d, act, w0):
+@pytest.mark.parametrize("dtype,d,act,w0,flags", [("f32", 64, "relu", True, 0), ("bf16", 128, "relu", True, 0), ("bf16", 128, "none", False, 0),
+                                                  ("bf16", 128, "relu", True, 32)])
+def test_rgcn_stays_inside_its_buffers(dtype, d, act, w0, flags):
     import torch
     from paper_2412_04747_amd import binding as B
     from paper_2412_04747_amd.harness import Graph, RgcnLayer
     rng, src, dst, rel, _ = _graph(502, 3000, 40, 40000)
     print(f"bounds case rgcn {dtype} d={d} act={act} W0={w0}", flush=True)
     g = Graph(3000, 40, src, dst, rel)
-    L = RgcnLayer(g, d, "in_degree_per_rel", act, w0, dtype=dtype)
+    L = RgcnLayer(g, d, "in_degree_per_rel", act, w0, dtype=dtype, flags=flags)
     p = synth.rgcn_params(rng, 3000, 40, d, d, self_loop=w0)
     if dtype == "bf16":
         p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}
@@ -83,8 +86,8 @@ def test_rgcn_stays_inside_its_buffers(dtype, d, act, w0):
 
 
 @pytest.mark.parametrize("tied", [False, True])
-@pytest.mark.parametrize("dtype,d,H", [("f32", 64, 2), ("bf16", 128, 4), ("bf16", 64, 4)])
-def test_hgt_stays_inside_its_buffers(dtype, d, H, tied):
+@pytest.mark.parametrize("dtype,d,H,flags", [("f32", 64, 2, 0), ("bf16", 128, 4, 0), ("bf16", 64, 4, 0), ("bf16", 128, 4, 32), ("f32", 64, 2, 32)])
+def test_hgt_stays_inside_its_buffers(dtype, d, H, flags, tied):
     """`tied`: every relation's sources have one node type (the source's type is set by its relation),
     which selects the path with folded weights and a smaller `saved`."""
     import torch
@@ -96,7 +99,7 @@ def test_hgt_stays_inside_its_buffers(dtype, d, H, tied):
         src = (src // 3 * 3 + rel % 3).astype(np.int32)          # source type = relation mod 3
     print(f"bounds case hgt {dtype} d={d} H={H} tied={tied}", flush=True)
     g = Graph(3000, 12, src, dst, rel, ntype, 3)
-    L = HgtLayer(g, d, H, with_mu=True, dtype=dtype)
+    L = HgtLayer(g, d, H, with_mu=True, dtype=dtype, flags=flags)
     p = synth.hgt_params(rng, 3000, 3, 12, d, H, with_mu=True)
     if dtype == "bf16":
         p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}
