@@ -84,7 +84,8 @@ typedef struct {
  *              queries, values and their gradients, in the workspace and in `saved`) in
  *              bfloat16, rounded to nearest even from the fp32 accumulators; results then
  *              agree with an fp64 evaluation to a few 1e-3 relative to the largest entry.
- *   d_in,d_out feature widths.  Supported: d_in == d_out in {32, 64, 128}.
+ *   d_in,d_out feature widths.  Supported: d_in == d_out in {32, 64, 128}; RGCN and RGAT with fp32 inputs also
+ *              take d_in, d_out in {32, 64} with d_in != d_out.
  *   heads      number of attention heads H of HGT and RGAT (d_out % H == 0; d_out/H in {16, 32, 64},
  *              any width for single-head RGAT).  With H > 1, num_nodes * H and num_edges * H
  *              must stay below 2^31 (EUNSUPPORTED otherwise).

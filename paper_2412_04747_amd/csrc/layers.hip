@@ -61,8 +61,12 @@ rgnn_status_t check_desc(const rgnn_graph_t* g, const rgnn_layer_desc_t* d, int 
     if ((d->flags & (RGNN_FLAG_EDGE_PARALLEL_AGGREGATION | RGNN_FLAG_SEPARATE_SOFTMAX)) && (layer != RGNN_LAYER_RGAT || d->heads != 1))
         RGNN_FAIL(RGNN_EUNSUPPORTED, "the edge-parallel aggregation and the separate softmax pass are schedules of single-head RGAT only");
     if (d->dtype != RGNN_F32 && d->dtype != RGNN_BF16) RGNN_FAIL(RGNN_EINVAL, "unknown dtype %d", d->dtype);
-    if (d->d_in != d->d_out || (d->d_in != 32 && d->d_in != 64 && d->d_in != 128))
-        RGNN_FAIL(RGNN_EUNSUPPORTED, "need d_in == d_out in {32, 64, 128}, got %d -> %d", d->d_in, d->d_out);
+    // widths: 32, 64 or 128 on both sides; RGCN and RGAT with fp32 inputs also take 32 -> 64 and 64 -> 32
+    const bool w_in = d->d_in == 32 || d->d_in == 64 || d->d_in == 128, w_out = d->d_out == 32 || d->d_out == 64 || d->d_out == 128;
+    const bool mixed_ok = layer != RGNN_LAYER_HGT && d->dtype == RGNN_F32 && d->d_in <= 64 && d->d_out <= 64;
+    if (!w_in || !w_out || (d->d_in != d->d_out && !mixed_ok))
+        RGNN_FAIL(RGNN_EUNSUPPORTED, "need d_in == d_out in {32, 64, 128} (RGCN / RGAT with fp32 inputs: also 32 -> 64 and 64 -> 32), got %d -> %d",
+                  d->d_in, d->d_out);
     if (layer == RGNN_LAYER_RGAT) {
         if (d->heads < 1 || d->d_out % d->heads != 0) RGNN_FAIL(RGNN_EINVAL, "heads must divide d_out");
         const int dh = d->d_out / d->heads;
@@ -295,10 +299,13 @@ void* saved_or_scratch(const rgnn_graph_t* g, int layer, const rgnn_layer_desc_t
 // Chunking: the bf16 kernel with the weight in bf16 does best on many short chunks (`tiles`); when
 // the weight has to be split, and in the fp32 kernels, loading a segment's weight costs more and one
 // resident round of long chunks (`wide`) wins.
+// d_in (fp32 kernels only): width of the input rows when it differs from the output width d.
 rgnn_status_t tl_fwd(bool bf16, const rgnn::TileList* tiles, const rgnn::TileList* wide, int d, const float* A32,
                      const void* A16, const int32_t* gather, int scatter, const float* W32, const void* W16, void* Y,
-                     bool y16, const char* label, hipStream_t st) {
+                     bool y16, const char* label, hipStream_t st, int d_in = 0) {
+    if (d_in == 0) d_in = d;
     if (bf16) {
+        if (d_in != d) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear on the bf16 matrix cores: equal widths only");
         TypedLinearBf16Args a{};
         a.tiles = W16 ? tiles : wide; a.A = A16 ? A16 : A32; a.a_bf16 = A16 != nullptr; a.gather = gather; a.scatter_out = scatter;
         a.W = W16 ? W16 : W32; a.w_bf16 = W16 != nullptr; a.Y = Y; a.y_bf16 = y16; a.label = label;
@@ -307,7 +314,7 @@ rgnn_status_t tl_fwd(bool bf16, const rgnn::TileList* tiles, const rgnn::TileLis
     TypedLinearArgs a{};
     a.tiles = wide; a.X = A32; a.gather = gather; a.W = W32; a.Y = static_cast<float*>(Y); a.scatter_out = scatter;
     a.label = label;
-    return typed_linear_fwd(d, d, a, st);
+    return typed_linear_fwd(d_in, d, a, st);
 }
 
 // Backward typed linear: dXrow = dY W^T (rows through `gather` on both sides when `both_gathered`),
@@ -323,7 +330,9 @@ rgnn_status_t tl_bwd(bool rows16, const rgnn::TileList* tiles, const rgnn::TileL
                      const int32_t* gather, int both_gathered, const float* W32, const void* W16, const void* dY,
                      void* dXrow, bool dx16, float* dW, float* part, const char* label, hipStream_t st,
                      bool dx_acc = false, const int32_t* ysel = nullptr, const void* y_alt = nullptr,
-                     const float* yscale = nullptr) {
+                     const float* yscale = nullptr, int d_in = 0) {
+    if (d_in == 0) d_in = d;
+    if (rows16 && d_in != d) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward on the bf16 matrix cores: equal widths only");
     if (ysel && (!rows16 || both_gathered)) RGNN_FAIL(RGNN_EUNSUPPORTED, "row selector: bf16 rows and ungathered dY only");
     if (rows16) {
         TypedLinearBf16Args a{};
@@ -342,7 +351,7 @@ rgnn_status_t tl_bwd(bool rows16, const rgnn::TileList* tiles, const rgnn::TileL
     b.tiles = wide; b.X = static_cast<const float*>(X); b.gather = gather; b.W = W32; b.dY = static_cast<const float*>(dY);
     b.dy_gathered = both_gathered; b.dXrow = static_cast<float*>(dXrow); b.scatter_dx = both_gathered; b.dW = dW;
     b.part = part; b.label = label;
-    return typed_linear_bwd(d, d, b, st);
+    return typed_linear_bwd(d_in, d, b, st);
 }
 
 }  // namespace
@@ -416,7 +425,8 @@ extern "C" rgnn_status_t rgnn_rgcn_fwd(const rgnn_graph_t* g, const rgnn_layer_d
     const float* W032 = stg.in(W0, (size_t)desc->d_in * D);
     RGNN_TRY(stg.status);
     // 1. compact messages: Hs[p] = X[pair_src[p]] W[rel(p)]
-    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, X32, X16, g->idx[RGNN_IDX_PAIR_SRC], 0, W32, W16, w.Hs, h, "typed_linear_fwd", st));
+    RGNN_TRY(tl_fwd(bf16, &g->pair_tiles, &g->pair_tiles_wide, D, X32, X16, g->idx[RGNN_IDX_PAIR_SRC], 0, W32, W16, w.Hs, h, "typed_linear_fwd", st,
+                    desc->d_in));
     // 2. out[v] = sum_e (1/c) Hs[pair_e]
     const float* coef = desc->norm == RGNN_NORM_IN_DEGREE_PER_REL ? g->in_invc : nullptr;
     RGNN_TRY(gather_sum(g->dst_items, D, nullptr, g->idx[RGNN_IDX_IN_PAIR], 0, coef, 1, 0, w.Hs, out, w.partial, st, 0,
@@ -486,7 +496,7 @@ extern "C" rgnn_status_t rgnn_rgcn_bwd(const rgnn_graph_t* g, const rgnn_layer_d
                         w.partial, st, 1, "aggregate_bwd_pair", "aggregate_bwd_pair.combine", 1, h, h));
     // 2. per pair dXp = dHs W^T; dW[r] = sum X^T dHs
     RGNN_TRY(tl_bwd(h, &g->pair_tiles, &g->pair_tiles_wide, D, h ? X : static_cast<const void*>(X32), g->idx[RGNN_IDX_PAIR_SRC], 0, W32, W16, w.G,
-                    w.dXp, h, static_cast<float*>(dW), w.tl_part, "typed_linear_bwd", st, false, ysel, y_alt, yscale));
+                    w.dXp, h, static_cast<float*>(dW), w.tl_part, "typed_linear_bwd", st, false, ysel, y_alt, yscale, K));
     // 3. self-loop: dX0 = dPre W0^T, dW0 = X^T dPre
     if (W0) {
         TypedLinearBwdArgs s{};

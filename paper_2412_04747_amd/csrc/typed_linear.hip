@@ -712,7 +712,9 @@ static rgnn_status_t launch_fwd(const TypedLinearArgs& a, hipStream_t st) {
         RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear: %d heads for the row-vector products at width %d", a.s_heads, ND);
     if (g && !sc && !ac && v) return launch_fwd_wave<KD, ND, true, false, false, true>(a, st);
     if (g && !sc && !ac && !v) return launch_fwd_wave<KD, ND, true, false, false, false>(a, st);
-    if (g && sc && !ac && !v) return launch_fwd_wave<KD, ND, true, true, false, false>(a, st);
+    if constexpr (KD == ND) {
+        if (g && sc && !ac && !v) return launch_fwd_wave<KD, ND, true, true, false, false>(a, st);
+    }
     if (!g && !ac && !v) return launch_fwd_wave<KD, ND, false, false, false, false>(a, st);
     if (!g && ac && !v) return launch_fwd_wave<KD, ND, false, false, true, false>(a, st);
     RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear forward: this combination of gather / scatter / accumulate / vec is not built");
@@ -723,7 +725,9 @@ rgnn_status_t typed_linear_fwd(int d_in, int d_out, const TypedLinearArgs& a, hi
     if (d_in == 64 && d_out == 64) return launch_fwd<64, 64>(a, st);
     if (d_in == 32 && d_out == 32) return launch_fwd<32, 32>(a, st);
     if (d_in == 128 && d_out == 128) return launch_fwd<128, 128>(a, st);
-    RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear: d_in = %d, d_out = %d not supported (need equal, 32/64/128)", d_in, d_out);
+    if (d_in == 32 && d_out == 64) return launch_fwd<32, 64>(a, st);
+    if (d_in == 64 && d_out == 32) return launch_fwd<64, 32>(a, st);
+    RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear: d_in = %d, d_out = %d not supported (need 32 / 64 / 128, different widths only among 32 and 64)", d_in, d_out);
 }
 
 size_t typed_linear_bwd_scratch_floats(int d_in, int d_out, const TileList& t, int vectors) {
@@ -807,8 +811,9 @@ static rgnn_status_t launch_bwd(const TypedLinearBwdArgs& a, hipStream_t st) {
             else if (a.ysel) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true, true>(a, st)));
             else if (g && !dg && !sc && rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, true>(a, st)));
             else if (g && !dg && !sc && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, false, false, false>(a, st)));
-            else if (g && dg && sc && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, true, true, true, false>(a, st)));
-            else if (!g && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, false, false, false, false>(a, st)));
+            else if (KD == ND && g && dg && sc && !rs) {
+                if constexpr (KD == ND) RGNN_TRY((launch_bwd_wave<KD, ND, true, true, true, false>(a, st)));
+            } else if (!g && !rs) RGNN_TRY((launch_bwd_wave<KD, ND, false, false, false, false>(a, st)));
             else done = false;
         }
         if (!done) RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: this combination of gather / scatter / rowscale is not built");
@@ -830,7 +835,9 @@ rgnn_status_t typed_linear_bwd(int d_in, int d_out, const TypedLinearBwdArgs& a,
     if (d_in == 64 && d_out == 64) return launch_bwd<64, 64>(a, st);
     if (d_in == 32 && d_out == 32) return launch_bwd<32, 32>(a, st);
     if (d_in == 128 && d_out == 128) return launch_bwd<128, 128>(a, st);
-    RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: d_in = %d, d_out = %d not supported (need equal, 32/64/128)", d_in, d_out);
+    if (d_in == 32 && d_out == 64) return launch_bwd<32, 64>(a, st);
+    if (d_in == 64 && d_out == 32) return launch_bwd<64, 32>(a, st);
+    RGNN_FAIL(RGNN_EUNSUPPORTED, "typed linear backward: d_in = %d, d_out = %d not supported (need 32 / 64 / 128, different widths only among 32 and 64)", d_in, d_out);
 }
 
 }  // namespace rgnn

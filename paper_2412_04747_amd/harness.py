@@ -67,17 +67,19 @@ class Graph:
 class RgatLayer:
     """Device buffers for one RGAT layer call pair on a graph."""
 
-    def __init__(self, graph, d, slope=0.2, dtype="f32", heads=1, flags=0):
+    def __init__(self, graph, d, slope=0.2, dtype="f32", heads=1, flags=0, d_in=None):
+        """d: output width; d_in: input width when it differs."""
         self.g, self.d, self.H = graph, d, heads
+        k = d_in or d
         code, self.tdt = _tdtype(dtype)
-        self.desc = B.make_desc(code, d, d, heads, slope, flags=flags)
+        self.desc = B.make_desc(code, k, d, heads, slope, flags=flags)
         f, b, s = B.rgnn_workspace_bytes(graph.handle, B.RGNN_LAYER_RGAT, self.desc)
         self.ws = _buf(max(f, b))
         self.saved = _buf(s)
         N, R = graph.N, graph.R
         self.out = torch.empty(N, d, device="cuda")
-        self.dX = torch.empty(N, d, device="cuda")
-        self.dW = torch.empty(R, d, d, device="cuda")
+        self.dX = torch.empty(N, k, device="cuda")
+        self.dW = torch.empty(R, k, d, device="cuda")
         self.dw_s = torch.empty(R, d, device="cuda")
         self.dw_t = torch.empty(R, d, device="cuda")
 
@@ -109,10 +111,12 @@ class RgatLayer:
 
 
 class RgcnLayer:
-    def __init__(self, graph, d, norm="in_degree_per_rel", act="none", self_loop=False, dtype="f32", flags=0):
+    def __init__(self, graph, d, norm="in_degree_per_rel", act="none", self_loop=False, dtype="f32", flags=0, d_in=None):
+        """d: output width; d_in: input width when it differs."""
         self.g, self.d, self.self_loop = graph, d, self_loop
+        k = d_in or d
         code, self.tdt = _tdtype(dtype)
-        self.desc = B.make_desc(code, d, d, 1, 0.0,
+        self.desc = B.make_desc(code, k, d, 1, 0.0,
                                 B.RGNN_NORM_IN_DEGREE_PER_REL if norm == "in_degree_per_rel" else B.RGNN_NORM_NONE,
                                 B.RGNN_ACT_RELU if act == "relu" else B.RGNN_ACT_NONE, flags)
         f, b, s = B.rgnn_workspace_bytes(graph.handle, B.RGNN_LAYER_RGCN, self.desc)
@@ -120,9 +124,9 @@ class RgcnLayer:
         self.saved = _buf(s)
         N, R = graph.N, graph.R
         self.out = torch.empty(N, d, device="cuda")
-        self.dX = torch.empty(N, d, device="cuda")
-        self.dW = torch.empty(R, d, d, device="cuda")
-        self.dW0 = torch.empty(d, d, device="cuda") if self_loop else None
+        self.dX = torch.empty(N, k, device="cuda")
+        self.dW = torch.empty(R, k, d, device="cuda")
+        self.dW0 = torch.empty(k, d, device="cuda") if self_loop else None
 
     def load(self, X, W, W0=None, dOut=None):
         t = self.tdt

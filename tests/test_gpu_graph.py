@@ -97,7 +97,7 @@ def test_layer_argument_errors():
     # every pointer argument is a buffer far larger than any tensor or workspace of this 20-node graph, so a
     # descriptor that a later version accepts cannot make one of these calls write out of bounds
     x = torch.zeros(1 << 24, device="cuda")
-    for bad, status in ((B.make_desc(d_in=48, d_out=48), 2), (B.make_desc(d_in=64, d_out=32), 2),
+    for bad, status in ((B.make_desc(d_in=48, d_out=48), 2), (B.make_desc(d_in=64, d_out=128), 2), (B.make_desc(dtype=B.RGNN_BF16, d_in=64, d_out=32), 2),
                         (B.make_desc(heads=8), 2), (B.make_desc(heads=3), 1), (B.make_desc(flags=64), 1), (B.make_desc(flags=1, heads=2), 2), (B.make_desc(flags=16, heads=2), 2),
                         (B.make_desc(dtype=7), 1)):
         with pytest.raises(B.RgnnError) as e:

@@ -10,14 +10,14 @@ from parity import check, TOL_F32
 pytestmark = pytest.mark.gpu
 
 
-def _run(N, R, src, dst, rel, p, d, tag, slope=0.2, check_saved=True, dtype="f32"):
+def _run(N, R, src, dst, rel, p, d, tag, slope=0.2, check_saved=True, dtype="f32", d_in=None):
     import torch
     from paper_2412_04747_amd.harness import Graph, RgatLayer
     from parity import TOL_BF16
     print(f"rgat case {tag}: N={N} R={R} E={len(src)} d={d} {dtype}", flush=True)
     TOL_F32 = TOL_BF16 if dtype == "bf16" else 1e-4        # the tolerance of this case, under the name used below
     g = Graph(N, R, src, dst, rel)
-    L = RgatLayer(g, d, slope, dtype=dtype)
+    L = RgatLayer(g, d, slope, dtype=dtype, d_in=d_in)
     L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
     L.fwd()
     torch.cuda.synchronize()
@@ -67,6 +67,15 @@ def test_small_random(d):
     _run(500, 6, src, dst, rel, p, d, f"small-d{d}")
 
 
+@pytest.mark.parametrize("d_in,d", [(32, 64), (64, 32)])
+def test_input_width_differs_from_output_width(d_in, d):
+    rng, src, dst, rel, _ = synth.tiny(75 + d, N=700, R=6, E=6000)
+    dst[:900] = 11                                   # a hub cut into pieces
+    src[900:1300] = 3; rel[900:1300] = 2             # one pair with many edges
+    p = synth.rgat_params(rng, 700, 6, d_in, d)
+    _run(700, 6, src, dst, rel, p, d, f"widths-{d_in}-{d}", d_in=d_in)
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_single_head_bf16_inputs(d):
     """bf16 X, W, w_s, w_t, dOut (rounded once on the host; the oracle consumes the rounded values in fp64),
@@ -103,14 +112,14 @@ def test_many_single_edge_destinations():
     _run(N, R, src, dst, rel, p, d, "singles")
 
 
-def _run_heads(N, R, src, dst, rel, p, d, H, tag, dtype="f32", slope=0.2, flags=0):
+def _run_heads(N, R, src, dst, rel, p, d, H, tag, dtype="f32", slope=0.2, flags=0, d_in=None):
     import torch
     from paper_2412_04747_amd.harness import Graph, RgatLayer
     from parity import TOL_BF16
     print(f"rgat case {tag}: N={N} R={R} E={len(src)} d={d} heads={H} {dtype}", flush=True)
     tol = TOL_BF16 if dtype == "bf16" else TOL_F32
     g = Graph(N, R, src, dst, rel)
-    L = RgatLayer(g, d, slope, dtype=dtype, heads=H, flags=flags)
+    L = RgatLayer(g, d, slope, dtype=dtype, heads=H, flags=flags, d_in=d_in)
     L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
     L.fwd()
     torch.cuda.synchronize()
@@ -155,6 +164,15 @@ def test_multi_head_rows_written_per_pair(d, H):
     src[:300] = 9; rel[:300] = 2
     p = synth.rgat_params(rng, 800, 6, d, d)
     _run_heads(800, 6, src, dst, rel, p, d, H, f"heads-d{d}-H{H}-noselect", flags=4)       # RGNN_FLAG_NO_ROW_SELECT
+
+
+@pytest.mark.parametrize("d_in,d,H,flags", [(32, 64, 4, 0), (64, 32, 2, 0), (32, 64, 2, 4)])
+def test_multi_head_input_width_differs(d_in, d, H, flags):
+    rng, src, dst, rel, _ = synth.tiny(195 + d + H, N=800, R=6, E=7000)
+    dst[:1200] = 4
+    src[:300] = 9; rel[:300] = 2
+    p = synth.rgat_params(rng, 800, 6, d_in, d)
+    _run_heads(800, 6, src, dst, rel, p, d, H, f"heads-{d_in}-{d}-H{H}-flags{flags}", flags=flags, d_in=d_in)
 
 
 def test_multi_head_bf16_inputs_and_empty_relation():

@@ -9,12 +9,12 @@ from parity import check, TOL_F32, TOL_BF16
 pytestmark = pytest.mark.gpu
 
 
-def _run(N, R, src, dst, rel, p, d, norm, act, self_loop, bwd=True, tag="", dtype="f32"):
+def _run(N, R, src, dst, rel, p, d, norm, act, self_loop, bwd=True, tag="", dtype="f32", d_in=None):
     import torch
     from paper_2412_04747_amd.harness import Graph, RgcnLayer
     print(f"rgcn case {tag}: N={N} R={R} E={len(src)} d={d} norm={norm} act={act} W0={self_loop}", flush=True)
     g = Graph(N, R, src, dst, rel)
-    L = RgcnLayer(g, d, norm, act, self_loop, dtype=dtype)
+    L = RgcnLayer(g, d, norm, act, self_loop, dtype=dtype, d_in=d_in)
     tol = TOL_BF16 if dtype == "bf16" else TOL_F32
     W0 = p["W0"] if self_loop else None
     L.load(p["X"], p["W"], W0, p["dOut"])
@@ -48,6 +48,15 @@ def test_forward_backward_all_options(d):
     _run(700, 5, src, dst, rel, p, d, "in_degree_per_rel", "none", True, tag=f"d{d}")
     _run(700, 5, src, dst, rel, p, d, "none", "relu", True, tag=f"d{d}-relu")
     _run(700, 5, src, dst, rel, p, d, "none", "none", False, tag=f"d{d}-plain")
+
+
+@pytest.mark.parametrize("d_in,d", [(32, 64), (64, 32)])
+def test_input_width_differs_from_output_width(d_in, d):
+    rng, src, dst, rel, _ = synth.tiny(45 + d, N=700, R=5, E=6000)
+    dst[:800] = 9           # a hub cut into pieces
+    p = synth.rgcn_params(rng, 700, 5, d_in, d, self_loop=True)
+    _run(700, 5, src, dst, rel, p, d, "in_degree_per_rel", "none", True, tag=f"widths-{d_in}-{d}", d_in=d_in)
+    _run(700, 5, src, dst, rel, p, d, "none", "relu", False, tag=f"widths-{d_in}-{d}-relu", d_in=d_in)
 
 
 def test_hub_and_isolated_nodes():

@@ -32,17 +32,19 @@ def _graph(seed, N, R, E, T=1):
 
 
 # flags 32: gradients accumulate (the parameter gradients of the call then live in the workspace too)
-@pytest.mark.parametrize("dtype,d,heads,flags", [("f32", 64, 1, 0), ("f32", 32, 2, 0), ("bf16", 128, 4, 0), ("f32", 128, 1, 0),
-                                                 ("f32", 64, 1, 32), ("f32", 64, 4, 32)])
-def test_rgat_stays_inside_its_buffers(dtype, d, heads, flags):
+# d_in: input width where it differs from the output width d
+@pytest.mark.parametrize("dtype,d,heads,flags,d_in", [("f32", 64, 1, 0, None), ("f32", 32, 2, 0, None), ("bf16", 128, 4, 0, None),
+                                                      ("f32", 128, 1, 0, None), ("f32", 64, 1, 32, None), ("f32", 64, 4, 32, None),
+                                                      ("f32", 64, 1, 0, 32), ("f32", 32, 2, 32, 64), ("f32", 64, 4, 0, 32)])
+def test_rgat_stays_inside_its_buffers(dtype, d, heads, flags, d_in):
     import torch
     from paper_2412_04747_amd import binding as B
     from paper_2412_04747_amd.harness import Graph, RgatLayer
     rng, src, dst, rel, _ = _graph(501, 3000, 40, 40000)
-    print(f"bounds case rgat {dtype} d={d} heads={heads}", flush=True)
+    print(f"bounds case rgat {dtype} d_in={d_in or d} d={d} heads={heads} flags={flags}", flush=True)
     g = Graph(3000, 40, src, dst, rel)
-    L = RgatLayer(g, d, dtype=dtype, heads=heads, flags=flags)
-    p = synth.rgat_params(rng, 3000, 40, d, d)
+    L = RgatLayer(g, d, dtype=dtype, heads=heads, flags=flags, d_in=d_in)
+    p = synth.rgat_params(rng, 3000, 40, d_in or d, d)
     if dtype == "bf16":
         p = {k: synth.round_to_bf16(v) for k, v in p.items()}
     L.load(p["X"], p["W"], p["w_s"], p["w_t"], p["dOut"])
@@ -59,17 +61,18 @@ def test_rgat_stays_inside_its_buffers(dtype, d, heads, flags):
     g.close()
 
 
-@pytest.mark.parametrize("dtype,d,act,w0,flags", [("f32", 64, "relu", True, 0), ("bf16", 128, "relu", True, 0), ("bf16", 128, "none", False, 0),
-                                                  ("bf16", 128, "relu", True, 32)])
-def test_rgcn_stays_inside_its_buffers(dtype, d, act, w0, flags):
+@pytest.mark.parametrize("dtype,d,act,w0,flags,d_in", [("f32", 64, "relu", True, 0, None), ("bf16", 128, "relu", True, 0, None),
+                                                       ("bf16", 128, "none", False, 0, None), ("bf16", 128, "relu", True, 32, None),
+                                                       ("f32", 64, "relu", True, 0, 32), ("f32", 32, "none", True, 32, 64)])
+def test_rgcn_stays_inside_its_buffers(dtype, d, act, w0, flags, d_in):
     import torch
     from paper_2412_04747_amd import binding as B
     from paper_2412_04747_amd.harness import Graph, RgcnLayer
     rng, src, dst, rel, _ = _graph(502, 3000, 40, 40000)
-    print(f"bounds case rgcn {dtype} d={d} act={act} W0={w0}", flush=True)
+    print(f"bounds case rgcn {dtype} d_in={d_in or d} d={d} act={act} W0={w0}", flush=True)
     g = Graph(3000, 40, src, dst, rel)
-    L = RgcnLayer(g, d, "in_degree_per_rel", act, w0, dtype=dtype, flags=flags)
-    p = synth.rgcn_params(rng, 3000, 40, d, d, self_loop=w0)
+    L = RgcnLayer(g, d, "in_degree_per_rel", act, w0, dtype=dtype, flags=flags, d_in=d_in)
+    p = synth.rgcn_params(rng, 3000, 40, d_in or d, d, self_loop=w0)
     if dtype == "bf16":
         p = {k: (None if v is None else synth.round_to_bf16(v)) for k, v in p.items()}
     L.load(p["X"], p["W"], p["W0"], p["dOut"])
