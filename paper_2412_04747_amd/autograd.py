@@ -48,9 +48,9 @@ class _Rgat(torch.autograd.Function):
     @staticmethod
     def forward(ctx, graph, slope, heads, X, W, w_s, w_t):
         X, W, w_s, w_t = _f32(X), _f32(W), _f32(w_s), _f32(w_t)
-        d = W.shape[-1]
-        desc = B.make_desc(B.RGNN_F32, d, d, heads, slope)
-        ws, s = _bufs(graph, B.RGNN_LAYER_RGAT, desc, (d, heads))
+        d_in, d = W.shape[-2], W.shape[-1]
+        desc = B.make_desc(B.RGNN_F32, d_in, d, heads, slope)
+        ws, s = _bufs(graph, B.RGNN_LAYER_RGAT, desc, (d_in, d, heads))
         out = torch.empty(graph.N, d, device=X.device)
         saved = _buf(s)
         B.rgnn_rgat_fwd(graph.handle, desc, X, W, w_s, w_t, out, saved, ws, _stream())
@@ -72,11 +72,11 @@ class _Rgcn(torch.autograd.Function):
     @staticmethod
     def forward(ctx, graph, norm, act, X, W, W0):
         X, W, W0 = _f32(X), _f32(W), _f32(W0)
-        d = W.shape[-1]
-        desc = B.make_desc(B.RGNN_F32, d, d, 1, 0.0,
+        d_in, d = W.shape[-2], W.shape[-1]
+        desc = B.make_desc(B.RGNN_F32, d_in, d, 1, 0.0,
                            B.RGNN_NORM_IN_DEGREE_PER_REL if norm == "in_degree_per_rel" else B.RGNN_NORM_NONE,
                            B.RGNN_ACT_RELU if act == "relu" else B.RGNN_ACT_NONE)
-        ws, _ = _bufs(graph, B.RGNN_LAYER_RGCN, desc, (d, norm, act))
+        ws, _ = _bufs(graph, B.RGNN_LAYER_RGCN, desc, (d_in, d, norm, act))
         out = torch.empty(graph.N, d, device=X.device)
         B.rgnn_rgcn_fwd(graph.handle, desc, X, W, W0, out, None, ws, _stream())
         ctx.graph, ctx.desc, ctx.ws, ctx.has_w0 = graph, desc, ws, W0 is not None
@@ -141,21 +141,25 @@ def _param(*shape, fan_in):
 
 
 class RgatConv(torch.nn.Module):
-    def __init__(self, num_rels, d, slope=0.2, heads=1):
+    def __init__(self, num_rels, d, slope=0.2, heads=1, d_in=None):
+        """d: output width; d_in: input width when it differs (32 and 64 may be mixed)."""
         super().__init__()
         self.slope, self.heads = slope, heads
-        self.W, self.w_s, self.w_t = _param(num_rels, d, d, fan_in=d), _param(num_rels, d, fan_in=d), _param(num_rels, d, fan_in=d)
+        k = d_in or d
+        self.W, self.w_s, self.w_t = _param(num_rels, k, d, fan_in=k), _param(num_rels, d, fan_in=d), _param(num_rels, d, fan_in=d)
 
     def forward(self, graph, X):
         return rgat(graph, X, self.W, self.w_s, self.w_t, self.slope, self.heads)
 
 
 class RgcnConv(torch.nn.Module):
-    def __init__(self, num_rels, d, self_loop=True, norm="in_degree_per_rel", act="none"):
+    def __init__(self, num_rels, d, self_loop=True, norm="in_degree_per_rel", act="none", d_in=None):
+        """d: output width; d_in: input width when it differs (32 and 64 may be mixed)."""
         super().__init__()
         self.norm, self.act = norm, act
-        self.W = _param(num_rels, d, d, fan_in=d)
-        self.W0 = _param(d, d, fan_in=d) if self_loop else None
+        k = d_in or d
+        self.W = _param(num_rels, k, d, fan_in=k)
+        self.W0 = _param(k, d, fan_in=k) if self_loop else None
 
     def forward(self, graph, X):
         return rgcn(graph, X, self.W, self.W0, self.norm, self.act)

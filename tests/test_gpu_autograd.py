@@ -24,16 +24,17 @@ def _nll_head(h, train, labels):
     return loss, dh
 
 
-def test_two_layer_rgat_nll():
+@pytest.mark.parametrize("d0,d,d2", [(64, 64, 64), (32, 64, 32)])       # input, hidden and output width
+def test_two_layer_rgat_nll(d0, d, d2):
     import torch
     from paper_2412_04747_amd import autograd as A
-    N, R, E, d = 900, 6, 8000, 64
+    N, R, E = 900, 6, 8000
     rng, src, dst, rel, _ = synth.tiny(301, N=N, R=R, E=E)
     dst[:700] = 11                                  # a hub cut into pieces
-    p1, p2 = synth.rgat_params(rng, N, R, d, d), synth.rgat_params(rng, N, R, d, d)
+    p1, p2 = synth.rgat_params(rng, N, R, d0, d), synth.rgat_params(rng, N, R, d, d2)
     train = rng.choice(N, 300, replace=False)
-    labels = rng.integers(0, d, 300)
-    print(f"autograd case rgat2: N={N} R={R} E={E} d={d}", flush=True)
+    labels = rng.integers(0, d2, 300)
+    print(f"autograd case rgat2: N={N} R={R} E={E} widths {d0} -> {d} -> {d2}", flush=True)
 
     g = A.Graph(N, R, src, dst, rel)
     t = lambda a: torch.tensor(a, dtype=torch.float32, device="cuda", requires_grad=True)
